@@ -1,0 +1,212 @@
+/*
+ * rbe.h -- C ABI of the MI355X (gfx950) library for exhaustive retrieval over
+ * Recurrent Binary Embedding (RBE) vectors.
+ *
+ * What it computes (paper: "Recurrent Binary Embedding for GPU-Enabled
+ * Exhaustive Retrieval from Billion-Scale Semantic Vectors", Sec. 5 and 6):
+ * every item of a corpus resident in GPU memory is scored against each query
+ * and the k best items per query are returned.
+ *
+ * Representation (Sec. 4.1, Eq. 8-11).  An item z is P "ingredient vectors"
+ * (a base vector and P-1 residual vectors) in {-1,+1}^dim, each packed one bit
+ * per dimension -- dimension i is bit (i % 64) of 64-bit word (i / 64), bit 1
+ * means +1, bit 0 means -1 (the binarisation of Eq. 12 maps x <= 0 to -1) --
+ * and each with a non-negative fp32 scale a_j[z].  The paper's fixed residual
+ * weights 2^-j and its stored keyword norm (Sec. 4.3, Sec. 5.1) are the
+ * special case a_j[z] = 2^-j / ||b_z||.  A query has Pq ingredient vectors
+ * with scales c_i; Pq need not equal P (asymmetric design, Sec. 5.2).
+ *
+ * Score (Eq. 14 with the bit-wise identity of Sec. 5.1, sign corrected):
+ *     s(q, z) = sum_{j<P} a_j[z] * sum_{i<Pq} c_i * (dim - 2 * popcount(Q_i XOR K_j[z]))
+ * The popcounts are exact integers; the combination is evaluated in fp32 in
+ * the order written (i inner, j outer), each inner sum starting from
+ * dim * sum_i c_i and accumulating -2 c_i * popcount with fused multiply-adds.
+ *
+ * Selection (Sec. 6).  Results are ordered by (score descending, id
+ * ascending).  RBE_SELECT_EXACT returns exactly the k best under that order.
+ * RBE_SELECT_NEARLOSSLESS reproduces Algorithm 1 with a priority queue of
+ * length 1: items are grouped as thread y = z mod 256 of block
+ * x = z div (256 * I) would visit them, every group forwards only its best
+ * item, and the k best forwarded items are returned (Appendix A gives the
+ * probability that this loses any of the true top k).
+ *
+ * Conventions.  Every function returns RBE_OK (0) or a negative error code and
+ * never aborts; rbe_last_error() gives a message for the calling thread's last
+ * failure.  Output arguments are untouched on error unless stated.  Pointers
+ * are HOST pointers unless the argument description says otherwise.  A
+ * `hip_stream` argument is a hipStream_t passed as void* (NULL = the default
+ * stream); all device work of the call is enqueued on it.  An index may be
+ * used by one thread at a time.  One GPU: the device current at
+ * rbe_index_create() owns the index.
+ */
+#ifndef RBE_H
+#define RBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rbe_index rbe_index; /* opaque; owns its device memory */
+
+enum {
+    RBE_OK = 0,
+    RBE_EINVAL = -1,    /* bad argument (range, alignment, NULL)               */
+    RBE_ENOMEM = -2,    /* host or device allocation failed                    */
+    RBE_EHIP = -3,      /* a HIP runtime call failed; see rbe_last_error()     */
+    RBE_ESTATE = -4,    /* call not valid in the index's current state         */
+    RBE_EUNSUPPORTED = -5 /* valid request this build has no kernel for        */
+};
+
+enum { RBE_MEM_HOST = 0, RBE_MEM_DEVICE = 1 }; /* where a caller's array lives */
+
+enum {
+    RBE_COSINE = 1u << 1 /* at rbe_finalize(): divide every item's scales by the
+                            norm of its reconstructed vector sum_j a_j b_j, so that
+                            scores become the cosine of Eq. 14 up to the query's own
+                            norm (which Sec. 5.1 drops as constant per query)      */
+};
+
+enum { RBE_SELECT_EXACT = 0, RBE_SELECT_NEARLOSSLESS = 1 };
+
+/* Limits */
+#define RBE_MAX_PLANES 4u     /* P and Pq                                        */
+#define RBE_MAX_QUERIES 64u   /* queries per rbe_search call                     */
+#define RBE_MAX_K 4096u
+#define RBE_MAX_ITEMS 4294966272ull /* ids are kept in 32 bits on the device     */
+
+/* ---------------------------------------------------------------------------
+ * Corpus (the offline keyword side of Fig. 3: embeddings are produced ahead of
+ * time and uploaded once, Sec. 5).  Storage on the device is structure-of-
+ * arrays by ingredient vector (Sec. 6.1): all base vectors, then all first
+ * residuals, ..., then the scale arrays in the same order.
+ * ------------------------------------------------------------------------- */
+
+/* Allocates device storage for n_items items of `dim` dimensions and
+ * `n_planes` ingredient vectors.  dim in {64, 128, 256}; 1 <= n_planes <= 4;
+ * 1 <= n_items <= RBE_MAX_ITEMS.  flags: 0 or RBE_COSINE.  The index starts
+ * in the "loading" state.  Device memory: n_items * n_planes * (dim/8 + 4)
+ * bytes, rounded up to a multiple of 1024 items.                             */
+int rbe_index_create(rbe_index **out, uint64_t n_items, uint32_t dim,
+                     uint32_t n_planes, uint32_t flags);
+
+/* Copies items [first_item, first_item + count) into the index.
+ *   planes: [n_planes][count][dim/64] uint64, scales: [n_planes][count] float,
+ *   both in host memory (mem_kind = RBE_MEM_HOST) or both in device memory
+ *   (RBE_MEM_DEVICE; e.g. torch tensors).  The caller keeps ownership; the
+ *   arrays may be released once the stream has passed the copies (host arrays:
+ *   on return).  Scales must be finite and >= 0 (not checked).
+ * Only valid while loading.                                                   */
+int rbe_load_chunk(rbe_index *ix, uint64_t first_item, uint64_t count,
+                   const uint64_t *planes, const float *scales,
+                   int mem_kind, void *hip_stream);
+
+/* Ends loading: applies RBE_COSINE if requested, waits for the stream, and
+ * makes the index searchable.  Items never loaded score as all-(-1) vectors
+ * with scale 0.                                                               */
+int rbe_finalize(rbe_index *ix, void *hip_stream);
+
+/* rbe_index_create + one rbe_load_chunk of the whole corpus + rbe_finalize.
+ *   planes: [n_planes][n_items][dim/64], scales: [n_planes][n_items].         */
+int rbe_load_corpus(rbe_index **out, const uint64_t *planes, const float *scales,
+                    uint64_t n_items, uint32_t dim, uint32_t n_planes,
+                    int mem_kind, uint32_t flags, void *hip_stream);
+
+/* Releases the index and everything it owns.  NULL is allowed.                */
+void rbe_free(rbe_index *ix);
+
+/* ---------------------------------------------------------------------------
+ * Query side.  The paper's learned RBE layers (Eq. 8-11) need trained matrices;
+ * this stand-in produces vectors of the same form by greedy residual
+ * binarisation: r_0 = x; for t < n_planes: scale_t = mean_i |r_t[i]| (summed in
+ * double, stored as fp32), bit_t[i] = (r_t[i] > 0), r_{t+1} = fp32(r_t -
+ * scale_t * (2 bit_t - 1)).  Pure host function; no GPU involved.
+ *   x: [dim] float; planes_out: [n_planes][dim/64]; scales_out: [n_planes].
+ * ------------------------------------------------------------------------- */
+int rbe_encode_query(const float *x, uint32_t dim, uint32_t n_planes,
+                     uint64_t *planes_out, float *scales_out);
+
+/* ---------------------------------------------------------------------------
+ * Search: exhaustive match + selection (Sec. 5-6, Algorithm 1).
+ *   q_planes : [n_queries][q_n_planes][dim/64] uint64 (host)
+ *   q_scales : [n_queries][q_n_planes] float (host), finite
+ *   1 <= n_queries <= RBE_MAX_QUERIES, 1 <= q_n_planes <= 4, 1 <= k <= RBE_MAX_K
+ *   mode     : RBE_SELECT_EXACT or RBE_SELECT_NEARLOSSLESS
+ *   group_size_I : items per group for the near-lossless mode (the paper's I,
+ *                  1..65535; 0 means 256); ignored in exact mode
+ *   ids_out  : [n_queries][k] int64 (host), scores_out: [n_queries][k] float
+ *              (host).  Per query sorted by (score desc, id asc).  If fewer
+ *              than k results exist (k > n_items, or k > number of groups) the
+ *              tail holds id = -1, score = -INFINITY.
+ * The call returns after the results are in the host arrays (it waits for the
+ * stream).  Device scratch is grown on demand inside the call.               */
+int rbe_search(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
+               uint32_t n_queries, uint32_t q_n_planes, uint32_t k,
+               uint32_t mode, uint32_t group_size_I,
+               int64_t *ids_out, float *scores_out, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Measurement.  With profiling on, rbe_search brackets each kernel with HIP
+ * events on the search stream and fills rbe_search_stats after the call.
+ * ------------------------------------------------------------------------- */
+#define RBE_MAX_LEVELS 8
+
+typedef struct rbe_search_stats {
+    uint32_t n_levels;        /* scan+select rounds of the last search           */
+    uint32_t fallback;        /* 1 if the bounded-segment slow path was taken    */
+    uint32_t grid_blocks;     /* workgroups of the widest scan launch            */
+    uint32_t reserved;
+    uint64_t items_scanned[RBE_MAX_LEVELS];   /* items read by each scan         */
+    uint64_t candidates_max[RBE_MAX_LEVELS];  /* largest per-query candidate
+                                                 count handed to each select     */
+    float scan_ms[RBE_MAX_LEVELS];            /* kernel time of each scan        */
+    float select_ms[RBE_MAX_LEVELS];          /* kernel time of each select      */
+    float total_gpu_ms;       /* first enqueue to results ready, on the stream   */
+} rbe_search_stats;
+
+int rbe_set_profiling(rbe_index *ix, int enabled);
+int rbe_get_search_stats(const rbe_index *ix, rbe_search_stats *out);
+
+/* Tuning knobs (0 keeps the current value):
+ *   sample_ratio    : each refinement level scans sample_ratio times more of
+ *                     the corpus than the one before (default 64)
+ *   cand_capacity   : candidate slots per query (default max(65536, 4*ratio*k))
+ *   blocks_per_cu   : persistent workgroups per compute unit for the scan
+ *                     (default: as many as the kernel's occupancy allows)      */
+int rbe_set_tuning(rbe_index *ix, uint32_t sample_ratio, uint32_t cand_capacity,
+                   uint32_t blocks_per_cu);
+
+/* ---------------------------------------------------------------------------
+ * Test hooks (dense dumps for parity checks; small ranges only).
+ * ------------------------------------------------------------------------- */
+
+/* popcount(Q_i XOR K_j[z]) for z in [first_item, first_item+count):
+ *   q_planes [q_n_planes][dim/64] (host) -> out [count][n_planes][q_n_planes]
+ *   int32 (host).                                                            */
+int rbe_debug_popcounts(rbe_index *ix, const uint64_t *q_planes, uint32_t q_n_planes,
+                        uint64_t first_item, uint64_t count, int32_t *out, void *hip_stream);
+
+/* fp32 scores s(q, z) of one query for z in [first_item, first_item+count):
+ *   out [count] float (host).  Same arithmetic as rbe_search.                */
+int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
+                     uint32_t q_n_planes, uint64_t first_item, uint64_t count,
+                     float *out, void *hip_stream);
+
+/* Copies the (possibly cosine-folded) scales of items [first_item,
+ * first_item+count) back: out [n_planes][count] float (host).                */
+int rbe_debug_read_scales(rbe_index *ix, uint64_t first_item, uint64_t count,
+                          float *out, void *hip_stream);
+
+const char *rbe_strerror(int code);
+const char *rbe_last_error(void);
+/* n_items / dim / n_planes of an index (0 for NULL). */
+uint64_t rbe_n_items(const rbe_index *ix);
+uint32_t rbe_dim(const rbe_index *ix);
+uint32_t rbe_n_planes(const rbe_index *ix);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RBE_H */

@@ -54,6 +54,8 @@ def _c():
         lib.orc_popcounts.argtypes = [vp, u64, u32, u32, vp, u32, vp]
         lib.orc_scores.restype = None
         lib.orc_scores.argtypes = [vp, vp, u64, u32, u32, vp, vp, u32, u64, u64, vp]
+        lib.orc_scores_at.restype = None
+        lib.orc_scores_at.argtypes = [vp, vp, u64, u32, u32, vp, vp, u32, vp, u64, vp]
         lib.orc_topk.restype = i64
         lib.orc_topk.argtypes = [vp, vp, u64, u32, u32, vp, vp, u32, u64, u64, u64, vp, vp]
         lib.orc_topk_of_scores.restype = i64
@@ -133,6 +135,18 @@ def scores(planes, scales, q_planes, q_scales, z0: int = 0, z1: int | None = Non
     z1 = N if z1 is None else z1
     out = np.zeros(z1 - z0, dtype=np.float64)
     _c().orc_scores(_p(planes), _p(scales), N, 64 * W, P, _p(q_planes), _p(q_scales), Pq, z0, z1, _p(out))
+    return out
+
+
+def scores_at(planes, scales, q_planes, q_scales, ids):
+    """Float64 scores of one query against the listed item ids."""
+    planes, scales, P, N, W = _corpus(planes, scales)
+    q_planes, q_scales, Pq = _query(q_planes, q_scales, W)
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    if ids.size and (ids.min() < 0 or ids.max() >= N):
+        raise ValueError("id out of range")
+    out = np.zeros(ids.size, dtype=np.float64)
+    _c().orc_scores_at(_p(planes), _p(scales), N, 64 * W, P, _p(q_planes), _p(q_scales), Pq, _p(ids), ids.size, _p(out))
     return out
 
 

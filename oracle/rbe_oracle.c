@@ -89,6 +89,16 @@ void orc_scores(const uint64_t *planes, const float *scales, uint64_t N,
         out[z - z0] = score_pair(planes, scales, N, d, P, z, q_planes, q_scales, Pq);
 }
 
+/* Scores of one query against an explicit list of item ids.  out[r], double. */
+void orc_scores_at(const uint64_t *planes, const float *scales, uint64_t N,
+                   uint32_t d, uint32_t P,
+                   const uint64_t *q_planes, const float *q_scales, uint32_t Pq,
+                   const int64_t *ids, uint64_t n_ids, double *out)
+{
+    for (uint64_t r = 0; r < n_ids; ++r)
+        out[r] = score_pair(planes, scales, N, d, P, (uint64_t)ids[r], q_planes, q_scales, Pq);
+}
+
 /* ------------------------------------------------------------------ */
 /* Exact top-k under the total order (score descending, id ascending).
  * Definition: sort every (score, id) by that order and keep the first k.

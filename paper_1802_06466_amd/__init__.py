@@ -1,0 +1,287 @@
+"""Thin Python binding of the RBE retrieval library (include/rbe.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``librbe_hip.so``.  There is no CPU fallback -- importing works without the
+library (so that CPU-only tooling can inspect the package), but any call raises
+``RuntimeError`` if the shared library has not been built.
+
+Function names match the C ABI.  Host arrays are numpy arrays; device arrays
+are torch tensors (used for device memory and streams only).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+from . import _build
+
+RBE_OK, RBE_EINVAL, RBE_ENOMEM, RBE_EHIP, RBE_ESTATE, RBE_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+RBE_MEM_HOST, RBE_MEM_DEVICE = 0, 1
+RBE_COSINE = 1 << 1
+RBE_SELECT_EXACT, RBE_SELECT_NEARLOSSLESS = 0, 1
+RBE_MAX_PLANES, RBE_MAX_QUERIES, RBE_MAX_K, RBE_MAX_LEVELS = 4, 64, 4096, 8
+RBE_MAX_ITEMS = 4294966272
+
+LIB_PATH = _build.LIB
+
+
+class RbeError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"rbe error {code}: {message}")
+        self.code = code
+
+
+class rbe_search_stats(ctypes.Structure):
+    _fields_ = [
+        ("n_levels", ctypes.c_uint32),
+        ("fallback", ctypes.c_uint32),
+        ("grid_blocks", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
+        ("items_scanned", ctypes.c_uint64 * RBE_MAX_LEVELS),
+        ("candidates_max", ctypes.c_uint64 * RBE_MAX_LEVELS),
+        ("scan_ms", ctypes.c_float * RBE_MAX_LEVELS),
+        ("select_ms", ctypes.c_float * RBE_MAX_LEVELS),
+        ("total_gpu_ms", ctypes.c_float),
+    ]
+
+
+_lib = None
+
+_u64, _u32, _i32, _vp = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p
+
+# name -> (restype, argtypes); the single source for ctypes prototypes
+PROTOTYPES = {
+    "rbe_index_create": (_i32, [ctypes.POINTER(_vp), _u64, _u32, _u32, _u32]),
+    "rbe_load_chunk": (_i32, [_vp, _u64, _u64, _vp, _vp, _i32, _vp]),
+    "rbe_finalize": (_i32, [_vp, _vp]),
+    "rbe_load_corpus": (_i32, [ctypes.POINTER(_vp), _vp, _vp, _u64, _u32, _u32, _i32, _u32, _vp]),
+    "rbe_free": (None, [_vp]),
+    "rbe_encode_query": (_i32, [_vp, _u32, _u32, _vp, _vp]),
+    "rbe_search": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "rbe_set_profiling": (_i32, [_vp, _i32]),
+    "rbe_get_search_stats": (_i32, [_vp, ctypes.POINTER(rbe_search_stats)]),
+    "rbe_set_tuning": (_i32, [_vp, _u32, _u32, _u32]),
+    "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
+    "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
+    "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
+    "rbe_strerror": (ctypes.c_char_p, [_i32]),
+    "rbe_last_error": (ctypes.c_char_p, []),
+    "rbe_n_items": (_u64, [_vp]),
+    "rbe_dim": (_u32, [_vp]),
+    "rbe_n_planes": (_u32, [_vp]),
+}
+
+
+def load_library():
+    """dlopen librbe_hip.so (built in-tree by ``_build.build``).  Raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_1802_06466_amd._build "
+                "or __graft_entry__.build()); there is no CPU fallback")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in PROTOTYPES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(code: int):
+    if code != RBE_OK:
+        lib = load_library()
+        raise RbeError(code, f"{lib.rbe_strerror(code).decode()}: {lib.rbe_last_error().decode()}")
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    """hipStream_t of a torch stream; None -> torch's current stream if torch has a
+    GPU context, else the default stream."""
+    if stream is not None:
+        return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+    try:
+        import torch
+        if torch.cuda.is_available():
+            return int(torch.cuda.current_stream().cuda_stream)
+    except ImportError:
+        pass
+    return None
+
+
+def _host(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data_as(_vp)
+
+
+class Index:
+    """Owner of an ``rbe_index*``."""
+
+    def __init__(self, handle: int):
+        self._h = _vp(handle)
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RbeError(RBE_ESTATE, "index already freed")
+        return self._h
+
+    @property
+    def n_items(self) -> int:
+        return int(load_library().rbe_n_items(self.handle))
+
+    @property
+    def dim(self) -> int:
+        return int(load_library().rbe_dim(self.handle))
+
+    @property
+    def n_planes(self) -> int:
+        return int(load_library().rbe_n_planes(self.handle))
+
+    def free(self):
+        if self._h:
+            load_library().rbe_free(self._h)
+            self._h = _vp(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _corpus_ptrs(planes, scales, n_planes: int, count: int, W: int):
+    """(planes_ptr, scales_ptr, mem_kind, keepalive) for numpy arrays or torch tensors."""
+    if isinstance(planes, np.ndarray) or isinstance(scales, np.ndarray):
+        p, pp = _host(planes, np.uint64)
+        s, sp = _host(scales, np.float32)
+        if p.shape != (n_planes, count, W) or s.shape != (n_planes, count):
+            raise RbeError(RBE_EINVAL, f"expected planes {(n_planes, count, W)} / scales {(n_planes, count)}, "
+                                       f"got {p.shape} / {s.shape}")
+        return pp, sp, RBE_MEM_HOST, (p, s)
+    import torch
+    if not (isinstance(planes, torch.Tensor) and isinstance(scales, torch.Tensor)):
+        raise RbeError(RBE_EINVAL, "planes/scales must both be numpy arrays or both torch tensors")
+    if planes.dtype not in (torch.int64, torch.uint64) or scales.dtype != torch.float32:
+        raise RbeError(RBE_EINVAL, "planes must be int64/uint64 and scales float32")
+    if tuple(planes.shape) != (n_planes, count, W) or tuple(scales.shape) != (n_planes, count):
+        raise RbeError(RBE_EINVAL, "planes/scales have the wrong shape")
+    if planes.device != scales.device:
+        raise RbeError(RBE_EINVAL, "planes and scales live on different devices")
+    planes, scales = planes.contiguous(), scales.contiguous()
+    kind = RBE_MEM_DEVICE if planes.is_cuda else RBE_MEM_HOST
+    return _vp(planes.data_ptr()), _vp(scales.data_ptr()), kind, (planes, scales)
+
+
+def rbe_index_create(n_items: int, dim: int, n_planes: int, flags: int = 0) -> Index:
+    out = _vp(None)
+    _check(load_library().rbe_index_create(ctypes.byref(out), n_items, dim, n_planes, flags))
+    return Index(out.value)
+
+
+def rbe_load_chunk(ix: Index, first_item: int, planes, scales, stream=None):
+    count = int(planes.shape[1])
+    pp, sp, kind, keep = _corpus_ptrs(planes, scales, ix.n_planes, count, ix.dim // 64)
+    _check(load_library().rbe_load_chunk(ix.handle, first_item, count, pp, sp, kind, _stream_ptr(stream)))
+    if kind == RBE_MEM_DEVICE:
+        import torch
+        torch.cuda.current_stream().synchronize() if stream is None else stream.synchronize()
+    del keep
+
+
+def rbe_finalize(ix: Index, stream=None):
+    _check(load_library().rbe_finalize(ix.handle, _stream_ptr(stream)))
+
+
+def rbe_load_corpus(planes, scales, flags: int = 0, stream=None) -> Index:
+    """planes [P][N][W] uint64, scales [P][N] float32 (numpy = host, torch cuda = device)."""
+    P, N, W = (int(v) for v in planes.shape)
+    pp, sp, kind, keep = _corpus_ptrs(planes, scales, P, N, W)
+    out = _vp(None)
+    _check(load_library().rbe_load_corpus(ctypes.byref(out), pp, sp, N, 64 * W, P, kind, flags, _stream_ptr(stream)))
+    del keep
+    return Index(out.value)
+
+
+def rbe_free(ix: Index):
+    ix.free()
+
+
+def rbe_encode_query(x, n_planes: int):
+    """x [dim] float32 -> (planes uint64 [n_planes][dim/64], scales float32 [n_planes])."""
+    x, xp = _host(x, np.float32)
+    if x.ndim != 1:
+        raise RbeError(RBE_EINVAL, "x must be one vector")
+    dim = x.shape[0]
+    planes = np.zeros((n_planes, max(dim // 64, 1)), dtype=np.uint64)
+    scales = np.zeros(n_planes, dtype=np.float32)
+    _check(load_library().rbe_encode_query(xp, dim, n_planes, planes.ctypes.data_as(_vp), scales.ctypes.data_as(_vp)))
+    return planes, scales
+
+
+def rbe_search(ix: Index, q_planes, q_scales, k: int, mode: int = RBE_SELECT_EXACT, group_size_I: int = 0,
+               stream=None):
+    """q_planes [Q][Pq][W] uint64, q_scales [Q][Pq] float32 -> (ids int64 [Q][k], scores float32 [Q][k])."""
+    qp, qpp = _host(q_planes, np.uint64)
+    qs, qsp = _host(q_scales, np.float32)
+    if qp.ndim != 3 or qs.ndim != 2 or qp.shape[:2] != qs.shape or qp.shape[2] != ix.dim // 64:
+        raise RbeError(RBE_EINVAL, f"expected q_planes [Q][Pq][{ix.dim // 64}] and q_scales [Q][Pq], "
+                                   f"got {qp.shape} / {qs.shape}")
+    Q, Pq = qs.shape
+    ids = np.empty((Q, max(k, 0)), dtype=np.int64)
+    scores = np.empty((Q, max(k, 0)), dtype=np.float32)
+    _check(load_library().rbe_search(ix.handle, qpp, qsp, Q, Pq, k, mode, group_size_I,
+                                     ids.ctypes.data_as(_vp), scores.ctypes.data_as(_vp), _stream_ptr(stream)))
+    return ids, scores
+
+
+def rbe_set_profiling(ix: Index, enabled: bool):
+    _check(load_library().rbe_set_profiling(ix.handle, int(bool(enabled))))
+
+
+def rbe_get_search_stats(ix: Index) -> dict:
+    st = rbe_search_stats()
+    _check(load_library().rbe_get_search_stats(ix.handle, ctypes.byref(st)))
+    n = st.n_levels
+    return {
+        "n_levels": n, "fallback": st.fallback, "grid_blocks": st.grid_blocks,
+        "items_scanned": list(st.items_scanned)[:n], "candidates_max": list(st.candidates_max)[:n],
+        "scan_ms": list(st.scan_ms)[:n], "select_ms": list(st.select_ms)[:n],
+        "total_gpu_ms": st.total_gpu_ms,
+    }
+
+
+def rbe_set_tuning(ix: Index, sample_ratio: int = 0, cand_capacity: int = 0, blocks_per_cu: int = 0):
+    _check(load_library().rbe_set_tuning(ix.handle, sample_ratio, cand_capacity, blocks_per_cu))
+
+
+def rbe_debug_popcounts(ix: Index, q_planes, first_item: int, count: int, stream=None):
+    qp, qpp = _host(q_planes, np.uint64)
+    Pq = qp.shape[0]
+    out = np.empty((count, ix.n_planes, Pq), dtype=np.int32)
+    _check(load_library().rbe_debug_popcounts(ix.handle, qpp, Pq, first_item, count, out.ctypes.data_as(_vp),
+                                              _stream_ptr(stream)))
+    return out
+
+
+def rbe_debug_scores(ix: Index, q_planes, q_scales, first_item: int, count: int, stream=None):
+    qp, qpp = _host(q_planes, np.uint64)
+    qs, qsp = _host(q_scales, np.float32)
+    out = np.empty(count, dtype=np.float32)
+    _check(load_library().rbe_debug_scores(ix.handle, qpp, qsp, qs.shape[0], first_item, count,
+                                           out.ctypes.data_as(_vp), _stream_ptr(stream)))
+    return out
+
+
+def rbe_debug_read_scales(ix: Index, first_item: int, count: int, stream=None):
+    out = np.empty((ix.n_planes, count), dtype=np.float32)
+    _check(load_library().rbe_debug_read_scales(ix.handle, first_item, count, out.ctypes.data_as(_vp),
+                                                _stream_ptr(stream)))
+    return out
+
+
+def rbe_strerror(code: int) -> str:
+    return load_library().rbe_strerror(code).decode()

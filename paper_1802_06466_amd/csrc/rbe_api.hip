@@ -1,0 +1,640 @@
+// Host side of the RBE retrieval library: the C ABI declared in include/rbe.h,
+// argument checks, device storage, the refinement plan and kernel launches.
+#include "rbe.h"
+#include "rbe_kernels.hpp"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+#define HIP_TRY(expr)                                                                       \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess) {                                                             \
+            set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return (e_ == hipErrorOutOfMemory) ? RBE_ENOMEM : RBE_EHIP;                     \
+        }                                                                                   \
+    } while (0)
+
+#define ARG_CHECK(cond, ...)                                                                \
+    do {                                                                                    \
+        if (!(cond)) {                                                                      \
+            set_error(__VA_ARGS__);                                                         \
+            return RBE_EINVAL;                                                              \
+        }                                                                                   \
+    } while (0)
+
+constexpr uint32_t kMaxEvents = 2 * RBE_MAX_LEVELS + 2;
+
+}  // namespace
+
+struct rbe_index {
+    uint64_t n_items = 0;
+    size_t stride = 0;  // items per plane array on the device (n_items rounded up to a tile)
+    uint32_t dim = 0, W = 0, P = 0, flags = 0;
+    int ready = 0;
+    int n_cu = 0;
+
+    uint64_t* d_planes = nullptr;
+    float* d_scales = nullptr;
+
+    // tuning
+    uint32_t ratio = 64, cap_override = 0, blocks_per_cu = 0;  // 0 = from occupancy
+
+    // search workspace (grown on demand)
+    uint32_t ws_queries = 0, ws_cap = 0, ws_k = 0;
+    uint64_t* d_cand = nullptr;
+    uint32_t* d_count = nullptr;
+    uint64_t* d_tau = nullptr;
+    uint32_t* d_status = nullptr;
+    uint32_t* d_seen = nullptr;     // [RBE_MAX_LEVELS][RBE_MAX_QUERIES]
+    uint32_t* d_qwords = nullptr;   // [Q][PQ][2W]
+    float* d_qcoef = nullptr;       // [Q][PQ+1]
+    int64_t* d_ids = nullptr;
+    float* d_scores = nullptr;
+    // pinned host mirrors
+    uint32_t* h_qwords = nullptr;
+    float* h_qcoef = nullptr;
+    int64_t* h_ids = nullptr;
+    float* h_scores = nullptr;
+    uint32_t* h_status = nullptr;
+    uint32_t* h_seen = nullptr;
+
+    int profiling = 0;
+    hipEvent_t ev[kMaxEvents] = {};
+    bool ev_ok = false;
+    rbe_search_stats stats = {};
+};
+
+namespace {
+
+using namespace rbe;
+
+// ---------------------------------------------------------------- kernel dispatch
+using ScanFn = void (*)(const ScanArgs);
+
+template <int W, int P>
+ScanFn scan_fn_p(uint32_t PQ, bool single)
+{
+    switch (PQ) {
+        case 1: return single ? scan_exact<W, P, 1, true> : scan_exact<W, P, 1, false>;
+        case 2: return single ? scan_exact<W, P, 2, true> : scan_exact<W, P, 2, false>;
+        case 3: return single ? scan_exact<W, P, 3, true> : scan_exact<W, P, 3, false>;
+        default: return single ? scan_exact<W, P, 4, true> : scan_exact<W, P, 4, false>;
+    }
+}
+
+template <int W>
+ScanFn scan_fn_w(uint32_t P, uint32_t PQ, bool single)
+{
+    switch (P) {
+        case 1: return scan_fn_p<W, 1>(PQ, single);
+        case 2: return scan_fn_p<W, 2>(PQ, single);
+        case 3: return scan_fn_p<W, 3>(PQ, single);
+        default: return scan_fn_p<W, 4>(PQ, single);
+    }
+}
+
+ScanFn scan_fn(uint32_t W, uint32_t P, uint32_t PQ, bool single)
+{
+    switch (W) {
+        case 1: return scan_fn_w<1>(P, PQ, single);
+        case 2: return scan_fn_w<2>(P, PQ, single);
+        default: return scan_fn_w<4>(P, PQ, single);
+    }
+}
+
+template <int W, int P>
+void launch_dense_p(uint32_t PQ, uint32_t grid, hipStream_t st, const rbe_index* ix, uint64_t first, uint64_t count, float* out)
+{
+#define RBE_DENSE(PQV)                                                                             \
+    hipLaunchKernelGGL((dense_scores<W, P, PQV>), dim3(grid), dim3(256), 0, st, ix->d_planes,      \
+                       ix->d_scales, ix->stride, ix->d_qwords, ix->d_qcoef, first, count, out)
+    switch (PQ) {
+        case 1: RBE_DENSE(1); break;
+        case 2: RBE_DENSE(2); break;
+        case 3: RBE_DENSE(3); break;
+        default: RBE_DENSE(4); break;
+    }
+#undef RBE_DENSE
+}
+
+template <int W>
+void launch_dense_w(uint32_t P, uint32_t PQ, uint32_t grid, hipStream_t st, const rbe_index* ix, uint64_t first, uint64_t count, float* out)
+{
+    switch (P) {
+        case 1: launch_dense_p<W, 1>(PQ, grid, st, ix, first, count, out); break;
+        case 2: launch_dense_p<W, 2>(PQ, grid, st, ix, first, count, out); break;
+        case 3: launch_dense_p<W, 3>(PQ, grid, st, ix, first, count, out); break;
+        default: launch_dense_p<W, 4>(PQ, grid, st, ix, first, count, out); break;
+    }
+}
+
+void launch_dense(const rbe_index* ix, uint32_t PQ, uint32_t grid, hipStream_t st, uint64_t first, uint64_t count, float* out)
+{
+    switch (ix->W) {
+        case 1: launch_dense_w<1>(ix->P, PQ, grid, st, ix, first, count, out); break;
+        case 2: launch_dense_w<2>(ix->P, PQ, grid, st, ix, first, count, out); break;
+        default: launch_dense_w<4>(ix->P, PQ, grid, st, ix, first, count, out); break;
+    }
+}
+
+// ---------------------------------------------------------------- workspace
+void free_workspace(rbe_index* ix)
+{
+    (void)hipFree(ix->d_cand);   ix->d_cand = nullptr;
+    (void)hipFree(ix->d_ids);    ix->d_ids = nullptr;
+    (void)hipFree(ix->d_scores); ix->d_scores = nullptr;
+    (void)hipHostFree(ix->h_ids);    ix->h_ids = nullptr;
+    (void)hipHostFree(ix->h_scores); ix->h_scores = nullptr;
+    ix->ws_queries = ix->ws_cap = ix->ws_k = 0;
+}
+
+int ensure_fixed(rbe_index* ix)
+{
+    if (ix->d_count) return RBE_OK;
+    const size_t Q = RBE_MAX_QUERIES;
+    HIP_TRY(hipMalloc(&ix->d_count, Q * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ix->d_tau, Q * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&ix->d_status, sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ix->d_seen, RBE_MAX_LEVELS * Q * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ix->d_qwords, Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ix->d_qcoef, Q * (RBE_MAX_PLANES + 1) * sizeof(float)));
+    HIP_TRY(hipHostMalloc(&ix->h_qwords, Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t), hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc(&ix->h_qcoef, Q * (RBE_MAX_PLANES + 1) * sizeof(float), hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc(&ix->h_status, sizeof(uint32_t), hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc(&ix->h_seen, RBE_MAX_LEVELS * Q * sizeof(uint32_t), hipHostMallocDefault));
+    for (uint32_t i = 0; i < kMaxEvents; ++i) HIP_TRY(hipEventCreate(&ix->ev[i]));
+    ix->ev_ok = true;
+    return RBE_OK;
+}
+
+int ensure_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
+{
+    int rc = ensure_fixed(ix);
+    if (rc) return rc;
+    if (Q <= ix->ws_queries && cap <= ix->ws_cap && k <= ix->ws_k) return RBE_OK;
+    const uint32_t nQ = std::max(Q, ix->ws_queries), nC = std::max(cap, ix->ws_cap), nK = std::max(k, ix->ws_k);
+    free_workspace(ix);
+    HIP_TRY(hipMalloc(&ix->d_cand, (size_t)nQ * nC * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&ix->d_ids, (size_t)nQ * nK * sizeof(int64_t)));
+    HIP_TRY(hipMalloc(&ix->d_scores, (size_t)nQ * nK * sizeof(float)));
+    HIP_TRY(hipHostMalloc(&ix->h_ids, (size_t)nQ * nK * sizeof(int64_t), hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc(&ix->h_scores, (size_t)nQ * nK * sizeof(float), hipHostMallocDefault));
+    ix->ws_queries = nQ; ix->ws_cap = nC; ix->ws_k = nK;
+    return RBE_OK;
+}
+
+// Stage one batch of queries: words as 32-bit halves, coefficients (-2 c_i ..., dim * sum c_i).
+int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ, hipStream_t st)
+{
+    const uint32_t W = ix->W;
+    for (uint32_t q = 0; q < Q; ++q) {
+        float sum = 0.0f;
+        for (uint32_t i = 0; i < PQ; ++i) {
+            const float c = q_scales[(size_t)q * PQ + i];
+            if (!std::isfinite(c)) { set_error("q_scales[%u][%u] is not finite", q, i); return RBE_EINVAL; }
+            for (uint32_t w = 0; w < W; ++w) {
+                const uint64_t word = q_planes[((size_t)q * PQ + i) * W + w];
+                ix->h_qwords[((size_t)q * PQ + i) * 2 * W + 2 * w] = (uint32_t)word;
+                ix->h_qwords[((size_t)q * PQ + i) * 2 * W + 2 * w + 1] = (uint32_t)(word >> 32);
+            }
+            ix->h_qcoef[(size_t)q * (PQ + 1) + i] = -2.0f * c;
+            sum += c;
+        }
+        ix->h_qcoef[(size_t)q * (PQ + 1) + PQ] = (float)ix->dim * sum;
+    }
+    HIP_TRY(hipMemcpyAsync(ix->d_qwords, ix->h_qwords, (size_t)Q * PQ * 2 * W * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->d_qcoef, ix->h_qcoef, (size_t)Q * (PQ + 1) * sizeof(float), hipMemcpyHostToDevice, st));
+    return RBE_OK;
+}
+
+struct Level { uint32_t stride, skip, units, valid; };
+
+// Refinement plan for the exact mode.  The coarsest level reads every
+// `stride`-th tile with no threshold and must fit the candidate list whole; each
+// finer level reads `ratio` times more tiles, minus those already read, and
+// keeps only items that reach the k-th best key found so far.
+std::vector<Level> make_plan(uint64_t n_tiles, uint32_t ratio, uint32_t cap)
+{
+    std::vector<uint32_t> strides{1};
+    while ((uint64_t)((n_tiles + strides.back() - 1) / strides.back()) * kTile > cap &&
+           strides.size() < RBE_MAX_LEVELS && (uint64_t)strides.back() * ratio < n_tiles * (uint64_t)ratio)
+        strides.push_back(strides.back() * ratio);
+    std::vector<Level> plan;
+    for (size_t l = strides.size(); l-- > 0;) {
+        Level lv;
+        lv.stride = strides[l];
+        lv.units = (uint32_t)((n_tiles + lv.stride - 1) / lv.stride);
+        lv.skip = (l + 1 == strides.size()) ? 0u : ratio;
+        lv.valid = lv.skip ? lv.units - (lv.units + ratio - 1) / ratio : lv.units;
+        plan.push_back(lv);
+    }
+    return plan;
+}
+
+}  // namespace
+
+// =========================================================================== C ABI
+extern "C" {
+
+const char* rbe_strerror(int code)
+{
+    switch (code) {
+        case RBE_OK: return "ok";
+        case RBE_EINVAL: return "invalid argument";
+        case RBE_ENOMEM: return "out of memory";
+        case RBE_EHIP: return "HIP runtime error";
+        case RBE_ESTATE: return "index is in the wrong state for this call";
+        case RBE_EUNSUPPORTED: return "unsupported configuration";
+        default: return "unknown error code";
+    }
+}
+
+const char* rbe_last_error(void) { return g_err; }
+
+uint64_t rbe_n_items(const rbe_index* ix) { return ix ? ix->n_items : 0; }
+uint32_t rbe_dim(const rbe_index* ix) { return ix ? ix->dim : 0; }
+uint32_t rbe_n_planes(const rbe_index* ix) { return ix ? ix->P : 0; }
+
+int rbe_index_create(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags)
+{
+    ARG_CHECK(out != nullptr, "out is NULL");
+    ARG_CHECK(dim == 64 || dim == 128 || dim == 256, "dim must be 64, 128 or 256 (got %u)", dim);
+    ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES, "n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, n_planes);
+    ARG_CHECK(n_items >= 1 && n_items <= RBE_MAX_ITEMS, "n_items must be 1..%llu", (unsigned long long)RBE_MAX_ITEMS);
+    ARG_CHECK((flags & ~(uint32_t)RBE_COSINE) == 0, "unknown flags 0x%x", flags);
+
+    rbe_index* ix = new (std::nothrow) rbe_index();
+    if (!ix) { set_error("host allocation failed"); return RBE_ENOMEM; }
+    ix->n_items = n_items;
+    ix->dim = dim;
+    ix->W = dim / 64;
+    ix->P = n_planes;
+    ix->flags = flags;
+    ix->stride = (size_t)((n_items + kTile - 1) / kTile) * kTile;
+
+    int dev = 0;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) {
+        set_error("no usable HIP device: %s", hipGetErrorString(e));
+        delete ix;
+        return RBE_EHIP;
+    }
+    ix->n_cu = prop.multiProcessorCount;
+
+    const size_t plane_bytes = (size_t)ix->P * ix->stride * ix->W * sizeof(uint64_t);
+    const size_t scale_bytes = (size_t)ix->P * ix->stride * sizeof(float);
+    e = hipMalloc(&ix->d_planes, plane_bytes);
+    if (e == hipSuccess) e = hipMalloc(&ix->d_scales, scale_bytes);
+    if (e == hipSuccess) e = hipMemset(ix->d_planes, 0, plane_bytes);
+    if (e == hipSuccess) e = hipMemset(ix->d_scales, 0, scale_bytes);
+    if (e != hipSuccess) {
+        set_error("device allocation of %zu bytes failed: %s", plane_bytes + scale_bytes, hipGetErrorString(e));
+        (void)hipFree(ix->d_planes);
+        (void)hipFree(ix->d_scales);
+        delete ix;
+        return e == hipErrorOutOfMemory ? RBE_ENOMEM : RBE_EHIP;
+    }
+    *out = ix;
+    return RBE_OK;
+}
+
+int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uint64_t* planes,
+                   const float* scales, int mem_kind, void* hip_stream)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    if (ix->ready) { set_error("rbe_load_chunk after rbe_finalize"); return RBE_ESTATE; }
+    ARG_CHECK(planes != nullptr && scales != nullptr, "planes/scales is NULL");
+    ARG_CHECK(mem_kind == RBE_MEM_HOST || mem_kind == RBE_MEM_DEVICE, "bad mem_kind %d", mem_kind);
+    ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item,
+              "items [%llu, +%llu) outside the index of %llu items", (unsigned long long)first_item,
+              (unsigned long long)count, (unsigned long long)ix->n_items);
+    if (count == 0) return RBE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const hipMemcpyKind kind = mem_kind == RBE_MEM_HOST ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice;
+    for (uint32_t j = 0; j < ix->P; ++j) {
+        HIP_TRY(hipMemcpyAsync(ix->d_planes + ((size_t)j * ix->stride + first_item) * ix->W,
+                               planes + (size_t)j * count * ix->W, (size_t)count * ix->W * sizeof(uint64_t), kind, st));
+        HIP_TRY(hipMemcpyAsync(ix->d_scales + (size_t)j * ix->stride + first_item,
+                               scales + (size_t)j * count, (size_t)count * sizeof(float), kind, st));
+    }
+    if (mem_kind == RBE_MEM_HOST) HIP_TRY(hipStreamSynchronize(st));
+    return RBE_OK;
+}
+
+int rbe_finalize(rbe_index* ix, void* hip_stream)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    if (ix->ready) { set_error("rbe_finalize called twice"); return RBE_ESTATE; }
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (ix->flags & RBE_COSINE) {
+        const uint32_t grid = (uint32_t)((ix->n_items + 255) / 256);
+        hipLaunchKernelGGL(rbe::fold_cosine, dim3(grid), dim3(256), 0, st, ix->d_planes, ix->d_scales,
+                           ix->stride, ix->W, ix->P, ix->n_items);
+        HIP_TRY(hipGetLastError());
+    }
+    HIP_TRY(hipStreamSynchronize(st));
+    ix->ready = 1;
+    return RBE_OK;
+}
+
+int rbe_load_corpus(rbe_index** out, const uint64_t* planes, const float* scales, uint64_t n_items,
+                    uint32_t dim, uint32_t n_planes, int mem_kind, uint32_t flags, void* hip_stream)
+{
+    ARG_CHECK(out != nullptr, "out is NULL");
+    rbe_index* ix = nullptr;
+    int rc = rbe_index_create(&ix, n_items, dim, n_planes, flags);
+    if (rc) return rc;
+    rc = rbe_load_chunk(ix, 0, n_items, planes, scales, mem_kind, hip_stream);
+    if (!rc) rc = rbe_finalize(ix, hip_stream);
+    if (rc) { rbe_free(ix); return rc; }
+    *out = ix;
+    return RBE_OK;
+}
+
+void rbe_free(rbe_index* ix)
+{
+    if (!ix) return;
+    free_workspace(ix);
+    (void)hipFree(ix->d_planes);
+    (void)hipFree(ix->d_scales);
+    (void)hipFree(ix->d_count);
+    (void)hipFree(ix->d_tau);
+    (void)hipFree(ix->d_status);
+    (void)hipFree(ix->d_seen);
+    (void)hipFree(ix->d_qwords);
+    (void)hipFree(ix->d_qcoef);
+    (void)hipHostFree(ix->h_qwords);
+    (void)hipHostFree(ix->h_qcoef);
+    (void)hipHostFree(ix->h_status);
+    (void)hipHostFree(ix->h_seen);
+    if (ix->ev_ok)
+        for (uint32_t i = 0; i < kMaxEvents; ++i) (void)hipEventDestroy(ix->ev[i]);
+    delete ix;
+}
+
+int rbe_encode_query(const float* x, uint32_t dim, uint32_t n_planes, uint64_t* planes_out, float* scales_out)
+{
+    ARG_CHECK(x && planes_out && scales_out, "NULL argument");
+    ARG_CHECK(dim >= 64 && dim % 64 == 0 && dim <= 4096, "dim must be a multiple of 64 up to 4096 (got %u)", dim);
+    ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES, "n_planes must be 1..%u", RBE_MAX_PLANES);
+    const uint32_t W = dim / 64;
+    std::vector<float> r(x, x + dim);
+    for (uint32_t i = 0; i < dim; ++i)
+        if (!std::isfinite(r[i])) { set_error("x[%u] is not finite", i); return RBE_EINVAL; }
+    for (uint32_t t = 0; t < n_planes; ++t) {
+        double acc = 0.0;
+        for (uint32_t i = 0; i < dim; ++i) acc += std::fabs((double)r[i]);
+        const float scale = (float)(acc / (double)dim);
+        uint64_t* words = planes_out + (size_t)t * W;
+        std::fill(words, words + W, (uint64_t)0);
+        for (uint32_t i = 0; i < dim; ++i) {
+            const bool positive = r[i] > 0.0f;
+            if (positive) words[i >> 6] |= 1ull << (i & 63);
+            const double step = positive ? (double)scale : -(double)scale;
+            r[i] = (float)((double)r[i] - step);
+        }
+        scales_out[t] = scale;
+    }
+    return RBE_OK;
+}
+
+int rbe_set_profiling(rbe_index* ix, int enabled)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    ix->profiling = enabled ? 1 : 0;
+    return RBE_OK;
+}
+
+int rbe_get_search_stats(const rbe_index* ix, rbe_search_stats* out)
+{
+    ARG_CHECK(ix != nullptr && out != nullptr, "NULL argument");
+    *out = ix->stats;
+    return RBE_OK;
+}
+
+int rbe_set_tuning(rbe_index* ix, uint32_t sample_ratio, uint32_t cand_capacity, uint32_t blocks_per_cu)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    ARG_CHECK(sample_ratio == 0 || (sample_ratio >= 8 && sample_ratio <= 4096), "sample_ratio must be 8..4096");
+    ARG_CHECK(cand_capacity == 0 || (cand_capacity >= 2 * (uint32_t)rbe::kTile && cand_capacity <= (1u << 24)),
+              "cand_capacity must be %d..2^24", 2 * rbe::kTile);
+    ARG_CHECK(blocks_per_cu <= 16, "blocks_per_cu must be <= 16");
+    if (sample_ratio) ix->ratio = sample_ratio;
+    if (cand_capacity) ix->cap_override = cand_capacity;
+    if (blocks_per_cu) ix->blocks_per_cu = blocks_per_cu;
+    return RBE_OK;
+}
+
+// Enqueue one scan + select round.  `final_pass` makes the select write the results.
+static int run_round(rbe_index* ix, hipStream_t st, uint32_t Q, uint32_t PQ, uint32_t k, uint32_t cap,
+                     uint32_t v_begin, uint32_t v_end, uint32_t stride, uint32_t skip,
+                     int final_pass, uint32_t level_slot, bool record)
+{
+    ScanArgs sa;
+    sa.planes = ix->d_planes; sa.scales = ix->d_scales; sa.plane_stride = ix->stride; sa.n_items = ix->n_items;
+    sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = Q;
+    sa.tau = ix->d_tau; sa.cand = ix->d_cand; sa.count = ix->d_count; sa.cap = cap;
+    sa.v_begin = v_begin; sa.v_end = v_end; sa.stride = stride; sa.skip = skip;
+    const uint32_t n_valid = v_end - v_begin;
+    if (n_valid > 0) {
+        const ScanFn fn = scan_fn(ix->W, ix->P, PQ, Q == 1);
+        uint32_t per_cu = ix->blocks_per_cu;
+        if (per_cu == 0) {  // as many workgroups as are resident at once: one wave of persistent groups
+            int nb = 0;
+            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0));
+            per_cu = (uint32_t)std::max(nb, 1);
+        }
+        const uint32_t grid = std::min<uint32_t>(n_valid, (uint32_t)ix->n_cu * per_cu);
+        ix->stats.grid_blocks = std::max(ix->stats.grid_blocks, grid);
+        fn<<<dim3(grid), dim3(kBlock), 0, st>>>(sa);
+        HIP_TRY(hipGetLastError());
+    }
+    if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 1], st));
+
+    SelectArgs se;
+    se.cand = ix->d_cand; se.count = ix->d_count; se.tau = ix->d_tau; se.cap = cap; se.k = k;
+    se.status = ix->d_status; se.count_seen = ix->d_seen + (size_t)level_slot * RBE_MAX_QUERIES;
+    se.final_pass = final_pass; se.ids_out = ix->d_ids; se.scores_out = ix->d_scores;
+    hipLaunchKernelGGL(rbe::select_topk, dim3(Q), dim3(kSelBlock), 0, st, se);
+    HIP_TRY(hipGetLastError());
+    if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 2], st));
+    return RBE_OK;
+}
+
+int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
+               uint32_t q_n_planes, uint32_t k, uint32_t mode, uint32_t group_size_I,
+               int64_t* ids_out, float* scores_out, void* hip_stream)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    if (!ix->ready) { set_error("rbe_search before rbe_finalize"); return RBE_ESTATE; }
+    ARG_CHECK(q_planes && q_scales && ids_out && scores_out, "NULL argument");
+    ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries must be 1..%u (got %u)", RBE_MAX_QUERIES, n_queries);
+    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, q_n_planes);
+    ARG_CHECK(k >= 1 && k <= RBE_MAX_K, "k must be 1..%u (got %u)", RBE_MAX_K, k);
+    ARG_CHECK(mode == RBE_SELECT_EXACT || mode == RBE_SELECT_NEARLOSSLESS, "unknown mode %u", mode);
+    ARG_CHECK(group_size_I <= 65535, "group_size_I must be <= 65535");
+    if (mode == RBE_SELECT_NEARLOSSLESS) { set_error("near-lossless mode is not built yet"); return RBE_EUNSUPPORTED; }
+    (void)group_size_I;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    const uint32_t Q = n_queries, PQ = q_n_planes;
+    uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->ratio * k);
+    cap = std::max<uint32_t>(cap, k + 2 * kTile);
+    int rc = ensure_workspace(ix, Q, k, cap);
+    if (rc) return rc;
+
+    rc = stage_queries(ix, q_planes, q_scales, Q, PQ, st);
+    if (rc) return rc;
+
+    const uint64_t n_tiles = ix->stride / kTile;
+    const std::vector<Level> plan = make_plan(n_tiles, ix->ratio, cap);
+    const bool plan_dense_ok = (uint64_t)plan.front().units * kTile <= cap;
+
+    ix->stats = rbe_search_stats{};
+    const bool prof = ix->profiling != 0;
+    bool fallback = !plan_dense_ok;
+
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, st, ix->d_count, ix->d_tau, ix->d_status, Q);
+        HIP_TRY(hipGetLastError());
+        if (!fallback) {
+            if (prof) HIP_TRY(hipEventRecord(ix->ev[0], st));
+            for (size_t l = 0; l < plan.size(); ++l) {
+                const Level& lv = plan[l];
+                rc = run_round(ix, st, Q, PQ, k, cap, 0, lv.valid, lv.stride, lv.skip,
+                               l + 1 == plan.size(), (uint32_t)l, prof);
+                if (rc) return rc;
+                ix->stats.items_scanned[l] = (uint64_t)lv.valid * kTile;
+            }
+            ix->stats.n_levels = (uint32_t)plan.size();
+        } else {
+            // Slow path that cannot overflow: segments of at most cap - k items, each followed
+            // by a selection that compacts the list back to k entries.
+            const uint32_t seg = std::max<uint32_t>(1u, (cap - k) / kTile);
+            for (uint64_t u0 = 0; u0 < n_tiles; u0 += seg) {
+                const uint32_t u1 = (uint32_t)std::min<uint64_t>(n_tiles, u0 + seg);
+                rc = run_round(ix, st, Q, PQ, k, cap, (uint32_t)u0, u1, 1, 0, u1 == n_tiles, 0, false);
+                if (rc) return rc;
+            }
+            ix->stats.n_levels = 1;
+            ix->stats.fallback = 1;
+            ix->stats.items_scanned[0] = ix->stride;
+        }
+        HIP_TRY(hipMemcpyAsync(ix->h_status, ix->d_status, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipMemcpyAsync(ix->h_seen, ix->d_seen, RBE_MAX_LEVELS * RBE_MAX_QUERIES * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipMemcpyAsync(ix->h_ids, ix->d_ids, (size_t)Q * k * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipMemcpyAsync(ix->h_scores, ix->d_scores, (size_t)Q * k * sizeof(float), hipMemcpyDeviceToHost, st));
+        if (prof && !fallback) HIP_TRY(hipEventRecord(ix->ev[kMaxEvents - 1], st));
+        HIP_TRY(hipStreamSynchronize(st));
+        if (!(*ix->h_status & rbe::kStatusOverflow)) break;
+        if (fallback) { set_error("candidate list overflowed in the bounded-segment path"); return RBE_EHIP; }
+        fallback = true;  // a level produced more survivors than the list holds: redo on the slow path
+    }
+
+    if (!fallback) {
+        for (uint32_t l = 0; l < ix->stats.n_levels; ++l) {
+            uint32_t mx = 0;
+            for (uint32_t q = 0; q < Q; ++q) mx = std::max(mx, ix->h_seen[(size_t)l * RBE_MAX_QUERIES + q]);
+            ix->stats.candidates_max[l] = mx;
+            if (prof) {
+                HIP_TRY(hipEventElapsedTime(&ix->stats.scan_ms[l], ix->ev[2 * l], ix->ev[2 * l + 1]));
+                HIP_TRY(hipEventElapsedTime(&ix->stats.select_ms[l], ix->ev[2 * l + 1], ix->ev[2 * l + 2]));
+            }
+        }
+        if (prof) HIP_TRY(hipEventElapsedTime(&ix->stats.total_gpu_ms, ix->ev[0], ix->ev[kMaxEvents - 1]));
+    }
+    std::memcpy(ids_out, ix->h_ids, (size_t)Q * k * sizeof(int64_t));
+    std::memcpy(scores_out, ix->h_scores, (size_t)Q * k * sizeof(float));
+    return RBE_OK;
+}
+
+int rbe_debug_popcounts(rbe_index* ix, const uint64_t* q_planes, uint32_t q_n_planes, uint64_t first_item,
+                        uint64_t count, int32_t* out, void* hip_stream)
+{
+    ARG_CHECK(ix && q_planes && out, "NULL argument");
+    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u", RBE_MAX_PLANES);
+    ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item, "item range outside the index");
+    ARG_CHECK(count <= (1ull << 26), "count too large for a debug dump");
+    if (count == 0) return RBE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint64_t* d_q = nullptr;
+    int32_t* d_out = nullptr;
+    const size_t qbytes = (size_t)q_n_planes * ix->W * sizeof(uint64_t);
+    const size_t obytes = (size_t)count * ix->P * q_n_planes * sizeof(int32_t);
+    HIP_TRY(hipMalloc(&d_q, qbytes));
+    hipError_t e = hipMalloc(&d_out, obytes);
+    if (e == hipSuccess) e = hipMemcpyAsync(d_q, q_planes, qbytes, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(rbe::dense_popcounts, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st,
+                           ix->d_planes, ix->stride, ix->W, ix->P, d_q, q_n_planes, first_item, count, d_out);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, obytes, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(d_q);
+    (void)hipFree(d_out);
+    if (e != hipSuccess) { set_error("rbe_debug_popcounts: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    return RBE_OK;
+}
+
+int rbe_debug_scores(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t q_n_planes,
+                     uint64_t first_item, uint64_t count, float* out, void* hip_stream)
+{
+    ARG_CHECK(ix && q_planes && q_scales && out, "NULL argument");
+    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u", RBE_MAX_PLANES);
+    ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item, "item range outside the index");
+    ARG_CHECK(count <= (1ull << 28), "count too large for a debug dump");
+    if (count == 0) return RBE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = ensure_fixed(ix);
+    if (rc) return rc;
+    rc = stage_queries(ix, q_planes, q_scales, 1, q_n_planes, st);
+    if (rc) return rc;
+    float* d_out = nullptr;
+    HIP_TRY(hipMalloc(&d_out, (size_t)count * sizeof(float)));
+    launch_dense(ix, q_n_planes, (uint32_t)((count + 255) / 256), st, first_item, count, d_out);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, (size_t)count * sizeof(float), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(d_out);
+    if (e != hipSuccess) { set_error("rbe_debug_scores: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    return RBE_OK;
+}
+
+int rbe_debug_read_scales(rbe_index* ix, uint64_t first_item, uint64_t count, float* out, void* hip_stream)
+{
+    ARG_CHECK(ix && out, "NULL argument");
+    ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item, "item range outside the index");
+    hipStream_t st = (hipStream_t)hip_stream;
+    for (uint32_t j = 0; j < ix->P; ++j)
+        HIP_TRY(hipMemcpyAsync(out + (size_t)j * count, ix->d_scales + (size_t)j * ix->stride + first_item,
+                               (size_t)count * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    return RBE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+"""Acceptance protocol shared by the GPU parity tests.
+
+The GPU combines scores in fp32, the oracle in float64, so ids can legitimately
+differ where scores tie to within rounding at the k-th place.  Tolerance: 1e-5
+relative to the score, but never tighter than the fp32 rounding floor of the
+sum itself -- the GPU performs Pq+1 roundings per plane and P per item on
+partial sums bounded by M = d * sum_i |c_i| * max_z sum_j a_j[z], i.e. an
+absolute error up to about (Pq+2) * P * 2^-24 * M <= 1e-6 * M, which matters only
+when a score is a near-cancellation (random, unclustered corpora).  With s_k the
+oracle's k-th best score and eps = max(1e-5 * |s_k|, 1e-6 * M) a result is
+accepted iff
+  * ids are unique, in range, and padded with -1 / -inf only past the number
+    of existing results;
+  * every returned score is within 1e-5 relative (or 1e-6 * M absolute) of the
+    oracle's score of that id;
+  * every item the oracle scores above s_k + eps is returned;
+  * no returned item scores below s_k - eps in the oracle;
+  * the list is sorted by (score desc, id asc) in the GPU's own fp32 scores.
+"""
+import numpy as np
+
+import oracle
+
+REL = 1e-5
+
+
+def check_topk(planes, scales, q_planes, q_scales, k, ids, scores, n_valid=None, exact=None):
+    """Check one query's result (ids int64[k], scores f32[k]).  `exact` may carry a
+    precomputed oracle.topk result; n_valid is the number of results that exist."""
+    N = planes.shape[1]
+    m = min(k, N) if n_valid is None else n_valid
+    ids = np.asarray(ids)
+    scores = np.asarray(scores)
+    assert ids.shape == (k,) and scores.shape == (k,)
+    assert np.all(ids[m:] == -1), "tail must be padded with id -1"
+    assert np.all(np.isneginf(scores[m:])), "tail must be padded with -inf"
+    got = ids[:m]
+    assert got.min(initial=0) >= 0 and got.max(initial=0) < N, "id out of range"
+    assert np.unique(got).size == m, "duplicate ids in the result"
+
+    o_ids, o_sc = exact if exact is not None else oracle.topk(planes, scales, q_planes, q_scales, k)
+    if m == 0:
+        return
+    s_k = o_sc[m - 1]
+    floor = rounding_floor(planes, scales, q_scales)
+    eps = max(REL * abs(s_k), floor)
+    true_sc = oracle.scores_at(planes, scales, q_planes, q_scales, got)
+    np.testing.assert_allclose(scores[:m], true_sc, rtol=REL, atol=floor,
+                               err_msg="returned score differs from the oracle's score of that id")
+    assert np.all(true_sc >= s_k - eps), "returned an item below the k-th best"
+    must = set(o_ids[:m][o_sc[:m] > s_k + eps].tolist())
+    missing = must - set(got.tolist())
+    assert not missing, f"missed {len(missing)} items above the k-th best, e.g. {sorted(missing)[:5]}"
+    # order: score descending, equal scores by ascending id
+    sc = scores[:m]
+    assert np.all(sc[:-1] >= sc[1:]), "scores not sorted"
+    same = sc[:-1] == sc[1:]
+    assert np.all(got[:-1][same] < got[1:][same]), "equal scores must be ordered by id"
+
+
+def rounding_floor(planes, scales, q_scales):
+    d = 64 * planes.shape[2]
+    return 1e-6 * d * float(np.sum(np.abs(q_scales))) * float(np.max(np.sum(scales.astype(np.float64), axis=0)))
+
+
+def check_batch(planes, scales, q_planes, q_scales, k, ids, scores):
+    for q in range(q_planes.shape[0]):
+        check_topk(planes, scales, q_planes[q], q_scales[q], k, ids[q], scores[q])
+
+
+def score_tolerance(scales, q_scales, d):
+    """Absolute tolerance for dense fp32 scores: 1e-5 of the largest magnitude the
+    sum can reach, d * (sum_i |c_i|) * (sum_j a_j[z])."""
+    return REL * d * float(np.sum(np.abs(q_scales))) * np.sum(scales.astype(np.float64), axis=0)

@@ -1,0 +1,294 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1802_06466_amd as rbe
+import rbe_synth
+from parity import check_batch, check_topk, score_tolerance
+
+pytestmark = pytest.mark.gpu
+
+
+def random_corpus(rng, N, d, P):
+    planes = rng.integers(0, 2**64, size=(P, N, d // 64), dtype=np.uint64)
+    scales = rng.uniform(0.01, 1.0, size=(P, N)).astype(np.float32)
+    return planes, scales
+
+
+def random_queries(rng, Q, d, Pq):
+    return (rng.integers(0, 2**64, size=(Q, Pq, d // 64), dtype=np.uint64),
+            rng.uniform(0.01, 1.0, size=(Q, Pq)).astype(np.float32))
+
+
+def clustered(N, d, P, n_clusters, sigma, Q, Pq, seed=0, sort_by_cluster=False):
+    c = rbe_synth.centres_numpy(n_clusters, d)
+    x = rbe_synth.vectors_numpy(N, c, sigma, seed=rbe_synth.SEED_ITEMS + seed, sort_by_cluster=sort_by_cluster)
+    q = rbe_synth.vectors_numpy(Q, c, sigma, seed=rbe_synth.SEED_QUERIES + seed)
+    planes, scales = oracle.encode(x, P)
+    qp, qs = oracle.encode(q, Pq)
+    return planes, scales, np.ascontiguousarray(qp.transpose(1, 0, 2)), np.ascontiguousarray(qs.T)
+
+
+# ------------------------------------------------------------------ binary dot products: bit-exact
+@pytest.mark.parametrize("N,d,P,Pq", [(1, 64, 1, 1), (63, 64, 3, 3), (1025, 64, 3, 2), (5000, 128, 4, 4),
+                                      (3000, 128, 2, 3), (2049, 256, 2, 2)])
+def test_popcounts_bit_exact(N, d, P, Pq):
+    rng = np.random.default_rng(N + d + P + Pq)
+    planes, scales = random_corpus(rng, N, d, P)
+    qp, _ = random_queries(rng, 1, d, Pq)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    got = rbe.rbe_debug_popcounts(ix, qp[0], 0, N)
+    np.testing.assert_array_equal(got, oracle.popcounts(planes, qp[0]))
+    if N > 100:
+        part = rbe.rbe_debug_popcounts(ix, qp[0], 37, 50)
+        np.testing.assert_array_equal(part, oracle.popcounts(planes[:, 37:87], qp[0]))
+    rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ combined fp32 scores
+@pytest.mark.parametrize("N,d,P,Pq", [(777, 64, 1, 1), (4099, 64, 3, 3), (4099, 64, 2, 3), (3001, 128, 4, 4),
+                                      (1500, 128, 4, 1), (1030, 256, 3, 2)])
+def test_dense_scores_within_tolerance(N, d, P, Pq):
+    rng = np.random.default_rng(7 * N + d + P + Pq)
+    planes, scales = random_corpus(rng, N, d, P)
+    qp, qs = random_queries(rng, 1, d, Pq)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    got = rbe.rbe_debug_scores(ix, qp[0], qs[0], 0, N).astype(np.float64)
+    ref = oracle.scores(planes, scales, qp[0], qs[0])
+    assert np.all(np.abs(got - ref) <= score_tolerance(scales, qs[0], d))
+    rbe.rbe_free(ix)
+
+
+def test_dense_scores_on_encoded_corpus_relative():
+    planes, scales, qp, qs = clustered(20000, 64, 3, 16, 0.3, 1, 3)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    got = rbe.rbe_debug_scores(ix, qp[0], qs[0], 0, 20000).astype(np.float64)
+    ref = oracle.scores(planes, scales, qp[0], qs[0])
+    big = np.abs(ref) > 0.1 * np.abs(ref).max()
+    np.testing.assert_allclose(got[big], ref[big], rtol=1e-5)
+    rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ exact search, size sweep
+@pytest.mark.parametrize("N", [1, 63, 64, 65, 1000, 1024, 1025, 65537])
+@pytest.mark.parametrize("k", [1, 100, 1000])
+def test_search_sizes(N, k):
+    rng = np.random.default_rng(N * 31 + k)
+    planes, scales = random_corpus(rng, N, 64, 3)
+    qp, qs = random_queries(rng, 2, 64, 3)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k)
+    check_batch(planes, scales, qp, qs, k, ids, sc)
+    rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("d,P,Pq,Q,k", [(64, 1, 1, 1, 10), (64, 2, 3, 8, 100), (64, 3, 3, 64, 50), (64, 4, 4, 3, 4096),
+                                        (128, 4, 4, 8, 1000), (128, 1, 2, 1, 7), (128, 3, 1, 5, 333), (256, 2, 2, 4, 100)])
+def test_search_shapes(d, P, Pq, Q, k):
+    N = 30011
+    rng = np.random.default_rng(d + 10 * P + 100 * Pq + Q + k)
+    planes, scales = random_corpus(rng, N, d, P)
+    qp, qs = random_queries(rng, Q, d, Pq)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k)
+    check_batch(planes, scales, qp, qs, k, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_k_larger_than_corpus():
+    rng = np.random.default_rng(5)
+    planes, scales = random_corpus(rng, 300, 64, 2)
+    qp, qs = random_queries(rng, 3, 64, 2)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 301)
+    check_batch(planes, scales, qp, qs, 301, ids, sc)
+    assert np.all(ids[:, 300] == -1)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 300)
+    check_batch(planes, scales, qp, qs, 300, ids, sc)
+    rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ multi-level plan and the slow path
+def test_multi_level_plan_small_capacity():
+    planes, scales, qp, qs = clustered(300_000, 64, 3, 64, 0.3, 4, 3, seed=1)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    rbe.rbe_set_tuning(ix, sample_ratio=8, cand_capacity=4096)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 100)
+    st = rbe.rbe_get_search_stats(ix)
+    assert st["n_levels"] >= 3 and not st["fallback"]
+    check_batch(planes, scales, qp, qs, 100, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_overflow_takes_bounded_segment_path_and_stays_exact():
+    # every tile the coarse levels sample holds only weak items, so their threshold
+    # prunes nothing and the finer level overflows the (tiny) candidate list
+    rng = np.random.default_rng(6)
+    N = 200_000
+    planes, scales = random_corpus(rng, N, 64, 2)
+    tile = np.arange(N) // 1024
+    scales[:, tile % 8 == 0] *= np.float32(1e-3)
+    qp, qs = random_queries(rng, 2, 64, 2)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    rbe.rbe_set_tuning(ix, sample_ratio=8, cand_capacity=4096)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 50)
+    assert rbe.rbe_get_search_stats(ix)["fallback"] == 1
+    check_batch(planes, scales, qp, qs, 50, ids, sc)
+    rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ adversarial orders and ties
+def test_all_items_identical():
+    N, k = 50_000, 200
+    one_p = np.array([0x0123456789ABCDEF], dtype=np.uint64)
+    planes = np.broadcast_to(one_p, (3, N, 1)).copy()
+    scales = np.full((3, N), 0.25, dtype=np.float32)
+    qp = planes[:, :1].transpose(1, 0, 2).copy()
+    qs = np.full((1, 3), 0.5, dtype=np.float32)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k)
+    np.testing.assert_array_equal(ids[0], np.arange(k))        # all tie: lowest ids win, in order
+    assert np.all(sc[0] == sc[0][0])
+    rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("order", ["ascending", "descending"])
+def test_items_sorted_by_score(order):
+    planes, scales, qp, qs = clustered(120_000, 64, 3, 32, 0.3, 1, 3, seed=2)
+    s = oracle.scores(planes, scales, qp[0], qs[0])
+    perm = np.argsort(s if order == "ascending" else -s, kind="stable")
+    planes, scales = np.ascontiguousarray(planes[:, perm]), np.ascontiguousarray(scales[:, perm])
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 500)
+    check_batch(planes, scales, qp, qs, 500, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_topk_inside_one_wave_row():
+    rng = np.random.default_rng(8)
+    N, k = 100_000, 100
+    planes, scales = random_corpus(rng, N, 64, 3)
+    qp, qs = random_queries(rng, 1, 64, 3)
+    # plant k near-copies of the query in one 256-item row that no coarse level samples
+    start = 1024 * 37 + 256 * 2
+    planes[:, start:start + k, 0] = qp[0][:, None, 0][:3]
+    scales[:, start:start + k] = rng.uniform(2.0, 3.0, size=(3, k)).astype(np.float32)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k)
+    assert set(ids[0].tolist()) == set(range(start, start + k))
+    check_batch(planes, scales, qp, qs, k, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_duplicates_and_permutation_invariance():
+    x = rbe_synth.near_duplicates_numpy(40_000, 64, 50, seed=3)
+    planes, scales = oracle.encode(x, 3)
+    qp, qs = oracle.encode(x[:2], 3)
+    qp, qs = np.ascontiguousarray(qp.transpose(1, 0, 2)), np.ascontiguousarray(qs.T)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 1500)
+    check_batch(planes, scales, qp, qs, 1500, ids, sc)
+    rbe.rbe_free(ix)
+    perm = np.random.default_rng(9).permutation(40_000)
+    ix2 = rbe.rbe_load_corpus(np.ascontiguousarray(planes[:, perm]), np.ascontiguousarray(scales[:, perm]))
+    ids2, sc2 = rbe.rbe_search(ix2, qp, qs, 1500)
+    np.testing.assert_array_equal(sc2, sc)                      # same multiset of scores, bit for bit
+    rbe.rbe_free(ix2)
+
+
+# ------------------------------------------------------------------ loading paths
+def test_chunked_and_device_loading():
+    import torch
+    rng = np.random.default_rng(10)
+    N = 10_000
+    planes, scales = random_corpus(rng, N, 128, 3)
+    qp, qs = random_queries(rng, 2, 128, 3)
+    ix = rbe.rbe_index_create(N, 128, 3)
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_search(ix, qp, qs, 5)                            # not finalized
+    cuts = [0, 1, 1023, 4096, 7777, N]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        if (a // 1000) % 2:
+            rbe.rbe_load_chunk(ix, a, planes[:, a:b], scales[:, a:b])
+        else:
+            tp = torch.from_numpy(planes[:, a:b].view(np.int64).copy()).cuda()
+            ts = torch.from_numpy(scales[:, a:b].copy()).cuda()
+            rbe.rbe_load_chunk(ix, a, tp, ts)
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_load_chunk(ix, N - 5, planes[:, :10], scales[:, :10])   # out of range
+    rbe.rbe_finalize(ix)
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_load_chunk(ix, 0, planes[:, :10], scales[:, :10])       # after finalize
+    ids, sc = rbe.rbe_search(ix, qp, qs, 64)
+    check_batch(planes, scales, qp, qs, 64, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_cosine_flag_folds_item_norm():
+    planes, scales, qp, qs = clustered(30_000, 64, 3, 16, 0.3, 2, 3, seed=4)
+    scales = (scales * np.random.default_rng(11).uniform(0.2, 5.0, size=scales.shape[1]).astype(np.float32)[None])
+    ix = rbe.rbe_load_corpus(planes, scales, flags=rbe.RBE_COSINE)
+    folded = oracle.fold_cosine(planes, scales)
+    np.testing.assert_allclose(rbe.rbe_debug_read_scales(ix, 0, 30_000), folded, rtol=2e-7)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 100)
+    check_batch(planes, folded, qp, qs, 100, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_paper_operating_point_dyadic_weights_asymmetric():
+    """rbe*: 3 query vectors, 2 keyword vectors, weights 2^-t, stored inverse norm."""
+    rng = np.random.default_rng(12)
+    N = 150_000
+    planes = rng.integers(0, 2**64, size=(2, N, 1), dtype=np.uint64)
+    weights = np.array([[1.0], [0.5]], dtype=np.float32) * np.ones((2, N), dtype=np.float32)
+    qp = rng.integers(0, 2**64, size=(4, 3, 1), dtype=np.uint64)
+    qs = np.tile(np.array([1.0, 0.5, 0.25], dtype=np.float32), (4, 1))
+    ix = rbe.rbe_load_corpus(planes, weights, flags=rbe.RBE_COSINE)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 1000)
+    check_batch(planes, oracle.fold_cosine(planes, weights), qp, qs, 1000, ids, sc)
+    rbe.rbe_free(ix)
+    # without the norm the scores are small dyadic rationals: massive exact ties
+    ix = rbe.rbe_load_corpus(planes, weights)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 1000)
+    check_batch(planes, weights, qp, qs, 1000, ids, sc)
+    for q in range(4):      # exact arithmetic on both sides: identical ids
+        o_ids, o_sc = oracle.topk(planes, weights, qp[q], qs[q], 1000)
+        np.testing.assert_array_equal(ids[q], o_ids)
+        np.testing.assert_array_equal(sc[q].astype(np.float64), o_sc)
+    rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ paper-shaped configurations
+def test_config_1M_d64_k100():
+    planes, scales, qp, qs = clustered(1_000_000, 64, 3, 256, 0.3, 1, 3)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 100)
+    check_batch(planes, scales, qp, qs, 100, ids, sc)
+    assert not rbe.rbe_get_search_stats(ix)["fallback"]
+    rbe.rbe_free(ix)
+
+
+def test_config_1M_cluster_sorted_ids():
+    planes, scales, qp, qs = clustered(1_000_000, 64, 3, 256, 0.3, 4, 3, seed=5, sort_by_cluster=True)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 1000)
+    check_batch(planes, scales, qp, qs, 1000, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_config_d128_4planes_batch():
+    planes, scales, qp, qs = clustered(400_000, 128, 4, 512, 0.3, 16, 4, seed=6)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 1000)
+    check_batch(planes, scales, qp, qs, 1000, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_near_duplicate_clusters_k4000():
+    planes, scales, qp, qs = clustered(600_000, 64, 3, 64, 0.05, 8, 3, seed=7)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 4000)
+    check_batch(planes, scales, qp, qs, 4000, ids, sc)
+    rbe.rbe_free(ix)
