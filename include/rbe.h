@@ -79,9 +79,14 @@ enum { RBE_SELECT_EXACT = 0, RBE_SELECT_NEARLOSSLESS = 1 };
 
 /* ---------------------------------------------------------------------------
  * Corpus (the offline keyword side of Fig. 3: embeddings are produced ahead of
- * time and uploaded once, Sec. 5).  Storage on the device is structure-of-
- * arrays by ingredient vector (Sec. 6.1): all base vectors, then all first
- * residuals, ..., then the scale arrays in the same order.
+ * time and uploaded once, Sec. 5).  On the device, items are kept in tiles of
+ * 1024 consecutive ids; inside a tile storage is structure-of-arrays by
+ * ingredient vector (the grouping of Sec. 6.1): all base vectors of the tile,
+ * then all first residuals, ..., then the scale arrays in the same order.
+ * Tiles are stored in "nested-sample-major" order, so that every evenly
+ * strided sample of tiles (stride = a power of the sample ratio) is a
+ * contiguous prefix of memory.  Callers never see this order: the arrays they
+ * pass are plain [plane][item][word] and ids are item numbers.
  * ------------------------------------------------------------------------- */
 
 /* Allocates device storage for n_items items of `dim` dimensions and
@@ -91,6 +96,14 @@ enum { RBE_SELECT_EXACT = 0, RBE_SELECT_NEARLOSSLESS = 1 };
  * bytes, rounded up to a multiple of 1024 items.                             */
 int rbe_index_create(rbe_index **out, uint64_t n_items, uint32_t dim,
                      uint32_t n_planes, uint32_t flags);
+
+/* Same, with an explicit sample ratio r (2..4096; 0 = the default 64): level c
+ * of the exact search reads every r^c-th tile, so each refinement round reads r
+ * times more of the corpus than the one before and hands about r*k survivors
+ * per query to its selection.  The ratio fixes the tile order, hence it is a
+ * property of the index.                                                      */
+int rbe_index_create_ex(rbe_index **out, uint64_t n_items, uint32_t dim,
+                        uint32_t n_planes, uint32_t flags, uint32_t sample_ratio);
 
 /* Copies items [first_item, first_item + count) into the index.
  *   planes: [n_planes][count][dim/64] uint64, scales: [n_planes][count] float,
@@ -170,13 +183,11 @@ int rbe_set_profiling(rbe_index *ix, int enabled);
 int rbe_get_search_stats(const rbe_index *ix, rbe_search_stats *out);
 
 /* Tuning knobs (0 keeps the current value):
- *   sample_ratio    : each refinement level scans sample_ratio times more of
- *                     the corpus than the one before (default 64)
- *   cand_capacity   : candidate slots per query (default max(65536, 4*ratio*k))
+ *   cand_capacity   : candidate slots per query (default max(65536, 4*ratio*k));
+ *                     2048..2^24
  *   blocks_per_cu   : persistent workgroups per compute unit for the scan
  *                     (default: as many as the kernel's occupancy allows)      */
-int rbe_set_tuning(rbe_index *ix, uint32_t sample_ratio, uint32_t cand_capacity,
-                   uint32_t blocks_per_cu);
+int rbe_set_tuning(rbe_index *ix, uint32_t cand_capacity, uint32_t blocks_per_cu);
 
 /* ---------------------------------------------------------------------------
  * Test hooks (dense dumps for parity checks; small ranges only).
@@ -198,6 +209,19 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
  * first_item+count) back: out [n_planes][count] float (host).                */
 int rbe_debug_read_scales(rbe_index *ix, uint64_t first_item, uint64_t count,
                           float *out, void *hip_stream);
+
+/* Tile order (pure host functions, for tests): physical position of logical
+ * tile `tile` in a corpus of n_tiles tiles with the given sample ratio, and the
+ * inverse.                                                                     */
+uint32_t rbe_debug_tile_to_phys(uint32_t n_tiles, uint32_t sample_ratio, uint32_t tile);
+uint32_t rbe_debug_phys_to_tile(uint32_t n_tiles, uint32_t sample_ratio, uint32_t phys);
+
+/* Measurement yardstick: enqueues a plain copy kernel ("calib_copy") of `bytes`
+ * bytes from src_dev to dst_dev (DEVICE pointers, 16-byte aligned, bytes a
+ * multiple of 16, non-overlapping).  It reads and writes exactly `bytes` each,
+ * so hardware-counter readings of other kernels can be scaled by what the same
+ * counters report for it.  Asynchronous on the stream.                         */
+int rbe_debug_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
 
 const char *rbe_strerror(int code);
 const char *rbe_last_error(void);

@@ -55,6 +55,7 @@ _u64, _u32, _i32, _vp = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c
 # name -> (restype, argtypes); the single source for ctypes prototypes
 PROTOTYPES = {
     "rbe_index_create": (_i32, [ctypes.POINTER(_vp), _u64, _u32, _u32, _u32]),
+    "rbe_index_create_ex": (_i32, [ctypes.POINTER(_vp), _u64, _u32, _u32, _u32, _u32]),
     "rbe_load_chunk": (_i32, [_vp, _u64, _u64, _vp, _vp, _i32, _vp]),
     "rbe_finalize": (_i32, [_vp, _vp]),
     "rbe_load_corpus": (_i32, [ctypes.POINTER(_vp), _vp, _vp, _u64, _u32, _u32, _i32, _u32, _vp]),
@@ -63,10 +64,13 @@ PROTOTYPES = {
     "rbe_search": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_set_profiling": (_i32, [_vp, _i32]),
     "rbe_get_search_stats": (_i32, [_vp, ctypes.POINTER(rbe_search_stats)]),
-    "rbe_set_tuning": (_i32, [_vp, _u32, _u32, _u32]),
+    "rbe_set_tuning": (_i32, [_vp, _u32, _u32]),
+    "rbe_debug_tile_to_phys": (_u32, [_u32, _u32, _u32]),
+    "rbe_debug_phys_to_tile": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
+    "rbe_debug_copy": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
     "rbe_strerror": (ctypes.c_char_p, [_i32]),
     "rbe_last_error": (ctypes.c_char_p, []),
     "rbe_n_items": (_u64, [_vp]),
@@ -182,6 +186,12 @@ def rbe_index_create(n_items: int, dim: int, n_planes: int, flags: int = 0) -> I
     return Index(out.value)
 
 
+def rbe_index_create_ex(n_items: int, dim: int, n_planes: int, flags: int = 0, sample_ratio: int = 0) -> Index:
+    out = _vp(None)
+    _check(load_library().rbe_index_create_ex(ctypes.byref(out), n_items, dim, n_planes, flags, sample_ratio))
+    return Index(out.value)
+
+
 def rbe_load_chunk(ix: Index, first_item: int, planes, scales, stream=None):
     count = int(planes.shape[1])
     pp, sp, kind, keep = _corpus_ptrs(planes, scales, ix.n_planes, count, ix.dim // 64)
@@ -254,8 +264,16 @@ def rbe_get_search_stats(ix: Index) -> dict:
     }
 
 
-def rbe_set_tuning(ix: Index, sample_ratio: int = 0, cand_capacity: int = 0, blocks_per_cu: int = 0):
-    _check(load_library().rbe_set_tuning(ix.handle, sample_ratio, cand_capacity, blocks_per_cu))
+def rbe_set_tuning(ix: Index, cand_capacity: int = 0, blocks_per_cu: int = 0):
+    _check(load_library().rbe_set_tuning(ix.handle, cand_capacity, blocks_per_cu))
+
+
+def rbe_debug_tile_to_phys(n_tiles: int, sample_ratio: int, tile: int) -> int:
+    return int(load_library().rbe_debug_tile_to_phys(n_tiles, sample_ratio, tile))
+
+
+def rbe_debug_phys_to_tile(n_tiles: int, sample_ratio: int, phys: int) -> int:
+    return int(load_library().rbe_debug_phys_to_tile(n_tiles, sample_ratio, phys))
 
 
 def rbe_debug_popcounts(ix: Index, q_planes, first_item: int, count: int, stream=None):
@@ -281,6 +299,14 @@ def rbe_debug_read_scales(ix: Index, first_item: int, count: int, stream=None):
     _check(load_library().rbe_debug_read_scales(ix.handle, first_item, count, out.ctypes.data_as(_vp),
                                                 _stream_ptr(stream)))
     return out
+
+
+def rbe_debug_copy(dst, src, stream=None):
+    """Plain device-to-device copy kernel between two torch cuda tensors of equal byte size."""
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size() or not (src.is_cuda and dst.is_cuda):
+        raise RbeError(RBE_EINVAL, "src and dst must be cuda tensors of equal byte size")
+    _check(load_library().rbe_debug_copy(_vp(dst.data_ptr()), _vp(src.data_ptr()), nbytes, _stream_ptr(stream)))
 
 
 def rbe_strerror(code: int) -> str:

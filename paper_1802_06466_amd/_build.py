@@ -9,7 +9,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librbe_hip.so")
 SOURCES = [os.path.join(CSRC, "rbe_api.hip")]
-HEADERS = [os.path.join(CSRC, "rbe_kernels.hpp"), os.path.join(ROOT, "include", "rbe.h")]
+HEADERS = [os.path.join(CSRC, "rbe_kernels.hpp"), os.path.join(CSRC, "rbe_layout.hpp"),
+           os.path.join(ROOT, "include", "rbe.h")]
 
 
 def hipcc_command(out: str = LIB) -> list[str]:

@@ -50,16 +50,17 @@ constexpr uint32_t kMaxEvents = 2 * RBE_MAX_LEVELS + 2;
 
 struct rbe_index {
     uint64_t n_items = 0;
-    size_t stride = 0;  // items per plane array on the device (n_items rounded up to a tile)
     uint32_t dim = 0, W = 0, P = 0, flags = 0;
     int ready = 0;
+    bool loaded_any = false;
     int n_cu = 0;
 
-    uint64_t* d_planes = nullptr;
-    float* d_scales = nullptr;
+    char* d_tiles = nullptr;        // n_tiles tiles in nested-sample-major order (rbe_layout.hpp)
+    rbe::Layout layout = {};
+    rbe::TileGeom geom = {};
 
     // tuning
-    uint32_t ratio = 64, cap_override = 0, blocks_per_cu = 0;  // 0 = from occupancy
+    uint32_t cap_override = 0, blocks_per_cu = 0;  // 0 = derived
 
     // search workspace (grown on demand)
     uint32_t ws_queries = 0, ws_cap = 0, ws_k = 0;
@@ -128,8 +129,8 @@ template <int W, int P>
 void launch_dense_p(uint32_t PQ, uint32_t grid, hipStream_t st, const rbe_index* ix, uint64_t first, uint64_t count, float* out)
 {
 #define RBE_DENSE(PQV)                                                                             \
-    hipLaunchKernelGGL((dense_scores<W, P, PQV>), dim3(grid), dim3(256), 0, st, ix->d_planes,      \
-                       ix->d_scales, ix->stride, ix->d_qwords, ix->d_qcoef, first, count, out)
+    hipLaunchKernelGGL((dense_scores<W, P, PQV>), dim3(grid), dim3(256), 0, st, ix->d_tiles,       \
+                       ix->layout, ix->d_qwords, ix->d_qcoef, first, count, out)
     switch (PQ) {
         case 1: RBE_DENSE(1); break;
         case 2: RBE_DENSE(2); break;
@@ -229,27 +230,23 @@ int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales
     return RBE_OK;
 }
 
-struct Level { uint32_t stride, skip, units, valid; };
+struct Level { uint32_t p_begin, p_end; };
 
-// Refinement plan for the exact mode.  The coarsest level reads every
-// `stride`-th tile with no threshold and must fit the candidate list whole; each
-// finer level reads `ratio` times more tiles, minus those already read, and
-// keeps only items that reach the k-th best key found so far.
-std::vector<Level> make_plan(uint64_t n_tiles, uint32_t ratio, uint32_t cap)
+// Refinement plan for the exact mode.  Thanks to the nested-sample-major tile
+// order every level is a contiguous range of physical tiles.  The coarsest
+// level (an evenly strided sample of the corpus) is read with no threshold and
+// must fit the candidate list whole; each finer level reads `ratio` times more
+// tiles, minus those already read, and keeps only items that reach the k-th
+// best key found so far -- a proven lower bound for the final k-th best.
+// Returns an empty plan if even the coarsest sample does not fit `cap`.
+std::vector<Level> make_plan(const rbe::Layout& l, uint32_t cap)
 {
-    std::vector<uint32_t> strides{1};
-    while ((uint64_t)((n_tiles + strides.back() - 1) / strides.back()) * kTile > cap &&
-           strides.size() < RBE_MAX_LEVELS && (uint64_t)strides.back() * ratio < n_tiles * (uint64_t)ratio)
-        strides.push_back(strides.back() * ratio);
     std::vector<Level> plan;
-    for (size_t l = strides.size(); l-- > 0;) {
-        Level lv;
-        lv.stride = strides[l];
-        lv.units = (uint32_t)((n_tiles + lv.stride - 1) / lv.stride);
-        lv.skip = (l + 1 == strides.size()) ? 0u : ratio;
-        lv.valid = lv.skip ? lv.units - (lv.units + ratio - 1) / ratio : lv.units;
-        plan.push_back(lv);
-    }
+    uint32_t c0 = 0;
+    while (c0 <= l.top && (uint64_t)l.n_ge[c0] * kTileItems > cap) ++c0;
+    if (c0 > l.top) return plan;
+    plan.push_back(Level{0, l.n_ge[c0]});
+    for (uint32_t c = c0; c-- > 0;) plan.push_back(Level{l.n_ge[c + 1], l.n_ge[c]});
     return plan;
 }
 
@@ -277,13 +274,14 @@ uint64_t rbe_n_items(const rbe_index* ix) { return ix ? ix->n_items : 0; }
 uint32_t rbe_dim(const rbe_index* ix) { return ix ? ix->dim : 0; }
 uint32_t rbe_n_planes(const rbe_index* ix) { return ix ? ix->P : 0; }
 
-int rbe_index_create(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags)
+static int create_with_ratio(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags, uint32_t ratio)
 {
     ARG_CHECK(out != nullptr, "out is NULL");
     ARG_CHECK(dim == 64 || dim == 128 || dim == 256, "dim must be 64, 128 or 256 (got %u)", dim);
     ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES, "n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, n_planes);
     ARG_CHECK(n_items >= 1 && n_items <= RBE_MAX_ITEMS, "n_items must be 1..%llu", (unsigned long long)RBE_MAX_ITEMS);
     ARG_CHECK((flags & ~(uint32_t)RBE_COSINE) == 0, "unknown flags 0x%x", flags);
+    ARG_CHECK(ratio >= 2 && ratio <= 4096, "sample ratio must be 2..4096 (got %u)", ratio);
 
     rbe_index* ix = new (std::nothrow) rbe_index();
     if (!ix) { set_error("host allocation failed"); return RBE_ENOMEM; }
@@ -292,7 +290,8 @@ int rbe_index_create(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n
     ix->W = dim / 64;
     ix->P = n_planes;
     ix->flags = flags;
-    ix->stride = (size_t)((n_items + kTile - 1) / kTile) * kTile;
+    ix->geom = rbe::TileGeom{ix->W, ix->P};
+    ix->layout = rbe::make_layout((uint32_t)((n_items + kTileItems - 1) / kTileItems), ratio);
 
     int dev = 0;
     hipDeviceProp_t prop;
@@ -305,21 +304,40 @@ int rbe_index_create(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n
     }
     ix->n_cu = prop.multiProcessorCount;
 
-    const size_t plane_bytes = (size_t)ix->P * ix->stride * ix->W * sizeof(uint64_t);
-    const size_t scale_bytes = (size_t)ix->P * ix->stride * sizeof(float);
-    e = hipMalloc(&ix->d_planes, plane_bytes);
-    if (e == hipSuccess) e = hipMalloc(&ix->d_scales, scale_bytes);
-    if (e == hipSuccess) e = hipMemset(ix->d_planes, 0, plane_bytes);
-    if (e == hipSuccess) e = hipMemset(ix->d_scales, 0, scale_bytes);
+    const size_t bytes = (size_t)ix->layout.n_tiles * ix->geom.tile_bytes();
+    e = hipMalloc(&ix->d_tiles, bytes);
+    if (e == hipSuccess) e = hipMemset(ix->d_tiles, 0, bytes);
     if (e != hipSuccess) {
-        set_error("device allocation of %zu bytes failed: %s", plane_bytes + scale_bytes, hipGetErrorString(e));
-        (void)hipFree(ix->d_planes);
-        (void)hipFree(ix->d_scales);
+        set_error("device allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+        (void)hipFree(ix->d_tiles);
         delete ix;
         return e == hipErrorOutOfMemory ? RBE_ENOMEM : RBE_EHIP;
     }
     *out = ix;
     return RBE_OK;
+}
+
+int rbe_index_create(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags)
+{
+    return create_with_ratio(out, n_items, dim, n_planes, flags, 64);
+}
+
+int rbe_index_create_ex(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags,
+                        uint32_t sample_ratio)
+{
+    return create_with_ratio(out, n_items, dim, n_planes, flags, sample_ratio ? sample_ratio : 64);
+}
+
+uint32_t rbe_debug_tile_to_phys(uint32_t n_tiles, uint32_t sample_ratio, uint32_t tile)
+{
+    const rbe::Layout l = rbe::make_layout(n_tiles, sample_ratio);
+    return rbe::tile_to_phys(l, tile);
+}
+
+uint32_t rbe_debug_phys_to_tile(uint32_t n_tiles, uint32_t sample_ratio, uint32_t phys)
+{
+    const rbe::Layout l = rbe::make_layout(n_tiles, sample_ratio);
+    return rbe::phys_to_tile(l, phys);
 }
 
 int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uint64_t* planes,
@@ -334,14 +352,34 @@ int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uin
               (unsigned long long)count, (unsigned long long)ix->n_items);
     if (count == 0) return RBE_OK;
     hipStream_t st = (hipStream_t)hip_stream;
-    const hipMemcpyKind kind = mem_kind == RBE_MEM_HOST ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice;
-    for (uint32_t j = 0; j < ix->P; ++j) {
-        HIP_TRY(hipMemcpyAsync(ix->d_planes + ((size_t)j * ix->stride + first_item) * ix->W,
-                               planes + (size_t)j * count * ix->W, (size_t)count * ix->W * sizeof(uint64_t), kind, st));
-        HIP_TRY(hipMemcpyAsync(ix->d_scales + (size_t)j * ix->stride + first_item,
-                               scales + (size_t)j * count, (size_t)count * sizeof(float), kind, st));
+    const uint64_t* src_planes = planes;
+    const float* src_scales = scales;
+    uint64_t* tmp_planes = nullptr;
+    float* tmp_scales = nullptr;
+    const size_t pbytes = (size_t)ix->P * count * ix->W * sizeof(uint64_t);
+    const size_t sbytes = (size_t)ix->P * count * sizeof(float);
+    if (mem_kind == RBE_MEM_HOST) {  // stage the chunk on the device, then scatter it into tiles
+        hipError_t e = hipMalloc(&tmp_planes, pbytes);
+        if (e == hipSuccess) e = hipMalloc(&tmp_scales, sbytes);
+        if (e == hipSuccess) e = hipMemcpyAsync(tmp_planes, planes, pbytes, hipMemcpyHostToDevice, st);
+        if (e == hipSuccess) e = hipMemcpyAsync(tmp_scales, scales, sbytes, hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) {
+            set_error("staging a chunk of %zu bytes failed: %s", pbytes + sbytes, hipGetErrorString(e));
+            (void)hipFree(tmp_planes);
+            (void)hipFree(tmp_scales);
+            return e == hipErrorOutOfMemory ? RBE_ENOMEM : RBE_EHIP;
+        }
+        src_planes = tmp_planes;
+        src_scales = tmp_scales;
     }
-    if (mem_kind == RBE_MEM_HOST) HIP_TRY(hipStreamSynchronize(st));
+    hipLaunchKernelGGL(rbe::scatter_chunk, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st, ix->d_tiles,
+                       ix->layout, ix->geom, src_planes, src_scales, first_item, count);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && mem_kind == RBE_MEM_HOST) e = hipStreamSynchronize(st);
+    (void)hipFree(tmp_planes);
+    (void)hipFree(tmp_scales);
+    if (e != hipSuccess) { set_error("rbe_load_chunk: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    ix->loaded_any = true;
     return RBE_OK;
 }
 
@@ -351,9 +389,9 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
     if (ix->ready) { set_error("rbe_finalize called twice"); return RBE_ESTATE; }
     hipStream_t st = (hipStream_t)hip_stream;
     if (ix->flags & RBE_COSINE) {
-        const uint32_t grid = (uint32_t)((ix->n_items + 255) / 256);
-        hipLaunchKernelGGL(rbe::fold_cosine, dim3(grid), dim3(256), 0, st, ix->d_planes, ix->d_scales,
-                           ix->stride, ix->W, ix->P, ix->n_items);
+        const uint64_t n_slots = (uint64_t)ix->layout.n_tiles * kTileItems;
+        hipLaunchKernelGGL(rbe::fold_cosine, dim3((uint32_t)((n_slots + 255) / 256)), dim3(256), 0, st,
+                           ix->d_tiles, ix->geom, n_slots);
         HIP_TRY(hipGetLastError());
     }
     HIP_TRY(hipStreamSynchronize(st));
@@ -379,8 +417,7 @@ void rbe_free(rbe_index* ix)
 {
     if (!ix) return;
     free_workspace(ix);
-    (void)hipFree(ix->d_planes);
-    (void)hipFree(ix->d_scales);
+    (void)hipFree(ix->d_tiles);
     (void)hipFree(ix->d_count);
     (void)hipFree(ix->d_tau);
     (void)hipFree(ix->d_status);
@@ -436,14 +473,12 @@ int rbe_get_search_stats(const rbe_index* ix, rbe_search_stats* out)
     return RBE_OK;
 }
 
-int rbe_set_tuning(rbe_index* ix, uint32_t sample_ratio, uint32_t cand_capacity, uint32_t blocks_per_cu)
+int rbe_set_tuning(rbe_index* ix, uint32_t cand_capacity, uint32_t blocks_per_cu)
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
-    ARG_CHECK(sample_ratio == 0 || (sample_ratio >= 8 && sample_ratio <= 4096), "sample_ratio must be 8..4096");
-    ARG_CHECK(cand_capacity == 0 || (cand_capacity >= 2 * (uint32_t)rbe::kTile && cand_capacity <= (1u << 24)),
-              "cand_capacity must be %d..2^24", 2 * rbe::kTile);
+    ARG_CHECK(cand_capacity == 0 || (cand_capacity >= 2u * kTileItems && cand_capacity <= (1u << 24)),
+              "cand_capacity must be %d..2^24", 2 * kTileItems);
     ARG_CHECK(blocks_per_cu <= 16, "blocks_per_cu must be <= 16");
-    if (sample_ratio) ix->ratio = sample_ratio;
     if (cand_capacity) ix->cap_override = cand_capacity;
     if (blocks_per_cu) ix->blocks_per_cu = blocks_per_cu;
     return RBE_OK;
@@ -451,16 +486,15 @@ int rbe_set_tuning(rbe_index* ix, uint32_t sample_ratio, uint32_t cand_capacity,
 
 // Enqueue one scan + select round.  `final_pass` makes the select write the results.
 static int run_round(rbe_index* ix, hipStream_t st, uint32_t Q, uint32_t PQ, uint32_t k, uint32_t cap,
-                     uint32_t v_begin, uint32_t v_end, uint32_t stride, uint32_t skip,
-                     int final_pass, uint32_t level_slot, bool record)
+                     uint32_t p_begin, uint32_t p_end, int final_pass, uint32_t level_slot, bool record)
 {
     ScanArgs sa;
-    sa.planes = ix->d_planes; sa.scales = ix->d_scales; sa.plane_stride = ix->stride; sa.n_items = ix->n_items;
+    sa.tiles = ix->d_tiles; sa.layout = ix->layout; sa.n_items = ix->n_items;
     sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = Q;
     sa.tau = ix->d_tau; sa.cand = ix->d_cand; sa.count = ix->d_count; sa.cap = cap;
-    sa.v_begin = v_begin; sa.v_end = v_end; sa.stride = stride; sa.skip = skip;
-    const uint32_t n_valid = v_end - v_begin;
-    if (n_valid > 0) {
+    sa.p_begin = p_begin; sa.p_end = p_end;
+    const uint32_t n_tiles = p_end - p_begin;
+    if (n_tiles > 0) {
         const ScanFn fn = scan_fn(ix->W, ix->P, PQ, Q == 1);
         uint32_t per_cu = ix->blocks_per_cu;
         if (per_cu == 0) {  // as many workgroups as are resident at once: one wave of persistent groups
@@ -468,7 +502,7 @@ static int run_round(rbe_index* ix, hipStream_t st, uint32_t Q, uint32_t PQ, uin
             HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0));
             per_cu = (uint32_t)std::max(nb, 1);
         }
-        const uint32_t grid = std::min<uint32_t>(n_valid, (uint32_t)ix->n_cu * per_cu);
+        const uint32_t grid = std::min<uint32_t>(n_tiles, (uint32_t)ix->n_cu * per_cu);
         ix->stats.grid_blocks = std::max(ix->stats.grid_blocks, grid);
         fn<<<dim3(grid), dim3(kBlock), 0, st>>>(sa);
         HIP_TRY(hipGetLastError());
@@ -502,17 +536,17 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
 
     hipStream_t st = (hipStream_t)hip_stream;
     const uint32_t Q = n_queries, PQ = q_n_planes;
-    uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->ratio * k);
-    cap = std::max<uint32_t>(cap, k + 2 * kTile);
+    uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->layout.ratio * k);
+    cap = std::max<uint32_t>(cap, k + 2 * kTileItems);
     int rc = ensure_workspace(ix, Q, k, cap);
     if (rc) return rc;
 
     rc = stage_queries(ix, q_planes, q_scales, Q, PQ, st);
     if (rc) return rc;
 
-    const uint64_t n_tiles = ix->stride / kTile;
-    const std::vector<Level> plan = make_plan(n_tiles, ix->ratio, cap);
-    const bool plan_dense_ok = (uint64_t)plan.front().units * kTile <= cap;
+    const uint32_t n_tiles = ix->layout.n_tiles;
+    const std::vector<Level> plan = make_plan(ix->layout, cap);
+    const bool plan_dense_ok = !plan.empty();
 
     ix->stats = rbe_search_stats{};
     const bool prof = ix->profiling != 0;
@@ -525,24 +559,23 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
             if (prof) HIP_TRY(hipEventRecord(ix->ev[0], st));
             for (size_t l = 0; l < plan.size(); ++l) {
                 const Level& lv = plan[l];
-                rc = run_round(ix, st, Q, PQ, k, cap, 0, lv.valid, lv.stride, lv.skip,
-                               l + 1 == plan.size(), (uint32_t)l, prof);
+                rc = run_round(ix, st, Q, PQ, k, cap, lv.p_begin, lv.p_end, l + 1 == plan.size(), (uint32_t)l, prof);
                 if (rc) return rc;
-                ix->stats.items_scanned[l] = (uint64_t)lv.valid * kTile;
+                ix->stats.items_scanned[l] = (uint64_t)(lv.p_end - lv.p_begin) * kTileItems;
             }
             ix->stats.n_levels = (uint32_t)plan.size();
         } else {
             // Slow path that cannot overflow: segments of at most cap - k items, each followed
             // by a selection that compacts the list back to k entries.
-            const uint32_t seg = std::max<uint32_t>(1u, (cap - k) / kTile);
+            const uint32_t seg = std::max<uint32_t>(1u, (cap - k) / kTileItems);
             for (uint64_t u0 = 0; u0 < n_tiles; u0 += seg) {
                 const uint32_t u1 = (uint32_t)std::min<uint64_t>(n_tiles, u0 + seg);
-                rc = run_round(ix, st, Q, PQ, k, cap, (uint32_t)u0, u1, 1, 0, u1 == n_tiles, 0, false);
+                rc = run_round(ix, st, Q, PQ, k, cap, (uint32_t)u0, u1, u1 == n_tiles, 0, false);
                 if (rc) return rc;
             }
             ix->stats.n_levels = 1;
             ix->stats.fallback = 1;
-            ix->stats.items_scanned[0] = ix->stride;
+            ix->stats.items_scanned[0] = (uint64_t)n_tiles * kTileItems;
         }
         HIP_TRY(hipMemcpyAsync(ix->h_status, ix->d_status, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
         HIP_TRY(hipMemcpyAsync(ix->h_seen, ix->d_seen, RBE_MAX_LEVELS * RBE_MAX_QUERIES * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
@@ -590,7 +623,7 @@ int rbe_debug_popcounts(rbe_index* ix, const uint64_t* q_planes, uint32_t q_n_pl
     if (e == hipSuccess) e = hipMemcpyAsync(d_q, q_planes, qbytes, hipMemcpyHostToDevice, st);
     if (e == hipSuccess) {
         hipLaunchKernelGGL(rbe::dense_popcounts, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st,
-                           ix->d_planes, ix->stride, ix->W, ix->P, d_q, q_n_planes, first_item, count, d_out);
+                           ix->d_tiles, ix->layout, ix->geom, d_q, q_n_planes, first_item, count, d_out);
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, obytes, hipMemcpyDeviceToHost, st);
@@ -629,11 +662,37 @@ int rbe_debug_read_scales(rbe_index* ix, uint64_t first_item, uint64_t count, fl
 {
     ARG_CHECK(ix && out, "NULL argument");
     ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item, "item range outside the index");
+    ARG_CHECK(count <= (1ull << 28), "count too large for a debug dump");
+    if (count == 0) return RBE_OK;
     hipStream_t st = (hipStream_t)hip_stream;
-    for (uint32_t j = 0; j < ix->P; ++j)
-        HIP_TRY(hipMemcpyAsync(out + (size_t)j * count, ix->d_scales + (size_t)j * ix->stride + first_item,
-                               (size_t)count * sizeof(float), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));
+    float* d_out = nullptr;
+    const size_t bytes = (size_t)ix->P * count * sizeof(float);
+    HIP_TRY(hipMalloc(&d_out, bytes));
+    hipLaunchKernelGGL(rbe::gather_scales, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st, ix->d_tiles,
+                       ix->layout, ix->geom, first_item, count, d_out);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, bytes, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(d_out);
+    if (e != hipSuccess) { set_error("rbe_debug_read_scales: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    return RBE_OK;
+}
+
+int rbe_debug_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream)
+{
+    ARG_CHECK(dst_dev && src_dev, "NULL argument");
+    ARG_CHECK(bytes % 16 == 0 && ((uintptr_t)dst_dev % 16) == 0 && ((uintptr_t)src_dev % 16) == 0,
+              "size and pointers must be multiples of 16 bytes");
+    if (bytes == 0) return RBE_OK;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    const size_t n_vec = bytes / 16;
+    const uint32_t grid = (uint32_t)std::min<size_t>((n_vec + 255) / 256, (size_t)prop.multiProcessorCount * 8);
+    hipLaunchKernelGGL(rbe::calib_copy, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const rbe::u32x4*)src_dev, (rbe::u32x4*)dst_dev, n_vec);
+    HIP_TRY(hipGetLastError());
     return RBE_OK;
 }
 

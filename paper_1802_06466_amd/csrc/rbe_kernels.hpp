@@ -2,29 +2,36 @@
 //
 // Kernels:
 //   scan_exact<W,P,PQ,SINGLE>  streaming exhaustive match (Eq. 14 by XOR/popcount,
-//                              Sec. 5.1) fused with threshold pruning: an item whose
+//                              Sec. 5.1) fused with local selection: an item whose
 //                              (score, id) key reaches the query's proven lower bound
-//                              is appended to the query's candidate list.
+//                              is staged in the wave's LDS queue and later appended
+//                              to the query's global candidate list.
 //   select_topk                per query: k-th largest candidate key by radix
 //                              descent, compaction of the k best to the front of the
-//                              list, bitonic sort, new threshold (the per-GPU global
-//                              selection of Sec. 5 / Sec. 6).
-//   dense_popcounts / dense_scores / fold_cosine / init_state   small helpers.
+//                              list, new threshold, sorted output on the last round
+//                              (the per-GPU global selection of Sec. 5 / Sec. 6).
+//   scatter_chunk              load path: caller's [P][n][W] / [P][n] arrays -> tiles.
+//   dense_popcounts / dense_scores / gather_scales / fold_cosine / init_state /
+//   calib_copy                 small helpers.
 //
 // Wavefronts are 64 wide.  One wave reads a "row" of 256 consecutive items per
 // step: every plane with 16-byte loads per lane (1 KiB contiguous per wave
-// instruction), every scale array with the matching 8- or 4-byte loads.
+// instruction), every scale array with the matching 8- or 4-byte loads.  The
+// four waves of a workgroup read the four rows of one 1024-item tile, which is
+// one contiguous block of memory (rbe_layout.hpp).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "rbe_layout.hpp"
 
 namespace rbe {
 
 constexpr int kBlock = 256;             // threads per workgroup of the scan
 constexpr int kWavesPerBlock = kBlock / 64;
 constexpr int kRow = 256;               // items one wave handles per step
-constexpr int kTile = kRow * kWavesPerBlock;  // items one workgroup handles per step
 constexpr int kItemsPerLane = 4;
+static_assert(kRow * kWavesPerBlock == kTileItems, "a workgroup step covers one tile");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -95,19 +102,19 @@ __device__ __forceinline__ uint32_t lane_item(int lane, int m)
     return (uint32_t)(m * 64 + lane);
 }
 
+// Loads the wave's row (`wave` = 0..3) of the tile that starts at `tile`.
 template <int W, int P>
-__device__ __forceinline__ void load_row(RowRegs<W, P>& r, const uint64_t* __restrict__ planes,
-                                         const float* __restrict__ scales, size_t plane_stride,
-                                         size_t row_base, int lane)
+__device__ __forceinline__ void load_row(RowRegs<W, P>& r, const char* __restrict__ tile, int wave, int lane)
 {
+    const TileGeom g{(uint32_t)W, (uint32_t)P};
 #pragma unroll
     for (int j = 0; j < P; ++j) {
-        const uint64_t* pj = planes + (size_t)j * plane_stride * W;
-        const float* sj = scales + (size_t)j * plane_stride;
+        const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)wave * kRow * W;
+        const float* sj = reinterpret_cast<const float*>(tile + g.scales_offset()) + j * kTileItems + wave * kRow;
         if (W == 1) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const size_t it = row_base + s * 128 + 2 * lane;
+                const int it = s * 128 + 2 * lane;
                 const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + it));
                 r.w[j][2 * s][0] = v.x; r.w[j][2 * s][1] = v.y;
                 r.w[j][2 * s + 1][0] = v.z; r.w[j][2 * s + 1][1] = v.w;
@@ -117,10 +124,10 @@ __device__ __forceinline__ void load_row(RowRegs<W, P>& r, const uint64_t* __res
         } else {
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
-                const size_t it = row_base + m * 64 + lane;
+                const int it = m * 64 + lane;
 #pragma unroll
                 for (int h = 0; h < W / 2; ++h) {
-                    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + it * W) + h);
+                    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + (size_t)it * W) + h);
                     r.w[j][m][4 * h + 0] = v.x; r.w[j][m][4 * h + 1] = v.y;
                     r.w[j][m][4 * h + 2] = v.z; r.w[j][m][4 * h + 3] = v.w;
                 }
@@ -151,36 +158,15 @@ __device__ __forceinline__ float score_item(const RowRegs<W, P>& r, int m, const
     return s;
 }
 
-// Wave-cooperative append of the lanes with ok == true: one atomic per wave.
-// Must be reached by all lanes of the wave.
-__device__ __forceinline__ void append_keys(bool ok, uint64_t key, uint64_t* __restrict__ cand_q,
-                                            uint32_t* __restrict__ count_q, uint32_t cap, int lane)
-{
-    const uint64_t mask = __ballot(ok);
-    if (mask == 0) return;
-    const int leader = __ffsll((long long)mask) - 1;
-    uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(count_q, (uint32_t)__popcll(mask));
-    base = __shfl(base, leader);
-    if (ok) {
-        const uint32_t pos = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        if (pos < cap) cand_q[pos] = key;  // the count keeps running so that overflow is seen
-    }
-}
-
-// Map the v-th unit that is NOT a multiple of `skip` to its unit number
-// (skip == 0: identity).  Units that are multiples of `skip` were scanned by
-// the previous, coarser level.
-__device__ __forceinline__ uint32_t unit_of(uint32_t v, uint32_t skip)
-{
-    if (skip == 0) return v;
-    return (v / (skip - 1)) * skip + (v % (skip - 1)) + 1;
-}
+// ---------------------------------------------------------------- per-wave candidate staging
+// Survivors are first written to a queue in LDS that belongs to one wave (no
+// atomics, no workgroup barrier), and moved to the query's global candidate list
+// in bulk: one global atomic per flushed group instead of one per survivor.
+constexpr int kStage = 512;  // entries per wave; an append adds at most 64
 
 struct ScanArgs {
-    const uint64_t* planes;   // [P][plane_stride][W]
-    const float* scales;      // [P][plane_stride]
-    size_t plane_stride;      // items per plane array (multiple of kTile)
+    const char* tiles;        // physical tile 0
+    Layout layout;
     uint64_t n_items;
     const uint32_t* qwords;   // [Q][PQ][2W]
     const float* qcoef;       // [Q][PQ+1]
@@ -189,22 +175,86 @@ struct ScanArgs {
     uint64_t* cand;           // [Q][cap]
     uint32_t* count;          // [Q]
     uint32_t cap;
-    uint32_t v_begin, v_end;  // range of valid-unit indices this launch covers
-    uint32_t stride;          // tile = unit * stride
-    uint32_t skip;            // see unit_of
+    uint32_t p_begin, p_end;  // physical tile range this launch covers
 };
 
-// Streaming exhaustive match + threshold pruning.  Persistent workgroups:
-// workgroup b takes valid units b, b + grid, ...; the next tile's loads are
-// issued before the current tile is scored.
+template <bool SINGLE>
+__device__ __forceinline__ void stage_flush(uint64_t* s_keys, uint8_t* s_q, uint32_t fill, const ScanArgs& a, int lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (SINGLE) {
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(a.count, fill);
+        base = __shfl(base, 0);
+        for (uint32_t i = lane; i < fill; i += 64) {
+            const uint32_t pos = base + i;
+            if (pos < a.cap) a.cand[pos] = s_keys[i];  // the count keeps running so that overflow is seen
+        }
+    } else {
+        for (uint32_t i0 = 0; i0 < fill; i0 += 64) {
+            const uint32_t i = i0 + lane;
+            const bool valid = i < fill;
+            const uint64_t key = valid ? s_keys[i] : 0;
+            const uint32_t myq = valid ? s_q[i] : 0xFFFFFFFFu;
+            uint64_t todo = __ballot(valid);
+            while (todo) {  // one round per distinct query present in this group of 64
+                const int lead = __ffsll((long long)todo) - 1;
+                const uint32_t q0 = __shfl(myq, lead);
+                const uint64_t sel = __ballot(valid && myq == q0);
+                uint32_t base = 0;
+                if (lane == lead) base = atomicAdd(a.count + q0, (uint32_t)__popcll(sel));
+                base = __shfl(base, lead);
+                if (valid && myq == q0) {
+                    const uint32_t pos = base + (uint32_t)__popcll(sel & ((1ull << lane) - 1ull));
+                    if (pos < a.cap) a.cand[(size_t)q0 * a.cap + pos] = key;
+                }
+                todo &= ~sel;
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Must be reached by all lanes of the wave.  Returns the new fill level.
+template <bool SINGLE>
+__device__ __forceinline__ uint32_t stage_append(bool ok, uint64_t key, uint32_t q, uint64_t* s_keys, uint8_t* s_q,
+                                                 uint32_t fill, const ScanArgs& a, int lane)
+{
+    const uint64_t mask = __ballot(ok);
+    if (mask == 0) return fill;
+    const uint32_t n = (uint32_t)__popcll(mask);
+    if (fill + n > (uint32_t)kStage) {
+        stage_flush<SINGLE>(s_keys, s_q, fill, a, lane);
+        fill = 0;
+    }
+    if (ok) {
+        const uint32_t pos = fill + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        s_keys[pos] = key;
+        if (!SINGLE) s_q[pos] = (uint8_t)q;
+    }
+    return fill + n;
+}
+
+// Streaming exhaustive match + local selection over physical tiles
+// [p_begin, p_end).  Persistent workgroups: workgroup b takes tiles p_begin + b,
+// + grid, ...; the next tile's loads are issued before the current one is scored.
 template <int W, int P, int PQ, bool SINGLE>
 __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
 {
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ uint8_t s_q_all[SINGLE ? 1 : kWavesPerBlock][SINGLE ? 1 : kStage];
+
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    uint8_t* s_q = SINGLE ? s_q_all[0] : s_q_all[wave];
     const uint32_t G = gridDim.x;
-    uint32_t v = a.v_begin + blockIdx.x;
-    if (v >= a.v_end) return;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P};
+    const size_t tile_bytes = geom.tile_bytes();
+
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
 
     QueryRegs<W, PQ> q0;
     uint64_t tau0 = 0;
@@ -215,18 +265,14 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
         taus0 = threshold_score(tau0);
     }
 
+    uint32_t fill = 0;
     RowRegs<W, P> cur, nxt;
-    size_t row = ((size_t)unit_of(v, a.skip) * a.stride) * kTile + (size_t)wave * kRow;
-    load_row<W, P>(cur, a.planes, a.scales, a.plane_stride, row, lane);
+    load_row<W, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
 
     for (;;) {
-        const uint32_t vn = v + G;
-        const bool has_next = vn < a.v_end;
-        size_t row_n = 0;
-        if (has_next) {
-            row_n = ((size_t)unit_of(vn, a.skip) * a.stride) * kTile + (size_t)wave * kRow;
-            load_row<W, P>(nxt, a.planes, a.scales, a.plane_stride, row_n, lane);
-        }
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        if (has_next) load_row<W, P>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
 
         const uint32_t nq = SINGLE ? 1u : a.n_queries;
         for (uint32_t q = 0; q < nq; ++q) {
@@ -247,156 +293,245 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
                 any |= (s[m] >= taus);
             }
             if (__ballot(any)) {   // rare: at least one lane of the wave has a survivor
+                const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
 #pragma unroll
                 for (int m = 0; m < kItemsPerLane; ++m) {
-                    const uint64_t id = row + lane_item<W>(lane, m);
+                    const uint64_t id = row_id + lane_item<W>(lane, m);
                     bool ok = (s[m] >= taus) && (id < a.n_items);
                     uint64_t key = 0;
                     if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
-                    append_keys(ok, key, a.cand + (size_t)q * a.cap, a.count + q, a.cap, lane);
+                    fill = stage_append<SINGLE>(ok, key, q, s_keys, s_q, fill, a, lane);
                 }
             }
         }
 
         if (!has_next) break;
         cur = nxt;
-        row = row_n;
-        v = vn;
+        p = pn;
     }
+    if (fill) stage_flush<SINGLE>(s_keys, s_q, fill, a, lane);
 }
 
 // ---------------------------------------------------------------- selection
 constexpr int kSelBlock = 1024;
 constexpr int kSelMaxK = 4096;
+constexpr int kSelBins = 2048;      // 11-bit digits
+constexpr int kSelBound = 1024;     // boundary keys finished by an LDS sort
+constexpr int kSelUnroll = 8;
 
 enum : uint32_t { kStatusOverflow = 1u };
 
 struct SelectArgs {
-    uint64_t* cand;      // [Q][cap], in/out: on return the best min(n,k) keys, sorted, at the front
+    uint64_t* cand;      // [Q][cap], in/out: on return the best min(n,k) keys at the front
     uint32_t* count;     // [Q] in: appended so far; out: number kept
-    uint64_t* tau;       // [Q] out: k-th best key if at least k candidates, else unchanged... see kernel
+    uint64_t* tau;       // [Q] out: k-th best key once at least k candidates exist
     uint32_t cap;
     uint32_t k;
     uint32_t* status;    // bit 0 set if any query's count exceeded cap
     uint32_t* count_seen;  // [Q] out: candidate count before selection (for statistics)
     int final_pass;
-    int64_t* ids_out;    // [Q][k]   (final pass)
+    int64_t* ids_out;    // [Q][k]   (final pass; sorted)
     float* scores_out;   // [Q][k]
 };
+
+// Inclusive prefix sum over the 1024 threads of the select workgroup.
+__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* s_wave /*[16]*/)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t add = 0;
+    for (int w = 0; w < wave; ++w) add += s_wave[w];
+    __syncthreads();
+    return incl + add;
+}
+
+// Bitonic sort of `pow2` keys in LDS, descending.  All threads of the workgroup call it.
+__device__ __forceinline__ void bitonic_desc(uint64_t* keys, uint32_t pow2)
+{
+    for (uint32_t size = 2; size <= pow2; size <<= 1) {
+        for (uint32_t st = size >> 1; st > 0; st >>= 1) {
+            for (uint32_t i = threadIdx.x; i < pow2 / 2; i += kSelBlock) {
+                const uint32_t lo = 2 * i - (i & (st - 1));
+                const uint32_t hi = lo + st;
+                const bool desc = ((lo & size) == 0);
+                const uint64_t x = keys[lo], y = keys[hi];
+                if ((x < y) == desc) { keys[lo] = y; keys[hi] = x; }
+            }
+            __syncthreads();
+        }
+    }
+}
 
 // One workgroup per query.
 __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
 {
-    __shared__ uint64_t skeys[kSelMaxK];
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t s_digit, s_remaining, s_fill;
+    __shared__ uint64_t skeys[kSelMaxK];    // keys known to be kept
+    __shared__ uint64_t sbound[kSelBound];  // keys of the boundary bin
+    __shared__ uint32_t hist[kSelBins];
+    __shared__ uint32_t s_wave[16];
+    __shared__ uint64_t s_and, s_or;
+    __shared__ uint32_t s_digit, s_remaining, s_binpop, s_fill_keep, s_fill_bound;
 
     const uint32_t q = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     uint64_t* keys = a.cand + (size_t)q * a.cap;
     const uint32_t appended = a.count[q];
     const uint32_t n = appended < a.cap ? appended : a.cap;
+    const uint32_t k = a.k;
     if (tid == 0) {
         a.count_seen[q] = appended;
         if (appended > a.cap) atomicOr(a.status, kStatusOverflow);
     }
-    const uint32_t k = a.k;
 
-    uint64_t kth = 0;  // keys >= kth are kept
-    if (n > k) {
-        uint64_t prefix = 0, mask = 0;
-        uint32_t remaining = k;
-        for (int shift = 56; shift >= 0; shift -= 8) {
-            if (tid < 256) hist[tid] = 0;
+    uint32_t m;  // number of keys kept
+    if (n <= k) {
+        // everything is kept; nothing to prune.  Only the final round needs them sorted.
+        m = n;
+        if (!a.final_pass) return;
+        for (uint32_t i = tid; i < n; i += kSelBlock) skeys[i] = keys[i];
+    } else {
+        m = k;
+        // ---- bits that differ between any two keys
+        uint64_t vand = ~0ull, vor = 0;
+        for (uint32_t base = 0; base < n; base += kSelBlock * kSelUnroll) {
+            uint64_t kk[kSelUnroll];
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const uint32_t i = base + u * kSelBlock + tid;
+                kk[u] = i < n ? keys[i] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const uint32_t i = base + u * kSelBlock + tid;
+                if (i < n) { vand &= kk[u]; vor |= kk[u]; }
+            }
+        }
+        if (tid == 0) { s_and = ~0ull; s_or = 0; }
+        __syncthreads();
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) {
+            vand &= __shfl_xor(vand, d);
+            vor |= __shfl_xor(vor, d);
+        }
+        if ((tid & 63) == 0) { atomicAnd((unsigned long long*)&s_and, (unsigned long long)vand); atomicOr((unsigned long long*)&s_or, (unsigned long long)vor); }
+        __syncthreads();
+        const uint64_t diff = s_and ^ s_or;       // non-zero: the n > k >= 1 keys are distinct
+        int pos = 64 - __clzll((long long)diff);   // low `pos` bits are undetermined
+        uint64_t mask = pos >= 64 ? 0ull : ~((1ull << pos) - 1ull);
+        uint64_t prefix = s_or & mask;
+        uint32_t remaining = k;                    // rank of the wanted key among keys matching the prefix
+
+        // ---- radix descent, 11 bits per round, until the boundary bin fits an LDS sort
+        for (;;) {
+            const int bits = pos < 11 ? pos : 11;
+            const int shift = pos - bits;
+            const uint32_t dmask = (1u << bits) - 1u;
+            for (uint32_t i = tid; i < kSelBins; i += kSelBlock) hist[i] = 0;
             __syncthreads();
-            for (uint32_t i = tid; i < n; i += kSelBlock) {
-                const uint64_t key = keys[i];
-                if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+            for (uint32_t base = 0; base < n; base += kSelBlock * kSelUnroll) {
+                uint64_t kk[kSelUnroll];
+#pragma unroll
+                for (int u = 0; u < kSelUnroll; ++u) {
+                    const uint32_t i = base + u * kSelBlock + tid;
+                    kk[u] = i < n ? keys[i] : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < kSelUnroll; ++u) {
+                    const uint32_t i = base + u * kSelBlock + tid;
+                    if (i < n && (kk[u] & mask) == prefix) atomicAdd(&hist[(uint32_t)(kk[u] >> shift) & dmask], 1u);
+                }
             }
             __syncthreads();
-            if (tid < 64) {
-                // lane l owns digits 255-4l .. 252-4l (descending); find where the running
-                // count from the top reaches `remaining`
-                const int top = 255 - 4 * (int)tid;
-                const uint32_t c0 = hist[top], c1 = hist[top - 1], c2 = hist[top - 2], c3 = hist[top - 3];
-                const uint32_t mine = c0 + c1 + c2 + c3;
-                uint32_t incl = mine;
-#pragma unroll
-                for (int d = 1; d < 64; d <<= 1) {
-                    const uint32_t o = __shfl_up(incl, d);
-                    if ((int)tid >= d) incl += o;
-                }
-                const uint32_t before = incl - mine;   // keys with larger digits than this lane's
-                if (before < remaining && incl >= remaining) {
-                    uint32_t acc = before;
-                    int dsel = top;
-                    if (acc + c0 >= remaining) dsel = top;
-                    else { acc += c0;
-                        if (acc + c1 >= remaining) dsel = top - 1;
-                        else { acc += c1;
-                            if (acc + c2 >= remaining) dsel = top - 2;
-                            else { acc += c2; dsel = top - 3; } } }
-                    s_digit = (uint32_t)dsel;
-                    s_remaining = remaining - acc;
-                }
+            // thread t owns digits 2047-2t and 2046-2t (descending order)
+            const uint32_t d1 = kSelBins - 1 - 2 * tid, d0 = d1 - 1;
+            const uint32_t c1 = hist[d1], c0 = hist[d0];
+            const uint32_t incl = block_scan_incl(c1 + c0, s_wave);
+            const uint32_t before = incl - (c1 + c0);
+            if (before < remaining && incl >= remaining) {
+                if (before + c1 >= remaining) { s_digit = d1; s_remaining = remaining - before; s_binpop = c1; }
+                else { s_digit = d0; s_remaining = remaining - before - c1; s_binpop = c0; }
             }
             __syncthreads();
             prefix |= (uint64_t)s_digit << shift;
-            mask |= (uint64_t)0xFFu << shift;
+            mask |= (uint64_t)dmask << shift;
             remaining = s_remaining;
+            pos = shift;
+            const uint32_t binpop = s_binpop;
             __syncthreads();
+            if (binpop <= (uint32_t)kSelBound || pos == 0) break;
         }
-        kth = prefix;
+
+        // ---- gather: keys above the boundary bin are kept; the bin itself is sorted in LDS
+        if (tid == 0) { s_fill_keep = 0; s_fill_bound = 0; }
+        __syncthreads();
+        for (uint32_t base = 0; base < n; base += kSelBlock * kSelUnroll) {
+            uint64_t kk[kSelUnroll];
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const uint32_t i = base + u * kSelBlock + tid;
+                kk[u] = i < n ? keys[i] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const uint32_t i = base + u * kSelBlock + tid;
+                if (i < n) {
+                    const uint64_t hi = kk[u] & mask;
+                    if (hi > prefix) {
+                        const uint32_t o = atomicAdd(&s_fill_keep, 1u);
+                        if (o < (uint32_t)kSelMaxK) skeys[o] = kk[u];
+                    } else if (hi == prefix) {
+                        const uint32_t o = atomicAdd(&s_fill_bound, 1u);
+                        if (o < (uint32_t)kSelBound) sbound[o] = kk[u];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t n_keep = k - remaining;      // == s_fill_keep
+        const uint32_t n_bound = s_fill_bound < (uint32_t)kSelBound ? s_fill_bound : (uint32_t)kSelBound;
+        uint32_t bp2 = 1;
+        while (bp2 < n_bound) bp2 <<= 1;
+        for (uint32_t i = n_bound + tid; i < bp2; i += kSelBlock) sbound[i] = 0;
+        __syncthreads();
+        bitonic_desc(sbound, bp2);
+        const uint32_t take = remaining < n_bound ? remaining : n_bound;   // == remaining (keys are distinct)
+        for (uint32_t i = tid; i < take; i += kSelBlock) skeys[n_keep + i] = sbound[i];
+        __syncthreads();
+        if (tid == 0 && take > 0) a.tau[q] = sbound[take - 1];   // k-th best of everything seen so far
+    }
+    __syncthreads();
+
+    if (!a.final_pass) {
+        for (uint32_t i = tid; i < m; i += kSelBlock) keys[i] = skeys[i];
+        if (tid == 0) a.count[q] = m;
+        return;
     }
 
-    // gather the kept keys into LDS (keys are distinct, so exactly min(n,k) qualify)
-    const uint32_t m = n < k ? n : k;
+    // ---- final round: sort the kept keys and emit ids and scores
     uint32_t pow2 = 1;
     while (pow2 < m) pow2 <<= 1;
-    if (tid == 0) s_fill = 0;
-    __syncthreads();
-    for (uint32_t i = tid; i < n; i += kSelBlock) {
-        const uint64_t key = keys[i];
-        if (key >= kth) {
-            const uint32_t pos = atomicAdd(&s_fill, 1u);
-            if (pos < (uint32_t)kSelMaxK) skeys[pos] = key;
-        }
-    }
-    __syncthreads();
     for (uint32_t i = m + tid; i < pow2; i += kSelBlock) skeys[i] = 0;
     __syncthreads();
-
-    // bitonic sort, descending
-    for (uint32_t size = 2; size <= pow2; size <<= 1) {
-        for (uint32_t st = size >> 1; st > 0; st >>= 1) {
-            for (uint32_t i = tid; i < pow2 / 2; i += kSelBlock) {
-                const uint32_t lo = 2 * i - (i & (st - 1));
-                const uint32_t hi = lo + st;
-                const bool desc = ((lo & size) == 0);
-                const uint64_t x = skeys[lo], y = skeys[hi];
-                if ((x < y) == desc) { skeys[lo] = y; skeys[hi] = x; }
-            }
-            __syncthreads();
+    bitonic_desc(skeys, pow2);
+    if (tid == 0) a.count[q] = m;
+    for (uint32_t i = tid; i < k; i += kSelBlock) {
+        int64_t id = -1;
+        float sc = -__builtin_inff();
+        if (i < m) {
+            const uint64_t key = skeys[i];
+            keys[i] = key;
+            id = (int64_t)(uint32_t)(~(uint32_t)key);
+            sc = ordered_to_score((uint32_t)(key >> 32));
         }
-    }
-
-    for (uint32_t i = tid; i < m; i += kSelBlock) keys[i] = skeys[i];
-    if (tid == 0) {
-        a.count[q] = m;
-        if (n >= k && m > 0) a.tau[q] = skeys[m - 1];   // k-th best of everything seen so far
-    }
-    if (a.final_pass) {
-        for (uint32_t i = tid; i < k; i += kSelBlock) {
-            int64_t id = -1;
-            float sc = -__builtin_inff();
-            if (i < m) {
-                const uint64_t key = skeys[i];
-                id = (int64_t)(uint32_t)(~(uint32_t)key);
-                sc = ordered_to_score((uint32_t)(key >> 32));
-            }
-            a.ids_out[(size_t)q * k + i] = id;
-            a.scores_out[(size_t)q * k + i] = sc;
-        }
+        a.ids_out[(size_t)q * k + i] = id;
+        a.scores_out[(size_t)q * k + i] = sc;
     }
 }
 
@@ -407,68 +542,123 @@ __global__ void init_state(uint32_t* count, uint64_t* tau, uint32_t* status, uin
     if (i == 0) *status = 0;
 }
 
+// ---------------------------------------------------------------- load path
+// Address of item z's plane-j words / scale inside the tiled layout.
+__device__ __forceinline__ char* item_tile(char* tiles, const Layout& l, const TileGeom& g, uint64_t z)
+{
+    return tiles + (size_t)tile_to_phys(l, (uint32_t)(z / kTileItems)) * g.tile_bytes();
+}
+
+// Caller's chunk ([P][count][W] words, [P][count] scales, items first..first+count) -> tiles.
+// One thread per item.
+__global__ void scatter_chunk(char* __restrict__ tiles, const Layout l, const TileGeom g,
+                              const uint64_t* __restrict__ planes, const float* __restrict__ scales,
+                              uint64_t first, uint64_t count)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const uint64_t z = first + t;
+    char* tile = item_tile(tiles, l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    for (uint32_t j = 0; j < g.P; ++j) {
+        uint64_t* dst = reinterpret_cast<uint64_t*>(tile + j * g.plane_bytes()) + (size_t)o * g.W;
+        for (uint32_t w = 0; w < g.W; ++w) dst[w] = planes[((size_t)j * count + t) * g.W + w];
+        reinterpret_cast<float*>(tile + g.scales_offset())[j * kTileItems + o] = scales[(size_t)j * count + t];
+    }
+}
+
+// ---------------------------------------------------------------- calibration
+// Plain 16-byte-per-lane copy of a known size: the yardstick that hardware
+// counter readings of the scan are scaled by.
+__global__ __launch_bounds__(256) void calib_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n_vec)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
+}
+
 // ---------------------------------------------------------------- dense helpers (tests, cosine fold)
-__global__ void dense_popcounts(const uint64_t* __restrict__ planes, size_t plane_stride, uint32_t W, uint32_t P,
+__global__ void dense_popcounts(const char* __restrict__ tiles, const Layout l, const TileGeom g,
                                 const uint64_t* __restrict__ qplanes, uint32_t PQ,
                                 uint64_t first, uint64_t count, int32_t* __restrict__ out)
 {
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= count) return;
     const uint64_t z = first + t;
-    for (uint32_t j = 0; j < P; ++j)
+    const char* tile = item_tile(const_cast<char*>(tiles), l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    for (uint32_t j = 0; j < g.P; ++j) {
+        const uint64_t* kw = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)o * g.W;
         for (uint32_t i = 0; i < PQ; ++i) {
             int32_t pc = 0;
-            for (uint32_t w = 0; w < W; ++w)
-                pc += __popcll(planes[((size_t)j * plane_stride + z) * W + w] ^ qplanes[i * W + w]);
-            out[(t * P + j) * PQ + i] = pc;
+            for (uint32_t w = 0; w < g.W; ++w) pc += __popcll(kw[w] ^ qplanes[i * g.W + w]);
+            out[(t * g.P + j) * PQ + i] = pc;
         }
+    }
 }
 
 template <int W, int P, int PQ>
-__global__ void dense_scores(const uint64_t* __restrict__ planes, const float* __restrict__ scales,
-                             size_t plane_stride, const uint32_t* __restrict__ qwords,
-                             const float* __restrict__ qcoef, uint64_t first, uint64_t count,
-                             float* __restrict__ out)
+__global__ void dense_scores(const char* __restrict__ tiles, const Layout l,
+                             const uint32_t* __restrict__ qwords, const float* __restrict__ qcoef,
+                             uint64_t first, uint64_t count, float* __restrict__ out)
 {
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= count) return;
     const uint64_t z = first + t;
+    const TileGeom g{(uint32_t)W, (uint32_t)P};
+    const char* tile = item_tile(const_cast<char*>(tiles), l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
     const QueryRegs<W, PQ> q = load_query<W, PQ>(qwords, qcoef, 0);
     RowRegs<W, P> r;
 #pragma unroll
     for (int j = 0; j < P; ++j) {
-        const uint32_t* pw = reinterpret_cast<const uint32_t*>(planes + ((size_t)j * plane_stride + z) * W);
+        const uint32_t* pw = reinterpret_cast<const uint32_t*>(tile + j * g.plane_bytes()) + (size_t)o * 2 * W;
 #pragma unroll
         for (int h = 0; h < 2 * W; ++h) r.w[j][0][h] = pw[h];
-        r.a[j][0] = scales[(size_t)j * plane_stride + z];
+        r.a[j][0] = reinterpret_cast<const float*>(tile + g.scales_offset())[j * kTileItems + o];
     }
     out[t] = score_item<W, P, PQ>(r, 0, q);
 }
 
+// out[j][t] = scale j of item first + t
+__global__ void gather_scales(const char* __restrict__ tiles, const Layout l, const TileGeom g,
+                              uint64_t first, uint64_t count, float* __restrict__ out)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const uint64_t z = first + t;
+    const char* tile = item_tile(const_cast<char*>(tiles), l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    for (uint32_t j = 0; j < g.P; ++j)
+        out[(size_t)j * count + t] = reinterpret_cast<const float*>(tile + g.scales_offset())[j * kTileItems + o];
+}
+
 // Divide each item's scales by the norm of its reconstructed vector:
 // ||sum_j a_j b_j||^2 = dim * sum_j a_j^2 + 2 sum_{j<j'} a_j a_j' (dim - 2 popcount(K_j ^ K_j')).
-__global__ void fold_cosine(const uint64_t* __restrict__ planes, float* __restrict__ scales,
-                            size_t plane_stride, uint32_t W, uint32_t P, uint64_t n_items)
+// One thread per physical slot; slots never loaded have scale 0 and are left alone.
+__global__ void fold_cosine(char* __restrict__ tiles, const TileGeom g, uint64_t n_slots)
 {
-    const uint64_t z = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (z >= n_items) return;
-    const double dim = 64.0 * W;
+    const uint64_t s = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n_slots) return;
+    char* tile = tiles + (size_t)(s / kTileItems) * g.tile_bytes();
+    const uint32_t o = (uint32_t)(s % kTileItems);
+    float* sc = reinterpret_cast<float*>(tile + g.scales_offset());
+    const double dim = 64.0 * g.W;
     double a[4];
-    for (uint32_t j = 0; j < P; ++j) a[j] = (double)scales[(size_t)j * plane_stride + z];
+    for (uint32_t j = 0; j < g.P; ++j) a[j] = (double)sc[j * kTileItems + o];
     double n2 = 0.0;
-    for (uint32_t j = 0; j < P; ++j) {
+    for (uint32_t j = 0; j < g.P; ++j) {
         n2 += dim * a[j] * a[j];
-        for (uint32_t jj = j + 1; jj < P; ++jj) {
+        const uint64_t* kj = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)o * g.W;
+        for (uint32_t jj = j + 1; jj < g.P; ++jj) {
+            const uint64_t* kk = reinterpret_cast<const uint64_t*>(tile + jj * g.plane_bytes()) + (size_t)o * g.W;
             int pc = 0;
-            for (uint32_t w = 0; w < W; ++w)
-                pc += __popcll(planes[((size_t)j * plane_stride + z) * W + w] ^
-                               planes[((size_t)jj * plane_stride + z) * W + w]);
+            for (uint32_t w = 0; w < g.W; ++w) pc += __popcll(kj[w] ^ kk[w]);
             n2 += 2.0 * a[j] * a[jj] * (dim - 2.0 * pc);
         }
     }
     if (n2 > 0.0) {
         const double nrm = sqrt(n2);
-        for (uint32_t j = 0; j < P; ++j) scales[(size_t)j * plane_stride + z] = (float)(a[j] / nrm);
+        for (uint32_t j = 0; j < g.P; ++j) sc[j * kTileItems + o] = (float)(a[j] / nrm);
     }
 }
 

@@ -92,6 +92,38 @@ def test_encode_query_rejects_bad_input(lib):
         rbe.rbe_encode_query(x, 2)
 
 
+@pytest.mark.parametrize("n_tiles,ratio", [(1, 64), (2, 2), (31, 2), (64, 64), (65, 64), (977, 8), (4097, 64),
+                                           (5000, 3), (300000, 64)])
+def test_tile_order_is_a_bijection_with_nested_sample_prefixes(lib, n_tiles, ratio):
+    to_phys = lambda t: rbe.rbe_debug_tile_to_phys(n_tiles, ratio, t)
+    to_tile = lambda p: rbe.rbe_debug_phys_to_tile(n_tiles, ratio, p)
+    step = max(1, n_tiles // 5000)
+    tiles = sorted(set(range(0, n_tiles, step)) | {n_tiles - 1})
+    phys = [to_phys(t) for t in tiles]
+    assert all(0 <= p < n_tiles for p in phys) and len(set(phys)) == len(tiles)
+    assert [to_tile(p) for p in phys] == tiles
+    assert to_phys(0) == 0
+    if n_tiles <= 5000:
+        assert sorted(phys) == list(range(n_tiles))
+    # number of sample levels: split while the coarsest sample still has more than 32 tiles
+    top, n_ge = 0, n_tiles
+    while n_ge > 32 and ratio ** (top + 1) < n_tiles and top + 1 < 8:
+        top += 1
+        n_ge = -(-n_tiles // ratio ** top)
+    for c in range(1, top + 1):
+        # the stride-r^c sample of tiles is exactly the first ceil(T / r^c) physical tiles
+        size = -(-n_tiles // ratio ** c)
+        probe = range(size) if size <= 3000 else list(range(0, size, size // 1000)) + [size - 1]
+        assert all(to_tile(p) % ratio ** c == 0 for p in probe)
+        if size < n_tiles:
+            assert to_tile(size) % ratio ** c != 0
+        # and within a class tiles ascend
+        ts = [to_tile(p) for p in (probe if size <= 3000 else range(min(size, 200)))]
+        lo = -(-n_tiles // ratio ** (c + 1)) if c < top else 0
+        seg = ts[lo:] if size <= 3000 else ts[lo:200]
+        assert seg == sorted(seg)
+
+
 def test_product_does_not_import_oracle():
     pkg = os.path.join(ROOT, "paper_1802_06466_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -31,6 +31,14 @@ def clustered(N, d, P, n_clusters, sigma, Q, Pq, seed=0, sort_by_cluster=False):
     return planes, scales, np.ascontiguousarray(qp.transpose(1, 0, 2)), np.ascontiguousarray(qs.T)
 
 
+def load_with_ratio(planes, scales, ratio, flags=0):
+    P, N, W = planes.shape
+    ix = rbe.rbe_index_create_ex(N, 64 * W, P, flags, ratio)
+    rbe.rbe_load_chunk(ix, 0, planes, scales)
+    rbe.rbe_finalize(ix)
+    return ix
+
+
 # ------------------------------------------------------------------ binary dot products: bit-exact
 @pytest.mark.parametrize("N,d,P,Pq", [(1, 64, 1, 1), (63, 64, 3, 3), (1025, 64, 3, 2), (5000, 128, 4, 4),
                                       (3000, 128, 2, 3), (2049, 256, 2, 2)])
@@ -113,8 +121,8 @@ def test_k_larger_than_corpus():
 # ------------------------------------------------------------------ multi-level plan and the slow path
 def test_multi_level_plan_small_capacity():
     planes, scales, qp, qs = clustered(300_000, 64, 3, 64, 0.3, 4, 3, seed=1)
-    ix = rbe.rbe_load_corpus(planes, scales)
-    rbe.rbe_set_tuning(ix, sample_ratio=8, cand_capacity=4096)
+    ix = load_with_ratio(planes, scales, 8)
+    rbe.rbe_set_tuning(ix, cand_capacity=6144)
     ids, sc = rbe.rbe_search(ix, qp, qs, 100)
     st = rbe.rbe_get_search_stats(ix)
     assert st["n_levels"] >= 3 and not st["fallback"]
@@ -131,11 +139,24 @@ def test_overflow_takes_bounded_segment_path_and_stays_exact():
     tile = np.arange(N) // 1024
     scales[:, tile % 8 == 0] *= np.float32(1e-3)
     qp, qs = random_queries(rng, 2, 64, 2)
-    ix = rbe.rbe_load_corpus(planes, scales)
-    rbe.rbe_set_tuning(ix, sample_ratio=8, cand_capacity=4096)
+    ix = load_with_ratio(planes, scales, 8)
+    rbe.rbe_set_tuning(ix, cand_capacity=6144)
     ids, sc = rbe.rbe_search(ix, qp, qs, 50)
     assert rbe.rbe_get_search_stats(ix)["fallback"] == 1
     check_batch(planes, scales, qp, qs, 50, ids, sc)
+    rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("ratio,cap", [(2, 2048), (3, 4096), (16, 8192), (64, 0), (4096, 0)])
+def test_sample_ratios(ratio, cap):
+    planes, scales, qp, qs = clustered(150_001, 64, 3, 32, 0.3, 3, 3, seed=8)
+    ix = load_with_ratio(planes, scales, ratio)
+    if cap:
+        rbe.rbe_set_tuning(ix, cand_capacity=cap)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 64)
+    check_batch(planes, scales, qp, qs, 64, ids, sc)
+    got = rbe.rbe_debug_popcounts(ix, qp[0], 0, 150_001)
+    np.testing.assert_array_equal(got, oracle.popcounts(planes, qp[0]))
     rbe.rbe_free(ix)
 
 
