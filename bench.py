@@ -30,6 +30,20 @@ def log(msg: str):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per finest-level scan launch from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE scaled by the plain-copy yardstick), if it covers this workload."""
+    path = os.path.join(ROOT, "profiles", "scan_exact_1e9_d64_p3_q1.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f)
+        if rec.get("workload") == workload:
+            return rec.get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def lane_ops_per_pair(W: int, P: int, Pq: int) -> int:
     """32-bit vector lane-operations the scoring arithmetic needs per (query, item)
     pair: per plane pair 2W xor + 2W popcount-accumulate + 1 convert + 1 fma, per
@@ -255,6 +269,7 @@ def main():
                              "gbs_read_plus_write": 2 * nbytes / (ms * 1e-3) / 1e9}
         log(f"calib_copy {args.calibrate_copy} MiB: {ms:.3f} ms -> {2 * nbytes / (ms * 1e-3) / 1e9:.0f} GB/s (r+w)")
 
+    out["roofline"]["traffic"] = measured_traffic(out["config"]["workload"])
     rbe.rbe_free(ix)
     print(json.dumps(out), flush=True)
 

@@ -238,13 +238,19 @@ struct Level { uint32_t p_begin, p_end; };
 // must fit the candidate list whole; each finer level reads `ratio` times more
 // tiles, minus those already read, and keeps only items that reach the k-th
 // best key found so far -- a proven lower bound for the final k-th best.
+// The plan starts at the coarsest sample that still holds at least 4k items
+// (its k-th best is then a useful threshold and every selection sees about
+// ratio*k candidates); failing that, at the finest one that fits `cap`.
 // Returns an empty plan if even the coarsest sample does not fit `cap`.
-std::vector<Level> make_plan(const rbe::Layout& l, uint32_t cap)
+std::vector<Level> make_plan(const rbe::Layout& l, uint32_t cap, uint32_t k)
 {
     std::vector<Level> plan;
-    uint32_t c0 = 0;
-    while (c0 <= l.top && (uint64_t)l.n_ge[c0] * kTileItems > cap) ++c0;
-    if (c0 > l.top) return plan;
+    uint32_t cmin = 0;
+    while (cmin <= l.top && (uint64_t)l.n_ge[cmin] * kTileItems > cap) ++cmin;
+    if (cmin > l.top) return plan;
+    uint32_t c0 = cmin;
+    for (uint32_t c = l.top; c > cmin; --c)
+        if ((uint64_t)l.n_ge[c] * kTileItems >= 4ull * k) { c0 = c; break; }
     plan.push_back(Level{0, l.n_ge[c0]});
     for (uint32_t c = c0; c-- > 0;) plan.push_back(Level{l.n_ge[c + 1], l.n_ge[c]});
     return plan;
@@ -545,7 +551,7 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
     if (rc) return rc;
 
     const uint32_t n_tiles = ix->layout.n_tiles;
-    const std::vector<Level> plan = make_plan(ix->layout, cap);
+    const std::vector<Level> plan = make_plan(ix->layout, cap, k);
     const bool plan_dense_ok = !plan.empty();
 
     ix->stats = rbe_search_stats{};
