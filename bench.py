@@ -89,21 +89,22 @@ def make_queries(rbe, rbe_synth, torch, centres, n, sigma, P, seed_chunk):
     return np.stack([e[0] for e in enc]), np.stack([e[1] for e in enc])
 
 
-def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup):
+def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_size_I=0):
     """Runs warmup + steps searches of Q queries each (different queries per call)."""
     import numpy as np
-    per_step, scan_ms, select_ms, total_gpu = [], [], [], []
+    per_step, scan_ms, select_ms, total_gpu, all_ids = [], [], [], [], []
     stats = None
     for s in range(warmup):
         sl = slice(s * Q, (s + 1) * Q)
-        rbe.rbe_search(ix, qp[sl], qs[sl], k)
+        rbe.rbe_search(ix, qp[sl], qs[sl], k, mode, group_size_I)
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
     for s in range(warmup, warmup + steps):
         sl = slice(s * Q, (s + 1) * Q)
         t0 = time.perf_counter()
-        rbe.rbe_search(ix, qp[sl], qs[sl], k)
+        ids, _ = rbe.rbe_search(ix, qp[sl], qs[sl], k, mode, group_size_I)
         per_step.append((time.perf_counter() - t0) * 1e3)
+        all_ids.append(ids)
         stats = rbe.rbe_get_search_stats(ix)
         if stats["n_levels"] and not stats["fallback"]:
             scan_ms.append(stats["scan_ms"][-1])
@@ -114,6 +115,7 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup):
     return {
         "wall_s": wall, "per_step_ms": np.array(per_step), "scan_ms": np.array(scan_ms),
         "select_ms": np.array(select_ms), "total_gpu_ms": np.array(total_gpu), "stats": stats,
+        "ids": all_ids,
     }
 
 
@@ -134,6 +136,7 @@ def main():
     ap.add_argument("--cpu-sample-items", type=int, default=100_000_000)
     ap.add_argument("--cpu-sample-queries", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-nearlossless", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also launch the plain copy kernel of this size 5 times (yardstick for rocprofv3 counters)")
     args = ap.parse_args()
@@ -215,6 +218,25 @@ def main():
             "grid_blocks": st["grid_blocks"],
         },
     }
+
+    # ---------------- near-lossless selector (Algorithm 1, queue length 1, I = 256) on the same queries
+    if not args.no_nearlossless:
+        I = 256
+        rn = timed_searches(rbe, torch, ix, qp1, qs1, 1, k, args.steps, args.warmup, rbe.RBE_SELECT_NEARLOSSLESS, I)
+        recalls = [len(set(a[0].tolist()) & set(b[0].tolist()) - {-1}) / k for a, b in zip(rn["ids"], r1["ids"])]
+        groups = -(-N // (256 * I)) * 256
+        slots = groups * I
+        # Appendix A: E[M]/N = (T/N) (1 - prod_{i<I} (1 - N/(C-i))) ~ 1 - (N-1)(I-1)/(2(C-1))
+        predicted = 1.0 - (k - 1) * (I - 1) / (2.0 * (slots - 1))
+        n_ms = rn["wall_s"] * 1e3 / args.steps
+        out["near_lossless"] = {
+            "group_size_I": I, "ms_per_step": n_ms, "p50_ms": float(np.percentile(rn["per_step_ms"], 50)),
+            "value": N * args.steps / rn["wall_s"], "unit": "candidates/s",
+            "scan_kernel_ms": float(rn["scan_ms"].mean()) if rn["scan_ms"].size else None,
+            "recall_vs_exact_mean": float(np.mean(recalls)), "recall_vs_exact_min": float(np.min(recalls)),
+            "recall_predicted_appendix_a": predicted, "queries": len(recalls),
+        }
+        log(f"near-lossless I={I}: {n_ms:.3f} ms/step, recall {np.mean(recalls):.5f} (Appendix A: {predicted:.5f})")
 
     # ---------------- batch leg
     if args.batch > 0:

@@ -125,6 +125,39 @@ ScanFn scan_fn(uint32_t W, uint32_t P, uint32_t PQ, bool single)
     }
 }
 
+using GroupFn = void (*)(const GroupArgs);
+
+template <int W, int P>
+GroupFn group_fn_p(uint32_t PQ, bool single)
+{
+    switch (PQ) {
+        case 1: return single ? scan_groupmax<W, P, 1, 1> : scan_groupmax<W, P, 1, 4>;
+        case 2: return single ? scan_groupmax<W, P, 2, 1> : scan_groupmax<W, P, 2, 4>;
+        case 3: return single ? scan_groupmax<W, P, 3, 1> : scan_groupmax<W, P, 3, 4>;
+        default: return single ? scan_groupmax<W, P, 4, 1> : scan_groupmax<W, P, 4, 4>;
+    }
+}
+
+template <int W>
+GroupFn group_fn_w(uint32_t P, uint32_t PQ, bool single)
+{
+    switch (P) {
+        case 1: return group_fn_p<W, 1>(PQ, single);
+        case 2: return group_fn_p<W, 2>(PQ, single);
+        case 3: return group_fn_p<W, 3>(PQ, single);
+        default: return group_fn_p<W, 4>(PQ, single);
+    }
+}
+
+GroupFn group_fn(uint32_t W, uint32_t P, uint32_t PQ, bool single)
+{
+    switch (W) {
+        case 1: return group_fn_w<1>(P, PQ, single);
+        case 2: return group_fn_w<2>(P, PQ, single);
+        default: return group_fn_w<4>(P, PQ, single);
+    }
+}
+
 template <int W, int P>
 void launch_dense_p(uint32_t PQ, uint32_t grid, hipStream_t st, const rbe_index* ix, uint64_t first, uint64_t count, float* out)
 {
@@ -490,39 +523,103 @@ int rbe_set_tuning(rbe_index* ix, uint32_t cand_capacity, uint32_t blocks_per_cu
     return RBE_OK;
 }
 
-// Enqueue one scan + select round.  `final_pass` makes the select write the results.
-static int run_round(rbe_index* ix, hipStream_t st, uint32_t Q, uint32_t PQ, uint32_t k, uint32_t cap,
-                     uint32_t p_begin, uint32_t p_end, int final_pass, uint32_t level_slot, bool record)
+// One scan + select round.  Exact mode: physical tiles [begin, end).  Near-lossless
+// mode: super-block ranks [begin, end) with unit = rank (skip == 0) or the rank-th
+// non-multiple of `skip`, super-block = unit * stride.
+struct Round { uint32_t begin, end, stride, skip; };
+
+struct SearchCtx {
+    rbe_index* ix; hipStream_t st; uint32_t Q, PQ, k, cap, mode, I;
+};
+
+static int launch_scan_round(const SearchCtx& c, const Round& r)
 {
-    ScanArgs sa;
-    sa.tiles = ix->d_tiles; sa.layout = ix->layout; sa.n_items = ix->n_items;
-    sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = Q;
-    sa.tau = ix->d_tau; sa.cand = ix->d_cand; sa.count = ix->d_count; sa.cap = cap;
-    sa.p_begin = p_begin; sa.p_end = p_end;
-    const uint32_t n_tiles = p_end - p_begin;
-    if (n_tiles > 0) {
-        const ScanFn fn = scan_fn(ix->W, ix->P, PQ, Q == 1);
+    rbe_index* ix = c.ix;
+    if (r.end <= r.begin) return RBE_OK;
+    const uint32_t n_units = r.end - r.begin;
+    if (c.mode == RBE_SELECT_EXACT) {
+        ScanArgs sa;
+        sa.tiles = ix->d_tiles; sa.layout = ix->layout; sa.n_items = ix->n_items;
+        sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = c.Q;
+        sa.tau = ix->d_tau; sa.cand = ix->d_cand; sa.count = ix->d_count; sa.cap = c.cap;
+        sa.p_begin = r.begin; sa.p_end = r.end;
+        const ScanFn fn = scan_fn(ix->W, ix->P, c.PQ, c.Q == 1);
         uint32_t per_cu = ix->blocks_per_cu;
         if (per_cu == 0) {  // as many workgroups as are resident at once: one wave of persistent groups
             int nb = 0;
             HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0));
             per_cu = (uint32_t)std::max(nb, 1);
         }
-        const uint32_t grid = std::min<uint32_t>(n_tiles, (uint32_t)ix->n_cu * per_cu);
+        const uint32_t grid = std::min<uint32_t>(n_units, (uint32_t)ix->n_cu * per_cu);
         ix->stats.grid_blocks = std::max(ix->stats.grid_blocks, grid);
-        fn<<<dim3(grid), dim3(kBlock), 0, st>>>(sa);
+        fn<<<dim3(grid), dim3(kBlock), 0, c.st>>>(sa);
+        HIP_TRY(hipGetLastError());
+        return RBE_OK;
+    }
+    GroupArgs ga;
+    ga.tiles = ix->d_tiles; ga.layout = ix->layout; ga.n_items = ix->n_items;
+    ga.rows_total = (uint32_t)((ix->n_items + kRow - 1) / kRow); ga.I = c.I;
+    ga.qwords = ix->d_qwords; ga.qcoef = ix->d_qcoef;
+    ga.tau = ix->d_tau; ga.cand = ix->d_cand; ga.count = ix->d_count; ga.cap = c.cap;
+    ga.v_begin = r.begin; ga.v_end = r.end; ga.stride = r.stride; ga.skip = r.skip;
+    const bool single = c.Q == 1;
+    const uint32_t QB = single ? 1 : 4;
+    const GroupFn fn = group_fn(ix->W, ix->P, c.PQ, single);
+    uint32_t per_cu = ix->blocks_per_cu;
+    if (per_cu == 0) {
+        int nb = 0;
+        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0));
+        per_cu = (uint32_t)std::max(nb, 1);
+    }
+    const uint32_t grid = std::min<uint32_t>(n_units, (uint32_t)ix->n_cu * per_cu);
+    ix->stats.grid_blocks = std::max(ix->stats.grid_blocks, grid);
+    for (uint32_t q0 = 0; q0 < c.Q; q0 += QB) {   // the corpus range is re-read once per block of QB queries
+        ga.q_begin = q0;
+        ga.nq = std::min<uint32_t>(QB, c.Q - q0);
+        fn<<<dim3(grid), dim3(kBlock), 0, c.st>>>(ga);
         HIP_TRY(hipGetLastError());
     }
-    if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 1], st));
+    return RBE_OK;
+}
+
+static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_t level_slot, bool record)
+{
+    rbe_index* ix = c.ix;
+    int rc = launch_scan_round(c, r);
+    if (rc) return rc;
+    if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 1], c.st));
 
     SelectArgs se;
-    se.cand = ix->d_cand; se.count = ix->d_count; se.tau = ix->d_tau; se.cap = cap; se.k = k;
+    se.cand = ix->d_cand; se.count = ix->d_count; se.tau = ix->d_tau; se.cap = c.cap; se.k = c.k;
     se.status = ix->d_status; se.count_seen = ix->d_seen + (size_t)level_slot * RBE_MAX_QUERIES;
     se.final_pass = final_pass; se.ids_out = ix->d_ids; se.scores_out = ix->d_scores;
-    hipLaunchKernelGGL(rbe::select_topk, dim3(Q), dim3(kSelBlock), 0, st, se);
+    hipLaunchKernelGGL(rbe::select_topk, dim3(c.Q), dim3(kSelBlock), 0, c.st, se);
     HIP_TRY(hipGetLastError());
-    if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 2], st));
+    if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 2], c.st));
     return RBE_OK;
+}
+
+// Rounds of the near-lossless mode: the same nested-sample idea over super-blocks.
+// Every super-block forwards at most 256 group winners; the coarsest sample is
+// read with no threshold and must fit the candidate list.
+static std::vector<Round> make_group_plan(uint32_t n_super, uint32_t ratio, uint32_t cap)
+{
+    std::vector<uint32_t> strides{1};
+    while ((uint64_t)((n_super + strides.back() - 1) / strides.back()) * kRow > cap &&
+           strides.size() < RBE_MAX_LEVELS && strides.back() < n_super)
+        strides.push_back(strides.back() * ratio);
+    std::vector<Round> plan;
+    if ((uint64_t)((n_super + strides.back() - 1) / strides.back()) * kRow > cap) return plan;
+    for (size_t l = strides.size(); l-- > 0;) {
+        Round r;
+        r.stride = strides[l];
+        const uint32_t units = (n_super + r.stride - 1) / r.stride;
+        r.skip = (l + 1 == strides.size()) ? 0u : ratio;
+        r.begin = 0;
+        r.end = r.skip ? units - (units + ratio - 1) / ratio : units;
+        plan.push_back(r);
+    }
+    return plan;
 }
 
 int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
@@ -537,58 +634,63 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
     ARG_CHECK(k >= 1 && k <= RBE_MAX_K, "k must be 1..%u (got %u)", RBE_MAX_K, k);
     ARG_CHECK(mode == RBE_SELECT_EXACT || mode == RBE_SELECT_NEARLOSSLESS, "unknown mode %u", mode);
     ARG_CHECK(group_size_I <= 65535, "group_size_I must be <= 65535");
-    if (mode == RBE_SELECT_NEARLOSSLESS) { set_error("near-lossless mode is not built yet"); return RBE_EUNSUPPORTED; }
-    (void)group_size_I;
 
-    hipStream_t st = (hipStream_t)hip_stream;
-    const uint32_t Q = n_queries, PQ = q_n_planes;
+    SearchCtx c;
+    c.ix = ix; c.st = (hipStream_t)hip_stream; c.Q = n_queries; c.PQ = q_n_planes; c.k = k; c.mode = mode;
+    c.I = group_size_I ? group_size_I : 256;
     uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->layout.ratio * k);
-    cap = std::max<uint32_t>(cap, k + 2 * kTileItems);
-    int rc = ensure_workspace(ix, Q, k, cap);
+    c.cap = std::max<uint32_t>(cap, k + 2 * kTileItems);
+    int rc = ensure_workspace(ix, c.Q, k, c.cap);
+    if (rc) return rc;
+    rc = stage_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
     if (rc) return rc;
 
-    rc = stage_queries(ix, q_planes, q_scales, Q, PQ, st);
-    if (rc) return rc;
-
-    const uint32_t n_tiles = ix->layout.n_tiles;
-    const std::vector<Level> plan = make_plan(ix->layout, cap, k);
-    const bool plan_dense_ok = !plan.empty();
+    // units of the slow path: tiles (exact) or super-blocks (near-lossless), `per_unit` candidates each at most
+    const uint32_t rows_total = (uint32_t)((ix->n_items + kRow - 1) / kRow);
+    const uint32_t n_units = mode == RBE_SELECT_EXACT ? ix->layout.n_tiles : (rows_total + c.I - 1) / c.I;
+    const uint32_t per_unit = mode == RBE_SELECT_EXACT ? kTileItems : kRow;
+    std::vector<Round> plan;
+    if (mode == RBE_SELECT_EXACT) {
+        for (const Level& lv : make_plan(ix->layout, c.cap, k)) plan.push_back(Round{lv.p_begin, lv.p_end, 1, 0});
+    } else {
+        plan = make_group_plan(n_units, ix->layout.ratio, c.cap);
+    }
 
     ix->stats = rbe_search_stats{};
     const bool prof = ix->profiling != 0;
-    bool fallback = !plan_dense_ok;
+    bool fallback = plan.empty();
 
     for (int attempt = 0; attempt < 2; ++attempt) {
-        hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, st, ix->d_count, ix->d_tau, ix->d_status, Q);
+        hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, c.st, ix->d_count, ix->d_tau, ix->d_status, c.Q);
         HIP_TRY(hipGetLastError());
         if (!fallback) {
-            if (prof) HIP_TRY(hipEventRecord(ix->ev[0], st));
+            if (prof) HIP_TRY(hipEventRecord(ix->ev[0], c.st));
             for (size_t l = 0; l < plan.size(); ++l) {
-                const Level& lv = plan[l];
-                rc = run_round(ix, st, Q, PQ, k, cap, lv.p_begin, lv.p_end, l + 1 == plan.size(), (uint32_t)l, prof);
+                rc = run_round(c, plan[l], l + 1 == plan.size(), (uint32_t)l, prof);
                 if (rc) return rc;
-                ix->stats.items_scanned[l] = (uint64_t)(lv.p_end - lv.p_begin) * kTileItems;
+                ix->stats.items_scanned[l] = (uint64_t)(plan[l].end - plan[l].begin) *
+                                             (mode == RBE_SELECT_EXACT ? (uint64_t)kTileItems : (uint64_t)c.I * kRow);
             }
             ix->stats.n_levels = (uint32_t)plan.size();
         } else {
-            // Slow path that cannot overflow: segments of at most cap - k items, each followed
-            // by a selection that compacts the list back to k entries.
-            const uint32_t seg = std::max<uint32_t>(1u, (cap - k) / kTileItems);
-            for (uint64_t u0 = 0; u0 < n_tiles; u0 += seg) {
-                const uint32_t u1 = (uint32_t)std::min<uint64_t>(n_tiles, u0 + seg);
-                rc = run_round(ix, st, Q, PQ, k, cap, (uint32_t)u0, u1, u1 == n_tiles, 0, false);
+            // Slow path that cannot overflow: segments that add at most cap - k candidates, each
+            // followed by a selection that compacts the list back to k entries.
+            const uint32_t seg = std::max<uint32_t>(1u, (c.cap - k) / per_unit);
+            for (uint64_t u0 = 0; u0 < n_units; u0 += seg) {
+                const uint32_t u1 = (uint32_t)std::min<uint64_t>(n_units, u0 + seg);
+                rc = run_round(c, Round{(uint32_t)u0, u1, 1, 0}, u1 == n_units, 0, false);
                 if (rc) return rc;
             }
             ix->stats.n_levels = 1;
             ix->stats.fallback = 1;
-            ix->stats.items_scanned[0] = (uint64_t)n_tiles * kTileItems;
+            ix->stats.items_scanned[0] = (uint64_t)ix->layout.n_tiles * kTileItems;
         }
-        HIP_TRY(hipMemcpyAsync(ix->h_status, ix->d_status, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipMemcpyAsync(ix->h_seen, ix->d_seen, RBE_MAX_LEVELS * RBE_MAX_QUERIES * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipMemcpyAsync(ix->h_ids, ix->d_ids, (size_t)Q * k * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipMemcpyAsync(ix->h_scores, ix->d_scores, (size_t)Q * k * sizeof(float), hipMemcpyDeviceToHost, st));
-        if (prof && !fallback) HIP_TRY(hipEventRecord(ix->ev[kMaxEvents - 1], st));
-        HIP_TRY(hipStreamSynchronize(st));
+        HIP_TRY(hipMemcpyAsync(ix->h_status, ix->d_status, sizeof(uint32_t), hipMemcpyDeviceToHost, c.st));
+        HIP_TRY(hipMemcpyAsync(ix->h_seen, ix->d_seen, RBE_MAX_LEVELS * RBE_MAX_QUERIES * sizeof(uint32_t), hipMemcpyDeviceToHost, c.st));
+        HIP_TRY(hipMemcpyAsync(ix->h_ids, ix->d_ids, (size_t)c.Q * k * sizeof(int64_t), hipMemcpyDeviceToHost, c.st));
+        HIP_TRY(hipMemcpyAsync(ix->h_scores, ix->d_scores, (size_t)c.Q * k * sizeof(float), hipMemcpyDeviceToHost, c.st));
+        if (prof && !fallback) HIP_TRY(hipEventRecord(ix->ev[kMaxEvents - 1], c.st));
+        HIP_TRY(hipStreamSynchronize(c.st));
         if (!(*ix->h_status & rbe::kStatusOverflow)) break;
         if (fallback) { set_error("candidate list overflowed in the bounded-segment path"); return RBE_EHIP; }
         fallback = true;  // a level produced more survivors than the list holds: redo on the slow path
@@ -597,7 +699,7 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
     if (!fallback) {
         for (uint32_t l = 0; l < ix->stats.n_levels; ++l) {
             uint32_t mx = 0;
-            for (uint32_t q = 0; q < Q; ++q) mx = std::max(mx, ix->h_seen[(size_t)l * RBE_MAX_QUERIES + q]);
+            for (uint32_t q = 0; q < c.Q; ++q) mx = std::max(mx, ix->h_seen[(size_t)l * RBE_MAX_QUERIES + q]);
             ix->stats.candidates_max[l] = mx;
             if (prof) {
                 HIP_TRY(hipEventElapsedTime(&ix->stats.scan_ms[l], ix->ev[2 * l], ix->ev[2 * l + 1]));
@@ -606,8 +708,8 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
         }
         if (prof) HIP_TRY(hipEventElapsedTime(&ix->stats.total_gpu_ms, ix->ev[0], ix->ev[kMaxEvents - 1]));
     }
-    std::memcpy(ids_out, ix->h_ids, (size_t)Q * k * sizeof(int64_t));
-    std::memcpy(scores_out, ix->h_scores, (size_t)Q * k * sizeof(float));
+    std::memcpy(ids_out, ix->h_ids, (size_t)c.Q * k * sizeof(int64_t));
+    std::memcpy(scores_out, ix->h_scores, (size_t)c.Q * k * sizeof(float));
     return RBE_OK;
 }
 

@@ -6,7 +6,7 @@ import pytest
 import oracle
 import paper_1802_06466_amd as rbe
 import rbe_synth
-from parity import check_batch, check_topk, score_tolerance
+from parity import check_batch, check_nearlossless, check_topk, score_tolerance
 
 pytestmark = pytest.mark.gpu
 
@@ -312,4 +312,84 @@ def test_near_duplicate_clusters_k4000():
     ix = rbe.rbe_load_corpus(planes, scales)
     ids, sc = rbe.rbe_search(ix, qp, qs, 4000)
     check_batch(planes, scales, qp, qs, 4000, ids, sc)
+    rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ near-lossless selection (Algorithm 1, queue length 1)
+@pytest.mark.parametrize("N,I,Q,k", [(1000, 1, 1, 50), (1000, 3, 2, 50), (65536, 256, 1, 100), (70001, 256, 3, 300),
+                                     (70001, 16, 5, 1000), (300_000, 4, 1, 1000), (300_000, 255, 8, 64),
+                                     (5000, 256, 2, 300)])
+def test_nearlossless_matches_oracle(N, I, Q, k):
+    rng = np.random.default_rng(N + I + Q + k)
+    planes, scales = random_corpus(rng, N, 64, 3)
+    qp, qs = random_queries(rng, Q, 64, 3)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=I)
+    for q in range(Q):
+        check_nearlossless(planes, scales, qp[q], qs[q], k, I, ids[q], sc[q])
+    if I == 1:      # every item is its own group: the selector is exact
+        check_batch(planes, scales, qp, qs, k, ids, sc)
+    rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("d,P,Pq", [(128, 4, 4), (128, 2, 3), (256, 2, 2), (64, 1, 1)])
+def test_nearlossless_shapes(d, P, Pq):
+    planes, scales, qp, qs = clustered(200_003, d, P, 64, 0.3, 6, Pq, seed=9)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 200, mode=rbe.RBE_SELECT_NEARLOSSLESS)   # I = 256 by default
+    for q in range(6):
+        check_nearlossless(planes, scales, qp[q], qs[q], 200, 256, ids[q], sc[q])
+    rbe.rbe_free(ix)
+
+
+def test_nearlossless_exact_ties_pick_lowest_id():
+    N = 100_000
+    one = np.array([0x0F0F0F0F0F0F0F0F], dtype=np.uint64)
+    planes = np.broadcast_to(one, (2, N, 1)).copy()
+    scales = np.full((2, N), 0.5, dtype=np.float32)
+    qp = planes[:, :1].transpose(1, 0, 2).copy()
+    qs = np.ones((1, 2), dtype=np.float32)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 300, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=256)
+    o_ids, _ = oracle.nearlossless(planes, scales, qp[0], qs[0], 300, I=256)
+    np.testing.assert_array_equal(ids[0], o_ids)     # all scores equal and exact: winners are the lowest ids
+    rbe.rbe_free(ix)
+
+
+def test_nearlossless_multi_level_and_slow_path():
+    planes, scales, qp, qs = clustered(1_200_000, 64, 3, 128, 0.3, 2, 3, seed=10)
+    ix = load_with_ratio(planes, scales, 8)
+    rbe.rbe_set_tuning(ix, cand_capacity=6144)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 100, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=16)
+    st = rbe.rbe_get_search_stats(ix)
+    assert st["n_levels"] >= 2 and not st["fallback"]
+    for q in range(2):
+        check_nearlossless(planes, scales, qp[q], qs[q], 100, 16, ids[q], sc[q])
+    # a corpus whose sampled super-blocks are all weak: the threshold prunes nothing -> slow path
+    rng = np.random.default_rng(13)
+    N = 600_000
+    planes, scales = random_corpus(rng, N, 64, 2)
+    sb = np.arange(N) // (256 * 4)
+    scales[:, sb % 8 == 0] *= np.float32(1e-3)
+    qp, qs = random_queries(rng, 2, 64, 2)
+    ix2 = load_with_ratio(planes, scales, 8)
+    rbe.rbe_set_tuning(ix2, cand_capacity=6144)
+    ids, sc = rbe.rbe_search(ix2, qp, qs, 50, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=4)
+    assert rbe.rbe_get_search_stats(ix2)["fallback"] == 1
+    for q in range(2):
+        check_nearlossless(planes, scales, qp[q], qs[q], 50, 4, ids[q], sc[q])
+    rbe.rbe_free(ix); rbe.rbe_free(ix2)
+
+
+def test_nearlossless_recall_tracks_appendix_a():
+    """Random-order ids: recall of the GPU near-lossless selector against the GPU exact
+    selector, averaged over queries, agrees with E[M]/N of Appendix A."""
+    N, I, k, Q = 2_097_152, 256, 1000, 32
+    planes, scales, qp, qs = clustered(N, 64, 3, 256, 0.3, Q, 3, seed=11)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    exact, _ = rbe.rbe_search(ix, qp, qs, k)
+    near, _ = rbe.rbe_search(ix, qp, qs, k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=I)
+    rec = np.mean([oracle.recall(near[q], exact[q]) for q in range(Q)])
+    expect = oracle.expected_recall(k, N, I)
+    assert abs(rec - expect) < 4 * np.sqrt(expect * (1 - expect) / (k * Q)) + 2e-3, (rec, expect)
     rbe.rbe_free(ix)
