@@ -236,9 +236,41 @@ __device__ __forceinline__ uint32_t stage_append(bool ok, uint64_t key, uint32_t
     return fill + n;
 }
 
+// Scores the lane's 4 items of `cur` against one query and queues the survivors.
+template <int W, int P, int PQ, bool SINGLE>
+__device__ __forceinline__ uint32_t score_and_stage(const RowRegs<W, P>& cur, const QueryRegs<W, PQ>& qr, uint64_t tau,
+                                                    float taus, uint32_t q, uint32_t p, int wave, int lane,
+                                                    uint64_t* s_keys, uint8_t* s_q, uint32_t fill, const ScanArgs& a)
+{
+    float s[kItemsPerLane];
+    bool any = false;
+#pragma unroll
+    for (int m = 0; m < kItemsPerLane; ++m) {
+        s[m] = score_item<W, P, PQ>(cur, m, qr);
+        any |= (s[m] >= taus);
+    }
+    if (__ballot(any)) {   // rare: at least one lane of the wave has a survivor
+        const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            const uint64_t id = row_id + lane_item<W>(lane, m);
+            bool ok = (s[m] >= taus) && (id < a.n_items);
+            uint64_t key = 0;
+            if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
+            fill = stage_append<SINGLE>(ok, key, q, s_keys, s_q, fill, a, lane);
+        }
+    }
+    return fill;
+}
+
 // Streaming exhaustive match + local selection over physical tiles
 // [p_begin, p_end).  Persistent workgroups: workgroup b takes tiles p_begin + b,
-// + grid, ...; the next tile's loads are issued before the current one is scored.
+// + grid, ....
+// SINGLE (one query, HBM-bound): the query lives in SGPRs and the next tile's loads
+// are issued before the current one is scored (register double buffering).
+// Batch (VALU-bound): one tile in registers, all queries applied to it; the next
+// query's words and coefficients are fetched by scalar loads while the current
+// one is being applied, and memory latency is covered by the other resident waves.
 template <int W, int P, int PQ, bool SINGLE>
 __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
 {
@@ -255,59 +287,41 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
 
     uint32_t p = a.p_begin + blockIdx.x;
     if (p >= a.p_end) return;
-
-    QueryRegs<W, PQ> q0;
-    uint64_t tau0 = 0;
-    float taus0 = 0.f;
-    if (SINGLE) {
-        q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
-        tau0 = a.tau[0];
-        taus0 = threshold_score(tau0);
-    }
-
     uint32_t fill = 0;
-    RowRegs<W, P> cur, nxt;
-    load_row<W, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
 
-    for (;;) {
-        const uint32_t pn = p + G;
-        const bool has_next = pn < a.p_end;
-        if (has_next) load_row<W, P>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
-
-        const uint32_t nq = SINGLE ? 1u : a.n_queries;
-        for (uint32_t q = 0; q < nq; ++q) {
-            QueryRegs<W, PQ> qr;
-            uint64_t tau;
-            float taus;
-            if (SINGLE) { qr = q0; tau = tau0; taus = taus0; }
-            else {
-                qr = load_query<W, PQ>(a.qwords, a.qcoef, q);
-                tau = a.tau[q];
-                taus = threshold_score(tau);
-            }
-            float s[kItemsPerLane];
-            bool any = false;
-#pragma unroll
-            for (int m = 0; m < kItemsPerLane; ++m) {
-                s[m] = score_item<W, P, PQ>(cur, m, qr);
-                any |= (s[m] >= taus);
-            }
-            if (__ballot(any)) {   // rare: at least one lane of the wave has a survivor
-                const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
-#pragma unroll
-                for (int m = 0; m < kItemsPerLane; ++m) {
-                    const uint64_t id = row_id + lane_item<W>(lane, m);
-                    bool ok = (s[m] >= taus) && (id < a.n_items);
-                    uint64_t key = 0;
-                    if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
-                    fill = stage_append<SINGLE>(ok, key, q, s_keys, s_q, fill, a, lane);
+    if (SINGLE) {
+        const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+        const uint64_t tau0 = a.tau[0];
+        const float taus0 = threshold_score(tau0);
+        RowRegs<W, P> cur, nxt;
+        load_row<W, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+        for (;;) {
+            const uint32_t pn = p + G;
+            const bool has_next = pn < a.p_end;
+            if (has_next) load_row<W, P>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            fill = score_and_stage<W, P, PQ, SINGLE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, s_q, fill, a);
+            if (!has_next) break;
+            cur = nxt;
+            p = pn;
+        }
+    } else {
+        const uint32_t nq = a.n_queries;
+        for (; p < a.p_end; p += G) {
+            RowRegs<W, P> cur;
+            load_row<W, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+            uint64_t tau_n = a.tau[0];
+            for (uint32_t q = 0; q < nq; ++q) {
+                const QueryRegs<W, PQ> qr = qn;
+                const uint64_t tau = tau_n;
+                if (q + 1 < nq) {
+                    qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
+                    tau_n = a.tau[q + 1];
                 }
+                fill = score_and_stage<W, P, PQ, SINGLE>(cur, qr, tau, threshold_score(tau), q, p, wave, lane,
+                                                         s_keys, s_q, fill, a);
             }
         }
-
-        if (!has_next) break;
-        cur = nxt;
-        p = pn;
     }
     if (fill) stage_flush<SINGLE>(s_keys, s_q, fill, a, lane);
 }
