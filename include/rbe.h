@@ -63,10 +63,22 @@ enum {
 enum { RBE_MEM_HOST = 0, RBE_MEM_DEVICE = 1 }; /* where a caller's array lives */
 
 enum {
-    RBE_COSINE = 1u << 1 /* at rbe_finalize(): divide every item's scales by the
+    RBE_COSINE = 1u << 1, /* at rbe_finalize(): divide every item's scales by the
                             norm of its reconstructed vector sum_j a_j b_j, so that
                             scores become the cosine of Eq. 14 up to the query's own
                             norm (which Sec. 5.1 drops as constant per query)      */
+    RBE_DYADIC = 1u << 2  /* the paper's own representation (Sec. 4.3, Sec. 5.1):
+                            plane j of every item has the fixed weight 2^-j and plane
+                            i of every query the weight 2^-i; no per-plane scales are
+                            stored.  The weighted sum of the binary dot products is
+                            formed with integer shift-adds in Horner order (Sec. 5.1,
+                            footnote) and is exact.  With RBE_COSINE one fp32 inverse
+                            norm per item is computed at rbe_finalize() and kept with
+                            the item (dim/8 * P + 4 bytes per item: 20 at dim 64, P = 2);
+                            without it nothing but the bits is stored (16 bytes) and
+                            scores are exact dyadic rationals.  The `scales` arguments
+                            of the load calls are ignored (may be NULL); q_scales of
+                            rbe_search must be NULL or exactly 2^-i.  dim 64 or 128.   */
 };
 
 enum { RBE_SELECT_EXACT = 0, RBE_SELECT_NEARLOSSLESS = 1 };
@@ -91,9 +103,10 @@ enum { RBE_SELECT_EXACT = 0, RBE_SELECT_NEARLOSSLESS = 1 };
 
 /* Allocates device storage for n_items items of `dim` dimensions and
  * `n_planes` ingredient vectors.  dim in {64, 128, 256}; 1 <= n_planes <= 4;
- * 1 <= n_items <= RBE_MAX_ITEMS.  flags: 0 or RBE_COSINE.  The index starts
+ * 1 <= n_items <= RBE_MAX_ITEMS.  flags: 0 or any of RBE_COSINE, RBE_DYADIC.  The index starts
  * in the "loading" state.  Device memory: n_items * n_planes * (dim/8 + 4)
- * bytes, rounded up to a multiple of 1024 items.                             */
+ * bytes (see RBE_DYADIC for its smaller footprint), rounded up to a multiple of
+ * 1024 items.                           */
 int rbe_index_create(rbe_index **out, uint64_t n_items, uint32_t dim,
                      uint32_t n_planes, uint32_t flags);
 

@@ -21,6 +21,7 @@ from . import _build
 RBE_OK, RBE_EINVAL, RBE_ENOMEM, RBE_EHIP, RBE_ESTATE, RBE_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 RBE_MEM_HOST, RBE_MEM_DEVICE = 0, 1
 RBE_COSINE = 1 << 1
+RBE_DYADIC = 1 << 2
 RBE_SELECT_EXACT, RBE_SELECT_NEARLOSSLESS = 0, 1
 RBE_MAX_PLANES, RBE_MAX_QUERIES, RBE_MAX_K, RBE_MAX_LEVELS = 4, 64, 4096, 8
 RBE_MAX_ITEMS = 4294966272
@@ -158,25 +159,32 @@ class Index:
 
 
 def _corpus_ptrs(planes, scales, n_planes: int, count: int, W: int):
-    """(planes_ptr, scales_ptr, mem_kind, keepalive) for numpy arrays or torch tensors."""
+    """(planes_ptr, scales_ptr, mem_kind, keepalive) for numpy arrays or torch tensors.
+    scales may be None (dyadic indexes take no scales)."""
     if isinstance(planes, np.ndarray) or isinstance(scales, np.ndarray):
         p, pp = _host(planes, np.uint64)
+        if p.shape != (n_planes, count, W):
+            raise RbeError(RBE_EINVAL, f"expected planes {(n_planes, count, W)}, got {p.shape}")
+        if scales is None:
+            return pp, None, RBE_MEM_HOST, (p,)
         s, sp = _host(scales, np.float32)
-        if p.shape != (n_planes, count, W) or s.shape != (n_planes, count):
-            raise RbeError(RBE_EINVAL, f"expected planes {(n_planes, count, W)} / scales {(n_planes, count)}, "
-                                       f"got {p.shape} / {s.shape}")
+        if s.shape != (n_planes, count):
+            raise RbeError(RBE_EINVAL, f"expected scales {(n_planes, count)}, got {s.shape}")
         return pp, sp, RBE_MEM_HOST, (p, s)
     import torch
-    if not (isinstance(planes, torch.Tensor) and isinstance(scales, torch.Tensor)):
+    if not isinstance(planes, torch.Tensor) or not (scales is None or isinstance(scales, torch.Tensor)):
         raise RbeError(RBE_EINVAL, "planes/scales must both be numpy arrays or both torch tensors")
-    if planes.dtype not in (torch.int64, torch.uint64) or scales.dtype != torch.float32:
-        raise RbeError(RBE_EINVAL, "planes must be int64/uint64 and scales float32")
-    if tuple(planes.shape) != (n_planes, count, W) or tuple(scales.shape) != (n_planes, count):
-        raise RbeError(RBE_EINVAL, "planes/scales have the wrong shape")
+    if planes.dtype not in (torch.int64, torch.uint64) or tuple(planes.shape) != (n_planes, count, W):
+        raise RbeError(RBE_EINVAL, "planes must be int64/uint64 of shape [P][count][W]")
+    planes = planes.contiguous()
+    kind = RBE_MEM_DEVICE if planes.is_cuda else RBE_MEM_HOST
+    if scales is None:
+        return _vp(planes.data_ptr()), None, kind, (planes,)
+    if scales.dtype != torch.float32 or tuple(scales.shape) != (n_planes, count):
+        raise RbeError(RBE_EINVAL, "scales must be float32 of shape [P][count]")
     if planes.device != scales.device:
         raise RbeError(RBE_EINVAL, "planes and scales live on different devices")
-    planes, scales = planes.contiguous(), scales.contiguous()
-    kind = RBE_MEM_DEVICE if planes.is_cuda else RBE_MEM_HOST
+    scales = scales.contiguous()
     return _vp(planes.data_ptr()), _vp(scales.data_ptr()), kind, (planes, scales)
 
 
@@ -207,7 +215,8 @@ def rbe_finalize(ix: Index, stream=None):
 
 
 def rbe_load_corpus(planes, scales, flags: int = 0, stream=None) -> Index:
-    """planes [P][N][W] uint64, scales [P][N] float32 (numpy = host, torch cuda = device)."""
+    """planes [P][N][W] uint64, scales [P][N] float32 or None for RBE_DYADIC
+    (numpy = host, torch cuda = device)."""
     P, N, W = (int(v) for v in planes.shape)
     pp, sp, kind, keep = _corpus_ptrs(planes, scales, P, N, W)
     out = _vp(None)
@@ -236,11 +245,14 @@ def rbe_search(ix: Index, q_planes, q_scales, k: int, mode: int = RBE_SELECT_EXA
                stream=None):
     """q_planes [Q][Pq][W] uint64, q_scales [Q][Pq] float32 -> (ids int64 [Q][k], scores float32 [Q][k])."""
     qp, qpp = _host(q_planes, np.uint64)
-    qs, qsp = _host(q_scales, np.float32)
-    if qp.ndim != 3 or qs.ndim != 2 or qp.shape[:2] != qs.shape or qp.shape[2] != ix.dim // 64:
-        raise RbeError(RBE_EINVAL, f"expected q_planes [Q][Pq][{ix.dim // 64}] and q_scales [Q][Pq], "
-                                   f"got {qp.shape} / {qs.shape}")
-    Q, Pq = qs.shape
+    if qp.ndim != 3 or qp.shape[2] != ix.dim // 64:
+        raise RbeError(RBE_EINVAL, f"expected q_planes [Q][Pq][{ix.dim // 64}], got {qp.shape}")
+    Q, Pq = qp.shape[:2]
+    qsp = None
+    if q_scales is not None:
+        qs, qsp = _host(q_scales, np.float32)
+        if qs.shape != (Q, Pq):
+            raise RbeError(RBE_EINVAL, f"expected q_scales {(Q, Pq)}, got {qs.shape}")
     ids = np.empty((Q, max(k, 0)), dtype=np.int64)
     scores = np.empty((Q, max(k, 0)), dtype=np.float32)
     _check(load_library().rbe_search(ix.handle, qpp, qsp, Q, Pq, k, mode, group_size_I,
@@ -287,9 +299,11 @@ def rbe_debug_popcounts(ix: Index, q_planes, first_item: int, count: int, stream
 
 def rbe_debug_scores(ix: Index, q_planes, q_scales, first_item: int, count: int, stream=None):
     qp, qpp = _host(q_planes, np.uint64)
-    qs, qsp = _host(q_scales, np.float32)
+    qsp = None
+    if q_scales is not None:
+        qs, qsp = _host(q_scales, np.float32)
     out = np.empty(count, dtype=np.float32)
-    _check(load_library().rbe_debug_scores(ix.handle, qpp, qsp, qs.shape[0], first_item, count,
+    _check(load_library().rbe_debug_scores(ix.handle, qpp, qsp, qp.shape[0], first_item, count,
                                            out.ctypes.data_as(_vp), _stream_ptr(stream)))
     return out
 

@@ -1,27 +1,31 @@
-"""Builds librbe_hip.so (gfx950) in-tree with hipcc."""
+"""Builds librbe_hip.so (gfx950) in-tree with hipcc.
+
+The scan kernel families are compiled once per word count (dim / 64) as separate
+objects, in parallel, and linked with the host code into one shared library.
+"""
 from __future__ import annotations
 
 import os
 import subprocess
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librbe_hip.so")
-SOURCES = [os.path.join(CSRC, "rbe_api.hip")]
-HEADERS = [os.path.join(CSRC, "rbe_kernels.hpp"), os.path.join(CSRC, "rbe_layout.hpp"),
-           os.path.join(ROOT, "include", "rbe.h")]
+HEADERS = [os.path.join(CSRC, h) for h in ("rbe_kernels.hpp", "rbe_layout.hpp", "rbe_internal.hpp",
+                                           "rbe_misc_kernels.hpp")] + [os.path.join(ROOT, "include", "rbe.h")]
+# (source, extra defines, object suffix)
+UNITS = [("rbe_api.hip", [], "api")] + \
+        [("rbe_scan.hip", [f"-DRBE_W={w}"], f"scan_w{w}") for w in (1, 2, 4)] + \
+        [("rbe_group.hip", [f"-DRBE_W={w}"], f"group_w{w}") for w in (1, 2, 4)]
+SOURCES = sorted({os.path.join(CSRC, u[0]) for u in UNITS})
 
-
-def hipcc_command(out: str = LIB) -> list[str]:
-    return [
-        os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"),
-        "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
-        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-Wall", "-Wno-unused-function",
-        "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-        "-o", out, *SOURCES,
-    ]
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument",
+          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
 def is_stale() -> bool:
@@ -33,11 +37,31 @@ def is_stale() -> bool:
 
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile the library.  With force=False, only when missing."""
-    if force or not os.path.exists(LIB):
-        cmd = hipcc_command()
+    if not force and os.path.exists(LIB):
+        return LIB
+    with tempfile.TemporaryDirectory(prefix="rbe_build_") as tmp:
+        procs, objs = [], []
+        for src, defs, tag in UNITS:
+            obj = os.path.join(tmp, tag + ".o")
+            cmd = [HIPCC, *COMMON, *defs, "-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+            objs.append(obj)
+        failed = []
+        for cmd, pr in procs:
+            out, _ = pr.communicate()
+            out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+            if pr.returncode != 0:
+                failed.append((cmd, out))
+            elif verbose and out.strip():
+                print(out, flush=True)
+        if failed:
+            raise RuntimeError("hipcc failed:\n" + "\n".join(" ".join(c) + "\n" + o for c, o in failed))
+        link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
         if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.check_call(cmd)
+            print(" ".join(link), flush=True)
+        subprocess.check_call(link)
     return LIB
 
 

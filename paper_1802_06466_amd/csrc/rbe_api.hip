@@ -1,7 +1,8 @@
 // Host side of the RBE retrieval library: the C ABI declared in include/rbe.h,
 // argument checks, device storage, the refinement plan and kernel launches.
 #include "rbe.h"
-#include "rbe_kernels.hpp"
+#include "rbe_internal.hpp"
+#include "rbe_misc_kernels.hpp"
 
 #include <hip/hip_runtime.h>
 
@@ -51,6 +52,7 @@ constexpr uint32_t kMaxEvents = 2 * RBE_MAX_LEVELS + 2;
 struct rbe_index {
     uint64_t n_items = 0;
     uint32_t dim = 0, W = 0, P = 0, flags = 0;
+    int mode = rbe::kModeScaled;   // scoring mode of the kernels
     int ready = 0;
     bool loaded_any = false;
     int n_cu = 0;
@@ -91,105 +93,35 @@ namespace {
 
 using namespace rbe;
 
-// ---------------------------------------------------------------- kernel dispatch
-using ScanFn = void (*)(const ScanArgs);
-
-template <int W, int P>
-ScanFn scan_fn_p(uint32_t PQ, bool single)
-{
-    switch (PQ) {
-        case 1: return single ? scan_exact<W, P, 1, true> : scan_exact<W, P, 1, false>;
-        case 2: return single ? scan_exact<W, P, 2, true> : scan_exact<W, P, 2, false>;
-        case 3: return single ? scan_exact<W, P, 3, true> : scan_exact<W, P, 3, false>;
-        default: return single ? scan_exact<W, P, 4, true> : scan_exact<W, P, 4, false>;
-    }
-}
-
-template <int W>
-ScanFn scan_fn_w(uint32_t P, uint32_t PQ, bool single)
-{
-    switch (P) {
-        case 1: return scan_fn_p<W, 1>(PQ, single);
-        case 2: return scan_fn_p<W, 2>(PQ, single);
-        case 3: return scan_fn_p<W, 3>(PQ, single);
-        default: return scan_fn_p<W, 4>(PQ, single);
-    }
-}
-
-ScanFn scan_fn(uint32_t W, uint32_t P, uint32_t PQ, bool single)
+// ---------------------------------------------------------------- kernel dispatch (per word count W)
+hipError_t launch_scan_exact(uint32_t W, const KernelSel& k, const ScanArgs& a, uint32_t n_cu, uint32_t per_cu,
+                             hipStream_t st, uint32_t* grid)
 {
     switch (W) {
-        case 1: return scan_fn_w<1>(P, PQ, single);
-        case 2: return scan_fn_w<2>(P, PQ, single);
-        default: return scan_fn_w<4>(P, PQ, single);
+        case 1: return launch_scan_exact_w<1>(k, a, n_cu, per_cu, st, grid);
+        case 2: return launch_scan_exact_w<2>(k, a, n_cu, per_cu, st, grid);
+        default: return launch_scan_exact_w<4>(k, a, n_cu, per_cu, st, grid);
     }
 }
 
-using GroupFn = void (*)(const GroupArgs);
-
-template <int W, int P>
-GroupFn group_fn_p(uint32_t PQ, bool single)
-{
-    switch (PQ) {
-        case 1: return single ? scan_groupmax<W, P, 1, 1> : scan_groupmax<W, P, 1, 4>;
-        case 2: return single ? scan_groupmax<W, P, 2, 1> : scan_groupmax<W, P, 2, 4>;
-        case 3: return single ? scan_groupmax<W, P, 3, 1> : scan_groupmax<W, P, 3, 4>;
-        default: return single ? scan_groupmax<W, P, 4, 1> : scan_groupmax<W, P, 4, 4>;
-    }
-}
-
-template <int W>
-GroupFn group_fn_w(uint32_t P, uint32_t PQ, bool single)
-{
-    switch (P) {
-        case 1: return group_fn_p<W, 1>(PQ, single);
-        case 2: return group_fn_p<W, 2>(PQ, single);
-        case 3: return group_fn_p<W, 3>(PQ, single);
-        default: return group_fn_p<W, 4>(PQ, single);
-    }
-}
-
-GroupFn group_fn(uint32_t W, uint32_t P, uint32_t PQ, bool single)
+hipError_t launch_scan_groupmax(uint32_t W, const KernelSel& k, const GroupArgs& a, uint32_t Q, uint32_t n_cu,
+                                uint32_t per_cu, hipStream_t st, uint32_t* grid)
 {
     switch (W) {
-        case 1: return group_fn_w<1>(P, PQ, single);
-        case 2: return group_fn_w<2>(P, PQ, single);
-        default: return group_fn_w<4>(P, PQ, single);
+        case 1: return launch_scan_groupmax_w<1>(k, a, Q, n_cu, per_cu, st, grid);
+        case 2: return launch_scan_groupmax_w<2>(k, a, Q, n_cu, per_cu, st, grid);
+        default: return launch_scan_groupmax_w<4>(k, a, Q, n_cu, per_cu, st, grid);
     }
 }
 
-template <int W, int P>
-void launch_dense_p(uint32_t PQ, uint32_t grid, hipStream_t st, const rbe_index* ix, uint64_t first, uint64_t count, float* out)
+hipError_t launch_dense_scores(uint32_t W, const KernelSel& k, const char* tiles, const Layout& l,
+                               const uint32_t* qwords, const float* qcoef, uint64_t first, uint64_t count,
+                               float* out, hipStream_t st)
 {
-#define RBE_DENSE(PQV)                                                                             \
-    hipLaunchKernelGGL((dense_scores<W, P, PQV>), dim3(grid), dim3(256), 0, st, ix->d_tiles,       \
-                       ix->layout, ix->d_qwords, ix->d_qcoef, first, count, out)
-    switch (PQ) {
-        case 1: RBE_DENSE(1); break;
-        case 2: RBE_DENSE(2); break;
-        case 3: RBE_DENSE(3); break;
-        default: RBE_DENSE(4); break;
-    }
-#undef RBE_DENSE
-}
-
-template <int W>
-void launch_dense_w(uint32_t P, uint32_t PQ, uint32_t grid, hipStream_t st, const rbe_index* ix, uint64_t first, uint64_t count, float* out)
-{
-    switch (P) {
-        case 1: launch_dense_p<W, 1>(PQ, grid, st, ix, first, count, out); break;
-        case 2: launch_dense_p<W, 2>(PQ, grid, st, ix, first, count, out); break;
-        case 3: launch_dense_p<W, 3>(PQ, grid, st, ix, first, count, out); break;
-        default: launch_dense_p<W, 4>(PQ, grid, st, ix, first, count, out); break;
-    }
-}
-
-void launch_dense(const rbe_index* ix, uint32_t PQ, uint32_t grid, hipStream_t st, uint64_t first, uint64_t count, float* out)
-{
-    switch (ix->W) {
-        case 1: launch_dense_w<1>(ix->P, PQ, grid, st, ix, first, count, out); break;
-        case 2: launch_dense_w<2>(ix->P, PQ, grid, st, ix, first, count, out); break;
-        default: launch_dense_w<4>(ix->P, PQ, grid, st, ix, first, count, out); break;
+    switch (W) {
+        case 1: return launch_dense_scores_w<1>(k, tiles, l, qwords, qcoef, first, count, out, st);
+        case 2: return launch_dense_scores_w<2>(k, tiles, l, qwords, qcoef, first, count, out, st);
+        default: return launch_dense_scores_w<4>(k, tiles, l, qwords, qcoef, first, count, out, st);
     }
 }
 
@@ -243,10 +175,19 @@ int ensure_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
 int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ, hipStream_t st)
 {
     const uint32_t W = ix->W;
+    const bool dyadic = ix->mode != rbe::kModeScaled;
+    if (!dyadic && !q_scales) { set_error("q_scales is NULL"); return RBE_EINVAL; }
     for (uint32_t q = 0; q < Q; ++q) {
         float sum = 0.0f;
         for (uint32_t i = 0; i < PQ; ++i) {
-            const float c = q_scales[(size_t)q * PQ + i];
+            float c = std::ldexp(1.0f, -(int)i);
+            if (q_scales) {
+                c = q_scales[(size_t)q * PQ + i];
+                if (dyadic && c != std::ldexp(1.0f, -(int)i)) {
+                    set_error("dyadic index: q_scales[%u][%u] must be 2^-%u (or pass NULL)", q, i, i);
+                    return RBE_EINVAL;
+                }
+            }
             if (!std::isfinite(c)) { set_error("q_scales[%u][%u] is not finite", q, i); return RBE_EINVAL; }
             for (uint32_t w = 0; w < W; ++w) {
                 const uint64_t word = q_planes[((size_t)q * PQ + i) * W + w];
@@ -319,7 +260,11 @@ static int create_with_ratio(rbe_index** out, uint64_t n_items, uint32_t dim, ui
     ARG_CHECK(dim == 64 || dim == 128 || dim == 256, "dim must be 64, 128 or 256 (got %u)", dim);
     ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES, "n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, n_planes);
     ARG_CHECK(n_items >= 1 && n_items <= RBE_MAX_ITEMS, "n_items must be 1..%llu", (unsigned long long)RBE_MAX_ITEMS);
-    ARG_CHECK((flags & ~(uint32_t)RBE_COSINE) == 0, "unknown flags 0x%x", flags);
+    ARG_CHECK((flags & ~(uint32_t)(RBE_COSINE | RBE_DYADIC)) == 0, "unknown flags 0x%x", flags);
+    if ((flags & RBE_DYADIC) && !rbe::dyadic_supported(dim / 64)) {
+        set_error("RBE_DYADIC is built for dim 64 and 128 only (got %u)", dim);
+        return RBE_EUNSUPPORTED;
+    }
     ARG_CHECK(ratio >= 2 && ratio <= 4096, "sample ratio must be 2..4096 (got %u)", ratio);
 
     rbe_index* ix = new (std::nothrow) rbe_index();
@@ -329,7 +274,8 @@ static int create_with_ratio(rbe_index** out, uint64_t n_items, uint32_t dim, ui
     ix->W = dim / 64;
     ix->P = n_planes;
     ix->flags = flags;
-    ix->geom = rbe::TileGeom{ix->W, ix->P};
+    ix->mode = (flags & RBE_DYADIC) ? ((flags & RBE_COSINE) ? rbe::kModeDyadicNorm : rbe::kModeDyadic) : rbe::kModeScaled;
+    ix->geom = rbe::TileGeom{ix->W, ix->P, (uint32_t)rbe::scale_arrays(ix->mode, (int)ix->P)};
     ix->layout = rbe::make_layout((uint32_t)((n_items + kTileItems - 1) / kTileItems), ratio);
 
     int dev = 0;
@@ -384,7 +330,9 @@ int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uin
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
     if (ix->ready) { set_error("rbe_load_chunk after rbe_finalize"); return RBE_ESTATE; }
-    ARG_CHECK(planes != nullptr && scales != nullptr, "planes/scales is NULL");
+    ARG_CHECK(planes != nullptr, "planes is NULL");
+    const bool want_scales = ix->mode == rbe::kModeScaled;
+    ARG_CHECK(!want_scales || scales != nullptr, "scales is NULL");
     ARG_CHECK(mem_kind == RBE_MEM_HOST || mem_kind == RBE_MEM_DEVICE, "bad mem_kind %d", mem_kind);
     ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item,
               "items [%llu, +%llu) outside the index of %llu items", (unsigned long long)first_item,
@@ -399,9 +347,9 @@ int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uin
     const size_t sbytes = (size_t)ix->P * count * sizeof(float);
     if (mem_kind == RBE_MEM_HOST) {  // stage the chunk on the device, then scatter it into tiles
         hipError_t e = hipMalloc(&tmp_planes, pbytes);
-        if (e == hipSuccess) e = hipMalloc(&tmp_scales, sbytes);
+        if (e == hipSuccess && want_scales) e = hipMalloc(&tmp_scales, sbytes);
         if (e == hipSuccess) e = hipMemcpyAsync(tmp_planes, planes, pbytes, hipMemcpyHostToDevice, st);
-        if (e == hipSuccess) e = hipMemcpyAsync(tmp_scales, scales, sbytes, hipMemcpyHostToDevice, st);
+        if (e == hipSuccess && want_scales) e = hipMemcpyAsync(tmp_scales, scales, sbytes, hipMemcpyHostToDevice, st);
         if (e != hipSuccess) {
             set_error("staging a chunk of %zu bytes failed: %s", pbytes + sbytes, hipGetErrorString(e));
             (void)hipFree(tmp_planes);
@@ -536,49 +484,28 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
 {
     rbe_index* ix = c.ix;
     if (r.end <= r.begin) return RBE_OK;
-    const uint32_t n_units = r.end - r.begin;
+    const KernelSel sel{ix->P, c.PQ, ix->mode, c.Q == 1};
+    const CandList out{ix->d_cand, ix->d_count, c.cap};
+    uint32_t grid = 0;
+    hipError_t e;
     if (c.mode == RBE_SELECT_EXACT) {
         ScanArgs sa;
         sa.tiles = ix->d_tiles; sa.layout = ix->layout; sa.n_items = ix->n_items;
         sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = c.Q;
-        sa.tau = ix->d_tau; sa.cand = ix->d_cand; sa.count = ix->d_count; sa.cap = c.cap;
+        sa.tau = ix->d_tau; sa.out = out;
         sa.p_begin = r.begin; sa.p_end = r.end;
-        const ScanFn fn = scan_fn(ix->W, ix->P, c.PQ, c.Q == 1);
-        uint32_t per_cu = ix->blocks_per_cu;
-        if (per_cu == 0) {  // as many workgroups as are resident at once: one wave of persistent groups
-            int nb = 0;
-            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0));
-            per_cu = (uint32_t)std::max(nb, 1);
-        }
-        const uint32_t grid = std::min<uint32_t>(n_units, (uint32_t)ix->n_cu * per_cu);
-        ix->stats.grid_blocks = std::max(ix->stats.grid_blocks, grid);
-        fn<<<dim3(grid), dim3(kBlock), 0, c.st>>>(sa);
-        HIP_TRY(hipGetLastError());
-        return RBE_OK;
+        e = launch_scan_exact(ix->W, sel, sa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
+    } else {
+        GroupArgs ga;
+        ga.tiles = ix->d_tiles; ga.layout = ix->layout; ga.n_items = ix->n_items;
+        ga.rows_total = (uint32_t)((ix->n_items + kRow - 1) / kRow); ga.I = c.I;
+        ga.qwords = ix->d_qwords; ga.qcoef = ix->d_qcoef; ga.q_begin = 0; ga.nq = 0;
+        ga.tau = ix->d_tau; ga.out = out;
+        ga.v_begin = r.begin; ga.v_end = r.end; ga.stride = r.stride; ga.skip = r.skip;
+        e = launch_scan_groupmax(ix->W, sel, ga, c.Q, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
     }
-    GroupArgs ga;
-    ga.tiles = ix->d_tiles; ga.layout = ix->layout; ga.n_items = ix->n_items;
-    ga.rows_total = (uint32_t)((ix->n_items + kRow - 1) / kRow); ga.I = c.I;
-    ga.qwords = ix->d_qwords; ga.qcoef = ix->d_qcoef;
-    ga.tau = ix->d_tau; ga.cand = ix->d_cand; ga.count = ix->d_count; ga.cap = c.cap;
-    ga.v_begin = r.begin; ga.v_end = r.end; ga.stride = r.stride; ga.skip = r.skip;
-    const bool single = c.Q == 1;
-    const uint32_t QB = single ? 1 : 4;
-    const GroupFn fn = group_fn(ix->W, ix->P, c.PQ, single);
-    uint32_t per_cu = ix->blocks_per_cu;
-    if (per_cu == 0) {
-        int nb = 0;
-        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0));
-        per_cu = (uint32_t)std::max(nb, 1);
-    }
-    const uint32_t grid = std::min<uint32_t>(n_units, (uint32_t)ix->n_cu * per_cu);
+    if (e != hipSuccess) { set_error("scan launch failed: %s", hipGetErrorString(e)); return RBE_EHIP; }
     ix->stats.grid_blocks = std::max(ix->stats.grid_blocks, grid);
-    for (uint32_t q0 = 0; q0 < c.Q; q0 += QB) {   // the corpus range is re-read once per block of QB queries
-        ga.q_begin = q0;
-        ga.nq = std::min<uint32_t>(QB, c.Q - q0);
-        fn<<<dim3(grid), dim3(kBlock), 0, c.st>>>(ga);
-        HIP_TRY(hipGetLastError());
-    }
     return RBE_OK;
 }
 
@@ -628,7 +555,7 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
     if (!ix->ready) { set_error("rbe_search before rbe_finalize"); return RBE_ESTATE; }
-    ARG_CHECK(q_planes && q_scales && ids_out && scores_out, "NULL argument");
+    ARG_CHECK(q_planes && ids_out && scores_out, "NULL argument");
     ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries must be 1..%u (got %u)", RBE_MAX_QUERIES, n_queries);
     ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, q_n_planes);
     ARG_CHECK(k >= 1 && k <= RBE_MAX_K, "k must be 1..%u (got %u)", RBE_MAX_K, k);
@@ -745,7 +672,7 @@ int rbe_debug_popcounts(rbe_index* ix, const uint64_t* q_planes, uint32_t q_n_pl
 int rbe_debug_scores(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t q_n_planes,
                      uint64_t first_item, uint64_t count, float* out, void* hip_stream)
 {
-    ARG_CHECK(ix && q_planes && q_scales && out, "NULL argument");
+    ARG_CHECK(ix && q_planes && out, "NULL argument");
     ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u", RBE_MAX_PLANES);
     ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item, "item range outside the index");
     ARG_CHECK(count <= (1ull << 28), "count too large for a debug dump");
@@ -757,8 +684,8 @@ int rbe_debug_scores(rbe_index* ix, const uint64_t* q_planes, const float* q_sca
     if (rc) return rc;
     float* d_out = nullptr;
     HIP_TRY(hipMalloc(&d_out, (size_t)count * sizeof(float)));
-    launch_dense(ix, q_n_planes, (uint32_t)((count + 255) / 256), st, first_item, count, d_out);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_dense_scores(ix->W, KernelSel{ix->P, q_n_planes, ix->mode, true}, ix->d_tiles, ix->layout,
+                                       ix->d_qwords, ix->d_qcoef, first_item, count, d_out, st);
     if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, (size_t)count * sizeof(float), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(d_out);

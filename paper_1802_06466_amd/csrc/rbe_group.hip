@@ -1,0 +1,187 @@
+// Near-lossless scan kernels (Algorithm 1, queue length 1) for one word count W
+// (compile with -DRBE_W=1, 2 or 4).
+#include "rbe_internal.hpp"
+
+#ifndef RBE_W
+#error "compile with -DRBE_W=1|2|4"
+#endif
+
+namespace rbe {
+
+// ---------------------------------------------------------------- near-lossless local selection
+// Algorithm 1 with a priority queue of length 1: thread y of block x visits
+// items x*256*I + y, + 256, ... (I of them) and forwards only its best one.  In
+// rows of 256 items: "super-block" x is rows [x*I, (x+1)*I), and the group of an
+// item is (super-block, column = id mod 256).  One workgroup takes one
+// super-block per step; wave w scans rows w, w+4, ... keeping, per lane and
+// column, the best (score, row) seen; the four waves' partial winners are merged
+// through LDS and the group winners that reach the threshold are queued like the
+// survivors of the exact scan.
+
+// Physical address of logical row `row` (wave-uniform).
+__device__ __forceinline__ const char* row_tile(const GroupArgs& a, const TileGeom& g, uint32_t row)
+{
+    return a.tiles + (size_t)tile_to_phys(a.layout, row >> 2) * g.tile_bytes();
+}
+
+template <int W, int P, int PQ, int QB, int MODE>
+__global__ __launch_bounds__(kBlock) void scan_groupmax(const GroupArgs a)
+{
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ uint8_t s_q_all[kWavesPerBlock][kStage];
+    __shared__ float s_best[QB][kWavesPerBlock][kItemsPerLane][64];
+    __shared__ uint32_t s_brow[QB][kWavesPerBlock][kItemsPerLane][64];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint64_t* s_keys = s_keys_all[wave];
+    uint8_t* s_q = s_q_all[wave];
+    constexpr int S = scale_arrays(MODE, P);
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const float ninf = -__builtin_inff();
+
+
+    QueryRegs<W, PQ> qr[QB];
+    uint64_t tau[QB];
+    float taus[QB];
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+        const uint32_t q = a.q_begin + (b < (int)a.nq ? b : 0);
+        qr[b] = load_query<W, PQ>(a.qwords, a.qcoef, q);
+        tau[b] = a.tau[q];
+        taus[b] = threshold_score(tau[b]);
+    }
+
+    uint32_t fill = 0;
+    for (uint32_t v = a.v_begin + blockIdx.x; v < a.v_end; v += gridDim.x) {
+        const uint32_t x = (a.skip ? nth_non_multiple(v, a.skip) : v) * a.stride;
+        const uint32_t row0 = x * a.I;
+        const uint32_t n_rows = a.rows_total - row0 < a.I ? a.rows_total - row0 : a.I;
+
+        float best[QB][kItemsPerLane];
+        uint32_t brow[QB][kItemsPerLane];
+#pragma unroll
+        for (int b = 0; b < QB; ++b)
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) { best[b][m] = ninf; brow[b][m] = 0xFFFFFFFFu; }
+
+        uint32_t r = (uint32_t)wave;
+        RowRegs<W, P, S> cur, nxt;
+        if (r < n_rows) load_row<W, P, S>(cur, row_tile(a, geom, row0 + r), (int)((row0 + r) & 3), lane);
+        while (r < n_rows) {
+            const uint32_t rn = r + kWavesPerBlock;
+            if (rn < n_rows) load_row<W, P, S>(nxt, row_tile(a, geom, row0 + rn), (int)((row0 + rn) & 3), lane);
+            const uint64_t row_id = (uint64_t)(row0 + r) * kRow;
+            const bool tail = row_id + kRow > a.n_items;   // only the corpus' last row can hold missing slots
+#pragma unroll
+            for (int b = 0; b < QB; ++b) {
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m) {
+                    float s = score_item<W, P, PQ, MODE>(cur, m, qr[b]) + 0.0f;
+                    if (tail && row_id + lane_item<W>(lane, m) >= a.n_items) s = ninf;
+                    // rows are visited in ascending order: ">" keeps the lowest id among equal scores
+                    if (s > best[b][m]) { best[b][m] = s; brow[b][m] = r; }
+                }
+            }
+            if (rn < n_rows) cur = nxt;
+            r = rn;
+        }
+
+        // merge the four waves' partial winners: wave w finalises item slot m = w of every lane
+#pragma unroll
+        for (int b = 0; b < QB; ++b)
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) { s_best[b][wave][m][lane] = best[b][m]; s_brow[b][wave][m][lane] = brow[b][m]; }
+        __syncthreads();
+        for (int b = 0; b < QB; ++b) {
+            if (b >= (int)a.nq) break;
+            float ws = ninf;
+            uint32_t wr = 0xFFFFFFFFu;
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock; ++w) {
+                const float s = s_best[b][w][wave][lane];
+                const uint32_t rr = s_brow[b][w][wave][lane];
+                if (rr != 0xFFFFFFFFu && (wr == 0xFFFFFFFFu || s > ws || (s == ws && rr < wr))) { ws = s; wr = rr; }
+            }
+            bool ok = (wr != 0xFFFFFFFFu) && (ws >= taus[b]);
+            uint64_t key = 0;
+            if (ok) {
+                const uint64_t id = (uint64_t)(row0 + wr) * kRow + lane_item<W>(lane, wave);
+                key = make_key(ws, (uint32_t)id);
+                ok = key >= tau[b];
+            }
+            fill = stage_append<false>(ok, key, a.q_begin + b, s_keys, s_q, fill, a.out, lane);
+        }
+        __syncthreads();
+    }
+    if (fill) stage_flush<false>(s_keys, s_q, fill, a.out, lane);
+}
+
+// ---------------------------------------------------------------- dispatch
+namespace {
+
+using GroupFn = void (*)(const GroupArgs);
+
+template <int W, int P, int PQ>
+GroupFn group_fn_m(int mode, bool single)
+{
+    if (mode == kModeScaled) return single ? scan_groupmax<W, P, PQ, 1, kModeScaled> : scan_groupmax<W, P, PQ, 4, kModeScaled>;
+    if constexpr (dyadic_supported(W)) {
+        if (mode == kModeDyadicNorm)
+            return single ? scan_groupmax<W, P, PQ, 1, kModeDyadicNorm> : scan_groupmax<W, P, PQ, 4, kModeDyadicNorm>;
+        if (mode == kModeDyadic)
+            return single ? scan_groupmax<W, P, PQ, 1, kModeDyadic> : scan_groupmax<W, P, PQ, 4, kModeDyadic>;
+    }
+    return nullptr;
+}
+
+#define RBE_SWITCH_PQ(FN, P, ...)                       \
+    switch (k.PQ) {                                     \
+        case 1: return FN<RBE_W, P, 1>(__VA_ARGS__);    \
+        case 2: return FN<RBE_W, P, 2>(__VA_ARGS__);    \
+        case 3: return FN<RBE_W, P, 3>(__VA_ARGS__);    \
+        case 4: return FN<RBE_W, P, 4>(__VA_ARGS__);    \
+        default: return nullptr;                        \
+    }
+
+GroupFn group_fn(const KernelSel& k)
+{
+    switch (k.P) {
+        case 1: RBE_SWITCH_PQ(group_fn_m, 1, k.mode, k.single)
+        case 2: RBE_SWITCH_PQ(group_fn_m, 2, k.mode, k.single)
+        case 3: RBE_SWITCH_PQ(group_fn_m, 3, k.mode, k.single)
+        case 4: RBE_SWITCH_PQ(group_fn_m, 4, k.mode, k.single)
+        default: return nullptr;
+    }
+}
+
+}  // namespace
+
+template <>
+hipError_t launch_scan_groupmax_w<RBE_W>(const KernelSel& k, GroupArgs a, uint32_t n_queries, uint32_t n_cu,
+                                         uint32_t per_cu, hipStream_t st, uint32_t* grid_out)
+{
+    const GroupFn fn = group_fn(k);
+    if (!fn) return hipErrorInvalidValue;
+    if (a.v_end <= a.v_begin) return hipSuccess;
+    if (per_cu == 0) {
+        int nb = 0;
+        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0);
+        if (e != hipSuccess) return e;
+        per_cu = (uint32_t)(nb > 0 ? nb : 1);
+    }
+    const uint32_t units = a.v_end - a.v_begin;
+    const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;
+    if (grid_out) *grid_out = grid;
+    const uint32_t QB = k.single ? 1 : 4;
+    for (uint32_t q0 = 0; q0 < n_queries; q0 += QB) {   // the range is re-read once per block of QB queries
+        a.q_begin = q0;
+        a.nq = n_queries - q0 < QB ? n_queries - q0 : QB;
+        fn<<<dim3(grid), dim3(kBlock), 0, st>>>(a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace rbe

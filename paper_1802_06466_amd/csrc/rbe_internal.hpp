@@ -1,0 +1,49 @@
+// Launchers of the heavy kernel families.  Each family is compiled once per word
+// count W in its own translation unit (rbe_scan.hip / rbe_group.hip with
+// -DRBE_W=1|2|4) so that the builds run in parallel; rbe_api.hip only sees these
+// declarations.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "rbe_kernels.hpp"
+
+namespace rbe {
+
+struct KernelSel {
+    uint32_t P, PQ;   // corpus planes, query planes
+    int mode;         // kModeScaled / kModeDyadicNorm / kModeDyadic
+    bool single;      // one query per call
+};
+
+// Grid = min(units, n_cu * per_cu); per_cu == 0 means "as many workgroups as are
+// resident at once" (from the kernel's occupancy).  *grid_out receives the grid.
+template <int W>
+hipError_t launch_scan_exact_w(const KernelSel& k, const ScanArgs& a, uint32_t n_cu, uint32_t per_cu,
+                               hipStream_t st, uint32_t* grid_out);
+
+// One launch per block of 4 queries (1 if single).
+template <int W>
+hipError_t launch_scan_groupmax_w(const KernelSel& k, GroupArgs a, uint32_t n_queries, uint32_t n_cu,
+                                  uint32_t per_cu, hipStream_t st, uint32_t* grid_out);
+
+template <int W>
+hipError_t launch_dense_scores_w(const KernelSel& k, const char* tiles, const Layout& l, const uint32_t* qwords,
+                                 const float* qcoef, uint64_t first, uint64_t count, float* out, hipStream_t st);
+
+#define RBE_DECLARE_W(Wv)                                                                                         \
+    template <> hipError_t launch_scan_exact_w<Wv>(const KernelSel&, const ScanArgs&, uint32_t, uint32_t,         \
+                                                   hipStream_t, uint32_t*);                                       \
+    template <> hipError_t launch_scan_groupmax_w<Wv>(const KernelSel&, GroupArgs, uint32_t, uint32_t, uint32_t,  \
+                                                      hipStream_t, uint32_t*);                                    \
+    template <> hipError_t launch_dense_scores_w<Wv>(const KernelSel&, const char*, const Layout&,                \
+                                                     const uint32_t*, const float*, uint64_t, uint64_t, float*,   \
+                                                     hipStream_t);
+RBE_DECLARE_W(1)
+RBE_DECLARE_W(2)
+RBE_DECLARE_W(4)
+#undef RBE_DECLARE_W
+
+// Dyadic modes are built for d = 64 and d = 128.
+constexpr bool dyadic_supported(uint32_t W) { return W <= 2; }
+
+}  // namespace rbe

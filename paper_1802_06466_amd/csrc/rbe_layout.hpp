@@ -5,7 +5,10 @@
 // block (the grouping of Sec. 6.1, applied per tile so that one workgroup step
 // reads a single contiguous region):
 //
-//     [plane 0: 1024 x W words][plane 1] ... [plane P-1][scales 0: 1024 floats] ... [scales P-1]
+//     [plane 0: 1024 x W words][plane 1] ... [plane P-1][scales 0: 1024 floats] ... [scales S-1]
+//
+// with S = P scale arrays in the general mode, S = 1 (one inverse norm per item)
+// or S = 0 in the dyadic modes, where the plane weights are the constants 2^-j.
 //
 // Tile ORDER in memory is "nested-sample major".  With ratio r, the class of
 // logical tile t is the largest c <= L with r^c | t (tile 0 has class L).
@@ -76,12 +79,20 @@ RBE_HD uint32_t phys_to_tile(const Layout& l, uint32_t p)
     return nth_non_multiple(p - l.n_ge[c + 1], l.ratio) * l.pow_r[c];
 }
 
+// Scoring modes (compile-time parameter of the kernels).
+enum : int {
+    kModeScaled = 0,      // per-item fp32 scale per plane, fp32 query scales
+    kModeDyadicNorm = 1,  // plane weights 2^-j on both sides (integer shift-adds), one fp32 scale per item
+    kModeDyadic = 2       // plane weights 2^-j on both sides, no per-item scale: scores are exact
+};
+RBE_HD constexpr int scale_arrays(int mode, int P) { return mode == kModeScaled ? P : (mode == kModeDyadicNorm ? 1 : 0); }
+
 // Byte geometry of a tile.
 struct TileGeom {
-    uint32_t W, P;
+    uint32_t W, P, S;   // words per plane, planes, scale arrays
     RBE_HD size_t plane_bytes() const { return (size_t)kTileItems * W * 8; }
     RBE_HD size_t scales_offset() const { return plane_bytes() * P; }
-    RBE_HD size_t tile_bytes() const { return scales_offset() + (size_t)kTileItems * 4 * P; }
+    RBE_HD size_t tile_bytes() const { return scales_offset() + (size_t)kTileItems * 4 * S; }
 };
 
 }  // namespace rbe

@@ -1,0 +1,347 @@
+// Small kernels of the RBE retrieval library: global selection, state reset, load
+// scatter, cosine fold, calibration copy and dense test dumps.
+#pragma once
+#include "rbe_kernels.hpp"
+
+namespace rbe {
+
+// ---------------------------------------------------------------- selection
+constexpr int kSelBlock = 1024;
+constexpr int kSelMaxK = 4096;
+constexpr int kSelBins = 2048;      // 11-bit digits
+constexpr int kSelBound = 1024;     // boundary keys finished by an LDS sort
+constexpr int kSelUnroll = 8;
+
+enum : uint32_t { kStatusOverflow = 1u };
+
+struct SelectArgs {
+    uint64_t* cand;      // [Q][cap], in/out: on return the best min(n,k) keys at the front
+    uint32_t* count;     // [Q] in: appended so far; out: number kept
+    uint64_t* tau;       // [Q] out: k-th best key once at least k candidates exist
+    uint32_t cap;
+    uint32_t k;
+    uint32_t* status;    // bit 0 set if any query's count exceeded cap
+    uint32_t* count_seen;  // [Q] out: candidate count before selection (for statistics)
+    int final_pass;
+    int64_t* ids_out;    // [Q][k]   (final pass; sorted)
+    float* scores_out;   // [Q][k]
+};
+
+// Inclusive prefix sum over the 1024 threads of the select workgroup.
+__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* s_wave /*[16]*/)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t add = 0;
+    for (int w = 0; w < wave; ++w) add += s_wave[w];
+    __syncthreads();
+    return incl + add;
+}
+
+// Bitonic sort of `pow2` keys in LDS, descending.  All threads of the workgroup call it.
+__device__ __forceinline__ void bitonic_desc(uint64_t* keys, uint32_t pow2)
+{
+    for (uint32_t size = 2; size <= pow2; size <<= 1) {
+        for (uint32_t st = size >> 1; st > 0; st >>= 1) {
+            for (uint32_t i = threadIdx.x; i < pow2 / 2; i += kSelBlock) {
+                const uint32_t lo = 2 * i - (i & (st - 1));
+                const uint32_t hi = lo + st;
+                const bool desc = ((lo & size) == 0);
+                const uint64_t x = keys[lo], y = keys[hi];
+                if ((x < y) == desc) { keys[lo] = y; keys[hi] = x; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// One workgroup per query.
+__global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
+{
+    __shared__ uint64_t skeys[kSelMaxK];    // keys known to be kept
+    __shared__ uint64_t sbound[kSelBound];  // keys of the boundary bin
+    __shared__ uint32_t hist[kSelBins];
+    __shared__ uint32_t s_wave[16];
+    __shared__ uint64_t s_and, s_or;
+    __shared__ uint32_t s_digit, s_remaining, s_binpop, s_fill_keep, s_fill_bound;
+
+    const uint32_t q = blockIdx.x;
+    const uint32_t tid = threadIdx.x;
+    uint64_t* keys = a.cand + (size_t)q * a.cap;
+    const uint32_t appended = a.count[q];
+    const uint32_t n = appended < a.cap ? appended : a.cap;
+    const uint32_t k = a.k;
+    if (tid == 0) {
+        a.count_seen[q] = appended;
+        if (appended > a.cap) atomicOr(a.status, kStatusOverflow);
+    }
+
+    uint32_t m;  // number of keys kept
+    if (n <= k) {
+        // everything is kept; nothing to prune.  Only the final round needs them sorted.
+        m = n;
+        if (!a.final_pass) return;
+        for (uint32_t i = tid; i < n; i += kSelBlock) skeys[i] = keys[i];
+    } else {
+        m = k;
+        // ---- bits that differ between any two keys
+        uint64_t vand = ~0ull, vor = 0;
+        for (uint32_t base = 0; base < n; base += kSelBlock * kSelUnroll) {
+            uint64_t kk[kSelUnroll];
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const uint32_t i = base + u * kSelBlock + tid;
+                kk[u] = i < n ? keys[i] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const uint32_t i = base + u * kSelBlock + tid;
+                if (i < n) { vand &= kk[u]; vor |= kk[u]; }
+            }
+        }
+        if (tid == 0) { s_and = ~0ull; s_or = 0; }
+        __syncthreads();
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) {
+            vand &= __shfl_xor(vand, d);
+            vor |= __shfl_xor(vor, d);
+        }
+        if ((tid & 63) == 0) { atomicAnd((unsigned long long*)&s_and, (unsigned long long)vand); atomicOr((unsigned long long*)&s_or, (unsigned long long)vor); }
+        __syncthreads();
+        const uint64_t diff = s_and ^ s_or;       // non-zero: the n > k >= 1 keys are distinct
+        int pos = 64 - __clzll((long long)diff);   // low `pos` bits are undetermined
+        uint64_t mask = pos >= 64 ? 0ull : ~((1ull << pos) - 1ull);
+        uint64_t prefix = s_or & mask;
+        uint32_t remaining = k;                    // rank of the wanted key among keys matching the prefix
+
+        // ---- radix descent, 11 bits per round, until the boundary bin fits an LDS sort
+        for (;;) {
+            const int bits = pos < 11 ? pos : 11;
+            const int shift = pos - bits;
+            const uint32_t dmask = (1u << bits) - 1u;
+            for (uint32_t i = tid; i < kSelBins; i += kSelBlock) hist[i] = 0;
+            __syncthreads();
+            for (uint32_t base = 0; base < n; base += kSelBlock * kSelUnroll) {
+                uint64_t kk[kSelUnroll];
+#pragma unroll
+                for (int u = 0; u < kSelUnroll; ++u) {
+                    const uint32_t i = base + u * kSelBlock + tid;
+                    kk[u] = i < n ? keys[i] : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < kSelUnroll; ++u) {
+                    const uint32_t i = base + u * kSelBlock + tid;
+                    if (i < n && (kk[u] & mask) == prefix) atomicAdd(&hist[(uint32_t)(kk[u] >> shift) & dmask], 1u);
+                }
+            }
+            __syncthreads();
+            // thread t owns digits 2047-2t and 2046-2t (descending order)
+            const uint32_t d1 = kSelBins - 1 - 2 * tid, d0 = d1 - 1;
+            const uint32_t c1 = hist[d1], c0 = hist[d0];
+            const uint32_t incl = block_scan_incl(c1 + c0, s_wave);
+            const uint32_t before = incl - (c1 + c0);
+            if (before < remaining && incl >= remaining) {
+                if (before + c1 >= remaining) { s_digit = d1; s_remaining = remaining - before; s_binpop = c1; }
+                else { s_digit = d0; s_remaining = remaining - before - c1; s_binpop = c0; }
+            }
+            __syncthreads();
+            prefix |= (uint64_t)s_digit << shift;
+            mask |= (uint64_t)dmask << shift;
+            remaining = s_remaining;
+            pos = shift;
+            const uint32_t binpop = s_binpop;
+            __syncthreads();
+            if (binpop <= (uint32_t)kSelBound || pos == 0) break;
+        }
+
+        // ---- gather: keys above the boundary bin are kept; the bin itself is sorted in LDS
+        if (tid == 0) { s_fill_keep = 0; s_fill_bound = 0; }
+        __syncthreads();
+        for (uint32_t base = 0; base < n; base += kSelBlock * kSelUnroll) {
+            uint64_t kk[kSelUnroll];
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const uint32_t i = base + u * kSelBlock + tid;
+                kk[u] = i < n ? keys[i] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const uint32_t i = base + u * kSelBlock + tid;
+                if (i < n) {
+                    const uint64_t hi = kk[u] & mask;
+                    if (hi > prefix) {
+                        const uint32_t o = atomicAdd(&s_fill_keep, 1u);
+                        if (o < (uint32_t)kSelMaxK) skeys[o] = kk[u];
+                    } else if (hi == prefix) {
+                        const uint32_t o = atomicAdd(&s_fill_bound, 1u);
+                        if (o < (uint32_t)kSelBound) sbound[o] = kk[u];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t n_keep = k - remaining;      // == s_fill_keep
+        const uint32_t n_bound = s_fill_bound < (uint32_t)kSelBound ? s_fill_bound : (uint32_t)kSelBound;
+        uint32_t bp2 = 1;
+        while (bp2 < n_bound) bp2 <<= 1;
+        for (uint32_t i = n_bound + tid; i < bp2; i += kSelBlock) sbound[i] = 0;
+        __syncthreads();
+        bitonic_desc(sbound, bp2);
+        const uint32_t take = remaining < n_bound ? remaining : n_bound;   // == remaining (keys are distinct)
+        for (uint32_t i = tid; i < take; i += kSelBlock) skeys[n_keep + i] = sbound[i];
+        __syncthreads();
+        if (tid == 0 && take > 0) a.tau[q] = sbound[take - 1];   // k-th best of everything seen so far
+    }
+    __syncthreads();
+
+    if (!a.final_pass) {
+        for (uint32_t i = tid; i < m; i += kSelBlock) keys[i] = skeys[i];
+        if (tid == 0) a.count[q] = m;
+        return;
+    }
+
+    // ---- final round: sort the kept keys and emit ids and scores
+    uint32_t pow2 = 1;
+    while (pow2 < m) pow2 <<= 1;
+    for (uint32_t i = m + tid; i < pow2; i += kSelBlock) skeys[i] = 0;
+    __syncthreads();
+    bitonic_desc(skeys, pow2);
+    if (tid == 0) a.count[q] = m;
+    for (uint32_t i = tid; i < k; i += kSelBlock) {
+        int64_t id = -1;
+        float sc = -__builtin_inff();
+        if (i < m) {
+            const uint64_t key = skeys[i];
+            keys[i] = key;
+            id = (int64_t)(uint32_t)(~(uint32_t)key);
+            sc = ordered_to_score((uint32_t)(key >> 32));
+        }
+        a.ids_out[(size_t)q * k + i] = id;
+        a.scores_out[(size_t)q * k + i] = sc;
+    }
+}
+
+__global__ void init_state(uint32_t* count, uint64_t* tau, uint32_t* status, uint32_t n_queries)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_queries) { count[i] = 0; tau[i] = 0; }
+    if (i == 0) *status = 0;
+}
+
+// ---------------------------------------------------------------- load path
+// Address of item z's plane-j words / scale inside the tiled layout.
+__device__ __forceinline__ char* item_tile(char* tiles, const Layout& l, const TileGeom& g, uint64_t z)
+{
+    return tiles + (size_t)tile_to_phys(l, (uint32_t)(z / kTileItems)) * g.tile_bytes();
+}
+
+// Caller's chunk ([P][count][W] words, [P][count] scales, items first..first+count) -> tiles.
+// One thread per item.
+__global__ void scatter_chunk(char* __restrict__ tiles, const Layout l, const TileGeom g,
+                              const uint64_t* __restrict__ planes, const float* __restrict__ scales,
+                              uint64_t first, uint64_t count)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const uint64_t z = first + t;
+    char* tile = item_tile(tiles, l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    for (uint32_t j = 0; j < g.P; ++j) {
+        uint64_t* dst = reinterpret_cast<uint64_t*>(tile + j * g.plane_bytes()) + (size_t)o * g.W;
+        for (uint32_t w = 0; w < g.W; ++w) dst[w] = planes[((size_t)j * count + t) * g.W + w];
+    }
+    if (g.S == g.P)   // general mode: one scale per plane.  Dyadic modes take no scales from the caller.
+        for (uint32_t j = 0; j < g.P; ++j)
+            reinterpret_cast<float*>(tile + g.scales_offset())[j * kTileItems + o] = scales[(size_t)j * count + t];
+}
+
+// ---------------------------------------------------------------- calibration
+// Plain 16-byte-per-lane copy of a known size: the yardstick that hardware
+// counter readings of the scan are scaled by.
+__global__ __launch_bounds__(256) void calib_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n_vec)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------- dense helpers (tests, cosine fold)
+__global__ void dense_popcounts(const char* __restrict__ tiles, const Layout l, const TileGeom g,
+                                const uint64_t* __restrict__ qplanes, uint32_t PQ,
+                                uint64_t first, uint64_t count, int32_t* __restrict__ out)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const uint64_t z = first + t;
+    const char* tile = item_tile(const_cast<char*>(tiles), l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    for (uint32_t j = 0; j < g.P; ++j) {
+        const uint64_t* kw = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)o * g.W;
+        for (uint32_t i = 0; i < PQ; ++i) {
+            int32_t pc = 0;
+            for (uint32_t w = 0; w < g.W; ++w) pc += __popcll(kw[w] ^ qplanes[i * g.W + w]);
+            out[(t * g.P + j) * PQ + i] = pc;
+        }
+    }
+}
+
+// out[j][t] = effective scale of plane j of item first + t
+__global__ void gather_scales(const char* __restrict__ tiles, const Layout l, const TileGeom g,
+                              uint64_t first, uint64_t count, float* __restrict__ out)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const uint64_t z = first + t;
+    const char* tile = item_tile(const_cast<char*>(tiles), l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    const float* sc = reinterpret_cast<const float*>(tile + g.scales_offset());
+    for (uint32_t j = 0; j < g.P; ++j) {
+        float v;
+        if (g.S == g.P) v = sc[j * kTileItems + o];
+        else v = (g.S == 1 ? sc[o] : 1.0f) / (float)(1u << j);   // dyadic: 2^-j times the item's scale
+        out[(size_t)j * count + t] = v;
+    }
+}
+
+// Cosine fold.  With a_j the plane weights of an item (its stored scales, or 2^-j in
+// the dyadic mode), ||sum_j a_j b_j||^2 = dim * sum_j a_j^2 + 2 sum_{j<j'} a_j a_j' (dim - 2 popcount(K_j ^ K_j')).
+// General mode: every scale of the item is divided by that norm.  Dyadic mode with one
+// scale array: the inverse norm is stored there (the keyword magnitude that Sec. 5.1
+// precomputes and keeps with the embedding).  One thread per physical slot; in the
+// general mode slots never loaded have scale 0 and are left alone.
+__global__ void fold_cosine(char* __restrict__ tiles, const TileGeom g, uint64_t n_slots)
+{
+    const uint64_t s = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n_slots) return;
+    char* tile = tiles + (size_t)(s / kTileItems) * g.tile_bytes();
+    const uint32_t o = (uint32_t)(s % kTileItems);
+    float* sc = reinterpret_cast<float*>(tile + g.scales_offset());
+    const bool dyadic = g.S != g.P;
+    const double dim = 64.0 * g.W;
+    double a[4];
+    for (uint32_t j = 0; j < g.P; ++j) a[j] = dyadic ? 1.0 / (double)(1u << j) : (double)sc[j * kTileItems + o];
+    double n2 = 0.0;
+    for (uint32_t j = 0; j < g.P; ++j) {
+        n2 += dim * a[j] * a[j];
+        const uint64_t* kj = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)o * g.W;
+        for (uint32_t jj = j + 1; jj < g.P; ++jj) {
+            const uint64_t* kk = reinterpret_cast<const uint64_t*>(tile + jj * g.plane_bytes()) + (size_t)o * g.W;
+            int pc = 0;
+            for (uint32_t w = 0; w < g.W; ++w) pc += __popcll(kj[w] ^ kk[w]);
+            n2 += 2.0 * a[j] * a[jj] * (dim - 2.0 * pc);
+        }
+    }
+    if (n2 > 0.0) {
+        const double nrm = sqrt(n2);
+        if (dyadic) sc[o] = (float)(1.0 / nrm);
+        else for (uint32_t j = 0; j < g.P; ++j) sc[j * kTileItems + o] = (float)(a[j] / nrm);
+    }
+}
+
+}  // namespace rbe

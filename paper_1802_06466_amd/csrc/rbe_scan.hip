@@ -1,0 +1,222 @@
+// Exact-mode scan kernels and the dense score dump, for one word count W
+// (compile with -DRBE_W=1, 2 or 4).
+#include "rbe_internal.hpp"
+
+#ifndef RBE_W
+#error "compile with -DRBE_W=1|2|4"
+#endif
+
+namespace rbe {
+
+// Scores the lane's 4 items of `cur` against one query and queues the survivors.
+template <int W, int P, int PQ, bool SINGLE, int MODE>
+__device__ __forceinline__ uint32_t score_and_stage(const RowRegs<W, P, scale_arrays(MODE, P)>& cur, const QueryRegs<W, PQ>& qr, uint64_t tau,
+                                                    float taus, uint32_t q, uint32_t p, int wave, int lane,
+                                                    uint64_t* s_keys, uint8_t* s_q, uint32_t fill, const ScanArgs& a)
+{
+    float s[kItemsPerLane];
+    bool any = false;
+#pragma unroll
+    for (int m = 0; m < kItemsPerLane; ++m) {
+        s[m] = score_item<W, P, PQ, MODE>(cur, m, qr);
+        any |= (s[m] >= taus);
+    }
+    if (__ballot(any)) {   // rare: at least one lane of the wave has a survivor
+        const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            const uint64_t id = row_id + lane_item<W>(lane, m);
+            bool ok = (s[m] >= taus) && (id < a.n_items);
+            uint64_t key = 0;
+            if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
+            fill = stage_append<SINGLE>(ok, key, q, s_keys, s_q, fill, a.out, lane);
+        }
+    }
+    return fill;
+}
+
+// Streaming exhaustive match + local selection over physical tiles
+// [p_begin, p_end).  Persistent workgroups: workgroup b takes tiles p_begin + b,
+// + grid, ....
+// SINGLE (one query, HBM-bound): the query lives in SGPRs and the next tile's loads
+// are issued before the current one is scored (register double buffering).
+// Batch (VALU-bound): one tile in registers, all queries applied to it; the next
+// query's words and coefficients are fetched by scalar loads while the current
+// one is being applied, and memory latency is covered by the other resident waves.
+template <int W, int P, int PQ, bool SINGLE, int MODE>
+__global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
+{
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ uint8_t s_q_all[SINGLE ? 1 : kWavesPerBlock][SINGLE ? 1 : kStage];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    uint8_t* s_q = SINGLE ? s_q_all[0] : s_q_all[wave];
+    const uint32_t G = gridDim.x;
+    constexpr int S = scale_arrays(MODE, P);
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    uint32_t fill = 0;
+
+    if (SINGLE) {
+        const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+        const uint64_t tau0 = a.tau[0];
+        const float taus0 = threshold_score(tau0);
+        RowRegs<W, P, S> cur, nxt;
+        load_row<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+        for (;;) {
+            const uint32_t pn = p + G;
+            const bool has_next = pn < a.p_end;
+            if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            fill = score_and_stage<W, P, PQ, SINGLE, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, s_q, fill, a);
+            if (!has_next) break;
+            cur = nxt;
+            p = pn;
+        }
+    } else {
+        const uint32_t nq = a.n_queries;
+        for (; p < a.p_end; p += G) {
+            RowRegs<W, P, S> cur;
+            load_row<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+            uint64_t tau_n = a.tau[0];
+            for (uint32_t q = 0; q < nq; ++q) {
+                const QueryRegs<W, PQ> qr = qn;
+                const uint64_t tau = tau_n;
+                if (q + 1 < nq) {
+                    qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
+                    tau_n = a.tau[q + 1];
+                }
+                fill = score_and_stage<W, P, PQ, SINGLE, MODE>(cur, qr, tau, threshold_score(tau), q, p, wave, lane,
+                                                         s_keys, s_q, fill, a);
+            }
+        }
+    }
+    if (fill) stage_flush<SINGLE>(s_keys, s_q, fill, a.out, lane);
+}
+
+
+// fp32 score of one query for items first .. first+count (test hook); same arithmetic as the scan.
+template <int W, int P, int PQ, int MODE>
+__global__ void dense_scores(const char* __restrict__ tiles, const Layout l,
+                             const uint32_t* __restrict__ qwords, const float* __restrict__ qcoef,
+                             uint64_t first, uint64_t count, float* __restrict__ out)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const uint64_t z = first + t;
+    constexpr int S = scale_arrays(MODE, P);
+    const TileGeom g{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const char* tile = tiles + (size_t)tile_to_phys(l, (uint32_t)(z / kTileItems)) * g.tile_bytes();
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    const QueryRegs<W, PQ> q = load_query<W, PQ>(qwords, qcoef, 0);
+    RowRegs<W, P, S> r;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const uint32_t* pw = reinterpret_cast<const uint32_t*>(tile + j * g.plane_bytes()) + (size_t)o * 2 * W;
+#pragma unroll
+        for (int h = 0; h < 2 * W; ++h) r.w[j][0][h] = pw[h];
+    }
+#pragma unroll
+    for (int j = 0; j < S; ++j) r.a[j][0] = reinterpret_cast<const float*>(tile + g.scales_offset())[j * kTileItems + o];
+    out[t] = score_item<W, P, PQ, MODE>(r, 0, q);
+}
+
+// ---------------------------------------------------------------- dispatch
+namespace {
+
+using ScanFn = void (*)(const ScanArgs);
+using DenseFn = void (*)(const char*, const Layout, const uint32_t*, const float*, uint64_t, uint64_t, float*);
+
+template <int W, int P, int PQ>
+ScanFn scan_fn_m(int mode, bool single)
+{
+    if (mode == kModeScaled) return single ? scan_exact<W, P, PQ, true, kModeScaled> : scan_exact<W, P, PQ, false, kModeScaled>;
+    if constexpr (dyadic_supported(W)) {
+        if (mode == kModeDyadicNorm)
+            return single ? scan_exact<W, P, PQ, true, kModeDyadicNorm> : scan_exact<W, P, PQ, false, kModeDyadicNorm>;
+        if (mode == kModeDyadic)
+            return single ? scan_exact<W, P, PQ, true, kModeDyadic> : scan_exact<W, P, PQ, false, kModeDyadic>;
+    }
+    return nullptr;
+}
+
+template <int W, int P, int PQ>
+DenseFn dense_fn_m(int mode)
+{
+    if (mode == kModeScaled) return dense_scores<W, P, PQ, kModeScaled>;
+    if constexpr (dyadic_supported(W)) {
+        if (mode == kModeDyadicNorm) return dense_scores<W, P, PQ, kModeDyadicNorm>;
+        if (mode == kModeDyadic) return dense_scores<W, P, PQ, kModeDyadic>;
+    }
+    return nullptr;
+}
+
+#define RBE_SWITCH_PQ(FN, P, ...)                       \
+    switch (k.PQ) {                                     \
+        case 1: return FN<RBE_W, P, 1>(__VA_ARGS__);    \
+        case 2: return FN<RBE_W, P, 2>(__VA_ARGS__);    \
+        case 3: return FN<RBE_W, P, 3>(__VA_ARGS__);    \
+        case 4: return FN<RBE_W, P, 4>(__VA_ARGS__);    \
+        default: return nullptr;                        \
+    }
+
+ScanFn scan_fn(const KernelSel& k)
+{
+    switch (k.P) {
+        case 1: RBE_SWITCH_PQ(scan_fn_m, 1, k.mode, k.single)
+        case 2: RBE_SWITCH_PQ(scan_fn_m, 2, k.mode, k.single)
+        case 3: RBE_SWITCH_PQ(scan_fn_m, 3, k.mode, k.single)
+        case 4: RBE_SWITCH_PQ(scan_fn_m, 4, k.mode, k.single)
+        default: return nullptr;
+    }
+}
+
+DenseFn dense_fn(const KernelSel& k)
+{
+    switch (k.P) {
+        case 1: RBE_SWITCH_PQ(dense_fn_m, 1, k.mode)
+        case 2: RBE_SWITCH_PQ(dense_fn_m, 2, k.mode)
+        case 3: RBE_SWITCH_PQ(dense_fn_m, 3, k.mode)
+        case 4: RBE_SWITCH_PQ(dense_fn_m, 4, k.mode)
+        default: return nullptr;
+    }
+}
+
+}  // namespace
+
+template <>
+hipError_t launch_scan_exact_w<RBE_W>(const KernelSel& k, const ScanArgs& a, uint32_t n_cu, uint32_t per_cu,
+                                      hipStream_t st, uint32_t* grid_out)
+{
+    const ScanFn fn = scan_fn(k);
+    if (!fn) return hipErrorInvalidValue;
+    if (a.p_end <= a.p_begin) return hipSuccess;
+    if (per_cu == 0) {
+        int nb = 0;
+        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0);
+        if (e != hipSuccess) return e;
+        per_cu = (uint32_t)(nb > 0 ? nb : 1);
+    }
+    const uint32_t units = a.p_end - a.p_begin;
+    const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;
+    if (grid_out) *grid_out = grid;
+    fn<<<dim3(grid), dim3(kBlock), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+template <>
+hipError_t launch_dense_scores_w<RBE_W>(const KernelSel& k, const char* tiles, const Layout& l, const uint32_t* qwords,
+                                        const float* qcoef, uint64_t first, uint64_t count, float* out, hipStream_t st)
+{
+    const DenseFn fn = dense_fn(k);
+    if (!fn) return hipErrorInvalidValue;
+    fn<<<dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st>>>(tiles, l, qwords, qcoef, first, count, out);
+    return hipGetLastError();
+}
+
+}  // namespace rbe

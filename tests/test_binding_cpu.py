@@ -54,6 +54,9 @@ def test_constants_match_header():
     for name in ("RBE_MAX_PLANES", "RBE_MAX_QUERIES", "RBE_MAX_K", "RBE_MAX_ITEMS", "RBE_MAX_LEVELS"):
         m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
         assert m and int(m.group(1)) == getattr(rbe, name), name
+    for name in ("RBE_COSINE", "RBE_DYADIC"):
+        m = re.search(r"%s\s*=\s*1u\s*<<\s*(\d+)" % name, text)
+        assert m and (1 << int(m.group(1))) == getattr(rbe, name), name
     assert ctypes.sizeof(rbe.rbe_search_stats) == 16 + 8 * 8 * 2 + 4 * 8 * 2 + 8
 
 

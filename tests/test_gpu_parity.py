@@ -393,3 +393,79 @@ def test_nearlossless_recall_tracks_appendix_a():
     expect = oracle.expected_recall(k, N, I)
     assert abs(rec - expect) < 4 * np.sqrt(expect * (1 - expect) / (k * Q)) + 2e-3, (rec, expect)
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ the paper's own representation (RBE_DYADIC)
+def dyadic_weights(P, N):
+    return (np.array([2.0 ** -j for j in range(P)], dtype=np.float32)[:, None] * np.ones((P, N), dtype=np.float32))
+
+
+@pytest.mark.parametrize("d,P,Pq", [(64, 2, 3), (64, 2, 2), (64, 3, 3), (64, 1, 1), (128, 3, 4), (128, 4, 2)])
+def test_dyadic_scores_are_exact(d, P, Pq):
+    rng = np.random.default_rng(d + P + Pq)
+    N = 50_003
+    planes = rng.integers(0, 2**64, size=(P, N, d // 64), dtype=np.uint64)
+    qp = rng.integers(0, 2**64, size=(3, Pq, d // 64), dtype=np.uint64)
+    qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (3, 1))
+    w = dyadic_weights(P, N)
+    ix = rbe.rbe_load_corpus(planes, None, flags=rbe.RBE_DYADIC)
+    np.testing.assert_array_equal(rbe.rbe_debug_read_scales(ix, 0, N), w)
+    np.testing.assert_array_equal(rbe.rbe_debug_popcounts(ix, qp[0], 0, N), oracle.popcounts(planes, qp[0]))
+    dense = rbe.rbe_debug_scores(ix, qp[0], None, 0, N)
+    np.testing.assert_array_equal(dense.astype(np.float64), oracle.scores(planes, w, qp[0], qs[0]))   # exact rationals
+    for q_scales in (None, qs):
+        ids, sc = rbe.rbe_search(ix, qp, q_scales, 500)
+        for q in range(3):
+            o_ids, o_sc = oracle.topk(planes, w, qp[q], qs[q], 500)
+            np.testing.assert_array_equal(ids[q], o_ids)         # exact arithmetic on both sides, massive ties
+            np.testing.assert_array_equal(sc[q].astype(np.float64), o_sc)
+    nl, nsc = rbe.rbe_search(ix, qp[:1], None, 100, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=16)
+    o_ids, o_sc = oracle.nearlossless(planes, w, qp[0], qs[0], 100, I=16)
+    np.testing.assert_array_equal(nl[0], o_ids)
+    np.testing.assert_array_equal(nsc[0].astype(np.float64), o_sc)
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_search(ix, qp, qs * np.float32(1.5), 10)       # query scales must be the dyadic weights
+    rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("d,P,Pq", [(64, 2, 3), (128, 3, 3)])
+def test_dyadic_with_stored_inverse_norm(d, P, Pq):
+    """rbe*-style: weights 2^-t, one stored inverse norm per keyword (Sec. 5.1)."""
+    rng = np.random.default_rng(7 * d + P + Pq)
+    N = 120_000
+    planes = rng.integers(0, 2**64, size=(P, N, d // 64), dtype=np.uint64)
+    qp = rng.integers(0, 2**64, size=(5, Pq, d // 64), dtype=np.uint64)
+    qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (5, 1))
+    folded = oracle.fold_cosine(planes, dyadic_weights(P, N))
+    ix = rbe.rbe_load_corpus(planes, None, flags=rbe.RBE_DYADIC | rbe.RBE_COSINE)
+    np.testing.assert_array_equal(rbe.rbe_debug_read_scales(ix, 0, N), folded)    # same double norm, same rounding
+    dense = rbe.rbe_debug_scores(ix, qp[0], None, 0, N)
+    # an exact integer combination times one fp32 factor: a single rounding on the GPU, none in the oracle
+    np.testing.assert_array_equal(dense, oracle.scores(planes, folded, qp[0], qs[0]).astype(np.float32))
+    ids, sc = rbe.rbe_search(ix, qp, None, 1000)
+    check_batch(planes, folded, qp, qs, 1000, ids, sc)
+    ids1, sc1 = rbe.rbe_search(ix, qp[:1], None, 1000)
+    np.testing.assert_array_equal(ids1[0], ids[0])
+    nl, nsc = rbe.rbe_search(ix, qp, None, 200, mode=rbe.RBE_SELECT_NEARLOSSLESS)
+    for q in range(5):
+        check_nearlossless(planes, folded, qp[q], qs[q], 200, 256, nl[q], nsc[q])
+    rbe.rbe_free(ix)
+
+
+def test_dyadic_unsupported_dim_and_chunked_device_load():
+    import torch
+    with pytest.raises(rbe.RbeError) as e:
+        rbe.rbe_index_create(1000, 256, 2, rbe.RBE_DYADIC)
+    assert e.value.code == rbe.RBE_EUNSUPPORTED
+    rng = np.random.default_rng(3)
+    N = 30_000
+    planes = rng.integers(0, 2**64, size=(2, N, 1), dtype=np.uint64)
+    ix = rbe.rbe_index_create(N, 64, 2, rbe.RBE_DYADIC | rbe.RBE_COSINE)
+    rbe.rbe_load_chunk(ix, 0, torch.from_numpy(planes[:, :12345].view(np.int64).copy()).cuda(), None)
+    rbe.rbe_load_chunk(ix, 12345, planes[:, 12345:], None)
+    rbe.rbe_finalize(ix)
+    qp = rng.integers(0, 2**64, size=(2, 3, 1), dtype=np.uint64)
+    qs = np.tile(np.array([1.0, 0.5, 0.25], dtype=np.float32), (2, 1))
+    ids, sc = rbe.rbe_search(ix, qp, None, 50)
+    check_batch(planes, oracle.fold_cosine(planes, dyadic_weights(2, N)), qp, qs, 50, ids, sc)
+    rbe.rbe_free(ix)
