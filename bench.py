@@ -213,6 +213,7 @@ def main():
         "levels": st["n_levels"],
         "candidates_max": st["candidates_max"],
         "select_ms_total": float(r1["select_ms"].mean()) if r1["select_ms"].size else None,
+        "last_search_level_ms": {"scan": st["scan_ms"], "select": st["select_ms"]},
         "roofline": {
             "kernel": "scan_exact (finest level)",
             "bound": "hbm",

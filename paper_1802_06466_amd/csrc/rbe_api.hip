@@ -69,6 +69,7 @@ struct rbe_index {
     uint64_t* d_cand = nullptr;
     uint32_t* d_count = nullptr;
     uint64_t* d_tau = nullptr;
+    uint64_t* d_kmax = nullptr;
     uint32_t* d_status = nullptr;
     uint32_t* d_seen = nullptr;     // [RBE_MAX_LEVELS][RBE_MAX_QUERIES]
     uint32_t* d_qwords = nullptr;   // [Q][PQ][2W]
@@ -142,6 +143,7 @@ int ensure_fixed(rbe_index* ix)
     const size_t Q = RBE_MAX_QUERIES;
     HIP_TRY(hipMalloc(&ix->d_count, Q * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&ix->d_tau, Q * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&ix->d_kmax, Q * sizeof(uint64_t)));
     HIP_TRY(hipMalloc(&ix->d_status, sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&ix->d_seen, RBE_MAX_LEVELS * Q * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&ix->d_qwords, Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t)));
@@ -407,6 +409,7 @@ void rbe_free(rbe_index* ix)
     (void)hipFree(ix->d_tiles);
     (void)hipFree(ix->d_count);
     (void)hipFree(ix->d_tau);
+    (void)hipFree(ix->d_kmax);
     (void)hipFree(ix->d_status);
     (void)hipFree(ix->d_seen);
     (void)hipFree(ix->d_qwords);
@@ -485,7 +488,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
     rbe_index* ix = c.ix;
     if (r.end <= r.begin) return RBE_OK;
     const KernelSel sel{ix->P, c.PQ, ix->mode, c.Q == 1};
-    const CandList out{ix->d_cand, ix->d_count, c.cap};
+    const CandList out{ix->d_cand, ix->d_count, ix->d_kmax, c.cap};
     uint32_t grid = 0;
     hipError_t e;
     if (c.mode == RBE_SELECT_EXACT) {
@@ -517,7 +520,7 @@ static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_
     if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 1], c.st));
 
     SelectArgs se;
-    se.cand = ix->d_cand; se.count = ix->d_count; se.tau = ix->d_tau; se.cap = c.cap; se.k = c.k;
+    se.cand = ix->d_cand; se.count = ix->d_count; se.tau = ix->d_tau; se.kmax = ix->d_kmax; se.cap = c.cap; se.k = c.k;
     se.status = ix->d_status; se.count_seen = ix->d_seen + (size_t)level_slot * RBE_MAX_QUERIES;
     se.final_pass = final_pass; se.ids_out = ix->d_ids; se.scores_out = ix->d_scores;
     hipLaunchKernelGGL(rbe::select_topk, dim3(c.Q), dim3(kSelBlock), 0, c.st, se);
@@ -588,7 +591,7 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
     bool fallback = plan.empty();
 
     for (int attempt = 0; attempt < 2; ++attempt) {
-        hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, c.st, ix->d_count, ix->d_tau, ix->d_status, c.Q);
+        hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, c.st, ix->d_count, ix->d_tau, ix->d_kmax, ix->d_status, c.Q);
         HIP_TRY(hipGetLastError());
         if (!fallback) {
             if (prof) HIP_TRY(hipEventRecord(ix->ev[0], c.st));

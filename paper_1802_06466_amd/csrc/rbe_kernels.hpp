@@ -198,8 +198,20 @@ constexpr int kStage = 512;  // entries per wave; an append adds at most 64
 struct CandList {
     uint64_t* cand;   // [Q][cap]
     uint32_t* count;  // [Q]
+    uint64_t* kmax;   // [Q] largest key ever appended (the selection starts its radix descent below
+                      //     the bits that the threshold and this maximum have in common)
     uint32_t cap;
 };
+
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
+{
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const uint64_t o = __shfl_xor(v, d);
+        v = o > v ? o : v;
+    }
+    return v;
+}
 
 template <bool SINGLE>
 __device__ __forceinline__ void stage_flush(uint64_t* s_keys, uint8_t* s_q, uint32_t fill, const CandList& a, int lane)
@@ -210,10 +222,15 @@ __device__ __forceinline__ void stage_flush(uint64_t* s_keys, uint8_t* s_q, uint
         uint32_t base = 0;
         if (lane == 0) base = atomicAdd(a.count, fill);
         base = __shfl(base, 0);
+        uint64_t mx = 0;
         for (uint32_t i = lane; i < fill; i += 64) {
             const uint32_t pos = base + i;
-            if (pos < a.cap) a.cand[pos] = s_keys[i];  // the count keeps running so that overflow is seen
+            const uint64_t key = s_keys[i];
+            mx = key > mx ? key : mx;
+            if (pos < a.cap) a.cand[pos] = key;  // the count keeps running so that overflow is seen
         }
+        mx = wave_max_u64(mx);
+        if (lane == 0) atomicMax((unsigned long long*)a.kmax, (unsigned long long)mx);
     } else {
         for (uint32_t i0 = 0; i0 < fill; i0 += 64) {
             const uint32_t i = i0 + lane;
@@ -232,6 +249,8 @@ __device__ __forceinline__ void stage_flush(uint64_t* s_keys, uint8_t* s_q, uint
                     const uint32_t pos = base + (uint32_t)__popcll(sel & ((1ull << lane) - 1ull));
                     if (pos < a.cap) a.cand[(size_t)q0 * a.cap + pos] = key;
                 }
+                const uint64_t mx = wave_max_u64((valid && myq == q0) ? key : 0);
+                if (lane == lead) atomicMax((unsigned long long*)(a.kmax + q0), (unsigned long long)mx);
                 todo &= ~sel;
             }
         }

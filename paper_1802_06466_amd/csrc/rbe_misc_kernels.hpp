@@ -17,7 +17,9 @@ enum : uint32_t { kStatusOverflow = 1u };
 struct SelectArgs {
     uint64_t* cand;      // [Q][cap], in/out: on return the best min(n,k) keys at the front
     uint32_t* count;     // [Q] in: appended so far; out: number kept
-    uint64_t* tau;       // [Q] out: k-th best key once at least k candidates exist
+    uint64_t* tau;       // [Q] in: threshold the candidates were collected with; out: k-th best key once at
+                         //     least k candidates exist
+    const uint64_t* kmax;  // [Q] largest key ever appended
     uint32_t cap;
     uint32_t k;
     uint32_t* status;    // bit 0 set if any query's count exceeded cap
@@ -46,10 +48,17 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* s_wave
 }
 
 // Bitonic sort of `pow2` keys in LDS, descending.  All threads of the workgroup call it.
+// Pair index i of a stage is owned by thread i % 1024, so while the stride is at most
+// 64 every wave works inside its own 128-key blocks and only needs to order its own LDS
+// traffic; workgroup barriers are needed around the stages with stride >= 128 only.
 __device__ __forceinline__ void bitonic_desc(uint64_t* keys, uint32_t pow2)
 {
+    bool prev_wide = true;   // data written by other threads before the call
     for (uint32_t size = 2; size <= pow2; size <<= 1) {
         for (uint32_t st = size >> 1; st > 0; st >>= 1) {
+            const bool wide = st >= 128;
+            if (wide || prev_wide) __syncthreads();
+            else { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier(); }
             for (uint32_t i = threadIdx.x; i < pow2 / 2; i += kSelBlock) {
                 const uint32_t lo = 2 * i - (i & (st - 1));
                 const uint32_t hi = lo + st;
@@ -57,9 +66,10 @@ __device__ __forceinline__ void bitonic_desc(uint64_t* keys, uint32_t pow2)
                 const uint64_t x = keys[lo], y = keys[hi];
                 if ((x < y) == desc) { keys[lo] = y; keys[hi] = x; }
             }
-            __syncthreads();
+            prev_wide = wide;
         }
     }
+    __syncthreads();
 }
 
 // One workgroup per query.
@@ -69,7 +79,6 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
     __shared__ uint64_t sbound[kSelBound];  // keys of the boundary bin
     __shared__ uint32_t hist[kSelBins];
     __shared__ uint32_t s_wave[16];
-    __shared__ uint64_t s_and, s_or;
     __shared__ uint32_t s_digit, s_remaining, s_binpop, s_fill_keep, s_fill_bound;
 
     const uint32_t q = blockIdx.x;
@@ -91,34 +100,14 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
         for (uint32_t i = tid; i < n; i += kSelBlock) skeys[i] = keys[i];
     } else {
         m = k;
-        // ---- bits that differ between any two keys
-        uint64_t vand = ~0ull, vor = 0;
-        for (uint32_t base = 0; base < n; base += kSelBlock * kSelUnroll) {
-            uint64_t kk[kSelUnroll];
-#pragma unroll
-            for (int u = 0; u < kSelUnroll; ++u) {
-                const uint32_t i = base + u * kSelBlock + tid;
-                kk[u] = i < n ? keys[i] : 0;
-            }
-#pragma unroll
-            for (int u = 0; u < kSelUnroll; ++u) {
-                const uint32_t i = base + u * kSelBlock + tid;
-                if (i < n) { vand &= kk[u]; vor |= kk[u]; }
-            }
-        }
-        if (tid == 0) { s_and = ~0ull; s_or = 0; }
-        __syncthreads();
-#pragma unroll
-        for (int d = 32; d > 0; d >>= 1) {
-            vand &= __shfl_xor(vand, d);
-            vor |= __shfl_xor(vor, d);
-        }
-        if ((tid & 63) == 0) { atomicAnd((unsigned long long*)&s_and, (unsigned long long)vand); atomicOr((unsigned long long*)&s_or, (unsigned long long)vor); }
-        __syncthreads();
-        const uint64_t diff = s_and ^ s_or;       // non-zero: the n > k >= 1 keys are distinct
-        int pos = 64 - __clzll((long long)diff);   // low `pos` bits are undetermined
+        // ---- every key lies in [threshold used by the scan, largest key appended]: the bits
+        //      these two have in common are common to all keys and need no radix round
+        const uint64_t lo_key = a.tau[q], hi_key = a.kmax[q];
+        const uint64_t diff = lo_key ^ hi_key;
+        int pos = diff ? 64 - __clzll((long long)diff) : 0;   // low `pos` bits are undetermined
         uint64_t mask = pos >= 64 ? 0ull : ~((1ull << pos) - 1ull);
-        uint64_t prefix = s_or & mask;
+        uint64_t prefix = hi_key & mask;
+        __syncthreads();                           // everyone has read tau before it is rewritten below
         uint32_t remaining = k;                    // rank of the wanted key among keys matching the prefix
 
         // ---- radix descent, 11 bits per round, until the boundary bin fits an LDS sort
@@ -228,10 +217,10 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
     }
 }
 
-__global__ void init_state(uint32_t* count, uint64_t* tau, uint32_t* status, uint32_t n_queries)
+__global__ void init_state(uint32_t* count, uint64_t* tau, uint64_t* kmax, uint32_t* status, uint32_t n_queries)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_queries) { count[i] = 0; tau[i] = 0; }
+    if (i < n_queries) { count[i] = 0; tau[i] = 0; kmax[i] = 0; }
     if (i == 0) *status = 0;
 }
 
