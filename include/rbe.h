@@ -129,6 +129,20 @@ int rbe_load_chunk(rbe_index *ix, uint64_t first_item, uint64_t count,
                    const uint64_t *planes, const float *scales,
                    int mem_kind, void *hip_stream);
 
+/* Encodes items [first_item, first_item + count) on the GPU with the stand-in
+ * encoder described at rbe_encode_query() (same arithmetic, same bits) and
+ * stores them in the index: the offline "keyword side" step of Fig. 3.
+ *   x: [count][dim] float, row-major, in host or device memory (mem_kind).
+ * Not available for RBE_DYADIC indexes (their planes come from the model).
+ * Only valid while loading.                                                   */
+int rbe_encode_chunk(rbe_index *ix, uint64_t first_item, uint64_t count,
+                     const float *x, int mem_kind, void *hip_stream);
+
+/* rbe_index_create + rbe_encode_chunk of all n_items vectors + rbe_finalize.   */
+int rbe_encode_corpus(rbe_index **out, const float *x, uint64_t n_items,
+                      uint32_t dim, uint32_t n_planes, int mem_kind,
+                      uint32_t flags, void *hip_stream);
+
 /* Ends loading: applies RBE_COSINE if requested, waits for the stream, and
  * makes the index searchable.  Items never loaded score as all-(-1) vectors
  * with scale 0.                                                               */
@@ -222,6 +236,11 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
  * first_item+count) back: out [n_planes][count] float (host).                */
 int rbe_debug_read_scales(rbe_index *ix, uint64_t first_item, uint64_t count,
                           float *out, void *hip_stream);
+
+/* Copies the plane words of items [first_item, first_item+count) back:
+ * out [n_planes][count][dim/64] uint64 (host).                               */
+int rbe_debug_read_planes(rbe_index *ix, uint64_t first_item, uint64_t count,
+                          uint64_t *out, void *hip_stream);
 
 /* Tile order (pure host functions, for tests): physical position of logical
  * tile `tile` in a corpus of n_tiles tiles with the given sample ratio, and the

@@ -58,6 +58,8 @@ PROTOTYPES = {
     "rbe_index_create": (_i32, [ctypes.POINTER(_vp), _u64, _u32, _u32, _u32]),
     "rbe_index_create_ex": (_i32, [ctypes.POINTER(_vp), _u64, _u32, _u32, _u32, _u32]),
     "rbe_load_chunk": (_i32, [_vp, _u64, _u64, _vp, _vp, _i32, _vp]),
+    "rbe_encode_chunk": (_i32, [_vp, _u64, _u64, _vp, _i32, _vp]),
+    "rbe_encode_corpus": (_i32, [ctypes.POINTER(_vp), _vp, _u64, _u32, _u32, _i32, _u32, _vp]),
     "rbe_finalize": (_i32, [_vp, _vp]),
     "rbe_load_corpus": (_i32, [ctypes.POINTER(_vp), _vp, _vp, _u64, _u32, _u32, _i32, _u32, _vp]),
     "rbe_free": (None, [_vp]),
@@ -71,6 +73,7 @@ PROTOTYPES = {
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
+    "rbe_debug_read_planes": (_i32, [_vp, _u64, _u64, _vp, _vp]),
     "rbe_debug_copy": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
     "rbe_strerror": (ctypes.c_char_p, [_i32]),
     "rbe_last_error": (ctypes.c_char_p, []),
@@ -210,6 +213,40 @@ def rbe_load_chunk(ix: Index, first_item: int, planes, scales, stream=None):
     del keep
 
 
+def _vectors_ptr(x, dim: int):
+    """(ptr, mem_kind, count, keepalive) for a [count][dim] float32 numpy array or torch tensor."""
+    if isinstance(x, np.ndarray):
+        a, ap = _host(x, np.float32)
+        if a.ndim != 2 or a.shape[1] != dim:
+            raise RbeError(RBE_EINVAL, f"expected x [count][{dim}], got {a.shape}")
+        return ap, RBE_MEM_HOST, a.shape[0], a
+    import torch
+    if not isinstance(x, torch.Tensor) or x.dtype != torch.float32 or x.dim() != 2 or x.shape[1] != dim:
+        raise RbeError(RBE_EINVAL, f"expected x float32 [count][{dim}]")
+    x = x.contiguous()
+    return _vp(x.data_ptr()), (RBE_MEM_DEVICE if x.is_cuda else RBE_MEM_HOST), int(x.shape[0]), x
+
+
+def rbe_encode_chunk(ix: Index, first_item: int, x, stream=None):
+    xp, kind, count, keep = _vectors_ptr(x, ix.dim)
+    _check(load_library().rbe_encode_chunk(ix.handle, first_item, count, xp, kind, _stream_ptr(stream)))
+    if kind == RBE_MEM_DEVICE:
+        import torch
+        torch.cuda.current_stream().synchronize() if stream is None else stream.synchronize()
+    del keep
+
+
+def rbe_encode_corpus(x, n_planes: int, flags: int = 0, stream=None) -> Index:
+    """x [N][dim] float32 (numpy = host, torch cuda = device) -> searchable index."""
+    dim = int(x.shape[1])
+    xp, kind, count, keep = _vectors_ptr(x, dim)
+    out = _vp(None)
+    _check(load_library().rbe_encode_corpus(ctypes.byref(out), xp, count, dim, n_planes, kind, flags,
+                                            _stream_ptr(stream)))
+    del keep
+    return Index(out.value)
+
+
 def rbe_finalize(ix: Index, stream=None):
     _check(load_library().rbe_finalize(ix.handle, _stream_ptr(stream)))
 
@@ -311,6 +348,13 @@ def rbe_debug_scores(ix: Index, q_planes, q_scales, first_item: int, count: int,
 def rbe_debug_read_scales(ix: Index, first_item: int, count: int, stream=None):
     out = np.empty((ix.n_planes, count), dtype=np.float32)
     _check(load_library().rbe_debug_read_scales(ix.handle, first_item, count, out.ctypes.data_as(_vp),
+                                                _stream_ptr(stream)))
+    return out
+
+
+def rbe_debug_read_planes(ix: Index, first_item: int, count: int, stream=None):
+    out = np.empty((ix.n_planes, count, ix.dim // 64), dtype=np.uint64)
+    _check(load_library().rbe_debug_read_planes(ix.handle, first_item, count, out.ctypes.data_as(_vp),
                                                 _stream_ptr(stream)))
     return out
 

@@ -332,9 +332,9 @@ int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uin
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
     if (ix->ready) { set_error("rbe_load_chunk after rbe_finalize"); return RBE_ESTATE; }
-    ARG_CHECK(planes != nullptr, "planes is NULL");
+    ARG_CHECK(count == 0 || planes != nullptr, "planes is NULL");
     const bool want_scales = ix->mode == rbe::kModeScaled;
-    ARG_CHECK(!want_scales || scales != nullptr, "scales is NULL");
+    ARG_CHECK(count == 0 || !want_scales || scales != nullptr, "scales is NULL");
     ARG_CHECK(mem_kind == RBE_MEM_HOST || mem_kind == RBE_MEM_DEVICE, "bad mem_kind %d", mem_kind);
     ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item,
               "items [%llu, +%llu) outside the index of %llu items", (unsigned long long)first_item,
@@ -369,6 +369,64 @@ int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uin
     (void)hipFree(tmp_scales);
     if (e != hipSuccess) { set_error("rbe_load_chunk: %s", hipGetErrorString(e)); return RBE_EHIP; }
     ix->loaded_any = true;
+    return RBE_OK;
+}
+
+int rbe_encode_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const float* x, int mem_kind,
+                     void* hip_stream)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    if (ix->ready) { set_error("rbe_encode_chunk after rbe_finalize"); return RBE_ESTATE; }
+    ARG_CHECK(count == 0 || x != nullptr, "x is NULL");
+    ARG_CHECK(mem_kind == RBE_MEM_HOST || mem_kind == RBE_MEM_DEVICE, "bad mem_kind %d", mem_kind);
+    ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item,
+              "items [%llu, +%llu) outside the index of %llu items", (unsigned long long)first_item,
+              (unsigned long long)count, (unsigned long long)ix->n_items);
+    if (ix->mode != rbe::kModeScaled) {
+        set_error("rbe_encode_chunk produces per-plane scales; a dyadic index takes planes from the model");
+        return RBE_EUNSUPPORTED;
+    }
+    if (count == 0) return RBE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const float* src = x;
+    float* tmp = nullptr;
+    const size_t bytes = (size_t)count * ix->dim * sizeof(float);
+    if (mem_kind == RBE_MEM_HOST) {
+        hipError_t e = hipMalloc(&tmp, bytes);
+        if (e == hipSuccess) e = hipMemcpyAsync(tmp, x, bytes, hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) {
+            set_error("staging %zu bytes of vectors failed: %s", bytes, hipGetErrorString(e));
+            (void)hipFree(tmp);
+            return e == hipErrorOutOfMemory ? RBE_ENOMEM : RBE_EHIP;
+        }
+        src = tmp;
+    }
+    const uint32_t per_block = 256 / ix->W;
+    const dim3 grid((uint32_t)((count + per_block - 1) / per_block));
+    switch (ix->W) {
+        case 1: hipLaunchKernelGGL(rbe::encode_chunk<1>, grid, dim3(256), 0, st, ix->d_tiles, ix->layout, ix->geom, src, first_item, count); break;
+        case 2: hipLaunchKernelGGL(rbe::encode_chunk<2>, grid, dim3(256), 0, st, ix->d_tiles, ix->layout, ix->geom, src, first_item, count); break;
+        default: hipLaunchKernelGGL(rbe::encode_chunk<4>, grid, dim3(256), 0, st, ix->d_tiles, ix->layout, ix->geom, src, first_item, count); break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && mem_kind == RBE_MEM_HOST) e = hipStreamSynchronize(st);
+    (void)hipFree(tmp);
+    if (e != hipSuccess) { set_error("rbe_encode_chunk: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    ix->loaded_any = true;
+    return RBE_OK;
+}
+
+int rbe_encode_corpus(rbe_index** out, const float* x, uint64_t n_items, uint32_t dim, uint32_t n_planes,
+                      int mem_kind, uint32_t flags, void* hip_stream)
+{
+    ARG_CHECK(out != nullptr, "out is NULL");
+    rbe_index* ix = nullptr;
+    int rc = rbe_index_create(&ix, n_items, dim, n_planes, flags);
+    if (rc) return rc;
+    rc = rbe_encode_chunk(ix, 0, n_items, x, mem_kind, hip_stream);
+    if (!rc) rc = rbe_finalize(ix, hip_stream);
+    if (rc) { rbe_free(ix); return rc; }
+    *out = ix;
     return RBE_OK;
 }
 
@@ -713,6 +771,26 @@ int rbe_debug_read_scales(rbe_index* ix, uint64_t first_item, uint64_t count, fl
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(d_out);
     if (e != hipSuccess) { set_error("rbe_debug_read_scales: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    return RBE_OK;
+}
+
+int rbe_debug_read_planes(rbe_index* ix, uint64_t first_item, uint64_t count, uint64_t* out, void* hip_stream)
+{
+    ARG_CHECK(ix && out, "NULL argument");
+    ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item, "item range outside the index");
+    ARG_CHECK(count <= (1ull << 26), "count too large for a debug dump");
+    if (count == 0) return RBE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint64_t* d_out = nullptr;
+    const size_t bytes = (size_t)ix->P * count * ix->W * sizeof(uint64_t);
+    HIP_TRY(hipMalloc(&d_out, bytes));
+    hipLaunchKernelGGL(rbe::gather_planes, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st, ix->d_tiles,
+                       ix->layout, ix->geom, first_item, count, d_out);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, bytes, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(d_out);
+    if (e != hipSuccess) { set_error("rbe_debug_read_planes: %s", hipGetErrorString(e)); return RBE_EHIP; }
     return RBE_OK;
 }
 

@@ -251,6 +251,62 @@ __global__ void scatter_chunk(char* __restrict__ tiles, const Layout l, const Ti
             reinterpret_cast<float*>(tile + g.scales_offset())[j * kTileItems + o] = scales[(size_t)j * count + t];
 }
 
+// Stand-in encoder on the device (greedy residual sign binarisation, see rbe.h):
+// x [count][dim] fp32 -> planes and per-plane scales written straight into the tiles.
+// One thread encodes one item with the same sequential arithmetic as the host
+// encoder (absolute values summed in double in dimension order), so both produce
+// the same bits.  A workgroup first stages its 256 / W items in LDS with coalesced
+// loads; rows are padded by one float against bank conflicts.
+template <int W>
+__global__ __launch_bounds__(256) void encode_chunk(char* __restrict__ tiles, const Layout l, const TileGeom g,
+                                                    const float* __restrict__ x, uint64_t first, uint64_t count)
+{
+    constexpr int D = 64 * W;
+    constexpr int IB = 256 / W;           // items per workgroup
+    __shared__ float sx[IB][D + 1];
+    const uint64_t t0 = (uint64_t)blockIdx.x * IB;
+    const uint32_t n_here = (uint32_t)(count - t0 < (uint64_t)IB ? count - t0 : (uint64_t)IB);
+    for (uint32_t e = threadIdx.x; e < n_here * D; e += 256) sx[e / D][e % D] = x[t0 * D + e];
+    __syncthreads();
+    if (threadIdx.x >= n_here) return;
+    float* r = sx[threadIdx.x];
+    const uint64_t z = first + t0 + threadIdx.x;
+    char* tile = item_tile(tiles, l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    for (uint32_t p = 0; p < g.P; ++p) {
+        double acc = 0.0;
+        for (int i = 0; i < D; ++i) acc += fabs((double)r[i]);
+        const float scale = (float)(acc / (double)D);
+        uint64_t* dst = reinterpret_cast<uint64_t*>(tile + p * g.plane_bytes()) + (size_t)o * W;
+        for (int w = 0; w < W; ++w) {
+            uint64_t word = 0;
+            for (int b = 0; b < 64; ++b) {
+                const float v = r[w * 64 + b];
+                const bool positive = v > 0.0f;
+                word |= (uint64_t)positive << b;
+                r[w * 64 + b] = (float)((double)v - (positive ? (double)scale : -(double)scale));
+            }
+            dst[w] = word;
+        }
+        reinterpret_cast<float*>(tile + g.scales_offset())[p * kTileItems + o] = scale;
+    }
+}
+
+// out[j][t][w] = plane words of item first + t (test hook)
+__global__ void gather_planes(const char* __restrict__ tiles, const Layout l, const TileGeom g,
+                              uint64_t first, uint64_t count, uint64_t* __restrict__ out)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const uint64_t z = first + t;
+    const char* tile = item_tile(const_cast<char*>(tiles), l, g, z);
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    for (uint32_t j = 0; j < g.P; ++j)
+        for (uint32_t w = 0; w < g.W; ++w)
+            out[((size_t)j * count + t) * g.W + w] =
+                reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes())[(size_t)o * g.W + w];
+}
+
 // ---------------------------------------------------------------- calibration
 // Plain 16-byte-per-lane copy of a known size: the yardstick that hardware
 // counter readings of the scan are scaled by.

@@ -469,3 +469,39 @@ def test_dyadic_unsupported_dim_and_chunked_device_load():
     ids, sc = rbe.rbe_search(ix, qp, None, 50)
     check_batch(planes, oracle.fold_cosine(planes, dyadic_weights(2, N)), qp, qs, 50, ids, sc)
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ on-device corpus encoder
+@pytest.mark.parametrize("N,d,P", [(1, 64, 1), (1000, 64, 3), (70_001, 64, 3), (33_333, 128, 4), (5_000, 256, 2)])
+def test_encode_corpus_matches_oracle_encoder_bit_for_bit(N, d, P):
+    import torch
+    c = rbe_synth.centres_numpy(32, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=20 + N)
+    x[0, 3] = 0.0                                               # rho(0) = -1
+    planes, scales = oracle.encode(x, P)
+    ix = rbe.rbe_encode_corpus(x, P)
+    np.testing.assert_array_equal(rbe.rbe_debug_read_planes(ix, 0, N), planes)
+    np.testing.assert_array_equal(rbe.rbe_debug_read_scales(ix, 0, N).view(np.uint32), scales.view(np.uint32))
+    rbe.rbe_free(ix)
+    # chunked, from device memory, then searched
+    ix = rbe.rbe_index_create(N, d, P)
+    cut = N // 3
+    rbe.rbe_encode_chunk(ix, 0, torch.from_numpy(x[:cut]).cuda())
+    rbe.rbe_encode_chunk(ix, cut, x[cut:])
+    rbe.rbe_finalize(ix)
+    np.testing.assert_array_equal(rbe.rbe_debug_read_planes(ix, 0, N), planes)
+    q = rbe_synth.vectors_numpy(2, c, 0.3, seed=21)
+    qp = np.stack([rbe.rbe_encode_query(q[i], P)[0] for i in range(2)])
+    qs = np.stack([rbe.rbe_encode_query(q[i], P)[1] for i in range(2)])
+    k = min(100, N)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k)
+    check_batch(planes, scales, qp, qs, k, ids, sc)
+    rbe.rbe_free(ix)
+
+
+def test_encode_chunk_rejected_for_dyadic_index():
+    ix = rbe.rbe_index_create(100, 64, 2, rbe.RBE_DYADIC)
+    with pytest.raises(rbe.RbeError) as e:
+        rbe.rbe_encode_chunk(ix, 0, np.zeros((100, 64), np.float32))
+    assert e.value.code == rbe.RBE_EUNSUPPORTED
+    rbe.rbe_free(ix)
