@@ -88,6 +88,42 @@ def verify(N, centres, sigma, P, qp, qs, k, ids, sc, full_scan_queries, sampled_
         assert np.all(true_sc[q] >= o_sc[-1] - eps), f"{label}: query {q} returned an item below the k-th best"
 
 
+def test_1e7_items_batch32_top1000_full_oracle():
+    """10,000,000 items, d=64, 3 planes, 1024 clusters, 32 queries, k=1000: every query against a
+    full oracle scan (host-generated corpus, oracle encoder)."""
+    from parity import check_batch
+    N, d, P, k, Q = 10_000_000, 64, 3, 1000, 32
+    c = rbe_synth.centres_numpy(1024, d)
+    planes = np.empty((P, N, 1), dtype=np.uint64)
+    scales = np.empty((P, N), dtype=np.float32)
+    step = 2_000_000
+    for i, z0 in enumerate(range(0, N, step)):
+        x = rbe_synth.vectors_numpy(step, c, 0.3, seed=rbe_synth.SEED_ITEMS, chunk=i)
+        pl, sc = oracle.encode(x, P)
+        planes[:, z0:z0 + step] = pl
+        scales[:, z0:z0 + step] = sc
+    print("  1e7: corpus encoded", flush=True)
+    q = rbe_synth.vectors_numpy(Q, c, 0.3, seed=rbe_synth.SEED_QUERIES)
+    qp = np.stack([rbe.rbe_encode_query(q[i], P)[0] for i in range(Q)])
+    qs = np.stack([rbe.rbe_encode_query(q[i], P)[1] for i in range(Q)])
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k)
+    assert not rbe.rbe_get_search_stats(ix)["fallback"]
+    rbe.rbe_free(ix)
+    check_batch(planes, scales, qp, qs, k, ids, sc)
+
+
+def test_1e8_items_d128_4planes_batch64_top1000():
+    N, d, P, k, sigma, Q = 100_000_000, 128, 4, 1000, 0.3, 64
+    ix, centres = build(N, d, P, 4096, sigma, "1e8 d128")
+    qp, qs = queries(centres, Q, sigma, P)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k)
+    assert not rbe.rbe_get_search_stats(ix)["fallback"]
+    rbe.rbe_free(ix)
+    verify(N, centres, sigma, P, qp, qs, k, ids, sc, full_scan_queries=[0, 63], sampled_chunks={1, 12},
+           label="1e8 d128 k=1000")
+
+
 def test_1e9_items_single_query_and_batch16_top1000():
     N, d, P, k, sigma = 1_000_000_000, 64, 3, 1000, 0.3
     ix, centres = build(N, d, P, 4096, sigma, "1e9 sigma 0.3")
