@@ -26,7 +26,7 @@ RBE_SELECT_EXACT, RBE_SELECT_NEARLOSSLESS = 0, 1
 RBE_MAX_PLANES, RBE_MAX_QUERIES, RBE_MAX_K, RBE_MAX_LEVELS = 4, 64, 4096, 8
 RBE_MAX_ITEMS = 4294966272
 
-LIB_PATH = _build.LIB
+LIB_PATH = os.environ.get("RBE_HIP_LIB", _build.LIB)   # override: experiments with alternative builds
 
 
 class RbeError(RuntimeError):

@@ -35,34 +35,34 @@ def is_stale() -> bool:
     return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
+def build(force: bool = True, verbose: bool = False, out: str = LIB, extra_flags=()) -> str:
     """Compile the library.  With force=False, only when missing."""
-    if not force and os.path.exists(LIB):
-        return LIB
+    if not force and os.path.exists(out):
+        return out
     with tempfile.TemporaryDirectory(prefix="rbe_build_") as tmp:
         procs, objs = [], []
         for src, defs, tag in UNITS:
             obj = os.path.join(tmp, tag + ".o")
-            cmd = [HIPCC, *COMMON, *defs, "-c", os.path.join(CSRC, src), "-o", obj]
+            cmd = [HIPCC, *COMMON, *extra_flags, *defs, "-c", os.path.join(CSRC, src), "-o", obj]
             if verbose:
                 print(" ".join(cmd), flush=True)
             procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
             objs.append(obj)
         failed = []
         for cmd, pr in procs:
-            out, _ = pr.communicate()
-            out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+            log, _ = pr.communicate()
+            log = "\n".join(l for l in log.splitlines() if "packed-fp32-ops" not in l)
             if pr.returncode != 0:
-                failed.append((cmd, out))
-            elif verbose and out.strip():
-                print(out, flush=True)
+                failed.append((cmd, log))
+            elif verbose and log.strip():
+                print(log, flush=True)
         if failed:
             raise RuntimeError("hipcc failed:\n" + "\n".join(" ".join(c) + "\n" + o for c, o in failed))
-        link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+        link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
         if verbose:
             print(" ".join(link), flush=True)
         subprocess.check_call(link)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -10,7 +10,7 @@ namespace rbe {
 
 // Scores the lane's 4 items of `cur` against one query and queues the survivors.
 template <int W, int P, int PQ, bool SINGLE, int MODE>
-__device__ __forceinline__ uint32_t score_and_stage(const RowRegs<W, P, scale_arrays(MODE, P)>& cur, const QueryRegs<W, PQ>& qr, uint64_t tau,
+__device__ __forceinline__ uint32_t score_and_stage(RowRegs<W, P, scale_arrays(MODE, P)>& cur, const QueryRegs<W, PQ>& qr, uint64_t tau,
                                                     float taus, uint32_t q, uint32_t p, int wave, int lane,
                                                     uint64_t* s_keys, uint8_t* s_q, uint32_t fill, const ScanArgs& a)
 {
@@ -20,6 +20,17 @@ __device__ __forceinline__ uint32_t score_and_stage(const RowRegs<W, P, scale_ar
     for (int m = 0; m < kItemsPerLane; ++m) {
         s[m] = score_item<W, P, PQ, MODE>(cur, m, qr);
         any |= (s[m] >= taus);
+        // Batch kernel only: the empty asm makes the next item's plane words "depend" on this
+        // item's score, at no cost.  Without it the scheduler interleaves the popcount chains of
+        // all four items; wide configurations then spill to the accumulation registers, and the
+        // VALU-bound kernel loses 10 % (d=64, 3x3 planes) to 30 % (d=128, 4x4).  The one-query
+        // kernel is HBM-bound and measurably prefers the interleaved schedule.
+        if (!SINGLE && m + 1 < kItemsPerLane) {
+#pragma unroll
+            for (int j = 0; j < P; ++j)
+#pragma unroll
+                for (int h = 0; h < 2 * W; ++h) asm volatile("" : "+v"(s[m]), "+v"(cur.w[j][m + 1][h]));
+        }
     }
     if (__ballot(any)) {   // rare: at least one lane of the wave has a survivor
         const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
@@ -82,6 +93,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
         for (; p < a.p_end; p += G) {
             RowRegs<W, P, S> cur;
             load_row<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            // do not start scoring piecemeal as individual loads land: that keeps every partial
+            // popcount of the tile alive at once and overflows the register file
+            __builtin_amdgcn_sched_barrier(0);
             QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
             uint64_t tau_n = a.tau[0];
             for (uint32_t q = 0; q < nq; ++q) {
