@@ -66,6 +66,12 @@ def _c():
         lib.orc_nearlossless.argtypes = [vp, vp, u64, u32, u32, vp, vp, u32, u64, u64, u64, vp, vp, vp, vp]
         lib.orc_encode.restype = None
         lib.orc_encode.argtypes = [vp, u64, u32, u32, vp, vp]
+        lib.orc_scores_fq.restype = None
+        lib.orc_scores_fq.argtypes = [vp, vp, u64, u32, u32, vp, u64, u64, vp]
+        lib.orc_scores_at_fq.restype = None
+        lib.orc_scores_at_fq.argtypes = [vp, vp, u64, u32, u32, vp, vp, u64, vp]
+        lib.orc_topk_fq.restype = i64
+        lib.orc_topk_fq.argtypes = [vp, vp, u64, u32, u32, vp, u64, u64, u64, vp, vp]
         lib.orc_recon_norms.restype = None
         lib.orc_recon_norms.argtypes = [vp, vp, u64, u32, u32, vp]
         _lib = lib
@@ -213,6 +219,46 @@ def fold_cosine(planes, scales):
     nrm = recon_norms(planes, scales)
     safe = np.where(nrm > 0, nrm, 1.0)
     return (np.asarray(scales, dtype=np.float64) / safe[None, :]).astype(np.float32)
+
+
+def _fquery(q, d):
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    if q.shape != (d,):
+        raise ValueError(f"float query must have shape ({d},)")
+    return q
+
+
+def scores_fq(planes, scales, q, z0: int = 0, z1: int | None = None):
+    """Hybrid scoring (fp32 query x RBE items, the paper's model m_5): float64 scores of items [z0, z1)."""
+    planes, scales, P, N, W = _corpus(planes, scales)
+    q = _fquery(q, 64 * W)
+    z1 = N if z1 is None else z1
+    out = np.zeros(z1 - z0, dtype=np.float64)
+    _c().orc_scores_fq(_p(planes), _p(scales), N, 64 * W, P, _p(q), z0, z1, _p(out))
+    return out
+
+
+def scores_at_fq(planes, scales, q, ids):
+    planes, scales, P, N, W = _corpus(planes, scales)
+    q = _fquery(q, 64 * W)
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    if ids.size and (ids.min() < 0 or ids.max() >= N):
+        raise ValueError("id out of range")
+    out = np.zeros(ids.size, dtype=np.float64)
+    _c().orc_scores_at_fq(_p(planes), _p(scales), N, 64 * W, P, _p(q), _p(ids), ids.size, _p(out))
+    return out
+
+
+def topk_fq(planes, scales, q, k: int, z0: int = 0, z1: int | None = None):
+    planes, scales, P, N, W = _corpus(planes, scales)
+    q = _fquery(q, 64 * W)
+    z1 = N if z1 is None else z1
+    ids = np.zeros(k, dtype=np.int64)
+    sc = np.zeros(k, dtype=np.float64)
+    r = _c().orc_topk_fq(_p(planes), _p(scales), N, 64 * W, P, _p(q), z0, z1, k, _p(ids), _p(sc))
+    if r < 0:
+        raise MemoryError
+    return ids, sc
 
 
 def recall(result_ids, exact_ids) -> float:

@@ -313,3 +313,52 @@ void orc_recon_norms(const uint64_t *planes, const float *scales, uint64_t N,
         out[z] = sqrt(n2);
     }
 }
+
+
+/* ------------------------------------------------------------------ */
+/* Hybrid scoring: a full-precision query against RBE items (the paper's
+ * "hybrid rbe" model m_5, Sec. 8.1: 32-bit query, binary keyword).  With
+ * q in R^d and the item reconstructed as khat_z = sum_j a_j[z] b_z^j,
+ *     s(q, z) = q . khat_z = sum_j a_j[z] * sum_i q[i] * b_z^j[i],
+ * evaluated by unpacking every bit (no table, no popcount), in double.     */
+/* ------------------------------------------------------------------ */
+static double score_pair_fq(const uint64_t *planes, const float *scales, uint64_t N,
+                            uint32_t d, uint32_t P, uint64_t z, const float *q)
+{
+    const uint32_t W = d / 64;
+    double s = 0.0;
+    for (uint32_t j = 0; j < P; ++j) {
+        const uint64_t *kj = planes + ((uint64_t)j * N + z) * W;
+        double t = 0.0;
+        for (uint32_t i = 0; i < d; ++i)
+            t += ((kj[i / 64] >> (i % 64)) & 1) ? (double)q[i] : -(double)q[i];
+        s += (double)scales[(uint64_t)j * N + z] * t;
+    }
+    return s;
+}
+
+void orc_scores_fq(const uint64_t *planes, const float *scales, uint64_t N, uint32_t d, uint32_t P,
+                   const float *q, uint64_t z0, uint64_t z1, double *out)
+{
+    for (uint64_t z = z0; z < z1; ++z) out[z - z0] = score_pair_fq(planes, scales, N, d, P, z, q);
+}
+
+void orc_scores_at_fq(const uint64_t *planes, const float *scales, uint64_t N, uint32_t d, uint32_t P,
+                      const float *q, const int64_t *ids, uint64_t n_ids, double *out)
+{
+    for (uint64_t r = 0; r < n_ids; ++r)
+        out[r] = score_pair_fq(planes, scales, N, d, P, (uint64_t)ids[r], q);
+}
+
+int64_t orc_topk_fq(const uint64_t *planes, const float *scales, uint64_t N, uint32_t d, uint32_t P,
+                    const float *q, uint64_t z0, uint64_t z1, uint64_t k,
+                    int64_t *ids_out, double *scores_out)
+{
+    topk_t t = { (cand_t *)malloc((k ? k : 1) * sizeof(cand_t)), 0, k };
+    if (!t.h) return -1;
+    for (uint64_t z = z0; z < z1; ++z)
+        topk_offer(&t, score_pair_fq(planes, scales, N, d, P, z, q), (int64_t)z);
+    uint64_t n = topk_finish(&t, ids_out, scores_out);
+    free(t.h);
+    return (int64_t)n;
+}

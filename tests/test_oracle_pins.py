@@ -295,6 +295,33 @@ def test_duplicates_tie_and_order_by_id():
         assert list(ids[r]) == sorted(ids[r])
 
 
+# ---------------------------------------------------------------- hybrid scoring (float query)
+@pytest.mark.parametrize("d,P", [(64, 1), (64, 3), (128, 4)])
+def test_float_query_score_is_dot_with_reconstruction(d, P):
+    rng = np.random.default_rng(50 + d + P)
+    N = 200
+    planes, scales = random_corpus(rng, N, d, P)
+    q = rng.standard_normal(d).astype(np.float32)
+    s = oracle.scores_fq(planes, scales, q)
+    for z in range(N):
+        assert s[z] == pytest.approx(float(np.dot(q.astype(np.float64), reconstruct(planes, scales, z, d))), rel=1e-12, abs=1e-12)
+    np.testing.assert_array_equal(oracle.scores_at_fq(planes, scales, q, [5, 0, 199]), s[[5, 0, 199]])
+    ids, sc = oracle.topk_fq(planes, scales, q, 30)
+    assert list(ids) == full_sort_topk(s, 30)
+    np.testing.assert_array_equal(sc, s[ids])
+
+
+def test_float_query_equal_to_reconstructed_binary_query_gives_binary_score():
+    """If the float query is exactly the reconstruction sum_i c_i b_q^i of an RBE query, the hybrid
+    score equals the all-binary score of Eq. 14 (dyadic c_i keep the reconstruction exact in fp32)."""
+    rng = np.random.default_rng(51)
+    planes, scales = random_corpus(rng, 300, 64, 3)
+    qp = rng.integers(0, 2**64, size=(3, 1), dtype=np.uint64)
+    qs = np.array([1.0, 0.5, 0.25], dtype=np.float32)
+    qf = reconstruct_query(qp, qs, 64).astype(np.float32)
+    np.testing.assert_allclose(oracle.scores_fq(planes, scales, qf), oracle.scores(planes, scales, qp, qs), rtol=1e-12, atol=1e-12)
+
+
 # ---------------------------------------------------------------- P9: exact top-k
 @pytest.mark.parametrize("N,k", [(1, 1), (10, 3), (10, 10), (10, 25), (1000, 1), (1000, 100), (5000, 4096)])
 def test_topk_equals_full_sort(N, k):
