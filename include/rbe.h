@@ -187,6 +187,20 @@ int rbe_search(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
                uint32_t mode, uint32_t group_size_I,
                int64_t *ids_out, float *scores_out, void *hip_stream);
 
+/* Hybrid scoring: full-precision queries against the binary items (the paper's
+ * "hybrid rbe" model, Sec. 8.1, which bounds the accuracy of every RBE model with
+ * the same keyword bits):
+ *     s(q, z) = sum_j a_j[z] * sum_i q[i] * b_z^j[i],      q in R^dim (fp32).
+ * Evaluated through per-byte tables: t_j = sum over the dim/8 bytes p of plane j of
+ * T[p][byte], T[p][v] = sum_{b<8} q[8p+b] * (bit b of v ? +1 : -1) (built in double,
+ * stored as fp32, added in fp32 in byte order), then fp32 fused multiply-adds over j.
+ * For RBE_DYADIC indexes a_j = 2^-j (times the stored inverse norm with RBE_COSINE).
+ *   q: [n_queries][dim] float (host), finite.  Other arguments as rbe_search.
+ * Only RBE_SELECT_EXACT is built; the corpus is read once per query.            */
+int rbe_search_float(rbe_index *ix, const float *q, uint32_t n_queries, uint32_t k,
+                     uint32_t mode, uint32_t group_size_I,
+                     int64_t *ids_out, float *scores_out, void *hip_stream);
+
 /* ---------------------------------------------------------------------------
  * Measurement.  With profiling on, rbe_search brackets each kernel with HIP
  * events on the search stream and fills rbe_search_stats after the call.
@@ -231,6 +245,11 @@ int rbe_debug_popcounts(rbe_index *ix, const uint64_t *q_planes, uint32_t q_n_pl
 int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
                      uint32_t q_n_planes, uint64_t first_item, uint64_t count,
                      float *out, void *hip_stream);
+
+/* fp32 hybrid scores (rbe_search_float arithmetic) of one fp32 query q [dim] for z in
+ * [first_item, first_item+count): out [count] float (host).                  */
+int rbe_debug_scores_float(rbe_index *ix, const float *q, uint64_t first_item,
+                           uint64_t count, float *out, void *hip_stream);
 
 /* Copies the (possibly cosine-folded) scales of items [first_item,
  * first_item+count) back: out [n_planes][count] float (host).                */

@@ -65,6 +65,8 @@ PROTOTYPES = {
     "rbe_free": (None, [_vp]),
     "rbe_encode_query": (_i32, [_vp, _u32, _u32, _vp, _vp]),
     "rbe_search": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "rbe_search_float": (_i32, [_vp, _vp, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "rbe_debug_scores_float": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
     "rbe_set_profiling": (_i32, [_vp, _i32]),
     "rbe_get_search_stats": (_i32, [_vp, ctypes.POINTER(rbe_search_stats)]),
     "rbe_set_tuning": (_i32, [_vp, _u32, _u32]),
@@ -295,6 +297,29 @@ def rbe_search(ix: Index, q_planes, q_scales, k: int, mode: int = RBE_SELECT_EXA
     _check(load_library().rbe_search(ix.handle, qpp, qsp, Q, Pq, k, mode, group_size_I,
                                      ids.ctypes.data_as(_vp), scores.ctypes.data_as(_vp), _stream_ptr(stream)))
     return ids, scores
+
+
+def rbe_search_float(ix: Index, q, k: int, mode: int = RBE_SELECT_EXACT, group_size_I: int = 0, stream=None):
+    """q [Q][dim] float32 -> (ids int64 [Q][k], scores float32 [Q][k]); hybrid scoring."""
+    qa, qap = _host(q, np.float32)
+    if qa.ndim != 2 or qa.shape[1] != ix.dim:
+        raise RbeError(RBE_EINVAL, f"expected q [Q][{ix.dim}], got {qa.shape}")
+    Q = qa.shape[0]
+    ids = np.empty((Q, max(k, 0)), dtype=np.int64)
+    scores = np.empty((Q, max(k, 0)), dtype=np.float32)
+    _check(load_library().rbe_search_float(ix.handle, qap, Q, k, mode, group_size_I, ids.ctypes.data_as(_vp),
+                                           scores.ctypes.data_as(_vp), _stream_ptr(stream)))
+    return ids, scores
+
+
+def rbe_debug_scores_float(ix: Index, q, first_item: int, count: int, stream=None):
+    qa, qap = _host(q, np.float32)
+    if qa.shape != (ix.dim,):
+        raise RbeError(RBE_EINVAL, f"expected q [{ix.dim}]")
+    out = np.empty(count, dtype=np.float32)
+    _check(load_library().rbe_debug_scores_float(ix.handle, qap, first_item, count, out.ctypes.data_as(_vp),
+                                                 _stream_ptr(stream)))
+    return out
 
 
 def rbe_set_profiling(ix: Index, enabled: bool):

@@ -72,6 +72,8 @@ struct rbe_index {
     uint64_t* d_kmax = nullptr;
     uint32_t* d_status = nullptr;
     uint32_t* d_seen = nullptr;     // [RBE_MAX_LEVELS][RBE_MAX_QUERIES]
+    float* d_lut = nullptr;         // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
+    float* h_lut = nullptr;
     uint32_t* d_qwords = nullptr;   // [Q][PQ][2W]
     float* d_qcoef = nullptr;       // [Q][PQ+1]
     int64_t* d_ids = nullptr;
@@ -112,6 +114,26 @@ hipError_t launch_scan_groupmax(uint32_t W, const KernelSel& k, const GroupArgs&
         case 1: return launch_scan_groupmax_w<1>(k, a, Q, n_cu, per_cu, st, grid);
         case 2: return launch_scan_groupmax_w<2>(k, a, Q, n_cu, per_cu, st, grid);
         default: return launch_scan_groupmax_w<4>(k, a, Q, n_cu, per_cu, st, grid);
+    }
+}
+
+hipError_t launch_scan_exact_fq(uint32_t W, const KernelSel& k, const FqArgs& a, uint32_t n_cu, uint32_t per_cu,
+                                hipStream_t st, uint32_t* grid)
+{
+    switch (W) {
+        case 1: return launch_scan_exact_fq_w<1>(k, a, n_cu, per_cu, st, grid);
+        case 2: return launch_scan_exact_fq_w<2>(k, a, n_cu, per_cu, st, grid);
+        default: return launch_scan_exact_fq_w<4>(k, a, n_cu, per_cu, st, grid);
+    }
+}
+
+hipError_t launch_dense_scores_fq(uint32_t W, const KernelSel& k, const char* tiles, const Layout& l, const float* lut,
+                                  uint64_t first, uint64_t count, float* out, hipStream_t st)
+{
+    switch (W) {
+        case 1: return launch_dense_scores_fq_w<1>(k, tiles, l, lut, first, count, out, st);
+        case 2: return launch_dense_scores_fq_w<2>(k, tiles, l, lut, first, count, out, st);
+        default: return launch_dense_scores_fq_w<4>(k, tiles, l, lut, first, count, out, st);
     }
 }
 
@@ -203,6 +225,30 @@ int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales
     }
     HIP_TRY(hipMemcpyAsync(ix->d_qwords, ix->h_qwords, (size_t)Q * PQ * 2 * W * sizeof(uint32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(ix->d_qcoef, ix->h_qcoef, (size_t)Q * (PQ + 1) * sizeof(float), hipMemcpyHostToDevice, st));
+    return RBE_OK;
+}
+
+// Byte tables of fp32 queries: lut[q][p][v] = sum_{b<8} q[8p+b] * (bit b of v ? +1 : -1), summed in
+// double in bit order and rounded to fp32.
+int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t st)
+{
+    const size_t per_q = (size_t)8 * ix->W * 256;
+    if (!ix->d_lut) {
+        HIP_TRY(hipMalloc(&ix->d_lut, RBE_MAX_QUERIES * per_q * sizeof(float)));
+        HIP_TRY(hipHostMalloc(&ix->h_lut, RBE_MAX_QUERIES * per_q * sizeof(float), hipHostMallocDefault));
+    }
+    for (uint32_t n = 0; n < Q; ++n) {
+        const float* x = q + (size_t)n * ix->dim;
+        for (uint32_t i = 0; i < ix->dim; ++i)
+            if (!std::isfinite(x[i])) { set_error("q[%u][%u] is not finite", n, i); return RBE_EINVAL; }
+        for (uint32_t p = 0; p < 8 * ix->W; ++p)
+            for (uint32_t v = 0; v < 256; ++v) {
+                double acc = 0.0;
+                for (uint32_t b = 0; b < 8; ++b) acc += ((v >> b) & 1u) ? (double)x[8 * p + b] : -(double)x[8 * p + b];
+                ix->h_lut[n * per_q + (size_t)p * 256 + v] = (float)acc;
+            }
+    }
+    HIP_TRY(hipMemcpyAsync(ix->d_lut, ix->h_lut, (size_t)Q * per_q * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
 
@@ -471,6 +517,8 @@ void rbe_free(rbe_index* ix)
     (void)hipFree(ix->d_status);
     (void)hipFree(ix->d_seen);
     (void)hipFree(ix->d_qwords);
+    (void)hipFree(ix->d_lut);
+    (void)hipHostFree(ix->h_lut);
     (void)hipFree(ix->d_qcoef);
     (void)hipHostFree(ix->h_qwords);
     (void)hipHostFree(ix->h_qcoef);
@@ -539,6 +587,7 @@ struct Round { uint32_t begin, end, stride, skip; };
 
 struct SearchCtx {
     rbe_index* ix; hipStream_t st; uint32_t Q, PQ, k, cap, mode, I;
+    bool float_query;   // hybrid scoring: fp32 queries through byte tables
 };
 
 static int launch_scan_round(const SearchCtx& c, const Round& r)
@@ -549,7 +598,18 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
     const CandList out{ix->d_cand, ix->d_count, ix->d_kmax, c.cap};
     uint32_t grid = 0;
     hipError_t e;
-    if (c.mode == RBE_SELECT_EXACT) {
+    if (c.float_query) {
+        e = hipSuccess;
+        const size_t per_q = (size_t)8 * ix->W * 256;
+        for (uint32_t q = 0; q < c.Q && e == hipSuccess; ++q) {   // one pass over the range per query
+            FqArgs fa;
+            fa.tiles = ix->d_tiles; fa.layout = ix->layout; fa.n_items = ix->n_items;
+            fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
+            fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q, ix->d_kmax + q, c.cap};
+            fa.p_begin = r.begin; fa.p_end = r.end;
+            e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
+        }
+    } else if (c.mode == RBE_SELECT_EXACT) {
         ScanArgs sa;
         sa.tiles = ix->d_tiles; sa.layout = ix->layout; sa.n_items = ix->n_items;
         sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = c.Q;
@@ -610,29 +670,13 @@ static std::vector<Round> make_group_plan(uint32_t n_super, uint32_t ratio, uint
     return plan;
 }
 
-int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
-               uint32_t q_n_planes, uint32_t k, uint32_t mode, uint32_t group_size_I,
-               int64_t* ids_out, float* scores_out, void* hip_stream)
+// Common part of the search entry points: plan, enqueue, wait, copy out.  The queries have
+// been staged on the stream already.
+static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
 {
-    ARG_CHECK(ix != nullptr, "index is NULL");
-    if (!ix->ready) { set_error("rbe_search before rbe_finalize"); return RBE_ESTATE; }
-    ARG_CHECK(q_planes && ids_out && scores_out, "NULL argument");
-    ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries must be 1..%u (got %u)", RBE_MAX_QUERIES, n_queries);
-    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, q_n_planes);
-    ARG_CHECK(k >= 1 && k <= RBE_MAX_K, "k must be 1..%u (got %u)", RBE_MAX_K, k);
-    ARG_CHECK(mode == RBE_SELECT_EXACT || mode == RBE_SELECT_NEARLOSSLESS, "unknown mode %u", mode);
-    ARG_CHECK(group_size_I <= 65535, "group_size_I must be <= 65535");
-
-    SearchCtx c;
-    c.ix = ix; c.st = (hipStream_t)hip_stream; c.Q = n_queries; c.PQ = q_n_planes; c.k = k; c.mode = mode;
-    c.I = group_size_I ? group_size_I : 256;
-    uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->layout.ratio * k);
-    c.cap = std::max<uint32_t>(cap, k + 2 * kTileItems);
-    int rc = ensure_workspace(ix, c.Q, k, c.cap);
-    if (rc) return rc;
-    rc = stage_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
-    if (rc) return rc;
-
+    rbe_index* ix = c.ix;
+    const uint32_t k = c.k, mode = c.mode;
+    int rc;
     // units of the slow path: tiles (exact) or super-blocks (near-lossless), `per_unit` candidates each at most
     const uint32_t rows_total = (uint32_t)((ix->n_items + kRow - 1) / kRow);
     const uint32_t n_units = mode == RBE_SELECT_EXACT ? ix->layout.n_tiles : (rows_total + c.I - 1) / c.I;
@@ -698,6 +742,77 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
     }
     std::memcpy(ids_out, ix->h_ids, (size_t)c.Q * k * sizeof(int64_t));
     std::memcpy(scores_out, ix->h_scores, (size_t)c.Q * k * sizeof(float));
+    return RBE_OK;
+}
+
+static int search_prologue(rbe_index* ix, SearchCtx& c, uint32_t n_queries, uint32_t k, uint32_t mode,
+                           uint32_t group_size_I, const void* ids_out, const void* scores_out, void* hip_stream)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    if (!ix->ready) { set_error("search before rbe_finalize"); return RBE_ESTATE; }
+    ARG_CHECK(ids_out && scores_out, "NULL output argument");
+    ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries must be 1..%u (got %u)", RBE_MAX_QUERIES, n_queries);
+    ARG_CHECK(k >= 1 && k <= RBE_MAX_K, "k must be 1..%u (got %u)", RBE_MAX_K, k);
+    ARG_CHECK(mode == RBE_SELECT_EXACT || mode == RBE_SELECT_NEARLOSSLESS, "unknown mode %u", mode);
+    ARG_CHECK(group_size_I <= 65535, "group_size_I must be <= 65535");
+    c.ix = ix; c.st = (hipStream_t)hip_stream; c.Q = n_queries; c.PQ = 1; c.k = k; c.mode = mode;
+    c.I = group_size_I ? group_size_I : 256;
+    c.float_query = false;
+    const uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->layout.ratio * k);
+    c.cap = std::max<uint32_t>(cap, k + 2 * kTileItems);
+    return ensure_workspace(ix, c.Q, k, c.cap);
+}
+
+int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
+               uint32_t q_n_planes, uint32_t k, uint32_t mode, uint32_t group_size_I,
+               int64_t* ids_out, float* scores_out, void* hip_stream)
+{
+    SearchCtx c;
+    int rc = search_prologue(ix, c, n_queries, k, mode, group_size_I, ids_out, scores_out, hip_stream);
+    if (rc) return rc;
+    ARG_CHECK(q_planes != nullptr, "q_planes is NULL");
+    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, q_n_planes);
+    c.PQ = q_n_planes;
+    rc = stage_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
+    if (rc) return rc;
+    return run_search(c, ids_out, scores_out);
+}
+
+int rbe_search_float(rbe_index* ix, const float* q, uint32_t n_queries, uint32_t k, uint32_t mode,
+                     uint32_t group_size_I, int64_t* ids_out, float* scores_out, void* hip_stream)
+{
+    SearchCtx c;
+    int rc = search_prologue(ix, c, n_queries, k, mode, group_size_I, ids_out, scores_out, hip_stream);
+    if (rc) return rc;
+    ARG_CHECK(q != nullptr, "q is NULL");
+    if (mode != RBE_SELECT_EXACT) {
+        set_error("rbe_search_float is built for RBE_SELECT_EXACT only");
+        return RBE_EUNSUPPORTED;
+    }
+    c.float_query = true;
+    rc = stage_float_queries(ix, q, c.Q, c.st);
+    if (rc) return rc;
+    return run_search(c, ids_out, scores_out);
+}
+
+int rbe_debug_scores_float(rbe_index* ix, const float* q, uint64_t first_item, uint64_t count, float* out,
+                           void* hip_stream)
+{
+    ARG_CHECK(ix && q && out, "NULL argument");
+    ARG_CHECK(first_item <= ix->n_items && count <= ix->n_items - first_item, "item range outside the index");
+    ARG_CHECK(count <= (1ull << 28), "count too large for a debug dump");
+    if (count == 0) return RBE_OK;
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = stage_float_queries(ix, q, 1, st);
+    if (rc) return rc;
+    float* d_out = nullptr;
+    HIP_TRY(hipMalloc(&d_out, (size_t)count * sizeof(float)));
+    hipError_t e = launch_dense_scores_fq(ix->W, KernelSel{ix->P, 1, ix->mode, true}, ix->d_tiles, ix->layout,
+                                          ix->d_lut, first_item, count, d_out, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, (size_t)count * sizeof(float), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(d_out);
+    if (e != hipSuccess) { set_error("rbe_debug_scores_float: %s", hipGetErrorString(e)); return RBE_EHIP; }
     return RBE_OK;
 }
 

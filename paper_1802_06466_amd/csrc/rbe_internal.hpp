@@ -30,6 +30,15 @@ template <int W>
 hipError_t launch_dense_scores_w(const KernelSel& k, const char* tiles, const Layout& l, const uint32_t* qwords,
                                  const float* qcoef, uint64_t first, uint64_t count, float* out, hipStream_t st);
 
+// Hybrid scoring: one launch per query (k.PQ and k.single are ignored).
+template <int W>
+hipError_t launch_scan_exact_fq_w(const KernelSel& k, const FqArgs& a, uint32_t n_cu, uint32_t per_cu,
+                                  hipStream_t st, uint32_t* grid_out);
+
+template <int W>
+hipError_t launch_dense_scores_fq_w(const KernelSel& k, const char* tiles, const Layout& l, const float* lut,
+                                    uint64_t first, uint64_t count, float* out, hipStream_t st);
+
 #define RBE_DECLARE_W(Wv)                                                                                         \
     template <> hipError_t launch_scan_exact_w<Wv>(const KernelSel&, const ScanArgs&, uint32_t, uint32_t,         \
                                                    hipStream_t, uint32_t*);                                       \
@@ -37,7 +46,11 @@ hipError_t launch_dense_scores_w(const KernelSel& k, const char* tiles, const La
                                                       hipStream_t, uint32_t*);                                    \
     template <> hipError_t launch_dense_scores_w<Wv>(const KernelSel&, const char*, const Layout&,                \
                                                      const uint32_t*, const float*, uint64_t, uint64_t, float*,   \
-                                                     hipStream_t);
+                                                     hipStream_t);                                                \
+    template <> hipError_t launch_scan_exact_fq_w<Wv>(const KernelSel&, const FqArgs&, uint32_t, uint32_t,        \
+                                                      hipStream_t, uint32_t*);                                    \
+    template <> hipError_t launch_dense_scores_fq_w<Wv>(const KernelSel&, const char*, const Layout&,             \
+                                                        const float*, uint64_t, uint64_t, float*, hipStream_t);
 RBE_DECLARE_W(1)
 RBE_DECLARE_W(2)
 RBE_DECLARE_W(4)

@@ -291,6 +291,19 @@ struct ScanArgs {
     uint32_t p_begin, p_end;  // physical tile range this launch covers
 };
 
+// Hybrid scoring (fp32 query against RBE items, the paper's model m_5, Sec. 8.1): one query per
+// launch; `lut` holds, for every byte position p of a plane and every byte value v,
+// sum_{b<8} q[8p+b] * (bit b of v ? +1 : -1).
+struct FqArgs {
+    const char* tiles;
+    Layout layout;
+    uint64_t n_items;
+    const float* lut;         // [8W][256]
+    const uint64_t* tau_ptr;  // [1] threshold key of this query
+    CandList out;             // this query's list (pointers already offset)
+    uint32_t p_begin, p_end;
+};
+
 struct GroupArgs {
     const char* tiles;
     Layout layout;

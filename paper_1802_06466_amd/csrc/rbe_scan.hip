@@ -114,6 +114,105 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
 }
 
 
+// ---------------------------------------------------------------- hybrid scoring (fp32 query)
+// t_j = sum over the 8W bytes of plane j of lut[p][byte], accumulated in fp32 in byte order;
+// kModeScaled: s = sum_j fma(a_j, t_j, s).  Dyadic modes: s = (sum_j 2^-j t_j) [* the item's scale].
+template <int W, int P, int MODE>
+__device__ __forceinline__ float score_item_fq(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m,
+                                               const float (*lut)[256])
+{
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        float t = 0.0f;
+#pragma unroll
+        for (int h = 0; h < 2 * W; ++h) {
+            const uint32_t w = r.w[j][m][h];
+            t += lut[4 * h + 0][w & 255u];
+            t += lut[4 * h + 1][(w >> 8) & 255u];
+            t += lut[4 * h + 2][(w >> 16) & 255u];
+            t += lut[4 * h + 3][w >> 24];
+        }
+        if (MODE == kModeScaled) s = __fmaf_rn(r.a[j][m], t, s);
+        else s = __fmaf_rn(1.0f / (float)(1 << j), t, s);
+    }
+    return MODE == kModeDyadicNorm ? s * r.a[0][m] : s;
+}
+
+template <int W, int P, int MODE>
+__global__ __launch_bounds__(kBlock) void scan_exact_fq(const FqArgs a)
+{
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ float s_lut[8 * W][256];
+    constexpr int S = scale_arrays(MODE, P);
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    for (int i = threadIdx.x; i < 8 * W * 256; i += kBlock) (&s_lut[0][0])[i] = a.lut[i];
+    __syncthreads();
+
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    const uint64_t tau = a.tau_ptr[0];
+    const float taus = threshold_score(tau);
+    uint32_t fill = 0;
+    RowRegs<W, P, S> cur, nxt;
+    load_row<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    for (;;) {
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+        float s[kItemsPerLane];
+        bool any = false;
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            s[m] = score_item_fq<W, P, MODE>(cur, m, s_lut);
+            any |= (s[m] >= taus);
+        }
+        if (__ballot(any)) {
+            const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                const uint64_t id = row_id + lane_item<W>(lane, m);
+                bool ok = (s[m] >= taus) && (id < a.n_items);
+                uint64_t key = 0;
+                if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
+                fill = stage_append<true>(ok, key, 0, s_keys, nullptr, fill, a.out, lane);
+            }
+        }
+        if (!has_next) break;
+        cur = nxt;
+        p = pn;
+    }
+    if (fill) stage_flush<true>(s_keys, nullptr, fill, a.out, lane);
+}
+
+template <int W, int P, int MODE>
+__global__ void dense_scores_fq(const char* __restrict__ tiles, const Layout l, const float* __restrict__ lut,
+                                uint64_t first, uint64_t count, float* __restrict__ out)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const uint64_t z = first + t;
+    constexpr int S = scale_arrays(MODE, P);
+    const TileGeom g{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const char* tile = tiles + (size_t)tile_to_phys(l, (uint32_t)(z / kTileItems)) * g.tile_bytes();
+    const uint32_t o = (uint32_t)(z % kTileItems);
+    RowRegs<W, P, S> r;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const uint32_t* pw = reinterpret_cast<const uint32_t*>(tile + j * g.plane_bytes()) + (size_t)o * 2 * W;
+#pragma unroll
+        for (int h = 0; h < 2 * W; ++h) r.w[j][0][h] = pw[h];
+    }
+#pragma unroll
+    for (int j = 0; j < S; ++j) r.a[j][0] = reinterpret_cast<const float*>(tile + g.scales_offset())[j * kTileItems + o];
+    out[t] = score_item_fq<W, P, MODE>(r, 0, reinterpret_cast<const float (*)[256]>(lut));
+}
+
 // fp32 score of one query for items first .. first+count (test hook); same arithmetic as the scan.
 template <int W, int P, int PQ, int MODE>
 __global__ void dense_scores(const char* __restrict__ tiles, const Layout l,
@@ -202,6 +301,77 @@ DenseFn dense_fn(const KernelSel& k)
 }
 
 }  // namespace
+
+namespace {
+using FqFn = void (*)(const FqArgs);
+using DenseFqFn = void (*)(const char*, const Layout, const float*, uint64_t, uint64_t, float*);
+
+template <int W, int P>
+FqFn fq_fn_m(int mode)
+{
+    if (mode == kModeScaled) return scan_exact_fq<W, P, kModeScaled>;
+    if constexpr (dyadic_supported(W)) {
+        if (mode == kModeDyadicNorm) return scan_exact_fq<W, P, kModeDyadicNorm>;
+        if (mode == kModeDyadic) return scan_exact_fq<W, P, kModeDyadic>;
+    }
+    return nullptr;
+}
+
+template <int W, int P>
+DenseFqFn dense_fq_fn_m(int mode)
+{
+    if (mode == kModeScaled) return dense_scores_fq<W, P, kModeScaled>;
+    if constexpr (dyadic_supported(W)) {
+        if (mode == kModeDyadicNorm) return dense_scores_fq<W, P, kModeDyadicNorm>;
+        if (mode == kModeDyadic) return dense_scores_fq<W, P, kModeDyadic>;
+    }
+    return nullptr;
+}
+}  // namespace
+
+template <>
+hipError_t launch_scan_exact_fq_w<RBE_W>(const KernelSel& k, const FqArgs& a, uint32_t n_cu, uint32_t per_cu,
+                                         hipStream_t st, uint32_t* grid_out)
+{
+    FqFn fn = nullptr;
+    switch (k.P) {
+        case 1: fn = fq_fn_m<RBE_W, 1>(k.mode); break;
+        case 2: fn = fq_fn_m<RBE_W, 2>(k.mode); break;
+        case 3: fn = fq_fn_m<RBE_W, 3>(k.mode); break;
+        case 4: fn = fq_fn_m<RBE_W, 4>(k.mode); break;
+        default: break;
+    }
+    if (!fn) return hipErrorInvalidValue;
+    if (a.p_end <= a.p_begin) return hipSuccess;
+    if (per_cu == 0) {
+        int nb = 0;
+        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0);
+        if (e != hipSuccess) return e;
+        per_cu = (uint32_t)(nb > 0 ? nb : 1);
+    }
+    const uint32_t units = a.p_end - a.p_begin;
+    const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;
+    if (grid_out) *grid_out = grid;
+    fn<<<dim3(grid), dim3(kBlock), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+template <>
+hipError_t launch_dense_scores_fq_w<RBE_W>(const KernelSel& k, const char* tiles, const Layout& l, const float* lut,
+                                           uint64_t first, uint64_t count, float* out, hipStream_t st)
+{
+    DenseFqFn fn = nullptr;
+    switch (k.P) {
+        case 1: fn = dense_fq_fn_m<RBE_W, 1>(k.mode); break;
+        case 2: fn = dense_fq_fn_m<RBE_W, 2>(k.mode); break;
+        case 3: fn = dense_fq_fn_m<RBE_W, 3>(k.mode); break;
+        case 4: fn = dense_fq_fn_m<RBE_W, 4>(k.mode); break;
+        default: break;
+    }
+    if (!fn) return hipErrorInvalidValue;
+    fn<<<dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, st>>>(tiles, l, lut, first, count, out);
+    return hipGetLastError();
+}
 
 template <>
 hipError_t launch_scan_exact_w<RBE_W>(const KernelSel& k, const ScanArgs& a, uint32_t n_cu, uint32_t per_cu,

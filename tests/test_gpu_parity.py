@@ -505,3 +505,67 @@ def test_encode_chunk_rejected_for_dyadic_index():
         rbe.rbe_encode_chunk(ix, 0, np.zeros((100, 64), np.float32))
     assert e.value.code == rbe.RBE_EUNSUPPORTED
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ hybrid scoring: fp32 query x binary items
+def check_topk_float(planes, scales, q, k, ids, scores):
+    """Same acceptance protocol as check_topk, against the oracle's hybrid score."""
+    N = planes.shape[1]
+    m = min(k, N)
+    assert np.all(ids[m:] == -1) and np.all(np.isneginf(scores[m:]))
+    got = ids[:m]
+    assert got.min() >= 0 and got.max() < N and np.unique(got).size == m
+    o_ids, o_sc = oracle.topk_fq(planes, scales, q, k)
+    floor = 1e-6 * float(np.sum(np.abs(q))) * float(np.max(np.sum(scales.astype(np.float64), axis=0)))
+    s_k = o_sc[m - 1]
+    eps = max(1e-5 * abs(s_k), floor)
+    true_sc = oracle.scores_at_fq(planes, scales, q, got)
+    np.testing.assert_allclose(scores[:m], true_sc, rtol=1e-5, atol=floor)
+    assert np.all(true_sc >= s_k - eps)
+    assert set(o_ids[:m][o_sc[:m] > s_k + eps].tolist()) <= set(got.tolist())
+    sc = scores[:m]
+    assert np.all(sc[:-1] >= sc[1:])
+    same = sc[:-1] == sc[1:]
+    assert np.all(got[:-1][same] < got[1:][same])
+
+
+@pytest.mark.parametrize("N,d,P,Q,k", [(1, 64, 1, 1, 1), (5000, 64, 3, 3, 100), (150_001, 64, 3, 2, 1000),
+                                       (60_000, 128, 4, 2, 300), (20_000, 256, 2, 1, 50)])
+def test_float_query_search(N, d, P, Q, k):
+    c = rbe_synth.centres_numpy(32, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=30 + N)
+    q = rbe_synth.vectors_numpy(Q, c, 0.3, seed=31)
+    planes, scales = oracle.encode(x, P)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    dense = rbe.rbe_debug_scores_float(ix, q[0], 0, N).astype(np.float64)
+    ref = oracle.scores_fq(planes, scales, q[0])
+    tol = 1e-6 * float(np.sum(np.abs(q[0]))) * np.sum(scales.astype(np.float64), axis=0)
+    assert np.all(np.abs(dense - ref) <= np.maximum(tol, 1e-5 * np.abs(ref)))
+    ids, sc = rbe.rbe_search_float(ix, q, k)
+    for i in range(Q):
+        check_topk_float(planes, scales, q[i], k, ids[i], sc[i])
+    with pytest.raises(rbe.RbeError) as e:
+        rbe.rbe_search_float(ix, q, k, mode=rbe.RBE_SELECT_NEARLOSSLESS)
+    assert e.value.code == rbe.RBE_EUNSUPPORTED
+    rbe.rbe_free(ix)
+
+
+def test_float_query_on_dyadic_index_and_hybrid_beats_binary_query():
+    rng = np.random.default_rng(32)
+    N, d = 80_000, 64
+    c = rbe_synth.centres_numpy(16, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=33)
+    q = rbe_synth.vectors_numpy(4, c, 0.3, seed=34)
+    planes, _ = oracle.encode(x, 2)
+    w = dyadic_weights(2, N)
+    folded = oracle.fold_cosine(planes, w)
+    ix = rbe.rbe_load_corpus(planes, None, flags=rbe.RBE_DYADIC | rbe.RBE_COSINE)
+    ids, sc = rbe.rbe_search_float(ix, q, 200)
+    for i in range(4):
+        check_topk_float(planes, folded, q[i], 200, ids[i], sc[i])
+    rbe.rbe_free(ix)
+    ix = rbe.rbe_load_corpus(planes, None, flags=rbe.RBE_DYADIC)
+    ids, sc = rbe.rbe_search_float(ix, q, 200)
+    for i in range(4):
+        check_topk_float(planes, w, q[i], 200, ids[i], sc[i])
+    rbe.rbe_free(ix)
