@@ -144,6 +144,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-nearlossless", action="store_true")
     ap.add_argument("--no-paper-point", action="store_true")
+    ap.add_argument("--no-hybrid", action="store_true")
     ap.add_argument("--paper-items", type=int, default=136 * 136 * 256 * 256)
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also launch the plain copy kernel of this size 5 times (yardstick for rocprofv3 counters)")
@@ -246,6 +247,25 @@ def main():
             "recall_predicted_appendix_a": predicted, "queries": len(recalls),
         }
         log(f"near-lossless I={I}: {n_ms:.3f} ms/step, recall {np.mean(recalls):.5f} (Appendix A: {predicted:.5f})")
+
+    # ---------------- hybrid scoring: fp32 query against the binary items (the paper's model m_5)
+    if not args.no_hybrid:
+        xq = rbe_synth.vectors_torch(args.warmup + args.steps, centres, args.sigma, rbe_synth.SEED_QUERIES, 0).cpu().numpy()
+        for s_ in range(args.warmup):
+            rbe.rbe_search_float(ix, xq[s_:s_ + 1], k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        h_scan = []
+        for s_ in range(args.warmup, args.warmup + args.steps):
+            rbe.rbe_search_float(ix, xq[s_:s_ + 1], k)
+            h_scan.append(rbe.rbe_get_search_stats(ix)["scan_ms"][-1])
+        torch.cuda.synchronize()
+        h_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        h_gbs = last_items * bytes_per_item / (float(np.mean(h_scan)) * 1e-3) / 1e9
+        out["hybrid_float_query"] = {"ms_per_step": h_ms, "value": N / (h_ms * 1e-3), "unit": "candidates/s",
+                                     "scan_kernel_ms": float(np.mean(h_scan)), "hbm_gbs": h_gbs,
+                                     "hbm_frac": h_gbs / HBM_PEAK_GBS}
+        log(f"hybrid fp32 query: {h_ms:.3f} ms/step, scan kernel {np.mean(h_scan):.3f} ms -> {h_gbs:.0f} GB/s")
 
     # ---------------- batch leg
     if args.batch > 0:

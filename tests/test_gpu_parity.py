@@ -569,3 +569,36 @@ def test_float_query_on_dyadic_index_and_hybrid_beats_binary_query():
     for i in range(4):
         check_topk_float(planes, w, q[i], 200, ids[i], sc[i])
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ near-lossless selector: group size sweep, id order
+@pytest.mark.parametrize("I", [64, 256, 1024])
+def test_nearlossless_recall_sweep_over_group_size(I):
+    N, k, Q = 2_097_152, 1000, 16
+    planes, scales, qp, qs = clustered(N, 64, 3, 256, 0.3, Q, 3, seed=12)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    exact, _ = rbe.rbe_search(ix, qp, qs, k)
+    near, _ = rbe.rbe_search(ix, qp, qs, k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=I)
+    rec = np.mean([oracle.recall(near[q], exact[q]) for q in range(Q)])
+    expect = oracle.expected_recall(k, N, I)
+    print(f"  I={I}: recall {rec:.4f}, Appendix A {expect:.4f}")
+    assert abs(rec - expect) < 4 * np.sqrt(expect * (1 - expect) / (k * Q)) + 3e-3, (I, rec, expect)
+    rbe.rbe_free(ix)
+
+
+def test_nearlossless_assumes_random_id_order():
+    """Appendix A places the relevant items uniformly at random.  With ids sorted by cluster the
+    true neighbours of a query are adjacent, share groups, and the selector loses most of them;
+    the exact mode is unaffected."""
+    N, k = 2_097_152, 1000
+    planes, scales, qp, qs = clustered(N, 64, 3, 256, 0.3, 4, 3, seed=13, sort_by_cluster=True)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    exact, esc = rbe.rbe_search(ix, qp, qs, k)
+    check_batch(planes, scales, qp, qs, k, exact, esc)
+    near, _ = rbe.rbe_search(ix, qp, qs, k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=256)
+    rec = np.mean([oracle.recall(near[q], exact[q]) for q in range(4)])
+    print(f"  cluster-sorted ids: recall {rec:.3f} (random order would give {oracle.expected_recall(k, N, 256):.3f})")
+    assert rec < 0.6
+    for q in range(4):
+        check_nearlossless(planes, scales, qp[q], qs[q], k, 256, near[q], _[q])
+    rbe.rbe_free(ix)
