@@ -21,6 +21,11 @@
  * The popcounts are exact integers; the combination is evaluated in fp32 in
  * the order written (i inner, j outer), each inner sum starting from
  * dim * sum_i c_i and accumulating -2 c_i * popcount with fused multiply-adds.
+ * With 4 or more queries per call (exact mode, dim <= 128) the same score is
+ * evaluated on the matrix cores instead, as sum_j a_j[z] * (qhat . b_z^j) with
+ * qhat = sum_i c_i b_q^i reconstructed on the host in double, scaled by a power
+ * of two and carried as two half-precision terms (about 22 bits), products
+ * exact, fp32 accumulation; it agrees with the formula above to ~1e-6 relative.
  *
  * Selection (Sec. 6).  Results are ordered by (score descending, id
  * ascending).  RBE_SELECT_EXACT returns exactly the k best under that order.
@@ -245,6 +250,11 @@ int rbe_debug_popcounts(rbe_index *ix, const uint64_t *q_planes, uint32_t q_n_pl
 int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
                      uint32_t q_n_planes, uint64_t first_item, uint64_t count,
                      float *out, void *hip_stream);
+
+/* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 4
+ * queries per call on, dim <= 128), 1 = always the XOR/popcount kernel, 2 = the
+ * matrix-core kernel for any number of queries (dim <= 128).                     */
+int rbe_debug_set_batch_path(rbe_index *ix, int path);
 
 /* fp32 hybrid scores (rbe_search_float arithmetic) of one fp32 query q [dim] for z in
  * [first_item, first_item+count): out [count] float (host).                  */

@@ -72,6 +72,7 @@ PROTOTYPES = {
     "rbe_set_tuning": (_i32, [_vp, _u32, _u32]),
     "rbe_debug_tile_to_phys": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_phys_to_tile": (_u32, [_u32, _u32, _u32]),
+    "rbe_debug_set_batch_path": (_i32, [_vp, _i32]),
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
@@ -348,6 +349,10 @@ def rbe_debug_tile_to_phys(n_tiles: int, sample_ratio: int, tile: int) -> int:
 
 def rbe_debug_phys_to_tile(n_tiles: int, sample_ratio: int, phys: int) -> int:
     return int(load_library().rbe_debug_phys_to_tile(n_tiles, sample_ratio, phys))
+
+
+def rbe_debug_set_batch_path(ix: Index, path: int):
+    _check(load_library().rbe_debug_set_batch_path(ix.handle, path))
 
 
 def rbe_debug_popcounts(ix: Index, q_planes, first_item: int, count: int, stream=None):

@@ -18,7 +18,8 @@ HEADERS = [os.path.join(CSRC, h) for h in ("rbe_kernels.hpp", "rbe_layout.hpp", 
 # (source, extra defines, object suffix)
 UNITS = [("rbe_api.hip", [], "api")] + \
         [("rbe_scan.hip", [f"-DRBE_W={w}"], f"scan_w{w}") for w in (1, 2, 4)] + \
-        [("rbe_group.hip", [f"-DRBE_W={w}"], f"group_w{w}") for w in (1, 2, 4)]
+        [("rbe_group.hip", [f"-DRBE_W={w}"], f"group_w{w}") for w in (1, 2, 4)] + \
+        [("rbe_batch.hip", [f"-DRBE_W={w}"], f"batch_w{w}") for w in (1, 2)]
 SOURCES = sorted({os.path.join(CSRC, u[0]) for u in UNITS})
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -72,6 +72,11 @@ struct rbe_index {
     uint64_t* d_kmax = nullptr;
     uint32_t* d_status = nullptr;
     uint32_t* d_seen = nullptr;     // [RBE_MAX_LEVELS][RBE_MAX_QUERIES]
+    uint32_t* d_aops = nullptr;     // matrix-core query operands (BatchArgs::a_ops)
+    uint32_t* h_aops = nullptr;
+    float* d_unscale = nullptr;     // [Q]
+    float* h_unscale = nullptr;
+    int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
     float* d_lut = nullptr;         // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
     float* h_lut = nullptr;
     uint32_t* d_qwords = nullptr;   // [Q][PQ][2W]
@@ -249,6 +254,68 @@ int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t s
             }
     }
     HIP_TRY(hipMemcpyAsync(ix->d_lut, ix->h_lut, (size_t)Q * per_q * sizeof(float), hipMemcpyHostToDevice, st));
+    return RBE_OK;
+}
+
+// Number of 16-query tiles the matrix-core scan is built for: 1, 2 or 4.
+uint32_t batch_tiles(uint32_t Q) { return Q <= 16 ? 1u : (Q <= 32 ? 2u : 4u); }
+
+bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query)
+{
+    if (mode != RBE_SELECT_EXACT || float_query || !rbe::batch_mfma_supported(ix->W)) return false;
+    if (ix->batch_path == 1) return false;
+    if (ix->batch_path == 2) return true;
+    return Q >= 4;   // below that the XOR/popcount kernel is at or near the HBM bound already
+}
+
+// Matrix-core operands of a batch: each query reconstructed in double as qhat = sum_i c_i b^i,
+// scaled by a power of two into [0.5, 1), split into two halves (hi = half(qhat), lo = half(qhat - hi)),
+// and laid out as lane l of the wave will load it: query (l % 16), dims 32*part + 8*(l / 16) + 0..7.
+int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
+                        hipStream_t st)
+{
+    const uint32_t W = ix->W, KP = 2 * W, NQT = batch_tiles(Q);
+    const size_t max_words = (size_t)4 * 2 * 4 * 64 * 4;   // NQT <= 4, parts <= 4
+    if (!ix->d_aops) {
+        HIP_TRY(hipMalloc(&ix->d_aops, max_words * sizeof(uint32_t)));
+        HIP_TRY(hipHostMalloc(&ix->h_aops, max_words * sizeof(uint32_t), hipHostMallocDefault));
+        HIP_TRY(hipMalloc(&ix->d_unscale, RBE_MAX_QUERIES * sizeof(float)));
+        HIP_TRY(hipHostMalloc(&ix->h_unscale, RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
+    }
+    const bool dyadic = ix->mode != rbe::kModeScaled;
+    const size_t n_words = (size_t)NQT * 2 * KP * 64 * 4;
+    std::memset(ix->h_aops, 0, n_words * sizeof(uint32_t));
+    uint16_t* halves = reinterpret_cast<uint16_t*>(ix->h_aops);
+    std::vector<double> qhat(ix->dim);
+    for (uint32_t q = 0; q < Q; ++q) {
+        double biggest = 0.0;
+        for (uint32_t d = 0; d < ix->dim; ++d) {
+            double v = 0.0;
+            for (uint32_t i = 0; i < PQ; ++i) {
+                const double c = dyadic ? std::ldexp(1.0, -(int)i) : (double)q_scales[(size_t)q * PQ + i];
+                const uint64_t word = q_planes[((size_t)q * PQ + i) * W + d / 64];
+                v += ((word >> (d % 64)) & 1ull) ? c : -c;
+            }
+            qhat[d] = v;
+            biggest = std::max(biggest, std::fabs(v));
+        }
+        const int k = biggest > 0.0 ? -(std::ilogb(biggest) + 1) : 0;   // qhat * 2^k lies in [0.5, 1)
+        ix->h_unscale[q] = std::ldexp(1.0f, -k);
+        const uint32_t qt = q / 16, row = q % 16;
+        for (uint32_t d = 0; d < ix->dim; ++d) {
+            const double v = std::ldexp(qhat[d], k);
+            const _Float16 hi = (_Float16)(float)v;
+            const _Float16 lo = (_Float16)(float)(v - (double)(float)hi);
+            const uint32_t part = d / 32, grp = (d % 32) / 8, t = d % 8, lane = grp * 16 + row;
+            uint16_t bits_hi, bits_lo;
+            std::memcpy(&bits_hi, &hi, 2);
+            std::memcpy(&bits_lo, &lo, 2);
+            halves[((((size_t)qt * 2 + 0) * KP + part) * 64 + lane) * 8 + t] = bits_hi;
+            halves[((((size_t)qt * 2 + 1) * KP + part) * 64 + lane) * 8 + t] = bits_lo;
+        }
+    }
+    HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, n_words * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, Q * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
 
@@ -518,6 +585,10 @@ void rbe_free(rbe_index* ix)
     (void)hipFree(ix->d_seen);
     (void)hipFree(ix->d_qwords);
     (void)hipFree(ix->d_lut);
+    (void)hipFree(ix->d_aops);
+    (void)hipFree(ix->d_unscale);
+    (void)hipHostFree(ix->h_aops);
+    (void)hipHostFree(ix->h_unscale);
     (void)hipHostFree(ix->h_lut);
     (void)hipFree(ix->d_qcoef);
     (void)hipHostFree(ix->h_qwords);
@@ -588,6 +659,7 @@ struct Round { uint32_t begin, end, stride, skip; };
 struct SearchCtx {
     rbe_index* ix; hipStream_t st; uint32_t Q, PQ, k, cap, mode, I;
     bool float_query;   // hybrid scoring: fp32 queries through byte tables
+    bool batch_mfma;    // exact mode, several queries: matrix-core scan
 };
 
 static int launch_scan_round(const SearchCtx& c, const Round& r)
@@ -609,6 +681,13 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
         }
+    } else if (c.batch_mfma) {
+        BatchArgs ba;
+        ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
+        ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.tau = ix->d_tau; ba.n_queries = c.Q;
+        ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
+        e = ix->W == 1 ? launch_scan_batch_w<1>(sel, ba, batch_tiles(c.Q), (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid)
+                       : launch_scan_batch_w<2>(sel, ba, batch_tiles(c.Q), (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
     } else if (c.mode == RBE_SELECT_EXACT) {
         ScanArgs sa;
         sa.tiles = ix->d_tiles; sa.layout = ix->layout; sa.n_items = ix->n_items;
@@ -758,6 +837,7 @@ static int search_prologue(rbe_index* ix, SearchCtx& c, uint32_t n_queries, uint
     c.ix = ix; c.st = (hipStream_t)hip_stream; c.Q = n_queries; c.PQ = 1; c.k = k; c.mode = mode;
     c.I = group_size_I ? group_size_I : 256;
     c.float_query = false;
+    c.batch_mfma = false;
     const uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->layout.ratio * k);
     c.cap = std::max<uint32_t>(cap, k + 2 * kTileItems);
     return ensure_workspace(ix, c.Q, k, c.cap);
@@ -775,6 +855,11 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
     c.PQ = q_n_planes;
     rc = stage_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
     if (rc) return rc;
+    c.batch_mfma = use_batch_mfma(ix, c.Q, mode, false);
+    if (c.batch_mfma) {
+        rc = stage_batch_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
+        if (rc) return rc;
+    }
     return run_search(c, ids_out, scores_out);
 }
 
@@ -813,6 +898,14 @@ int rbe_debug_scores_float(rbe_index* ix, const float* q, uint64_t first_item, u
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(d_out);
     if (e != hipSuccess) { set_error("rbe_debug_scores_float: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    return RBE_OK;
+}
+
+int rbe_debug_set_batch_path(rbe_index* ix, int path)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    ARG_CHECK(path >= 0 && path <= 2, "path must be 0 (auto), 1 (XOR/popcount) or 2 (matrix cores)");
+    ix->batch_path = path;
     return RBE_OK;
 }
 

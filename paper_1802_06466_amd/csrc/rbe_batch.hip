@@ -1,0 +1,274 @@
+// Batched exact-mode scan on the matrix cores, for one word count W (-DRBE_W=1|2).
+//
+// For several queries per call the scoring is a dense contraction: with the
+// query reconstructed as qhat = sum_i c_i b_q^i in R^d (Eq. 11 unrolled), Eq. 14 is
+//     s(q, z) = sum_j a_j[z] * ( qhat . b_z^j ),
+// i.e. per plane j a [queries x d] by [d x items] product whose right factor is
+// +-1.  One wave handles a row of 256 items: it stages the row's plane words and
+// scales in LDS, expands 8 bits at a time to eight +-1.0 halves through a 256-entry
+// table, and feeds v_mfma_f32_16x16x32_f16 with 16 queries x 16 items x 32 dims per
+// instruction.  qhat is scaled by a power of two into [0.5, 1) and split into two
+// halves (hi + lo, about 22 bits together), products are exact and accumulate in
+// fp32, so scores agree with the XOR/popcount path to about 1e-6 relative; the
+// binary dot products themselves are never rounded because they are never formed.
+// The per-pair VALU work drops from ~58 lane-ops to P fused multiply-adds and one
+// compare; bit expansion is paid once per item, whatever the number of queries.
+#include "rbe_internal.hpp"
+
+#ifndef RBE_W
+#error "compile with -DRBE_W=1|2"
+#endif
+
+namespace rbe {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Raw (still packed) row as it comes from memory: 16-byte plane loads, matching scale loads.
+template <int W, int P, int S>
+struct RawRow {
+    u32x4 pl[P][2 * W];                    // W=1: items (2l,2l+1) and (128+2l,129+2l); W=2: items m*64+l, m<4
+    float sc[S > 0 ? S : 1][kItemsPerLane];
+};
+
+template <int W, int P, int S>
+__device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restrict__ tile, int wave, int lane)
+{
+    const TileGeom g{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)wave * kRow * W;
+#pragma unroll
+        for (int s = 0; s < 2 * W; ++s) {
+            const uint64_t* src = (W == 1) ? pj + s * 128 + 2 * lane : pj + (size_t)(s * 64 + lane) * 2;
+            r.pl[j][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+        const float* sj = reinterpret_cast<const float*>(tile + g.scales_offset()) + j * kTileItems + wave * kRow;
+        if (W == 1) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const f32x2 a = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sj + s * 128 + 2 * lane));
+                r.sc[j][2 * s] = a.x; r.sc[j][2 * s + 1] = a.y;
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) r.sc[j][m] = __builtin_nontemporal_load(sj + m * 64 + lane);
+        }
+    }
+}
+
+template <int W, int P, int MODE, int NQT>
+__global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
+{
+    constexpr int S = scale_arrays(MODE, P);
+    constexpr int KP = 2 * W;                          // 32-dimension parts of a plane
+    __shared__ u32x4 s_lut[256];                       // byte -> eight +-1.0 halves (bit b -> half b)
+    __shared__ uint64_t s_pl[kWavesPerBlock][P][kRow * W];
+    __shared__ float s_sc[kWavesPerBlock][S > 0 ? S : 1][kRow];
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ uint8_t s_q_all[kWavesPerBlock][kStage];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int g = lane >> 4;       // lane group: which 8 dims of a 32-dim part / which 4 queries of a tile
+    const int col = lane & 15;     // item column inside a 16-item group, query row when loading A
+    uint64_t* s_keys = s_keys_all[wave];
+    uint8_t* s_q = s_q_all[wave];
+
+    {   // expansion table
+        const uint32_t v = threadIdx.x;
+        u32x4 e;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t lo = ((v >> (2 * t)) & 1u) ? 0x3C00u : 0xBC00u;
+            const uint32_t hi = ((v >> (2 * t + 1)) & 1u) ? 0x3C00u : 0xBC00u;
+            e[t] = lo | (hi << 16);
+        }
+        s_lut[v] = e;
+    }
+    __syncthreads();
+
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+
+    // query operands (16 queries per tile, hi and lo halves, KP parts), already in lane order
+    half8 A[NQT][2][KP];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+            for (int kp = 0; kp < KP; ++kp) {
+                const u32x4 v = reinterpret_cast<const u32x4*>(a.a_ops)[((qt * 2 + sp) * KP + kp) * 64 + lane];
+                A[qt][sp][kp] = __builtin_bit_cast(half8, v);
+            }
+    // this lane's queries: tile qt, rows 4g .. 4g+3.  Scores are formed in the query's scaled
+    // domain (qhat * 2^k); thresholds are moved there, survivors are moved back (both exact).
+    uint64_t tau[NQT][4];
+    float taus[NQT][4], unscale[NQT][4];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t q = qt * 16 + 4 * g + r;
+            if (q < a.n_queries) {
+                tau[qt][r] = a.tau[q];
+                unscale[qt][r] = a.q_unscale[q];
+                taus[qt][r] = threshold_score(tau[qt][r]) / unscale[qt][r];
+            } else {
+                tau[qt][r] = ~0ull; unscale[qt][r] = 1.0f; taus[qt][r] = __builtin_inff();
+            }
+        }
+
+    uint32_t fill = 0;
+    RawRow<W, P, S> cur, nxt;
+    load_raw<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    for (;;) {
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        if (has_next) load_raw<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+
+        // stage the row in this wave's LDS area, in item order
+#pragma unroll
+        for (int j = 0; j < P; ++j)
+#pragma unroll
+            for (int s = 0; s < 2 * W; ++s) {
+                uint64_t* dst = (W == 1) ? &s_pl[wave][j][s * 128 + 2 * lane] : &s_pl[wave][j][(s * 64 + lane) * 2];
+                *reinterpret_cast<u32x4*>(dst) = cur.pl[j][s];
+            }
+#pragma unroll
+        for (int j = 0; j < S; ++j)
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) s_sc[wave][j][lane_item<W>(lane, m)] = cur.sc[j][m];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+        for (int c = 0; c < kRow / 16; ++c) {
+            const int item = 16 * c + col;
+            floatx4 D[NQT][P];
+#pragma unroll
+            for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                for (int j = 0; j < P; ++j) D[qt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+                uint32_t part[KP];
+                if constexpr (W == 1) {
+                    const uint64_t w = s_pl[wave][j][item];
+                    part[0] = (uint32_t)w; part[1] = (uint32_t)(w >> 32);
+                } else {
+                    const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][j][item * 2]);
+                    part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
+                }
+#pragma unroll
+                for (int kp = 0; kp < KP; ++kp) {
+                    const half8 B = __builtin_bit_cast(half8, s_lut[(part[kp] >> (8 * g)) & 255u]);
+#pragma unroll
+                    for (int qt = 0; qt < NQT; ++qt) {
+                        D[qt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][0][kp], B, D[qt][j], 0, 0, 0);
+                        D[qt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][1][kp], B, D[qt][j], 0, 0, 0);
+                    }
+                }
+            }
+            float aj[P];
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+                if (MODE == kModeScaled) aj[j] = s_sc[wave][j][item];
+                else aj[j] = (MODE == kModeDyadicNorm ? s_sc[wave][0][item] : 1.0f) / (float)(1 << j);
+            }
+            float s[NQT][4];
+            bool any = false;
+#pragma unroll
+            for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < P; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
+                    s[qt][r] = v;
+                    any |= (v >= taus[qt][r]);
+                }
+            if (__ballot(any)) {
+                const uint64_t id = row_id + (uint64_t)item;
+#pragma unroll
+                for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        bool ok = (s[qt][r] >= taus[qt][r]) && (id < a.n_items);
+                        uint64_t key = 0;
+                        if (ok) { key = make_key(s[qt][r] * unscale[qt][r], (uint32_t)id); ok = key >= tau[qt][r]; }
+                        fill = stage_append<false>(ok, key, (uint32_t)(qt * 16 + 4 * g + r), s_keys, s_q, fill, a.out, lane);
+                    }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        if (!has_next) break;
+        cur = nxt;
+        p = pn;
+    }
+    if (fill) stage_flush<false>(s_keys, s_q, fill, a.out, lane);
+}
+
+namespace {
+using BatchFn = void (*)(const BatchArgs);
+
+template <int W, int P, int MODE>
+BatchFn batch_fn_q(uint32_t nqt)
+{
+    switch (nqt) {
+        case 1: return scan_batch_mfma<W, P, MODE, 1>;
+        case 2: return scan_batch_mfma<W, P, MODE, 2>;
+        case 4: return scan_batch_mfma<W, P, MODE, 4>;
+        default: return nullptr;
+    }
+}
+
+template <int W, int P>
+BatchFn batch_fn_m(int mode, uint32_t nqt)
+{
+    switch (mode) {
+        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt);
+        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt);
+        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt);
+        default: return nullptr;
+    }
+}
+}  // namespace
+
+template <>
+hipError_t launch_scan_batch_w<RBE_W>(const KernelSel& k, const BatchArgs& a, uint32_t n_query_tiles, uint32_t n_cu,
+                                      uint32_t per_cu, hipStream_t st, uint32_t* grid_out)
+{
+    BatchFn fn = nullptr;
+    switch (k.P) {
+        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles); break;
+        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles); break;
+        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles); break;
+        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles); break;
+        default: break;
+    }
+    if (!fn) return hipErrorInvalidValue;
+    if (a.p_end <= a.p_begin) return hipSuccess;
+    if (per_cu == 0) {
+        int nb = 0;
+        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0);
+        if (e != hipSuccess) return e;
+        per_cu = (uint32_t)(nb > 0 ? nb : 1);
+    }
+    const uint32_t units = a.p_end - a.p_begin;
+    const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;
+    if (grid_out) *grid_out = grid;
+    fn<<<dim3(grid), dim3(kBlock), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace rbe

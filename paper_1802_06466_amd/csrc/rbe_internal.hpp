@@ -39,6 +39,16 @@ template <int W>
 hipError_t launch_dense_scores_fq_w(const KernelSel& k, const char* tiles, const Layout& l, const float* lut,
                                     uint64_t first, uint64_t count, float* out, hipStream_t st);
 
+// Batched exact scan on the matrix cores; n_query_tiles in {1, 2, 4} (16 queries each).  Built for W <= 2.
+template <int W>
+hipError_t launch_scan_batch_w(const KernelSel& k, const BatchArgs& a, uint32_t n_query_tiles, uint32_t n_cu,
+                               uint32_t per_cu, hipStream_t st, uint32_t* grid_out);
+template <> hipError_t launch_scan_batch_w<1>(const KernelSel&, const BatchArgs&, uint32_t, uint32_t, uint32_t,
+                                              hipStream_t, uint32_t*);
+template <> hipError_t launch_scan_batch_w<2>(const KernelSel&, const BatchArgs&, uint32_t, uint32_t, uint32_t,
+                                              hipStream_t, uint32_t*);
+constexpr bool batch_mfma_supported(uint32_t W) { return W <= 2; }
+
 #define RBE_DECLARE_W(Wv)                                                                                         \
     template <> hipError_t launch_scan_exact_w<Wv>(const KernelSel&, const ScanArgs&, uint32_t, uint32_t,         \
                                                    hipStream_t, uint32_t*);                                       \

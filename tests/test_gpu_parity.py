@@ -442,10 +442,14 @@ def test_dyadic_with_stored_inverse_norm(d, P, Pq):
     dense = rbe.rbe_debug_scores(ix, qp[0], None, 0, N)
     # an exact integer combination times one fp32 factor: a single rounding on the GPU, none in the oracle
     np.testing.assert_array_equal(dense, oracle.scores(planes, folded, qp[0], qs[0]).astype(np.float32))
+    ids, sc = rbe.rbe_search(ix, qp, None, 1000)                 # 5 queries: matrix-core kernel
+    check_batch(planes, folded, qp, qs, 1000, ids, sc)
+    rbe.rbe_debug_set_batch_path(ix, 1)                          # XOR/popcount kernel for batch and single alike
     ids, sc = rbe.rbe_search(ix, qp, None, 1000)
     check_batch(planes, folded, qp, qs, 1000, ids, sc)
     ids1, sc1 = rbe.rbe_search(ix, qp[:1], None, 1000)
     np.testing.assert_array_equal(ids1[0], ids[0])
+    rbe.rbe_debug_set_batch_path(ix, 0)
     nl, nsc = rbe.rbe_search(ix, qp, None, 200, mode=rbe.RBE_SELECT_NEARLOSSLESS)
     for q in range(5):
         check_nearlossless(planes, folded, qp[q], qs[q], 200, 256, nl[q], nsc[q])
@@ -602,3 +606,45 @@ def test_nearlossless_assumes_random_id_order():
     for q in range(4):
         check_nearlossless(planes, scales, qp[q], qs[q], k, 256, near[q], _[q])
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ batched scan on the matrix cores
+@pytest.mark.parametrize("d,P,Pq,Q,k", [(64, 3, 3, 16, 1000), (64, 3, 3, 1, 100), (64, 2, 3, 5, 64), (64, 4, 4, 33, 500),
+                                        (64, 1, 1, 64, 10), (128, 4, 4, 17, 300), (128, 2, 1, 4, 50)])
+def test_matrix_core_batch_path_matches_oracle_and_popcount_path(d, P, Pq, Q, k):
+    N = 120_011
+    planes, scales, qp, qs = clustered(N, d, P, 64, 0.3, Q, Pq, seed=40 + Q)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    rbe.rbe_debug_set_batch_path(ix, 2)
+    ids_m, sc_m = rbe.rbe_search(ix, qp, qs, k)
+    check_batch(planes, scales, qp, qs, k, ids_m, sc_m)
+    rbe.rbe_debug_set_batch_path(ix, 1)
+    ids_v, sc_v = rbe.rbe_search(ix, qp, qs, k)
+    check_batch(planes, scales, qp, qs, k, ids_v, sc_v)
+    np.testing.assert_allclose(sc_m, sc_v, rtol=1e-5)
+    agree = np.mean([len(set(ids_m[q].tolist()) & set(ids_v[q].tolist())) / k for q in range(Q)])
+    assert agree > 0.995
+    rbe.rbe_free(ix)
+
+
+def test_matrix_core_batch_path_random_corpus_multi_level_and_dyadic():
+    rng = np.random.default_rng(41)
+    planes, scales = random_corpus(rng, 300_000, 64, 3)
+    qp, qs = random_queries(rng, 12, 64, 3)
+    ix = load_with_ratio(planes, scales, 8)
+    rbe.rbe_set_tuning(ix, cand_capacity=6144)
+    rbe.rbe_debug_set_batch_path(ix, 2)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 100)
+    assert rbe.rbe_get_search_stats(ix)["n_levels"] >= 3
+    check_batch(planes, scales, qp, qs, 100, ids, sc)
+    rbe.rbe_free(ix)
+    # dyadic weights: exact integers times powers of two survive the half split exactly
+    planes = rng.integers(0, 2**64, size=(2, 90_000, 1), dtype=np.uint64)
+    qp = rng.integers(0, 2**64, size=(20, 3, 1), dtype=np.uint64)
+    qs = np.tile(np.array([1.0, 0.5, 0.25], dtype=np.float32), (20, 1))
+    for flags, oscales in ((rbe.RBE_DYADIC, dyadic_weights(2, 90_000)),
+                           (rbe.RBE_DYADIC | rbe.RBE_COSINE, oracle.fold_cosine(planes, dyadic_weights(2, 90_000)))):
+        ix = rbe.rbe_load_corpus(planes, None, flags=flags)
+        ids, sc = rbe.rbe_search(ix, qp, None, 400)          # 20 queries: matrix cores by default
+        check_batch(planes, oscales, qp, qs, 400, ids, sc)
+        rbe.rbe_free(ix)
