@@ -281,6 +281,8 @@ def main():
         out["batch"] = {
             "queries_per_step": B, "steps": args.batch_steps, "ms_per_step": b_ms,
             "value": N * B * args.batch_steps / rb["wall_s"], "unit": "candidates/s",
+            "last_search_level_ms": {"scan": rb["stats"]["scan_ms"], "select": rb["stats"]["select_ms"]},
+            "gpu_ms_per_search": float(rb["total_gpu_ms"].mean()) if rb["total_gpu_ms"].size else None,
             "roofline": {"kernel": "scan_exact (finest level)", "bound": "alu", "achieved": ach,
                          "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-ops/s", "frac": ach / VALU_PEAK_TLANEOPS,
                          "kernel_ms": b_scan, "lane_ops_per_pair": lane_ops_per_pair(W, P, P),

@@ -21,6 +21,8 @@
 
 namespace rbe {
 
+constexpr int kBatchStage = 256;   // staged survivors per wave (all sub-queues together)
+
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -68,15 +70,16 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     __shared__ u32x4 s_lut[256];                       // byte -> eight +-1.0 halves (bit b -> half b)
     __shared__ uint64_t s_pl[kWavesPerBlock][P][kRow * W];
     __shared__ float s_sc[kWavesPerBlock][S > 0 ? S : 1][kRow];
-    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
-    __shared__ uint8_t s_q_all[kWavesPerBlock][kStage];
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kBatchStage];
+    __shared__ uint32_t s_cnt_all[kWavesPerBlock][16 * NQT + 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int g = lane >> 4;       // lane group: which 8 dims of a 32-dim part / which 4 queries of a tile
     const int col = lane & 15;     // item column inside a 16-item group, query row when loading A
-    uint64_t* s_keys = s_keys_all[wave];
-    uint8_t* s_q = s_q_all[wave];
+    const MultiStage ms{s_keys_all[wave], s_cnt_all[wave], (uint32_t)kBatchStage / (16u * NQT), 0u, 16u * NQT};
+    if (lane < 16 * NQT) s_cnt_all[wave][lane] = 0;
+    if (lane == 0) s_cnt_all[wave][16 * NQT] = 0;
 
     {   // expansion table
         const uint32_t v = threadIdx.x;
@@ -126,7 +129,6 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
             }
         }
 
-    uint32_t fill = 0;
     RawRow<W, P, S> cur, nxt;
     load_raw<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
     for (;;) {
@@ -150,6 +152,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
         __builtin_amdgcn_wave_barrier();
 
         const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+#pragma unroll 2
         for (int c = 0; c < kRow / 16; ++c) {
             const int item = 16 * c + col;
             floatx4 D[NQT][P];
@@ -204,7 +207,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                         bool ok = (s[qt][r] >= taus[qt][r]) && (id < a.n_items);
                         uint64_t key = 0;
                         if (ok) { key = make_key(s[qt][r] * unscale[qt][r], (uint32_t)id); ok = key >= tau[qt][r]; }
-                        fill = stage_append<false>(ok, key, (uint32_t)(qt * 16 + 4 * g + r), s_keys, s_q, fill, a.out, lane);
+                        mstage_append(ok, key, (uint32_t)(qt * 16 + 4 * g + r), ms, a.out, lane);
                     }
             }
         }
@@ -215,7 +218,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
         cur = nxt;
         p = pn;
     }
-    if (fill) stage_flush<false>(s_keys, s_q, fill, a.out, lane);
+    mstage_drain(ms, a.out, lane);
 }
 
 namespace {

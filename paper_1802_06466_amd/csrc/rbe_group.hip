@@ -28,14 +28,17 @@ template <int W, int P, int PQ, int QB, int MODE>
 __global__ __launch_bounds__(kBlock) void scan_groupmax(const GroupArgs a)
 {
     __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
-    __shared__ uint8_t s_q_all[kWavesPerBlock][kStage];
+    __shared__ uint32_t s_cnt_all[kWavesPerBlock][17];
     __shared__ float s_best[QB][kWavesPerBlock][kItemsPerLane][64];
     __shared__ uint32_t s_brow[QB][kWavesPerBlock][kItemsPerLane][64];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint64_t* s_keys = s_keys_all[wave];
-    uint8_t* s_q = s_q_all[wave];
+    // sub-queues for the (at most 4) queries of this launch; 16 counters keep the layout of the batch scan
+    const MultiStage ms{s_keys_all[wave], s_cnt_all[wave], (uint32_t)kStage / 16u, a.q_begin, 16u};
+    if (lane < 17) s_cnt_all[wave][lane] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     constexpr int S = scale_arrays(MODE, P);
     const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
     const float ninf = -__builtin_inff();
@@ -52,7 +55,6 @@ __global__ __launch_bounds__(kBlock) void scan_groupmax(const GroupArgs a)
         taus[b] = threshold_score(tau[b]);
     }
 
-    uint32_t fill = 0;
     for (uint32_t v = a.v_begin + blockIdx.x; v < a.v_end; v += gridDim.x) {
         const uint32_t x = (a.skip ? nth_non_multiple(v, a.skip) : v) * a.stride;
         const uint32_t row0 = x * a.I;
@@ -110,11 +112,11 @@ __global__ __launch_bounds__(kBlock) void scan_groupmax(const GroupArgs a)
                 key = make_key(ws, (uint32_t)id);
                 ok = key >= tau[b];
             }
-            fill = stage_append<false>(ok, key, a.q_begin + b, s_keys, s_q, fill, a.out, lane);
+            mstage_append(ok, key, (uint32_t)b, ms, a.out, lane);
         }
         __syncthreads();
     }
-    if (fill) stage_flush<false>(s_keys, s_q, fill, a.out, lane);
+    mstage_drain(ms, a.out, lane);
 }
 
 // ---------------------------------------------------------------- dispatch

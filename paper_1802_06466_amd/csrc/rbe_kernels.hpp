@@ -4,7 +4,7 @@
 //   QueryRegs/load_query per-query words and coefficients
 //   RowRegs/load_row     one lane's share of a 256-item row of a tile
 //   score_item           Eq. 14 by XOR/popcount (Sec. 5.1), three scoring modes
-//   stage_append/flush   per-wave LDS queue of survivors -> global candidate list
+//   stage_*1 / mstage_*  per-wave LDS queues of survivors -> global candidate lists
 //
 // Wavefronts are 64 wide.  One wave reads a "row" of 256 consecutive items per
 // step: every plane with 16-byte loads per lane (1 KiB contiguous per wave
@@ -213,70 +213,121 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
     return v;
 }
 
-template <bool SINGLE>
-__device__ __forceinline__ void stage_flush(uint64_t* s_keys, uint8_t* s_q, uint32_t fill, const CandList& a, int lane)
+// One query per launch: a single queue per wave.
+__device__ __forceinline__ void stage_flush1(uint64_t* s_keys, uint32_t fill, const CandList& a, int lane)
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (SINGLE) {
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(a.count, fill);
-        base = __shfl(base, 0);
-        uint64_t mx = 0;
-        for (uint32_t i = lane; i < fill; i += 64) {
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(a.count, fill);
+    base = __shfl(base, 0);
+    uint64_t mx = 0;
+    for (uint32_t i0 = 0; i0 < fill; i0 += 64) {   // wave-uniform trip count
+        const uint32_t i = i0 + (uint32_t)lane;
+        if (i < fill) {
             const uint32_t pos = base + i;
             const uint64_t key = s_keys[i];
             mx = key > mx ? key : mx;
             if (pos < a.cap) a.cand[pos] = key;  // the count keeps running so that overflow is seen
         }
-        mx = wave_max_u64(mx);
-        if (lane == 0) atomicMax((unsigned long long*)a.kmax, (unsigned long long)mx);
-    } else {
-        for (uint32_t i0 = 0; i0 < fill; i0 += 64) {
-            const uint32_t i = i0 + lane;
-            const bool valid = i < fill;
-            const uint64_t key = valid ? s_keys[i] : 0;
-            const uint32_t myq = valid ? s_q[i] : 0xFFFFFFFFu;
-            uint64_t todo = __ballot(valid);
-            while (todo) {  // one round per distinct query present in this group of 64
-                const int lead = __ffsll((long long)todo) - 1;
-                const uint32_t q0 = __shfl(myq, lead);
-                const uint64_t sel = __ballot(valid && myq == q0);
-                uint32_t base = 0;
-                if (lane == lead) base = atomicAdd(a.count + q0, (uint32_t)__popcll(sel));
-                base = __shfl(base, lead);
-                if (valid && myq == q0) {
-                    const uint32_t pos = base + (uint32_t)__popcll(sel & ((1ull << lane) - 1ull));
-                    if (pos < a.cap) a.cand[(size_t)q0 * a.cap + pos] = key;
-                }
-                const uint64_t mx = wave_max_u64((valid && myq == q0) ? key : 0);
-                if (lane == lead) atomicMax((unsigned long long*)(a.kmax + q0), (unsigned long long)mx);
-                todo &= ~sel;
-            }
-        }
     }
+    mx = wave_max_u64(mx);
+    if (lane == 0) atomicMax((unsigned long long*)a.kmax, (unsigned long long)mx);
     __builtin_amdgcn_wave_barrier();
 }
 
 // Must be reached by all lanes of the wave.  Returns the new fill level.
-template <bool SINGLE>
-__device__ __forceinline__ uint32_t stage_append(bool ok, uint64_t key, uint32_t q, uint64_t* s_keys, uint8_t* s_q,
-                                                 uint32_t fill, const CandList& a, int lane)
+__device__ __forceinline__ uint32_t stage_append1(bool ok, uint64_t key, uint64_t* s_keys, uint32_t fill,
+                                                  const CandList& a, int lane)
 {
     const uint64_t mask = __ballot(ok);
     if (mask == 0) return fill;
     const uint32_t n = (uint32_t)__popcll(mask);
     if (fill + n > (uint32_t)kStage) {
-        stage_flush<SINGLE>(s_keys, s_q, fill, a, lane);
+        stage_flush1(s_keys, fill, a, lane);
         fill = 0;
     }
-    if (ok) {
-        const uint32_t pos = fill + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        s_keys[pos] = key;
-        if (!SINGLE) s_q[pos] = (uint8_t)q;
-    }
+    if (ok) s_keys[fill + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = key;
     return fill + n;
 }
+
+// Several queries per launch: the wave's queue is split into one sub-queue per query
+// (`qcap` entries each, counters in LDS), so that a flush reserves a whole sub-queue in
+// the query's global list with ONE atomic.  With a queue shared by all queries every group
+// of 64 staged entries held up to 16 different queries and needed as many atomics; thousands
+// of waves then serialised on the few per-query counters.
+struct MultiStage {
+    uint64_t* keys;    // [n_sub][qcap] this wave's LDS
+    uint32_t* cnt;     // [n_sub + 1]: fill of each sub-queue, then a spare word (see mstage_append)
+    uint32_t qcap;     // entries per sub-queue (power of two)
+    uint32_t q_base;   // global query index of sub-queue 0
+    uint32_t n_sub;    // sub-queues
+};
+
+// Moves the first n entries of sub-queue q to the global list.  All lanes of the wave.
+__device__ __forceinline__ void mstage_flush_query(const MultiStage& ms, uint32_t q, uint32_t n, const CandList& a,
+                                                   int lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t gq = ms.q_base + q;
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(a.count + gq, n);
+    base = __shfl(base, 0);
+    uint64_t mx = 0;
+    if ((uint32_t)lane < n) {   // n <= qcap <= 64
+        const uint32_t pos = base + (uint32_t)lane;
+        mx = ms.keys[q * ms.qcap + (uint32_t)lane];
+        if (pos < a.cap) a.cand[(size_t)gq * a.cap + pos] = mx;
+    }
+    mx = wave_max_u64(mx);
+    if (lane == 0) atomicMax((unsigned long long*)(a.kmax + gq), (unsigned long long)mx);
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Queues `key` for sub-queue q of every lane with ok == true.  All lanes of the wave.
+//
+// Written without a branch on per-lane state around the wave-wide steps: the loop state is the wave-uniform mask
+// `pend` of lanes still holding an entry, and lanes with nothing to draw increment a spare counter (index n_sub)
+// instead of skipping the atomic.  With `if (ok) pos = atomicAdd(...)` in front of the loop the compiler split the
+// loop by that condition and the two halves of the wave ran the ballots and flushes separately.
+__device__ __forceinline__ void mstage_append(bool ok, uint64_t key, uint32_t q, const MultiStage& ms, const CandList& a,
+                                              int lane)
+{
+    uint64_t pend = __ballot(ok);
+    if (pend == 0) return;
+    uint32_t pos = atomicAdd(&ms.cnt[ok ? q : ms.n_sub], 1u);
+    for (;;) {
+        const bool fits = ((pend >> lane) & 1ull) != 0 && pos < ms.qcap;
+        if (fits) ms.keys[q * ms.qcap + pos] = key;
+        pend &= ~__ballot(fits);
+        if (pend == 0) break;
+        // a sub-queue is full (its counter overshot): flush it, reset it, let its lanes draw again
+        const int lead = __ffsll((long long)pend) - 1;
+        const uint32_t q0 = __shfl(q, lead);
+        mstage_flush_query(ms, q0, ms.qcap, a, lane);
+        if (lane == lead) ms.cnt[q0] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const bool again = ((pend >> lane) & 1ull) != 0 && q == q0;
+        const uint32_t drawn = atomicAdd(&ms.cnt[again ? q0 : ms.n_sub], 1u);
+        pos = again ? drawn : pos;
+    }
+}
+
+// End of kernel: flush whatever is left.  All lanes of the wave.
+__device__ __forceinline__ void mstage_drain(const MultiStage& ms, const CandList& a, int lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t q = 0; q < ms.n_sub; ++q) {
+        const uint32_t n = ms.cnt[q];
+        if (n) mstage_flush_query(ms, q, n < ms.qcap ? n : ms.qcap, a, lane);
+    }
+}
+
+// Sub-queue count for n queries: 16, 32 or 64 (power of two so that qcap is one too).
+__device__ __forceinline__ uint32_t sub_queues_for(uint32_t n) { return n <= 16 ? 16u : (n <= 32 ? 32u : 64u); }
 
 // ---------------------------------------------------------------- kernel arguments
 struct ScanArgs {

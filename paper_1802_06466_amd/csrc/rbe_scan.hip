@@ -12,7 +12,7 @@ namespace rbe {
 template <int W, int P, int PQ, bool SINGLE, int MODE>
 __device__ __forceinline__ uint32_t score_and_stage(RowRegs<W, P, scale_arrays(MODE, P)>& cur, const QueryRegs<W, PQ>& qr, uint64_t tau,
                                                     float taus, uint32_t q, uint32_t p, int wave, int lane,
-                                                    uint64_t* s_keys, uint8_t* s_q, uint32_t fill, const ScanArgs& a)
+                                                    uint64_t* s_keys, const MultiStage& ms, uint32_t fill, const ScanArgs& a)
 {
     float s[kItemsPerLane];
     bool any = false;
@@ -40,7 +40,8 @@ __device__ __forceinline__ uint32_t score_and_stage(RowRegs<W, P, scale_arrays(M
             bool ok = (s[m] >= taus) && (id < a.n_items);
             uint64_t key = 0;
             if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
-            fill = stage_append<SINGLE>(ok, key, q, s_keys, s_q, fill, a.out, lane);
+            if (SINGLE) fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
+            else mstage_append(ok, key, q, ms, a.out, lane);
         }
     }
     return fill;
@@ -58,12 +59,20 @@ template <int W, int P, int PQ, bool SINGLE, int MODE>
 __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
 {
     __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
-    __shared__ uint8_t s_q_all[SINGLE ? 1 : kWavesPerBlock][SINGLE ? 1 : kStage];
+    __shared__ uint32_t s_cnt_all[SINGLE ? 1 : kWavesPerBlock][SINGLE ? 1 : 65];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     uint64_t* s_keys = s_keys_all[wave];
-    uint8_t* s_q = SINGLE ? s_q_all[0] : s_q_all[wave];
+    MultiStage ms{};
+    if (!SINGLE) {
+        const uint32_t n_sub = sub_queues_for(a.n_queries);
+        ms = MultiStage{s_keys, s_cnt_all[wave], (uint32_t)kStage / n_sub, 0u, n_sub};
+        s_cnt_all[wave][lane] = 0;
+        if (lane == 0) s_cnt_all[wave][64] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
     const uint32_t G = gridDim.x;
     constexpr int S = scale_arrays(MODE, P);
     const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
@@ -83,7 +92,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
             const uint32_t pn = p + G;
             const bool has_next = pn < a.p_end;
             if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
-            fill = score_and_stage<W, P, PQ, SINGLE, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, s_q, fill, a);
+            fill = score_and_stage<W, P, PQ, SINGLE, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
             if (!has_next) break;
             cur = nxt;
             p = pn;
@@ -106,11 +115,12 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
                     tau_n = a.tau[q + 1];
                 }
                 fill = score_and_stage<W, P, PQ, SINGLE, MODE>(cur, qr, tau, threshold_score(tau), q, p, wave, lane,
-                                                         s_keys, s_q, fill, a);
+                                                         s_keys, ms, fill, a);
             }
         }
     }
-    if (fill) stage_flush<SINGLE>(s_keys, s_q, fill, a.out, lane);
+    if (SINGLE) { if (fill) stage_flush1(s_keys, fill, a.out, lane); }
+    else mstage_drain(ms, a.out, lane);
 }
 
 
@@ -180,14 +190,14 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq(const FqArgs a)
                 bool ok = (s[m] >= taus) && (id < a.n_items);
                 uint64_t key = 0;
                 if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
-                fill = stage_append<true>(ok, key, 0, s_keys, nullptr, fill, a.out, lane);
+                fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
             }
         }
         if (!has_next) break;
         cur = nxt;
         p = pn;
     }
-    if (fill) stage_flush<true>(s_keys, nullptr, fill, a.out, lane);
+    if (fill) stage_flush1(s_keys, fill, a.out, lane);
 }
 
 template <int W, int P, int MODE>

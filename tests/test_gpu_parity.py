@@ -381,6 +381,23 @@ def test_nearlossless_multi_level_and_slow_path():
     rbe.rbe_free(ix); rbe.rbe_free(ix2)
 
 
+@pytest.mark.parametrize("Q", [1, 3])
+def test_nearlossless_many_super_blocks_per_workgroup(Q):
+    """More super-blocks than workgroups and a large k: every wave forwards group winners over
+    many iterations, so its per-query staging queues fill up and are flushed in the middle of
+    the kernel, with one query (wave-uniform queue index) and with several."""
+    N, I, k = 6_000_123, 2, 4000
+    rng = np.random.default_rng(99 + Q)
+    planes, scales = random_corpus(rng, N, 64, 1)
+    qp, qs = random_queries(rng, Q, 64, 1)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=I)
+    assert not rbe.rbe_get_search_stats(ix)["fallback"]
+    for q in range(Q):
+        check_nearlossless(planes, scales, qp[q], qs[q], k, I, ids[q], sc[q])
+    rbe.rbe_free(ix)
+
+
 def test_nearlossless_recall_tracks_appendix_a():
     """Random-order ids: recall of the GPU near-lossless selector against the GPU exact
     selector, averaged over queries, agrees with E[M]/N of Appendix A."""
