@@ -16,10 +16,14 @@ LIB = os.path.join(HERE, "librbe_hip.so")
 HEADERS = [os.path.join(CSRC, h) for h in ("rbe_kernels.hpp", "rbe_layout.hpp", "rbe_internal.hpp",
                                            "rbe_misc_kernels.hpp")] + [os.path.join(ROOT, "include", "rbe.h")]
 # (source, extra defines, object suffix)
+# The matrix-core kernel reads every accumulator with ordinary vector instructions right after the MFMAs:
+# keep the accumulators in the ordinary register file (gfx950 has one unified file) instead of copying
+# each result out of the accumulation registers first.
+MFMA_VGPR = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
 UNITS = [("rbe_api.hip", [], "api")] + \
         [("rbe_scan.hip", [f"-DRBE_W={w}"], f"scan_w{w}") for w in (1, 2, 4)] + \
         [("rbe_group.hip", [f"-DRBE_W={w}"], f"group_w{w}") for w in (1, 2, 4)] + \
-        [("rbe_batch.hip", [f"-DRBE_W={w}"], f"batch_w{w}") for w in (1, 2)]
+        [("rbe_batch.hip", [f"-DRBE_W={w}", *MFMA_VGPR], f"batch_w{w}") for w in (1, 2)]
 SOURCES = sorted({os.path.join(CSRC, u[0]) for u in UNITS})
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

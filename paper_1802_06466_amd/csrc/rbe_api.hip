@@ -257,8 +257,15 @@ int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t s
     return RBE_OK;
 }
 
-// Number of 16-query tiles the matrix-core scan is built for: 1, 2 or 4.
-uint32_t batch_tiles(uint32_t Q) { return Q <= 16 ? 1u : (Q <= 32 ? 2u : 4u); }
+// 16-query tiles of a batch, and how many of them one launch of the matrix-core scan takes (1 or 2): two while
+// the query operands of both fit in about 64 registers.  Per tile they take 4 registers per 32-dimension part,
+// times two halves (general scales) or times the item planes (dyadic modes).
+uint32_t batch_tiles(uint32_t Q) { return (Q + 15u) / 16u; }
+uint32_t batch_tiles_per_launch(const rbe_index* ix)
+{
+    const uint32_t per_tile = 4u * 2u * ix->W * (ix->mode == rbe::kModeScaled ? 2u : ix->P);
+    return 2u * per_tile <= 64u ? 2u : 1u;
+}
 
 bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query)
 {
@@ -275,7 +282,7 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
                         hipStream_t st)
 {
     const uint32_t W = ix->W, KP = 2 * W, NQT = batch_tiles(Q);
-    const size_t max_words = (size_t)4 * 2 * 4 * 64 * 4;   // NQT <= 4, parts <= 4
+    const size_t max_words = (size_t)(RBE_MAX_QUERIES / 16) * 4 * 4 * 64 * 4;   // per tile: (terms x plane copies) x parts <= 16
     if (!ix->d_aops) {
         HIP_TRY(hipMalloc(&ix->d_aops, max_words * sizeof(uint32_t)));
         HIP_TRY(hipHostMalloc(&ix->h_aops, max_words * sizeof(uint32_t), hipHostMallocDefault));
@@ -283,7 +290,9 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
         HIP_TRY(hipHostMalloc(&ix->h_unscale, RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
     }
     const bool dyadic = ix->mode != rbe::kModeScaled;
-    const size_t n_words = (size_t)NQT * 2 * KP * 64 * 4;
+    // general scales: hi + lo halves of the query; dyadic modes: one exact half, one copy per item plane (x 2^-j)
+    const uint32_t TERMS = dyadic ? 1 : 2, PA = dyadic ? ix->P : 1;
+    const size_t n_words = (size_t)NQT * TERMS * PA * KP * 64 * 4;
     std::memset(ix->h_aops, 0, n_words * sizeof(uint32_t));
     uint16_t* halves = reinterpret_cast<uint16_t*>(ix->h_aops);
     std::vector<double> qhat(ix->dim);
@@ -303,15 +312,19 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
         ix->h_unscale[q] = std::ldexp(1.0f, -k);
         const uint32_t qt = q / 16, row = q % 16;
         for (uint32_t d = 0; d < ix->dim; ++d) {
-            const double v = std::ldexp(qhat[d], k);
-            const _Float16 hi = (_Float16)(float)v;
-            const _Float16 lo = (_Float16)(float)(v - (double)(float)hi);
-            const uint32_t part = d / 32, grp = (d % 32) / 8, t = d % 8, lane = grp * 16 + row;
-            uint16_t bits_hi, bits_lo;
-            std::memcpy(&bits_hi, &hi, 2);
-            std::memcpy(&bits_lo, &lo, 2);
-            halves[((((size_t)qt * 2 + 0) * KP + part) * 64 + lane) * 8 + t] = bits_hi;
-            halves[((((size_t)qt * 2 + 1) * KP + part) * 64 + lane) * 8 + t] = bits_lo;
+            const uint32_t part = d / 32, grp = (d % 32) / 8, e = d % 8, lane = grp * 16 + row;
+            for (uint32_t pa = 0; pa < PA; ++pa) {
+                const double v = std::ldexp(qhat[d], k - (int)pa);
+                const _Float16 hi = (_Float16)(float)v;
+                uint16_t bits;
+                std::memcpy(&bits, &hi, 2);
+                halves[(((((size_t)qt * TERMS + 0) * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
+                if (TERMS == 2) {
+                    const _Float16 lo = (_Float16)(float)(v - (double)(float)hi);
+                    std::memcpy(&bits, &lo, 2);
+                    halves[(((((size_t)qt * TERMS + 1) * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
+                }
+            }
         }
     }
     HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, n_words * sizeof(uint32_t), hipMemcpyHostToDevice, st));
@@ -686,8 +699,14 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
         ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.tau = ix->d_tau; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
-        e = ix->W == 1 ? launch_scan_batch_w<1>(sel, ba, batch_tiles(c.Q), (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid)
-                       : launch_scan_batch_w<2>(sel, ba, batch_tiles(c.Q), (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
+        e = hipSuccess;
+        const uint32_t tiles = batch_tiles(c.Q), per_launch = batch_tiles_per_launch(ix);
+        for (uint32_t t0 = 0; t0 < tiles && e == hipSuccess; t0 += per_launch) {   // one pass over the range per launch
+            const uint32_t nt = std::min(per_launch, tiles - t0);
+            ba.q_begin = 16u * t0;
+            e = ix->W == 1 ? launch_scan_batch_w<1>(sel, ba, nt, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid)
+                           : launch_scan_batch_w<2>(sel, ba, nt, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
+        }
     } else if (c.mode == RBE_SELECT_EXACT) {
         ScanArgs sa;
         sa.tiles = ix->d_tiles; sa.layout = ix->layout; sa.n_items = ix->n_items;

@@ -5,14 +5,22 @@
 //     s(q, z) = sum_j a_j[z] * ( qhat . b_z^j ),
 // i.e. per plane j a [queries x d] by [d x items] product whose right factor is
 // +-1.  One wave handles a row of 256 items: it stages the row's plane words and
-// scales in LDS, expands 8 bits at a time to eight +-1.0 halves through a 256-entry
-// table, and feeds v_mfma_f32_16x16x32_f16 with 16 queries x 16 items x 32 dims per
-// instruction.  qhat is scaled by a power of two into [0.5, 1) and split into two
-// halves (hi + lo, about 22 bits together), products are exact and accumulate in
-// fp32, so scores agree with the XOR/popcount path to about 1e-6 relative; the
-// binary dot products themselves are never rounded because they are never formed.
-// The per-pair VALU work drops from ~58 lane-ops to P fused multiply-adds and one
-// compare; bit expansion is paid once per item, whatever the number of queries.
+// scales in LDS and feeds v_mfma_f32_16x16x32_f16 with 16 queries x 16 items x 32
+// dims per instruction.
+//
+// Item operand.  Eight bits become eight +-1.0 halves through a 256-entry table in LDS:
+// one byte read, one shift (the table offset) and one 16-byte read per operand.  This
+// costs the vector ALU one instruction per operand; forming the halves arithmetically
+// costs four to eight, and on this chip vector instructions and MFMAs of one SIMD do
+// not overlap (the measured time per step is 4 cycles per vector instruction plus 16
+// per MFMA), so instruction count, not LDS traffic, is what the choice turns on.
+//
+// qhat is scaled by a power of two into [0.5, 1) and split into two halves (hi + lo,
+// about 22 bits together); products are exact and accumulate in fp32, so scores
+// agree with the XOR/popcount path to about 1e-6 relative; the binary dot products
+// themselves are never rounded because they are never formed.  The per-pair VALU
+// work drops from ~58 lane-ops to P fused multiply-adds and one compare; bit
+// expansion is paid once per item, whatever the number of queries.
 #include "rbe_internal.hpp"
 
 #ifndef RBE_W
@@ -67,6 +75,13 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
 {
     constexpr int S = scale_arrays(MODE, P);
     constexpr int KP = 2 * W;                          // 32-dimension parts of a plane
+    // General scales: one accumulator per plane (the item's a_j is applied afterwards) and the query as hi + lo.
+    // Dyadic modes: the plane weight 2^-j is folded into a per-plane copy of the query operand, all planes add
+    // into one accumulator, and the query (a short dyadic fraction) is exact in one half.
+    constexpr bool kDy = MODE != kModeScaled;
+    constexpr int TERMS = kDy ? 1 : 2;
+    constexpr int PA = kDy ? P : 1;
+    constexpr int PD = kDy ? 1 : P;
     __shared__ u32x4 s_lut[256];                       // byte -> eight +-1.0 halves (bit b -> half b)
     __shared__ uint64_t s_pl[kWavesPerBlock][P][kRow * W];
     __shared__ float s_sc[kWavesPerBlock][S > 0 ? S : 1][kRow];
@@ -77,7 +92,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     const int wave = threadIdx.x >> 6;
     const int g = lane >> 4;       // lane group: which 8 dims of a 32-dim part / which 4 queries of a tile
     const int col = lane & 15;     // item column inside a 16-item group, query row when loading A
-    const MultiStage ms{s_keys_all[wave], s_cnt_all[wave], (uint32_t)kBatchStage / (16u * NQT), 0u, 16u * NQT};
+    const MultiStage ms{s_keys_all[wave], s_cnt_all[wave], (uint32_t)kBatchStage / (16u * NQT), a.q_begin, 16u * NQT};
     if (lane < 16 * NQT) s_cnt_all[wave][lane] = 0;
     if (lane == 0) s_cnt_all[wave][16 * NQT] = 0;
 
@@ -101,32 +116,29 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     if (p >= a.p_end) return;
 
     // query operands (16 queries per tile, hi and lo halves, KP parts), already in lane order
-    half8 A[NQT][2][KP];
+    half8 A[NQT][TERMS][PA][KP];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp)
+        for (int sp = 0; sp < TERMS; ++sp)
 #pragma unroll
-            for (int kp = 0; kp < KP; ++kp) {
-                const u32x4 v = reinterpret_cast<const u32x4*>(a.a_ops)[((qt * 2 + sp) * KP + kp) * 64 + lane];
-                A[qt][sp][kp] = __builtin_bit_cast(half8, v);
-            }
-    // this lane's queries: tile qt, rows 4g .. 4g+3.  Scores are formed in the query's scaled
-    // domain (qhat * 2^k); thresholds are moved there, survivors are moved back (both exact).
-    uint64_t tau[NQT][4];
-    float taus[NQT][4], unscale[NQT][4];
+            for (int pa = 0; pa < PA; ++pa)
+#pragma unroll
+                for (int kp = 0; kp < KP; ++kp) {
+                    const u32x4 v =
+                        reinterpret_cast<const u32x4*>(a.a_ops)[((((a.q_begin / 16 + qt) * TERMS + sp) * PA + pa) * KP + kp) * 64 + lane];
+                    A[qt][sp][pa][kp] = __builtin_bit_cast(half8, v);
+                }
+    // this lane's queries: tile qt, rows 4g .. 4g+3 (query a.q_begin + 16 qt + 4g + r).  Scores are formed in the
+    // query's scaled domain (qhat * 2^k); thresholds are moved there, survivors are moved back (both exact).
+    // Only what the common path needs stays in registers; the rare survivor path re-reads the rest.
+    float taus[NQT][4];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const uint32_t q = qt * 16 + 4 * g + r;
-            if (q < a.n_queries) {
-                tau[qt][r] = a.tau[q];
-                unscale[qt][r] = a.q_unscale[q];
-                taus[qt][r] = threshold_score(tau[qt][r]) / unscale[qt][r];
-            } else {
-                tau[qt][r] = ~0ull; unscale[qt][r] = 1.0f; taus[qt][r] = __builtin_inff();
-            }
+            const uint32_t q = a.q_begin + qt * 16 + 4 * g + r;
+            taus[qt][r] = q < a.n_queries ? threshold_score(a.tau[q]) / a.q_unscale[q] : __builtin_inff();
         }
 
     RawRow<W, P, S> cur, nxt;
@@ -155,36 +167,32 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
 #pragma unroll 2
         for (int c = 0; c < kRow / 16; ++c) {
             const int item = 16 * c + col;
-            floatx4 D[NQT][P];
+            floatx4 D[NQT][PD];
 #pragma unroll
             for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-                for (int j = 0; j < P; ++j) D[qt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+                for (int j = 0; j < PD; ++j) D[qt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < P; ++j) {
-                uint32_t part[KP];
-                if constexpr (W == 1) {
-                    const uint64_t w = s_pl[wave][j][item];
-                    part[0] = (uint32_t)w; part[1] = (uint32_t)(w >> 32);
-                } else {
-                    const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][j][item * 2]);
-                    part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
-                }
+                // lane group g expands byte g of every 32-dimension part: dims 32 kp + 8 g + 0..7 of item `item`
+                const uint8_t* bytes = reinterpret_cast<const uint8_t*>(&s_pl[wave][j][item * W]) + g;
 #pragma unroll
                 for (int kp = 0; kp < KP; ++kp) {
-                    const half8 B = __builtin_bit_cast(half8, s_lut[(part[kp] >> (8 * g)) & 255u]);
+                    const half8 B = __builtin_bit_cast(half8, s_lut[bytes[4 * kp]]);
 #pragma unroll
-                    for (int qt = 0; qt < NQT; ++qt) {
-                        D[qt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][0][kp], B, D[qt][j], 0, 0, 0);
-                        D[qt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][1][kp], B, D[qt][j], 0, 0, 0);
-                    }
+                    for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                        for (int sp = 0; sp < TERMS; ++sp)
+                            D[qt][kDy ? 0 : j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][sp][kDy ? j : 0][kp], B,
+                                                                                       D[qt][kDy ? 0 : j], 0, 0, 0);
                 }
             }
             float aj[P];
+            if (MODE == kModeScaled) {
 #pragma unroll
-            for (int j = 0; j < P; ++j) {
-                if (MODE == kModeScaled) aj[j] = s_sc[wave][j][item];
-                else aj[j] = (MODE == kModeDyadicNorm ? s_sc[wave][0][item] : 1.0f) / (float)(1 << j);
+                for (int j = 0; j < P; ++j) aj[j] = s_sc[wave][j][item];
+            } else if (MODE == kModeDyadicNorm) {
+                aj[0] = s_sc[wave][0][item];
             }
             float s[NQT][4];
             bool any = false;
@@ -192,9 +200,16 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
             for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float v = 0.0f;
+                    float v;
+                    if (MODE == kModeScaled) {
+                        v = 0.0f;
 #pragma unroll
-                    for (int j = 0; j < P; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
+                        for (int j = 0; j < P; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
+                    } else if (MODE == kModeDyadicNorm) {
+                        v = aj[0] * D[qt][0][r];
+                    } else {
+                        v = D[qt][0][r];
+                    }
                     s[qt][r] = v;
                     any |= (v >= taus[qt][r]);
                 }
@@ -204,10 +219,14 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                 for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        bool ok = (s[qt][r] >= taus[qt][r]) && (id < a.n_items);
+                        bool ok = (s[qt][r] >= taus[qt][r]) && (id < a.n_items);   // false for padding queries
+                        const uint32_t ql = (uint32_t)(qt * 16 + 4 * g + r);
                         uint64_t key = 0;
-                        if (ok) { key = make_key(s[qt][r] * unscale[qt][r], (uint32_t)id); ok = key >= tau[qt][r]; }
-                        mstage_append(ok, key, (uint32_t)(qt * 16 + 4 * g + r), ms, a.out, lane);
+                        if (ok) {
+                            key = make_key(s[qt][r] * a.q_unscale[a.q_begin + ql], (uint32_t)id);
+                            ok = key >= a.tau[a.q_begin + ql];
+                        }
+                        mstage_append(ok, key, ql, ms, a.out, lane);
                     }
             }
         }
@@ -230,7 +249,6 @@ BatchFn batch_fn_q(uint32_t nqt)
     switch (nqt) {
         case 1: return scan_batch_mfma<W, P, MODE, 1>;
         case 2: return scan_batch_mfma<W, P, MODE, 2>;
-        case 4: return scan_batch_mfma<W, P, MODE, 4>;
         default: return nullptr;
     }
 }

@@ -39,7 +39,7 @@ template <int W>
 hipError_t launch_dense_scores_fq_w(const KernelSel& k, const char* tiles, const Layout& l, const float* lut,
                                     uint64_t first, uint64_t count, float* out, hipStream_t st);
 
-// Batched exact scan on the matrix cores; n_query_tiles in {1, 2, 4} (16 queries each).  Built for W <= 2.
+// Batched exact scan on the matrix cores; n_query_tiles in {1, 2} (16 queries each, from a.q_begin).  Built for W <= 2.
 template <int W>
 hipError_t launch_scan_batch_w(const KernelSel& k, const BatchArgs& a, uint32_t n_query_tiles, uint32_t n_cu,
                                uint32_t per_cu, hipStream_t st, uint32_t* grid_out);
