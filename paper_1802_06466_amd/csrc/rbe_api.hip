@@ -286,8 +286,8 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
     if (!ix->d_aops) {
         HIP_TRY(hipMalloc(&ix->d_aops, max_words * sizeof(uint32_t)));
         HIP_TRY(hipHostMalloc(&ix->h_aops, max_words * sizeof(uint32_t), hipHostMallocDefault));
-        HIP_TRY(hipMalloc(&ix->d_unscale, RBE_MAX_QUERIES * sizeof(float)));
-        HIP_TRY(hipHostMalloc(&ix->h_unscale, RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
+        HIP_TRY(hipMalloc(&ix->d_unscale, 2 * RBE_MAX_QUERIES * sizeof(float)));
+        HIP_TRY(hipHostMalloc(&ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
     }
     const bool dyadic = ix->mode != rbe::kModeScaled;
     // general scales: hi + lo halves of the query; dyadic modes: one exact half, one copy per item plane (x 2^-j)
@@ -308,27 +308,44 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
             qhat[d] = v;
             biggest = std::max(biggest, std::fabs(v));
         }
-        const int k = biggest > 0.0 ? -(std::ilogb(biggest) + 1) : 0;   // qhat * 2^k lies in [0.5, 1)
+        const int k = biggest > 0.0 ? -(std::ilogb(biggest) + 1) : 0;   // v = qhat * 2^k lies in (-1, 1)
         ix->h_unscale[q] = std::ldexp(1.0f, -k);
         const uint32_t qt = q / 16, row = q % 16;
-        for (uint32_t d = 0; d < ix->dim; ++d) {
-            const uint32_t part = d / 32, grp = (d % 32) / 8, e = d % 8, lane = grp * 16 + row;
-            for (uint32_t pa = 0; pa < PA; ++pa) {
-                const double v = std::ldexp(qhat[d], k - (int)pa);
-                const _Float16 hi = (_Float16)(float)v;
-                uint16_t bits;
-                std::memcpy(&bits, &hi, 2);
-                halves[(((((size_t)qt * TERMS + 0) * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
-                if (TERMS == 2) {
-                    const _Float16 lo = (_Float16)(float)(v - (double)(float)hi);
-                    std::memcpy(&bits, &lo, 2);
-                    halves[(((((size_t)qt * TERMS + 1) * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
+        double sum = 0.0;
+        // The kernel's B operand holds, for item bit b, the half whose only set bit is bit 10 + t (t = 0..3):
+        // 0 or val_t = 2^-14, 2^-13, 2^-11, 2^-7.  With rho = 2b - 1:
+        //     sum_d v_d rho_d = sum_d (2 v_d / val_t) (b_d val_t) - sum_d v_d,
+        // so the A operand carries 2 v_d / val_t (below 2^15) and the accumulator starts at -sum_d v_d.
+        // Lane (g, row) of 32-dimension part kp holds slot e = 2t + h; the kernel rotates the part's word left by
+        // 4g and takes bits 10 + t (h = 0) and 26 + t (h = 1), i.e. original bit (10 + 16h + t - 4g) mod 32.
+        static const int kValExp[4] = {-14, -13, -11, -7};
+        for (uint32_t part = 0; part < KP; ++part)
+            for (uint32_t grp = 0; grp < 4; ++grp)
+                for (uint32_t e = 0; e < 8; ++e) {
+                    const uint32_t t = e >> 1, h = e & 1u;
+                    const uint32_t bit = (10u + 16u * h + t + 32u - 4u * grp) & 31u;
+                    const double v = std::ldexp(qhat[part * 32 + bit], k);
+                    const uint32_t lane = grp * 16 + row;
+                    sum += v;
+                    for (uint32_t pa = 0; pa < PA; ++pa) {
+                        const double aval = std::ldexp(v, 1 - kValExp[t] - (int)pa);
+                        const _Float16 hi = (_Float16)(float)aval;
+                        uint16_t bits;
+                        std::memcpy(&bits, &hi, 2);
+                        halves[(((((size_t)qt * TERMS + 0) * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
+                        if (TERMS == 2) {
+                            const _Float16 lo = (_Float16)(float)(aval - (double)(float)hi);
+                            std::memcpy(&bits, &lo, 2);
+                            halves[(((((size_t)qt * TERMS + 1) * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
+                        }
+                    }
                 }
-            }
-        }
+        // dyadic modes: every plane's term starts from its own -2^-j sum
+        if (dyadic) sum *= 2.0 - std::ldexp(1.0, 1 - (int)ix->P);
+        ix->h_unscale[RBE_MAX_QUERIES + q] = (float)-sum;
     }
     HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, n_words * sizeof(uint32_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, Q * sizeof(float), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
 
@@ -697,7 +714,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
     } else if (c.batch_mfma) {
         BatchArgs ba;
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
-        ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.tau = ix->d_tau; ba.n_queries = c.Q;
+        ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.tau = ix->d_tau; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
         e = hipSuccess;
         const uint32_t tiles = batch_tiles(c.Q), per_launch = batch_tiles_per_launch(ix);

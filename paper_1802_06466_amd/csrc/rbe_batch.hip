@@ -8,14 +8,26 @@
 // scales in LDS and feeds v_mfma_f32_16x16x32_f16 with 16 queries x 16 items x 32
 // dims per instruction.
 //
-// Item operand.  Eight bits become eight +-1.0 halves through a 256-entry table in LDS:
-// one byte read, one shift (the table offset) and one 16-byte read per operand.  This
-// costs the vector ALU one instruction per operand; forming the halves arithmetically
-// costs four to eight, and on this chip vector instructions and MFMAs of one SIMD do
-// not overlap (the measured time per step is 4 cycles per vector instruction plus 16
-// per MFMA), so instruction count, not LDS traffic, is what the choice turns on.
+// Item operand.  Turning bits into +-1.0 halves costs either a table read of 16 bytes
+// per eight bits (random 16-byte reads: the LDS bank conflicts then bound the kernel) or
+// two vector operations per pair of bits.  Instead the bits are used where they are: a
+// half whose only set bit is bit 10 + t (t = 0..3) is the number 2^-14, 2^-13, 2^-11 or
+// 2^-7, so ONE AND of the (rotated) plane word with 0x04000400 << t yields a dword of
+// two operand halves, each 0 or val_t.  The query operand absorbs the rest: with
+// rho = 2b - 1,
+//     qhat . rho = sum_d (2 qhat_d / val_t(d)) * (b_d val_t(d))  -  sum_d qhat_d ,
+// so the host stores 2 qhat_d / val_t in the order the kernel picks the bits and the
+// accumulators start at -sum_d qhat_d.  The contraction is free to visit the dimensions
+// in any order, which is what lets lane group g take bits (10 + 16h + t - 4g) mod 32 of
+// every 32-bit part with one rotate and four ANDs.
 //
-// qhat is scaled by a power of two into [0.5, 1) and split into two halves (hi + lo,
+// Schedule.  Vector instructions overlap with the MFMAs of the same SIMD only if they
+// are independent of them, so the row is processed four item groups at a time in one
+// straight-line block (the survivor test comes once per block): the expansion of the
+// next group and the fp32 combination of the previous one issue while a group's MFMAs
+// are in the pipeline.
+//
+// qhat is scaled by a power of two into (-1, 1) and split into two halves (hi + lo,
 // about 22 bits together); products are exact and accumulate in fp32, so scores
 // agree with the XOR/popcount path to about 1e-6 relative; the binary dot products
 // themselves are never rounded because they are never formed.  The per-pair VALU
@@ -82,7 +94,6 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     constexpr int TERMS = kDy ? 1 : 2;
     constexpr int PA = kDy ? P : 1;
     constexpr int PD = kDy ? 1 : P;
-    __shared__ u32x4 s_lut[256];                       // byte -> eight +-1.0 halves (bit b -> half b)
     __shared__ uint64_t s_pl[kWavesPerBlock][P][kRow * W];
     __shared__ float s_sc[kWavesPerBlock][S > 0 ? S : 1][kRow];
     __shared__ uint64_t s_keys_all[kWavesPerBlock][kBatchStage];
@@ -95,19 +106,6 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     const MultiStage ms{s_keys_all[wave], s_cnt_all[wave], (uint32_t)kBatchStage / (16u * NQT), a.q_begin, 16u * NQT};
     if (lane < 16 * NQT) s_cnt_all[wave][lane] = 0;
     if (lane == 0) s_cnt_all[wave][16 * NQT] = 0;
-
-    {   // expansion table
-        const uint32_t v = threadIdx.x;
-        u32x4 e;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const uint32_t lo = ((v >> (2 * t)) & 1u) ? 0x3C00u : 0xBC00u;
-            const uint32_t hi = ((v >> (2 * t + 1)) & 1u) ? 0x3C00u : 0xBC00u;
-            e[t] = lo | (hi << 16);
-        }
-        s_lut[v] = e;
-    }
-    __syncthreads();
 
     const uint32_t G = gridDim.x;
     const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
@@ -132,13 +130,14 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     // this lane's queries: tile qt, rows 4g .. 4g+3 (query a.q_begin + 16 qt + 4g + r).  Scores are formed in the
     // query's scaled domain (qhat * 2^k); thresholds are moved there, survivors are moved back (both exact).
     // Only what the common path needs stays in registers; the rare survivor path re-reads the rest.
-    float taus[NQT][4];
+    float taus[NQT][4], bias[NQT][4];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const uint32_t q = a.q_begin + qt * 16 + 4 * g + r;
             taus[qt][r] = q < a.n_queries ? threshold_score(a.tau[q]) / a.q_unscale[q] : __builtin_inff();
+            bias[qt][r] = q < a.n_queries ? a.q_bias[q] : 0.0f;
         }
 
     RawRow<W, P, S> cur, nxt;
@@ -164,70 +163,87 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
         __builtin_amdgcn_wave_barrier();
 
         const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
-#pragma unroll 2
-        for (int c = 0; c < kRow / 16; ++c) {
-            const int item = 16 * c + col;
-            floatx4 D[NQT][PD];
-#pragma unroll
-            for (int qt = 0; qt < NQT; ++qt)
-#pragma unroll
-                for (int j = 0; j < PD; ++j) D[qt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < P; ++j) {
-                // lane group g expands byte g of every 32-dimension part: dims 32 kp + 8 g + 0..7 of item `item`
-                const uint8_t* bytes = reinterpret_cast<const uint8_t*>(&s_pl[wave][j][item * W]) + g;
-#pragma unroll
-                for (int kp = 0; kp < KP; ++kp) {
-                    const half8 B = __builtin_bit_cast(half8, s_lut[bytes[4 * kp]]);
-#pragma unroll
-                    for (int qt = 0; qt < NQT; ++qt)
-#pragma unroll
-                        for (int sp = 0; sp < TERMS; ++sp)
-                            D[qt][kDy ? 0 : j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][sp][kDy ? j : 0][kp], B,
-                                                                                       D[qt][kDy ? 0 : j], 0, 0, 0);
-                }
-            }
-            float aj[P];
-            if (MODE == kModeScaled) {
-#pragma unroll
-                for (int j = 0; j < P; ++j) aj[j] = s_sc[wave][j][item];
-            } else if (MODE == kModeDyadicNorm) {
-                aj[0] = s_sc[wave][0][item];
-            }
-            float s[NQT][4];
+        constexpr int U = 2;   // item groups per straight-line block
+        for (int cb = 0; cb < kRow / (16 * U); ++cb) {
+            float s[U][NQT][4];
             bool any = false;
 #pragma unroll
-            for (int qt = 0; qt < NQT; ++qt)
+            for (int u = 0; u < U; ++u) {
+                const int item = 16 * (cb * U + u) + col;
+                floatx4 D[NQT][PD];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float v;
-                    if (MODE == kModeScaled) {
-                        v = 0.0f;
+                for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-                        for (int j = 0; j < P; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
-                    } else if (MODE == kModeDyadicNorm) {
-                        v = aj[0] * D[qt][0][r];
+                    for (int j = 0; j < PD; ++j) D[qt][j] = floatx4{bias[qt][0], bias[qt][1], bias[qt][2], bias[qt][3]};
+#pragma unroll
+                for (int j = 0; j < P; ++j) {
+                    uint32_t part[KP];
+                    if constexpr (W == 1) {
+                        const uint64_t w = s_pl[wave][j][item];
+                        part[0] = (uint32_t)w; part[1] = (uint32_t)(w >> 32);
                     } else {
-                        v = D[qt][0][r];
+                        const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][j][item * 2]);
+                        part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
                     }
-                    s[qt][r] = v;
-                    any |= (v >= taus[qt][r]);
+#pragma unroll
+                    for (int kp = 0; kp < KP; ++kp) {
+                        // item bits as halves: 0, or the power of two whose only set bit is bit 10 + t
+                        const uint32_t xr = __builtin_rotateleft32(part[kp], 4u * (uint32_t)g);
+                        u32x4 bw;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) bw[t] = xr & (0x04000400u << t);
+                        const half8 B = __builtin_bit_cast(half8, bw);
+#pragma unroll
+                        for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                            for (int sp = 0; sp < TERMS; ++sp)
+                                D[qt][kDy ? 0 : j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                                    A[qt][sp][kDy ? j : 0][kp], B, D[qt][kDy ? 0 : j], 0, 0, 0);
+                    }
                 }
-            if (__ballot(any)) {
-                const uint64_t id = row_id + (uint64_t)item;
+                float aj[P];
+                if (MODE == kModeScaled) {
+#pragma unroll
+                    for (int j = 0; j < P; ++j) aj[j] = s_sc[wave][j][item];
+                } else if (MODE == kModeDyadicNorm) {
+                    aj[0] = s_sc[wave][0][item];
+                }
 #pragma unroll
                 for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        bool ok = (s[qt][r] >= taus[qt][r]) && (id < a.n_items);   // false for padding queries
-                        const uint32_t ql = (uint32_t)(qt * 16 + 4 * g + r);
-                        uint64_t key = 0;
-                        if (ok) {
-                            key = make_key(s[qt][r] * a.q_unscale[a.q_begin + ql], (uint32_t)id);
-                            ok = key >= a.tau[a.q_begin + ql];
+                        float v;
+                        if (MODE == kModeScaled) {
+                            v = 0.0f;
+#pragma unroll
+                            for (int j = 0; j < P; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
+                        } else if (MODE == kModeDyadicNorm) {
+                            v = aj[0] * D[qt][0][r];
+                        } else {
+                            v = D[qt][0][r];
                         }
-                        mstage_append(ok, key, ql, ms, a.out, lane);
+                        s[u][qt][r] = v;
+                        any |= (v >= taus[qt][r]);
                     }
+            }
+            if (__ballot(any)) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint64_t id = row_id + (uint64_t)(16 * (cb * U + u) + col);
+#pragma unroll
+                    for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            bool ok = (s[u][qt][r] >= taus[qt][r]) && (id < a.n_items);   // false for padding queries
+                            const uint32_t ql = (uint32_t)(qt * 16 + 4 * g + r);
+                            uint64_t key = 0;
+                            if (ok) {
+                                key = make_key(s[u][qt][r] * a.q_unscale[a.q_begin + ql], (uint32_t)id);
+                                ok = key >= a.tau[a.q_begin + ql];
+                            }
+                            mstage_append(ok, key, ql, ms, a.out, lane);
+                        }
+                }
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");

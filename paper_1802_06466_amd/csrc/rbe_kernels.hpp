@@ -361,8 +361,11 @@ struct BatchArgs {
     Layout layout;
     uint64_t n_items;
     const uint32_t* a_ops;    // [query tile][term][plane copy][32-dim part][lane][4 dwords = 8 halves]: the scaled
-                              // reconstructed queries in the A-operand order of v_mfma_f32_16x16x32_f16
+                              // reconstructed queries in the A-operand order of v_mfma_f32_16x16x32_f16,
+                              // dimensions permuted and weighted to match the kernel's B operand
     const float* q_unscale;   // [Q] 2^-k: what a score formed from the scaled query is multiplied by
+    const float* q_bias;      // [Q] minus the (plane-weighted) sum of the scaled query's components: where
+                              // every accumulator starts
     const uint64_t* tau;      // [Q] threshold keys
     uint32_t n_queries;       // Q
     uint32_t q_begin;         // first query of this launch (a multiple of 16); it handles 16 or 32 from there
