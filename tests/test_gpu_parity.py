@@ -627,7 +627,9 @@ def test_nearlossless_assumes_random_id_order():
 
 # ------------------------------------------------------------------ batched scan on the matrix cores
 @pytest.mark.parametrize("d,P,Pq,Q,k", [(64, 3, 3, 16, 1000), (64, 3, 3, 1, 100), (64, 2, 3, 5, 64), (64, 4, 4, 33, 500),
-                                        (64, 1, 1, 64, 10), (128, 4, 4, 17, 300), (128, 2, 1, 4, 50)])
+                                        (64, 1, 1, 64, 10), (128, 4, 4, 17, 300), (128, 2, 1, 4, 50),
+                                        (64, 3, 3, 40, 200),      # three 16-query tiles: launches of 2 + 1
+                                        (128, 4, 4, 64, 100)])    # two launches of 32 queries
 def test_matrix_core_batch_path_matches_oracle_and_popcount_path(d, P, Pq, Q, k):
     N = 120_011
     planes, scales, qp, qs = clustered(N, d, P, 64, 0.3, Q, Pq, seed=40 + Q)
@@ -665,3 +667,29 @@ def test_matrix_core_batch_path_random_corpus_multi_level_and_dyadic():
         ids, sc = rbe.rbe_search(ix, qp, None, 400)          # 20 queries: matrix cores by default
         check_batch(planes, oscales, qp, qs, 400, ids, sc)
         rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("d,P,Pq,Q,cosine", [(64, 2, 3, 16, False), (64, 4, 4, 37, True), (128, 3, 4, 24, False),
+                                             (128, 4, 2, 20, True), (128, 2, 2, 33, False)])
+def test_matrix_core_batch_path_dyadic_is_bit_equal_to_popcount_path(d, P, Pq, Q, cosine):
+    """Dyadic weights: every term of the contraction is a short dyadic fraction, so the matrix-core
+    path (one query half, plane weights folded into the query operand, one accumulator chain;
+    16 queries per launch at d=128 with 3 or 4 planes, else 32) must reproduce the integer
+    shift-add path bit for bit, ids included."""
+    rng = np.random.default_rng(1000 + d + P + Q)
+    N, k = 70_003, 300
+    planes = rng.integers(0, 2**64, size=(P, N, d // 64), dtype=np.uint64)
+    qp = rng.integers(0, 2**64, size=(Q, Pq, d // 64), dtype=np.uint64)
+    ix = rbe.rbe_load_corpus(planes, None, flags=rbe.RBE_DYADIC | (rbe.RBE_COSINE if cosine else 0))
+    rbe.rbe_debug_set_batch_path(ix, 2)
+    ids_m, sc_m = rbe.rbe_search(ix, qp, None, k)
+    rbe.rbe_debug_set_batch_path(ix, 1)
+    ids_v, sc_v = rbe.rbe_search(ix, qp, None, k)
+    np.testing.assert_array_equal(sc_m, sc_v)
+    np.testing.assert_array_equal(ids_m, ids_v)
+    oscales = dyadic_weights(P, N)
+    if cosine:
+        oscales = oracle.fold_cosine(planes, oscales)
+    qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
+    check_batch(planes, oscales, qp, qs, k, ids_m, sc_m)
+    rbe.rbe_free(ix)
