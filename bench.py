@@ -306,6 +306,24 @@ def main():
             "roofline": roof,
         }
         log(f"Q={B}: {b_ms:.3f} ms/step, scan kernel {b_scan:.3f} ms")
+        if matrix_cores:
+            # the same calls on the XOR/popcount kernel (what one query uses), against the vector-ALU roofline
+            rbe.rbe_debug_set_batch_path(ix, 1)
+            steps_v = max(2, args.batch_steps // 2)
+            rv = timed_searches(rbe, torch, ix, qpb, qsb, B, k, steps_v, 1)
+            rbe.rbe_debug_set_batch_path(ix, 0)
+            v_ms = rv["wall_s"] * 1e3 / steps_v
+            v_scan = float(rv["scan_ms"].mean())
+            v_ach = lane_ops_per_pair(W, P, P) * B * rv["stats"]["items_scanned"][-1] / (v_scan * 1e-3) / 1e12
+            out["batch_popcount_kernel"] = {
+                "queries_per_step": B, "steps": steps_v, "ms_per_step": v_ms,
+                "value": N * B / (v_ms * 1e-3), "unit": "candidates/s", "dtype": "u64 xor/popcount + f32",
+                "roofline": {"kernel": "scan_exact (finest level)", "bound": "alu", "achieved": v_ach,
+                             "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-ops/s", "frac": v_ach / VALU_PEAK_TLANEOPS,
+                             "kernel_ms": v_scan, "lane_ops_per_pair": lane_ops_per_pair(W, P, P), "traffic": None},
+            }
+            log(f"Q={B}, XOR/popcount kernel: {v_ms:.3f} ms/step, scan kernel {v_scan:.3f} ms "
+                f"-> {v_ach:.1f} T lane-ops/s")
 
     # ---------------- CPU baseline: the oracle, as it stands, on a bounded sample
     if cpu_items > 0:
