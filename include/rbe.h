@@ -280,6 +280,29 @@ int rbe_debug_read_planes(rbe_index *ix, uint64_t first_item, uint64_t count,
 uint32_t rbe_debug_tile_to_phys(uint32_t n_tiles, uint32_t sample_ratio, uint32_t tile);
 uint32_t rbe_debug_phys_to_tile(uint32_t n_tiles, uint32_t sample_ratio, uint32_t phys);
 
+/* Refinement plan of the exact mode (pure host function, for tests): the levels
+ * rbe_search would run for such a corpus, each a range [first_tile, end_tile) of
+ * PHYSICAL tile positions; arrays of RBE_MAX_LEVELS entries.  n_levels = 0 means
+ * that no plan fits cand_capacity (the bounded-segment path is used instead).    */
+int rbe_debug_exact_plan(uint64_t n_items, uint32_t sample_ratio, uint32_t cand_capacity, uint32_t k,
+                         uint32_t *n_levels, uint32_t *first_tile, uint32_t *end_tile);
+
+/* Query operands of the matrix-core batch scan (pure host function, for tests).
+ * halves_out [tile][term][plane copy][part][lane][8] fp16 bit patterns, where
+ * tile = query / 16, lane = 16 g + query % 16, part = 32-dimension part of the
+ * query and slot e = 2t + h of lane group g stands for bit (10 + 16h + t - 4g)
+ * mod 32 of that part, weighted by 2 / val_t with val_t = 2^-14, 2^-13, 2^-11,
+ * 2^-7 (the value of a half whose only set bit is bit 10 + t: the form in which
+ * the kernel feeds item bits), times 2^-j in plane copy j (dyadic only; one copy
+ * otherwise).  term 0 = hi half, term 1 = lo half (general scales only).
+ * unscale_out[q] = 2^-k undoes the power-of-two scaling of query q; start_out[q]
+ * is where its accumulators start (minus the weighted sum of its components).
+ * shape_out = {tiles, terms, plane copies, parts}.  halves_capacity in halves.  */
+int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, uint32_t n_queries,
+                             uint32_t q_n_planes, uint32_t dim, uint32_t n_planes, uint32_t dyadic,
+                             uint16_t *halves_out, size_t halves_capacity, float *unscale_out,
+                             float *start_out, uint32_t *shape_out);
+
 /* Measurement yardstick: enqueues a plain copy kernel ("calib_copy") of `bytes`
  * bytes from src_dev to dst_dev (DEVICE pointers, 16-byte aligned, bytes a
  * multiple of 16, non-overlapping).  It reads and writes exactly `bytes` each,

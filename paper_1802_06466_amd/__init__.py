@@ -73,6 +73,8 @@ PROTOTYPES = {
     "rbe_debug_tile_to_phys": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_phys_to_tile": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_set_batch_path": (_i32, [_vp, _i32]),
+    "rbe_debug_exact_plan": (_i32, [_u64, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "rbe_debug_batch_operands": (_i32, [_vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
@@ -349,6 +351,35 @@ def rbe_debug_tile_to_phys(n_tiles: int, sample_ratio: int, tile: int) -> int:
 
 def rbe_debug_phys_to_tile(n_tiles: int, sample_ratio: int, phys: int) -> int:
     return int(load_library().rbe_debug_phys_to_tile(n_tiles, sample_ratio, phys))
+
+
+def rbe_debug_exact_plan(n_items: int, sample_ratio: int, cand_capacity: int, k: int):
+    """Levels of the exact-mode plan as (first_tile, end_tile) physical ranges (host only)."""
+    n = np.zeros(1, dtype=np.uint32)
+    first = np.zeros(RBE_MAX_LEVELS, dtype=np.uint32)
+    end = np.zeros(RBE_MAX_LEVELS, dtype=np.uint32)
+    _check(load_library().rbe_debug_exact_plan(n_items, sample_ratio, cand_capacity, k, n.ctypes.data,
+                                               first.ctypes.data, end.ctypes.data))
+    return [(int(first[i]), int(end[i])) for i in range(int(n[0]))]
+
+
+def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic: bool):
+    """Query operands of the matrix-core batch scan (host only): fp16 bit patterns
+    [tile][term][plane copy][part][lane][8], unscale [Q], start [Q]."""
+    q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
+    Q, Pq = q_planes.shape[0], q_planes.shape[1]
+    if q_scales is not None:
+        q_scales = np.ascontiguousarray(q_scales, dtype=np.float32)
+    cap = ((Q + 15) // 16) * 2 * 4 * (dim // 32) * 64 * 8
+    halves = np.zeros(cap, dtype=np.uint16)
+    unscale = np.zeros(Q, dtype=np.float32)
+    start = np.zeros(Q, dtype=np.float32)
+    shape = np.zeros(4, dtype=np.uint32)
+    _check(load_library().rbe_debug_batch_operands(
+        q_planes.ctypes.data, None if q_scales is None else q_scales.ctypes.data, Q, Pq, dim, n_planes,
+        1 if dyadic else 0, halves.ctypes.data, cap, unscale.ctypes.data, start.ctypes.data, shape.ctypes.data))
+    tiles, terms, copies, parts = (int(x) for x in shape)
+    return halves[:tiles * terms * copies * parts * 64 * 8].reshape(tiles, terms, copies, parts, 64, 8), unscale, start
 
 
 def rbe_debug_set_batch_path(ix: Index, path: int):

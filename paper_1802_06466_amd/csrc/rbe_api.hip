@@ -275,30 +275,43 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
     return Q >= 4;   // below that the XOR/popcount kernel is at or near the HBM bound already
 }
 
-// Matrix-core operands of a batch: each query reconstructed in double as qhat = sum_i c_i b^i,
-// scaled by a power of two into [0.5, 1), split into two halves (hi = half(qhat), lo = half(qhat - hi)),
-// and laid out as lane l of the wave will load it: query (l % 16), dims 32*part + 8*(l / 16) + 0..7.
-int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
-                        hipStream_t st)
+// Matrix-core operands of a batch (pure host arithmetic).  Each query is reconstructed in double as
+// qhat = sum_i c_i b^i and scaled by a power of two so that v = qhat * 2^k lies in (-1, 1).
+//
+// The kernel's B operand holds, for item bit b, the half whose only set bit is bit 10 + t (t = 0..3):
+// 0 or val_t = 2^-14, 2^-13, 2^-11, 2^-7.  With rho = 2b - 1:
+//     sum_d v_d rho_d = sum_d (2 v_d / val_t) (b_d val_t) - sum_d v_d,
+// so the A operand carries 2 v_d / val_t (below 2^15), as hi + lo halves with general scales, and the
+// accumulator starts at -sum_d v_d.  Lane (g, row) of 32-dimension part kp holds slot e = 2t + h; the kernel
+// rotates the part's word left by 4g and takes bits 10 + t (h = 0) and 26 + t (h = 1), i.e. original bit
+// (10 + 16h + t - 4g) mod 32.  Dyadic modes: one exact half, one copy per item plane j scaled by 2^-j, and
+// the start value covers all planes.
+//   halves  [tile][term][plane copy][part][lane][8]   (tile = query / 16, lane = 16 g + query % 16)
+//   unscale [Q] = 2^-k,   bias [Q] = start value of the accumulators
+struct BatchOperandShape { uint32_t tiles, terms, copies, parts; size_t n_halves; };
+
+BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint32_t Q)
 {
-    const uint32_t W = ix->W, KP = 2 * W, NQT = batch_tiles(Q);
-    const size_t max_words = (size_t)(RBE_MAX_QUERIES / 16) * 4 * 4 * 64 * 4;   // per tile: (terms x plane copies) x parts <= 16
-    if (!ix->d_aops) {
-        HIP_TRY(hipMalloc(&ix->d_aops, max_words * sizeof(uint32_t)));
-        HIP_TRY(hipHostMalloc(&ix->h_aops, max_words * sizeof(uint32_t), hipHostMallocDefault));
-        HIP_TRY(hipMalloc(&ix->d_unscale, 2 * RBE_MAX_QUERIES * sizeof(float)));
-        HIP_TRY(hipHostMalloc(&ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
-    }
-    const bool dyadic = ix->mode != rbe::kModeScaled;
-    // general scales: hi + lo halves of the query; dyadic modes: one exact half, one copy per item plane (x 2^-j)
-    const uint32_t TERMS = dyadic ? 1 : 2, PA = dyadic ? ix->P : 1;
-    const size_t n_words = (size_t)NQT * TERMS * PA * KP * 64 * 4;
-    std::memset(ix->h_aops, 0, n_words * sizeof(uint32_t));
-    uint16_t* halves = reinterpret_cast<uint16_t*>(ix->h_aops);
-    std::vector<double> qhat(ix->dim);
+    BatchOperandShape sh;
+    sh.tiles = batch_tiles(Q);
+    sh.terms = dyadic ? 1u : 2u;
+    sh.copies = dyadic ? P : 1u;
+    sh.parts = 2u * W;
+    sh.n_halves = (size_t)sh.tiles * sh.terms * sh.copies * sh.parts * 64 * 8;
+    return sh;
+}
+
+void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q_planes, const float* q_scales,
+                          uint32_t Q, uint32_t PQ, uint16_t* halves, float* unscale, float* bias)
+{
+    const BatchOperandShape sh = batch_operand_shape(W, P, dyadic, Q);
+    const uint32_t dim = 64 * W, KP = sh.parts, TERMS = sh.terms, PA = sh.copies;
+    std::memset(halves, 0, sh.n_halves * sizeof(uint16_t));
+    std::vector<double> qhat(dim);
+    static const int kValExp[4] = {-14, -13, -11, -7};
     for (uint32_t q = 0; q < Q; ++q) {
         double biggest = 0.0;
-        for (uint32_t d = 0; d < ix->dim; ++d) {
+        for (uint32_t d = 0; d < dim; ++d) {
             double v = 0.0;
             for (uint32_t i = 0; i < PQ; ++i) {
                 const double c = dyadic ? std::ldexp(1.0, -(int)i) : (double)q_scales[(size_t)q * PQ + i];
@@ -308,17 +321,10 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
             qhat[d] = v;
             biggest = std::max(biggest, std::fabs(v));
         }
-        const int k = biggest > 0.0 ? -(std::ilogb(biggest) + 1) : 0;   // v = qhat * 2^k lies in (-1, 1)
-        ix->h_unscale[q] = std::ldexp(1.0f, -k);
+        const int k = biggest > 0.0 ? -(std::ilogb(biggest) + 1) : 0;
+        unscale[q] = std::ldexp(1.0f, -k);
         const uint32_t qt = q / 16, row = q % 16;
         double sum = 0.0;
-        // The kernel's B operand holds, for item bit b, the half whose only set bit is bit 10 + t (t = 0..3):
-        // 0 or val_t = 2^-14, 2^-13, 2^-11, 2^-7.  With rho = 2b - 1:
-        //     sum_d v_d rho_d = sum_d (2 v_d / val_t) (b_d val_t) - sum_d v_d,
-        // so the A operand carries 2 v_d / val_t (below 2^15) and the accumulator starts at -sum_d v_d.
-        // Lane (g, row) of 32-dimension part kp holds slot e = 2t + h; the kernel rotates the part's word left by
-        // 4g and takes bits 10 + t (h = 0) and 26 + t (h = 1), i.e. original bit (10 + 16h + t - 4g) mod 32.
-        static const int kValExp[4] = {-14, -13, -11, -7};
         for (uint32_t part = 0; part < KP; ++part)
             for (uint32_t grp = 0; grp < 4; ++grp)
                 for (uint32_t e = 0; e < 8; ++e) {
@@ -340,11 +346,26 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
                         }
                     }
                 }
-        // dyadic modes: every plane's term starts from its own -2^-j sum
-        if (dyadic) sum *= 2.0 - std::ldexp(1.0, 1 - (int)ix->P);
-        ix->h_unscale[RBE_MAX_QUERIES + q] = (float)-sum;
+        if (dyadic) sum *= 2.0 - std::ldexp(1.0, 1 - (int)P);   // every plane's term starts from its own -2^-j sum
+        bias[q] = (float)-sum;
     }
-    HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, n_words * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+}
+
+int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
+                        hipStream_t st)
+{
+    const size_t max_halves = (size_t)(RBE_MAX_QUERIES / 16) * 4 * 4 * 64 * 8;   // per tile: (terms x copies) x parts <= 16
+    if (!ix->d_aops) {
+        HIP_TRY(hipMalloc(&ix->d_aops, max_halves * sizeof(uint16_t)));
+        HIP_TRY(hipHostMalloc(&ix->h_aops, max_halves * sizeof(uint16_t), hipHostMallocDefault));
+        HIP_TRY(hipMalloc(&ix->d_unscale, 2 * RBE_MAX_QUERIES * sizeof(float)));
+        HIP_TRY(hipHostMalloc(&ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
+    }
+    const bool dyadic = ix->mode != rbe::kModeScaled;
+    const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q);
+    build_batch_operands(ix->W, ix->P, dyadic, q_planes, q_scales, Q, PQ, reinterpret_cast<uint16_t*>(ix->h_aops),
+                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES);
+    HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, sh.n_halves * sizeof(uint16_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
@@ -468,6 +489,38 @@ uint32_t rbe_debug_phys_to_tile(uint32_t n_tiles, uint32_t sample_ratio, uint32_
 {
     const rbe::Layout l = rbe::make_layout(n_tiles, sample_ratio);
     return rbe::phys_to_tile(l, phys);
+}
+
+int rbe_debug_exact_plan(uint64_t n_items, uint32_t sample_ratio, uint32_t cand_capacity, uint32_t k,
+                         uint32_t* n_levels, uint32_t* first_tile, uint32_t* end_tile)
+{
+    ARG_CHECK(n_levels && first_tile && end_tile, "NULL argument");
+    ARG_CHECK(n_items >= 1 && n_items <= RBE_MAX_ITEMS, "n_items out of range");
+    ARG_CHECK(sample_ratio >= 2 && sample_ratio <= 4096, "sample_ratio out of range");
+    const rbe::Layout l = rbe::make_layout((uint32_t)((n_items + kTileItems - 1) / kTileItems), sample_ratio);
+    const std::vector<Level> plan = make_plan(l, cand_capacity, k);
+    ARG_CHECK(plan.size() <= RBE_MAX_LEVELS, "plan longer than RBE_MAX_LEVELS");
+    *n_levels = (uint32_t)plan.size();
+    for (size_t i = 0; i < plan.size(); ++i) { first_tile[i] = plan[i].p_begin; end_tile[i] = plan[i].p_end; }
+    return RBE_OK;
+}
+
+int rbe_debug_batch_operands(const uint64_t* q_planes, const float* q_scales, uint32_t n_queries, uint32_t q_n_planes,
+                             uint32_t dim, uint32_t n_planes, uint32_t dyadic, uint16_t* halves_out, size_t halves_capacity,
+                             float* unscale_out, float* start_out, uint32_t* shape_out)
+{
+    ARG_CHECK(q_planes && halves_out && unscale_out && start_out && shape_out, "NULL argument");
+    ARG_CHECK(dyadic || q_scales, "q_scales is NULL");
+    ARG_CHECK(dim == 64 || dim == 128, "dim must be 64 or 128");
+    ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES && q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES,
+              "plane counts out of range");
+    ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries out of range");
+    const BatchOperandShape sh = batch_operand_shape(dim / 64, n_planes, dyadic != 0, n_queries);
+    ARG_CHECK(halves_capacity >= sh.n_halves, "halves_out too small: %zu needed", sh.n_halves);
+    build_batch_operands(dim / 64, n_planes, dyadic != 0, q_planes, q_scales, n_queries, q_n_planes, halves_out,
+                         unscale_out, start_out);
+    shape_out[0] = sh.tiles; shape_out[1] = sh.terms; shape_out[2] = sh.copies; shape_out[3] = sh.parts;
+    return RBE_OK;
 }
 
 int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uint64_t* planes,

@@ -137,3 +137,118 @@ def test_product_does_not_import_oracle():
     for f in os.listdir(os.path.join(ROOT, "oracle")):
         if f.endswith((".py", ".c")):
             assert "paper_1802_06466_amd" not in open(os.path.join(ROOT, "oracle", f)).read()
+
+
+# ------------------------------------------------------------------ host logic: refinement plan of the exact mode
+@pytest.mark.parametrize("n_items,ratio,cap,k", [
+    (1_000_000_000, 64, 131072, 1000), (1_000_000_000, 64, 131072, 4000), (10_000_000, 64, 131072, 1000),
+    (1_000_000, 64, 131072, 100), (100_000_000, 8, 6144, 100), (5000, 64, 131072, 100), (1, 64, 131072, 1),
+    (4_294_966_272, 64, 131072, 4096), (1_212_153_856, 64, 131072, 1000), (3_000_000, 2, 8192, 50)])
+def test_exact_plan_partitions_the_corpus(lib, n_items, ratio, cap, k):
+    """Levels are contiguous physical ranges, each starting where the previous one ended, together
+    covering every tile exactly once; the first (threshold-free) level fits the candidate list;
+    each level is a nested strided sample: its end is ceil(T / ratio^c) for decreasing c."""
+    T = -(-n_items // 1024)
+    plan = rbe.rbe_debug_exact_plan(n_items, ratio, cap, k)
+    if not plan:                       # nothing fits: the library uses its bounded-segment path
+        assert T * 1024 > cap
+        return
+    assert plan[0][0] == 0 and plan[-1][1] == T
+    for (b0, e0), (b1, e1) in zip(plan, plan[1:]):
+        assert e0 == b1 and b1 < e1
+    assert plan[0][1] * 1024 <= cap
+    c = len(plan) - 1
+    for i, (_, e) in enumerate(plan):
+        assert e == -(-T // ratio ** (c - i))
+    # the start level holds at least 4k items whenever a coarser choice would not
+    if len(plan) > 1:
+        assert plan[0][1] * 1024 >= min(4 * k, cap // 2) or plan[0][1] * ratio * 1024 > cap
+
+
+def test_exact_plan_levels_are_strided_samples(lib):
+    """Physical prefix [0, end) of level i is exactly the set of logical tiles that are multiples of
+    ratio^(c-i): checked through the tile-order functions on a corpus of 70,001 tiles."""
+    T, ratio = 70_001, 8
+    plan = rbe.rbe_debug_exact_plan(T * 1024, ratio, 32768, 100)
+    assert len(plan) >= 3
+    c = len(plan) - 1
+    for i, (b, e) in enumerate(plan[:-1]):
+        step = ratio ** (c - i)
+        got = sorted(rbe.rbe_debug_phys_to_tile(T, ratio, p) for p in range(0, e))
+        assert got == list(range(0, T, step))
+
+
+# ------------------------------------------------------------------ host logic: query operands of the matrix-core scan
+def _halves_to_float(bits):
+    return np.asarray(bits, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+@pytest.mark.parametrize("dim,P,Pq,Q,dyadic", [(64, 3, 3, 16, False), (64, 2, 3, 5, True), (128, 4, 4, 33, False),
+                                                (128, 3, 4, 20, True), (64, 1, 1, 1, False)])
+def test_matrix_core_operands_reproduce_the_score(lib, dim, P, Pq, Q, dyadic):
+    """Emulates the kernel's side of the contract on the CPU: item bits become halves whose only set
+    bit is bit 10 + t (lane group g takes bits 10 + t and 26 + t of the part rotated left by 4g),
+    every lane multiplies its eight slots, and the sum over lanes, parts, terms and plane copies plus
+    the start value must equal qhat . rho (times the item-plane weights in the dyadic case), to the
+    22 bits the two halves carry -- exactly, for dyadic queries."""
+    rng = np.random.default_rng(dim + P + Q)
+    W = dim // 64
+    qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
+    qs = None if dyadic else rng.uniform(0.05, 1.0, size=(Q, Pq)).astype(np.float32)
+    halves, unscale, start = rbe.rbe_debug_batch_operands(qp, qs, dim, P, dyadic)
+    tiles, terms, copies, parts = halves.shape[:4]
+    assert (tiles, terms, copies, parts) == ((Q + 15) // 16, 1 if dyadic else 2, P if dyadic else 1, 2 * W)
+    A = _halves_to_float(halves)                                  # [tile][term][copy][part][lane][8]
+    coef = np.array([2.0 ** -i for i in range(Pq)]) if dyadic else None
+    val = np.array([2.0 ** -14, 2.0 ** -13, 2.0 ** -11, 2.0 ** -7])
+    n_items = 7
+    item_planes = rng.integers(0, 2**64, size=(P, n_items, W), dtype=np.uint64)
+    for q in range(Q):
+        c = coef if dyadic else qs[q].astype(np.float64)
+        qbits = ((qp[q][:, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)   # [Pq][W][64]
+        qhat = (c[:, None, None] * (2 * qbits - 1)).sum(axis=0).reshape(dim)
+        t_, row = q // 16, q % 16
+        for z in range(n_items):
+            for j in range(P):
+                word_bits = ((item_planes[j, z][:, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.int64).reshape(dim)
+                want = float(qhat @ (2 * word_bits - 1))
+                if not dyadic:
+                    got = float(start[q])
+                    for part in range(parts):
+                        bits32 = word_bits[32 * part: 32 * part + 32]
+                        for g in range(4):
+                            for e in range(8):
+                                t, h = e >> 1, e & 1
+                                b = bits32[(10 + 16 * h + t - 4 * g) % 32]      # what the rotate + AND picks
+                                for term in range(terms):
+                                    got += A[t_, term, 0, part, 16 * g + row, e] * (b * val[t])
+                    got *= float(unscale[q])
+                    assert abs(got - want) <= 2.0 ** -20 * np.abs(qhat).sum() + 1e-12, (q, z, j, got, want)
+            if dyadic:
+                want_all = 0.0
+                got = float(start[q])
+                for j in range(P):
+                    word_bits = ((item_planes[j, z][:, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.int64).reshape(dim)
+                    want_all += 2.0 ** -j * float(qhat @ (2 * word_bits - 1))
+                    for part in range(parts):
+                        bits32 = word_bits[32 * part: 32 * part + 32]
+                        for g in range(4):
+                            for e in range(8):
+                                t, h = e >> 1, e & 1
+                                got += A[t_, 0, j, part, 16 * g + row, e] * (bits32[(10 + 16 * h + t - 4 * g) % 32] * val[t])
+                assert got * float(unscale[q]) == want_all, (q, z, got, want_all)
+
+
+def test_matrix_core_operands_stay_in_half_range(lib):
+    """2 v / val_t is below 2^15 and the scaled query's largest component is at least 0.5: no
+    overflow to infinity, and the hi halves are normal numbers wherever the component is not tiny."""
+    rng = np.random.default_rng(5)
+    qp = rng.integers(0, 2**64, size=(64, 4, 2), dtype=np.uint64)
+    qs = rng.uniform(1e-3, 50.0, size=(64, 4)).astype(np.float32)
+    halves, unscale, start = rbe.rbe_debug_batch_operands(qp, qs, 128, 4, False)
+    A = _halves_to_float(halves)
+    assert np.isfinite(A).all() and np.abs(A).max() < 2.0 ** 15
+    assert (np.abs(A[:, 0]).reshape(4, -1).max(axis=1) >= 2.0 ** 7).all()
+    assert np.isfinite(start).all() and (unscale > 0).all()
+    lg = np.log2(unscale.astype(np.float64))
+    assert np.array_equal(lg, np.round(lg))       # powers of two
