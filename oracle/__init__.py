@@ -63,7 +63,7 @@ def _c():
         lib.orc_n_groups.restype = u64
         lib.orc_n_groups.argtypes = [u64, u64, u64]
         lib.orc_nearlossless.restype = i64
-        lib.orc_nearlossless.argtypes = [vp, vp, u64, u32, u32, vp, vp, u32, u64, u64, u64, vp, vp, vp, vp]
+        lib.orc_nearlossless.argtypes = [vp, vp, u64, u32, u32, vp, vp, u32, u64, u64, u64, u64, vp, vp, vp, vp]
         lib.orc_encode.restype = None
         lib.orc_encode.argtypes = [vp, u64, u32, u32, vp, vp]
         lib.orc_scores_fq.restype = None
@@ -187,20 +187,26 @@ def n_groups(N: int, I: int, Tb: int = 256) -> int:
 
 
 def nearlossless(planes, scales, q_planes, q_scales, k: int, I: int = 256, Tb: int = 256,
-                 return_winners: bool = False):
-    """Algorithm 1 with queue length 1, then exact top-k of the group winners."""
+                 return_winners: bool = False, queue_len: int = 1):
+    """Algorithm 1 with a priority queue of `queue_len` entries per thread (the paper's
+    choice is 1), then exact top-k of everything the queues hold.  With return_winners the
+    queues themselves come back as [n_groups, queue_len] arrays (squeezed for length 1)."""
     planes, scales, P, N, W = _corpus(planes, scales)
     q_planes, q_scales, Pq = _query(q_planes, q_scales, W)
+    if queue_len < 1:
+        raise ValueError("queue_len must be >= 1")
     ids = np.zeros(k, dtype=np.int64)
     sc = np.zeros(k, dtype=np.float64)
     G = n_groups(N, I, Tb)
-    w_ids = np.zeros(G, dtype=np.int64)
-    w_sc = np.zeros(G, dtype=np.float64)
+    w_ids = np.zeros((G, queue_len), dtype=np.int64)
+    w_sc = np.zeros((G, queue_len), dtype=np.float64)
     r = _c().orc_nearlossless(_p(planes), _p(scales), N, 64 * W, P, _p(q_planes), _p(q_scales), Pq,
-                              Tb, I, k, _p(ids), _p(sc), _p(w_ids), _p(w_sc))
+                              Tb, I, queue_len, k, _p(ids), _p(sc), _p(w_ids), _p(w_sc))
     if r < 0:
         raise MemoryError
     if return_winners:
+        if queue_len == 1:
+            return ids, sc, w_ids[:, 0], w_sc[:, 0]
         return ids, sc, w_ids, w_sc
     return ids, sc
 

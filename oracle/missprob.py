@@ -63,11 +63,26 @@ def miss_probability(l: int, N: int, C: int, I: int) -> float:
     return float(sum(prob_threads_hit(N - m, N, C, I) for m in range(l + 1)))
 
 
-def expected_recall(N: int, C: int, I: int) -> float:
-    """E[M] / N: a thread is hit unless all N relevant items avoid its I slots,
-    so E[M] = T * (1 - C(C - I, N) / C(C, N))."""
+def expected_recall(N: int, C: int, I: int, queue_len: int = 1) -> float:
+    """Expected fraction of the N relevant items that survive the local selection.
+
+    Queue length 1 (Appendix A): E[M] / N; a thread is hit unless all N relevant items avoid
+    its I slots, so E[M] = T * (1 - C(C - I, N) / C(C, N)).
+    Queue length p in general (same placement model): a thread holding n relevant items keeps
+    min(n, p) of them, and n is hypergeometric, P(n) = C(I, n) C(C - I, N - n) / C(C, N); by
+    linearity the expected number kept is T * sum_n min(n, p) P(n)."""
     if C % I:
         raise ValueError("Appendix A assumes T = C / I is an integer")
     T = C // I
-    p_empty = Fraction(comb(C - I, N), comb(C, N))
-    return float(T * (1 - p_empty) / N)
+    if queue_len == 1:
+        p_empty = Fraction(comb(C - I, N), comb(C, N))
+        return float(T * (1 - p_empty) / N)
+    total = comb(C, N)
+    kept = Fraction(0)
+    # P(n) falls off like (N I / C)^n: far beyond 40 terms nothing is left in double precision
+    for n in range(1, min(I, N) + 1):
+        pn = Fraction(comb(I, n) * comb(C - I, N - n), total)
+        kept += min(n, queue_len) * pn
+        if n > queue_len + 40 and pn < Fraction(1, 10 ** 40):
+            break
+    return float(T * kept / N)

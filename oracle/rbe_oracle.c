@@ -208,8 +208,9 @@ int64_t orc_topk_of_scores(const double *scores, const int64_t *ids, uint64_t n,
  * z = x*Tb*I + y, then z += Tb, I times, keeping only its best item.  So the
  * items sharing one queue ("group") are
  *     g(z) = (z div (Tb*I)) * Tb + (z mod Tb).
- * Each group forwards its best item under (score desc, id asc); slots past N
- * do not exist.  The answer is the exact top-k of the forwarded items.
+ * Each group forwards its best item (its best qlen items for a queue of length
+ * qlen) under (score desc, id asc); slots past N do not exist.  The answer is
+ * the exact top-k of the forwarded items.
  * winners_ids/winners_scores (optional, length n_groups) receive every
  * group's winner (id -1 / -inf for an empty group).                         */
 /* ------------------------------------------------------------------ */
@@ -222,30 +223,40 @@ uint64_t orc_n_groups(uint64_t N, uint64_t Tb, uint64_t I)
 int64_t orc_nearlossless(const uint64_t *planes, const float *scales, uint64_t N,
                          uint32_t d, uint32_t P,
                          const uint64_t *q_planes, const float *q_scales, uint32_t Pq,
-                         uint64_t Tb, uint64_t I, uint64_t k,
+                         uint64_t Tb, uint64_t I, uint64_t qlen, uint64_t k,
                          int64_t *ids_out, double *scores_out,
                          int64_t *winners_ids, double *winners_scores)
 {
+    /* Algorithm 1 with a priority queue of `qlen` entries per thread (the paper runs it with 1).
+     * winners_* (optional): [n_groups][qlen], best first, id -1 / -inf where a queue is not full. */
     const uint64_t G = orc_n_groups(N, Tb, I);
-    cand_t *win = (cand_t *)malloc((G ? G : 1) * sizeof(cand_t));
+    if (qlen == 0) return -1;
+    cand_t *win = (cand_t *)malloc((G ? G : 1) * qlen * sizeof(cand_t));
     if (!win) return -1;
-    for (uint64_t g = 0; g < G; ++g) { win[g].s = -INFINITY; win[g].id = -1; }
+    for (uint64_t g = 0; g < G * qlen; ++g) { win[g].s = -INFINITY; win[g].id = -1; }
 
     const uint64_t n_blocks = G / Tb;
     for (uint64_t x = 0; x < n_blocks; ++x)
         for (uint64_t y = 0; y < Tb; ++y) {
             uint64_t z = x * Tb * I + y;
-            cand_t *p = &win[x * Tb + y];          /* the length-1 queue */
+            cand_t *p = &win[(x * Tb + y) * qlen];          /* this thread's queue, best first */
             for (uint64_t it = 0; it < I; ++it, z += Tb) {
                 if (z >= N) continue;
                 cand_t c = { score_pair(planes, scales, N, d, P, z, q_planes, q_scales, Pq), (int64_t)z };
-                if (p->id < 0 || better(&c, p)) *p = c;
+                /* p.insert(s, z): the new entry enters before the first worse one; the last one drops out */
+                for (uint64_t e = 0; e < qlen; ++e) {
+                    if (p[e].id < 0 || better(&c, &p[e])) {
+                        for (uint64_t m = qlen - 1; m > e; --m) p[m] = p[m - 1];
+                        p[e] = c;
+                        break;
+                    }
+                }
             }
         }
 
     topk_t t = { (cand_t *)malloc((k ? k : 1) * sizeof(cand_t)), 0, k };
     if (!t.h) { free(win); return -1; }
-    for (uint64_t g = 0; g < G; ++g) {
+    for (uint64_t g = 0; g < G * qlen; ++g) {
         if (winners_ids)    winners_ids[g] = win[g].id;
         if (winners_scores) winners_scores[g] = win[g].s;
         if (win[g].id >= 0) topk_offer(&t, win[g].s, win[g].id);

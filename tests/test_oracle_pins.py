@@ -447,6 +447,73 @@ def test_nearlossless_I1_is_exact():
     assert list(a) == list(b)
 
 
+def simulate_algorithm1_queue(sc, Tb, I, k, qlen):
+    """Literal Algorithm 1 with a sorted list of at most qlen entries as the priority queue."""
+    N = len(sc)
+    n_blocks = -(-N // (Tb * I))
+    kept = []
+    queues = []
+    for x in range(n_blocks):
+        for y in range(Tb):
+            z = x * Tb * I + y
+            q = []
+            for _ in range(I):
+                if z < N:
+                    q.append((-sc[z], z))
+                    q.sort()
+                    del q[qlen:]
+                z += Tb
+            queues.append([e[1] for e in q])
+            kept += q
+    kept.sort()
+    return [e[1] for e in kept[:k]], queues
+
+
+@pytest.mark.parametrize("N,Tb,I,k,qlen", [(24, 4, 3, 5, 2), (25, 4, 3, 30, 2), (1000, 8, 16, 40, 2), (1000, 8, 16, 40, 3),
+                                           (1000, 256, 2, 600, 2), (70000, 256, 256, 100, 2), (500, 4, 5, 50, 5)])
+def test_nearlossless_longer_queue_matches_literal_algorithm1(N, Tb, I, k, qlen):
+    rng = np.random.default_rng(116 + N + qlen)
+    planes, scales = random_corpus(rng, N, 64, 2)
+    scales = np.round(scales, 1).astype(np.float32)       # many exact ties
+    qp, qs = random_query(rng, 64, 2)
+    s = oracle.scores(planes, scales, qp, qs)
+    ids, sc, w_ids, w_sc = oracle.nearlossless(planes, scales, qp, qs, k, I=I, Tb=Tb, return_winners=True, queue_len=qlen)
+    expect, queues = simulate_algorithm1_queue(s, Tb, I, k, qlen)
+    m = len(expect)
+    assert list(ids[:m]) == expect and np.all(ids[m:] == -1)
+    np.testing.assert_array_equal(sc[:m], s[expect])
+    for g, q in enumerate(queues):
+        assert [int(v) for v in w_ids[g][:len(q)]] == q and np.all(w_ids[g][len(q):] == -1)
+    # a longer queue keeps a superset of what a shorter one keeps
+    shorter, _ = oracle.nearlossless(planes, scales, qp, qs, k, I=I, Tb=Tb, queue_len=qlen - 1)
+    exact, _ = oracle.topk(planes, scales, qp, qs, k)
+    assert oracle.recall(ids, exact) >= oracle.recall(shorter, exact)
+    if qlen >= I:                                          # every item is forwarded: the selector is exact
+        assert list(ids) == list(exact)
+
+
+def test_expected_recall_with_longer_queue_by_enumeration():
+    """Tiny case, every placement enumerated: C = 12 slots in threads of I = 3, N = 4 relevant items;
+    a thread with n relevant items keeps min(n, p)."""
+    from itertools import combinations
+    C, I, N = 12, 3, 4
+    for p in (1, 2, 3):
+        kept = 0
+        total = 0
+        for placement in combinations(range(C), N):
+            per_thread = [0] * (C // I)
+            for slot in placement:
+                per_thread[slot // I] += 1
+            kept += sum(min(n, p) for n in per_thread)
+            total += 1
+        assert oracle.expected_recall(N, C, I, queue_len=p) == pytest.approx(kept / (total * N), abs=1e-12)
+    assert oracle.expected_recall(N, C, I, queue_len=3) == 1.0
+    # the paper's operating point: a second queue entry removes almost all of the (already small) loss
+    r1 = oracle.expected_recall(1000, 10**9, 256, queue_len=1)
+    r2 = oracle.expected_recall(1000, 10**9, 256, queue_len=2)
+    assert r1 < r2 < 1.0 and 1 - r2 < 1e-7 and 1 - r1 == pytest.approx(1.274e-4, rel=1e-2)
+
+
 # ---------------------------------------------------------------- P7: Appendix A
 def test_table7_values():
     rows = {}
