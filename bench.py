@@ -248,6 +248,15 @@ def main():
             "recall_predicted_appendix_a": predicted, "queries": len(recalls),
         }
         log(f"near-lossless I={I}: {n_ms:.3f} ms/step, recall {np.mean(recalls):.5f} (Appendix A: {predicted:.5f})")
+        # the same selector with priority queues of length 2 (Algorithm 1 leaves the length open)
+        steps2 = max(2, args.steps // 2)
+        rn2 = timed_searches(rbe, torch, ix, qp1, qs1, 1, k, steps2, args.warmup, rbe.RBE_SELECT_NEARLOSSLESS_Q2, I)
+        rec2 = [len(set(a[0].tolist()) & set(b[0].tolist()) - {-1}) / k for a, b in zip(rn2["ids"], r1["ids"])]
+        out["near_lossless_queue2"] = {
+            "group_size_I": I, "ms_per_step": rn2["wall_s"] * 1e3 / steps2, "steps": steps2,
+            "recall_vs_exact_mean": float(np.mean(rec2)), "recall_vs_exact_min": float(np.min(rec2)),
+        }
+        log(f"near-lossless I={I}, queue length 2: {rn2['wall_s'] * 1e3 / steps2:.3f} ms/step, recall {np.mean(rec2):.5f}")
 
     # ---------------- hybrid scoring: fp32 query against the binary items (the paper's model m_5)
     if not args.no_hybrid:

@@ -37,6 +37,9 @@
  * x = z div (256 * I) would visit them, every group forwards only its best
  * item, and the k best forwarded items are returned (Appendix A gives the
  * probability that this loses any of the true top k).
+ * RBE_SELECT_NEARLOSSLESS_Q2 is the same with priority queues of length 2: every
+ * group forwards its two best items, so a true top-k item is lost only where
+ * three or more of them share a group.
  *
  * Conventions.  Every function returns RBE_OK (0) or a negative error code and
  * never aborts; rbe_last_error() gives a message for the calling thread's last
@@ -89,7 +92,7 @@ enum {
                             rbe_search must be NULL or exactly 2^-i.  dim 64 or 128.   */
 };
 
-enum { RBE_SELECT_EXACT = 0, RBE_SELECT_NEARLOSSLESS = 1 };
+enum { RBE_SELECT_EXACT = 0, RBE_SELECT_NEARLOSSLESS = 1, RBE_SELECT_NEARLOSSLESS_Q2 = 2 };
 
 /* Limits */
 #define RBE_MAX_PLANES 4u     /* P and Pq                                        */
@@ -181,7 +184,7 @@ int rbe_encode_query(const float *x, uint32_t dim, uint32_t n_planes,
  *   q_planes : [n_queries][q_n_planes][dim/64] uint64 (host)
  *   q_scales : [n_queries][q_n_planes] float (host), finite
  *   1 <= n_queries <= RBE_MAX_QUERIES, 1 <= q_n_planes <= 4, 1 <= k <= RBE_MAX_K
- *   mode     : RBE_SELECT_EXACT or RBE_SELECT_NEARLOSSLESS
+ *   mode     : RBE_SELECT_EXACT, RBE_SELECT_NEARLOSSLESS or RBE_SELECT_NEARLOSSLESS_Q2
  *   group_size_I : items per group for the near-lossless mode (the paper's I,
  *                  1..65535; 0 means 256); ignored in exact mode
  *   ids_out  : [n_queries][k] int64 (host), scores_out: [n_queries][k] float

@@ -22,7 +22,7 @@ RBE_OK, RBE_EINVAL, RBE_ENOMEM, RBE_EHIP, RBE_ESTATE, RBE_EUNSUPPORTED = 0, -1, 
 RBE_MEM_HOST, RBE_MEM_DEVICE = 0, 1
 RBE_COSINE = 1 << 1
 RBE_DYADIC = 1 << 2
-RBE_SELECT_EXACT, RBE_SELECT_NEARLOSSLESS = 0, 1
+RBE_SELECT_EXACT, RBE_SELECT_NEARLOSSLESS, RBE_SELECT_NEARLOSSLESS_Q2 = 0, 1, 2
 RBE_MAX_PLANES, RBE_MAX_QUERIES, RBE_MAX_K, RBE_MAX_LEVELS = 4, 64, 4096, 8
 RBE_MAX_ITEMS = 4294966272
 

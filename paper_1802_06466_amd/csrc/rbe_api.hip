@@ -741,6 +741,7 @@ struct Round { uint32_t begin, end, stride, skip; };
 
 struct SearchCtx {
     rbe_index* ix; hipStream_t st; uint32_t Q, PQ, k, cap, mode, I;
+    uint32_t qlen;      // near-lossless: entries per group queue (1 or 2); mode holds RBE_SELECT_NEARLOSSLESS for both
     bool float_query;   // hybrid scoring: fp32 queries through byte tables
     bool batch_mfma;    // exact mode, several queries: matrix-core scan
 };
@@ -749,7 +750,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
 {
     rbe_index* ix = c.ix;
     if (r.end <= r.begin) return RBE_OK;
-    const KernelSel sel{ix->P, c.PQ, ix->mode, c.Q == 1};
+    const KernelSel sel{ix->P, c.PQ, ix->mode, c.Q == 1, c.qlen};
     const CandList out{ix->d_cand, ix->d_count, ix->d_kmax, c.cap};
     uint32_t grid = 0;
     hipError_t e;
@@ -818,14 +819,14 @@ static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_
 // Rounds of the near-lossless mode: the same nested-sample idea over super-blocks.
 // Every super-block forwards at most 256 group winners; the coarsest sample is
 // read with no threshold and must fit the candidate list.
-static std::vector<Round> make_group_plan(uint32_t n_super, uint32_t ratio, uint32_t cap)
+static std::vector<Round> make_group_plan(uint32_t n_super, uint32_t ratio, uint32_t cap, uint32_t per_super)
 {
     std::vector<uint32_t> strides{1};
-    while ((uint64_t)((n_super + strides.back() - 1) / strides.back()) * kRow > cap &&
+    while ((uint64_t)((n_super + strides.back() - 1) / strides.back()) * per_super > cap &&
            strides.size() < RBE_MAX_LEVELS && strides.back() < n_super)
         strides.push_back(strides.back() * ratio);
     std::vector<Round> plan;
-    if ((uint64_t)((n_super + strides.back() - 1) / strides.back()) * kRow > cap) return plan;
+    if ((uint64_t)((n_super + strides.back() - 1) / strides.back()) * per_super > cap) return plan;
     for (size_t l = strides.size(); l-- > 0;) {
         Round r;
         r.stride = strides[l];
@@ -848,12 +849,12 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     // units of the slow path: tiles (exact) or super-blocks (near-lossless), `per_unit` candidates each at most
     const uint32_t rows_total = (uint32_t)((ix->n_items + kRow - 1) / kRow);
     const uint32_t n_units = mode == RBE_SELECT_EXACT ? ix->layout.n_tiles : (rows_total + c.I - 1) / c.I;
-    const uint32_t per_unit = mode == RBE_SELECT_EXACT ? kTileItems : kRow;
+    const uint32_t per_unit = mode == RBE_SELECT_EXACT ? kTileItems : kRow * c.qlen;
     std::vector<Round> plan;
     if (mode == RBE_SELECT_EXACT) {
         for (const Level& lv : make_plan(ix->layout, c.cap, k)) plan.push_back(Round{lv.p_begin, lv.p_end, 1, 0});
     } else {
-        plan = make_group_plan(n_units, ix->layout.ratio, c.cap);
+        plan = make_group_plan(n_units, ix->layout.ratio, c.cap, per_unit);
     }
 
     ix->stats = rbe_search_stats{};
@@ -921,9 +922,12 @@ static int search_prologue(rbe_index* ix, SearchCtx& c, uint32_t n_queries, uint
     ARG_CHECK(ids_out && scores_out, "NULL output argument");
     ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries must be 1..%u (got %u)", RBE_MAX_QUERIES, n_queries);
     ARG_CHECK(k >= 1 && k <= RBE_MAX_K, "k must be 1..%u (got %u)", RBE_MAX_K, k);
-    ARG_CHECK(mode == RBE_SELECT_EXACT || mode == RBE_SELECT_NEARLOSSLESS, "unknown mode %u", mode);
+    ARG_CHECK(mode == RBE_SELECT_EXACT || mode == RBE_SELECT_NEARLOSSLESS || mode == RBE_SELECT_NEARLOSSLESS_Q2,
+              "unknown mode %u", mode);
     ARG_CHECK(group_size_I <= 65535, "group_size_I must be <= 65535");
-    c.ix = ix; c.st = (hipStream_t)hip_stream; c.Q = n_queries; c.PQ = 1; c.k = k; c.mode = mode;
+    c.ix = ix; c.st = (hipStream_t)hip_stream; c.Q = n_queries; c.PQ = 1; c.k = k;
+    c.mode = mode == RBE_SELECT_NEARLOSSLESS_Q2 ? (uint32_t)RBE_SELECT_NEARLOSSLESS : mode;
+    c.qlen = mode == RBE_SELECT_NEARLOSSLESS_Q2 ? 2u : 1u;
     c.I = group_size_I ? group_size_I : 256;
     c.float_query = false;
     c.batch_mfma = false;

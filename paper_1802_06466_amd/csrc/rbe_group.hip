@@ -24,13 +24,14 @@ __device__ __forceinline__ const char* row_tile(const GroupArgs& a, const TileGe
     return a.tiles + (size_t)tile_to_phys(a.layout, row >> 2) * g.tile_bytes();
 }
 
-template <int W, int P, int PQ, int QB, int MODE>
+// QL = length of the priority queue of Algorithm 1 (1: the paper's choice; 2: the two best items of a group).
+template <int W, int P, int PQ, int QB, int MODE, int QL>
 __global__ __launch_bounds__(kBlock) void scan_groupmax(const GroupArgs a)
 {
     __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
     __shared__ uint32_t s_cnt_all[kWavesPerBlock][17];
-    __shared__ float s_best[QB][kWavesPerBlock][kItemsPerLane][64];
-    __shared__ uint32_t s_brow[QB][kWavesPerBlock][kItemsPerLane][64];
+    __shared__ float s_best[QB][QL][kWavesPerBlock][kItemsPerLane][64];
+    __shared__ uint32_t s_brow[QB][QL][kWavesPerBlock][kItemsPerLane][64];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -60,12 +61,14 @@ __global__ __launch_bounds__(kBlock) void scan_groupmax(const GroupArgs a)
         const uint32_t row0 = x * a.I;
         const uint32_t n_rows = a.rows_total - row0 < a.I ? a.rows_total - row0 : a.I;
 
-        float best[QB][kItemsPerLane];
-        uint32_t brow[QB][kItemsPerLane];
+        float best[QB][QL][kItemsPerLane];
+        uint32_t brow[QB][QL][kItemsPerLane];
 #pragma unroll
         for (int b = 0; b < QB; ++b)
 #pragma unroll
-            for (int m = 0; m < kItemsPerLane; ++m) { best[b][m] = ninf; brow[b][m] = 0xFFFFFFFFu; }
+            for (int e = 0; e < QL; ++e)
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m) { best[b][e][m] = ninf; brow[b][e][m] = 0xFFFFFFFFu; }
 
         uint32_t r = (uint32_t)wave;
         RowRegs<W, P, S> cur, nxt;
@@ -82,37 +85,72 @@ __global__ __launch_bounds__(kBlock) void scan_groupmax(const GroupArgs a)
                     float s = score_item<W, P, PQ, MODE>(cur, m, qr[b]) + 0.0f;
                     if (tail && row_id + lane_item<W>(lane, m) >= a.n_items) s = ninf;
                     // rows are visited in ascending order: ">" keeps the lowest id among equal scores
-                    if (s > best[b][m]) { best[b][m] = s; brow[b][m] = r; }
+                    if (QL == 1) {
+                        if (s > best[b][0][m]) { best[b][0][m] = s; brow[b][0][m] = r; }
+                    } else {
+                        const bool first = s > best[b][0][m];
+                        const bool second = !first && s > best[b][QL - 1][m];
+                        if (first || second) {
+                            best[b][QL - 1][m] = first ? best[b][0][m] : s;
+                            brow[b][QL - 1][m] = first ? brow[b][0][m] : r;
+                        }
+                        if (first) { best[b][0][m] = s; brow[b][0][m] = r; }
+                    }
                 }
             }
             if (rn < n_rows) cur = nxt;
             r = rn;
         }
 
-        // merge the four waves' partial winners: wave w finalises item slot m = w of every lane
+        // merge the four waves' queues: wave w finalises item slot m = w of every lane
 #pragma unroll
         for (int b = 0; b < QB; ++b)
 #pragma unroll
-            for (int m = 0; m < kItemsPerLane; ++m) { s_best[b][wave][m][lane] = best[b][m]; s_brow[b][wave][m][lane] = brow[b][m]; }
+            for (int e = 0; e < QL; ++e)
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m) {
+                    s_best[b][e][wave][m][lane] = best[b][e][m];
+                    s_brow[b][e][wave][m][lane] = brow[b][e][m];
+                }
         __syncthreads();
         for (int b = 0; b < QB; ++b) {
             if (b >= (int)a.nq) break;
-            float ws = ninf;
-            uint32_t wr = 0xFFFFFFFFu;
+            float ws[QL];
+            uint32_t wr[QL];
 #pragma unroll
-            for (int w = 0; w < kWavesPerBlock; ++w) {
-                const float s = s_best[b][w][wave][lane];
-                const uint32_t rr = s_brow[b][w][wave][lane];
-                if (rr != 0xFFFFFFFFu && (wr == 0xFFFFFFFFu || s > ws || (s == ws && rr < wr))) { ws = s; wr = rr; }
+            for (int e = 0; e < QL; ++e) { ws[e] = ninf; wr[e] = 0xFFFFFFFFu; }
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock; ++w)
+#pragma unroll
+                for (int e = 0; e < QL; ++e) {
+                    const float s = s_best[b][e][w][wave][lane];
+                    const uint32_t rr = s_brow[b][e][w][wave][lane];
+                    // insert (s, rr) into the merged queue: better = higher score, then lower row
+                    const bool valid = rr != 0xFFFFFFFFu;
+                    const bool beats0 = valid && (wr[0] == 0xFFFFFFFFu || s > ws[0] || (s == ws[0] && rr < wr[0]));
+                    if (QL == 1) {
+                        if (beats0) { ws[0] = s; wr[0] = rr; }
+                    } else {
+                        const bool beats1 = valid && !beats0 &&
+                                            (wr[QL - 1] == 0xFFFFFFFFu || s > ws[QL - 1] || (s == ws[QL - 1] && rr < wr[QL - 1]));
+                        if (beats0 || beats1) {
+                            ws[QL - 1] = beats0 ? ws[0] : s;
+                            wr[QL - 1] = beats0 ? wr[0] : rr;
+                        }
+                        if (beats0) { ws[0] = s; wr[0] = rr; }
+                    }
+                }
+#pragma unroll
+            for (int e = 0; e < QL; ++e) {
+                bool ok = (wr[e] != 0xFFFFFFFFu) && (ws[e] >= taus[b]);
+                uint64_t key = 0;
+                if (ok) {
+                    const uint64_t id = (uint64_t)(row0 + wr[e]) * kRow + lane_item<W>(lane, wave);
+                    key = make_key(ws[e], (uint32_t)id);
+                    ok = key >= tau[b];
+                }
+                mstage_append(ok, key, (uint32_t)b, ms, a.out, lane);
             }
-            bool ok = (wr != 0xFFFFFFFFu) && (ws >= taus[b]);
-            uint64_t key = 0;
-            if (ok) {
-                const uint64_t id = (uint64_t)(row0 + wr) * kRow + lane_item<W>(lane, wave);
-                key = make_key(ws, (uint32_t)id);
-                ok = key >= tau[b];
-            }
-            mstage_append(ok, key, (uint32_t)b, ms, a.out, lane);
         }
         __syncthreads();
     }
@@ -124,15 +162,21 @@ namespace {
 
 using GroupFn = void (*)(const GroupArgs);
 
-template <int W, int P, int PQ>
-GroupFn group_fn_m(int mode, bool single)
+// Queue length 2 is built for one query per launch (its state doubles the registers of a query).
+template <int W, int P, int PQ, int MODE>
+GroupFn group_fn_q(bool single, uint32_t qlen)
 {
-    if (mode == kModeScaled) return single ? scan_groupmax<W, P, PQ, 1, kModeScaled> : scan_groupmax<W, P, PQ, 4, kModeScaled>;
+    if (qlen == 2) return scan_groupmax<W, P, PQ, 1, MODE, 2>;
+    return single ? scan_groupmax<W, P, PQ, 1, MODE, 1> : scan_groupmax<W, P, PQ, 4, MODE, 1>;
+}
+
+template <int W, int P, int PQ>
+GroupFn group_fn_m(int mode, bool single, uint32_t qlen)
+{
+    if (mode == kModeScaled) return group_fn_q<W, P, PQ, kModeScaled>(single, qlen);
     if constexpr (dyadic_supported(W)) {
-        if (mode == kModeDyadicNorm)
-            return single ? scan_groupmax<W, P, PQ, 1, kModeDyadicNorm> : scan_groupmax<W, P, PQ, 4, kModeDyadicNorm>;
-        if (mode == kModeDyadic)
-            return single ? scan_groupmax<W, P, PQ, 1, kModeDyadic> : scan_groupmax<W, P, PQ, 4, kModeDyadic>;
+        if (mode == kModeDyadicNorm) return group_fn_q<W, P, PQ, kModeDyadicNorm>(single, qlen);
+        if (mode == kModeDyadic) return group_fn_q<W, P, PQ, kModeDyadic>(single, qlen);
     }
     return nullptr;
 }
@@ -149,10 +193,10 @@ GroupFn group_fn_m(int mode, bool single)
 GroupFn group_fn(const KernelSel& k)
 {
     switch (k.P) {
-        case 1: RBE_SWITCH_PQ(group_fn_m, 1, k.mode, k.single)
-        case 2: RBE_SWITCH_PQ(group_fn_m, 2, k.mode, k.single)
-        case 3: RBE_SWITCH_PQ(group_fn_m, 3, k.mode, k.single)
-        case 4: RBE_SWITCH_PQ(group_fn_m, 4, k.mode, k.single)
+        case 1: RBE_SWITCH_PQ(group_fn_m, 1, k.mode, k.single, k.qlen)
+        case 2: RBE_SWITCH_PQ(group_fn_m, 2, k.mode, k.single, k.qlen)
+        case 3: RBE_SWITCH_PQ(group_fn_m, 3, k.mode, k.single, k.qlen)
+        case 4: RBE_SWITCH_PQ(group_fn_m, 4, k.mode, k.single, k.qlen)
         default: return nullptr;
     }
 }
@@ -175,7 +219,7 @@ hipError_t launch_scan_groupmax_w<RBE_W>(const KernelSel& k, GroupArgs a, uint32
     const uint32_t units = a.v_end - a.v_begin;
     const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;
     if (grid_out) *grid_out = grid;
-    const uint32_t QB = k.single ? 1 : 4;
+    const uint32_t QB = (k.single || k.qlen == 2) ? 1 : 4;
     for (uint32_t q0 = 0; q0 < n_queries; q0 += QB) {   // the range is re-read once per block of QB queries
         a.q_begin = q0;
         a.nq = n_queries - q0 < QB ? n_queries - q0 : QB;

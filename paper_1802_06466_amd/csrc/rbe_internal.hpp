@@ -13,6 +13,7 @@ struct KernelSel {
     uint32_t P, PQ;   // corpus planes, query planes
     int mode;         // kModeScaled / kModeDyadicNorm / kModeDyadic
     bool single;      // one query per call
+    uint32_t qlen = 1;   // near-lossless mode: length of the per-group priority queue (1 or 2)
 };
 
 // Grid = min(units, n_cu * per_cu); per_cu == 0 means "as many workgroups as are

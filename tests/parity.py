@@ -74,24 +74,26 @@ def score_tolerance(scales, q_scales, d):
     return REL * d * float(np.sum(np.abs(q_scales))) * np.sum(scales.astype(np.float64), axis=0)
 
 
-def check_nearlossless(planes, scales, q_planes, q_scales, k, I, ids, scores, Tb=256):
-    """Check one query's near-lossless result against the oracle's Algorithm 1.
+def check_nearlossless(planes, scales, q_planes, q_scales, k, I, ids, scores, Tb=256, queue_len=1):
+    """Check one query's near-lossless result against the oracle's Algorithm 1 (priority
+    queues of `queue_len` entries).
 
-    The winner of a group is an argmax decided in fp32 on the GPU and in float64 in
-    the oracle, so a group may legitimately forward a different item when two of its
-    items score within rounding of each other.  Accepted iff
-      * every returned id is in range, ids are unique and no two share a group;
-      * the returned item is a (near-)winner of its group: its oracle score is within
-        eps of the oracle's winner of that group, and it carries the lowest id among
-        the group's items that the GPU scores exactly equal;
-      * every group whose oracle winner scores above s_k + eps is represented, and no
-        returned item scores below s_k - eps (s_k = the oracle result's k-th score);
+    What a group forwards is decided in fp32 on the GPU and in float64 in the oracle, so a
+    group may legitimately forward a different item when two of its items score within
+    rounding of each other.  Accepted iff
+      * every returned id is in range, ids are unique and at most queue_len share a group;
+      * every returned item belongs in its group's queue: its oracle score is within eps of
+        the oracle queue's last (worst) entry or better;
+      * for every group, at least as many items are returned as its oracle queue holds above
+        s_k + eps, and no returned item scores below s_k - eps (s_k = the oracle result's
+        k-th score);
       * scores match the oracle's score of the returned id; sorted (score desc, id asc);
-        the tail past the number of existing groups is (-1, -inf).
+        the tail past the number of forwarded items is (-1, -inf).
     """
     N = planes.shape[1]
     o_ids, o_sc, w_ids, w_sc = oracle.nearlossless(planes, scales, q_planes, q_scales, k, I=I, Tb=Tb,
-                                                   return_winners=True)
+                                                   return_winners=True, queue_len=queue_len)
+    w_ids = w_ids.reshape(-1, queue_len); w_sc = w_sc.reshape(-1, queue_len)
     n_live = int(np.sum(w_ids >= 0))
     m = min(k, n_live)
     ids = np.asarray(ids); scores = np.asarray(scores)
@@ -101,16 +103,21 @@ def check_nearlossless(planes, scales, q_planes, q_scales, k, I, ids, scores, Tb
         return
     assert got.min() >= 0 and got.max() < N and np.unique(got).size == m
     group = (got // (Tb * I)) * Tb + (got % Tb)
-    assert np.unique(group).size == m, "two results from one group"
+    per_group = np.bincount(group, minlength=w_ids.shape[0])
+    assert per_group.max() <= queue_len, "more results from one group than its queue holds"
     floor = rounding_floor(planes, scales, q_scales)
     s_k = o_sc[m - 1]
     eps = max(REL * abs(s_k), floor)
     true_sc = oracle.scores_at(planes, scales, q_planes, q_scales, got)
     np.testing.assert_allclose(scores[:m], true_sc, rtol=REL, atol=floor)
-    assert np.all(true_sc >= w_sc[group] - np.maximum(REL * np.abs(w_sc[group]), floor)), "not a winner of its group"
+    # worst entry of each oracle queue (a queue that is not full accepts anything)
+    worst = np.where(w_ids[:, -1] >= 0, w_sc[:, -1], -np.inf)
+    lim = worst[group]
+    assert np.all(true_sc >= lim - np.maximum(REL * np.abs(np.where(np.isfinite(lim), lim, 0.0)), floor)), \
+        "an item that does not belong in its group's queue"
     assert np.all(true_sc >= s_k - eps)
-    must = set(np.flatnonzero(w_sc > s_k + eps).tolist())
-    assert must <= set(group.tolist()), "a group above the k-th best winner is missing"
+    need = np.sum((w_ids >= 0) & (w_sc > s_k + eps), axis=1)
+    assert np.all(per_group >= need), "a queue entry above the k-th best forwarded item is missing"
     sc = scores[:m]
     assert np.all(sc[:-1] >= sc[1:])
     same = sc[:-1] == sc[1:]

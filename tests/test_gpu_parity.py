@@ -693,3 +693,61 @@ def test_matrix_core_batch_path_dyadic_is_bit_equal_to_popcount_path(d, P, Pq, Q
     qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
     check_batch(planes, oscales, qp, qs, k, ids_m, sc_m)
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ near-lossless selection, priority queues of length 2
+@pytest.mark.parametrize("N,I,Q,k,d,P", [(1000, 3, 2, 50, 64, 3), (65536, 256, 1, 100, 64, 3), (70001, 16, 5, 1000, 64, 2),
+                                         (300_000, 4, 3, 1000, 64, 3), (5000, 256, 2, 300, 64, 3), (200_003, 256, 4, 200, 128, 4),
+                                         (90_000, 64, 2, 150, 256, 2), (6_000_123, 2, 1, 4000, 64, 1)])
+def test_nearlossless_queue_length_two_matches_oracle(N, I, Q, k, d, P):
+    rng = np.random.default_rng(2 * N + I + Q + k)
+    planes, scales = random_corpus(rng, N, d, P)
+    qp, qs = random_queries(rng, Q, d, P)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k, mode=rbe.RBE_SELECT_NEARLOSSLESS_Q2, group_size_I=I)
+    for q in range(Q):
+        check_nearlossless(planes, scales, qp[q], qs[q], k, I, ids[q], sc[q], queue_len=2)
+    rbe.rbe_free(ix)
+
+
+def test_nearlossless_queue_length_two_exact_ties_and_dyadic():
+    """All scores equal: each group forwards its two lowest ids; dyadic weights: bit-equal to the oracle."""
+    N = 100_000
+    one = np.array([0x0F0F0F0F0F0F0F0F], dtype=np.uint64)
+    planes = np.broadcast_to(one, (2, N, 1)).copy()
+    scales = np.full((2, N), 0.5, dtype=np.float32)
+    qp = planes[:, :1].transpose(1, 0, 2).copy()
+    qs = np.ones((1, 2), dtype=np.float32)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 700, mode=rbe.RBE_SELECT_NEARLOSSLESS_Q2, group_size_I=256)
+    o_ids, _ = oracle.nearlossless(planes, scales, qp[0], qs[0], 700, I=256, queue_len=2)
+    np.testing.assert_array_equal(ids[0], o_ids)
+    rbe.rbe_free(ix)
+    rng = np.random.default_rng(77)
+    planes = rng.integers(0, 2**64, size=(2, 150_000, 1), dtype=np.uint64)
+    qp = rng.integers(0, 2**64, size=(3, 3, 1), dtype=np.uint64)
+    qs = np.tile(np.array([1.0, 0.5, 0.25], dtype=np.float32), (3, 1))
+    ix = rbe.rbe_load_corpus(planes, None, flags=rbe.RBE_DYADIC)
+    ids, sc = rbe.rbe_search(ix, qp, None, 300, mode=rbe.RBE_SELECT_NEARLOSSLESS_Q2, group_size_I=32)
+    for q in range(3):
+        o_ids, o_sc = oracle.nearlossless(planes, dyadic_weights(2, 150_000), qp[q], qs[q], 300, I=32, queue_len=2)
+        np.testing.assert_array_equal(ids[q], o_ids)
+        np.testing.assert_array_equal(sc[q], o_sc.astype(np.float32))
+    rbe.rbe_free(ix)
+
+
+def test_nearlossless_queue_length_two_recall():
+    """Same corpus and queries as the Appendix A check above: the second queue entry removes nearly all
+    of the loss, as the hypergeometric model of the oracle predicts; a multi-level plan is exercised too."""
+    N, I, k, Q = 2_097_152, 256, 1000, 32
+    planes, scales, qp, qs = clustered(N, 64, 3, 256, 0.3, Q, 3, seed=11)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    exact, _ = rbe.rbe_search(ix, qp, qs, k)
+    near1, _ = rbe.rbe_search(ix, qp, qs, k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=I)
+    near2, _ = rbe.rbe_search(ix, qp, qs, k, mode=rbe.RBE_SELECT_NEARLOSSLESS_Q2, group_size_I=I)
+    r1 = np.mean([oracle.recall(near1[q], exact[q]) for q in range(Q)])
+    r2 = np.mean([oracle.recall(near2[q], exact[q]) for q in range(Q)])
+    e2 = oracle.expected_recall(k, N, I, queue_len=2)
+    assert r2 > r1 and e2 > 0.99
+    assert abs(r2 - e2) < 4 * np.sqrt(e2 * (1 - e2) / (k * Q)) + 2e-3, (r2, e2)
+    rbe.rbe_free(ix)
