@@ -412,6 +412,20 @@ def main():
         out["calib_copy"] = {"bytes_read": nbytes, "bytes_written": nbytes, "kernel_ms": ms,
                              "gbs_read_plus_write": 2 * nbytes / (ms * 1e-3) / 1e9}
         log(f"calib_copy {args.calibrate_copy} MiB: {ms:.3f} ms -> {2 * nbytes / (ms * 1e-3) / 1e9:.0f} GB/s (r+w)")
+        # read-only yardstick over a buffer several times the 256 MB last-level cache
+        del dst
+        big = torch.full((max(nbytes, 16 << 30) // 4,), 1.0, dtype=torch.float32, device="cuda:0")
+        sink = torch.empty(8 << 20, dtype=torch.uint8, device="cuda:0")
+        rbe.rbe_debug_read(big, sink)
+        ev0.record()
+        for _ in range(5):
+            rbe.rbe_debug_read(big, sink)
+        ev1.record()
+        torch.cuda.synchronize()
+        rms = ev0.elapsed_time(ev1) / 5
+        rbytes = big.numel() * 4
+        out["calib_read"] = {"bytes_read": rbytes, "kernel_ms": rms, "gbs_read": rbytes / (rms * 1e-3) / 1e9}
+        log(f"calib_read {rbytes >> 20} MiB: {rms:.3f} ms -> {rbytes / (rms * 1e-3) / 1e9:.0f} GB/s")
 
     out["roofline"]["traffic"] = measured_traffic(out["config"]["workload"])
     if ix is not None:

@@ -313,6 +313,14 @@ int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, ui
  * counters report for it.  Asynchronous on the stream.                         */
 int rbe_debug_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
 
+/* Measurement yardstick: enqueues a read-only kernel ("calib_read") that streams
+ * `bytes` bytes from src_dev (DEVICE pointer, 16-byte aligned, bytes a multiple
+ * of 16) with the scan's access shape and writes 16 bytes per thread to
+ * sink_dev (DEVICE, 16-byte aligned, at least 3 * 256 * 16 bytes per compute
+ * unit: 3 MiB covers 256 units; EINVAL if too small).  Its rate is the practical
+ * read ceiling the scan is compared with.  Asynchronous on the stream.         */
+int rbe_debug_read(const void *src_dev, size_t bytes, void *sink_dev, size_t sink_bytes, void *hip_stream);
+
 const char *rbe_strerror(int code);
 const char *rbe_last_error(void);
 /* n_items / dim / n_planes of an index (0 for NULL). */

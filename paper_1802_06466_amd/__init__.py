@@ -80,6 +80,7 @@ PROTOTYPES = {
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_planes": (_i32, [_vp, _u64, _u64, _vp, _vp]),
     "rbe_debug_copy": (_i32, [_vp, _vp, ctypes.c_size_t, _vp]),
+    "rbe_debug_read": (_i32, [_vp, ctypes.c_size_t, _vp, ctypes.c_size_t, _vp]),
     "rbe_strerror": (ctypes.c_char_p, [_i32]),
     "rbe_last_error": (ctypes.c_char_p, []),
     "rbe_n_items": (_u64, [_vp]),
@@ -426,6 +427,14 @@ def rbe_debug_copy(dst, src, stream=None):
     if nbytes != dst.numel() * dst.element_size() or not (src.is_cuda and dst.is_cuda):
         raise RbeError(RBE_EINVAL, "src and dst must be cuda tensors of equal byte size")
     _check(load_library().rbe_debug_copy(_vp(dst.data_ptr()), _vp(src.data_ptr()), nbytes, _stream_ptr(stream)))
+
+
+def rbe_debug_read(src, sink, stream=None):
+    """Read-only streaming kernel over a torch cuda tensor; `sink` is a cuda tensor of >= 8 MiB."""
+    if not (src.is_cuda and sink.is_cuda):
+        raise RbeError(RBE_EINVAL, "src and sink must be cuda tensors")
+    _check(load_library().rbe_debug_read(_vp(src.data_ptr()), src.numel() * src.element_size(), _vp(sink.data_ptr()),
+                                         sink.numel() * sink.element_size(), _stream_ptr(stream)))
 
 
 def rbe_strerror(code: int) -> str:

@@ -1113,4 +1113,23 @@ int rbe_debug_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_s
     return RBE_OK;
 }
 
+int rbe_debug_read(const void* src_dev, size_t bytes, void* sink_dev, size_t sink_bytes, void* hip_stream)
+{
+    ARG_CHECK(src_dev && sink_dev, "NULL argument");
+    ARG_CHECK(bytes % 16 == 0 && ((uintptr_t)src_dev % 16) == 0 && ((uintptr_t)sink_dev % 16) == 0,
+              "size and pointers must be multiples of 16 bytes");
+    if (bytes == 0) return RBE_OK;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    const size_t n_vec = bytes / 16;
+    const uint32_t grid = (uint32_t)std::min<size_t>((n_vec + 2047) / 2048, (size_t)prop.multiProcessorCount * 3);
+    ARG_CHECK(sink_bytes >= (size_t)grid * 256 * 16, "sink must hold %zu bytes", (size_t)grid * 256 * 16);
+    hipLaunchKernelGGL(rbe::calib_read, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const rbe::u32x4*)src_dev, n_vec, (rbe::u32x4*)sink_dev);
+    HIP_TRY(hipGetLastError());
+    return RBE_OK;
+}
+
 }  // extern "C"

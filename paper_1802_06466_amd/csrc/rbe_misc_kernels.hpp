@@ -316,6 +316,31 @@ __global__ __launch_bounds__(256) void calib_copy(const u32x4* __restrict__ src,
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
 }
 
+// Read-only counterpart: a persistent grid in which every workgroup streams contiguous 32 KiB
+// chunks (eight 16-byte non-temporal loads in flight per lane, the access shape of the scan) and
+// folds them into one value per lane, stored once at the end.  What this reaches is the practical
+// ceiling for a kernel that only reads.
+__global__ __launch_bounds__(256) void calib_read(const u32x4* __restrict__ src, size_t n_vec, u32x4* __restrict__ sink)
+{
+    constexpr int kUnroll = 8;
+    const size_t per_iter = (size_t)kUnroll * 256;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    size_t base = (size_t)blockIdx.x * per_iter;
+    for (; base + per_iter <= n_vec; base += (size_t)gridDim.x * per_iter) {
+        u32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(src + base + u * 256 + threadIdx.x);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+    }
+    for (size_t i = base + threadIdx.x; i < n_vec && base < n_vec; i += 256) {   // the one ragged chunk at the end
+        if (i >= base + per_iter) break;
+        const u32x4 a = __builtin_nontemporal_load(src + i);
+        acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
+    }
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
 // ---------------------------------------------------------------- dense helpers (tests, cosine fold)
 __global__ void dense_popcounts(const char* __restrict__ tiles, const Layout l, const TileGeom g,
                                 const uint64_t* __restrict__ qplanes, uint32_t PQ,

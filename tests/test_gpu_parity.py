@@ -751,3 +751,22 @@ def test_nearlossless_queue_length_two_recall():
     assert r2 > r1 and e2 > 0.99
     assert abs(r2 - e2) < 4 * np.sqrt(e2 * (1 - e2) / (k * Q)) + 2e-3, (r2, e2)
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ measurement yardsticks
+@pytest.mark.parametrize("n_vec", [1, 255, 2048, 2049, 1_000_003])
+def test_read_yardstick_touches_every_vector(n_vec):
+    """calib_read folds every 16-byte vector of the source exactly once (XOR), ragged tail included."""
+    import torch
+    rng = np.random.default_rng(n_vec)
+    host = rng.integers(0, 2**32, size=(n_vec, 4), dtype=np.uint32)
+    src = torch.from_numpy(host.view(np.int32)).cuda()
+    sink = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda:0")
+    rbe.rbe_debug_read(src, sink)
+    torch.cuda.synchronize()
+    folded = sink.cpu().numpy().view(np.uint32).reshape(-1, 4)
+    np.testing.assert_array_equal(np.bitwise_xor.reduce(folded, axis=0), np.bitwise_xor.reduce(host, axis=0))
+    dst = torch.empty_like(src)
+    rbe.rbe_debug_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
