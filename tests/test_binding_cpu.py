@@ -252,3 +252,13 @@ def test_matrix_core_operands_stay_in_half_range(lib):
     assert np.isfinite(start).all() and (unscale > 0).all()
     lg = np.log2(unscale.astype(np.float64))
     assert np.array_equal(lg, np.round(lg))       # powers of two
+
+
+# ------------------------------------------------------------------ compiled code: wave-wide steps stay wave-wide
+def test_scan_kernels_have_no_lane_peeling_loops():
+    """Compiles the scan units to gfx950 assembly (no GPU needed) and checks that no kernel with
+    wave-wide survivor staging contains a loop that removes lanes from the execution mask: such a
+    loop once made the two halves of a wave run their ballots and flushes separately and lose
+    entries.  Kernels whose per-lane loops are intended are listed in the checker."""
+    from paper_1802_06466_amd import _check_isa
+    assert _check_isa.main() == 0
