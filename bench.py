@@ -276,6 +276,19 @@ def main():
                                      "scan_kernel_ms": float(np.mean(h_scan)), "hbm_gbs": h_gbs,
                                      "hbm_frac": h_gbs / HBM_PEAK_GBS}
         log(f"hybrid fp32 query: {h_ms:.3f} ms/step, scan kernel {np.mean(h_scan):.3f} ms -> {h_gbs:.0f} GB/s")
+        if args.batch >= 4:
+            B = args.batch
+            xb = rbe_synth.vectors_torch(B * 4, centres, args.sigma, rbe_synth.SEED_QUERIES, 5).cpu().numpy()
+            rbe.rbe_search_float(ix, xb[:B], k)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s_ in range(1, 4):
+                rbe.rbe_search_float(ix, xb[s_ * B:(s_ + 1) * B], k)
+            torch.cuda.synchronize()
+            hb_ms = (time.perf_counter() - t0) * 1e3 / 3
+            out["hybrid_float_query"]["batch"] = {"queries_per_step": B, "ms_per_step": hb_ms,
+                                                  "value": N * B / (hb_ms * 1e-3), "unit": "candidates/s"}
+            log(f"hybrid fp32 queries, Q={B}: {hb_ms:.3f} ms/step")
 
     # ---------------- batch leg
     if args.batch > 0:

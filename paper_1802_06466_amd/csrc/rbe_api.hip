@@ -269,7 +269,9 @@ uint32_t batch_tiles_per_launch(const rbe_index* ix)
 
 bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query)
 {
-    if (mode != RBE_SELECT_EXACT || float_query || !rbe::batch_mfma_supported(ix->W)) return false;
+    if (mode != RBE_SELECT_EXACT || !rbe::batch_mfma_supported(ix->W)) return false;
+    // full-precision queries need both halves; the dyadic kernels carry one (their queries are exact in it)
+    if (float_query && ix->mode != rbe::kModeScaled) return false;
     if (ix->batch_path == 1) return false;
     if (ix->batch_path == 2) return true;
     return Q >= 4;   // below that the XOR/popcount kernel is at or near the HBM bound already
@@ -301,8 +303,11 @@ BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint3
     return sh;
 }
 
+// q_float != nullptr: the queries are given in full precision ([Q][dim], hybrid scoring) and q_planes / q_scales
+// are not read; general scales only.
 void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q_planes, const float* q_scales,
-                          uint32_t Q, uint32_t PQ, uint16_t* halves, float* unscale, float* bias)
+                          uint32_t Q, uint32_t PQ, uint16_t* halves, float* unscale, float* bias,
+                          const float* q_float = nullptr)
 {
     const BatchOperandShape sh = batch_operand_shape(W, P, dyadic, Q);
     const uint32_t dim = 64 * W, KP = sh.parts, TERMS = sh.terms, PA = sh.copies;
@@ -313,10 +318,14 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
         double biggest = 0.0;
         for (uint32_t d = 0; d < dim; ++d) {
             double v = 0.0;
-            for (uint32_t i = 0; i < PQ; ++i) {
-                const double c = dyadic ? std::ldexp(1.0, -(int)i) : (double)q_scales[(size_t)q * PQ + i];
-                const uint64_t word = q_planes[((size_t)q * PQ + i) * W + d / 64];
-                v += ((word >> (d % 64)) & 1ull) ? c : -c;
+            if (q_float) {
+                v = (double)q_float[(size_t)q * dim + d];
+            } else {
+                for (uint32_t i = 0; i < PQ; ++i) {
+                    const double c = dyadic ? std::ldexp(1.0, -(int)i) : (double)q_scales[(size_t)q * PQ + i];
+                    const uint64_t word = q_planes[((size_t)q * PQ + i) * W + d / 64];
+                    v += ((word >> (d % 64)) & 1ull) ? c : -c;
+                }
             }
             qhat[d] = v;
             biggest = std::max(biggest, std::fabs(v));
@@ -352,7 +361,7 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
 }
 
 int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
-                        hipStream_t st)
+                        hipStream_t st, const float* q_float = nullptr)
 {
     const size_t max_halves = (size_t)(RBE_MAX_QUERIES / 16) * 4 * 4 * 64 * 8;   // per tile: (terms x copies) x parts <= 16
     if (!ix->d_aops) {
@@ -364,7 +373,7 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
     const bool dyadic = ix->mode != rbe::kModeScaled;
     const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q);
     build_batch_operands(ix->W, ix->P, dyadic, q_planes, q_scales, Q, PQ, reinterpret_cast<uint16_t*>(ix->h_aops),
-                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES);
+                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float);
     HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, sh.n_halves * sizeof(uint16_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
@@ -967,8 +976,16 @@ int rbe_search_float(rbe_index* ix, const float* q, uint32_t n_queries, uint32_t
         set_error("rbe_search_float is built for RBE_SELECT_EXACT only");
         return RBE_EUNSUPPORTED;
     }
-    c.float_query = true;
-    rc = stage_float_queries(ix, q, c.Q, c.st);
+    for (size_t i = 0; i < (size_t)c.Q * ix->dim; ++i)
+        if (!std::isfinite(q[i])) { set_error("q[%zu][%zu] is not finite", i / ix->dim, i % ix->dim); return RBE_EINVAL; }
+    c.batch_mfma = use_batch_mfma(ix, c.Q, mode, true);
+    if (c.batch_mfma) {
+        // several queries: the same dense contraction as for binary queries, with the query itself as operand
+        rc = stage_batch_queries(ix, nullptr, nullptr, c.Q, 0, c.st, q);
+    } else {
+        c.float_query = true;
+        rc = stage_float_queries(ix, q, c.Q, c.st);
+    }
     if (rc) return rc;
     return run_search(c, ids_out, scores_out);
 }

@@ -770,3 +770,34 @@ def test_read_yardstick_touches_every_vector(n_vec):
     rbe.rbe_debug_copy(dst, src)
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
+
+
+# ------------------------------------------------------------------ hybrid scoring, batches on the matrix cores
+@pytest.mark.parametrize("N,d,P,Q,k", [(150_001, 64, 3, 16, 500), (60_000, 128, 4, 5, 300), (80_000, 64, 2, 40, 100),
+                                       (1, 64, 1, 4, 1)])
+def test_float_query_batches_use_the_matrix_cores_and_match_the_table_path(N, d, P, Q, k):
+    """Four or more fp32 queries per call are scored as one dense contraction (the query itself is the
+    left operand) instead of one table pass per query; both must pass the oracle's hybrid score."""
+    c = rbe_synth.centres_numpy(32, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=60 + N % 97)
+    q = rbe_synth.vectors_numpy(Q, c, 0.3, seed=61)
+    q[0] *= 37.5                       # scores scale with the query; the power-of-two scaling must follow
+    planes, scales = oracle.encode(x, P)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids_m, sc_m = rbe.rbe_search_float(ix, q, k)
+    rbe.rbe_debug_set_batch_path(ix, 1)
+    ids_t, sc_t = rbe.rbe_search_float(ix, q, k)
+    for i in range(Q):
+        check_topk_float(planes, scales, q[i], k, ids_m[i], sc_m[i])
+        check_topk_float(planes, scales, q[i], k, ids_t[i], sc_t[i])
+    np.testing.assert_allclose(sc_m, sc_t, rtol=1e-5)
+    rbe.rbe_free(ix)
+    # dyadic index: the one-half kernels cannot carry a full-precision query; the table path serves any batch
+    rng = np.random.default_rng(62)
+    dplanes = rng.integers(0, 2**64, size=(2, 50_000, d // 64), dtype=np.uint64) if d <= 128 else None
+    if dplanes is not None:
+        ixd = rbe.rbe_load_corpus(dplanes, None, flags=rbe.RBE_DYADIC)
+        ids, sc = rbe.rbe_search_float(ixd, q[:6], 50)
+        for i in range(min(6, Q)):
+            check_topk_float(dplanes, dyadic_weights(2, 50_000), q[i], 50, ids[i], sc[i])
+        rbe.rbe_free(ixd)
