@@ -153,7 +153,7 @@ def main():
 
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the whole 1e9-item corpus fits one MI355X); "
-              "--gpus must be 1. Item-range sharding across GPUs is described in DESIGN.md but not built.",
+              "--gpus must be 1: item-range sharding across GPUs is not built.",
               file=sys.stderr)
         sys.exit(2)
 
