@@ -20,16 +20,16 @@ pytestmark = pytest.mark.gpu
 CHUNK = 4_000_000
 
 
-def build(N, d, P, n_clusters, sigma, progress):
+def build(N, d, P, n_clusters, sigma, progress, flags=0):
     import torch
     dev = torch.device("cuda:0")
     centres = rbe_synth.centres_torch(n_clusters, d, dev)
-    ix = rbe.rbe_index_create(N, d, P)
+    ix = rbe.rbe_index_create(N, d, P, flags)
     for c, z0 in enumerate(range(0, N, CHUNK)):
         n = min(CHUNK, N - z0)
         x = rbe_synth.vectors_torch(n, centres, sigma, rbe_synth.SEED_ITEMS, c)
         planes, scales = rbe_synth.pack_planes_torch(x, P)
-        rbe.rbe_load_chunk(ix, z0, planes, scales)
+        rbe.rbe_load_chunk(ix, z0, planes, None if flags & rbe.RBE_DYADIC else scales)
         if c % 50 == 0:
             print(f"  {progress}: loaded {z0 + n} items", flush=True)
     rbe.rbe_finalize(ix)
@@ -37,12 +37,23 @@ def build(N, d, P, n_clusters, sigma, progress):
     return ix, centres
 
 
-def chunk_on_host(c, N, centres, sigma, P):
+def chunk_on_host(c, N, centres, sigma, P, dyadic_cosine=False):
+    """Chunk c regenerated for the oracle.  dyadic_cosine: the planes alone are the corpus (weights
+    2^-j); the oracle gets those weights divided by the reconstructed norm (Sec. 5.1)."""
     z0 = c * CHUNK
     n = min(CHUNK, N - z0)
     x = rbe_synth.vectors_torch(n, centres, sigma, rbe_synth.SEED_ITEMS, c)
     planes, scales = rbe_synth.pack_planes_torch(x, P)
-    return z0, planes.cpu().numpy().view(np.uint64), scales.cpu().numpy()
+    planes = planes.cpu().numpy().view(np.uint64)
+    if dyadic_cosine:
+        return z0, planes, None          # oracle scales are derived per subset, see dyadic_cosine_scales
+    return z0, planes, scales.cpu().numpy()
+
+
+def dyadic_cosine_scales(planes):
+    P, n = planes.shape[0], planes.shape[1]
+    w = np.array([2.0 ** -j for j in range(P)], dtype=np.float32)[:, None] * np.ones((P, n), dtype=np.float32)
+    return oracle.fold_cosine(planes, w)
 
 
 def queries(centres, n, sigma, P):
@@ -51,7 +62,7 @@ def queries(centres, n, sigma, P):
     return np.stack([e[0] for e in enc]), np.stack([e[1] for e in enc])
 
 
-def verify(N, centres, sigma, P, qp, qs, k, ids, sc, full_scan_queries, sampled_chunks, label):
+def verify(N, centres, sigma, P, qp, qs, k, ids, sc, full_scan_queries, sampled_chunks, label, dyadic_cosine=False):
     """ids/sc: [Q][k] results.  Queries listed in full_scan_queries get the exact oracle top-k
     over every chunk; all queries get per-id score checks and completeness on sampled_chunks."""
     Q = qp.shape[0]
@@ -60,12 +71,20 @@ def verify(N, centres, sigma, P, qp, qs, k, ids, sc, full_scan_queries, sampled_
     merged = {q: (np.empty(0, np.int64), np.empty(0)) for q in full_scan_queries}
     kth = sc[:, k - 1].astype(np.float64)
     for c in range(n_chunks):
-        z0, planes, scales = chunk_on_host(c, N, centres, sigma, P)
+        z0, planes, scales = chunk_on_host(c, N, centres, sigma, P, dyadic_cosine)
         n = planes.shape[1]
+        need_all = bool(merged) or c in sampled_chunks
+        if dyadic_cosine and need_all:
+            scales = dyadic_cosine_scales(planes)
         for q in range(Q):
             sel = np.flatnonzero((ids[q] >= z0) & (ids[q] < z0 + n))
             if sel.size:
-                true_sc[q, sel] = oracle.scores_at(planes, scales, qp[q], qs[q], ids[q][sel] - z0)
+                loc = ids[q][sel] - z0
+                if scales is None:        # only the returned items of this chunk are needed
+                    sub = np.ascontiguousarray(planes[:, loc])
+                    true_sc[q, sel] = oracle.scores_at(sub, dyadic_cosine_scales(sub), qp[q], qs[q], np.arange(loc.size))
+                else:
+                    true_sc[q, sel] = oracle.scores_at(planes, scales, qp[q], qs[q], loc)
             if q in merged:
                 c_ids, c_sc = oracle.topk(planes, scales, qp[q], qs[q], k)
                 a_ids = np.concatenate([merged[q][0], c_ids[c_ids >= 0] + z0])
@@ -157,3 +176,25 @@ def test_1e9_near_duplicate_clusters_batch8_top4000():
     expect = oracle.expected_recall(k, 15259 * 65536, 256)
     print(f"  near-lossless recall {rec:.5f}, Appendix A predicts {expect:.5f}", flush=True)
     assert abs(rec - expect) < 1.5e-3
+
+
+def test_paper_operating_point_1212153856_items_dyadic():
+    """The paper's own operating point at full size: 136^2 x 256^2 keywords, 2 keyword + 3 query bits per
+    dimension, residual weights 2^-t, stored inverse norm (20 B per keyword).  One query (shift-add kernel),
+    16 queries (matrix cores, one query half) and the near-lossless selector; every returned score against
+    the oracle, completeness on sampled chunks."""
+    N, d, P, Pq, k, sigma = 136 * 136 * 256 * 256, 64, 2, 3, 1000, 0.3
+    ix, centres = build(N, d, P, 4096, sigma, "paper point", flags=rbe.RBE_DYADIC | rbe.RBE_COSINE)
+    qp, _ = queries(centres, 17, sigma, Pq)
+    qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (17, 1))
+    ids1, sc1 = rbe.rbe_search(ix, qp[:1], None, k)
+    assert not rbe.rbe_get_search_stats(ix)["fallback"]
+    ids16, sc16 = rbe.rbe_search(ix, qp[1:], None, k)
+    near, nsc = rbe.rbe_search(ix, qp[:1], None, k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=256)
+    rbe.rbe_free(ix)
+    ids = np.concatenate([ids1, ids16]); sc = np.concatenate([sc1, sc16])
+    # the oracle's norm fold costs ~0.1 us per item on one core: completeness is checked on 12 of the 304 chunks
+    verify(N, centres, sigma, P, qp, qs, k, ids, sc, full_scan_queries=[],
+           sampled_chunks={0, 5, 33, 61, 99, 127, 150, 188, 222, 260, 300, 303}, label="paper point", dyadic_cosine=True)
+    lost = k - len(set(near[0].tolist()) & set(ids1[0].tolist()))
+    assert lost <= 4
