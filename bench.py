@@ -276,7 +276,7 @@ def main():
                                      "scan_kernel_ms": float(np.mean(h_scan)), "hbm_gbs": h_gbs,
                                      "hbm_frac": h_gbs / HBM_PEAK_GBS}
         log(f"hybrid fp32 query: {h_ms:.3f} ms/step, scan kernel {np.mean(h_scan):.3f} ms -> {h_gbs:.0f} GB/s")
-        if args.batch >= 4:
+        if args.batch >= 3:
             B = args.batch
             xb = rbe_synth.vectors_torch(B * 4, centres, args.sigma, rbe_synth.SEED_QUERIES, 5).cpu().numpy()
             rbe.rbe_search_float(ix, xb[:B], k)
@@ -299,7 +299,7 @@ def main():
         b_ms = rb["wall_s"] * 1e3 / args.batch_steps
         b_scan = float(rb["scan_ms"].mean()) if rb["scan_ms"].size else float("nan")
         b_items = rb["stats"]["items_scanned"][-1]
-        matrix_cores = B >= 4 and W <= 2     # the library's own choice of kernel for a batch
+        matrix_cores = B >= 8 and W <= 2     # the library's own choice of kernel for a batch
         if matrix_cores:
             # dense contraction [B x d] . [d x items] per corpus plane; the fp16 hi + lo split of the
             # query (general scales) doubles what the kernel issues, padding to 16 queries adds more
@@ -391,7 +391,7 @@ def main():
         }
         log(f"paper point: exact {rp['wall_s'] * 1e3 / args.steps:.3f} ms/step ({p_gbs:.0f} GB/s), "
             f"near-lossless {rpn['wall_s'] * 1e3 / args.steps:.3f} ms/step, recall {np.mean(rec):.5f}")
-        if args.batch >= 4:
+        if args.batch >= 8:
             B = args.batch
             qpb, _ = make_queries(rbe, rbe_synth, torch, centres_p, (2 + args.batch_steps) * B, args.sigma, Pq, 3)
             rpb = timed_searches(rbe, torch, ixp, qpb, None, B, k, args.batch_steps, 2)

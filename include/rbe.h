@@ -21,7 +21,7 @@
  * The popcounts are exact integers; the combination is evaluated in fp32 in
  * the order written (i inner, j outer), each inner sum starting from
  * dim * sum_i c_i and accumulating -2 c_i * popcount with fused multiply-adds.
- * With 4 or more queries per call (exact mode, dim <= 128) the same score is
+ * With 8 or more queries per call (exact mode, dim <= 128) the same score is
  * evaluated on the matrix cores instead, as sum_j a_j[z] * (qhat . b_z^j) with
  * qhat = sum_i c_i b_q^i reconstructed on the host in double, scaled by a power
  * of two and carried as two half-precision terms (about 22 bits; one term, exact,
@@ -206,7 +206,7 @@ int rbe_search(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
  * T[p][byte], T[p][v] = sum_{b<8} q[8p+b] * (bit b of v ? +1 : -1) (built in double,
  * stored as fp32, added in fp32 in byte order), then fp32 fused multiply-adds over j.
  * For RBE_DYADIC indexes a_j = 2^-j (times the stored inverse norm with RBE_COSINE).
- * With 4 or more queries per call on an index with general scales (dim <= 128) the
+ * With 3 or more queries per call on an index with general scales (dim <= 128) the
  * batch is scored on the matrix cores instead, exactly as rbe_search does with the
  * reconstructed binary queries (q itself is the left operand, split in two halves),
  * and the corpus is read once per 32 queries; otherwise it is read once per query.
@@ -261,7 +261,7 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
                      uint32_t q_n_planes, uint64_t first_item, uint64_t count,
                      float *out, void *hip_stream);
 
-/* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 4
+/* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 8
  * queries per call on, dim <= 128), 1 = always the XOR/popcount kernel, 2 = the
  * matrix-core kernel for any number of queries (dim <= 128).                     */
 int rbe_debug_set_batch_path(rbe_index *ix, int path);

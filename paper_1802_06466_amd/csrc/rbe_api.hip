@@ -274,7 +274,10 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
     if (float_query && ix->mode != rbe::kModeScaled) return false;
     if (ix->batch_path == 1) return false;
     if (ix->batch_path == 2) return true;
-    return Q >= 4;   // below that the XOR/popcount kernel is at or near the HBM bound already
+    // Measured crossover (1e9 items d=64 P=3, 1e8 items d=128 P=4): a 16-query tile costs the matrix-core scan
+    // about as much as 8 queries cost the XOR/popcount scan.  The byte-table scan of fp32 queries reads the
+    // corpus once per query, so there the matrix cores win from 3 queries on.
+    return Q >= (float_query ? 3u : 8u);
 }
 
 // Matrix-core operands of a batch (pure host arithmetic).  Each query is reconstructed in double as

@@ -776,7 +776,7 @@ def test_read_yardstick_touches_every_vector(n_vec):
 @pytest.mark.parametrize("N,d,P,Q,k", [(150_001, 64, 3, 16, 500), (60_000, 128, 4, 5, 300), (80_000, 64, 2, 40, 100),
                                        (1, 64, 1, 4, 1)])
 def test_float_query_batches_use_the_matrix_cores_and_match_the_table_path(N, d, P, Q, k):
-    """Four or more fp32 queries per call are scored as one dense contraction (the query itself is the
+    """Three or more fp32 queries per call are scored as one dense contraction (the query itself is the
     left operand) instead of one table pass per query; both must pass the oracle's hybrid score."""
     c = rbe_synth.centres_numpy(32, d)
     x = rbe_synth.vectors_numpy(N, c, 0.3, seed=60 + N % 97)
