@@ -46,6 +46,9 @@ void set_error(const char* fmt, ...)
     } while (0)
 
 constexpr uint32_t kMaxEvents = 2 * RBE_MAX_LEVELS + 2;
+// layout of the block a search sends back (rbe_index::d_result)
+constexpr size_t kResultStatusBytes = 256;
+constexpr size_t kResultHeaderBytes = kResultStatusBytes + (size_t)RBE_MAX_LEVELS * RBE_MAX_QUERIES * sizeof(uint32_t);
 
 }  // namespace
 
@@ -70,6 +73,11 @@ struct rbe_index {
     uint32_t* d_count = nullptr;
     uint64_t* d_tau = nullptr;
     uint64_t* d_kmax = nullptr;
+    // One block holds everything a search sends back, so that one copy fetches it:
+    //   [status: kResultStatusBytes][seen: RBE_MAX_LEVELS x RBE_MAX_QUERIES u32][ids: Q x k i64][scores: Q x k f32]
+    // (ids and scores packed for the Q and k of the current call).  The pointers below point into it.
+    char* d_result = nullptr;
+    char* h_result = nullptr;       // pinned mirror
     uint32_t* d_status = nullptr;
     uint32_t* d_seen = nullptr;     // [RBE_MAX_LEVELS][RBE_MAX_QUERIES]
     uint32_t* d_aops = nullptr;     // matrix-core query operands (BatchArgs::a_ops)
@@ -157,10 +165,11 @@ hipError_t launch_dense_scores(uint32_t W, const KernelSel& k, const char* tiles
 void free_workspace(rbe_index* ix)
 {
     (void)hipFree(ix->d_cand);   ix->d_cand = nullptr;
-    (void)hipFree(ix->d_ids);    ix->d_ids = nullptr;
-    (void)hipFree(ix->d_scores); ix->d_scores = nullptr;
-    (void)hipHostFree(ix->h_ids);    ix->h_ids = nullptr;
-    (void)hipHostFree(ix->h_scores); ix->h_scores = nullptr;
+    (void)hipFree(ix->d_result);     ix->d_result = nullptr;
+    (void)hipHostFree(ix->h_result); ix->h_result = nullptr;
+    ix->d_status = ix->d_seen = ix->h_status = ix->h_seen = nullptr;
+    ix->d_ids = ix->h_ids = nullptr;
+    ix->d_scores = ix->h_scores = nullptr;
     ix->ws_queries = ix->ws_cap = ix->ws_k = 0;
 }
 
@@ -171,14 +180,12 @@ int ensure_fixed(rbe_index* ix)
     HIP_TRY(hipMalloc(&ix->d_count, Q * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&ix->d_tau, Q * sizeof(uint64_t)));
     HIP_TRY(hipMalloc(&ix->d_kmax, Q * sizeof(uint64_t)));
-    HIP_TRY(hipMalloc(&ix->d_status, sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&ix->d_seen, RBE_MAX_LEVELS * Q * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&ix->d_qwords, Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&ix->d_qcoef, Q * (RBE_MAX_PLANES + 1) * sizeof(float)));
-    HIP_TRY(hipHostMalloc(&ix->h_qwords, Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t), hipHostMallocDefault));
-    HIP_TRY(hipHostMalloc(&ix->h_qcoef, Q * (RBE_MAX_PLANES + 1) * sizeof(float), hipHostMallocDefault));
-    HIP_TRY(hipHostMalloc(&ix->h_status, sizeof(uint32_t), hipHostMallocDefault));
-    HIP_TRY(hipHostMalloc(&ix->h_seen, RBE_MAX_LEVELS * Q * sizeof(uint32_t), hipHostMallocDefault));
+    // query words and coefficients share one block (coefficients at a fixed offset) so that one copy stages both
+    const size_t words_bytes = Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t), coef_bytes = Q * (RBE_MAX_PLANES + 1) * sizeof(float);
+    HIP_TRY(hipMalloc(&ix->d_qwords, words_bytes + coef_bytes));
+    HIP_TRY(hipHostMalloc(&ix->h_qwords, words_bytes + coef_bytes, hipHostMallocDefault));
+    ix->d_qcoef = reinterpret_cast<float*>(reinterpret_cast<char*>(ix->d_qwords) + words_bytes);
+    ix->h_qcoef = reinterpret_cast<float*>(reinterpret_cast<char*>(ix->h_qwords) + words_bytes);
     for (uint32_t i = 0; i < kMaxEvents; ++i) HIP_TRY(hipEventCreate(&ix->ev[i]));
     ix->ev_ok = true;
     return RBE_OK;
@@ -192,10 +199,15 @@ int ensure_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
     const uint32_t nQ = std::max(Q, ix->ws_queries), nC = std::max(cap, ix->ws_cap), nK = std::max(k, ix->ws_k);
     free_workspace(ix);
     HIP_TRY(hipMalloc(&ix->d_cand, (size_t)nQ * nC * sizeof(uint64_t)));
-    HIP_TRY(hipMalloc(&ix->d_ids, (size_t)nQ * nK * sizeof(int64_t)));
-    HIP_TRY(hipMalloc(&ix->d_scores, (size_t)nQ * nK * sizeof(float)));
-    HIP_TRY(hipHostMalloc(&ix->h_ids, (size_t)nQ * nK * sizeof(int64_t), hipHostMallocDefault));
-    HIP_TRY(hipHostMalloc(&ix->h_scores, (size_t)nQ * nK * sizeof(float), hipHostMallocDefault));
+    const size_t result_bytes = kResultHeaderBytes + (size_t)nQ * nK * (sizeof(int64_t) + sizeof(float));
+    HIP_TRY(hipMalloc(&ix->d_result, result_bytes));
+    HIP_TRY(hipHostMalloc(&ix->h_result, result_bytes, hipHostMallocDefault));
+    ix->d_status = reinterpret_cast<uint32_t*>(ix->d_result);
+    ix->h_status = reinterpret_cast<uint32_t*>(ix->h_result);
+    ix->d_seen = reinterpret_cast<uint32_t*>(ix->d_result + kResultStatusBytes);
+    ix->h_seen = reinterpret_cast<uint32_t*>(ix->h_result + kResultStatusBytes);
+    ix->d_ids = reinterpret_cast<int64_t*>(ix->d_result + kResultHeaderBytes);
+    ix->h_ids = reinterpret_cast<int64_t*>(ix->h_result + kResultHeaderBytes);
     ix->ws_queries = nQ; ix->ws_cap = nC; ix->ws_k = nK;
     return RBE_OK;
 }
@@ -228,8 +240,8 @@ int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales
         }
         ix->h_qcoef[(size_t)q * (PQ + 1) + PQ] = (float)ix->dim * sum;
     }
-    HIP_TRY(hipMemcpyAsync(ix->d_qwords, ix->h_qwords, (size_t)Q * PQ * 2 * W * sizeof(uint32_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(ix->d_qcoef, ix->h_qcoef, (size_t)Q * (PQ + 1) * sizeof(float), hipMemcpyHostToDevice, st));
+    const size_t staged = (size_t)((char*)ix->h_qcoef - (char*)ix->h_qwords) + (size_t)Q * (PQ + 1) * sizeof(float);
+    HIP_TRY(hipMemcpyAsync(ix->d_qwords, ix->h_qwords, staged, hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
 
@@ -676,8 +688,6 @@ void rbe_free(rbe_index* ix)
     (void)hipFree(ix->d_count);
     (void)hipFree(ix->d_tau);
     (void)hipFree(ix->d_kmax);
-    (void)hipFree(ix->d_status);
-    (void)hipFree(ix->d_seen);
     (void)hipFree(ix->d_qwords);
     (void)hipFree(ix->d_lut);
     (void)hipFree(ix->d_aops);
@@ -685,11 +695,7 @@ void rbe_free(rbe_index* ix)
     (void)hipHostFree(ix->h_aops);
     (void)hipHostFree(ix->h_unscale);
     (void)hipHostFree(ix->h_lut);
-    (void)hipFree(ix->d_qcoef);
     (void)hipHostFree(ix->h_qwords);
-    (void)hipHostFree(ix->h_qcoef);
-    (void)hipHostFree(ix->h_status);
-    (void)hipHostFree(ix->h_seen);
     if (ix->ev_ok)
         for (uint32_t i = 0; i < kMaxEvents; ++i) (void)hipEventDestroy(ix->ev[i]);
     delete ix;
@@ -869,6 +875,10 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         plan = make_group_plan(n_units, ix->layout.ratio, c.cap, per_unit);
     }
 
+    // this call's scores follow its ids directly, so that the results are one contiguous range
+    ix->d_scores = reinterpret_cast<float*>(ix->d_ids + (size_t)c.Q * k);
+    ix->h_scores = reinterpret_cast<float*>(ix->h_ids + (size_t)c.Q * k);
+
     ix->stats = rbe_search_stats{};
     const bool prof = ix->profiling != 0;
     bool fallback = plan.empty();
@@ -898,10 +908,9 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
             ix->stats.fallback = 1;
             ix->stats.items_scanned[0] = (uint64_t)ix->layout.n_tiles * kTileItems;
         }
-        HIP_TRY(hipMemcpyAsync(ix->h_status, ix->d_status, sizeof(uint32_t), hipMemcpyDeviceToHost, c.st));
-        HIP_TRY(hipMemcpyAsync(ix->h_seen, ix->d_seen, RBE_MAX_LEVELS * RBE_MAX_QUERIES * sizeof(uint32_t), hipMemcpyDeviceToHost, c.st));
-        HIP_TRY(hipMemcpyAsync(ix->h_ids, ix->d_ids, (size_t)c.Q * k * sizeof(int64_t), hipMemcpyDeviceToHost, c.st));
-        HIP_TRY(hipMemcpyAsync(ix->h_scores, ix->d_scores, (size_t)c.Q * k * sizeof(float), hipMemcpyDeviceToHost, c.st));
+        HIP_TRY(hipMemcpyAsync(ix->h_result, ix->d_result,
+                               kResultHeaderBytes + (size_t)c.Q * k * (sizeof(int64_t) + sizeof(float)),
+                               hipMemcpyDeviceToHost, c.st));
         if (prof && !fallback) HIP_TRY(hipEventRecord(ix->ev[kMaxEvents - 1], c.st));
         HIP_TRY(hipStreamSynchronize(c.st));
         if (!(*ix->h_status & rbe::kStatusOverflow)) break;
