@@ -339,6 +339,7 @@ def main():
             v_ach = lane_ops_per_pair(W, P, P) * B * rv["stats"]["items_scanned"][-1] / (v_scan * 1e-3) / 1e12
             out["batch_popcount_kernel"] = {
                 "queries_per_step": B, "steps": steps_v, "ms_per_step": v_ms,
+                "last_search_level_ms": {"scan": rv["stats"]["scan_ms"], "select": rv["stats"]["select_ms"]},
                 "value": N * B / (v_ms * 1e-3), "unit": "candidates/s", "dtype": "u64 xor/popcount + f32",
                 "roofline": {"kernel": "scan_exact (finest level)", "bound": "alu", "achieved": v_ach,
                              "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-ops/s", "frac": v_ach / VALU_PEAK_TLANEOPS,

@@ -364,9 +364,9 @@ def rbe_debug_exact_plan(n_items: int, sample_ratio: int, cand_capacity: int, k:
     return [(int(first[i]), int(end[i])) for i in range(int(n[0]))]
 
 
-def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic: bool):
+def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic: bool, hi_only: bool = False):
     """Query operands of the matrix-core batch scan (host only): fp16 bit patterns
-    [tile][term][plane copy][part][lane][8], unscale [Q], start [Q]."""
+    [tile][term][plane copy][part][lane][8], unscale [Q], start [Q]; with hi_only also the filter margin."""
     q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
     Q, Pq = q_planes.shape[0], q_planes.shape[1]
     if q_scales is not None:
@@ -375,12 +375,16 @@ def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic
     halves = np.zeros(cap, dtype=np.uint16)
     unscale = np.zeros(Q, dtype=np.float32)
     start = np.zeros(Q, dtype=np.float32)
-    shape = np.zeros(4, dtype=np.uint32)
+    shape = np.zeros(5, dtype=np.uint32)
+    form = 1 if dyadic else (2 if hi_only else 0)
     _check(load_library().rbe_debug_batch_operands(
         q_planes.ctypes.data, None if q_scales is None else q_scales.ctypes.data, Q, Pq, dim, n_planes,
-        1 if dyadic else 0, halves.ctypes.data, cap, unscale.ctypes.data, start.ctypes.data, shape.ctypes.data))
-    tiles, terms, copies, parts = (int(x) for x in shape)
-    return halves[:tiles * terms * copies * parts * 64 * 8].reshape(tiles, terms, copies, parts, 64, 8), unscale, start
+        form, halves.ctypes.data, cap, unscale.ctypes.data, start.ctypes.data, shape.ctypes.data))
+    tiles, terms, copies, parts = (int(x) for x in shape[:4])
+    out = halves[:tiles * terms * copies * parts * 64 * 8].reshape(tiles, terms, copies, parts, 64, 8)
+    if hi_only:
+        return out, unscale, start, float(shape[4:5].view(np.float32)[0])
+    return out, unscale, start
 
 
 def rbe_debug_set_batch_path(ix: Index, path: int):

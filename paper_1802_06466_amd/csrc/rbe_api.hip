@@ -85,6 +85,7 @@ struct rbe_index {
     float* d_unscale = nullptr;     // [Q]
     float* h_unscale = nullptr;
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
+    float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
     float* d_lut = nullptr;         // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
     float* h_lut = nullptr;
     uint32_t* d_qwords = nullptr;   // [Q][PQ][2W]
@@ -279,6 +280,10 @@ uint32_t batch_tiles_per_launch(const rbe_index* ix)
     return 2u * per_tile <= 64u ? 2u : 1u;
 }
 
+// General scales, binary queries: the contraction carries the hi half only and filters; survivors are rescored
+// exactly (see scan_batch_mfma).  Full-precision queries have no exact bitwise form: they carry hi + lo.
+bool batch_rescore(const rbe_index* ix, bool float_query) { return ix->mode == rbe::kModeScaled && !float_query; }
+
 bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query)
 {
     if (mode != RBE_SELECT_EXACT || !rbe::batch_mfma_supported(ix->W)) return false;
@@ -303,15 +308,19 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
 // rotates the part's word left by 4g and takes bits 10 + t (h = 0) and 26 + t (h = 1), i.e. original bit
 // (10 + 16h + t - 4g) mod 32.  Dyadic modes: one exact half, one copy per item plane j scaled by 2^-j, and
 // the start value covers all planes.
+// hi_only (general scales): only the hi half is stored; the accumulators then start at minus the sum of what the
+// halves actually hold, so that the contraction equals sum_d vhi_d rho_d exactly, and *margin receives a bound,
+// valid for every query of the batch, on |sum_d v_d rho_d - sum_d vhi_d rho_d| plus the fp32 rounding of either
+// side: max_q ( sum_d |v_d - vhi_d| + 2^-20 sum_d |v_d| ).
 //   halves  [tile][term][plane copy][part][lane][8]   (tile = query / 16, lane = 16 g + query % 16)
 //   unscale [Q] = 2^-k,   bias [Q] = start value of the accumulators
 struct BatchOperandShape { uint32_t tiles, terms, copies, parts; size_t n_halves; };
 
-BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint32_t Q)
+BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint32_t Q, bool hi_only)
 {
     BatchOperandShape sh;
     sh.tiles = batch_tiles(Q);
-    sh.terms = dyadic ? 1u : 2u;
+    sh.terms = (dyadic || hi_only) ? 1u : 2u;
     sh.copies = dyadic ? P : 1u;
     sh.parts = 2u * W;
     sh.n_halves = (size_t)sh.tiles * sh.terms * sh.copies * sh.parts * 64 * 8;
@@ -322,9 +331,10 @@ BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint3
 // are not read; general scales only.
 void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q_planes, const float* q_scales,
                           uint32_t Q, uint32_t PQ, uint16_t* halves, float* unscale, float* bias,
-                          const float* q_float = nullptr)
+                          const float* q_float = nullptr, bool hi_only = false, float* margin = nullptr)
 {
-    const BatchOperandShape sh = batch_operand_shape(W, P, dyadic, Q);
+    const BatchOperandShape sh = batch_operand_shape(W, P, dyadic, Q, hi_only);
+    double worst = 0.0;
     const uint32_t dim = 64 * W, KP = sh.parts, TERMS = sh.terms, PA = sh.copies;
     std::memset(halves, 0, sh.n_halves * sizeof(uint16_t));
     std::vector<double> qhat(dim);
@@ -348,7 +358,7 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
         const int k = biggest > 0.0 ? -(std::ilogb(biggest) + 1) : 0;
         unscale[q] = std::ldexp(1.0f, -k);
         const uint32_t qt = q / 16, row = q % 16;
-        double sum = 0.0;
+        double sum = 0.0, lost = 0.0, mass = 0.0;
         for (uint32_t part = 0; part < KP; ++part)
             for (uint32_t grp = 0; grp < 4; ++grp)
                 for (uint32_t e = 0; e < 8; ++e) {
@@ -356,7 +366,15 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
                     const uint32_t bit = (10u + 16u * h + t + 32u - 4u * grp) & 31u;
                     const double v = std::ldexp(qhat[part * 32 + bit], k);
                     const uint32_t lane = grp * 16 + row;
-                    sum += v;
+                    if (hi_only && !dyadic) {
+                        // what the hi half really holds, back in the units of v
+                        const double held = std::ldexp((double)(float)(_Float16)(float)std::ldexp(v, 1 - kValExp[t]), kValExp[t] - 1);
+                        sum += held;
+                        lost += std::fabs(v - held);
+                        mass += std::fabs(v);
+                    } else {
+                        sum += v;
+                    }
                     for (uint32_t pa = 0; pa < PA; ++pa) {
                         const double aval = std::ldexp(v, 1 - kValExp[t] - (int)pa);
                         const _Float16 hi = (_Float16)(float)aval;
@@ -372,12 +390,15 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
                 }
         if (dyadic) sum *= 2.0 - std::ldexp(1.0, 1 - (int)P);   // every plane's term starts from its own -2^-j sum
         bias[q] = (float)-sum;
+        worst = std::max(worst, lost + std::ldexp(mass, -20) + std::fabs(sum - (double)(float)sum));
     }
+    if (margin) *margin = (float)(worst * (1.0 + std::ldexp(1.0, -10)));
 }
 
 int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
                         hipStream_t st, const float* q_float = nullptr)
 {
+    const bool hi_only = batch_rescore(ix, q_float != nullptr);
     const size_t max_halves = (size_t)(RBE_MAX_QUERIES / 16) * 4 * 4 * 64 * 8;   // per tile: (terms x copies) x parts <= 16
     if (!ix->d_aops) {
         HIP_TRY(hipMalloc(&ix->d_aops, max_halves * sizeof(uint16_t)));
@@ -386,9 +407,9 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
         HIP_TRY(hipHostMalloc(&ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
     }
     const bool dyadic = ix->mode != rbe::kModeScaled;
-    const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q);
+    const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q, hi_only);
     build_batch_operands(ix->W, ix->P, dyadic, q_planes, q_scales, Q, PQ, reinterpret_cast<uint16_t*>(ix->h_aops),
-                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float);
+                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float, hi_only, &ix->batch_margin);
     HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, sh.n_halves * sizeof(uint16_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
@@ -530,20 +551,24 @@ int rbe_debug_exact_plan(uint64_t n_items, uint32_t sample_ratio, uint32_t cand_
 }
 
 int rbe_debug_batch_operands(const uint64_t* q_planes, const float* q_scales, uint32_t n_queries, uint32_t q_n_planes,
-                             uint32_t dim, uint32_t n_planes, uint32_t dyadic, uint16_t* halves_out, size_t halves_capacity,
+                             uint32_t dim, uint32_t n_planes, uint32_t dyadic /* form */, uint16_t* halves_out, size_t halves_capacity,
                              float* unscale_out, float* start_out, uint32_t* shape_out)
 {
     ARG_CHECK(q_planes && halves_out && unscale_out && start_out && shape_out, "NULL argument");
-    ARG_CHECK(dyadic || q_scales, "q_scales is NULL");
+    ARG_CHECK(dyadic == 1 || q_scales, "q_scales is NULL");
     ARG_CHECK(dim == 64 || dim == 128, "dim must be 64 or 128");
     ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES && q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES,
               "plane counts out of range");
     ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries out of range");
-    const BatchOperandShape sh = batch_operand_shape(dim / 64, n_planes, dyadic != 0, n_queries);
+    const bool dy = dyadic == 1, hi_only = dyadic == 2;
+    ARG_CHECK(dyadic <= 2, "form must be 0, 1 or 2");
+    const BatchOperandShape sh = batch_operand_shape(dim / 64, n_planes, dy, n_queries, hi_only);
     ARG_CHECK(halves_capacity >= sh.n_halves, "halves_out too small: %zu needed", sh.n_halves);
-    build_batch_operands(dim / 64, n_planes, dyadic != 0, q_planes, q_scales, n_queries, q_n_planes, halves_out,
-                         unscale_out, start_out);
+    float margin = 0.0f;
+    build_batch_operands(dim / 64, n_planes, dy, q_planes, q_scales, n_queries, q_n_planes, halves_out,
+                         unscale_out, start_out, nullptr, hi_only, &margin);
     shape_out[0] = sh.tiles; shape_out[1] = sh.terms; shape_out[2] = sh.copies; shape_out[3] = sh.parts;
+    std::memcpy(&shape_out[4], &margin, sizeof(float));
     return RBE_OK;
 }
 
@@ -762,9 +787,14 @@ struct SearchCtx {
     uint32_t qlen;      // near-lossless: entries per group queue (1 or 2); mode holds RBE_SELECT_NEARLOSSLESS for both
     bool float_query;   // hybrid scoring: fp32 queries through byte tables
     bool batch_mfma;    // exact mode, several queries: matrix-core scan
+    bool float_batch;   // ... of full-precision queries (no binary form to rescore with)
 };
 
-static int launch_scan_round(const SearchCtx& c, const Round& r)
+// dense: a coarse level of the plan, where a large share of the items passes the (still loose) threshold.
+// The matrix-core scan spends such a level in its survivor path; unless it was asked for explicitly, batches of
+// binary queries take the XOR/popcount scan there and the matrix cores for the last, large level only (both
+// produce the same scores bit for bit, so the levels of one search may mix them).
+static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
 {
     rbe_index* ix = c.ix;
     if (r.end <= r.begin) return RBE_OK;
@@ -783,11 +813,13 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
         }
-    } else if (c.batch_mfma) {
+    } else if (c.batch_mfma && !(dense && !c.float_batch && ix->batch_path == 0)) {
         BatchArgs ba;
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
         ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.tau = ix->d_tau; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
+        ba.rescore = batch_rescore(ix, c.float_batch) ? 1u : 0u;
+        ba.PQ = c.PQ; ba.qwords = ix->d_qwords; ba.qcoef = ix->d_qcoef; ba.margin = ix->batch_margin;
         e = hipSuccess;
         const uint32_t tiles = batch_tiles(c.Q), per_launch = batch_tiles_per_launch(ix);
         for (uint32_t t0 = 0; t0 < tiles && e == hipSuccess; t0 += per_launch) {   // one pass over the range per launch
@@ -817,10 +849,11 @@ static int launch_scan_round(const SearchCtx& c, const Round& r)
     return RBE_OK;
 }
 
-static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_t level_slot, bool record)
+static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_t level_slot, bool record,
+                     bool dense = false)
 {
     rbe_index* ix = c.ix;
-    int rc = launch_scan_round(c, r);
+    int rc = launch_scan_round(c, r, dense);
     if (rc) return rc;
     if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 1], c.st));
 
@@ -889,7 +922,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         if (!fallback) {
             if (prof) HIP_TRY(hipEventRecord(ix->ev[0], c.st));
             for (size_t l = 0; l < plan.size(); ++l) {
-                rc = run_round(c, plan[l], l + 1 == plan.size(), (uint32_t)l, prof);
+                rc = run_round(c, plan[l], l + 1 == plan.size(), (uint32_t)l, prof, l + 1 != plan.size());
                 if (rc) return rc;
                 ix->stats.items_scanned[l] = (uint64_t)(plan[l].end - plan[l].begin) *
                                              (mode == RBE_SELECT_EXACT ? (uint64_t)kTileItems : (uint64_t)c.I * kRow);
@@ -952,6 +985,7 @@ static int search_prologue(rbe_index* ix, SearchCtx& c, uint32_t n_queries, uint
     c.I = group_size_I ? group_size_I : 256;
     c.float_query = false;
     c.batch_mfma = false;
+    c.float_batch = false;
     const uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->layout.ratio * k);
     c.cap = std::max<uint32_t>(cap, k + 2 * kTileItems);
     return ensure_workspace(ix, c.Q, k, c.cap);
@@ -993,6 +1027,7 @@ int rbe_search_float(rbe_index* ix, const float* q, uint32_t n_queries, uint32_t
     c.batch_mfma = use_batch_mfma(ix, c.Q, mode, true);
     if (c.batch_mfma) {
         // several queries: the same dense contraction as for binary queries, with the query itself as operand
+        c.float_batch = true;
         rc = stage_batch_queries(ix, nullptr, nullptr, c.Q, 0, c.st, q);
     } else {
         c.float_query = true;

@@ -82,7 +82,11 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
     }
 }
 
-template <int W, int P, int MODE, int NQT>
+// RS (general scales, binary queries): the contraction runs with the hi half of the query only and is used as a
+// filter -- its distance from the true score is at most a.margin * sum_j a_j[item] (the host adds up the part of
+// every query component that the half does not hold) -- and what passes the filter is scored again exactly as the
+// XOR/popcount scan scores it.  Half the MFMAs, and results that do not depend on how many queries share a call.
+template <int W, int P, int MODE, int NQT, bool RS>
 __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
 {
     constexpr int S = scale_arrays(MODE, P);
@@ -91,7 +95,8 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     // Dyadic modes: the plane weight 2^-j is folded into a per-plane copy of the query operand, all planes add
     // into one accumulator, and the query (a short dyadic fraction) is exact in one half.
     constexpr bool kDy = MODE != kModeScaled;
-    constexpr int TERMS = kDy ? 1 : 2;
+    constexpr bool kRescore = RS && !kDy;
+    constexpr int TERMS = (kDy || kRescore) ? 1 : 2;
     constexpr int PA = kDy ? P : 1;
     constexpr int PD = kDy ? 1 : P;
     __shared__ uint64_t s_pl[kWavesPerBlock][P][kRow * W];
@@ -202,9 +207,16 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                     }
                 }
                 float aj[P];
+                float adj = 0.0f;      // filter slack of this item (kRescore)
                 if (MODE == kModeScaled) {
 #pragma unroll
                     for (int j = 0; j < P; ++j) aj[j] = s_sc[wave][j][item];
+                    if (kRescore) {
+                        float asum = aj[0];
+#pragma unroll
+                        for (int j = 1; j < P; ++j) asum += aj[j];
+                        adj = a.margin * asum;
+                    }
                 } else if (MODE == kModeDyadicNorm) {
                     aj[0] = s_sc[wave][0][item];
                 }
@@ -214,7 +226,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                     for (int r = 0; r < 4; ++r) {
                         float v;
                         if (MODE == kModeScaled) {
-                            v = 0.0f;
+                            v = adj;
 #pragma unroll
                             for (int j = 0; j < P; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
                         } else if (MODE == kModeDyadicNorm) {
@@ -238,7 +250,28 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                             const uint32_t ql = (uint32_t)(qt * 16 + 4 * g + r);
                             uint64_t key = 0;
                             if (ok) {
-                                key = make_key(s[u][qt][r] * a.q_unscale[a.q_begin + ql], (uint32_t)id);
+                                float score;
+                                if (kRescore) {
+                                    // exact score, in the arithmetic of the XOR/popcount scan (i inner, j outer)
+                                    const uint32_t it = (uint32_t)(16 * (cb * U + u) + col);
+                                    const uint32_t* qw = a.qwords + (size_t)(a.q_begin + ql) * a.PQ * 2 * W;
+                                    const float* qc = a.qcoef + (size_t)(a.q_begin + ql) * (a.PQ + 1);
+                                    score = 0.0f;
+                                    for (int j = 0; j < P; ++j) {
+                                        const uint32_t* kw = reinterpret_cast<const uint32_t*>(&s_pl[wave][j][it * W]);
+                                        float t = qc[a.PQ];
+                                        for (uint32_t i = 0; i < a.PQ; ++i) {
+                                            uint32_t pc = 0;
+                                            for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(kw[h] ^ qw[i * 2 * W + h]);
+                                            t = __fmaf_rn(qc[i], (float)pc, t);
+                                        }
+                                        score = __fmaf_rn(s_sc[wave][j][it], t, score);
+                                    }
+                                    score += 0.0f;
+                                } else {
+                                    score = s[u][qt][r] * a.q_unscale[a.q_begin + ql];
+                                }
+                                key = make_key(score, (uint32_t)id);
                                 ok = key >= a.tau[a.q_begin + ql];
                             }
                             mstage_append(ok, key, ql, ms, a.out, lane);
@@ -260,22 +293,29 @@ namespace {
 using BatchFn = void (*)(const BatchArgs);
 
 template <int W, int P, int MODE>
-BatchFn batch_fn_q(uint32_t nqt)
+BatchFn batch_fn_q(uint32_t nqt, bool rescore)
 {
+    if (MODE == kModeScaled && rescore) {
+        switch (nqt) {
+            case 1: return scan_batch_mfma<W, P, MODE, 1, true>;
+            case 2: return scan_batch_mfma<W, P, MODE, 2, true>;
+            default: return nullptr;
+        }
+    }
     switch (nqt) {
-        case 1: return scan_batch_mfma<W, P, MODE, 1>;
-        case 2: return scan_batch_mfma<W, P, MODE, 2>;
+        case 1: return scan_batch_mfma<W, P, MODE, 1, false>;
+        case 2: return scan_batch_mfma<W, P, MODE, 2, false>;
         default: return nullptr;
     }
 }
 
 template <int W, int P>
-BatchFn batch_fn_m(int mode, uint32_t nqt)
+BatchFn batch_fn_m(int mode, uint32_t nqt, bool rescore)
 {
     switch (mode) {
-        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt);
-        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt);
-        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt);
+        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore);
+        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, false);
+        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, false);
         default: return nullptr;
     }
 }
@@ -287,10 +327,10 @@ hipError_t launch_scan_batch_w<RBE_W>(const KernelSel& k, const BatchArgs& a, ui
 {
     BatchFn fn = nullptr;
     switch (k.P) {
-        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles); break;
-        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles); break;
-        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles); break;
-        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles); break;
+        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore != 0); break;
+        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore != 0); break;
+        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore != 0); break;
+        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore != 0); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;

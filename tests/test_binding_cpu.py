@@ -262,3 +262,37 @@ def test_scan_kernels_have_no_lane_peeling_loops():
     entries.  Kernels whose per-lane loops are intended are listed in the checker."""
     from paper_1802_06466_amd import _check_isa
     assert _check_isa.main() == 0
+
+
+def test_matrix_core_filter_operands_stay_within_their_margin(lib):
+    """Hi-half-only operands (binary queries, general scales): the emulated contraction may differ from
+    qhat . rho by at most the margin the host reports (per unit of item scale), and the margin is a small
+    fraction of the query's mass -- otherwise the filter would pass far more than the survivors."""
+    rng = np.random.default_rng(321)
+    dim, P, Pq, Q = 128, 3, 4, 19
+    W = dim // 64
+    qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
+    qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
+    halves, unscale, start, margin = rbe.rbe_debug_batch_operands(qp, qs, dim, P, False, hi_only=True)
+    assert halves.shape[:4] == ((Q + 15) // 16, 1, 1, 2 * W) and margin > 0
+    A = _halves_to_float(halves)
+    val = np.array([2.0 ** -14, 2.0 ** -13, 2.0 ** -11, 2.0 ** -7])
+    worst = 0.0
+    for q in range(Q):
+        qbits = ((qp[q][:, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
+        qhat = (qs[q].astype(np.float64)[:, None, None] * (2 * qbits - 1)).sum(axis=0).reshape(dim)
+        v = qhat / float(unscale[q])                     # the scaled query the operands describe
+        assert 0.5 <= np.abs(v).max() < 1.0
+        assert margin <= 2.0 ** -9 * np.abs(v).sum() + 2.0 ** -9
+        for _ in range(40):
+            bits = rng.integers(0, 2, size=dim)
+            got = float(start[q])
+            for part in range(2 * W):
+                b32 = bits[32 * part: 32 * part + 32]
+                for g in range(4):
+                    for e in range(8):
+                        t, h = e >> 1, e & 1
+                        got += A[q // 16, 0, 0, part, 16 * g + q % 16, e] * (b32[(10 + 16 * h + t - 4 * g) % 32] * val[t])
+            worst = max(worst, abs(got - float(v @ (2 * bits - 1))))
+    assert worst <= margin, (worst, margin)
+    assert worst > 0                                     # the lo halves really are missing

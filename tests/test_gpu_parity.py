@@ -640,9 +640,17 @@ def test_matrix_core_batch_path_matches_oracle_and_popcount_path(d, P, Pq, Q, k)
     rbe.rbe_debug_set_batch_path(ix, 1)
     ids_v, sc_v = rbe.rbe_search(ix, qp, qs, k)
     check_batch(planes, scales, qp, qs, k, ids_v, sc_v)
-    np.testing.assert_allclose(sc_m, sc_v, rtol=1e-5)
-    agree = np.mean([len(set(ids_m[q].tolist()) & set(ids_v[q].tolist())) / k for q in range(Q)])
-    assert agree > 0.995
+    # the contraction only filters; what passes is scored in the arithmetic of the XOR/popcount scan,
+    # so a query's result does not depend on the kernel or on how many queries share the call
+    np.testing.assert_array_equal(sc_m, sc_v)
+    np.testing.assert_array_equal(ids_m, ids_v)
+    rbe.rbe_debug_set_batch_path(ix, 0)          # automatic: popcount scan on the coarse levels, matrix cores last
+    ids_a, sc_a = rbe.rbe_search(ix, qp, qs, k)
+    np.testing.assert_array_equal(sc_a, sc_v)
+    np.testing.assert_array_equal(ids_a, ids_v)
+    one_i, one_s = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    np.testing.assert_array_equal(one_s[0], sc_v[0])
+    np.testing.assert_array_equal(one_i[0], ids_v[0])
     rbe.rbe_free(ix)
 
 
