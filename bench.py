@@ -301,10 +301,10 @@ def main():
         b_items = rb["stats"]["items_scanned"][-1]
         matrix_cores = B >= 8 and W <= 2     # the library's own choice of kernel for a batch
         if matrix_cores:
-            # dense contraction [B x d] . [d x items] per corpus plane; the fp16 hi + lo split of the
-            # query (general scales) doubles what the kernel issues, padding to 16 queries adds more
+            # dense contraction [B x d] . [d x items] per corpus plane (one fp16 half per query component:
+            # the contraction filters, survivors are rescored bitwise); padding to 16 queries adds to what is issued
             flops = 2.0 * B * b_items * d * P
-            terms = 2                        # the main corpus of this bench has general per-item scales
+            terms = 1
             issued = 2.0 * 16 * -(-B // 16) * b_items * d * P * terms
             ach = flops / (b_scan * 1e-3) / 1e12
             roof = {"kernel": "scan_batch_mfma (finest level)", "bound": "mfma", "achieved": ach,
@@ -322,7 +322,7 @@ def main():
         out["batch"] = {
             "queries_per_step": B, "steps": args.batch_steps, "ms_per_step": b_ms,
             "value": N * B * args.batch_steps / rb["wall_s"], "unit": "candidates/s",
-            "dtype": "f16 x f16 -> f32 (query as hi + lo halves)" if matrix_cores else "u64 xor/popcount + f32",
+            "dtype": "f16 x f16 -> f32 filter, u64 xor/popcount + f32 scores" if matrix_cores else "u64 xor/popcount + f32",
             "last_search_level_ms": {"scan": rb["stats"]["scan_ms"], "select": rb["stats"]["select_ms"]},
             "gpu_ms_per_search": float(rb["total_gpu_ms"].mean()) if rb["total_gpu_ms"].size else None,
             "roofline": roof,

@@ -21,14 +21,14 @@
  * The popcounts are exact integers; the combination is evaluated in fp32 in
  * the order written (i inner, j outer), each inner sum starting from
  * dim * sum_i c_i and accumulating -2 c_i * popcount with fused multiply-adds.
- * With 8 or more queries per call (exact mode, dim <= 128) the same score is
- * evaluated on the matrix cores instead, as sum_j a_j[z] * (qhat . b_z^j) with
- * qhat = sum_i c_i b_q^i reconstructed on the host in double, scaled by a power
- * of two and carried as two half-precision terms (about 22 bits; one term, exact,
- * for RBE_DYADIC), products exact, fp32 accumulation; it agrees with the formula
- * above to ~1e-6 relative (bit for bit with RBE_DYADIC).  Such a call reads the
- * corpus once per 32 queries (once per 16 for RBE_DYADIC with dim 128 and 3 or 4
- * planes).
+ * With 8 or more queries per call (exact mode, dim <= 128) the pairs are first
+ * filtered on the matrix cores: sum_j a_j[z] * (qhat . b_z^j), qhat = sum_i c_i b_q^i
+ * reconstructed on the host in double and carried as half-precision numbers, with
+ * a slack that covers the rounding; what can reach the threshold is then scored by
+ * the formula above, so the results do not depend on the number of queries per
+ * call.  (RBE_DYADIC: the half-precision form is exact and is the score.)  Such a
+ * call reads the corpus once per 32 queries (once per 16 for RBE_DYADIC with dim
+ * 128 and 3 or 4 planes).
  *
  * Selection (Sec. 6).  Results are ordered by (score descending, id
  * ascending).  RBE_SELECT_EXACT returns exactly the k best under that order.
