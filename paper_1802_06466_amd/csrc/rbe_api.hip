@@ -834,6 +834,9 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = c.Q;
         sa.tau = ix->d_tau; sa.out = out;
         sa.p_begin = r.begin; sa.p_end = r.end;
+        // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
+        // it for sub-queues of 32..64 entries (fewer, larger flushes)
+        sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);
         e = launch_scan_exact(ix->W, sel, sa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
     } else {
         GroupArgs ga;

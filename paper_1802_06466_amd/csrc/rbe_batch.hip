@@ -42,6 +42,7 @@
 namespace rbe {
 
 constexpr int kBatchStage = 256;   // staged survivors per wave (all sub-queues together)
+constexpr int kMaxPlanes = 4;      // query planes (RBE_MAX_PLANES of the C interface)
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -103,6 +104,12 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     __shared__ float s_sc[kWavesPerBlock][S > 0 ? S : 1][kRow];
     __shared__ uint64_t s_keys_all[kWavesPerBlock][kBatchStage];
     __shared__ uint32_t s_cnt_all[kWavesPerBlock][16 * NQT + 1];
+    // what the survivor path needs of this launch's queries, close at hand: at one wave per SIMD (d = 128 with
+    // 3 or 4 planes) a global read there would stall the whole SIMD
+    __shared__ uint64_t s_tau[16 * NQT];
+    __shared__ float s_unscale[16 * NQT];
+    __shared__ uint32_t s_qw[kRescore ? 16 * NQT : 1][kMaxPlanes][2 * W];
+    __shared__ float s_qc[kRescore ? 16 * NQT : 1][kMaxPlanes + 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -111,6 +118,19 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     const MultiStage ms{s_keys_all[wave], s_cnt_all[wave], (uint32_t)kBatchStage / (16u * NQT), a.q_begin, 16u * NQT};
     if (lane < 16 * NQT) s_cnt_all[wave][lane] = 0;
     if (lane == 0) s_cnt_all[wave][16 * NQT] = 0;
+
+    for (uint32_t ql = threadIdx.x; ql < 16u * NQT; ql += kBlock) {
+        const uint32_t q = a.q_begin + ql;
+        const bool live = q < a.n_queries;
+        s_tau[ql] = live ? a.tau[q] : ~0ull;
+        s_unscale[ql] = live ? a.q_unscale[q] : 1.0f;
+        if (kRescore) {
+            for (uint32_t i = 0; i <= a.PQ; ++i) s_qc[ql][i] = live ? a.qcoef[(size_t)q * (a.PQ + 1) + i] : 0.0f;
+            for (uint32_t i = 0; i < a.PQ; ++i)
+                for (int h = 0; h < 2 * W; ++h) s_qw[ql][i][h] = live ? a.qwords[((size_t)q * a.PQ + i) * 2 * W + h] : 0u;
+        }
+    }
+    __syncthreads();
 
     const uint32_t G = gridDim.x;
     const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
@@ -254,25 +274,24 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                                 if (kRescore) {
                                     // exact score, in the arithmetic of the XOR/popcount scan (i inner, j outer)
                                     const uint32_t it = (uint32_t)(16 * (cb * U + u) + col);
-                                    const uint32_t* qw = a.qwords + (size_t)(a.q_begin + ql) * a.PQ * 2 * W;
-                                    const float* qc = a.qcoef + (size_t)(a.q_begin + ql) * (a.PQ + 1);
+                                    const float* qc = s_qc[ql];
                                     score = 0.0f;
                                     for (int j = 0; j < P; ++j) {
                                         const uint32_t* kw = reinterpret_cast<const uint32_t*>(&s_pl[wave][j][it * W]);
                                         float t = qc[a.PQ];
                                         for (uint32_t i = 0; i < a.PQ; ++i) {
                                             uint32_t pc = 0;
-                                            for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(kw[h] ^ qw[i * 2 * W + h]);
+                                            for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(kw[h] ^ s_qw[ql][i][h]);
                                             t = __fmaf_rn(qc[i], (float)pc, t);
                                         }
                                         score = __fmaf_rn(s_sc[wave][j][it], t, score);
                                     }
                                     score += 0.0f;
                                 } else {
-                                    score = s[u][qt][r] * a.q_unscale[a.q_begin + ql];
+                                    score = s[u][qt][r] * s_unscale[ql];
                                 }
                                 key = make_key(score, (uint32_t)id);
-                                ok = key >= a.tau[a.q_begin + ql];
+                                ok = key >= s_tau[ql];
                             }
                             mstage_append(ok, key, ql, ms, a.out, lane);
                         }

@@ -340,6 +340,7 @@ struct ScanArgs {
     const uint64_t* tau;      // [Q] threshold keys
     CandList out;
     uint32_t p_begin, p_end;  // physical tile range this launch covers
+    uint32_t stage_entries;   // several queries: LDS queue entries per wave (512..4096), split into sub-queues
 };
 
 // Hybrid scoring (fp32 query against RBE items, the paper's model m_5, Sec. 8.1): one query per

@@ -58,16 +58,21 @@ __device__ __forceinline__ uint32_t score_and_stage(RowRegs<W, P, scale_arrays(M
 template <int W, int P, int PQ, bool SINGLE, int MODE>
 __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
 {
-    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    // one query: a fixed queue per wave.  Several: a.stage_entries per wave from the launch's dynamic LDS --
+    // a batch forwards Q times as many survivors, and with 64 sub-queues in 512 entries a flush (one returning
+    // global atomic, a microsecond of waiting) came every 8 survivors
+    __shared__ uint64_t s_keys_fixed[SINGLE ? kWavesPerBlock : 1][SINGLE ? kStage : 1];
+    extern __shared__ __align__(16) unsigned char s_dynamic[];
     __shared__ uint32_t s_cnt_all[SINGLE ? 1 : kWavesPerBlock][SINGLE ? 1 : 65];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    uint64_t* s_keys = s_keys_all[wave];
+    uint64_t* s_keys = SINGLE ? s_keys_fixed[SINGLE ? wave : 0] : reinterpret_cast<uint64_t*>(s_dynamic) + (size_t)wave * a.stage_entries;
     MultiStage ms{};
     if (!SINGLE) {
         const uint32_t n_sub = sub_queues_for(a.n_queries);
-        ms = MultiStage{s_keys, s_cnt_all[wave], (uint32_t)kStage / n_sub, 0u, n_sub};
+        const uint32_t per_sub = a.stage_entries / n_sub;
+        ms = MultiStage{s_keys, s_cnt_all[wave], per_sub > 64u ? 64u : per_sub, 0u, n_sub};   // a flush moves <= 64 entries
         s_cnt_all[wave][lane] = 0;
         if (lane == 0) s_cnt_all[wave][64] = 0;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -390,16 +395,22 @@ hipError_t launch_scan_exact_w<RBE_W>(const KernelSel& k, const ScanArgs& a, uin
     const ScanFn fn = scan_fn(k);
     if (!fn) return hipErrorInvalidValue;
     if (a.p_end <= a.p_begin) return hipSuccess;
+    const size_t dyn_lds = k.single ? 0 : (size_t)kWavesPerBlock * a.stage_entries * sizeof(uint64_t);
+    if (!k.single && (a.stage_entries < 512 || a.stage_entries > 4096)) return hipErrorInvalidValue;
+    if (dyn_lds > 32768) {   // beyond the default dynamic-LDS limit the kernel must be told
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds);
+        if (e != hipSuccess) return e;
+    }
     if (per_cu == 0) {
         int nb = 0;
-        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, 0);
+        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, dyn_lds);
         if (e != hipSuccess) return e;
         per_cu = (uint32_t)(nb > 0 ? nb : 1);
     }
     const uint32_t units = a.p_end - a.p_begin;
     const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;
     if (grid_out) *grid_out = grid;
-    fn<<<dim3(grid), dim3(kBlock), 0, st>>>(a);
+    fn<<<dim3(grid), dim3(kBlock), dyn_lds, st>>>(a);
     return hipGetLastError();
 }
 
