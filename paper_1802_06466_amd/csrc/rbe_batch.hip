@@ -47,23 +47,32 @@ constexpr int kMaxPlanes = 4;      // query planes (RBE_MAX_PLANES of the C inte
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// Raw (still packed) row as it comes from memory: 16-byte plane loads, matching scale loads.
+// A wave works through its row of 256 items in SEG segments.  One segment (d = 64) keeps the loads widest; at
+// d = 128 a whole row in flight costs 160 registers and 80 KB of LDS per workgroup with 4 planes -- one wave per
+// SIMD -- so the row is taken in quarters of 64 items (one 16-byte plane load per lane and plane).
+template <int W>
+constexpr int row_segments() { return W == 2 ? 4 : 1; }
+
+// Raw (still packed) segment as it comes from memory: 16-byte plane loads, matching scale loads.
 template <int W, int P, int S>
 struct RawRow {
-    u32x4 pl[P][2 * W];                    // W=1: items (2l,2l+1) and (128+2l,129+2l); W=2: items m*64+l, m<4
-    float sc[S > 0 ? S : 1][kItemsPerLane];
+    static constexpr int SEG = row_segments<W>();
+    u32x4 pl[P][2 * W / SEG];              // W=1: items (2l,2l+1) and (128+2l,129+2l); W=2: item seg*64 + l
+    float sc[S > 0 ? S : 1][kItemsPerLane / SEG];
 };
 
 template <int W, int P, int S>
-__device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restrict__ tile, int wave, int lane)
+__device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restrict__ tile, int wave, int seg, int lane)
 {
+    constexpr int SEG = row_segments<W>();
     const TileGeom g{(uint32_t)W, (uint32_t)P, (uint32_t)S};
 #pragma unroll
     for (int j = 0; j < P; ++j) {
         const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)wave * kRow * W;
 #pragma unroll
-        for (int s = 0; s < 2 * W; ++s) {
-            const uint64_t* src = (W == 1) ? pj + s * 128 + 2 * lane : pj + (size_t)(s * 64 + lane) * 2;
+        for (int s = 0; s < 2 * W / SEG; ++s) {
+            const uint64_t* src = (W == 1) ? pj + s * 128 + 2 * lane
+                                           : pj + (size_t)((seg * (4 / SEG) + s) * 64 + lane) * 2;
             r.pl[j][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
         }
     }
@@ -78,7 +87,8 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
             }
         } else {
 #pragma unroll
-            for (int m = 0; m < kItemsPerLane; ++m) r.sc[j][m] = __builtin_nontemporal_load(sj + m * 64 + lane);
+            for (int m = 0; m < kItemsPerLane / SEG; ++m)
+                r.sc[j][m] = __builtin_nontemporal_load(sj + (seg * (kItemsPerLane / SEG) + m) * 64 + lane);
         }
     }
 }
@@ -100,8 +110,10 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     constexpr int TERMS = (kDy || kRescore) ? 1 : 2;
     constexpr int PA = kDy ? P : 1;
     constexpr int PD = kDy ? 1 : P;
-    __shared__ uint64_t s_pl[kWavesPerBlock][P][kRow * W];
-    __shared__ float s_sc[kWavesPerBlock][S > 0 ? S : 1][kRow];
+    constexpr int SEG = row_segments<W>();
+    constexpr int kSegItems = kRow / SEG;
+    __shared__ uint64_t s_pl[kWavesPerBlock][P][kSegItems * W];
+    __shared__ float s_sc[kWavesPerBlock][S > 0 ? S : 1][kSegItems];
     __shared__ uint64_t s_keys_all[kWavesPerBlock][kBatchStage];
     __shared__ uint32_t s_cnt_all[kWavesPerBlock][16 * NQT + 1];
     // what the survivor path needs of this launch's queries, close at hand: at one wave per SIMD (d = 128 with
@@ -166,30 +178,34 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
         }
 
     RawRow<W, P, S> cur, nxt;
-    load_raw<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    int seg = 0;
+    load_raw<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, seg, lane);
     for (;;) {
-        const uint32_t pn = p + G;
+        const int segn = seg + 1 == SEG ? 0 : seg + 1;
+        const uint32_t pn = segn == 0 ? p + G : p;
         const bool has_next = pn < a.p_end;
-        if (has_next) load_raw<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+        if (has_next) load_raw<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, segn, lane);
 
-        // stage the row in this wave's LDS area, in item order
+        // stage the segment in this wave's LDS area, in item order
 #pragma unroll
         for (int j = 0; j < P; ++j)
 #pragma unroll
-            for (int s = 0; s < 2 * W; ++s) {
+            for (int s = 0; s < 2 * W / SEG; ++s) {
                 uint64_t* dst = (W == 1) ? &s_pl[wave][j][s * 128 + 2 * lane] : &s_pl[wave][j][(s * 64 + lane) * 2];
                 *reinterpret_cast<u32x4*>(dst) = cur.pl[j][s];
             }
 #pragma unroll
         for (int j = 0; j < S; ++j)
 #pragma unroll
-            for (int m = 0; m < kItemsPerLane; ++m) s_sc[wave][j][lane_item<W>(lane, m)] = cur.sc[j][m];
+            for (int m = 0; m < kItemsPerLane / SEG; ++m)
+                s_sc[wave][j][SEG == 1 ? lane_item<W>(lane, m) : m * 64 + lane] = cur.sc[j][m];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
-        const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+        const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow +
+                                (uint64_t)seg * kSegItems;
         constexpr int U = 2;   // item groups per straight-line block
-        for (int cb = 0; cb < kRow / (16 * U); ++cb) {
+        for (int cb = 0; cb < kSegItems / (16 * U); ++cb) {
             float s[U][NQT][4];
             bool any = false;
 #pragma unroll
@@ -304,6 +320,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
         if (!has_next) break;
         cur = nxt;
         p = pn;
+        seg = segn;
     }
     mstage_drain(ms, a.out, lane);
 }
