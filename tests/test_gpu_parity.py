@@ -809,3 +809,31 @@ def test_float_query_batches_use_the_matrix_cores_and_match_the_table_path(N, d,
         for i in range(min(6, Q)):
             check_topk_float(dplanes, dyadic_weights(2, 50_000), q[i], 50, ids[i], sc[i])
         rbe.rbe_free(ixd)
+
+
+# ------------------------------------------------------------------ a query's result does not depend on its batch
+@pytest.mark.parametrize("d,P,Pq,flags", [(64, 3, 3, 0), (128, 4, 3, 0), (64, 2, 3, "dyadic"), (128, 3, 2, "dyadic_cosine")])
+def test_results_are_identical_for_every_batch_size(d, P, Pq, flags):
+    """Exact mode: ids and scores of a query are the same bit for bit whether it is searched alone (one-query
+    scan), in a small batch (XOR/popcount batch scan) or in a large one (matrix-core filter + exact rescoring,
+    one or several launches per level)."""
+    N, k = 180_017, 400
+    rng = np.random.default_rng(4242 + d + P)
+    if flags == 0:
+        planes, scales, qp, qs = clustered(N, d, P, 48, 0.3, 40, Pq, seed=70 + d)
+        ix = rbe.rbe_load_corpus(planes, scales)
+    else:
+        planes = rng.integers(0, 2**64, size=(P, N, d // 64), dtype=np.uint64)
+        qp = rng.integers(0, 2**64, size=(40, Pq, d // 64), dtype=np.uint64)
+        qs = None
+        ix = rbe.rbe_load_corpus(planes, None, flags=rbe.RBE_DYADIC | (rbe.RBE_COSINE if flags == "dyadic_cosine" else 0))
+    ref_ids, ref_sc = [], []
+    for q in range(40):
+        i, s = rbe.rbe_search(ix, qp[q:q + 1], None if qs is None else qs[q:q + 1], k)
+        ref_ids.append(i[0]); ref_sc.append(s[0])
+    ref_ids = np.stack(ref_ids); ref_sc = np.stack(ref_sc)
+    for Q in (2, 3, 7, 8, 9, 16, 17, 33, 40):
+        ids, sc = rbe.rbe_search(ix, qp[:Q], None if qs is None else qs[:Q], k)
+        np.testing.assert_array_equal(sc, ref_sc[:Q], err_msg=f"scores differ at batch size {Q}")
+        np.testing.assert_array_equal(ids, ref_ids[:Q], err_msg=f"ids differ at batch size {Q}")
+    rbe.rbe_free(ix)
