@@ -837,3 +837,39 @@ def test_results_are_identical_for_every_batch_size(d, P, Pq, flags):
         np.testing.assert_array_equal(sc, ref_sc[:Q], err_msg=f"scores differ at batch size {Q}")
         np.testing.assert_array_equal(ids, ref_ids[:Q], err_msg=f"ids differ at batch size {Q}")
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ seeded sweep over shapes and modes
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_shapes_and_modes(seed):
+    """Seeded draw of corpus size (ragged tails, below and above one tile), dimension, plane counts,
+    batch size, k, selection mode and group size; every case against the oracle."""
+    rng = np.random.default_rng(9000 + seed)
+    d = int(rng.choice([64, 64, 128, 256]))
+    P = int(rng.integers(1, 5)); Pq = int(rng.integers(1, 5))
+    N = int(rng.choice([1, 63, 1024, 1025, 4097, 30_011, 131_072, 250_003]))
+    Q = int(rng.choice([1, 2, 5, 8, 13, 16, 31, 64]))
+    k = int(rng.choice([1, 10, 100, 1000, 4096]))
+    mode = int(rng.choice([rbe.RBE_SELECT_EXACT, rbe.RBE_SELECT_EXACT, rbe.RBE_SELECT_NEARLOSSLESS, rbe.RBE_SELECT_NEARLOSSLESS_Q2]))
+    I = int(rng.choice([1, 2, 7, 64, 256]))
+    dyadic = bool(rng.integers(0, 3) == 0) and d <= 128
+    planes = rng.integers(0, 2**64, size=(P, N, d // 64), dtype=np.uint64)
+    qp = rng.integers(0, 2**64, size=(Q, Pq, d // 64), dtype=np.uint64)
+    if dyadic:
+        scales, flags = dyadic_weights(P, N), rbe.RBE_DYADIC
+        qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
+        ix = rbe.rbe_load_corpus(planes, None, flags=flags)
+    else:
+        scales = rng.uniform(0.01, 1.0, size=(P, N)).astype(np.float32)
+        qs = rng.uniform(0.01, 1.0, size=(Q, Pq)).astype(np.float32)
+        ix = rbe.rbe_load_corpus(planes, scales)
+    label = f"d={d} P={P} Pq={Pq} N={N} Q={Q} k={k} mode={mode} I={I} dyadic={dyadic}"
+    print(label, flush=True)
+    ids, sc = rbe.rbe_search(ix, qp, None if dyadic else qs, k, mode=mode, group_size_I=I)
+    if mode == rbe.RBE_SELECT_EXACT:
+        check_batch(planes, scales, qp, qs, k, ids, sc)
+    else:
+        for q in range(min(Q, 6)):
+            check_nearlossless(planes, scales, qp[q], qs[q], k, I, ids[q], sc[q],
+                               queue_len=2 if mode == rbe.RBE_SELECT_NEARLOSSLESS_Q2 else 1)
+    rbe.rbe_free(ix)
