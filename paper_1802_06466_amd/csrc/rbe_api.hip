@@ -311,7 +311,10 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
 // hi_only (general scales): only the hi half is stored; the accumulators then start at minus the sum of what the
 // halves actually hold, so that the contraction equals sum_d vhi_d rho_d exactly, and *margin receives a bound,
 // valid for every query of the batch, on |sum_d v_d rho_d - sum_d vhi_d rho_d| plus the fp32 rounding of either
-// side: max_q ( sum_d |v_d - vhi_d| + 2^-20 sum_d |v_d| ).
+// side (worst case, not typical): the contraction adds about d + P terms in fp32, possibly truncating
+// (<= 2^-15 sum_d |v_d|), the XOR/popcount arithmetic rounds P (PQ + 2) times at magnitudes up to
+// d sum_i |c_i| (<= 2^-20 of that, which can exceed sum_d |v_d| when the query's planes cancel):
+//     margin = max_q ( sum_d |v_d - vhi_d| + 2^-15 sum_d |v_d| + 2^-20 d sum_i |c_i| 2^k ).
 //   halves  [tile][term][plane copy][part][lane][8]   (tile = query / 16, lane = 16 g + query % 16)
 //   unscale [Q] = 2^-k,   bias [Q] = start value of the accumulators
 struct BatchOperandShape { uint32_t tiles, terms, copies, parts; size_t n_halves; };
@@ -358,6 +361,10 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
         const int k = biggest > 0.0 ? -(std::ilogb(biggest) + 1) : 0;
         unscale[q] = std::ldexp(1.0f, -k);
         const uint32_t qt = q / 16, row = q % 16;
+        double coef_mass = 0.0;     // d * sum_i |c_i| in the scaled domain
+        if (!q_float && !dyadic)
+            for (uint32_t i = 0; i < PQ; ++i) coef_mass += std::fabs((double)q_scales[(size_t)q * PQ + i]);
+        coef_mass = std::ldexp(coef_mass * dim, k);
         double sum = 0.0, lost = 0.0, mass = 0.0;
         for (uint32_t part = 0; part < KP; ++part)
             for (uint32_t grp = 0; grp < 4; ++grp)
@@ -390,7 +397,7 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
                 }
         if (dyadic) sum *= 2.0 - std::ldexp(1.0, 1 - (int)P);   // every plane's term starts from its own -2^-j sum
         bias[q] = (float)-sum;
-        worst = std::max(worst, lost + std::ldexp(mass, -20) + std::fabs(sum - (double)(float)sum));
+        worst = std::max(worst, lost + std::ldexp(mass, -15) + std::ldexp(coef_mass, -20) + std::fabs(sum - (double)(float)sum));
     }
     if (margin) *margin = (float)(worst * (1.0 + std::ldexp(1.0, -10)));
 }

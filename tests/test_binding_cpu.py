@@ -283,7 +283,7 @@ def test_matrix_core_filter_operands_stay_within_their_margin(lib):
         qhat = (qs[q].astype(np.float64)[:, None, None] * (2 * qbits - 1)).sum(axis=0).reshape(dim)
         v = qhat / float(unscale[q])                     # the scaled query the operands describe
         assert 0.5 <= np.abs(v).max() < 1.0
-        assert margin <= 2.0 ** -9 * np.abs(v).sum() + 2.0 ** -9
+        assert margin <= 2.0 ** -9 * np.abs(v).sum() + 2.0 ** -9       # a few 1e-4 of the query's mass
         for _ in range(40):
             bits = rng.integers(0, 2, size=dim)
             got = float(start[q])
