@@ -873,3 +873,26 @@ def test_random_shapes_and_modes(seed):
             check_nearlossless(planes, scales, qp[q], qs[q], k, I, ids[q], sc[q],
                                queue_len=2 if mode == rbe.RBE_SELECT_NEARLOSSLESS_Q2 else 1)
     rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_cancelling_query_planes_in_a_batch(d):
+    """Queries whose second plane is the complement of the first, with nearly equal coefficients: the
+    reconstructed query is tiny next to d * sum|c_i|, the case where the XOR/popcount arithmetic rounds at a
+    magnitude far above the query's own. Batch results (matrix-core filter) still equal the one-query results
+    bit for bit and pass the oracle check."""
+    N, P, Q, k = 70_001, 3, 16, 300
+    rng = np.random.default_rng(515 + d)
+    planes = rng.integers(0, 2**64, size=(P, N, d // 64), dtype=np.uint64)
+    scales = rng.uniform(0.05, 1.0, size=(P, N)).astype(np.float32)
+    qp = rng.integers(0, 2**64, size=(Q, 2, d // 64), dtype=np.uint64)
+    qp[:, 1] = ~qp[:, 0]
+    qs = np.stack([np.full(Q, 0.7, dtype=np.float32),
+                   (0.7 * (1.0 - 2.0 ** -rng.integers(3, 14, size=Q))).astype(np.float32)], axis=1)
+    ix = rbe.rbe_load_corpus(planes, scales)
+    ids, sc = rbe.rbe_search(ix, qp, qs, k)
+    for q in range(Q):
+        i1, s1 = rbe.rbe_search(ix, qp[q:q + 1], qs[q:q + 1], k)
+        np.testing.assert_array_equal(sc[q], s1[0]); np.testing.assert_array_equal(ids[q], i1[0])
+    check_batch(planes, scales, qp, qs, k, ids, sc)
+    rbe.rbe_free(ix)
