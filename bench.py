@@ -321,6 +321,7 @@ def main():
                     "hbm_gbs": b_items * bytes_per_item / (b_scan * 1e-3) / 1e9}
         out["batch"] = {
             "queries_per_step": B, "steps": args.batch_steps, "ms_per_step": b_ms,
+            "p50_ms": float(np.percentile(rb["per_step_ms"], 50)),
             "value": N * B * args.batch_steps / rb["wall_s"], "unit": "candidates/s",
             "dtype": "f16 x f16 -> f32 filter, u64 xor/popcount + f32 scores" if matrix_cores else "u64 xor/popcount + f32",
             "last_search_level_ms": {"scan": rb["stats"]["scan_ms"], "select": rb["stats"]["select_ms"]},
@@ -339,13 +340,15 @@ def main():
             v_ach = lane_ops_per_pair(W, P, P) * B * rv["stats"]["items_scanned"][-1] / (v_scan * 1e-3) / 1e12
             out["batch_popcount_kernel"] = {
                 "queries_per_step": B, "steps": steps_v, "ms_per_step": v_ms,
+                "p50_ms": float(np.percentile(rv["per_step_ms"], 50)),
+                "gpu_ms_per_search": float(rv["total_gpu_ms"].mean()) if rv["total_gpu_ms"].size else None,
                 "last_search_level_ms": {"scan": rv["stats"]["scan_ms"], "select": rv["stats"]["select_ms"]},
                 "value": N * B / (v_ms * 1e-3), "unit": "candidates/s", "dtype": "u64 xor/popcount + f32",
                 "roofline": {"kernel": "scan_exact (finest level)", "bound": "alu", "achieved": v_ach,
                              "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-ops/s", "frac": v_ach / VALU_PEAK_TLANEOPS,
                              "kernel_ms": v_scan, "lane_ops_per_pair": lane_ops_per_pair(W, P, P), "traffic": None},
             }
-            log(f"Q={B}, XOR/popcount kernel: {v_ms:.3f} ms/step, scan kernel {v_scan:.3f} ms "
+            log(f"Q={B}, XOR/popcount kernel: {v_ms:.3f} ms/step (per step {np.round(rv['per_step_ms'], 2).tolist()}), scan kernel {v_scan:.3f} ms "
                 f"-> {v_ach:.1f} T lane-ops/s")
 
     # ---------------- CPU baseline: the oracle, as it stands, on a bounded sample

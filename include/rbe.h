@@ -295,25 +295,27 @@ int rbe_debug_exact_plan(uint64_t n_items, uint32_t sample_ratio, uint32_t cand_
                          uint32_t *n_levels, uint32_t *first_tile, uint32_t *end_tile);
 
 /* Query operands of the matrix-core batch scan (pure host function, for tests).
- * halves_out [tile][term][plane copy][part][lane][8] fp16 bit patterns, where
+ * The queries are binary (q_planes [Q][Pq][W] and, unless dyadic, q_scales
+ * [Q][Pq]; q_float NULL) or fp32 (q_float [Q][dim]; general scales only, the
+ * other two are not read).
+ * halves_out [tile][plane copy][part][lane][8] fp16 bit patterns, where
  * tile = query / 16, lane = 16 g + query % 16, part = 32-dimension part of the
  * query and slot e = 2t + h of lane group g stands for bit (10 + 16h + t - 4g)
  * mod 32 of that part, weighted by 2 / val_t with val_t = 2^-14, 2^-13, 2^-11,
  * 2^-7 (the value of a half whose only set bit is bit 10 + t: the form in which
  * the kernel feeds item bits), times 2^-j in plane copy j (dyadic only; one copy
- * otherwise).  form 0: term 0 = hi half, term 1 = lo half of every component
- * (general scales, the contraction is the score).  form 1: dyadic index, one exact
- * half.  form 2: hi half only (general scales, binary queries): the contraction is
- * a filter whose distance from the score is at most margin * sum_j a_j[item], and
- * survivors are scored again exactly.
+ * otherwise).  dyadic = 1: every half is exact and the contraction is the score.
+ * dyadic = 0 (general scales): every component is rounded to one half and the
+ * contraction is a filter whose distance from the score is at most
+ * margin * sum_j a_j[item]; survivors are scored again exactly.
  * unscale_out[q] = 2^-k undoes the power-of-two scaling of query q; start_out[q]
  * is where its accumulators start (minus the weighted sum of what the halves hold).
- * shape_out = {tiles, terms, plane copies, parts, margin (float bits)}: 5 entries.
+ * shape_out = {tiles, plane copies, parts, margin (float bits)}: 4 entries.
  * halves_capacity in halves.                                                    */
-int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, uint32_t n_queries,
-                             uint32_t q_n_planes, uint32_t dim, uint32_t n_planes, uint32_t form,
-                             uint16_t *halves_out, size_t halves_capacity, float *unscale_out,
-                             float *start_out, uint32_t *shape_out);
+int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, const float *q_float,
+                             uint32_t n_queries, uint32_t q_n_planes, uint32_t dim, uint32_t n_planes,
+                             uint32_t dyadic, uint16_t *halves_out, size_t halves_capacity,
+                             float *unscale_out, float *start_out, uint32_t *shape_out);
 
 /* Measurement yardstick: enqueues a plain copy kernel ("calib_copy") of `bytes`
  * bytes from src_dev to dst_dev (DEVICE pointers, 16-byte aligned, bytes a

@@ -74,7 +74,7 @@ PROTOTYPES = {
     "rbe_debug_phys_to_tile": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_set_batch_path": (_i32, [_vp, _i32]),
     "rbe_debug_exact_plan": (_i32, [_u64, _u32, _u32, _u32, _vp, _vp, _vp]),
-    "rbe_debug_batch_operands": (_i32, [_vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
+    "rbe_debug_batch_operands": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
@@ -364,27 +364,30 @@ def rbe_debug_exact_plan(n_items: int, sample_ratio: int, cand_capacity: int, k:
     return [(int(first[i]), int(end[i])) for i in range(int(n[0]))]
 
 
-def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic: bool, hi_only: bool = False):
+def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic: bool, q_float=None):
     """Query operands of the matrix-core batch scan (host only): fp16 bit patterns
-    [tile][term][plane copy][part][lane][8], unscale [Q], start [Q]; with hi_only also the filter margin."""
-    q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
-    Q, Pq = q_planes.shape[0], q_planes.shape[1]
+    [tile][plane copy][part][lane][8], unscale [Q], start [Q] and the filter margin (0 for a dyadic index).
+    q_float [Q][dim] replaces the binary queries (general scales only)."""
+    if q_float is not None:
+        q_float = np.ascontiguousarray(q_float, dtype=np.float32)
+        Q, Pq = q_float.shape[0], 0
+    else:
+        q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
+        Q, Pq = q_planes.shape[0], q_planes.shape[1]
     if q_scales is not None:
         q_scales = np.ascontiguousarray(q_scales, dtype=np.float32)
-    cap = ((Q + 15) // 16) * 2 * 4 * (dim // 32) * 64 * 8
+    cap = ((Q + 15) // 16) * 4 * (dim // 32) * 64 * 8
     halves = np.zeros(cap, dtype=np.uint16)
     unscale = np.zeros(Q, dtype=np.float32)
     start = np.zeros(Q, dtype=np.float32)
-    shape = np.zeros(5, dtype=np.uint32)
-    form = 1 if dyadic else (2 if hi_only else 0)
+    shape = np.zeros(4, dtype=np.uint32)
     _check(load_library().rbe_debug_batch_operands(
-        q_planes.ctypes.data, None if q_scales is None else q_scales.ctypes.data, Q, Pq, dim, n_planes,
-        form, halves.ctypes.data, cap, unscale.ctypes.data, start.ctypes.data, shape.ctypes.data))
-    tiles, terms, copies, parts = (int(x) for x in shape[:4])
-    out = halves[:tiles * terms * copies * parts * 64 * 8].reshape(tiles, terms, copies, parts, 64, 8)
-    if hi_only:
-        return out, unscale, start, float(shape[4:5].view(np.float32)[0])
-    return out, unscale, start
+        None if q_float is not None else q_planes.ctypes.data, None if q_scales is None else q_scales.ctypes.data,
+        None if q_float is None else q_float.ctypes.data, Q, Pq, dim, n_planes,
+        1 if dyadic else 0, halves.ctypes.data, cap, unscale.ctypes.data, start.ctypes.data, shape.ctypes.data))
+    tiles, copies, parts = (int(x) for x in shape[:3])
+    out = halves[:tiles * copies * parts * 64 * 8].reshape(tiles, copies, parts, 64, 8)
+    return out, unscale, start, float(shape[3:4].view(np.float32)[0])
 
 
 def rbe_debug_set_batch_path(ix: Index, path: int):

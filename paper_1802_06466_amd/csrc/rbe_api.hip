@@ -272,22 +272,26 @@ int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t s
 
 // 16-query tiles of a batch, and how many of them one launch of the matrix-core scan takes (1 or 2): two while
 // the query operands of both fit in about 64 registers.  Per tile they take 4 registers per 32-dimension part,
-// times two halves (general scales) or times the item planes (dyadic modes).
+// times the item planes in the dyadic modes (one weighted copy per plane).
 uint32_t batch_tiles(uint32_t Q) { return (Q + 15u) / 16u; }
 uint32_t batch_tiles_per_launch(const rbe_index* ix)
 {
-    const uint32_t per_tile = 4u * 2u * ix->W * (ix->mode == rbe::kModeScaled ? 2u : ix->P);
+    const uint32_t per_tile = 4u * 2u * ix->W * (ix->mode == rbe::kModeScaled ? 1u : ix->P);
     return 2u * per_tile <= 64u ? 2u : 1u;
 }
 
-// General scales, binary queries: the contraction carries the hi half only and filters; survivors are rescored
-// exactly (see scan_batch_mfma).  Full-precision queries have no exact bitwise form: they carry hi + lo.
-bool batch_rescore(const rbe_index* ix, bool float_query) { return ix->mode == rbe::kModeScaled && !float_query; }
+// General scales: the contraction carries the hi half only and filters; survivors are scored again exactly as the
+// one-query scan scores them (see scan_batch_mfma): 1 = binary queries (XOR/popcount), 2 = fp32 queries (byte
+// tables).  0 = dyadic modes, whose queries are exact in one half.
+uint32_t batch_rescore(const rbe_index* ix, bool float_query)
+{
+    return ix->mode != rbe::kModeScaled ? 0u : (float_query ? 2u : 1u);
+}
 
 bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query)
 {
     if (mode != RBE_SELECT_EXACT || !rbe::batch_mfma_supported(ix->W)) return false;
-    // full-precision queries need both halves; the dyadic kernels carry one (their queries are exact in it)
+    // full-precision queries need the filter; the dyadic kernels have none (their binary queries are exact)
     if (float_query && ix->mode != rbe::kModeScaled) return false;
     if (ix->batch_path == 1) return false;
     if (ix->batch_path == 2) return true;
@@ -303,30 +307,33 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
 // The kernel's B operand holds, for item bit b, the half whose only set bit is bit 10 + t (t = 0..3):
 // 0 or val_t = 2^-14, 2^-13, 2^-11, 2^-7.  With rho = 2b - 1:
 //     sum_d v_d rho_d = sum_d (2 v_d / val_t) (b_d val_t) - sum_d v_d,
-// so the A operand carries 2 v_d / val_t (below 2^15), as hi + lo halves with general scales, and the
-// accumulator starts at -sum_d v_d.  Lane (g, row) of 32-dimension part kp holds slot e = 2t + h; the kernel
+// so the A operand carries 2 v_d / val_t (below 2^15), rounded to one half, and the accumulator starts at
+// -sum_d v_d.  Lane (g, row) of 32-dimension part kp holds slot e = 2t + h; the kernel
 // rotates the part's word left by 4g and takes bits 10 + t (h = 0) and 26 + t (h = 1), i.e. original bit
 // (10 + 16h + t - 4g) mod 32.  Dyadic modes: one exact half, one copy per item plane j scaled by 2^-j, and
 // the start value covers all planes.
-// hi_only (general scales): only the hi half is stored; the accumulators then start at minus the sum of what the
+// General scales: the half is a rounding (hi); the accumulators then start at minus the sum of what the
 // halves actually hold, so that the contraction equals sum_d vhi_d rho_d exactly, and *margin receives a bound,
 // valid for every query of the batch, on |sum_d v_d rho_d - sum_d vhi_d rho_d| plus the fp32 rounding of either
-// side (worst case, not typical): the contraction adds about d + P terms in fp32, possibly truncating
-// (<= 2^-15 sum_d |v_d|), the XOR/popcount arithmetic rounds P (PQ + 2) times at magnitudes up to
-// d sum_i |c_i| (<= 2^-20 of that, which can exceed sum_d |v_d| when the query's planes cancel):
-//     margin = max_q ( sum_d |v_d - vhi_d| + 2^-15 sum_d |v_d| + 2^-20 d sum_i |c_i| 2^k ).
-//   halves  [tile][term][plane copy][part][lane][8]   (tile = query / 16, lane = 16 g + query % 16)
+// side (worst case, not typical): the contraction adds d + 1 terms of total magnitude <= 3 sum_d |v_d| in fp32,
+// possibly truncating (<= 3 (d + 8) 2^-23 sum_d |v_d|, the + 8 for the P FMAs after it); the XOR/popcount
+// arithmetic rounds P (PQ + 2) times at magnitudes up to d sum_i |c_i| (<= 2^-20 of that, which can exceed
+// sum_d |v_d| when the query's planes cancel); the byte-table arithmetic of fp32 queries rounds 8W table
+// entries and adds them (<= 2^-19 sum_d |v_d|):
+//     margin = max_q ( sum_d |v_d - vhi_d| + 3 (d + 8) 2^-23 sum_d |v_d| + 2^-20 d sum_i |c_i| 2^k  [+ 2^-19 sum_d |v_d|] ).
+// A hi half that would be subnormal is stored as zero (and counted as lost), so that the bound does not depend
+// on how the matrix cores treat subnormal inputs.
+//   halves  [tile][plane copy][part][lane][8]   (tile = query / 16, lane = 16 g + query % 16)
 //   unscale [Q] = 2^-k,   bias [Q] = start value of the accumulators
-struct BatchOperandShape { uint32_t tiles, terms, copies, parts; size_t n_halves; };
+struct BatchOperandShape { uint32_t tiles, copies, parts; size_t n_halves; };
 
-BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint32_t Q, bool hi_only)
+BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint32_t Q)
 {
     BatchOperandShape sh;
     sh.tiles = batch_tiles(Q);
-    sh.terms = (dyadic || hi_only) ? 1u : 2u;
     sh.copies = dyadic ? P : 1u;
     sh.parts = 2u * W;
-    sh.n_halves = (size_t)sh.tiles * sh.terms * sh.copies * sh.parts * 64 * 8;
+    sh.n_halves = (size_t)sh.tiles * sh.copies * sh.parts * 64 * 8;
     return sh;
 }
 
@@ -334,11 +341,11 @@ BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint3
 // are not read; general scales only.
 void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q_planes, const float* q_scales,
                           uint32_t Q, uint32_t PQ, uint16_t* halves, float* unscale, float* bias,
-                          const float* q_float = nullptr, bool hi_only = false, float* margin = nullptr)
+                          const float* q_float = nullptr, float* margin = nullptr)
 {
-    const BatchOperandShape sh = batch_operand_shape(W, P, dyadic, Q, hi_only);
+    const BatchOperandShape sh = batch_operand_shape(W, P, dyadic, Q);
     double worst = 0.0;
-    const uint32_t dim = 64 * W, KP = sh.parts, TERMS = sh.terms, PA = sh.copies;
+    const uint32_t dim = 64 * W, KP = sh.parts, PA = sh.copies;
     std::memset(halves, 0, sh.n_halves * sizeof(uint16_t));
     std::vector<double> qhat(dim);
     static const int kValExp[4] = {-14, -13, -11, -7};
@@ -373,9 +380,12 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
                     const uint32_t bit = (10u + 16u * h + t + 32u - 4u * grp) & 31u;
                     const double v = std::ldexp(qhat[part * 32 + bit], k);
                     const uint32_t lane = grp * 16 + row;
-                    if (hi_only && !dyadic) {
-                        // what the hi half really holds, back in the units of v
-                        const double held = std::ldexp((double)(float)(_Float16)(float)std::ldexp(v, 1 - kValExp[t]), kValExp[t] - 1);
+                    bool drop = false;
+                    if (!dyadic) {
+                        // what the half really holds, back in the units of v
+                        double held = std::ldexp((double)(float)(_Float16)(float)std::ldexp(v, 1 - kValExp[t]), kValExp[t] - 1);
+                        drop = std::fabs(std::ldexp(held, 1 - kValExp[t])) < std::ldexp(1.0, -14);
+                        if (drop) held = 0.0;
                         sum += held;
                         lost += std::fabs(v - held);
                         mass += std::fabs(v);
@@ -384,29 +394,24 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
                     }
                     for (uint32_t pa = 0; pa < PA; ++pa) {
                         const double aval = std::ldexp(v, 1 - kValExp[t] - (int)pa);
-                        const _Float16 hi = (_Float16)(float)aval;
+                        const _Float16 hi = drop ? (_Float16)0.0f : (_Float16)(float)aval;
                         uint16_t bits;
                         std::memcpy(&bits, &hi, 2);
-                        halves[(((((size_t)qt * TERMS + 0) * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
-                        if (TERMS == 2) {
-                            const _Float16 lo = (_Float16)(float)(aval - (double)(float)hi);
-                            std::memcpy(&bits, &lo, 2);
-                            halves[(((((size_t)qt * TERMS + 1) * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
-                        }
+                        halves[((((size_t)qt * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
                     }
                 }
         if (dyadic) sum *= 2.0 - std::ldexp(1.0, 1 - (int)P);   // every plane's term starts from its own -2^-j sum
         bias[q] = (float)-sum;
-        worst = std::max(worst, lost + std::ldexp(mass, -15) + std::ldexp(coef_mass, -20) + std::fabs(sum - (double)(float)sum));
+        worst = std::max(worst, lost + std::ldexp(mass * 3.0 * (dim + 8), -23) + std::ldexp(coef_mass, -20) +
+                                    (q_float ? std::ldexp(mass, -19) : 0.0) + std::fabs(sum - (double)(float)sum));
     }
-    if (margin) *margin = (float)(worst * (1.0 + std::ldexp(1.0, -10)));
+    if (margin) *margin = dyadic ? 0.0f : (float)(worst * (1.0 + std::ldexp(1.0, -10)));
 }
 
 int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
                         hipStream_t st, const float* q_float = nullptr)
 {
-    const bool hi_only = batch_rescore(ix, q_float != nullptr);
-    const size_t max_halves = (size_t)(RBE_MAX_QUERIES / 16) * 4 * 4 * 64 * 8;   // per tile: (terms x copies) x parts <= 16
+    const size_t max_halves = (size_t)(RBE_MAX_QUERIES / 16) * 4 * 4 * 64 * 8;   // per tile: copies x parts <= 16
     if (!ix->d_aops) {
         HIP_TRY(hipMalloc(&ix->d_aops, max_halves * sizeof(uint16_t)));
         HIP_TRY(hipHostMalloc(&ix->h_aops, max_halves * sizeof(uint16_t), hipHostMallocDefault));
@@ -414,9 +419,9 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
         HIP_TRY(hipHostMalloc(&ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
     }
     const bool dyadic = ix->mode != rbe::kModeScaled;
-    const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q, hi_only);
+    const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q);
     build_batch_operands(ix->W, ix->P, dyadic, q_planes, q_scales, Q, PQ, reinterpret_cast<uint16_t*>(ix->h_aops),
-                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float, hi_only, &ix->batch_margin);
+                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float, &ix->batch_margin);
     HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, sh.n_halves * sizeof(uint16_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
@@ -557,25 +562,26 @@ int rbe_debug_exact_plan(uint64_t n_items, uint32_t sample_ratio, uint32_t cand_
     return RBE_OK;
 }
 
-int rbe_debug_batch_operands(const uint64_t* q_planes, const float* q_scales, uint32_t n_queries, uint32_t q_n_planes,
-                             uint32_t dim, uint32_t n_planes, uint32_t dyadic /* form */, uint16_t* halves_out, size_t halves_capacity,
-                             float* unscale_out, float* start_out, uint32_t* shape_out)
+int rbe_debug_batch_operands(const uint64_t* q_planes, const float* q_scales, const float* q_float, uint32_t n_queries,
+                             uint32_t q_n_planes, uint32_t dim, uint32_t n_planes, uint32_t dyadic, uint16_t* halves_out,
+                             size_t halves_capacity, float* unscale_out, float* start_out, uint32_t* shape_out)
 {
-    ARG_CHECK(q_planes && halves_out && unscale_out && start_out && shape_out, "NULL argument");
-    ARG_CHECK(dyadic == 1 || q_scales, "q_scales is NULL");
+    ARG_CHECK(halves_out && unscale_out && start_out && shape_out, "NULL argument");
+    ARG_CHECK(dyadic <= 1, "dyadic must be 0 or 1");
+    ARG_CHECK(q_float ? dyadic == 0 : (q_planes && (dyadic == 1 || q_scales)), "queries missing (or fp32 queries on a dyadic index)");
     ARG_CHECK(dim == 64 || dim == 128, "dim must be 64 or 128");
-    ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES && q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES,
-              "plane counts out of range");
+    ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES, "n_planes out of range");
+    ARG_CHECK(q_float || (q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES), "q_n_planes out of range");
     ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries out of range");
-    const bool dy = dyadic == 1, hi_only = dyadic == 2;
-    ARG_CHECK(dyadic <= 2, "form must be 0, 1 or 2");
-    const BatchOperandShape sh = batch_operand_shape(dim / 64, n_planes, dy, n_queries, hi_only);
+    if (q_float)
+        for (size_t i = 0; i < (size_t)n_queries * dim; ++i) ARG_CHECK(std::isfinite(q_float[i]), "q_float[%zu] is not finite", i);
+    const BatchOperandShape sh = batch_operand_shape(dim / 64, n_planes, dyadic == 1, n_queries);
     ARG_CHECK(halves_capacity >= sh.n_halves, "halves_out too small: %zu needed", sh.n_halves);
     float margin = 0.0f;
-    build_batch_operands(dim / 64, n_planes, dy, q_planes, q_scales, n_queries, q_n_planes, halves_out,
-                         unscale_out, start_out, nullptr, hi_only, &margin);
-    shape_out[0] = sh.tiles; shape_out[1] = sh.terms; shape_out[2] = sh.copies; shape_out[3] = sh.parts;
-    std::memcpy(&shape_out[4], &margin, sizeof(float));
+    build_batch_operands(dim / 64, n_planes, dyadic == 1, q_planes, q_scales, n_queries, q_n_planes, halves_out,
+                         unscale_out, start_out, q_float, &margin);
+    shape_out[0] = sh.tiles; shape_out[1] = sh.copies; shape_out[2] = sh.parts;
+    std::memcpy(&shape_out[3], &margin, sizeof(float));
     return RBE_OK;
 }
 
@@ -794,7 +800,7 @@ struct SearchCtx {
     uint32_t qlen;      // near-lossless: entries per group queue (1 or 2); mode holds RBE_SELECT_NEARLOSSLESS for both
     bool float_query;   // hybrid scoring: fp32 queries through byte tables
     bool batch_mfma;    // exact mode, several queries: matrix-core scan
-    bool float_batch;   // ... of full-precision queries (no binary form to rescore with)
+    bool float_batch;   // ... of full-precision queries
 };
 
 // dense: a coarse level of the plan, where a large share of the items passes the (still loose) threshold.
@@ -825,8 +831,8 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
         ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.tau = ix->d_tau; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
-        ba.rescore = batch_rescore(ix, c.float_batch) ? 1u : 0u;
-        ba.PQ = c.PQ; ba.qwords = ix->d_qwords; ba.qcoef = ix->d_qcoef; ba.margin = ix->batch_margin;
+        ba.rescore = batch_rescore(ix, c.float_batch);
+        ba.PQ = c.PQ; ba.qwords = ix->d_qwords; ba.qcoef = ix->d_qcoef; ba.lut = ix->d_lut; ba.margin = ix->batch_margin;
         e = hipSuccess;
         const uint32_t tiles = batch_tiles(c.Q), per_launch = batch_tiles_per_launch(ix);
         for (uint32_t t0 = 0; t0 < tiles && e == hipSuccess; t0 += per_launch) {   // one pass over the range per launch
@@ -1039,6 +1045,7 @@ int rbe_search_float(rbe_index* ix, const float* q, uint32_t n_queries, uint32_t
         // several queries: the same dense contraction as for binary queries, with the query itself as operand
         c.float_batch = true;
         rc = stage_batch_queries(ix, nullptr, nullptr, c.Q, 0, c.st, q);
+        if (!rc) rc = stage_float_queries(ix, q, c.Q, c.st);   // the byte tables survivors are scored from
     } else {
         c.float_query = true;
         rc = stage_float_queries(ix, q, c.Q, c.st);

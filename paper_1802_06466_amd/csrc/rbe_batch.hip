@@ -22,17 +22,19 @@
 // every 32-bit part with one rotate and four ANDs.
 //
 // Schedule.  Vector instructions overlap with the MFMAs of the same SIMD only if they
-// are independent of them, so the row is processed four item groups at a time in one
+// are independent of them, so the row is processed two item groups at a time in one
 // straight-line block (the survivor test comes once per block): the expansion of the
 // next group and the fp32 combination of the previous one issue while a group's MFMAs
 // are in the pipeline.
 //
-// qhat is scaled by a power of two into (-1, 1) and split into two halves (hi + lo,
-// about 22 bits together); products are exact and accumulate in fp32, so scores
-// agree with the XOR/popcount path to about 1e-6 relative; the binary dot products
-// themselves are never rounded because they are never formed.  The per-pair VALU
-// work drops from ~58 lane-ops to P fused multiply-adds and one compare; bit
-// expansion is paid once per item, whatever the number of queries.
+// Precision.  qhat is scaled by a power of two into (-1, 1); products are exact and
+// accumulate in fp32.  Dyadic modes: every operand is exact in one half, so the
+// contraction is the score.  General scales: the operand is each component rounded to
+// one half, the contraction is a filter with a margin the host computes, and whatever
+// passes it is scored again in the arithmetic of the one-query scan, so the results
+// carry no trace of the half precision.  The per-pair VALU work drops from ~58
+// lane-ops to P fused multiply-adds and one compare; bit expansion is paid once per
+// item, whatever the number of queries.
 #include "rbe_internal.hpp"
 
 #ifndef RBE_W
@@ -93,21 +95,24 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
     }
 }
 
-// RS (general scales, binary queries): the contraction runs with the hi half of the query only and is used as a
-// filter -- its distance from the true score is at most a.margin * sum_j a_j[item] (the host adds up the part of
-// every query component that the half does not hold) -- and what passes the filter is scored again exactly as the
-// XOR/popcount scan scores it.  Half the MFMAs, and results that do not depend on how many queries share a call.
-template <int W, int P, int MODE, int NQT, bool RS>
+// RS != 0 (general scales): the contraction runs with the hi half of the query only and is used as a filter -- its
+// distance from the true score is at most a.margin * sum_j a_j[item] (the host adds up the part of every query
+// component that the half does not hold) -- and what passes the filter is scored again exactly as the one-query
+// scan scores it: RS = 1, binary queries, in the arithmetic of the XOR/popcount scan; RS = 2, fp32 queries, from
+// the byte tables of the hybrid scan.  Half the MFMAs, and results that do not depend on how many queries share
+// a call.
+template <int W, int P, int MODE, int NQT, int RS>
 __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
 {
     constexpr int S = scale_arrays(MODE, P);
     constexpr int KP = 2 * W;                          // 32-dimension parts of a plane
-    // General scales: one accumulator per plane (the item's a_j is applied afterwards) and the query as hi + lo.
-    // Dyadic modes: the plane weight 2^-j is folded into a per-plane copy of the query operand, all planes add
-    // into one accumulator, and the query (a short dyadic fraction) is exact in one half.
+    // General scales: one accumulator per plane (the item's a_j is applied afterwards); the query's hi half
+    // filters.  Dyadic modes: the plane weight 2^-j is folded into a per-plane copy of the query operand, all
+    // planes add into one accumulator, and the query (a short dyadic fraction) is exact in one half.
     constexpr bool kDy = MODE != kModeScaled;
-    constexpr bool kRescore = RS && !kDy;
-    constexpr int TERMS = (kDy || kRescore) ? 1 : 2;
+    constexpr bool kRescore = !kDy;
+    constexpr bool kBinary = kRescore && RS == 1;
+    static_assert(kDy ? RS == 0 : (RS == 1 || RS == 2), "general scales filter and rescore; dyadic modes are exact");
     constexpr int PA = kDy ? P : 1;
     constexpr int PD = kDy ? 1 : P;
     constexpr int SEG = row_segments<W>();
@@ -120,8 +125,8 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     // 3 or 4 planes) a global read there would stall the whole SIMD
     __shared__ uint64_t s_tau[16 * NQT];
     __shared__ float s_unscale[16 * NQT];
-    __shared__ uint32_t s_qw[kRescore ? 16 * NQT : 1][kMaxPlanes][2 * W];
-    __shared__ float s_qc[kRescore ? 16 * NQT : 1][kMaxPlanes + 1];
+    __shared__ uint32_t s_qw[kBinary ? 16 * NQT : 1][kMaxPlanes][2 * W];
+    __shared__ float s_qc[kBinary ? 16 * NQT : 1][kMaxPlanes + 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -136,7 +141,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
         const bool live = q < a.n_queries;
         s_tau[ql] = live ? a.tau[q] : ~0ull;
         s_unscale[ql] = live ? a.q_unscale[q] : 1.0f;
-        if (kRescore) {
+        if (kBinary) {
             for (uint32_t i = 0; i <= a.PQ; ++i) s_qc[ql][i] = live ? a.qcoef[(size_t)q * (a.PQ + 1) + i] : 0.0f;
             for (uint32_t i = 0; i < a.PQ; ++i)
                 for (int h = 0; h < 2 * W; ++h) s_qw[ql][i][h] = live ? a.qwords[((size_t)q * a.PQ + i) * 2 * W + h] : 0u;
@@ -150,20 +155,18 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     uint32_t p = a.p_begin + blockIdx.x;
     if (p >= a.p_end) return;
 
-    // query operands (16 queries per tile, hi and lo halves, KP parts), already in lane order
-    half8 A[NQT][TERMS][PA][KP];
+    // query operands (16 queries per tile, one half per component, KP parts), already in lane order
+    half8 A[NQT][PA][KP];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-        for (int sp = 0; sp < TERMS; ++sp)
+        for (int pa = 0; pa < PA; ++pa)
 #pragma unroll
-            for (int pa = 0; pa < PA; ++pa)
-#pragma unroll
-                for (int kp = 0; kp < KP; ++kp) {
-                    const u32x4 v =
-                        reinterpret_cast<const u32x4*>(a.a_ops)[((((a.q_begin / 16 + qt) * TERMS + sp) * PA + pa) * KP + kp) * 64 + lane];
-                    A[qt][sp][pa][kp] = __builtin_bit_cast(half8, v);
-                }
+            for (int kp = 0; kp < KP; ++kp) {
+                const u32x4 v =
+                    reinterpret_cast<const u32x4*>(a.a_ops)[(((a.q_begin / 16 + qt) * PA + pa) * KP + kp) * 64 + lane];
+                A[qt][pa][kp] = __builtin_bit_cast(half8, v);
+            }
     // this lane's queries: tile qt, rows 4g .. 4g+3 (query a.q_begin + 16 qt + 4g + r).  Scores are formed in the
     // query's scaled domain (qhat * 2^k); thresholds are moved there, survivors are moved back (both exact).
     // Only what the common path needs stays in registers; the rare survivor path re-reads the rest.
@@ -236,14 +239,12 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                         const half8 B = __builtin_bit_cast(half8, bw);
 #pragma unroll
                         for (int qt = 0; qt < NQT; ++qt)
-#pragma unroll
-                            for (int sp = 0; sp < TERMS; ++sp)
-                                D[qt][kDy ? 0 : j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                                    A[qt][sp][kDy ? j : 0][kp], B, D[qt][kDy ? 0 : j], 0, 0, 0);
+                            D[qt][kDy ? 0 : j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                                A[qt][kDy ? j : 0][kp], B, D[qt][kDy ? 0 : j], 0, 0, 0);
                     }
                 }
                 float aj[P];
-                float adj = 0.0f;      // filter slack of this item (kRescore)
+                float adj = 0.0f;      // filter slack of this item (general scales)
                 if (MODE == kModeScaled) {
 #pragma unroll
                     for (int j = 0; j < P; ++j) aj[j] = s_sc[wave][j][item];
@@ -287,9 +288,26 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                             uint64_t key = 0;
                             if (ok) {
                                 float score;
-                                if (kRescore) {
+                                const uint32_t it = (uint32_t)(16 * (cb * U + u) + col);
+                                if (kRescore && !kBinary) {
+                                    // exact score of the hybrid scan: byte-table entries added in byte order
+                                    const float(*lut)[256] =
+                                        reinterpret_cast<const float(*)[256]>(a.lut + (size_t)(a.q_begin + ql) * (8 * W * 256));
+                                    score = 0.0f;
+                                    for (int j = 0; j < P; ++j) {
+                                        const uint32_t* kw = reinterpret_cast<const uint32_t*>(&s_pl[wave][j][it * W]);
+                                        float t = 0.0f;
+                                        for (int h = 0; h < 2 * W; ++h) {
+                                            const uint32_t w = kw[h];
+                                            t += lut[4 * h + 0][w & 255u];
+                                            t += lut[4 * h + 1][(w >> 8) & 255u];
+                                            t += lut[4 * h + 2][(w >> 16) & 255u];
+                                            t += lut[4 * h + 3][w >> 24];
+                                        }
+                                        score = __fmaf_rn(s_sc[wave][j][it], t, score);
+                                    }
+                                } else if (kBinary) {
                                     // exact score, in the arithmetic of the XOR/popcount scan (i inner, j outer)
-                                    const uint32_t it = (uint32_t)(16 * (cb * U + u) + col);
                                     const float* qc = s_qc[ql];
                                     score = 0.0f;
                                     for (int j = 0; j < P; ++j) {
@@ -329,29 +347,41 @@ namespace {
 using BatchFn = void (*)(const BatchArgs);
 
 template <int W, int P, int MODE>
-BatchFn batch_fn_q(uint32_t nqt, bool rescore)
+BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore)
 {
-    if (MODE == kModeScaled && rescore) {
+    if constexpr (MODE == kModeScaled) {
+        if (rescore == 1) {
+            switch (nqt) {
+                case 1: return scan_batch_mfma<W, P, MODE, 1, 1>;
+                case 2: return scan_batch_mfma<W, P, MODE, 2, 1>;
+                default: return nullptr;
+            }
+        }
+        if (rescore == 2) {
+            switch (nqt) {
+                case 1: return scan_batch_mfma<W, P, MODE, 1, 2>;
+                case 2: return scan_batch_mfma<W, P, MODE, 2, 2>;
+                default: return nullptr;
+            }
+        }
+        return nullptr;
+    } else {
+        if (rescore != 0) return nullptr;
         switch (nqt) {
-            case 1: return scan_batch_mfma<W, P, MODE, 1, true>;
-            case 2: return scan_batch_mfma<W, P, MODE, 2, true>;
+            case 1: return scan_batch_mfma<W, P, MODE, 1, 0>;
+            case 2: return scan_batch_mfma<W, P, MODE, 2, 0>;
             default: return nullptr;
         }
-    }
-    switch (nqt) {
-        case 1: return scan_batch_mfma<W, P, MODE, 1, false>;
-        case 2: return scan_batch_mfma<W, P, MODE, 2, false>;
-        default: return nullptr;
     }
 }
 
 template <int W, int P>
-BatchFn batch_fn_m(int mode, uint32_t nqt, bool rescore)
+BatchFn batch_fn_m(int mode, uint32_t nqt, uint32_t rescore)
 {
     switch (mode) {
         case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore);
-        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, false);
-        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, false);
+        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0);
+        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0);
         default: return nullptr;
     }
 }
@@ -363,10 +393,10 @@ hipError_t launch_scan_batch_w<RBE_W>(const KernelSel& k, const BatchArgs& a, ui
 {
     BatchFn fn = nullptr;
     switch (k.P) {
-        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore != 0); break;
-        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore != 0); break;
-        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore != 0); break;
-        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore != 0); break;
+        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore); break;
+        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore); break;
+        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore); break;
+        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;

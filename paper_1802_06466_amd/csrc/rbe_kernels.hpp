@@ -370,12 +370,14 @@ struct BatchArgs {
     const uint64_t* tau;      // [Q] threshold keys
     uint32_t n_queries;       // Q
     uint32_t q_begin;         // first query of this launch (a multiple of 16); it handles 16 or 32 from there
-    // hi-half filter + exact rescoring (general scales, binary queries): the staged binary queries of the
-    // XOR/popcount scan, and the bound on |true - filter score| per unit of sum_j a_j[item], in the scaled domain
-    uint32_t rescore;         // 0: a_ops holds hi + lo halves and the contraction is the score
-    uint32_t PQ;              // query planes
-    const uint32_t* qwords;   // [Q][PQ][2W]
-    const float* qcoef;       // [Q][PQ+1]
+    // hi-half filter + exact rescoring (general scales): what the one-query scan scores with -- the staged binary
+    // queries of the XOR/popcount scan (rescore = 1) or the byte tables of fp32 queries (rescore = 2) -- and the
+    // bound on |true - filter score| per unit of sum_j a_j[item], in the scaled domain
+    uint32_t rescore;         // 0: a_ops holds hi + lo halves (or one exact half) and the contraction is the score
+    uint32_t PQ;              // query planes (rescore = 1)
+    const uint32_t* qwords;   // [Q][PQ][2W] (rescore = 1)
+    const float* qcoef;       // [Q][PQ+1] (rescore = 1)
+    const float* lut;         // [Q][8W][256] (rescore = 2)
     float margin;
     CandList out;
     uint32_t p_begin, p_end;

@@ -183,72 +183,69 @@ def _halves_to_float(bits):
     return np.asarray(bits, dtype=np.uint16).view(np.float16).astype(np.float64)
 
 
+def _emulated_contraction(A, start, q, bits, parts, copy=0):
+    """What the kernel's MFMAs add up for query q against one plane of item bits: lane group g takes bits
+    10 + t and 26 + t of each 32-bit part rotated left by 4g, as halves worth 0 or val_t."""
+    val = np.array([2.0 ** -14, 2.0 ** -13, 2.0 ** -11, 2.0 ** -7])
+    got = 0.0
+    for part in range(parts):
+        b32 = bits[32 * part: 32 * part + 32]
+        for g in range(4):
+            for e in range(8):
+                t, h = e >> 1, e & 1
+                got += A[q // 16, copy, part, 16 * g + q % 16, e] * (b32[(10 + 16 * h + t - 4 * g) % 32] * val[t])
+    return got
+
+
 @pytest.mark.parametrize("dim,P,Pq,Q,dyadic", [(64, 3, 3, 16, False), (64, 2, 3, 5, True), (128, 4, 4, 33, False),
                                                 (128, 3, 4, 20, True), (64, 1, 1, 1, False)])
 def test_matrix_core_operands_reproduce_the_score(lib, dim, P, Pq, Q, dyadic):
-    """Emulates the kernel's side of the contract on the CPU: item bits become halves whose only set
-    bit is bit 10 + t (lane group g takes bits 10 + t and 26 + t of the part rotated left by 4g),
-    every lane multiplies its eight slots, and the sum over lanes, parts, terms and plane copies plus
-    the start value must equal qhat . rho (times the item-plane weights in the dyadic case), to the
-    22 bits the two halves carry -- exactly, for dyadic queries."""
+    """Emulates the kernel's side of the contract on the CPU: the sum over lanes, parts and plane copies
+    plus the start value must equal qhat . rho (times the item-plane weights in the dyadic case) --
+    exactly for dyadic queries, within the reported filter margin for general scales."""
     rng = np.random.default_rng(dim + P + Q)
     W = dim // 64
     qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
     qs = None if dyadic else rng.uniform(0.05, 1.0, size=(Q, Pq)).astype(np.float32)
-    halves, unscale, start = rbe.rbe_debug_batch_operands(qp, qs, dim, P, dyadic)
-    tiles, terms, copies, parts = halves.shape[:4]
-    assert (tiles, terms, copies, parts) == ((Q + 15) // 16, 1 if dyadic else 2, P if dyadic else 1, 2 * W)
-    A = _halves_to_float(halves)                                  # [tile][term][copy][part][lane][8]
+    halves, unscale, start, margin = rbe.rbe_debug_batch_operands(qp, qs, dim, P, dyadic)
+    tiles, copies, parts = halves.shape[:3]
+    assert (tiles, copies, parts) == ((Q + 15) // 16, P if dyadic else 1, 2 * W)
+    assert (margin == 0.0) if dyadic else (margin > 0.0)
+    A = _halves_to_float(halves)                                  # [tile][copy][part][lane][8]
     coef = np.array([2.0 ** -i for i in range(Pq)]) if dyadic else None
-    val = np.array([2.0 ** -14, 2.0 ** -13, 2.0 ** -11, 2.0 ** -7])
     n_items = 7
     item_planes = rng.integers(0, 2**64, size=(P, n_items, W), dtype=np.uint64)
     for q in range(Q):
         c = coef if dyadic else qs[q].astype(np.float64)
         qbits = ((qp[q][:, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)   # [Pq][W][64]
         qhat = (c[:, None, None] * (2 * qbits - 1)).sum(axis=0).reshape(dim)
-        t_, row = q // 16, q % 16
         for z in range(n_items):
+            want_all, got_all = 0.0, float(start[q])
             for j in range(P):
                 word_bits = ((item_planes[j, z][:, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.int64).reshape(dim)
                 want = float(qhat @ (2 * word_bits - 1))
-                if not dyadic:
-                    got = float(start[q])
-                    for part in range(parts):
-                        bits32 = word_bits[32 * part: 32 * part + 32]
-                        for g in range(4):
-                            for e in range(8):
-                                t, h = e >> 1, e & 1
-                                b = bits32[(10 + 16 * h + t - 4 * g) % 32]      # what the rotate + AND picks
-                                for term in range(terms):
-                                    got += A[t_, term, 0, part, 16 * g + row, e] * (b * val[t])
-                    got *= float(unscale[q])
-                    assert abs(got - want) <= 2.0 ** -20 * np.abs(qhat).sum() + 1e-12, (q, z, j, got, want)
+                if dyadic:
+                    want_all += 2.0 ** -j * want
+                    got_all += _emulated_contraction(A, start, q, word_bits, parts, copy=j)
+                else:
+                    got = (float(start[q]) + _emulated_contraction(A, start, q, word_bits, parts)) * float(unscale[q])
+                    assert abs(got - want) <= margin * float(unscale[q]), (q, z, j, got, want)
             if dyadic:
-                want_all = 0.0
-                got = float(start[q])
-                for j in range(P):
-                    word_bits = ((item_planes[j, z][:, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.int64).reshape(dim)
-                    want_all += 2.0 ** -j * float(qhat @ (2 * word_bits - 1))
-                    for part in range(parts):
-                        bits32 = word_bits[32 * part: 32 * part + 32]
-                        for g in range(4):
-                            for e in range(8):
-                                t, h = e >> 1, e & 1
-                                got += A[t_, 0, j, part, 16 * g + row, e] * (bits32[(10 + 16 * h + t - 4 * g) % 32] * val[t])
-                assert got * float(unscale[q]) == want_all, (q, z, got, want_all)
+                assert got_all * float(unscale[q]) == want_all, (q, z, got_all, want_all)
 
 
 def test_matrix_core_operands_stay_in_half_range(lib):
     """2 v / val_t is below 2^15 and the scaled query's largest component is at least 0.5: no
-    overflow to infinity, and the hi halves are normal numbers wherever the component is not tiny."""
+    overflow to infinity, the halves are normal numbers or zero (never subnormal: the margin must not
+    depend on how the matrix cores treat those)."""
     rng = np.random.default_rng(5)
     qp = rng.integers(0, 2**64, size=(64, 4, 2), dtype=np.uint64)
     qs = rng.uniform(1e-3, 50.0, size=(64, 4)).astype(np.float32)
-    halves, unscale, start = rbe.rbe_debug_batch_operands(qp, qs, 128, 4, False)
+    halves, unscale, start, _ = rbe.rbe_debug_batch_operands(qp, qs, 128, 4, False)
     A = _halves_to_float(halves)
     assert np.isfinite(A).all() and np.abs(A).max() < 2.0 ** 15
-    assert (np.abs(A[:, 0]).reshape(4, -1).max(axis=1) >= 2.0 ** 7).all()
+    assert (np.abs(A).reshape(4, -1).max(axis=1) >= 2.0 ** 7).all()
+    assert ((A == 0) | (np.abs(A) >= 2.0 ** -14)).all()
     assert np.isfinite(start).all() and (unscale > 0).all()
     lg = np.log2(unscale.astype(np.float64))
     assert np.array_equal(lg, np.round(lg))       # powers of two
@@ -264,35 +261,38 @@ def test_scan_kernels_have_no_lane_peeling_loops():
     assert _check_isa.main() == 0
 
 
-def test_matrix_core_filter_operands_stay_within_their_margin(lib):
-    """Hi-half-only operands (binary queries, general scales): the emulated contraction may differ from
-    qhat . rho by at most the margin the host reports (per unit of item scale), and the margin is a small
-    fraction of the query's mass -- otherwise the filter would pass far more than the survivors."""
+@pytest.mark.parametrize("kind", ["binary", "fp32", "fp32_wide_range"])
+def test_matrix_core_filter_operands_stay_within_their_margin(lib, kind):
+    """General scales: the emulated contraction may differ from q . rho by at most the margin the host
+    reports (per unit of item scale), and the margin is a small fraction of the query's mass -- otherwise
+    the filter would pass far more than the survivors.  fp32 queries (hybrid scoring) included, also with
+    components so small that their halves would be subnormal (those are dropped and counted as lost)."""
     rng = np.random.default_rng(321)
     dim, P, Pq, Q = 128, 3, 4, 19
     W = dim // 64
-    qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
-    qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
-    halves, unscale, start, margin = rbe.rbe_debug_batch_operands(qp, qs, dim, P, False, hi_only=True)
-    assert halves.shape[:4] == ((Q + 15) // 16, 1, 1, 2 * W) and margin > 0
+    if kind == "binary":
+        qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
+        qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
+        halves, unscale, start, margin = rbe.rbe_debug_batch_operands(qp, qs, dim, P, False)
+        qbits = ((qp[:, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
+        qhat = (qs.astype(np.float64)[:, :, None, None] * (2 * qbits - 1)).sum(axis=1).reshape(Q, dim)
+    else:
+        qf = rng.standard_normal((Q, dim)).astype(np.float32)
+        if kind == "fp32_wide_range":
+            qf *= (2.0 ** rng.integers(-40, 1, size=(Q, dim))).astype(np.float32)
+        halves, unscale, start, margin = rbe.rbe_debug_batch_operands(None, None, dim, P, False, q_float=qf)
+        qhat = qf.astype(np.float64)
+    assert halves.shape[:3] == ((Q + 15) // 16, 1, 2 * W) and margin > 0
     A = _halves_to_float(halves)
-    val = np.array([2.0 ** -14, 2.0 ** -13, 2.0 ** -11, 2.0 ** -7])
+    assert ((A == 0) | (np.abs(A) >= 2.0 ** -14)).all()
     worst = 0.0
     for q in range(Q):
-        qbits = ((qp[q][:, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
-        qhat = (qs[q].astype(np.float64)[:, None, None] * (2 * qbits - 1)).sum(axis=0).reshape(dim)
-        v = qhat / float(unscale[q])                     # the scaled query the operands describe
+        v = qhat[q] / float(unscale[q])                  # the scaled query the operands describe
         assert 0.5 <= np.abs(v).max() < 1.0
         assert margin <= 2.0 ** -9 * np.abs(v).sum() + 2.0 ** -9       # a few 1e-4 of the query's mass
         for _ in range(40):
             bits = rng.integers(0, 2, size=dim)
-            got = float(start[q])
-            for part in range(2 * W):
-                b32 = bits[32 * part: 32 * part + 32]
-                for g in range(4):
-                    for e in range(8):
-                        t, h = e >> 1, e & 1
-                        got += A[q // 16, 0, 0, part, 16 * g + q % 16, e] * (b32[(10 + 16 * h + t - 4 * g) % 32] * val[t])
+            got = float(start[q]) + _emulated_contraction(A, start, q, bits, 2 * W)
             worst = max(worst, abs(got - float(v @ (2 * bits - 1))))
     assert worst <= margin, (worst, margin)
-    assert worst > 0                                     # the lo halves really are missing
+    assert worst > 0                                     # the halves really are roundings

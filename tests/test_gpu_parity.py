@@ -784,7 +784,7 @@ def test_read_yardstick_touches_every_vector(n_vec):
 @pytest.mark.parametrize("N,d,P,Q,k", [(150_001, 64, 3, 16, 500), (60_000, 128, 4, 5, 300), (80_000, 64, 2, 40, 100),
                                        (1, 64, 1, 4, 1)])
 def test_float_query_batches_use_the_matrix_cores_and_match_the_table_path(N, d, P, Q, k):
-    """Three or more fp32 queries per call are scored as one dense contraction (the query itself is the
+    """Three or more fp32 queries per call are filtered by one dense contraction (the query itself is the
     left operand) instead of one table pass per query; both must pass the oracle's hybrid score."""
     c = rbe_synth.centres_numpy(32, d)
     x = rbe_synth.vectors_numpy(N, c, 0.3, seed=60 + N % 97)
@@ -798,7 +798,21 @@ def test_float_query_batches_use_the_matrix_cores_and_match_the_table_path(N, d,
     for i in range(Q):
         check_topk_float(planes, scales, q[i], k, ids_m[i], sc_m[i])
         check_topk_float(planes, scales, q[i], k, ids_t[i], sc_t[i])
-    np.testing.assert_allclose(sc_m, sc_t, rtol=1e-5)
+    # the contraction only filters; what passes is scored from the byte tables, so both paths agree bit for bit
+    np.testing.assert_array_equal(sc_m, sc_t)
+    np.testing.assert_array_equal(ids_m, ids_t)
+    # components 2^-30 of the largest one (their operand halves would be subnormal) and a zero query
+    q2 = q.copy()
+    q2[1, ::3] *= 2.0 ** -30
+    q2[2] = 0.0
+    rbe.rbe_debug_set_batch_path(ix, 0)
+    ids_m, sc_m = rbe.rbe_search_float(ix, q2, k)
+    rbe.rbe_debug_set_batch_path(ix, 1)
+    ids_t, sc_t = rbe.rbe_search_float(ix, q2, k)
+    np.testing.assert_array_equal(sc_m, sc_t)
+    np.testing.assert_array_equal(ids_m, ids_t)
+    for i in range(min(Q, 3)):
+        check_topk_float(planes, scales, q2[i], k, ids_m[i], sc_m[i])
     rbe.rbe_free(ix)
     # dyadic index: the one-half kernels cannot carry a full-precision query; the table path serves any batch
     rng = np.random.default_rng(62)
