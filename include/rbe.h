@@ -207,9 +207,11 @@ int rbe_search(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
  * stored as fp32, added in fp32 in byte order), then fp32 fused multiply-adds over j.
  * For RBE_DYADIC indexes a_j = 2^-j (times the stored inverse norm with RBE_COSINE).
  * With 3 or more queries per call on an index with general scales (dim <= 128) the
- * batch is scored on the matrix cores instead, exactly as rbe_search does with the
- * reconstructed binary queries (q itself is the left operand, split in two halves),
- * and the corpus is read once per 32 queries; otherwise it is read once per query.
+ * pairs are first filtered on the matrix cores, exactly as rbe_search does with the
+ * reconstructed binary queries (q itself, in half precision, is the left operand),
+ * what can reach the threshold is scored through the tables as above, so the results
+ * do not depend on the number of queries per call, and the corpus is read once per
+ * 32 queries; otherwise it is read once per query.
  *   q: [n_queries][dim] float (host), finite.  Other arguments as rbe_search.
  * Only RBE_SELECT_EXACT is built.                                               */
 int rbe_search_float(rbe_index *ix, const float *q, uint32_t n_queries, uint32_t k,
