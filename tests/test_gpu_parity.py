@@ -910,3 +910,51 @@ def test_cancelling_query_planes_in_a_batch(d):
         np.testing.assert_array_equal(sc[q], s1[0]); np.testing.assert_array_equal(ids[q], i1[0])
     check_batch(planes, scales, qp, qs, k, ids, sc)
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ several indexes, streams and host threads
+def test_two_indexes_searched_from_two_threads_on_their_own_streams():
+    """An index is used by one thread at a time, but different indexes are independent: two host threads,
+    each with its own index (different shapes) and its own stream (default priority), run searches of
+    varying batch size, k and selection mode at the same time; every result against the oracle."""
+    import threading
+    import torch
+    rng = np.random.default_rng(77)
+    cases = [(90_001, 64, 3), (40_003, 128, 4)]
+    data, errors = [], []
+    for N, d, P in cases:
+        planes, scales = random_corpus(rng, N, d, P)
+        data.append((planes, scales, rbe.rbe_load_corpus(planes, scales), torch.cuda.Stream()))
+    schedule = [(1, 100, rbe.RBE_SELECT_EXACT), (16, 1000, rbe.RBE_SELECT_EXACT), (3, 10, rbe.RBE_SELECT_NEARLOSSLESS),
+                (40, 50, rbe.RBE_SELECT_EXACT), (2, 4096, rbe.RBE_SELECT_EXACT), (9, 300, rbe.RBE_SELECT_EXACT),
+                (1, 1000, rbe.RBE_SELECT_NEARLOSSLESS_Q2), (5, 7, rbe.RBE_SELECT_EXACT)]
+    results = [[], []]
+
+    def worker(t):
+        try:
+            planes, scales, ix, stream = data[t]
+            r = np.random.default_rng(100 + t)
+            for Q, k, mode in schedule:
+                qp, qs = random_queries(r, Q, 64 * planes.shape[2], 3)
+                ids, sc = rbe.rbe_search(ix, qp, qs, k, mode=mode, group_size_I=4, stream=stream)
+                results[t].append((qp, qs, k, mode, ids, sc))
+        except Exception as e:      # noqa: BLE001 - reported by the main thread
+            errors.append((t, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    for t in range(2):
+        planes, scales, ix, _ = data[t]
+        assert len(results[t]) == len(schedule)
+        for qp, qs, k, mode, ids, sc in results[t]:
+            if mode == rbe.RBE_SELECT_EXACT:
+                check_batch(planes, scales, qp, qs, k, ids, sc)
+            else:
+                for q in range(qp.shape[0]):
+                    check_nearlossless(planes, scales, qp[q], qs[q], k, 4, ids[q], sc[q],
+                                       queue_len=2 if mode == rbe.RBE_SELECT_NEARLOSSLESS_Q2 else 1)
+        rbe.rbe_free(ix)
