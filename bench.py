@@ -304,8 +304,7 @@ def main():
             # dense contraction [B x d] . [d x items] per corpus plane (one fp16 half per query component:
             # the contraction filters, survivors are rescored bitwise); padding to 16 queries adds to what is issued
             flops = 2.0 * B * b_items * d * P
-            terms = 1
-            issued = 2.0 * 16 * -(-B // 16) * b_items * d * P * terms
+            issued = 2.0 * 16 * -(-B // 16) * b_items * d * P
             ach = flops / (b_scan * 1e-3) / 1e12
             roof = {"kernel": "scan_batch_mfma (finest level)", "bound": "mfma", "achieved": ach,
                     "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_F16_PEAK_TFLOPS,

@@ -361,7 +361,7 @@ struct BatchArgs {
     const char* tiles;
     Layout layout;
     uint64_t n_items;
-    const uint32_t* a_ops;    // [query tile][term][plane copy][32-dim part][lane][4 dwords = 8 halves]: the scaled
+    const uint32_t* a_ops;    // [query tile][plane copy][32-dim part][lane][4 dwords = 8 halves]: the scaled
                               // reconstructed queries in the A-operand order of v_mfma_f32_16x16x32_f16,
                               // dimensions permuted and weighted to match the kernel's B operand
     const float* q_unscale;   // [Q] 2^-k: what a score formed from the scaled query is multiplied by
@@ -373,7 +373,7 @@ struct BatchArgs {
     // hi-half filter + exact rescoring (general scales): what the one-query scan scores with -- the staged binary
     // queries of the XOR/popcount scan (rescore = 1) or the byte tables of fp32 queries (rescore = 2) -- and the
     // bound on |true - filter score| per unit of sum_j a_j[item], in the scaled domain
-    uint32_t rescore;         // 0: a_ops holds hi + lo halves (or one exact half) and the contraction is the score
+    uint32_t rescore;         // 0: a_ops is exact (dyadic modes) and the contraction is the score
     uint32_t PQ;              // query planes (rescore = 1)
     const uint32_t* qwords;   // [Q][PQ][2W] (rescore = 1)
     const float* qcoef;       // [Q][PQ+1] (rescore = 1)
