@@ -228,7 +228,9 @@ typedef struct rbe_search_stats {
     uint32_t n_levels;        /* scan+select rounds of the last search           */
     uint32_t fallback;        /* 1 if the bounded-segment slow path was taken    */
     uint32_t grid_blocks;     /* workgroups of the widest scan launch            */
-    uint32_t reserved;
+    uint32_t deep_rows;       /* one query, exact mode: rows of 256 items whose
+                                 last plane the last scan had to read (the others
+                                 were ruled out by the other planes and the scales)  */
     uint64_t items_scanned[RBE_MAX_LEVELS];   /* items read by each scan         */
     uint64_t candidates_max[RBE_MAX_LEVELS];  /* largest per-query candidate
                                                  count handed to each select     */
@@ -262,6 +264,26 @@ int rbe_debug_popcounts(rbe_index *ix, const uint64_t *q_planes, uint32_t q_n_pl
 int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
                      uint32_t q_n_planes, uint64_t first_item, uint64_t count,
                      float *out, void *hip_stream);
+
+/* One query per call, exact mode, 2 or more planes: the last (largest) level of
+ * the search reads plane 0 and the scales of every item but the other planes only
+ * of rows in which some item's upper bound -- plane 0's exact term plus the
+ * largest value the remaining planes could add -- reaches the threshold; such rows
+ * are then scored in full, so the results are those of the plain scan bit for bit.
+ * enabled = 0 switches it off (every plane of every item is read); default 1.    */
+int rbe_debug_set_progressive(rbe_index *ix, int enabled);
+
+/* The mass of one query as the progressive scan uses it (pure host function, for
+ * tests).  With qhat = sum_i c_i rho_i (rho = +-1 per bit), M = sum_d |qhat_d| is the
+ * largest value sum_i c_i (rho_i . rho) can take over all sign vectors rho.
+ * dyadic = 0: mass_out[0] >= M, larger by a few 2^-20 of dim * sum_i |c_i| (rounding
+ * allowance), mass_out[1] = 2^-19 mass_out[0].  dyadic = 1 (c_i = 2^-i, q_scales not
+ * read): the bits of mass_out[0] are the integer h_min = (dim (2^Pq - 1) - M') / 2 with
+ * M' = 2^(Pq-1) M, the least weighted mismatch count sum_i 2^(Pq-1-i) popcount(Q_i XOR K)
+ * any plane K can have; mass_out[1] = 0.
+ *   q_planes [q_n_planes][dim/64], q_scales [q_n_planes], mass_out [2]: host.    */
+int rbe_debug_query_mass(const uint64_t *q_planes, const float *q_scales, uint32_t q_n_planes,
+                         uint32_t dim, uint32_t dyadic, float *mass_out);
 
 /* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 8
  * queries per call on, dim <= 128), 1 = always the XOR/popcount kernel, 2 = the

@@ -40,7 +40,7 @@ class rbe_search_stats(ctypes.Structure):
         ("n_levels", ctypes.c_uint32),
         ("fallback", ctypes.c_uint32),
         ("grid_blocks", ctypes.c_uint32),
-        ("reserved", ctypes.c_uint32),
+        ("deep_rows", ctypes.c_uint32),
         ("items_scanned", ctypes.c_uint64 * RBE_MAX_LEVELS),
         ("candidates_max", ctypes.c_uint64 * RBE_MAX_LEVELS),
         ("scan_ms", ctypes.c_float * RBE_MAX_LEVELS),
@@ -73,6 +73,8 @@ PROTOTYPES = {
     "rbe_debug_tile_to_phys": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_phys_to_tile": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_set_batch_path": (_i32, [_vp, _i32]),
+    "rbe_debug_set_progressive": (_i32, [_vp, _i32]),
+    "rbe_debug_query_mass": (_i32, [_vp, _vp, _u32, _u32, _u32, _vp]),
     "rbe_debug_exact_plan": (_i32, [_u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_debug_batch_operands": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
@@ -335,7 +337,7 @@ def rbe_get_search_stats(ix: Index) -> dict:
     _check(load_library().rbe_get_search_stats(ix.handle, ctypes.byref(st)))
     n = st.n_levels
     return {
-        "n_levels": n, "fallback": st.fallback, "grid_blocks": st.grid_blocks,
+        "n_levels": n, "fallback": st.fallback, "grid_blocks": st.grid_blocks, "deep_rows": st.deep_rows,
         "items_scanned": list(st.items_scanned)[:n], "candidates_max": list(st.candidates_max)[:n],
         "scan_ms": list(st.scan_ms)[:n], "select_ms": list(st.select_ms)[:n],
         "total_gpu_ms": st.total_gpu_ms,
@@ -388,6 +390,24 @@ def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic
     tiles, copies, parts = (int(x) for x in shape[:3])
     out = halves[:tiles * copies * parts * 64 * 8].reshape(tiles, copies, parts, 64, 8)
     return out, unscale, start, float(shape[3:4].view(np.float32)[0])
+
+
+def rbe_debug_query_mass(q_planes, q_scales, dim: int, dyadic: bool = False):
+    """Mass of one query ([Pq][W] planes, [Pq] scales) as the progressive scan uses it (host only):
+    (x, y) floats for general scales, (h_min, 0) with h_min an int for a dyadic index."""
+    q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
+    if q_scales is not None:
+        q_scales = np.ascontiguousarray(q_scales, dtype=np.float32)
+    out = np.zeros(2, dtype=np.float32)
+    _check(load_library().rbe_debug_query_mass(q_planes.ctypes.data, None if q_scales is None else q_scales.ctypes.data,
+                                               q_planes.shape[0], dim, 1 if dyadic else 0, out.ctypes.data))
+    if dyadic:
+        return int(out[:1].view(np.uint32)[0]), 0.0
+    return float(out[0]), float(out[1])
+
+
+def rbe_debug_set_progressive(ix: Index, enabled: bool):
+    _check(load_library().rbe_debug_set_progressive(ix.handle, 1 if enabled else 0))
 
 
 def rbe_debug_set_batch_path(ix: Index, path: int):

@@ -85,6 +85,7 @@ struct rbe_index {
     float* d_unscale = nullptr;     // [Q]
     float* h_unscale = nullptr;
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
+    int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
     float* d_lut = nullptr;         // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
     float* h_lut = nullptr;
@@ -182,7 +183,7 @@ int ensure_fixed(rbe_index* ix)
     HIP_TRY(hipMalloc(&ix->d_tau, Q * sizeof(uint64_t)));
     HIP_TRY(hipMalloc(&ix->d_kmax, Q * sizeof(uint64_t)));
     // query words and coefficients share one block (coefficients at a fixed offset) so that one copy stages both
-    const size_t words_bytes = Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t), coef_bytes = Q * (RBE_MAX_PLANES + 1) * sizeof(float);
+    const size_t words_bytes = Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t), coef_bytes = Q * (RBE_MAX_PLANES + 1 + 2) * sizeof(float);
     HIP_TRY(hipMalloc(&ix->d_qwords, words_bytes + coef_bytes));
     HIP_TRY(hipHostMalloc(&ix->h_qwords, words_bytes + coef_bytes, hipHostMallocDefault));
     ix->d_qcoef = reinterpret_cast<float*>(reinterpret_cast<char*>(ix->d_qwords) + words_bytes);
@@ -213,7 +214,43 @@ int ensure_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
     return RBE_OK;
 }
 
-// Stage one batch of queries: words as 32-bit halves, coefficients (-2 c_i ..., dim * sum c_i).
+// Mass of one query, from which a scan bounds the contribution of planes it has not read (bound_item).  With
+// qhat = sum_i c_i rho_i, M = sum_d |qhat_d| is the largest inner sum any plane can reach (attained by the plane
+// whose signs are those of qhat).  General scales: out = {x, 2^-19 x}, x >= (M + 2^-20 d sum_i |c_i|) (1 + 2^-20):
+// the second term covers the rounding of the inner sums as the kernel forms them (magnitudes up to
+// 3 d sum_i |c_i|), the factor the rounding of the scale sums.  Dyadic modes, in units of 2^-(PQ-1): M is an
+// integer, a plane's weighted mismatch count is at least h_min = (d (2^PQ - 1) - M) / 2, and out[0] carries h_min
+// as an integer (out[1] = 0).
+void query_mass(const uint64_t* planes /* [PQ][W] */, const float* scales /* [PQ] or null */, uint32_t PQ, uint32_t dim,
+                bool dyadic, float* out)
+{
+    const uint32_t W = dim / 64;
+    double M = 0.0, B = 0.0;
+    for (uint32_t i = 0; i < PQ; ++i) B += std::fabs(dyadic ? std::ldexp(1.0, (int)(PQ - 1 - i)) : (double)scales[i]);
+    B *= dim;
+    for (uint32_t d = 0; d < dim; ++d) {
+        double v = 0.0;
+        for (uint32_t i = 0; i < PQ; ++i) {
+            const double c = dyadic ? std::ldexp(1.0, (int)(PQ - 1 - i)) : (double)scales[i];
+            v += ((planes[(size_t)i * W + d / 64] >> (d % 64)) & 1ull) ? c : -c;
+        }
+        M += std::fabs(v);
+    }
+    if (dyadic) {
+        const uint32_t h_min = (uint32_t)((dim * ((1u << PQ) - 1u) - (uint32_t)M) / 2u);
+        std::memcpy(&out[0], &h_min, sizeof(float));
+        out[1] = 0.0f;
+    } else {
+        const double x = (M + std::ldexp(B, -20)) * (1.0 + std::ldexp(1.0, -20));
+        float xf = (float)x;
+        if ((double)xf < x) xf = std::nextafter(xf, INFINITY);
+        out[0] = xf;
+        out[1] = std::ldexp(xf, -19);
+    }
+}
+
+// Stage one batch of queries: words as 32-bit halves, coefficients (-2 c_i ..., dim * sum c_i), and after the
+// coefficients of all queries their masses [Q][2].
 int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ, hipStream_t st)
 {
     const uint32_t W = ix->W;
@@ -240,8 +277,10 @@ int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales
             sum += c;
         }
         ix->h_qcoef[(size_t)q * (PQ + 1) + PQ] = (float)ix->dim * sum;
+        query_mass(q_planes + (size_t)q * PQ * W, q_scales ? q_scales + (size_t)q * PQ : nullptr, PQ, ix->dim, dyadic,
+                   ix->h_qcoef + (size_t)Q * (PQ + 1) + 2 * (size_t)q);
     }
-    const size_t staged = (size_t)((char*)ix->h_qcoef - (char*)ix->h_qwords) + (size_t)Q * (PQ + 1) * sizeof(float);
+    const size_t staged = (size_t)((char*)ix->h_qcoef - (char*)ix->h_qwords) + (size_t)Q * (PQ + 1 + 2) * sizeof(float);
     HIP_TRY(hipMemcpyAsync(ix->d_qwords, ix->h_qwords, staged, hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
@@ -811,7 +850,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
 {
     rbe_index* ix = c.ix;
     if (r.end <= r.begin) return RBE_OK;
-    const KernelSel sel{ix->P, c.PQ, ix->mode, c.Q == 1, c.qlen};
+    KernelSel sel{ix->P, c.PQ, ix->mode, c.Q == 1, c.qlen};
     const CandList out{ix->d_cand, ix->d_count, ix->d_kmax, c.cap};
     uint32_t grid = 0;
     hipError_t e;
@@ -847,6 +886,9 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = c.Q;
         sa.tau = ix->d_tau; sa.out = out;
         sa.p_begin = r.begin; sa.p_end = r.end;
+        // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
+        sel.progressive = c.Q == 1 && !dense && ix->P >= 2 && ix->progressive != 0;
+        sa.deep_rows = ix->d_status + 1;
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
         sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);
@@ -938,7 +980,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         if (!fallback) {
             if (prof) HIP_TRY(hipEventRecord(ix->ev[0], c.st));
             for (size_t l = 0; l < plan.size(); ++l) {
-                rc = run_round(c, plan[l], l + 1 == plan.size(), (uint32_t)l, prof, l + 1 != plan.size());
+                rc = run_round(c, plan[l], l + 1 == plan.size(), (uint32_t)l, prof, l + 1 != plan.size() || l == 0);
                 if (rc) return rc;
                 ix->stats.items_scanned[l] = (uint64_t)(plan[l].end - plan[l].begin) *
                                              (mode == RBE_SELECT_EXACT ? (uint64_t)kTileItems : (uint64_t)c.I * kRow);
@@ -950,7 +992,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
             const uint32_t seg = std::max<uint32_t>(1u, (c.cap - k) / per_unit);
             for (uint64_t u0 = 0; u0 < n_units; u0 += seg) {
                 const uint32_t u1 = (uint32_t)std::min<uint64_t>(n_units, u0 + seg);
-                rc = run_round(c, Round{(uint32_t)u0, u1, 1, 0}, u1 == n_units, 0, false);
+                rc = run_round(c, Round{(uint32_t)u0, u1, 1, 0}, u1 == n_units, 0, false, u0 == 0);
                 if (rc) return rc;
             }
             ix->stats.n_levels = 1;
@@ -967,6 +1009,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         fallback = true;  // a level produced more survivors than the list holds: redo on the slow path
     }
 
+    ix->stats.deep_rows = ix->h_status[1];
     if (!fallback) {
         for (uint32_t l = 0; l < ix->stats.n_levels; ++l) {
             uint32_t mx = 0;
@@ -1072,6 +1115,25 @@ int rbe_debug_scores_float(rbe_index* ix, const float* q, uint64_t first_item, u
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(d_out);
     if (e != hipSuccess) { set_error("rbe_debug_scores_float: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    return RBE_OK;
+}
+
+int rbe_debug_query_mass(const uint64_t* q_planes, const float* q_scales, uint32_t q_n_planes, uint32_t dim,
+                         uint32_t dyadic, float* mass_out)
+{
+    ARG_CHECK(q_planes && mass_out && (dyadic || q_scales), "NULL argument");
+    ARG_CHECK(dim >= 64 && dim <= 256 && dim % 64 == 0 && dim != 192, "dim must be 64, 128 or 256");
+    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes out of range");
+    if (!dyadic)
+        for (uint32_t i = 0; i < q_n_planes; ++i) ARG_CHECK(std::isfinite(q_scales[i]), "q_scales[%u] is not finite", i);
+    query_mass(q_planes, dyadic ? nullptr : q_scales, q_n_planes, dim, dyadic != 0, mass_out);
+    return RBE_OK;
+}
+
+int rbe_debug_set_progressive(rbe_index* ix, int enabled)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    ix->progressive = enabled ? 1 : 0;
     return RBE_OK;
 }
 

@@ -14,6 +14,7 @@ struct KernelSel {
     int mode;         // kModeScaled / kModeDyadicNorm / kModeDyadic
     bool single;      // one query per call
     uint32_t qlen = 1;   // near-lossless mode: length of the per-group priority queue (1 or 2)
+    bool progressive = false;   // exact mode, one query, P >= 2: read planes 1.. only where plane 0 cannot rule a row out
 };
 
 // Grid = min(units, n_cu * per_cu); per_cu == 0 means "as many workgroups as are

@@ -95,13 +95,13 @@ __device__ __forceinline__ uint32_t lane_item(int lane, int m)
     return (uint32_t)(m * 64 + lane);
 }
 
-// Loads the wave's row (`wave` = 0..3) of the tile that starts at `tile`.
-template <int W, int P, int S>
-__device__ __forceinline__ void load_row(RowRegs<W, P, S>& r, const char* __restrict__ tile, int wave, int lane)
+// Loads planes [J0, J1) of the wave's row (`wave` = 0..3) of the tile that starts at `tile`.
+template <int W, int P, int S, int J0, int J1>
+__device__ __forceinline__ void load_row_planes(RowRegs<W, P, S>& r, const char* __restrict__ tile, int wave, int lane)
 {
     const TileGeom g{(uint32_t)W, (uint32_t)P, (uint32_t)S};
 #pragma unroll
-    for (int j = 0; j < P; ++j) {
+    for (int j = J0; j < J1; ++j) {
         const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)wave * kRow * W;
         if (W == 1) {
 #pragma unroll
@@ -123,6 +123,13 @@ __device__ __forceinline__ void load_row(RowRegs<W, P, S>& r, const char* __rest
             }
         }
     }
+}
+
+// ... and its scales.
+template <int W, int P, int S>
+__device__ __forceinline__ void load_row_scales(RowRegs<W, P, S>& r, const char* __restrict__ tile, int wave, int lane)
+{
+    const TileGeom g{(uint32_t)W, (uint32_t)P, (uint32_t)S};
 #pragma unroll
     for (int j = 0; j < S; ++j) {
         const float* sj = reinterpret_cast<const float*>(tile + g.scales_offset()) + j * kTileItems + wave * kRow;
@@ -137,6 +144,14 @@ __device__ __forceinline__ void load_row(RowRegs<W, P, S>& r, const char* __rest
             for (int m = 0; m < kItemsPerLane; ++m) r.a[j][m] = __builtin_nontemporal_load(sj + m * 64 + lane);
         }
     }
+}
+
+// The whole row.
+template <int W, int P, int S>
+__device__ __forceinline__ void load_row(RowRegs<W, P, S>& r, const char* __restrict__ tile, int wave, int lane)
+{
+    load_row_planes<W, P, S, 0, P>(r, tile, wave, lane);
+    load_row_scales<W, P, S>(r, tile, wave, lane);
 }
 
 // Score of the lane's item m against one query.  The popcounts are exact in every mode.
@@ -182,6 +197,67 @@ __device__ __forceinline__ float score_item(const RowRegs<W, P, scale_arrays(MOD
             }
             H = (H << 1) + h_j;
         }
+        constexpr int kAll = 64 * W * ((1 << P) - 1) * ((1 << PQ) - 1);
+        constexpr float kScale = 1.0f / (float)(1 << (P + PQ - 2));
+        const float f = (float)(kAll - 2 * (int)H) * kScale;   // exact
+        return MODE == kModeDyadicNorm ? f * r.a[0][m] : f;
+    }
+}
+
+// Upper bound on score_item from planes 0 .. F-1 alone (1 <= F < P): whatever the other planes hold, the inner
+// sum of plane j lies in [-M, M] with M = sum_d |sum_i c_i rho_i[d]|, the query's mass (the sum is qhat . rho_j
+// and rho_j is a sign vector), and the scales are not negative.
+//
+// kModeScaled:  the first F steps exactly as score_item takes them, then  + (a_F + .. + a_{P-1}) * mass.x,  plus
+//               (a_0 + .. + a_{P-1}) * mass.y for the roundings on either side.  The host supplies mass.x >= M
+//               plus the rounding of the inner sums (which happen at magnitude d sum_i |c_i|, possibly far above
+//               M), and mass.y = 2^-19 mass.x.
+// Dyadic modes: integers.  Plane j contributes 2^(P-1-j) h_j to H and h_j >= h_min (the mismatch count of the
+//               best possible plane), so H >= sum_{j<F} 2^(P-1-j) h_j + (2^(P-F) - 1) h_min; mass.x carries
+//               h_min as an integer.  The conversion and the item's scale are monotone, so the bound is exact.
+struct QueryMass { float x, y; };
+
+template <int W, int P, int PQ, int MODE, int F>
+__device__ __forceinline__ float bound_item(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m,
+                                            const QueryRegs<W, PQ>& q, const QueryMass& mass)
+{
+    static_assert(F >= 1 && F < P, "a bound needs planes to compute and planes to skip");
+    if (MODE == kModeScaled) {
+        float s = 0.0f;
+#pragma unroll
+        for (int j = 0; j < F; ++j) {
+            float t = q.bias;
+#pragma unroll
+            for (int i = 0; i < PQ; ++i) {
+                uint32_t pc = 0;
+#pragma unroll
+                for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(r.w[j][m][h] ^ q.w[i][h]);
+                t = __fmaf_rn(q.m2c[i], (float)pc, t);
+            }
+            s = __fmaf_rn(r.a[j][m], t, s);
+        }
+        float tail = r.a[F][m];
+#pragma unroll
+        for (int j = F + 1; j < P; ++j) tail += r.a[j][m];
+        float all = tail;
+#pragma unroll
+        for (int j = 0; j < F; ++j) all += r.a[j][m];
+        return __fmaf_rn(all, mass.y, __fmaf_rn(tail, mass.x, s));
+    } else {
+        uint32_t H = 0;
+#pragma unroll
+        for (int j = 0; j < F; ++j) {
+            uint32_t h_j = 0;
+#pragma unroll
+            for (int i = 0; i < PQ; ++i) {
+                uint32_t pc = 0;
+#pragma unroll
+                for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(r.w[j][m][h] ^ q.w[i][h]);
+                h_j = (h_j << 1) + pc;
+            }
+            H = (H << 1) + h_j;
+        }
+        H = (H << (P - F)) + ((1u << (P - F)) - 1u) * __float_as_uint(mass.x);
         constexpr int kAll = 64 * W * ((1 << P) - 1) * ((1 << PQ) - 1);
         constexpr float kScale = 1.0f / (float)(1 << (P + PQ - 2));
         const float f = (float)(kAll - 2 * (int)H) * kScale;   // exact
@@ -335,11 +411,12 @@ struct ScanArgs {
     Layout layout;
     uint64_t n_items;
     const uint32_t* qwords;   // [Q][PQ][2W]
-    const float* qcoef;       // [Q][PQ+1]
+    const float* qcoef;       // [Q][PQ+1], then the queries' masses [Q][2] (see bound_item)
     uint32_t n_queries;
     const uint64_t* tau;      // [Q] threshold keys
     CandList out;
     uint32_t p_begin, p_end;  // physical tile range this launch covers
+    uint32_t* deep_rows;      // progressive scan: += rows whose planes 1.. had to be read
     uint32_t stage_entries;   // several queries: LDS queue entries per wave (512..4096), split into sub-queues
 };
 

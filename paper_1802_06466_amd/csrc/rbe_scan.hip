@@ -128,6 +128,73 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
     else mstage_drain(ms, a.out, lane);
 }
 
+// One query, P >= 2, progressive: the stream carries planes 0 .. F-1 (F = P - 1) and the scales only.  From them
+// every item gets an upper bound on its score (bound_item); only where some item of the wave's row can still
+// reach the threshold is the row's last plane read (a dependent load, exposed, but rare once the threshold is
+// tight: the rows that hold items of the query's own neighbourhood) and the row scored exactly as scan_exact
+// scores it.  What is appended is therefore identical to scan_exact's; what is read is 8W (P-1) + 4S of the
+// 8WP + 4S bytes of most items.  (The residual scales decay from plane to plane, so the last plane is the one
+// whose absence costs the bound least; with fewer planes in the stream the bound let most rows through on
+// clustered data.)
+// A wave that finds itself fetching the last plane for more than a quarter of its rows (a loose threshold, or
+// scales that do not decay) streams whole rows like scan_exact until the rate falls again.
+template <int W, int P, int PQ, int MODE>
+__global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
+{
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    const MultiStage ms{};
+    const uint32_t G = gridDim.x;
+    constexpr int S = scale_arrays(MODE, P);
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    constexpr int F = P - 1;
+    uint32_t fill = 0, rows = 0, deep = 0, full_rows = 0;   // rows seen, rows the bound let through, rows read in full
+    const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+    const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
+    const QueryMass mass{pm[0], pm[1]};
+    const uint64_t tau0 = a.tau[0];
+    const float taus0 = threshold_score(tau0);
+
+    RowRegs<W, P, S> cur, nxt;
+    load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_row_scales<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    bool whole = false;    // wave-uniform: cur holds every plane already
+    for (;;) {
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        const bool whole_next = deep * 4 > rows + 32;     // wave-uniform
+        if (has_next) {
+            const char* tn = a.tiles + (size_t)pn * tile_bytes;
+            load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
+            load_row_scales<W, P, S>(nxt, tn, wave, lane);
+            if (whole_next) load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+        }
+        bool reach = false;
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) reach |= (bound_item<W, P, PQ, MODE, F>(cur, m, q0, mass) >= taus0);
+        reach = __ballot(reach) != 0;
+        if (reach) {
+            if (!whole) load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            ++deep;
+        }
+        ++rows;
+        full_rows += (whole || reach) ? 1u : 0u;
+        if (reach) fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
+        if (!has_next) break;
+        cur = nxt;
+        whole = whole_next;
+        p = pn;
+    }
+    if (fill) stage_flush1(s_keys, fill, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+}
+
 
 // ---------------------------------------------------------------- hybrid scoring (fp32 query)
 // t_j = sum over the 8W bytes of plane j of lut[p][byte], accumulated in fp32 in byte order;
@@ -261,6 +328,19 @@ using ScanFn = void (*)(const ScanArgs);
 using DenseFn = void (*)(const char*, const Layout, const uint32_t*, const float*, uint64_t, uint64_t, float*);
 
 template <int W, int P, int PQ>
+ScanFn prog_fn_m(int mode)
+{
+    if constexpr (P >= 2) {
+        if (mode == kModeScaled) return scan_exact_prog<W, P, PQ, kModeScaled>;
+        if constexpr (dyadic_supported(W)) {
+            if (mode == kModeDyadicNorm) return scan_exact_prog<W, P, PQ, kModeDyadicNorm>;
+            if (mode == kModeDyadic) return scan_exact_prog<W, P, PQ, kModeDyadic>;
+        }
+    }
+    return nullptr;
+}
+
+template <int W, int P, int PQ>
 ScanFn scan_fn_m(int mode, bool single)
 {
     if (mode == kModeScaled) return single ? scan_exact<W, P, PQ, true, kModeScaled> : scan_exact<W, P, PQ, false, kModeScaled>;
@@ -293,8 +373,19 @@ DenseFn dense_fn_m(int mode)
         default: return nullptr;                        \
     }
 
+ScanFn prog_fn(const KernelSel& k)
+{
+    switch (k.P) {
+        case 2: RBE_SWITCH_PQ(prog_fn_m, 2, k.mode)
+        case 3: RBE_SWITCH_PQ(prog_fn_m, 3, k.mode)
+        case 4: RBE_SWITCH_PQ(prog_fn_m, 4, k.mode)
+        default: return nullptr;
+    }
+}
+
 ScanFn scan_fn(const KernelSel& k)
 {
+    if (k.progressive) return prog_fn(k);
     switch (k.P) {
         case 1: RBE_SWITCH_PQ(scan_fn_m, 1, k.mode, k.single)
         case 2: RBE_SWITCH_PQ(scan_fn_m, 2, k.mode, k.single)

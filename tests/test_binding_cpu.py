@@ -296,3 +296,49 @@ def test_matrix_core_filter_operands_stay_within_their_margin(lib, kind):
             worst = max(worst, abs(got - float(v @ (2 * bits - 1))))
     assert worst <= margin, (worst, margin)
     assert worst > 0                                     # the halves really are roundings
+
+
+# ------------------------------------------------------------------ host logic: query mass of the progressive scan
+@pytest.mark.parametrize("dim,Pq", [(64, 1), (64, 3), (128, 4), (256, 2)])
+def test_query_mass_bounds_every_plane(lib, dim, Pq):
+    """M = sum_d |qhat_d| is reached by the plane whose signs are those of qhat and by no other; the
+    reported mass is at least M, and above it only by a rounding allowance.  Checked against the
+    oracle's score of single-plane items with unit scale (the inner sum itself)."""
+    rng = np.random.default_rng(dim + Pq)
+    W = dim // 64
+    for trial in range(20):
+        qp = rng.integers(0, 2**64, size=(Pq, W), dtype=np.uint64)
+        qs = rng.uniform(0.01, 2.0, size=Pq).astype(np.float32)
+        if trial == 0 and Pq >= 2:
+            qp[1] = ~qp[0]; qs[1] = qs[0] * np.float32(1 - 2.0 ** -10)     # cancelling planes: M far below dim * sum|c|
+        x, y = rbe.rbe_debug_query_mass(qp, qs, dim)
+        qbits = ((qp[:, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64).reshape(Pq, dim)
+        qhat = (qs.astype(np.float64)[:, None] * (2 * qbits - 1)).sum(axis=0)
+        M = np.abs(qhat).sum()
+        B = dim * np.abs(qs.astype(np.float64)).sum()
+        assert M + 2.0 ** -21 * B <= x <= (M + 2.0 ** -19 * B) * (1 + 2.0 ** -18)
+        assert y == np.float32(x) * np.float32(2.0 ** -19)
+        # the best plane and random planes, through the oracle's scoring (one item plane, scale 1)
+        best = np.zeros((1, 1, W), dtype=np.uint64)
+        for d_ in range(dim):
+            if qhat[d_] > 0:
+                best[0, 0, d_ // 64] |= np.uint64(1) << np.uint64(d_ % 64)
+        planes = np.concatenate([best, rng.integers(0, 2**64, size=(1, 200, W), dtype=np.uint64)], axis=1)
+        s = oracle.scores(planes, np.ones((1, 201), dtype=np.float32), qp, qs)
+        assert abs(s[0] - M) <= 1e-9 * B and np.all(np.abs(s) <= M + 1e-9 * B)
+
+
+@pytest.mark.parametrize("dim,Pq", [(64, 1), (64, 3), (128, 4)])
+def test_query_mass_dyadic_is_the_least_mismatch_count(lib, dim, Pq):
+    """Dyadic index: h_min = min over planes K of sum_i 2^(Pq-1-i) popcount(Q_i XOR K).  The minimum
+    separates over dimensions, so brute force over the two choices per dimension gives it."""
+    rng = np.random.default_rng(7 * dim + Pq)
+    W = dim // 64
+    for _ in range(20):
+        qp = rng.integers(0, 2**64, size=(Pq, W), dtype=np.uint64)
+        h_min, y = rbe.rbe_debug_query_mass(qp, None, dim, dyadic=True)
+        qbits = ((qp[:, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.int64).reshape(Pq, dim)
+        wts = 2 ** np.arange(Pq - 1, -1, -1, dtype=np.int64)
+        cost1 = (wts[:, None] * (1 - qbits)).sum(axis=0)      # item bit 1: mismatches where the query bit is 0
+        cost0 = (wts[:, None] * qbits).sum(axis=0)
+        assert h_min == int(np.minimum(cost0, cost1).sum()) and y == 0.0

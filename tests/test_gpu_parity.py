@@ -958,3 +958,74 @@ def test_two_indexes_searched_from_two_threads_on_their_own_streams():
                     check_nearlossless(planes, scales, qp[q], qs[q], k, 4, ids[q], sc[q],
                                        queue_len=2 if mode == rbe.RBE_SELECT_NEARLOSSLESS_Q2 else 1)
         rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ progressive scan (one query, last level)
+def _search_both_ways(ix, qp, qs, k):
+    """Every query alone, with the progressive scan on and off; returns the two result lists and the share of
+    rows whose last plane was read."""
+    out, shares = {}, []
+    for prog in (True, False):
+        rbe.rbe_debug_set_progressive(ix, prog)
+        res = []
+        for q in range(qp.shape[0]):
+            res.append(rbe.rbe_search(ix, qp[q:q + 1], None if qs is None else qs[q:q + 1], k))
+            st = rbe.rbe_get_search_stats(ix)
+            rows = -(-st["items_scanned"][st["n_levels"] - 1] // 256)
+            if prog:
+                shares.append(st["deep_rows"] / rows)
+            else:
+                assert st["deep_rows"] == 0
+        out[prog] = res
+    rbe.rbe_debug_set_progressive(ix, True)
+    return out[True], out[False], shares
+
+
+@pytest.mark.parametrize("d,P,Pq,flags", [(64, 3, 3, 0), (64, 2, 3, 0), (128, 4, 4, 0), (256, 2, 2, 0), (64, 2, 3, "dyadic"),
+                                          (128, 3, 2, "dyadic_cosine"), (64, 4, 1, "dyadic")])
+def test_progressive_scan_changes_nothing_but_the_bytes_read(d, P, Pq, flags):
+    """One query, several levels: the last level reads the last plane only of rows that the other planes and the
+    scales cannot rule out.  Ids and scores are those of the plain scan bit for bit (and pass the oracle); on a
+    clustered corpus most rows are ruled out."""
+    N, k, Q = 400_003, 20, 6        # 2048 clusters of about 195 items: one row in nine holds an item of the query's
+    if flags == 0:
+        planes, scales, qp, qs = clustered(N, d, P, 2048, 0.3, Q, Pq, seed=90 + d + P)
+        ix = load_with_ratio(planes, scales, 8)
+    else:
+        c = rbe_synth.centres_numpy(2048, d)
+        x = rbe_synth.vectors_numpy(N, c, 0.3, seed=95 + d)
+        planes, _ = oracle.encode(x, P)
+        qpl, _ = oracle.encode(rbe_synth.vectors_numpy(Q, c, 0.3, seed=96), Pq)
+        qp, qs = np.ascontiguousarray(qpl.transpose(1, 0, 2)), None
+        scales = dyadic_weights(P, N)
+        fl = rbe.RBE_DYADIC | (rbe.RBE_COSINE if flags == "dyadic_cosine" else 0)
+        if flags == "dyadic_cosine":
+            scales = oracle.fold_cosine(planes, dyadic_weights(P, N))
+        ix = load_with_ratio(planes, None, 8, flags=fl)
+    on, off, shares = _search_both_ways(ix, qp, qs, k)
+    for (i1, s1), (i0, s0) in zip(on, off):
+        np.testing.assert_array_equal(i1, i0); np.testing.assert_array_equal(s1, s0)
+    qs_o = qs if qs is not None else np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
+    for q in range(Q):
+        check_topk(planes, scales, qp[q], qs_o[q], k, on[q][0][0], on[q][1][0])
+    assert 0 < np.mean(shares) < 0.5, shares       # rows of the query's own cluster are read in full, most others not
+    rbe.rbe_free(ix)
+
+
+def test_progressive_scan_on_corpora_where_the_bound_cannot_help():
+    """Random bits with random (non-decaying) scales, a zero query, a query whose planes cancel: the bound lets
+    most rows through, waves fall back to whole rows, and the results still equal the plain scan's."""
+    N, d, P, k = 300_007, 64, 3, 50
+    rng = np.random.default_rng(808)
+    planes, scales = random_corpus(rng, N, d, P)
+    qp, qs = random_queries(rng, 5, d, 3)
+    qs[1] = 0.0
+    qp[2, 1] = ~qp[2, 0]; qs[2, 1] = qs[2, 0] * np.float32(1 - 2.0 ** -12); qs[2, 2] = 0.0
+    qs[3] *= -1.0                                              # negative query scales: M uses |qhat|
+    ix = load_with_ratio(planes, scales, 8)
+    on, off, shares = _search_both_ways(ix, qp, qs, k)
+    for (i1, s1), (i0, s0) in zip(on, off):
+        np.testing.assert_array_equal(i1, i0); np.testing.assert_array_equal(s1, s0)
+    for q in range(5):
+        check_topk(planes, scales, qp[q], qs[q], k, on[q][0][0], on[q][1][0])
+    rbe.rbe_free(ix)
