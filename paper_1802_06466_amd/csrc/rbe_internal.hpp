@@ -68,6 +68,16 @@ RBE_DECLARE_W(2)
 RBE_DECLARE_W(4)
 #undef RBE_DECLARE_W
 
+// Persistent workgroups per compute unit for a one-query streaming scan: about 44 KB of tile stream in flight
+// per compute unit (a workgroup has one tile in flight; the progressive scan streams all planes but the last).
+inline uint32_t streaming_blocks_per_cu(uint32_t W, uint32_t P, uint32_t S, bool progressive)
+{
+    const uint32_t planes = progressive && P >= 2 ? P - 1 : P;
+    const uint32_t tile_stream = kTileItems * (8u * W * planes + 4u * S);
+    const uint32_t n = (44u * 1024u + tile_stream / 2) / tile_stream;
+    return n < 1u ? 1u : (n > 3u ? 3u : n);
+}
+
 // Dyadic modes are built for d = 64 and d = 128.
 constexpr bool dyadic_supported(uint32_t W) { return W <= 2; }
 

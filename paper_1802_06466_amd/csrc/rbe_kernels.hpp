@@ -217,15 +217,17 @@ __device__ __forceinline__ float score_item(const RowRegs<W, P, scale_arrays(MOD
 //               h_min as an integer.  The conversion and the item's scale are monotone, so the bound is exact.
 struct QueryMass { float x, y; };
 
-template <int W, int P, int PQ, int MODE, int F>
-__device__ __forceinline__ float bound_item(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m,
-                                            const QueryRegs<W, PQ>& q, const QueryMass& mass)
+// score_item taken in two steps: planes [0, F) first, the rest later, through exactly the same operations in
+// the same order, so that finish_item(partial_item(..)) == score_item(..) bit for bit.
+struct PartialScore { float s; uint32_t H; };
+
+template <int W, int P, int PQ, int MODE, int J0, int J1>
+__device__ __forceinline__ PartialScore score_planes(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m,
+                                                     const QueryRegs<W, PQ>& q, PartialScore acc)
 {
-    static_assert(F >= 1 && F < P, "a bound needs planes to compute and planes to skip");
-    if (MODE == kModeScaled) {
-        float s = 0.0f;
 #pragma unroll
-        for (int j = 0; j < F; ++j) {
+    for (int j = J0; j < J1; ++j) {
+        if (MODE == kModeScaled) {
             float t = q.bias;
 #pragma unroll
             for (int i = 0; i < PQ; ++i) {
@@ -234,19 +236,8 @@ __device__ __forceinline__ float bound_item(const RowRegs<W, P, scale_arrays(MOD
                 for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(r.w[j][m][h] ^ q.w[i][h]);
                 t = __fmaf_rn(q.m2c[i], (float)pc, t);
             }
-            s = __fmaf_rn(r.a[j][m], t, s);
-        }
-        float tail = r.a[F][m];
-#pragma unroll
-        for (int j = F + 1; j < P; ++j) tail += r.a[j][m];
-        float all = tail;
-#pragma unroll
-        for (int j = 0; j < F; ++j) all += r.a[j][m];
-        return __fmaf_rn(all, mass.y, __fmaf_rn(tail, mass.x, s));
-    } else {
-        uint32_t H = 0;
-#pragma unroll
-        for (int j = 0; j < F; ++j) {
+            acc.s = __fmaf_rn(r.a[j][m], t, acc.s);
+        } else {
             uint32_t h_j = 0;
 #pragma unroll
             for (int i = 0; i < PQ; ++i) {
@@ -255,13 +246,54 @@ __device__ __forceinline__ float bound_item(const RowRegs<W, P, scale_arrays(MOD
                 for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(r.w[j][m][h] ^ q.w[i][h]);
                 h_j = (h_j << 1) + pc;
             }
-            H = (H << 1) + h_j;
+            acc.H = (acc.H << 1) + h_j;
         }
-        H = (H << (P - F)) + ((1u << (P - F)) - 1u) * __float_as_uint(mass.x);
-        constexpr int kAll = 64 * W * ((1 << P) - 1) * ((1 << PQ) - 1);
-        constexpr float kScale = 1.0f / (float)(1 << (P + PQ - 2));
-        const float f = (float)(kAll - 2 * (int)H) * kScale;   // exact
-        return MODE == kModeDyadicNorm ? f * r.a[0][m] : f;
+    }
+    return acc;
+}
+
+template <int W, int P, int PQ, int MODE, int F>
+__device__ __forceinline__ PartialScore partial_item(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m,
+                                                     const QueryRegs<W, PQ>& q)
+{
+    return score_planes<W, P, PQ, MODE, 0, F>(r, m, q, PartialScore{0.0f, 0u});
+}
+
+template <int W, int P, int MODE>
+__device__ __forceinline__ float score_value(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m, uint32_t H, float s,
+                                             int PQ)
+{
+    if (MODE == kModeScaled) return s;
+    const int all = 64 * W * ((1 << P) - 1) * ((1 << PQ) - 1);
+    const float f = (float)(all - 2 * (int)H) * (1.0f / (float)(1 << (P + PQ - 2)));   // exact
+    return MODE == kModeDyadicNorm ? f * r.a[0][m] : f;
+}
+
+template <int W, int P, int PQ, int MODE, int F>
+__device__ __forceinline__ float finish_item(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m,
+                                             const QueryRegs<W, PQ>& q, PartialScore part)
+{
+    const PartialScore full = score_planes<W, P, PQ, MODE, F, P>(r, m, q, part);
+    return score_value<W, P, MODE>(r, m, full.H, full.s, PQ);
+}
+
+// The bound from a partial score (1 <= F < P).
+template <int W, int P, int PQ, int MODE, int F>
+__device__ __forceinline__ float bound_item(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m, PartialScore part,
+                                            const QueryMass& mass)
+{
+    static_assert(F >= 1 && F < P, "a bound needs planes to compute and planes to skip");
+    if (MODE == kModeScaled) {
+        float tail = r.a[F][m];
+#pragma unroll
+        for (int j = F + 1; j < P; ++j) tail += r.a[j][m];
+        float all = tail;
+#pragma unroll
+        for (int j = 0; j < F; ++j) all += r.a[j][m];
+        return __fmaf_rn(all, mass.y, __fmaf_rn(tail, mass.x, part.s));
+    } else {
+        const uint32_t H = (part.H << (P - F)) + ((1u << (P - F)) - 1u) * __float_as_uint(mass.x);
+        return score_value<W, P, MODE>(r, m, H, 0.0f, PQ);
     }
 }
 

@@ -8,6 +8,25 @@
 
 namespace rbe {
 
+// Queues the survivors among the lane's 4 scores.
+template <int W, bool SINGLE>
+__device__ __forceinline__ uint32_t stage_scores(const float (&s)[kItemsPerLane], uint64_t tau, float taus, uint32_t q,
+                                                 uint32_t p, int wave, int lane, uint64_t* s_keys, const MultiStage& ms,
+                                                 uint32_t fill, const ScanArgs& a)
+{
+    const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+#pragma unroll
+    for (int m = 0; m < kItemsPerLane; ++m) {
+        const uint64_t id = row_id + lane_item<W>(lane, m);
+        bool ok = (s[m] >= taus) && (id < a.n_items);
+        uint64_t key = 0;
+        if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
+        if (SINGLE) fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
+        else mstage_append(ok, key, q, ms, a.out, lane);
+    }
+    return fill;
+}
+
 // Scores the lane's 4 items of `cur` against one query and queues the survivors.
 template <int W, int P, int PQ, bool SINGLE, int MODE>
 __device__ __forceinline__ uint32_t score_and_stage(RowRegs<W, P, scale_arrays(MODE, P)>& cur, const QueryRegs<W, PQ>& qr, uint64_t tau,
@@ -32,18 +51,8 @@ __device__ __forceinline__ uint32_t score_and_stage(RowRegs<W, P, scale_arrays(M
                 for (int h = 0; h < 2 * W; ++h) asm volatile("" : "+v"(s[m]), "+v"(cur.w[j][m + 1][h]));
         }
     }
-    if (__ballot(any)) {   // rare: at least one lane of the wave has a survivor
-        const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
-#pragma unroll
-        for (int m = 0; m < kItemsPerLane; ++m) {
-            const uint64_t id = row_id + lane_item<W>(lane, m);
-            bool ok = (s[m] >= taus) && (id < a.n_items);
-            uint64_t key = 0;
-            if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
-            if (SINGLE) fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
-            else mstage_append(ok, key, q, ms, a.out, lane);
-        }
-    }
+    if (__ballot(any))     // rare: at least one lane of the wave has a survivor
+        fill = stage_scores<W, SINGLE>(s, tau, taus, q, p, wave, lane, s_keys, ms, fill, a);
     return fill;
 }
 
@@ -175,17 +184,28 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
             load_row_scales<W, P, S>(nxt, tn, wave, lane);
             if (whole_next) load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
         }
+        PartialScore part[kItemsPerLane];
         bool reach = false;
 #pragma unroll
-        for (int m = 0; m < kItemsPerLane; ++m) reach |= (bound_item<W, P, PQ, MODE, F>(cur, m, q0, mass) >= taus0);
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            part[m] = partial_item<W, P, PQ, MODE, F>(cur, m, q0);
+            reach |= (bound_item<W, P, PQ, MODE, F>(cur, m, part[m], mass) >= taus0);
+        }
         reach = __ballot(reach) != 0;
+        ++rows;
+        full_rows += (whole || reach) ? 1u : 0u;
         if (reach) {
             if (!whole) load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
             ++deep;
+            float s[kItemsPerLane];
+            bool any = false;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                s[m] = finish_item<W, P, PQ, MODE, F>(cur, m, q0, part[m]);
+                any |= (s[m] >= taus0);
+            }
+            if (__ballot(any)) fill = stage_scores<W, true>(s, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
         }
-        ++rows;
-        full_rows += (whole || reach) ? 1u : 0u;
-        if (reach) fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
         if (!has_next) break;
         cur = nxt;
         whole = whole_next;
@@ -497,6 +517,9 @@ hipError_t launch_scan_exact_w<RBE_W>(const KernelSel& k, const ScanArgs& a, uin
         const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kBlock, dyn_lds);
         if (e != hipSuccess) return e;
         per_cu = (uint32_t)(nb > 0 ? nb : 1);
+        // One query is a pure stream: what matters is the bytes in flight per compute unit, and more workgroups
+        // than that needs only spread the accesses (measured: 36 KB tiles 1 per CU, 20..28 KB 2, 12 KB 3..4).
+        if (k.single) per_cu = std::min(per_cu, streaming_blocks_per_cu(RBE_W, k.P, scale_arrays(k.mode, k.P), k.progressive));
     }
     const uint32_t units = a.p_end - a.p_begin;
     const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;
