@@ -380,7 +380,7 @@ BatchOperandShape batch_operand_shape(uint32_t W, uint32_t P, bool dyadic, uint3
 // are not read; general scales only.
 void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q_planes, const float* q_scales,
                           uint32_t Q, uint32_t PQ, uint16_t* halves, float* unscale, float* bias,
-                          const float* q_float = nullptr, float* margin = nullptr)
+                          const float* q_float = nullptr, float* margin = nullptr, float* qmass = nullptr)
 {
     const BatchOperandShape sh = batch_operand_shape(W, P, dyadic, Q);
     double worst = 0.0;
@@ -441,6 +441,14 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
                 }
         if (dyadic) sum *= 2.0 - std::ldexp(1.0, 1 - (int)P);   // every plane's term starts from its own -2^-j sum
         bias[q] = (float)-sum;
+        if (qmass) {
+            // sum_d |v_d|, rounded up: the largest value qhat . rho can take in the scaled domain (general scales)
+            double m_abs = 0.0;
+            for (uint32_t d = 0; d < dim; ++d) m_abs += std::fabs(std::ldexp(qhat[d], k));
+            float mf = (float)(m_abs * (1.0 + std::ldexp(1.0, -20)));
+            if ((double)mf < m_abs * (1.0 + std::ldexp(1.0, -20))) mf = std::nextafter(mf, INFINITY);
+            qmass[q] = mf;
+        }
         worst = std::max(worst, lost + std::ldexp(mass * 3.0 * (dim + 8), -23) + std::ldexp(coef_mass, -20) +
                                     (q_float ? std::ldexp(mass, -19) : 0.0) + std::fabs(sum - (double)(float)sum));
     }
@@ -454,15 +462,16 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
     if (!ix->d_aops) {
         HIP_TRY(hipMalloc(&ix->d_aops, max_halves * sizeof(uint16_t)));
         HIP_TRY(hipHostMalloc(&ix->h_aops, max_halves * sizeof(uint16_t), hipHostMallocDefault));
-        HIP_TRY(hipMalloc(&ix->d_unscale, 2 * RBE_MAX_QUERIES * sizeof(float)));
-        HIP_TRY(hipHostMalloc(&ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
+        HIP_TRY(hipMalloc(&ix->d_unscale, 3 * RBE_MAX_QUERIES * sizeof(float)));
+        HIP_TRY(hipHostMalloc(&ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
     }
     const bool dyadic = ix->mode != rbe::kModeScaled;
     const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q);
     build_batch_operands(ix->W, ix->P, dyadic, q_planes, q_scales, Q, PQ, reinterpret_cast<uint16_t*>(ix->h_aops),
-                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float, &ix->batch_margin);
+                         ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float, &ix->batch_margin,
+                         ix->h_unscale + 2 * RBE_MAX_QUERIES);
     HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, sh.n_halves * sizeof(uint16_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, 2 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
 
@@ -868,7 +877,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
     } else if (c.batch_mfma && !(dense && !c.float_batch && ix->batch_path == 0)) {
         BatchArgs ba;
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
-        ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.tau = ix->d_tau; ba.n_queries = c.Q;
+        ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.q_mass = ix->d_unscale + 2 * RBE_MAX_QUERIES; ba.tau = ix->d_tau; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
         ba.rescore = batch_rescore(ix, c.float_batch);
         ba.PQ = c.PQ; ba.qwords = ix->d_qwords; ba.qcoef = ix->d_qcoef; ba.lut = ix->d_lut; ba.margin = ix->batch_margin;

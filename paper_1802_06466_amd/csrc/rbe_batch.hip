@@ -113,8 +113,13 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     constexpr bool kRescore = !kDy;
     constexpr bool kBinary = kRescore && RS == 1;
     static_assert(kDy ? RS == 0 : (RS == 1 || RS == 2), "general scales filter and rescore; dyadic modes are exact");
+    // General scales, binary queries, two or more planes: the last plane (the smallest scales) stays out of the
+    // contraction; the filter adds the most it could contribute, a_{P-1}[item] * sum_d |v_d|, instead, and only a
+    // block of items in which that leaves some pair above its threshold contracts the last plane as well before
+    // anything is scored exactly.  (With fp32 queries the saving did not pay for the extra table reads.)
+    constexpr int F = (kBinary && P >= 2) ? P - 1 : P;
     constexpr int PA = kDy ? P : 1;
-    constexpr int PD = kDy ? 1 : P;
+    constexpr int PD = kDy ? 1 : F;
     constexpr int SEG = row_segments<W>();
     constexpr int kSegItems = kRow / SEG;
     __shared__ uint64_t s_pl[kWavesPerBlock][P][kSegItems * W];
@@ -170,7 +175,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     // this lane's queries: tile qt, rows 4g .. 4g+3 (query a.q_begin + 16 qt + 4g + r).  Scores are formed in the
     // query's scaled domain (qhat * 2^k); thresholds are moved there, survivors are moved back (both exact).
     // Only what the common path needs stays in registers; the rare survivor path re-reads the rest.
-    float taus[NQT][4], bias[NQT][4];
+    float taus[NQT][4], bias[NQT][4], qmass[NQT][4];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
@@ -178,6 +183,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
             const uint32_t q = a.q_begin + qt * 16 + 4 * g + r;
             taus[qt][r] = q < a.n_queries ? threshold_score(a.tau[q]) / a.q_unscale[q] : __builtin_inff();
             bias[qt][r] = q < a.n_queries ? a.q_bias[q] : 0.0f;
+            qmass[qt][r] = (F < P && q < a.n_queries) ? a.q_mass[q] : 0.0f;
         }
 
     RawRow<W, P, S> cur, nxt;
@@ -220,7 +226,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
 #pragma unroll
                     for (int j = 0; j < PD; ++j) D[qt][j] = floatx4{bias[qt][0], bias[qt][1], bias[qt][2], bias[qt][3]};
 #pragma unroll
-                for (int j = 0; j < P; ++j) {
+                for (int j = 0; j < (kDy ? P : F); ++j) {
                     uint32_t part[KP];
                     if constexpr (W == 1) {
                         const uint64_t w = s_pl[wave][j][item];
@@ -265,7 +271,8 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                         if (MODE == kModeScaled) {
                             v = adj;
 #pragma unroll
-                            for (int j = 0; j < P; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
+                            for (int j = 0; j < F; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
+                            if (F < P) v = __fmaf_rn(aj[P - 1], qmass[qt][r], v);
                         } else if (MODE == kModeDyadicNorm) {
                             v = aj[0] * D[qt][0][r];
                         } else {
@@ -275,7 +282,47 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                         any |= (v >= taus[qt][r]);
                     }
             }
-            if (__ballot(any)) {
+            bool go = __ballot(any) != 0;
+            if (F < P && go) {
+                // second look, with the last plane contracted too
+                bool any2 = false;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int item = 16 * (cb * U + u) + col;
+                    floatx4 DL[NQT];
+#pragma unroll
+                    for (int qt = 0; qt < NQT; ++qt) DL[qt] = floatx4{bias[qt][0], bias[qt][1], bias[qt][2], bias[qt][3]};
+                    uint32_t part[KP];
+                    if constexpr (W == 1) {
+                        const uint64_t w = s_pl[wave][P - 1][item];
+                        part[0] = (uint32_t)w; part[1] = (uint32_t)(w >> 32);
+                    } else {
+                        const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][P - 1][item * 2]);
+                        part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
+                    }
+#pragma unroll
+                    for (int kp = 0; kp < KP; ++kp) {
+                        const uint32_t xr = __builtin_rotateleft32(part[kp], 4u * (uint32_t)g);
+                        u32x4 bw;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) bw[t] = xr & (0x04000400u << t);
+                        const half8 B = __builtin_bit_cast(half8, bw);
+#pragma unroll
+                        for (int qt = 0; qt < NQT; ++qt)
+                            DL[qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][0][kp], B, DL[qt], 0, 0, 0);
+                    }
+                    const float a_last = s_sc[wave][P - 1][item];
+#pragma unroll
+                    for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            s[u][qt][r] = __fmaf_rn(a_last, DL[qt][r] - qmass[qt][r], s[u][qt][r]);
+                            any2 |= (s[u][qt][r] >= taus[qt][r]);
+                        }
+                }
+                go = __ballot(any2) != 0;
+            }
+            if (go) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const uint64_t id = row_id + (uint64_t)(16 * (cb * U + u) + col);
