@@ -439,15 +439,22 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
                         halves[((((size_t)qt * PA + pa) * KP + part) * 64 + lane) * 8 + e] = bits;
                     }
                 }
+        const double sum_v = sum;
         if (dyadic) sum *= 2.0 - std::ldexp(1.0, 1 - (int)P);   // every plane's term starts from its own -2^-j sum
         bias[q] = (float)-sum;
         if (qmass) {
-            // sum_d |v_d|, rounded up: the largest value qhat . rho can take in the scaled domain (general scales)
             double m_abs = 0.0;
             for (uint32_t d = 0; d < dim; ++d) m_abs += std::fabs(std::ldexp(qhat[d], k));
-            float mf = (float)(m_abs * (1.0 + std::ldexp(1.0, -20)));
-            if ((double)mf < m_abs * (1.0 + std::ldexp(1.0, -20))) mf = std::nextafter(mf, INFINITY);
-            qmass[q] = mf;
+            if (dyadic) {
+                // the most the last plane's term can add to an accumulator that already holds its start value:
+                // 2^-(P-1) (qhat . rho + sum_d v_d) <= 2^-(P-1) (sum_d |v_d| + sum_d v_d); a short dyadic fraction
+                qmass[q] = (float)std::ldexp(m_abs + sum_v, 1 - (int)P);
+            } else {
+                // sum_d |v_d|, rounded up: the largest value qhat . rho can take in the scaled domain
+                float mf = (float)(m_abs * (1.0 + std::ldexp(1.0, -20)));
+                if ((double)mf < m_abs * (1.0 + std::ldexp(1.0, -20))) mf = std::nextafter(mf, INFINITY);
+                qmass[q] = mf;
+            }
         }
         worst = std::max(worst, lost + std::ldexp(mass * 3.0 * (dim + 8), -23) + std::ldexp(coef_mass, -20) +
                                     (q_float ? std::ldexp(mass, -19) : 0.0) + std::fabs(sum - (double)(float)sum));

@@ -113,11 +113,12 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     constexpr bool kRescore = !kDy;
     constexpr bool kBinary = kRescore && RS == 1;
     static_assert(kDy ? RS == 0 : (RS == 1 || RS == 2), "general scales filter and rescore; dyadic modes are exact");
-    // General scales, binary queries, two or more planes: the last plane (the smallest scales) stays out of the
-    // contraction; the filter adds the most it could contribute, a_{P-1}[item] * sum_d |v_d|, instead, and only a
-    // block of items in which that leaves some pair above its threshold contracts the last plane as well before
-    // anything is scored exactly.  (With fp32 queries the saving did not pay for the extra table reads.)
-    constexpr int F = (kBinary && P >= 2) ? P - 1 : P;
+    // Binary queries, two or more planes: the last plane (the smallest weights) stays out of the contraction; the
+    // first look adds the most it could contribute instead (general scales: a_{P-1}[item] * sum_d |v_d|; dyadic
+    // modes: a.q_mass), and only a block of items in which that leaves some pair above its threshold contracts the
+    // last plane as well (dyadic modes: that is then the exact score) before anything is queued or scored exactly.
+    // (With fp32 queries the saving did not pay for the extra table reads.)
+    constexpr int F = ((kBinary || kDy) && P >= 2) ? P - 1 : P;
     constexpr int PA = kDy ? P : 1;
     constexpr int PD = kDy ? 1 : F;
     constexpr int SEG = row_segments<W>();
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
 #pragma unroll
                     for (int j = 0; j < PD; ++j) D[qt][j] = floatx4{bias[qt][0], bias[qt][1], bias[qt][2], bias[qt][3]};
 #pragma unroll
-                for (int j = 0; j < (kDy ? P : F); ++j) {
+                for (int j = 0; j < F; ++j) {
                     uint32_t part[KP];
                     if constexpr (W == 1) {
                         const uint64_t w = s_pl[wave][j][item];
@@ -274,9 +275,9 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                             for (int j = 0; j < F; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
                             if (F < P) v = __fmaf_rn(aj[P - 1], qmass[qt][r], v);
                         } else if (MODE == kModeDyadicNorm) {
-                            v = aj[0] * D[qt][0][r];
+                            v = aj[0] * (D[qt][0][r] + qmass[qt][r]);
                         } else {
-                            v = D[qt][0][r];
+                            v = D[qt][0][r] + qmass[qt][r];
                         }
                         s[u][qt][r] = v;
                         any |= (v >= taus[qt][r]);
@@ -289,34 +290,41 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int item = 16 * (cb * U + u) + col;
+                    // general scales: the last plane alone; dyadic modes: every plane again (the exact score)
                     floatx4 DL[NQT];
 #pragma unroll
                     for (int qt = 0; qt < NQT; ++qt) DL[qt] = floatx4{bias[qt][0], bias[qt][1], bias[qt][2], bias[qt][3]};
-                    uint32_t part[KP];
-                    if constexpr (W == 1) {
-                        const uint64_t w = s_pl[wave][P - 1][item];
-                        part[0] = (uint32_t)w; part[1] = (uint32_t)(w >> 32);
-                    } else {
-                        const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][P - 1][item * 2]);
-                        part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
+#pragma unroll
+                    for (int j = kDy ? 0 : P - 1; j < P; ++j) {
+                        uint32_t part[KP];
+                        if constexpr (W == 1) {
+                            const uint64_t w = s_pl[wave][j][item];
+                            part[0] = (uint32_t)w; part[1] = (uint32_t)(w >> 32);
+                        } else {
+                            const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][j][item * 2]);
+                            part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
+                        }
+#pragma unroll
+                        for (int kp = 0; kp < KP; ++kp) {
+                            const uint32_t xr = __builtin_rotateleft32(part[kp], 4u * (uint32_t)g);
+                            u32x4 bw;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) bw[t] = xr & (0x04000400u << t);
+                            const half8 B = __builtin_bit_cast(half8, bw);
+#pragma unroll
+                            for (int qt = 0; qt < NQT; ++qt)
+                                DL[qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][kDy ? j : 0][kp], B, DL[qt], 0, 0, 0);
+                        }
                     }
-#pragma unroll
-                    for (int kp = 0; kp < KP; ++kp) {
-                        const uint32_t xr = __builtin_rotateleft32(part[kp], 4u * (uint32_t)g);
-                        u32x4 bw;
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) bw[t] = xr & (0x04000400u << t);
-                        const half8 B = __builtin_bit_cast(half8, bw);
-#pragma unroll
-                        for (int qt = 0; qt < NQT; ++qt)
-                            DL[qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][0][kp], B, DL[qt], 0, 0, 0);
-                    }
-                    const float a_last = s_sc[wave][P - 1][item];
+                    float a_item = 1.0f;
+                    if constexpr (MODE == kModeScaled) a_item = s_sc[wave][P - 1][item];
+                    else if constexpr (MODE == kModeDyadicNorm) a_item = s_sc[wave][0][item];
 #pragma unroll
                     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            s[u][qt][r] = __fmaf_rn(a_last, DL[qt][r] - qmass[qt][r], s[u][qt][r]);
+                            if (MODE == kModeScaled) s[u][qt][r] = __fmaf_rn(a_item, DL[qt][r] - qmass[qt][r], s[u][qt][r]);
+                            else s[u][qt][r] = MODE == kModeDyadicNorm ? a_item * DL[qt][r] : DL[qt][r];
                             any2 |= (s[u][qt][r] >= taus[qt][r]);
                         }
                 }

@@ -476,8 +476,9 @@ struct BatchArgs {
     const float* q_unscale;   // [Q] 2^-k: what a score formed from the scaled query is multiplied by
     const float* q_bias;      // [Q] minus the (plane-weighted) sum of the scaled query's components: where
                               // every accumulator starts
-    const float* q_mass;      // [Q] general scales: sum_d |v_d| of the scaled query, rounded up: no plane's contraction
-                              // can exceed it, which is what lets the filter leave the last plane out
+    const float* q_mass;      // [Q] what lets the first look leave the last plane out.  General scales: sum_d |v_d| of
+                              // the scaled query, rounded up (no plane's qhat . rho exceeds it).  Dyadic modes: the most
+                              // the last plane's term can add to the accumulator, 2^-(P-1) (sum_d |v_d| + sum_d v_d)
     const uint64_t* tau;      // [Q] threshold keys
     uint32_t n_queries;       // Q
     uint32_t q_begin;         // first query of this launch (a multiple of 16); it handles 16 or 32 from there
