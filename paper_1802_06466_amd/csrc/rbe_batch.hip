@@ -35,6 +35,8 @@
 // carry no trace of the half precision.  The per-pair VALU work drops from ~58
 // lane-ops to P fused multiply-adds and one compare; bit expansion is paid once per
 // item, whatever the number of queries.
+#include <type_traits>
+
 #include "rbe_internal.hpp"
 
 #ifndef RBE_W
@@ -118,9 +120,9 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
     // modes: a.q_mass), and only a block of items in which that leaves some pair above its threshold contracts the
     // last plane as well (dyadic modes: that is then the exact score) before anything is queued or scored exactly.
     // (With fp32 queries the saving did not pay for the extra table reads.)
-    constexpr int F = ((kBinary || kDy) && P >= 2) ? P - 1 : P;
+    constexpr bool kCanSkip = (kBinary || kDy) && P >= 2;
     constexpr int PA = kDy ? P : 1;
-    constexpr int PD = kDy ? 1 : F;
+    constexpr int PD_MAX = kDy ? 1 : P;
     constexpr int SEG = row_segments<W>();
     constexpr int kSegItems = kRow / SEG;
     __shared__ uint64_t s_pl[kWavesPerBlock][P][kSegItems * W];
@@ -184,9 +186,11 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
             const uint32_t q = a.q_begin + qt * 16 + 4 * g + r;
             taus[qt][r] = q < a.n_queries ? threshold_score(a.tau[q]) / a.q_unscale[q] : __builtin_inff();
             bias[qt][r] = q < a.n_queries ? a.q_bias[q] : 0.0f;
-            qmass[qt][r] = (F < P && q < a.n_queries) ? a.q_mass[q] : 0.0f;
+            qmass[qt][r] = (kCanSkip && q < a.n_queries) ? a.q_mass[q] : 0.0f;
         }
 
+    bool skip_last = kCanSkip;              // wave-uniform
+    uint32_t blocks_seen = 0, second_looks = 0;
     RawRow<W, P, S> cur, nxt;
     int seg = 0;
     load_raw<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, seg, lane);
@@ -215,6 +219,13 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
         const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow +
                                 (uint64_t)seg * kSegItems;
         constexpr int U = 2;   // item groups per straight-line block
+        // the segment's blocks, with the last plane left out of the first look (SKIP) or not: two copies of the
+        // code, one of which runs per segment
+        auto blocks = [&](auto skip_tag) {
+        constexpr bool SKIP = decltype(skip_tag)::value;
+        constexpr int F = SKIP ? P - 1 : P;
+        constexpr int PD = kDy ? 1 : F;
+        static_assert(PD <= PD_MAX, "accumulators");
         for (int cb = 0; cb < kSegItems / (16 * U); ++cb) {
             float s[U][NQT][4];
             bool any = false;
@@ -275,16 +286,18 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                             for (int j = 0; j < F; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
                             if (F < P) v = __fmaf_rn(aj[P - 1], qmass[qt][r], v);
                         } else if (MODE == kModeDyadicNorm) {
-                            v = aj[0] * (D[qt][0][r] + qmass[qt][r]);
+                            v = aj[0] * (F < P ? D[qt][0][r] + qmass[qt][r] : D[qt][0][r]);
                         } else {
-                            v = D[qt][0][r] + qmass[qt][r];
+                            v = F < P ? D[qt][0][r] + qmass[qt][r] : D[qt][0][r];
                         }
                         s[u][qt][r] = v;
                         any |= (v >= taus[qt][r]);
                     }
             }
             bool go = __ballot(any) != 0;
+            ++blocks_seen;
             if (F < P && go) {
+                ++second_looks;
                 // second look, with the last plane contracted too
                 bool any2 = false;
 #pragma unroll
@@ -386,6 +399,16 @@ __global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
                         }
                 }
             }
+        }
+        };
+        if constexpr (kCanSkip) {
+            if (skip_last) blocks(std::true_type{});
+            else blocks(std::false_type{});
+            // a wave that takes the second look for more than half of its blocks (a loose threshold, or weights
+            // that do not decay) contracts every plane in the first look from then on
+            if (skip_last && second_looks * 2 > blocks_seen + 16) skip_last = false;
+        } else {
+            blocks(std::false_type{});
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
