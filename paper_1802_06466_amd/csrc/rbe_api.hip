@@ -87,6 +87,7 @@ struct rbe_index {
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
+    float fq_mass[RBE_MAX_QUERIES][2] = {};   // fp32 queries: {x, 2^-19 x}, x >= sum_d |q_d| (1 + 2^-18): bounds any plane's table sum
     float* d_lut = nullptr;         // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
     float* h_lut = nullptr;
     uint32_t* d_qwords = nullptr;   // [Q][PQ][2W]
@@ -296,8 +297,17 @@ int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t s
     }
     for (uint32_t n = 0; n < Q; ++n) {
         const float* x = q + (size_t)n * ix->dim;
-        for (uint32_t i = 0; i < ix->dim; ++i)
+        double m_abs = 0.0;
+        for (uint32_t i = 0; i < ix->dim; ++i) {
             if (!std::isfinite(x[i])) { set_error("q[%u][%u] is not finite", n, i); return RBE_EINVAL; }
+            m_abs += std::fabs((double)x[i]);
+        }
+        // a plane's table sum: 8W entries rounded to fp32 and 8W - 1 fp32 additions, all at magnitudes <= m_abs
+        m_abs *= 1.0 + std::ldexp(1.0, -18);
+        float xf = (float)m_abs;
+        if ((double)xf < m_abs) xf = std::nextafter(xf, INFINITY);
+        ix->fq_mass[n][0] = xf;
+        ix->fq_mass[n][1] = std::ldexp(xf, -19);
         for (uint32_t p = 0; p < 8 * ix->W; ++p)
             for (uint32_t v = 0; v < 256; ++v) {
                 double acc = 0.0;
@@ -872,11 +882,13 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
     hipError_t e;
     if (c.float_query) {
         e = hipSuccess;
+        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0;
         const size_t per_q = (size_t)8 * ix->W * 256;
         for (uint32_t q = 0; q < c.Q && e == hipSuccess; ++q) {   // one pass over the range per query
             FqArgs fa;
             fa.tiles = ix->d_tiles; fa.layout = ix->layout; fa.n_items = ix->n_items;
             fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
+            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1;
             fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q, ix->d_kmax + q, c.cap};
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);

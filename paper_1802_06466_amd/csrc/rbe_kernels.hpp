@@ -463,6 +463,8 @@ struct FqArgs {
     const uint64_t* tau_ptr;  // [1] threshold key of this query
     CandList out;             // this query's list (pointers already offset)
     uint32_t p_begin, p_end;
+    QueryMass mass;           // progressive scan: x >= sum_d |q_d| plus the rounding of the table sums, y = 2^-19 x
+    uint32_t* deep_rows;      // progressive scan: += rows whose last plane had to be read
 };
 
 // Batched scan on the matrix cores (rbe_batch.hip).

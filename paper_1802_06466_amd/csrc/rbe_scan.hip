@@ -219,13 +219,12 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 // ---------------------------------------------------------------- hybrid scoring (fp32 query)
 // t_j = sum over the 8W bytes of plane j of lut[p][byte], accumulated in fp32 in byte order;
 // kModeScaled: s = sum_j fma(a_j, t_j, s).  Dyadic modes: s = (sum_j 2^-j t_j) [* the item's scale].
-template <int W, int P, int MODE>
-__device__ __forceinline__ float score_item_fq(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m,
-                                               const float (*lut)[256])
+template <int W, int P, int MODE, int J0, int J1>
+__device__ __forceinline__ float fq_planes(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m, const float (*lut)[256],
+                                           float s)
 {
-    float s = 0.0f;
 #pragma unroll
-    for (int j = 0; j < P; ++j) {
+    for (int j = J0; j < J1; ++j) {
         float t = 0.0f;
 #pragma unroll
         for (int h = 0; h < 2 * W; ++h) {
@@ -238,7 +237,36 @@ __device__ __forceinline__ float score_item_fq(const RowRegs<W, P, scale_arrays(
         if (MODE == kModeScaled) s = __fmaf_rn(r.a[j][m], t, s);
         else s = __fmaf_rn(1.0f / (float)(1 << j), t, s);
     }
+    return s;
+}
+
+template <int W, int P, int MODE>
+__device__ __forceinline__ float score_item_fq(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m,
+                                               const float (*lut)[256])
+{
+    const float s = fq_planes<W, P, MODE, 0, P>(r, m, lut, 0.0f);
     return MODE == kModeDyadicNorm ? s * r.a[0][m] : s;
+}
+
+// Upper bound on score_item_fq from planes 0 .. P-2 (see bound_item): no plane's table sum exceeds the query's
+// mass sum_d |q_d| (mass.x, rounding of the table entries and of their sum included), the last plane's weight
+// is a_{P-1} or 2^-(P-1), and mass.y per unit of weight covers the roundings of the chain.
+template <int W, int P, int MODE>
+__device__ __forceinline__ float bound_item_fq(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m, float part,
+                                               const QueryMass& mass)
+{
+    float tail, all;
+    if (MODE == kModeScaled) {
+        tail = r.a[P - 1][m];
+        all = tail;
+#pragma unroll
+        for (int j = 0; j < P - 1; ++j) all += r.a[j][m];
+    } else {
+        tail = 1.0f / (float)(1 << (P - 1));
+        all = 2.0f;
+    }
+    const float ub = __fmaf_rn(all, mass.y, __fmaf_rn(tail, mass.x, part));
+    return MODE == kModeDyadicNorm ? ub * r.a[0][m] : ub;
 }
 
 template <int W, int P, int MODE>
@@ -290,6 +318,85 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq(const FqArgs a)
         p = pn;
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
+}
+
+// scan_exact_fq, progressive (P >= 2): as scan_exact_prog, with the table sums in place of the popcounts.
+template <int W, int P, int MODE>
+__global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
+{
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ float s_lut[8 * W][256];
+    constexpr int S = scale_arrays(MODE, P);
+    constexpr int F = P - 1;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    for (int i = threadIdx.x; i < 8 * W * 256; i += kBlock) (&s_lut[0][0])[i] = a.lut[i];
+    __syncthreads();
+
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    const uint64_t tau = a.tau_ptr[0];
+    const float taus = threshold_score(tau);
+    const QueryMass mass = a.mass;
+    uint32_t fill = 0, rows = 0, deep = 0, full_rows = 0;
+    RowRegs<W, P, S> cur, nxt;
+    load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_row_scales<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    bool whole = false;
+    for (;;) {
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        const bool whole_next = deep * 4 > rows + 32;
+        if (has_next) {
+            const char* tn = a.tiles + (size_t)pn * tile_bytes;
+            load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
+            load_row_scales<W, P, S>(nxt, tn, wave, lane);
+            if (whole_next) load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+        }
+        float part[kItemsPerLane];
+        bool reach = false;
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            part[m] = fq_planes<W, P, MODE, 0, F>(cur, m, s_lut, 0.0f);
+            reach |= (bound_item_fq<W, P, MODE>(cur, m, part[m], mass) >= taus);
+        }
+        reach = __ballot(reach) != 0;
+        ++rows;
+        full_rows += (whole || reach) ? 1u : 0u;
+        if (reach) {
+            if (!whole) load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            ++deep;
+            float s[kItemsPerLane];
+            bool any = false;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                const float v = fq_planes<W, P, MODE, F, P>(cur, m, s_lut, part[m]);
+                s[m] = MODE == kModeDyadicNorm ? v * cur.a[0][m] : v;
+                any |= (s[m] >= taus);
+            }
+            if (__ballot(any)) {
+                const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m) {
+                    const uint64_t id = row_id + lane_item<W>(lane, m);
+                    bool ok = (s[m] >= taus) && (id < a.n_items);
+                    uint64_t key = 0;
+                    if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
+                    fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
+                }
+            }
+        }
+        if (!has_next) break;
+        cur = nxt;
+        whole = whole_next;
+        p = pn;
+    }
+    if (fill) stage_flush1(s_keys, fill, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
 }
 
 template <int W, int P, int MODE>
@@ -433,6 +540,19 @@ using FqFn = void (*)(const FqArgs);
 using DenseFqFn = void (*)(const char*, const Layout, const float*, uint64_t, uint64_t, float*);
 
 template <int W, int P>
+FqFn fq_prog_fn_m(int mode)
+{
+    if constexpr (P >= 2) {
+        if (mode == kModeScaled) return scan_exact_fq_prog<W, P, kModeScaled>;
+        if constexpr (dyadic_supported(W)) {
+            if (mode == kModeDyadicNorm) return scan_exact_fq_prog<W, P, kModeDyadicNorm>;
+            if (mode == kModeDyadic) return scan_exact_fq_prog<W, P, kModeDyadic>;
+        }
+    }
+    return nullptr;
+}
+
+template <int W, int P>
 FqFn fq_fn_m(int mode)
 {
     if (mode == kModeScaled) return scan_exact_fq<W, P, kModeScaled>;
@@ -462,9 +582,9 @@ hipError_t launch_scan_exact_fq_w<RBE_W>(const KernelSel& k, const FqArgs& a, ui
     FqFn fn = nullptr;
     switch (k.P) {
         case 1: fn = fq_fn_m<RBE_W, 1>(k.mode); break;
-        case 2: fn = fq_fn_m<RBE_W, 2>(k.mode); break;
-        case 3: fn = fq_fn_m<RBE_W, 3>(k.mode); break;
-        case 4: fn = fq_fn_m<RBE_W, 4>(k.mode); break;
+        case 2: fn = k.progressive ? fq_prog_fn_m<RBE_W, 2>(k.mode) : fq_fn_m<RBE_W, 2>(k.mode); break;
+        case 3: fn = k.progressive ? fq_prog_fn_m<RBE_W, 3>(k.mode) : fq_fn_m<RBE_W, 3>(k.mode); break;
+        case 4: fn = k.progressive ? fq_prog_fn_m<RBE_W, 4>(k.mode) : fq_fn_m<RBE_W, 4>(k.mode); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;

@@ -1029,3 +1029,36 @@ def test_progressive_scan_on_corpora_where_the_bound_cannot_help():
     for q in range(5):
         check_topk(planes, scales, qp[q], qs[q], k, on[q][0][0], on[q][1][0])
     rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("d,P,flags", [(64, 3, 0), (128, 4, 0), (64, 2, "dyadic"), (128, 3, "dyadic_cosine")])
+def test_progressive_scan_with_fp32_queries(d, P, flags):
+    """Hybrid scoring, one table pass per query: the last level is progressive too, with the table sums in place of
+    the popcounts; same ids and scores as with every plane read, and the oracle's hybrid score."""
+    N, k, Q = 300_011, 20, 4
+    c = rbe_synth.centres_numpy(2048, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=120 + d)
+    q = rbe_synth.vectors_numpy(Q, c, 0.3, seed=121)
+    q[1] *= 1e-3
+    q[2, ::2] = 0.0
+    planes, scales = oracle.encode(x, P)
+    if flags == 0:
+        ix = load_with_ratio(planes, scales, 8)
+    else:
+        scales = dyadic_weights(P, N)
+        if flags == "dyadic_cosine":
+            scales = oracle.fold_cosine(planes, scales)
+        ix = load_with_ratio(planes, None, 8, flags=rbe.RBE_DYADIC | (rbe.RBE_COSINE if flags == "dyadic_cosine" else 0))
+    rbe.rbe_debug_set_batch_path(ix, 1)         # the table path for every batch size
+    res = {}
+    for prog in (True, False):
+        rbe.rbe_debug_set_progressive(ix, prog)
+        res[prog] = [rbe.rbe_search_float(ix, q[i:i + 1], k) for i in range(Q)] + [rbe.rbe_search_float(ix, q, k)]
+        st = rbe.rbe_get_search_stats(ix)
+        assert (st["deep_rows"] > 0) == prog
+    for (i1, s1), (i0, s0) in zip(res[True], res[False]):
+        np.testing.assert_array_equal(i1, i0); np.testing.assert_array_equal(s1, s0)
+    for i in range(Q):
+        check_topk_float(planes, scales, q[i], k, res[True][i][0][0], res[True][i][1][0])
+        np.testing.assert_array_equal(res[True][Q][0][i], res[True][i][0][0])
+    rbe.rbe_free(ix)
