@@ -915,7 +915,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         sa.tau = ix->d_tau; sa.out = out;
         sa.p_begin = r.begin; sa.p_end = r.end;
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
-        sel.progressive = c.Q == 1 && !dense && ix->P >= 2 && ix->progressive != 0;
+        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0;
         sa.deep_rows = ix->d_status + 1;
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)

@@ -137,6 +137,93 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
     else mstage_drain(ms, a.out, lane);
 }
 
+// Several queries (2..7 in practice), P >= 2, progressive: one row in registers, planes 0 .. P-2 and the scales
+// first; every query forms its partial scores and bounds from them, and the first query for which some item of
+// the row can still reach the threshold has the row's last plane read (once per row), after which it and any
+// later such query continue their partial chains to the full scores.  Most (query, row) pairs stop at the bound:
+// a third fewer XOR/popcounts at P = 3, and most rows never read their last plane.  Appends what the batch form
+// of scan_exact appends.
+template <int W, int P, int PQ, int MODE>
+__global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a)
+{
+    extern __shared__ __align__(16) unsigned char s_dynamic[];
+    __shared__ uint32_t s_cnt_all[kWavesPerBlock][65];
+    constexpr int F = P - 1;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = reinterpret_cast<uint64_t*>(s_dynamic) + (size_t)wave * a.stage_entries;
+    const uint32_t n_sub = sub_queues_for(a.n_queries);
+    const uint32_t per_sub = a.stage_entries / n_sub;
+    const MultiStage ms{s_keys, s_cnt_all[wave], per_sub > 64u ? 64u : per_sub, 0u, n_sub};
+    s_cnt_all[wave][lane] = 0;
+    if (lane == 0) s_cnt_all[wave][64] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    const uint32_t G = gridDim.x;
+    constexpr int S = scale_arrays(MODE, P);
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+    const uint32_t nq = a.n_queries;
+    const float* masses = a.qcoef + (size_t)nq * (PQ + 1);
+    uint32_t full_rows = 0;
+    for (uint32_t p = a.p_begin + blockIdx.x; p < a.p_end; p += G) {
+        const char* tile = a.tiles + (size_t)p * tile_bytes;
+        RowRegs<W, P, S> cur;
+        load_row_planes<W, P, S, 0, F>(cur, tile, wave, lane);
+        load_row_scales<W, P, S>(cur, tile, wave, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        bool have_last = false;     // wave-uniform
+        QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+        uint64_t tau_n = a.tau[0];
+        QueryMass mass_n{masses[0], masses[1]};
+        for (uint32_t q = 0; q < nq; ++q) {
+            const QueryRegs<W, PQ> qr = qn;
+            const uint64_t tau = tau_n;
+            const QueryMass mass = mass_n;
+            if (q + 1 < nq) {
+                qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
+                tau_n = a.tau[q + 1];
+                mass_n = QueryMass{masses[2 * (q + 1)], masses[2 * (q + 1) + 1]};
+            }
+            const float taus = threshold_score(tau);
+            PartialScore part[kItemsPerLane];
+            bool reach = false;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                part[m] = partial_item<W, P, PQ, MODE, F>(cur, m, qr);
+                reach |= (bound_item<W, P, PQ, MODE, F>(cur, m, part[m], mass) >= taus);
+                if (m + 1 < kItemsPerLane) {     // one item's popcount chains at a time (see score_and_stage)
+#pragma unroll
+                    for (int j = 0; j < F; ++j)
+#pragma unroll
+                        for (int h = 0; h < 2 * W; ++h) {
+                            if (MODE == kModeScaled) asm volatile("" : "+v"(part[m].s), "+v"(cur.w[j][m + 1][h]));
+                            else asm volatile("" : "+v"(part[m].H), "+v"(cur.w[j][m + 1][h]));
+                        }
+                }
+            }
+            if (__ballot(reach)) {
+                if (!have_last) {
+                    load_row_planes<W, P, S, F, P>(cur, tile, wave, lane);
+                    have_last = true;
+                    ++full_rows;
+                }
+                float s[kItemsPerLane];
+                bool any = false;
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m) {
+                    s[m] = finish_item<W, P, PQ, MODE, F>(cur, m, qr, part[m]);
+                    any |= (s[m] >= taus);
+                }
+                if (__ballot(any)) stage_scores<W, false>(s, tau, taus, q, p, wave, lane, s_keys, ms, 0, a);
+            }
+        }
+    }
+    mstage_drain(ms, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+}
+
 // One query, P >= 2, progressive: the stream carries planes 0 .. F-1 (F = P - 1) and the scales only.  From them
 // every item gets an upper bound on its score (bound_item); only where some item of the wave's row can still
 // reach the threshold is the row's last plane read (a dependent load, exposed, but rare once the threshold is
@@ -455,13 +542,16 @@ using ScanFn = void (*)(const ScanArgs);
 using DenseFn = void (*)(const char*, const Layout, const uint32_t*, const float*, uint64_t, uint64_t, float*);
 
 template <int W, int P, int PQ>
-ScanFn prog_fn_m(int mode)
+ScanFn prog_fn_m(int mode, bool single)
 {
     if constexpr (P >= 2) {
-        if (mode == kModeScaled) return scan_exact_prog<W, P, PQ, kModeScaled>;
+        if (mode == kModeScaled)
+            return single ? scan_exact_prog<W, P, PQ, kModeScaled> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
         if constexpr (dyadic_supported(W)) {
-            if (mode == kModeDyadicNorm) return scan_exact_prog<W, P, PQ, kModeDyadicNorm>;
-            if (mode == kModeDyadic) return scan_exact_prog<W, P, PQ, kModeDyadic>;
+            if (mode == kModeDyadicNorm)
+                return single ? scan_exact_prog<W, P, PQ, kModeDyadicNorm> : scan_exact_batch_prog<W, P, PQ, kModeDyadicNorm>;
+            if (mode == kModeDyadic)
+                return single ? scan_exact_prog<W, P, PQ, kModeDyadic> : scan_exact_batch_prog<W, P, PQ, kModeDyadic>;
         }
     }
     return nullptr;
@@ -503,9 +593,9 @@ DenseFn dense_fn_m(int mode)
 ScanFn prog_fn(const KernelSel& k)
 {
     switch (k.P) {
-        case 2: RBE_SWITCH_PQ(prog_fn_m, 2, k.mode)
-        case 3: RBE_SWITCH_PQ(prog_fn_m, 3, k.mode)
-        case 4: RBE_SWITCH_PQ(prog_fn_m, 4, k.mode)
+        case 2: RBE_SWITCH_PQ(prog_fn_m, 2, k.mode, k.single)
+        case 3: RBE_SWITCH_PQ(prog_fn_m, 3, k.mode, k.single)
+        case 4: RBE_SWITCH_PQ(prog_fn_m, 4, k.mode, k.single)
         default: return nullptr;
     }
 }

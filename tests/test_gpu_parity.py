@@ -1062,3 +1062,36 @@ def test_progressive_scan_with_fp32_queries(d, P, flags):
         check_topk_float(planes, scales, q[i], k, res[True][i][0][0], res[True][i][1][0])
         np.testing.assert_array_equal(res[True][Q][0][i], res[True][i][0][0])
     rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("d,P,Pq,flags", [(64, 3, 3, 0), (128, 4, 2, 0), (64, 2, 3, "dyadic"), (128, 3, 3, "dyadic_cosine")])
+def test_progressive_scan_for_small_batches(d, P, Pq, flags):
+    """2..7 queries per call (and any batch on the XOR/popcount kernel): the last level forms partial scores from all
+    planes but the last for every query and reads a row's last plane once, for the first query that needs it.
+    Same ids and scores with the switch on and off, and against the oracle."""
+    N, k = 350_003, 30
+    c = rbe_synth.centres_numpy(2048, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=140 + d)
+    planes, scales = oracle.encode(x, P)
+    qpl, qsl = oracle.encode(rbe_synth.vectors_numpy(16, c, 0.3, seed=141), Pq)
+    qp, qs = np.ascontiguousarray(qpl.transpose(1, 0, 2)), np.ascontiguousarray(qsl.T)
+    if flags == 0:
+        ix = load_with_ratio(planes, scales, 8)
+    else:
+        scales = dyadic_weights(P, N)
+        if flags == "dyadic_cosine":
+            scales = oracle.fold_cosine(planes, scales)
+        ix = load_with_ratio(planes, None, 8, flags=rbe.RBE_DYADIC | (rbe.RBE_COSINE if flags == "dyadic_cosine" else 0))
+        qs = None
+    qs_o = qs if qs is not None else np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (16, 1))
+    rbe.rbe_debug_set_batch_path(ix, 1)
+    for Q in (2, 5, 7, 16):
+        res = {}
+        for prog in (True, False):
+            rbe.rbe_debug_set_progressive(ix, prog)
+            res[prog] = rbe.rbe_search(ix, qp[:Q], None if qs is None else qs[:Q], k)
+            assert (rbe.rbe_get_search_stats(ix)["deep_rows"] > 0) == prog
+        np.testing.assert_array_equal(res[True][0], res[False][0])
+        np.testing.assert_array_equal(res[True][1], res[False][1])
+        check_batch(planes, scales, qp[:Q], qs_o[:Q], k, res[True][0], res[True][1])
+    rbe.rbe_free(ix)
