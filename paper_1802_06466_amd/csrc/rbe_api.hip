@@ -85,6 +85,7 @@ struct rbe_index {
     float* d_unscale = nullptr;     // [Q]
     float* h_unscale = nullptr;
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
+    float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize)
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
     float fq_mass[RBE_MAX_QUERIES][2] = {};   // fp32 queries: {x, 2^-19 x}, x >= sum_d |q_d| (1 + 2^-18): bounds any plane's table sum
@@ -764,6 +765,11 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
                            ix->d_tiles, ix->geom, n_slots);
         HIP_TRY(hipGetLastError());
     }
+    if (ix->geom.S > 0) {
+        HIP_TRY(hipMalloc(&ix->d_row_amax, (size_t)ix->layout.n_tiles * (kTileItems / kRow) * sizeof(float)));
+        hipLaunchKernelGGL(rbe::row_scale_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_row_amax);
+        HIP_TRY(hipGetLastError());
+    }
     HIP_TRY(hipStreamSynchronize(st));
     ix->ready = 1;
     return RBE_OK;
@@ -788,6 +794,7 @@ void rbe_free(rbe_index* ix)
     if (!ix) return;
     free_workspace(ix);
     (void)hipFree(ix->d_tiles);
+    (void)hipFree(ix->d_row_amax);
     (void)hipFree(ix->d_count);
     (void)hipFree(ix->d_tau);
     (void)hipFree(ix->d_kmax);
@@ -888,7 +895,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
             FqArgs fa;
             fa.tiles = ix->d_tiles; fa.layout = ix->layout; fa.n_items = ix->n_items;
             fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
-            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1;
+            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1; fa.row_amax = ix->d_row_amax;
             fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q, ix->d_kmax + q, c.cap};
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
@@ -916,7 +923,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         sa.p_begin = r.begin; sa.p_end = r.end;
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0;
-        sa.deep_rows = ix->d_status + 1;
+        sa.deep_rows = ix->d_status + 1; sa.row_amax = ix->d_row_amax;
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
         sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);

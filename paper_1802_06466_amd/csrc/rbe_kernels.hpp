@@ -125,13 +125,13 @@ __device__ __forceinline__ void load_row_planes(RowRegs<W, P, S>& r, const char*
     }
 }
 
-// ... and its scales.
-template <int W, int P, int S>
+// ... and its scale arrays [J0, J1).
+template <int W, int P, int S, int J0 = 0, int J1 = S>
 __device__ __forceinline__ void load_row_scales(RowRegs<W, P, S>& r, const char* __restrict__ tile, int wave, int lane)
 {
     const TileGeom g{(uint32_t)W, (uint32_t)P, (uint32_t)S};
 #pragma unroll
-    for (int j = 0; j < S; ++j) {
+    for (int j = J0; j < J1; ++j) {
         const float* sj = reinterpret_cast<const float*>(tile + g.scales_offset()) + j * kTileItems + wave * kRow;
         if (W == 1) {
 #pragma unroll
@@ -297,6 +297,29 @@ __device__ __forceinline__ float bound_item(const RowRegs<W, P, scale_arrays(MOD
     }
 }
 
+// The same bound with F = P - 1 and the last scale array (a_{P-1}; the single inverse-norm array of
+// kModeDyadicNorm) replaced by its largest value over the wave's row, so that the stream need not carry that
+// array either.  A product of an upper bound and a larger non-negative factor is an upper bound only while the
+// first is positive; a score whose bound is negative is bounded by 0.
+template <int W, int P, int PQ, int MODE>
+__device__ __forceinline__ float bound_item_rowmax(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m, PartialScore part,
+                                                   const QueryMass& mass, float amax)
+{
+    static_assert(P >= 2, "a bound needs planes to compute and a plane to skip");
+    if (MODE == kModeScaled) {
+        float all = amax;
+#pragma unroll
+        for (int j = 0; j < P - 1; ++j) all += r.a[j][m];
+        return __fmaf_rn(all, mass.y, __fmaf_rn(amax, mass.x, part.s));
+    } else {
+        const uint32_t H = (part.H << 1) + __float_as_uint(mass.x);
+        const int all = 64 * W * ((1 << P) - 1) * ((1 << PQ) - 1);
+        const float f = (float)(all - 2 * (int)H) * (1.0f / (float)(1 << (P + PQ - 2)));   // exact
+        if (MODE == kModeDyadic) return f;
+        return f > 0.0f ? f * amax : 0.0f;
+    }
+}
+
 // ---------------------------------------------------------------- per-wave candidate staging
 // Survivors are first written to a queue in LDS that belongs to one wave (no
 // atomics, no workgroup barrier), and moved to the query's global candidate list
@@ -449,6 +472,8 @@ struct ScanArgs {
     CandList out;
     uint32_t p_begin, p_end;  // physical tile range this launch covers
     uint32_t* deep_rows;      // progressive scan: += rows whose planes 1.. had to be read
+    const float* row_amax;    // [physical tile][4 rows] largest value of the last scale array over the row (one-query
+                              // progressive scans; unused where there is no scale array)
     uint32_t stage_entries;   // several queries: LDS queue entries per wave (512..4096), split into sub-queues
 };
 
@@ -465,6 +490,7 @@ struct FqArgs {
     uint32_t p_begin, p_end;
     QueryMass mass;           // progressive scan: x >= sum_d |q_d| plus the rounding of the table sums, y = 2^-19 x
     uint32_t* deep_rows;      // progressive scan: += rows whose last plane had to be read
+    const float* row_amax;    // as in ScanArgs
 };
 
 // Batched scan on the matrix cores (rbe_batch.hip).

@@ -414,4 +414,18 @@ __global__ void fold_cosine(char* __restrict__ tiles, const TileGeom g, uint64_t
     }
 }
 
+// Largest value of the last scale array over each row of 256 items: out[physical tile][row].  One workgroup of
+// 256 threads per tile, one wave per row.  The one-query progressive scans bound the last plane's contribution
+// with it instead of reading that array.
+__global__ void row_scale_max(const char* __restrict__ tiles, const TileGeom g, float* __restrict__ out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float* sc = reinterpret_cast<const float*>(tiles + (size_t)blockIdx.x * g.tile_bytes() + g.scales_offset()) +
+                      (size_t)(g.S - 1) * kTileItems + wave * kRow;
+    float mx = 0.0f;
+    for (int m = 0; m < kRow / 64; ++m) mx = fmaxf(mx, sc[m * 64 + lane]);
+    for (int d = 32; d > 0; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
+    if (lane == 0) out[(size_t)blockIdx.x * kWavesPerBlock + wave] = mx;
+}
+
 }  // namespace rbe

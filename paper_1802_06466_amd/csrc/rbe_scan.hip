@@ -257,10 +257,13 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
     const uint64_t tau0 = a.tau[0];
     const float taus0 = threshold_score(tau0);
 
+    // the last scale array stays out of the stream as well: its largest value over the row stands in for it
+    constexpr int SS = S > 0 ? S - 1 : 0;
     RowRegs<W, P, S> cur, nxt;
     load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
-    load_row_scales<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
-    bool whole = false;    // wave-uniform: cur holds every plane already
+    load_row_scales<W, P, S, 0, SS>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    float amax = S > 0 ? a.row_amax[(size_t)p * kWavesPerBlock + wave] : 0.0f, amax_n = 0.0f;
+    bool whole = false;    // wave-uniform: cur holds every plane and scale already
     for (;;) {
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
@@ -268,21 +271,28 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
         if (has_next) {
             const char* tn = a.tiles + (size_t)pn * tile_bytes;
             load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
-            load_row_scales<W, P, S>(nxt, tn, wave, lane);
-            if (whole_next) load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+            load_row_scales<W, P, S, 0, SS>(nxt, tn, wave, lane);
+            if (S > 0) amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+            if (whole_next) {
+                load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+                load_row_scales<W, P, S, SS, S>(nxt, tn, wave, lane);
+            }
         }
         PartialScore part[kItemsPerLane];
         bool reach = false;
 #pragma unroll
         for (int m = 0; m < kItemsPerLane; ++m) {
             part[m] = partial_item<W, P, PQ, MODE, F>(cur, m, q0);
-            reach |= (bound_item<W, P, PQ, MODE, F>(cur, m, part[m], mass) >= taus0);
+            reach |= (bound_item_rowmax<W, P, PQ, MODE>(cur, m, part[m], mass, amax) >= taus0);
         }
         reach = __ballot(reach) != 0;
         ++rows;
         full_rows += (whole || reach) ? 1u : 0u;
         if (reach) {
-            if (!whole) load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            if (!whole) {
+                load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+                load_row_scales<W, P, S, SS, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            }
             ++deep;
             float s[kItemsPerLane];
             bool any = false;
@@ -295,6 +305,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
         }
         if (!has_next) break;
         cur = nxt;
+        amax = amax_n;
         whole = whole_next;
         p = pn;
     }
@@ -335,17 +346,18 @@ __device__ __forceinline__ float score_item_fq(const RowRegs<W, P, scale_arrays(
     return MODE == kModeDyadicNorm ? s * r.a[0][m] : s;
 }
 
-// Upper bound on score_item_fq from planes 0 .. P-2 (see bound_item): no plane's table sum exceeds the query's
-// mass sum_d |q_d| (mass.x, rounding of the table entries and of their sum included), the last plane's weight
-// is a_{P-1} or 2^-(P-1), and mass.y per unit of weight covers the roundings of the chain.
+// Upper bound on score_item_fq from planes 0 .. P-2 (see bound_item_rowmax): no plane's table sum exceeds the
+// query's mass sum_d |q_d| (mass.x, rounding of the table entries and of their sum included), the last plane's
+// weight is at most amax (the row's largest a_{P-1}) or is 2^-(P-1), and mass.y per unit of weight covers the
+// roundings of the chain.  kModeDyadicNorm: the row's largest inverse norm multiplies a positive bound.
 template <int W, int P, int MODE>
 __device__ __forceinline__ float bound_item_fq(const RowRegs<W, P, scale_arrays(MODE, P)>& r, int m, float part,
-                                               const QueryMass& mass)
+                                               const QueryMass& mass, float amax)
 {
     float tail, all;
     if (MODE == kModeScaled) {
-        tail = r.a[P - 1][m];
-        all = tail;
+        tail = amax;
+        all = amax;
 #pragma unroll
         for (int j = 0; j < P - 1; ++j) all += r.a[j][m];
     } else {
@@ -353,7 +365,8 @@ __device__ __forceinline__ float bound_item_fq(const RowRegs<W, P, scale_arrays(
         all = 2.0f;
     }
     const float ub = __fmaf_rn(all, mass.y, __fmaf_rn(tail, mass.x, part));
-    return MODE == kModeDyadicNorm ? ub * r.a[0][m] : ub;
+    if (MODE == kModeDyadicNorm) return ub > 0.0f ? ub * amax : 0.0f;
+    return ub;
 }
 
 template <int W, int P, int MODE>
@@ -430,9 +443,11 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
     const float taus = threshold_score(tau);
     const QueryMass mass = a.mass;
     uint32_t fill = 0, rows = 0, deep = 0, full_rows = 0;
+    constexpr int SS = S > 0 ? S - 1 : 0;
     RowRegs<W, P, S> cur, nxt;
     load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
-    load_row_scales<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_row_scales<W, P, S, 0, SS>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    float amax = S > 0 ? a.row_amax[(size_t)p * kWavesPerBlock + wave] : 0.0f, amax_n = 0.0f;
     bool whole = false;
     for (;;) {
         const uint32_t pn = p + G;
@@ -441,21 +456,28 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
         if (has_next) {
             const char* tn = a.tiles + (size_t)pn * tile_bytes;
             load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
-            load_row_scales<W, P, S>(nxt, tn, wave, lane);
-            if (whole_next) load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+            load_row_scales<W, P, S, 0, SS>(nxt, tn, wave, lane);
+            if (S > 0) amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+            if (whole_next) {
+                load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+                load_row_scales<W, P, S, SS, S>(nxt, tn, wave, lane);
+            }
         }
         float part[kItemsPerLane];
         bool reach = false;
 #pragma unroll
         for (int m = 0; m < kItemsPerLane; ++m) {
             part[m] = fq_planes<W, P, MODE, 0, F>(cur, m, s_lut, 0.0f);
-            reach |= (bound_item_fq<W, P, MODE>(cur, m, part[m], mass) >= taus);
+            reach |= (bound_item_fq<W, P, MODE>(cur, m, part[m], mass, amax) >= taus);
         }
         reach = __ballot(reach) != 0;
         ++rows;
         full_rows += (whole || reach) ? 1u : 0u;
         if (reach) {
-            if (!whole) load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            if (!whole) {
+                load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+                load_row_scales<W, P, S, SS, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            }
             ++deep;
             float s[kItemsPerLane];
             bool any = false;
@@ -479,6 +501,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
         }
         if (!has_next) break;
         cur = nxt;
+        amax = amax_n;
         whole = whole_next;
         p = pn;
     }

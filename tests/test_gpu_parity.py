@@ -1008,7 +1008,9 @@ def test_progressive_scan_changes_nothing_but_the_bytes_read(d, P, Pq, flags):
     qs_o = qs if qs is not None else np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
     for q in range(Q):
         check_topk(planes, scales, qp[q], qs_o[q], k, on[q][0][0], on[q][1][0])
-    assert 0 < np.mean(shares) < 0.5, shares       # rows of the query's own cluster are read in full, most others not
+    # rows of the query's own cluster are read in full, most others not (with two planes and general scales the
+    # left-out plane weighs about 0.6 of the first one: the bound is correct but prunes little)
+    assert 0 < np.mean(shares) < (0.5 if (P >= 3 or flags != 0) else 1.0), shares
     rbe.rbe_free(ix)
 
 
@@ -1094,4 +1096,37 @@ def test_progressive_scan_for_small_batches(d, P, Pq, flags):
         np.testing.assert_array_equal(res[True][0], res[False][0])
         np.testing.assert_array_equal(res[True][1], res[False][1])
         check_batch(planes, scales, qp[:Q], qs_o[:Q], k, res[True][0], res[True][1])
+    rbe.rbe_free(ix)
+
+
+def test_progressive_scan_honours_large_last_scales():
+    """The one-query progressive scans do not read the last scale array; the row's largest value stands in for
+    it.  A few items whose last scale is 50x the usual one (and which owe their rank to it) must still be found,
+    with binary and with fp32 queries."""
+    N, d, P, k = 300_007, 64, 3, 40
+    c = rbe_synth.centres_numpy(2048, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=160)
+    planes, scales = oracle.encode(x, P)
+    rng = np.random.default_rng(161)
+    big = rng.choice(N, size=300, replace=False)
+    scales[P - 1, big] *= 50.0
+    qx = rbe_synth.vectors_numpy(4, c, 0.3, seed=162)
+    qpl, qsl = oracle.encode(qx, P)
+    qp, qs = np.ascontiguousarray(qpl.transpose(1, 0, 2)), np.ascontiguousarray(qsl.T)
+    ix = load_with_ratio(planes, scales, 8)
+    on, off, shares = _search_both_ways(ix, qp, qs, k)
+    hits = 0
+    for q in range(4):
+        np.testing.assert_array_equal(on[q][0], off[q][0]); np.testing.assert_array_equal(on[q][1], off[q][1])
+        check_topk(planes, scales, qp[q], qs[q], k, on[q][0][0], on[q][1][0])
+        hits += len(set(on[q][0][0].tolist()) & set(big.tolist()))
+        rbe.rbe_debug_set_batch_path(ix, 1)
+        i1, s1 = rbe.rbe_search_float(ix, qx[q:q + 1], k)
+        rbe.rbe_debug_set_progressive(ix, False)
+        i0, s0 = rbe.rbe_search_float(ix, qx[q:q + 1], k)
+        rbe.rbe_debug_set_progressive(ix, True)
+        rbe.rbe_debug_set_batch_path(ix, 0)
+        np.testing.assert_array_equal(i1, i0); np.testing.assert_array_equal(s1, s0)
+        check_topk_float(planes, scales, qx[q], k, i1[0], s1[0])
+    assert hits > 0          # the boosted items do reach the top k
     rbe.rbe_free(ix)
