@@ -188,14 +188,15 @@ def main():
     st = r1["stats"]
     last_items = st["items_scanned"][-1] if st["n_levels"] else N
     scan_avg_ms = float(r1["scan_ms"].mean()) if r1["scan_ms"].size else float("nan")
-    # The finest-level scan of one query is progressive: it reads every plane and scale array but the last of
-    # every item (and one precomputed fp32 per row of 256 items, the row's largest last scale), and the last plane
-    # and scale only of the rows that those cannot rule out (the library counts them).  `achieved` is priced on the
-    # bytes the kernel reads; the rate on the bytes of all planes is reported beside it.
+    # The finest-level scan of one query is progressive: of every item it reads every plane but the last and
+    # bfloat16 copies of the matching scale arrays (plus one precomputed fp32 per row of 256 items, the row's
+    # largest last scale); of the rows that those cannot rule out (the library counts them) it also reads the last
+    # plane and the P fp32 scale arrays.  `achieved` is priced on the bytes the kernel reads; the rate on the bytes
+    # of all planes is reported beside it.
     deep_avg = float(r1["deep_rows"].mean()) if r1["deep_rows"].size else 0.0
-    deep_row_bytes = 256 * (8 * W + 4)
+    deep_row_bytes = 256 * (8 * W + 4 * P)
     if P >= 2:
-        stream_bytes_per_item = (P - 1) * (8 * W + 4)
+        stream_bytes_per_item = (P - 1) * (8 * W + 2)
         bytes_read = last_items * stream_bytes_per_item + (last_items // 256) * 4 + deep_avg * deep_row_bytes
     else:
         stream_bytes_per_item = bytes_per_item
@@ -310,7 +311,9 @@ def main():
         torch.cuda.synchronize()
         h_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         # progressive like the binary-query scan: bytes read = streamed planes and scales + the last plane of some rows
-        h_bytes = last_items * stream_bytes_per_item + ((last_items // 256) * 4 + float(np.mean(h_deep)) * deep_row_bytes if P >= 2 else 0.0)
+        # (the fp32-query scan streams the fp32 scale arrays 0 .. P-2 themselves)
+        h_bytes = (last_items * (P - 1) * (8 * W + 4) + (last_items // 256) * 4 + float(np.mean(h_deep)) * 256 * (8 * W + 4)
+                   if P >= 2 else last_items * bytes_per_item)
         h_gbs = h_bytes / (float(np.mean(h_scan)) * 1e-3) / 1e9
         out["hybrid_float_query"] = {"ms_per_step": h_ms, "value": N / (h_ms * 1e-3), "unit": "candidates/s",
                                      "scan_kernel_ms": float(np.mean(h_scan)), "hbm_gbs": h_gbs,

@@ -85,6 +85,7 @@ struct rbe_index {
     float* d_unscale = nullptr;     // [Q]
     float* h_unscale = nullptr;
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
+    uint32_t* d_hints = nullptr;    // general scales, P >= 2: bfloat16 copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
     float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize)
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
@@ -770,6 +771,12 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
         hipLaunchKernelGGL(rbe::row_scale_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_row_amax);
         HIP_TRY(hipGetLastError());
     }
+    if (ix->mode == rbe::kModeScaled && ix->P >= 2) {
+        HIP_TRY(hipMalloc(&ix->d_hints, (size_t)ix->layout.n_tiles * kTileItems / 2 * (ix->P - 1) * sizeof(uint32_t)));
+        if (ix->W == 1) hipLaunchKernelGGL(rbe::scale_hints<1>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_hints);
+        else hipLaunchKernelGGL(rbe::scale_hints<2>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_hints);
+        HIP_TRY(hipGetLastError());
+    }
     HIP_TRY(hipStreamSynchronize(st));
     ix->ready = 1;
     return RBE_OK;
@@ -795,6 +802,7 @@ void rbe_free(rbe_index* ix)
     free_workspace(ix);
     (void)hipFree(ix->d_tiles);
     (void)hipFree(ix->d_row_amax);
+    (void)hipFree(ix->d_hints);
     (void)hipFree(ix->d_count);
     (void)hipFree(ix->d_tau);
     (void)hipFree(ix->d_kmax);
@@ -923,7 +931,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         sa.p_begin = r.begin; sa.p_end = r.end;
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0;
-        sa.deep_rows = ix->d_status + 1; sa.row_amax = ix->d_row_amax;
+        sa.deep_rows = ix->d_status + 1; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints;
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
         sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);

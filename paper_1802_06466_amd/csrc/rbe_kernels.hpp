@@ -26,6 +26,7 @@ constexpr int kItemsPerLane = 4;
 static_assert(kRow * kWavesPerBlock == kTileItems, "a workgroup step covers one tile");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------- keys
@@ -227,7 +228,7 @@ __device__ __forceinline__ PartialScore score_planes(const RowRegs<W, P, scale_a
 {
 #pragma unroll
     for (int j = J0; j < J1; ++j) {
-        if (MODE == kModeScaled) {
+        if constexpr (MODE == kModeScaled) {
             float t = q.bias;
 #pragma unroll
             for (int i = 0; i < PQ; ++i) {
@@ -283,7 +284,7 @@ __device__ __forceinline__ float bound_item(const RowRegs<W, P, scale_arrays(MOD
                                             const QueryMass& mass)
 {
     static_assert(F >= 1 && F < P, "a bound needs planes to compute and planes to skip");
-    if (MODE == kModeScaled) {
+    if constexpr (MODE == kModeScaled) {
         float tail = r.a[F][m];
 #pragma unroll
         for (int j = F + 1; j < P; ++j) tail += r.a[j][m];
@@ -306,7 +307,7 @@ __device__ __forceinline__ float bound_item_rowmax(const RowRegs<W, P, scale_arr
                                                    const QueryMass& mass, float amax)
 {
     static_assert(P >= 2, "a bound needs planes to compute and a plane to skip");
-    if (MODE == kModeScaled) {
+    if constexpr (MODE == kModeScaled) {
         float all = amax;
 #pragma unroll
         for (int j = 0; j < P - 1; ++j) all += r.a[j][m];
@@ -474,6 +475,7 @@ struct ScanArgs {
     uint32_t* deep_rows;      // progressive scan: += rows whose planes 1.. had to be read
     const float* row_amax;    // [physical tile][4 rows] largest value of the last scale array over the row (one-query
                               // progressive scans; unused where there is no scale array)
+    const uint32_t* hints;    // general scales: bfloat16 copies of the scale arrays 0 .. P-2 in lane order (scale_hints)
     uint32_t stage_entries;   // several queries: LDS queue entries per wave (512..4096), split into sub-queues
 };
 

@@ -428,4 +428,26 @@ __global__ void row_scale_max(const char* __restrict__ tiles, const TileGeom g, 
     if (lane == 0) out[(size_t)blockIdx.x * kWavesPerBlock + wave] = mx;
 }
 
+// Half-precision copies (bfloat16, round to nearest even) of the scale arrays 0 .. S-2, in the order in which the
+// lanes of the one-query progressive scan want them: out[physical tile][wave][lane][2 (S-1) words], halfword
+// 4 j + m of a lane = array j, the lane's item m (lane_item).  The scan bounds the partial score with them and
+// reads the fp32 arrays only for the rows it scores in full.
+template <int W>
+__global__ void scale_hints(const char* __restrict__ tiles, const TileGeom g, uint32_t* __restrict__ out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float* sc = reinterpret_cast<const float*>(tiles + (size_t)blockIdx.x * g.tile_bytes() + g.scales_offset()) + wave * kRow;
+    const uint32_t nw = 2u * (g.S - 1u);
+    uint32_t* dst = out + (((size_t)blockIdx.x * kWavesPerBlock + wave) * 64 + lane) * nw;
+    for (uint32_t j = 0; j + 1 < g.S; ++j) {
+        uint32_t h[kItemsPerLane];
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            const uint32_t b = __float_as_uint(sc[(size_t)j * kTileItems + lane_item<W>(lane, m)]);
+            h[m] = (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;        // finite, non-negative inputs
+        }
+        dst[2 * j] = h[0] | (h[1] << 16);
+        dst[2 * j + 1] = h[2] | (h[3] << 16);
+    }
+}
+
 }  // namespace rbe

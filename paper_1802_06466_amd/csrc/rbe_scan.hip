@@ -314,6 +314,125 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 }
 
 
+// scan_exact_prog for general scales: the stream carries no fp32 scale array at all.  The scale arrays 0 .. P-2
+// come as bfloat16 copies (a_j = h_j (1 +- 2^-9), so a_j t_j <= h_j t_j + 2^-8 h_j |t_j|; the kernel allows
+// 2^-7), the last one as its largest value over the row.  A row that the bound lets through reads its last plane
+// and its P fp32 scale arrays and is scored from scratch by score_item, so what is appended is still exactly
+// what scan_exact appends.  16 + 4 instead of 16 + 8 streamed bytes per item at d = 64, P = 3.
+// In the whole-row fallback the bound is evaluated for one row in eight only (it shares nothing with the exact
+// score here), enough to notice when it starts to prune again.
+template <int W, int P, int PQ>
+__global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
+{
+    constexpr int MODE = kModeScaled;
+    constexpr int S = P, F = P - 1;
+    constexpr int NW = 2 * (S - 1);            // hint words per lane and row
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    const MultiStage ms{};
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0;
+    const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+    const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
+    const QueryMass mass{pm[0], pm[1]};
+    const uint64_t tau0 = a.tau[0];
+    const float taus0 = threshold_score(tau0);
+
+    struct Hints { uint32_t w[NW]; };
+    auto load_hints = [&](Hints& h, uint32_t tile_p) {
+        const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
+        if constexpr (NW == 2) {
+            const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+            h.w[0] = v.x; h.w[1] = v.y;
+        } else {
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+            h.w[0] = v.x; h.w[1] = v.y; h.w[2] = v.z; h.w[3] = v.w;
+            if constexpr (NW == 6) {
+                const u32x2 v2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src + 4));
+                h.w[4] = v2.x; h.w[5] = v2.y;
+            }
+        }
+    };
+    auto hint = [](const Hints& h, int j, int m) {   // bfloat16 -> fp32
+        const uint32_t w = h.w[2 * j + (m >> 1)];
+        return __uint_as_float((m & 1) ? (w & 0xffff0000u) : (w << 16));
+    };
+
+    RowRegs<W, P, S> cur, nxt;
+    Hints hc, hn;
+    load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_hints(hc, p);
+    float amax = a.row_amax[(size_t)p * kWavesPerBlock + wave], amax_n = 0.0f;
+    bool whole = false;    // wave-uniform: cur holds every plane and scale already
+    for (;;) {
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        const bool whole_next = passed * 4 > probed + 32;     // wave-uniform
+        if (has_next) {
+            const char* tn = a.tiles + (size_t)pn * tile_bytes;
+            load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
+            load_hints(hn, pn);
+            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+            if (whole_next) {
+                load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+                load_row_scales<W, P, S>(nxt, tn, wave, lane);
+            }
+        }
+        bool reach = true;
+        if (!whole || (rows & 7u) == 0u) {
+            reach = false;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                float s = 0.0f, mag = 0.0f, all = amax;
+#pragma unroll
+                for (int j = 0; j < F; ++j) {
+                    float t = q0.bias;
+#pragma unroll
+                    for (int i = 0; i < PQ; ++i) {
+                        uint32_t pc = 0;
+#pragma unroll
+                        for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[j][m][h] ^ q0.w[i][h]);
+                        t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                    }
+                    const float hj = hint(hc, j, m);
+                    s = __fmaf_rn(hj, t, s);
+                    mag = __fmaf_rn(hj, __builtin_fabsf(t), mag);
+                    all += hj;
+                }
+                const float ub = __fmaf_rn(mag, 0.0078125f, __fmaf_rn(1.0078125f * all, mass.y, __fmaf_rn(amax, mass.x, s)));
+                reach |= (ub >= taus0);
+            }
+            reach = __ballot(reach) != 0;
+            ++probed;
+            passed += reach ? 1u : 0u;
+        }
+        ++rows;
+        full_rows += (whole || reach) ? 1u : 0u;
+        if (reach) {
+            if (!whole) {
+                load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+                load_row_scales<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            }
+            fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
+        }
+        if (!has_next) break;
+        cur = nxt;
+        hc = hn;
+        amax = amax_n;
+        whole = whole_next;
+        p = pn;
+    }
+    if (fill) stage_flush1(s_keys, fill, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+}
+
 // ---------------------------------------------------------------- hybrid scoring (fp32 query)
 // t_j = sum over the 8W bytes of plane j of lut[p][byte], accumulated in fp32 in byte order;
 // kModeScaled: s = sum_j fma(a_j, t_j, s).  Dyadic modes: s = (sum_j 2^-j t_j) [* the item's scale].
@@ -569,7 +688,7 @@ ScanFn prog_fn_m(int mode, bool single)
 {
     if constexpr (P >= 2) {
         if (mode == kModeScaled)
-            return single ? scan_exact_prog<W, P, PQ, kModeScaled> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
+            return single ? scan_exact_prog_hint<W, P, PQ> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
         if constexpr (dyadic_supported(W)) {
             if (mode == kModeDyadicNorm)
                 return single ? scan_exact_prog<W, P, PQ, kModeDyadicNorm> : scan_exact_batch_prog<W, P, PQ, kModeDyadicNorm>;
