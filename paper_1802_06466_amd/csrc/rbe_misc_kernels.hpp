@@ -444,6 +444,7 @@ __global__ void scale_hints(const char* __restrict__ tiles, const TileGeom g, ui
         for (int m = 0; m < kItemsPerLane; ++m) {
             const uint32_t b = __float_as_uint(sc[(size_t)j * kTileItems + lane_item<W>(lane, m)]);
             h[m] = (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;        // finite, non-negative inputs
+            if (h[m] > 0x7f7fu) h[m] = 0x7f7fu;                   // never round up to infinity (2^-8 below at most)
         }
         dst[2 * j] = h[0] | (h[1] << 16);
         dst[2 * j + 1] = h[2] | (h[3] << 16);
