@@ -406,8 +406,9 @@ def rbe_debug_query_mass(q_planes, q_scales, dim: int, dyadic: bool = False):
     return float(out[0]), float(out[1])
 
 
-def rbe_debug_set_progressive(ix: Index, enabled: bool):
-    _check(load_library().rbe_debug_set_progressive(ix.handle, 1 if enabled else 0))
+def rbe_debug_set_progressive(ix: Index, enabled):
+    """False/0 = off, True/1 = on, 2 = on without the half-precision scale copies."""
+    _check(load_library().rbe_debug_set_progressive(ix.handle, int(enabled)))
 
 
 def rbe_debug_set_batch_path(ix: Index, path: int):

@@ -772,7 +772,12 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
         HIP_TRY(hipGetLastError());
     }
     if (ix->mode == rbe::kModeScaled && ix->P >= 2) {
-        HIP_TRY(hipMalloc(&ix->d_hints, (size_t)ix->layout.n_tiles * kTileItems / 2 * (ix->P - 1) * sizeof(uint32_t)));
+        // optional: without them the one-query scan streams the fp32 scale arrays 0 .. P-2 instead
+        const hipError_t eh = hipMalloc(&ix->d_hints, (size_t)ix->layout.n_tiles * kTileItems / 2 * (ix->P - 1) * sizeof(uint32_t));
+        if (eh == hipErrorOutOfMemory) { (void)hipGetLastError(); ix->d_hints = nullptr; }
+        else HIP_TRY(eh);
+    }
+    if (ix->d_hints) {
         if (ix->W == 1) hipLaunchKernelGGL(rbe::scale_hints<1>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_hints);
         else hipLaunchKernelGGL(rbe::scale_hints<2>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_hints);
         HIP_TRY(hipGetLastError());
@@ -931,6 +936,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         sa.p_begin = r.begin; sa.p_end = r.end;
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0;
+        sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
         sa.deep_rows = ix->d_status + 1; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints;
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
@@ -1176,7 +1182,7 @@ int rbe_debug_query_mass(const uint64_t* q_planes, const float* q_scales, uint32
 int rbe_debug_set_progressive(rbe_index* ix, int enabled)
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
-    ix->progressive = enabled ? 1 : 0;
+    ix->progressive = enabled == 2 ? 2 : (enabled ? 1 : 0);
     return RBE_OK;
 }
 

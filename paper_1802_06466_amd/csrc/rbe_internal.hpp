@@ -14,7 +14,8 @@ struct KernelSel {
     int mode;         // kModeScaled / kModeDyadicNorm / kModeDyadic
     bool single;      // one query per call
     uint32_t qlen = 1;   // near-lossless mode: length of the per-group priority queue (1 or 2)
-    bool progressive = false;   // exact mode, one query, P >= 2: read planes 1.. only where plane 0 cannot rule a row out
+    bool progressive = false;   // exact mode, last level, P >= 2: read the last plane only where the others cannot rule a row out
+    bool hints = false;         // ... one query, general scales: the index holds half-precision copies of the scales
 };
 
 // Grid = min(units, n_cu * per_cu); per_cu == 0 means "as many workgroups as are
@@ -70,11 +71,11 @@ RBE_DECLARE_W(4)
 
 // Persistent workgroups per compute unit for a one-query streaming scan: about 44 KB of tile stream in flight
 // per compute unit (a workgroup has one tile in flight; the progressive scan streams all planes and scale arrays but the last).
-inline uint32_t streaming_blocks_per_cu(uint32_t W, uint32_t P, uint32_t S, bool progressive)
+inline uint32_t streaming_blocks_per_cu(uint32_t W, uint32_t P, uint32_t S, bool progressive, bool hints)
 {
     const bool prog = progressive && P >= 2;
     const uint32_t planes = prog ? P - 1 : P, scales = prog && S > 0 ? S - 1 : S;
-    const uint32_t tile_stream = kTileItems * (8u * W * planes + 4u * scales);
+    const uint32_t tile_stream = kTileItems * (8u * W * planes + (prog && hints ? 2u : 4u) * scales);
     const uint32_t n = (44u * 1024u + tile_stream / 2) / tile_stream;
     return n < 1u ? 1u : (n > 4u ? 4u : n);
 }

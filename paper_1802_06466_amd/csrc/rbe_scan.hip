@@ -684,11 +684,13 @@ using ScanFn = void (*)(const ScanArgs);
 using DenseFn = void (*)(const char*, const Layout, const uint32_t*, const float*, uint64_t, uint64_t, float*);
 
 template <int W, int P, int PQ>
-ScanFn prog_fn_m(int mode, bool single)
+ScanFn prog_fn_m(int mode, bool single, bool hints)
 {
     if constexpr (P >= 2) {
-        if (mode == kModeScaled)
-            return single ? scan_exact_prog_hint<W, P, PQ> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
+        if (mode == kModeScaled) {
+            if (!single) return scan_exact_batch_prog<W, P, PQ, kModeScaled>;
+            return hints ? scan_exact_prog_hint<W, P, PQ> : scan_exact_prog<W, P, PQ, kModeScaled>;
+        }
         if constexpr (dyadic_supported(W)) {
             if (mode == kModeDyadicNorm)
                 return single ? scan_exact_prog<W, P, PQ, kModeDyadicNorm> : scan_exact_batch_prog<W, P, PQ, kModeDyadicNorm>;
@@ -735,9 +737,9 @@ DenseFn dense_fn_m(int mode)
 ScanFn prog_fn(const KernelSel& k)
 {
     switch (k.P) {
-        case 2: RBE_SWITCH_PQ(prog_fn_m, 2, k.mode, k.single)
-        case 3: RBE_SWITCH_PQ(prog_fn_m, 3, k.mode, k.single)
-        case 4: RBE_SWITCH_PQ(prog_fn_m, 4, k.mode, k.single)
+        case 2: RBE_SWITCH_PQ(prog_fn_m, 2, k.mode, k.single, k.hints)
+        case 3: RBE_SWITCH_PQ(prog_fn_m, 3, k.mode, k.single, k.hints)
+        case 4: RBE_SWITCH_PQ(prog_fn_m, 4, k.mode, k.single, k.hints)
         default: return nullptr;
     }
 }
@@ -871,7 +873,7 @@ hipError_t launch_scan_exact_w<RBE_W>(const KernelSel& k, const ScanArgs& a, uin
         per_cu = (uint32_t)(nb > 0 ? nb : 1);
         // One query is a pure stream: what matters is the bytes in flight per compute unit, and more workgroups
         // than that needs only spread the accesses (measured: 36 KB tiles 1 per CU, 20..28 KB 2, 12 KB 3..4).
-        if (k.single) per_cu = std::min(per_cu, streaming_blocks_per_cu(RBE_W, k.P, scale_arrays(k.mode, k.P), k.progressive));
+        if (k.single) per_cu = std::min(per_cu, streaming_blocks_per_cu(RBE_W, k.P, scale_arrays(k.mode, k.P), k.progressive, k.hints));
     }
     const uint32_t units = a.p_end - a.p_begin;
     const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;

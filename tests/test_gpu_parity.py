@@ -965,20 +965,22 @@ def _search_both_ways(ix, qp, qs, k):
     """Every query alone, with the progressive scan on and off; returns the two result lists and the share of
     rows whose last plane was read."""
     out, shares = {}, []
-    for prog in (True, False):
+    for prog in (1, 2, 0):           # on; on without the half-precision scale copies; off
         rbe.rbe_debug_set_progressive(ix, prog)
         res = []
         for q in range(qp.shape[0]):
             res.append(rbe.rbe_search(ix, qp[q:q + 1], None if qs is None else qs[q:q + 1], k))
             st = rbe.rbe_get_search_stats(ix)
             rows = -(-st["items_scanned"][st["n_levels"] - 1] // 256)
-            if prog:
+            if prog == 1:
                 shares.append(st["deep_rows"] / rows)
-            else:
+            elif prog == 0:
                 assert st["deep_rows"] == 0
         out[prog] = res
     rbe.rbe_debug_set_progressive(ix, True)
-    return out[True], out[False], shares
+    for (i1, s1), (i2, s2) in zip(out[1], out[2]):
+        np.testing.assert_array_equal(i1, i2); np.testing.assert_array_equal(s1, s2)
+    return out[1], out[0], shares
 
 
 @pytest.mark.parametrize("d,P,Pq,flags", [(64, 3, 3, 0), (64, 2, 3, 0), (128, 4, 4, 0), (256, 2, 2, 0), (64, 2, 3, "dyadic"),
