@@ -403,7 +403,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
                     }
                     const float hj = hint(hc, j, m);
                     s = __fmaf_rn(hj, t, s);
-                    mag = __fmaf_rn(hj, __builtin_fabsf(t), mag);
+                    // (a scale so small that its copy is subnormal is off by up to 2^-134 absolutely, not 2^-9
+                    // relatively: the floor keeps the allowance above that)
+                    mag = __fmaf_rn(__builtin_fmaxf(hj, 0x1p-120f), __builtin_fabsf(t), mag);
                     all += hj;
                 }
                 const float ub = __fmaf_rn(mag, 0.0078125f, __fmaf_rn(1.0078125f * all, mass.y, __fmaf_rn(amax, mass.x, s)));

@@ -1132,3 +1132,25 @@ def test_progressive_scan_honours_large_last_scales():
         check_topk_float(planes, scales, qx[q], k, i1[0], s1[0])
     assert hits > 0          # the boosted items do reach the top k
     rbe.rbe_free(ix)
+
+
+def test_progressive_scan_with_extreme_scales():
+    """Scales across the fp32 range (1e-37 .. 1e30, zeros, subnormals): the half-precision copies stay valid bounds;
+    ids and scores equal the plain scan's."""
+    N, d, P, k = 200_003, 64, 3, 25
+    rng = np.random.default_rng(171)
+    planes = rng.integers(0, 2**64, size=(P, N, 1), dtype=np.uint64)
+    expo = rng.integers(-37, 8, size=(P, N))
+    scales = (rng.uniform(1.0, 9.99, size=(P, N)) * 10.0 ** expo).astype(np.float32)
+    scales[:, rng.choice(N, 5000, replace=False)] = 0.0
+    scales[1, rng.choice(N, 5000, replace=False)] = np.float32(1e-41)          # subnormal
+    scales[0, :100] = np.float32(3e30)
+    qp, qs = random_queries(rng, 4, d, 3)
+    ix = load_with_ratio(planes, scales, 8)
+    on, off, _ = _search_both_ways(ix, qp, qs, k)
+    for (i1, s1), (i0, s0) in zip(on, off):
+        np.testing.assert_array_equal(i1, i0); np.testing.assert_array_equal(s1, s0)
+        assert np.isfinite(s1).all()
+    for q in range(4):
+        check_topk(planes, scales, qp[q], qs[q], k, on[q][0][0], on[q][1][0])
+    rbe.rbe_free(ix)
