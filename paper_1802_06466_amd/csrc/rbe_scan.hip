@@ -315,8 +315,8 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 
 
 // scan_exact_prog for general scales: the stream carries no fp32 scale array at all.  The scale arrays 0 .. P-2
-// come as bfloat16 copies (a_j = h_j (1 +- 2^-9), so a_j t_j <= h_j t_j + 2^-8 h_j |t_j|; the kernel allows
-// 2^-7), the last one as its largest value over the row.  A row that the bound lets through reads its last plane
+// come as bfloat16 copies (a_j = h_j (1 +- 2^-9), so a_j t_j <= h_j t_j + 2^-8 h_j |t_j| <= h_j t_j + 2^-8 h_j M;
+// the kernel allows 2^-7), the last one as its largest value over the row.  A row that the bound lets through reads its last plane
 // and its P fp32 scale arrays and is scored from scratch by score_item, so what is appended is still exactly
 // what scan_exact appends.  16 + 4 instead of 16 + 8 streamed bytes per item at d = 64, P = 3.
 // In the whole-row fallback the bound is evaluated for one row in eight only (it shares nothing with the exact
@@ -342,6 +342,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
     const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
     const QueryMass mass{pm[0], pm[1]};
+    const float slack_all = 1.0078125f * mass.y + 0.0078125f * mass.x;
     const uint64_t tau0 = a.tau[0];
     const float taus0 = threshold_score(tau0);
 
@@ -390,7 +391,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
             reach = false;
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
-                float s = 0.0f, mag = 0.0f, all = amax;
+                float s = 0.0f, all = amax;
 #pragma unroll
                 for (int j = 0; j < F; ++j) {
                     float t = q0.bias;
@@ -403,12 +404,12 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
                     }
                     const float hj = hint(hc, j, m);
                     s = __fmaf_rn(hj, t, s);
-                    // (a scale so small that its copy is subnormal is off by up to 2^-134 absolutely, not 2^-9
-                    // relatively: the floor keeps the allowance above that)
-                    mag = __fmaf_rn(__builtin_fmaxf(hj, 0x1p-120f), __builtin_fabsf(t), mag);
                     all += hj;
                 }
-                const float ub = __fmaf_rn(mag, 0.0078125f, __fmaf_rn(1.0078125f * all, mass.y, __fmaf_rn(amax, mass.x, s)));
+                // |a_j t_j - h_j t_j| <= 2^-8.9 h_j |t_j| <= 2^-8.9 h_j mass.x, and the roundings of either chain:
+                // both per unit of the scale sum (slack_all).  A scale so small that its copy is subnormal is off by
+                // up to 2^-134 absolutely instead: the floor on the sum keeps the allowance above that.
+                const float ub = __fmaf_rn(__builtin_fmaxf(all, 0x1p-120f), slack_all, __fmaf_rn(amax, mass.x, s));
                 reach |= (ub >= taus0);
             }
             reach = __ballot(reach) != 0;
