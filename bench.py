@@ -311,8 +311,7 @@ def main():
         torch.cuda.synchronize()
         h_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         # progressive like the binary-query scan: bytes read = streamed planes and scales + the last plane of some rows
-        # (the fp32-query scan streams the fp32 scale arrays 0 .. P-2 themselves)
-        h_bytes = (last_items * (P - 1) * (8 * W + 4) + (last_items // 256) * 4 + float(np.mean(h_deep)) * 256 * (8 * W + 4)
+        h_bytes = (last_items * stream_bytes_per_item + (last_items // 256) * 4 + float(np.mean(h_deep)) * deep_row_bytes
                    if P >= 2 else last_items * bytes_per_item)
         h_gbs = h_bytes / (float(np.mean(h_scan)) * 1e-3) / 1e9
         out["hybrid_float_query"] = {"ms_per_step": h_ms, "value": N / (h_ms * 1e-3), "unit": "candidates/s",

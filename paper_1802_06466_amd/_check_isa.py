@@ -25,7 +25,7 @@ import tempfile
 from . import _build
 
 # kernel name prefixes whose lane-peeling loops are intended, with the number allowed per kernel
-EXPECTED = {"dense_scores": 1, "dense_scores_fq": 1, "scan_exact_fq": 1, "scan_exact_fq_prog": 1}
+EXPECTED = {"dense_scores": 1, "dense_scores_fq": 1, "scan_exact_fq": 1, "scan_exact_fq_prog": 1, "scan_exact_fq_prog_hint": 1}
 
 
 def kernel_family(mangled: str) -> str:

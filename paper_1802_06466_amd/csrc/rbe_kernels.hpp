@@ -493,6 +493,7 @@ struct FqArgs {
     QueryMass mass;           // progressive scan: x >= sum_d |q_d| plus the rounding of the table sums, y = 2^-19 x
     uint32_t* deep_rows;      // progressive scan: += rows whose last plane had to be read
     const float* row_amax;    // as in ScanArgs
+    const uint32_t* hints;    // as in ScanArgs
 };
 
 // Batched scan on the matrix cores (rbe_batch.hip).

@@ -631,6 +631,138 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
 }
 
+// scan_exact_fq_prog for general scales with the half-precision scale copies in the stream (see
+// scan_exact_prog_hint): rows that pass the bound are scored from scratch by score_item_fq.
+template <int W, int P>
+__global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a)
+{
+    constexpr int MODE = kModeScaled;
+    constexpr int S = P, F = P - 1;
+    constexpr int NW = 2 * (S - 1);
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ float s_lut[8 * W][256];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    for (int i = threadIdx.x; i < 8 * W * 256; i += kBlock) (&s_lut[0][0])[i] = a.lut[i];
+    __syncthreads();
+
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    const uint64_t tau = a.tau_ptr[0];
+    const float taus = threshold_score(tau);
+    const QueryMass mass = a.mass;
+    const float slack_all = 1.0078125f * mass.y + 0.0078125f * mass.x;
+    uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0;
+
+    struct Hints { uint32_t w[NW]; };
+    auto load_hints = [&](Hints& h, uint32_t tile_p) {
+        const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
+        if constexpr (NW == 2) {
+            const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+            h.w[0] = v.x; h.w[1] = v.y;
+        } else {
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+            h.w[0] = v.x; h.w[1] = v.y; h.w[2] = v.z; h.w[3] = v.w;
+            if constexpr (NW == 6) {
+                const u32x2 v2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src + 4));
+                h.w[4] = v2.x; h.w[5] = v2.y;
+            }
+        }
+    };
+    auto hint = [](const Hints& h, int j, int m) {
+        const uint32_t w = h.w[2 * j + (m >> 1)];
+        return __uint_as_float((m & 1) ? (w & 0xffff0000u) : (w << 16));
+    };
+
+    RowRegs<W, P, S> cur, nxt;
+    Hints hc, hn;
+    load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_hints(hc, p);
+    float amax = a.row_amax[(size_t)p * kWavesPerBlock + wave], amax_n = 0.0f;
+    bool whole = false;
+    for (;;) {
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        const bool whole_next = passed * 4 > probed + 32;
+        if (has_next) {
+            const char* tn = a.tiles + (size_t)pn * tile_bytes;
+            load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
+            load_hints(hn, pn);
+            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+            if (whole_next) {
+                load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+                load_row_scales<W, P, S>(nxt, tn, wave, lane);
+            }
+        }
+        bool reach = true;
+        if (!whole || (rows & 7u) == 0u) {
+            reach = false;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                float s = 0.0f, all = amax;
+#pragma unroll
+                for (int j = 0; j < F; ++j) {
+                    float t = 0.0f;
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) {
+                        const uint32_t w = cur.w[j][m][h];
+                        t += s_lut[4 * h + 0][w & 255u];
+                        t += s_lut[4 * h + 1][(w >> 8) & 255u];
+                        t += s_lut[4 * h + 2][(w >> 16) & 255u];
+                        t += s_lut[4 * h + 3][w >> 24];
+                    }
+                    const float hj = hint(hc, j, m);
+                    s = __fmaf_rn(hj, t, s);
+                    all += hj;
+                }
+                const float ub = __fmaf_rn(__builtin_fmaxf(all, 0x1p-120f), slack_all, __fmaf_rn(amax, mass.x, s));
+                reach |= (ub >= taus);
+            }
+            reach = __ballot(reach) != 0;
+            ++probed;
+            passed += reach ? 1u : 0u;
+        }
+        ++rows;
+        full_rows += (whole || reach) ? 1u : 0u;
+        if (reach) {
+            if (!whole) {
+                load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+                load_row_scales<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+            }
+            float s[kItemsPerLane];
+            bool any = false;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                s[m] = score_item_fq<W, P, MODE>(cur, m, s_lut);
+                any |= (s[m] >= taus);
+            }
+            if (__ballot(any)) {
+                const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m) {
+                    const uint64_t id = row_id + lane_item<W>(lane, m);
+                    bool ok = (s[m] >= taus) && (id < a.n_items);
+                    uint64_t key = 0;
+                    if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
+                    fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
+                }
+            }
+        }
+        if (!has_next) break;
+        cur = nxt;
+        hc = hn;
+        amax = amax_n;
+        whole = whole_next;
+        p = pn;
+    }
+    if (fill) stage_flush1(s_keys, fill, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+}
+
 template <int W, int P, int MODE>
 __global__ void dense_scores_fq(const char* __restrict__ tiles, const Layout l, const float* __restrict__ lut,
                                 uint64_t first, uint64_t count, float* __restrict__ out)
@@ -777,10 +909,10 @@ using FqFn = void (*)(const FqArgs);
 using DenseFqFn = void (*)(const char*, const Layout, const float*, uint64_t, uint64_t, float*);
 
 template <int W, int P>
-FqFn fq_prog_fn_m(int mode)
+FqFn fq_prog_fn_m(int mode, bool hints)
 {
     if constexpr (P >= 2) {
-        if (mode == kModeScaled) return scan_exact_fq_prog<W, P, kModeScaled>;
+        if (mode == kModeScaled) return hints ? scan_exact_fq_prog_hint<W, P> : scan_exact_fq_prog<W, P, kModeScaled>;
         if constexpr (dyadic_supported(W)) {
             if (mode == kModeDyadicNorm) return scan_exact_fq_prog<W, P, kModeDyadicNorm>;
             if (mode == kModeDyadic) return scan_exact_fq_prog<W, P, kModeDyadic>;
@@ -819,9 +951,9 @@ hipError_t launch_scan_exact_fq_w<RBE_W>(const KernelSel& k, const FqArgs& a, ui
     FqFn fn = nullptr;
     switch (k.P) {
         case 1: fn = fq_fn_m<RBE_W, 1>(k.mode); break;
-        case 2: fn = k.progressive ? fq_prog_fn_m<RBE_W, 2>(k.mode) : fq_fn_m<RBE_W, 2>(k.mode); break;
-        case 3: fn = k.progressive ? fq_prog_fn_m<RBE_W, 3>(k.mode) : fq_fn_m<RBE_W, 3>(k.mode); break;
-        case 4: fn = k.progressive ? fq_prog_fn_m<RBE_W, 4>(k.mode) : fq_fn_m<RBE_W, 4>(k.mode); break;
+        case 2: fn = k.progressive ? fq_prog_fn_m<RBE_W, 2>(k.mode, k.hints) : fq_fn_m<RBE_W, 2>(k.mode); break;
+        case 3: fn = k.progressive ? fq_prog_fn_m<RBE_W, 3>(k.mode, k.hints) : fq_fn_m<RBE_W, 3>(k.mode); break;
+        case 4: fn = k.progressive ? fq_prog_fn_m<RBE_W, 4>(k.mode, k.hints) : fq_fn_m<RBE_W, 4>(k.mode); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;
