@@ -325,9 +325,12 @@ int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t s
 // the query operands of both fit in about 64 registers.  Per tile they take 4 registers per 32-dimension part,
 // times the item planes in the dyadic modes (one weighted copy per plane).
 uint32_t batch_tiles(uint32_t Q) { return (Q + 15u) / 16u; }
-uint32_t batch_tiles_per_launch(const rbe_index* ix)
+uint32_t batch_tiles_per_launch(const rbe_index* ix, bool float_query)
 {
     const uint32_t per_tile = 4u * 2u * ix->W * (ix->mode == rbe::kModeScaled ? 1u : ix->P);
+    // fp32 queries at d = 128 with 4 planes: every plane stays in the first look, and two tiles of accumulators
+    // on top of the operands no longer fit the register file
+    if (float_query && ix->W == 2 && ix->P == 4) return 1u;
     return 2u * per_tile <= 64u ? 2u : 1u;
 }
 
@@ -922,7 +925,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         ba.rescore = batch_rescore(ix, c.float_batch);
         ba.PQ = c.PQ; ba.qwords = ix->d_qwords; ba.qcoef = ix->d_qcoef; ba.lut = ix->d_lut; ba.margin = ix->batch_margin;
         e = hipSuccess;
-        const uint32_t tiles = batch_tiles(c.Q), per_launch = batch_tiles_per_launch(ix);
+        const uint32_t tiles = batch_tiles(c.Q), per_launch = batch_tiles_per_launch(ix, c.float_batch);
         for (uint32_t t0 = 0; t0 < tiles && e == hipSuccess; t0 += per_launch) {   // one pass over the range per launch
             const uint32_t nt = std::min(per_launch, tiles - t0);
             ba.q_begin = 16u * t0;

@@ -104,7 +104,8 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
 // the byte tables of the hybrid scan.  Half the MFMAs, and results that do not depend on how many queries share
 // a call.
 template <int W, int P, int MODE, int NQT, int RS>
-__global__ __launch_bounds__(kBlock) void scan_batch_mfma(const BatchArgs a)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu((NQT == 1 && W == 1 && P <= 3) ? 3 : 1)))
+void scan_batch_mfma(const BatchArgs a)
 {
     constexpr int S = scale_arrays(MODE, P);
     constexpr int KP = 2 * W;                          // 32-dimension parts of a plane
