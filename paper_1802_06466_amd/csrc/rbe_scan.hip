@@ -166,14 +166,18 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
     const size_t tile_bytes = geom.tile_bytes();
     const uint32_t nq = a.n_queries;
     const float* masses = a.qcoef + (size_t)nq * (PQ + 1);
-    uint32_t full_rows = 0;
+    uint32_t full_rows = 0, rows = 0;
     for (uint32_t p = a.p_begin + blockIdx.x; p < a.p_end; p += G) {
         const char* tile = a.tiles + (size_t)p * tile_bytes;
         RowRegs<W, P, S> cur;
         load_row_planes<W, P, S, 0, F>(cur, tile, wave, lane);
         load_row_scales<W, P, S>(cur, tile, wave, lane);
+        // a wave that ends up reading the last plane of more than half of its rows (a loose threshold, many queries)
+        // asks for it together with the others
+        bool have_last = full_rows * 2 > rows + 16;     // wave-uniform
+        if (have_last) { load_row_planes<W, P, S, F, P>(cur, tile, wave, lane); ++full_rows; }
+        ++rows;
         __builtin_amdgcn_sched_barrier(0);
-        bool have_last = false;     // wave-uniform
         QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
         uint64_t tau_n = a.tau[0];
         QueryMass mass_n{masses[0], masses[1]};
