@@ -328,9 +328,9 @@ uint32_t batch_tiles(uint32_t Q) { return (Q + 15u) / 16u; }
 uint32_t batch_tiles_per_launch(const rbe_index* ix, bool float_query)
 {
     const uint32_t per_tile = 4u * 2u * ix->W * (ix->mode == rbe::kModeScaled ? 1u : ix->P);
-    // fp32 queries at d = 128 with 4 planes: every plane stays in the first look, and two tiles of accumulators
-    // on top of the operands no longer fit the register file
-    if (float_query && ix->W == 2 && ix->P == 4) return 1u;
+    // fp32 queries at d = 128: every plane stays in the first look, and with two tiles of accumulators on top of
+    // the operands the kernel needs 360 registers or more (one wave per SIMD, or spills)
+    if (float_query && ix->W == 2) return 1u;
     return 2u * per_tile <= 64u ? 2u : 1u;
 }
 
