@@ -233,7 +233,7 @@ def main():
         "select_ms_total": float(r1["select_ms"].mean()) if r1["select_ms"].size else None,
         "last_search_level_ms": {"scan": st["scan_ms"], "select": st["select_ms"]},
         "roofline": {
-            "kernel": "scan_exact_prog (finest level)" if P >= 2 else "scan_exact (finest level)",
+            "kernel": "scan_exact_prog_hint (finest level)" if P >= 2 else "scan_exact (finest level)",
             "bound": "hbm",
             "achieved": achieved_gbs,
             "peak": HBM_PEAK_GBS,
