@@ -86,7 +86,8 @@ struct rbe_index {
     float* h_unscale = nullptr;
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
     uint32_t* d_hints = nullptr;    // general scales, P >= 2: bfloat16 copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
-    float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize)
+    float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize),
+                                    // followed by [n_tiles][4] largest scale sum per row
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
     float fq_mass[RBE_MAX_QUERIES][2] = {};   // fp32 queries: {x, 2^-19 x}, x >= sum_d |q_d| (1 + 2^-18): bounds any plane's table sum
@@ -770,8 +771,10 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
         HIP_TRY(hipGetLastError());
     }
     if (ix->geom.S > 0) {
-        HIP_TRY(hipMalloc(&ix->d_row_amax, (size_t)ix->layout.n_tiles * (kTileItems / kRow) * sizeof(float)));
-        hipLaunchKernelGGL(rbe::row_scale_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_row_amax);
+        const size_t n_rows = (size_t)ix->layout.n_tiles * (kTileItems / kRow);
+        HIP_TRY(hipMalloc(&ix->d_row_amax, 2 * n_rows * sizeof(float)));
+        hipLaunchKernelGGL(rbe::row_scale_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_row_amax,
+                           ix->d_row_amax + n_rows);
         HIP_TRY(hipGetLastError());
     }
     if (ix->mode == rbe::kModeScaled && ix->P >= 2) {
@@ -920,7 +923,8 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
     } else if (c.batch_mfma && !(dense && !c.float_batch && ix->batch_path == 0)) {
         BatchArgs ba;
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
-        ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.q_mass = ix->d_unscale + 2 * RBE_MAX_QUERIES; ba.tau = ix->d_tau; ba.n_queries = c.Q;
+        ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.q_mass = ix->d_unscale + 2 * RBE_MAX_QUERIES; ba.tau = ix->d_tau;
+        ba.row_amax = ix->d_row_amax; ba.row_asum = ix->d_row_amax ? ix->d_row_amax + (size_t)ix->layout.n_tiles * (kTileItems / kRow) : nullptr; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
         ba.rescore = batch_rescore(ix, c.float_batch);
         ba.PQ = c.PQ; ba.qwords = ix->d_qwords; ba.qcoef = ix->d_qcoef; ba.lut = ix->d_lut; ba.margin = ix->batch_margin;

@@ -227,6 +227,19 @@ void scan_batch_mfma(const BatchArgs a)
         constexpr int F = SKIP ? P - 1 : P;
         constexpr int PD = kDy ? 1 : F;
         static_assert(PD <= PD_MAX, "accumulators");
+        // General scales, last plane left out: a pair can only reach its threshold if
+        //     sum_{j<P-1} a_j D_j  >=  tau - a_{P-1} mass_q - margin sum_j a_j,
+        // and with the row's largest last scale and largest scale sum the right-hand side is the same for every item
+        // of the row: one subtraction per query and row instead of a multiply-add per pair.
+        float row_taus[NQT][4];
+        if constexpr (MODE == kModeScaled && F < P) {
+            const float amax = a.row_amax[(size_t)p * kWavesPerBlock + wave], smax = a.row_asum[(size_t)p * kWavesPerBlock + wave];
+#pragma unroll
+            for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    row_taus[qt][r] = taus[qt][r] - 1.000001f * __fmaf_rn(amax, qmass[qt][r], a.margin * smax);
+        }
         for (int cb = 0; cb < kSegItems / (16 * U); ++cb) {
             float s[U][NQT][4];
             bool any = false;
@@ -265,9 +278,11 @@ void scan_batch_mfma(const BatchArgs a)
                 float aj[P];
                 float adj = 0.0f;      // filter slack of this item (general scales)
                 if (MODE == kModeScaled) {
+                    // first look without the last plane: its largest possible contribution and the filter slack
+                    // are taken with the row's largest last scale and scale sum and sit in row_taus already
 #pragma unroll
-                    for (int j = 0; j < P; ++j) aj[j] = s_sc[wave][j][item];
-                    if (kRescore) {
+                    for (int j = 0; j < F; ++j) aj[j] = s_sc[wave][j][item];
+                    if (kRescore && F == P) {
                         float asum = aj[0];
 #pragma unroll
                         for (int j = 1; j < P; ++j) asum += aj[j];
@@ -285,14 +300,13 @@ void scan_batch_mfma(const BatchArgs a)
                             v = adj;
 #pragma unroll
                             for (int j = 0; j < F; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
-                            if (F < P) v = __fmaf_rn(aj[P - 1], qmass[qt][r], v);
                         } else if (MODE == kModeDyadicNorm) {
                             v = aj[0] * (F < P ? D[qt][0][r] + qmass[qt][r] : D[qt][0][r]);
                         } else {
                             v = F < P ? D[qt][0][r] + qmass[qt][r] : D[qt][0][r];
                         }
                         s[u][qt][r] = v;
-                        any |= (v >= taus[qt][r]);
+                        any |= (v >= ((MODE == kModeScaled && F < P) ? row_taus[qt][r] : taus[qt][r]));
                     }
             }
             bool go = __ballot(any) != 0;
@@ -330,14 +344,21 @@ void scan_batch_mfma(const BatchArgs a)
                                 DL[qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][kDy ? j : 0][kp], B, DL[qt], 0, 0, 0);
                         }
                     }
-                    float a_item = 1.0f;
-                    if constexpr (MODE == kModeScaled) a_item = s_sc[wave][P - 1][item];
-                    else if constexpr (MODE == kModeDyadicNorm) a_item = s_sc[wave][0][item];
+                    float a_item = 1.0f, adj2 = 0.0f;
+                    if constexpr (MODE == kModeScaled) {
+                        a_item = s_sc[wave][P - 1][item];
+                        float asum = a_item;
+#pragma unroll
+                        for (int j = 0; j < P - 1; ++j) asum += s_sc[wave][j][item];
+                        adj2 = a.margin * asum;          // the item's own filter slack
+                    } else if constexpr (MODE == kModeDyadicNorm) {
+                        a_item = s_sc[wave][0][item];
+                    }
 #pragma unroll
                     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            if (MODE == kModeScaled) s[u][qt][r] = __fmaf_rn(a_item, DL[qt][r] - qmass[qt][r], s[u][qt][r]);
+                            if (MODE == kModeScaled) s[u][qt][r] = __fmaf_rn(a_item, DL[qt][r], s[u][qt][r]) + adj2;
                             else s[u][qt][r] = MODE == kModeDyadicNorm ? a_item * DL[qt][r] : DL[qt][r];
                             any2 |= (s[u][qt][r] >= taus[qt][r]);
                         }

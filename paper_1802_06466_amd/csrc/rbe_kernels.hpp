@@ -510,6 +510,8 @@ struct BatchArgs {
     const float* q_mass;      // [Q] what lets the first look leave the last plane out.  General scales: sum_d |v_d| of
                               // the scaled query, rounded up (no plane's qhat . rho exceeds it).  Dyadic modes: the most
                               // the last plane's term can add to the accumulator, 2^-(P-1) (sum_d |v_d| + sum_d v_d)
+    const float* row_amax;    // [physical tile][4 rows] largest last scale of the row, and ...
+    const float* row_asum;    // ... largest sum of an item's scales in the row (general scales)
     const uint64_t* tau;      // [Q] threshold keys
     uint32_t n_queries;       // Q
     uint32_t q_begin;         // first query of this launch (a multiple of 16); it handles 16 or 32 from there

@@ -414,18 +414,29 @@ __global__ void fold_cosine(char* __restrict__ tiles, const TileGeom g, uint64_t
     }
 }
 
-// Largest value of the last scale array over each row of 256 items: out[physical tile][row].  One workgroup of
+// Largest value of the last scale array over each row of 256 items: out[physical tile][row]; out_sum: largest
+// sum of an item's scales over the row.  One workgroup of
 // 256 threads per tile, one wave per row.  The one-query progressive scans bound the last plane's contribution
 // with it instead of reading that array.
-__global__ void row_scale_max(const char* __restrict__ tiles, const TileGeom g, float* __restrict__ out)
+__global__ void row_scale_max(const char* __restrict__ tiles, const TileGeom g, float* __restrict__ out,
+                              float* __restrict__ out_sum)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const float* sc = reinterpret_cast<const float*>(tiles + (size_t)blockIdx.x * g.tile_bytes() + g.scales_offset()) +
-                      (size_t)(g.S - 1) * kTileItems + wave * kRow;
-    float mx = 0.0f;
-    for (int m = 0; m < kRow / 64; ++m) mx = fmaxf(mx, sc[m * 64 + lane]);
-    for (int d = 32; d > 0; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
-    if (lane == 0) out[(size_t)blockIdx.x * kWavesPerBlock + wave] = mx;
+    const float* sc0 = reinterpret_cast<const float*>(tiles + (size_t)blockIdx.x * g.tile_bytes() + g.scales_offset()) + wave * kRow;
+    const float* sc = sc0 + (size_t)(g.S - 1) * kTileItems;
+    float mx = 0.0f, ms = 0.0f;      // ms: largest sum of an item's scales (summed upwards: never below the fp32 sum
+                                     // a kernel forms in any order)
+    for (int m = 0; m < kRow / 64; ++m) {
+        mx = fmaxf(mx, sc[m * 64 + lane]);
+        double sum = 0.0;
+        for (uint32_t j = 0; j < g.S; ++j) sum += (double)sc0[(size_t)j * kTileItems + m * 64 + lane];
+        ms = fmaxf(ms, __double2float_ru(sum * (1.0 + 1e-6)));
+    }
+    for (int d = 32; d > 0; d >>= 1) { mx = fmaxf(mx, __shfl_xor(mx, d)); ms = fmaxf(ms, __shfl_xor(ms, d)); }
+    if (lane == 0) {
+        out[(size_t)blockIdx.x * kWavesPerBlock + wave] = mx;
+        out_sum[(size_t)blockIdx.x * kWavesPerBlock + wave] = ms;
+    }
 }
 
 // Half-precision copies (bfloat16, round to nearest even) of the scale arrays 0 .. S-2, in the order in which the
