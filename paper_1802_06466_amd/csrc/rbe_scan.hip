@@ -228,12 +228,14 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
 }
 
-// One query, P >= 2, progressive: the stream carries planes 0 .. F-1 (F = P - 1) and the scales only.  From them
-// every item gets an upper bound on its score (bound_item); only where some item of the wave's row can still
-// reach the threshold is the row's last plane read (a dependent load, exposed, but rare once the threshold is
-// tight: the rows that hold items of the query's own neighbourhood) and the row scored exactly as scan_exact
-// scores it.  What is appended is therefore identical to scan_exact's; what is read is 8W (P-1) + 4S of the
-// 8WP + 4S bytes of most items.  (The residual scales decay from plane to plane, so the last plane is the one
+// One query, P >= 2, progressive: the stream carries planes 0 .. F-1 (F = P - 1) and the scale arrays 0 .. S-2
+// only; the row's largest last scale (row_amax) stands in for the last scale array.  From them every item gets an
+// upper bound on its score (bound_item_rowmax); only where some item of the wave's row can still reach the
+// threshold are the row's last plane and last scales read (a dependent load, exposed, but rare once the threshold
+// is tight: the rows that hold items of the query's own neighbourhood) and the partial scores continued to the
+// full ones, exactly as scan_exact forms them.  What is appended is therefore identical to scan_exact's; what is
+// read is (8W + 4)(P-1) of the (8W + 4) P bytes of most items (general scales; see scan_exact_prog_hint for the
+// variant that streams half-precision scale copies).  (The residual scales decay from plane to plane, so the last plane is the one
 // whose absence costs the bound least; with fewer planes in the stream the bound let most rows through on
 // clustered data.)
 // A wave that finds itself fetching the last plane for more than a quarter of its rows (a loose threshold, or
