@@ -101,6 +101,7 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_si
     import numpy as np
     per_step, scan_ms, select_ms, total_gpu, all_ids, deep_rows = [], [], [], [], [], []
     stats = None
+    fallbacks = 0
     for s in range(warmup):
         sl = slice(s * Q, (s + 1) * Q)
         rbe.rbe_search(ix, qp[sl], qs[sl], k, mode, group_size_I)
@@ -113,6 +114,7 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_si
         per_step.append((time.perf_counter() - t0) * 1e3)
         all_ids.append(ids)
         stats = rbe.rbe_get_search_stats(ix)
+        fallbacks += int(stats["fallback"])
         if stats["n_levels"] and not stats["fallback"]:
             scan_ms.append(stats["scan_ms"][-1])
             select_ms.append(sum(stats["select_ms"]))
@@ -123,7 +125,7 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_si
     return {
         "wall_s": wall, "per_step_ms": np.array(per_step), "scan_ms": np.array(scan_ms),
         "select_ms": np.array(select_ms), "total_gpu_ms": np.array(total_gpu), "stats": stats,
-        "ids": all_ids, "deep_rows": np.array(deep_rows),
+        "ids": all_ids, "deep_rows": np.array(deep_rows), "fallbacks": fallbacks,
     }
 
 
@@ -374,7 +376,8 @@ def main():
             "gpu_ms_per_search": float(rb["total_gpu_ms"].mean()) if rb["total_gpu_ms"].size else None,
             "roofline": roof,
         }
-        log(f"Q={B}: {b_ms:.3f} ms/step, scan kernel {b_scan:.3f} ms")
+        log(f"Q={B}: {b_ms:.3f} ms/step (per step {np.round(rb['per_step_ms'], 2).tolist()}, "
+            f"{rb['fallbacks']} on the bounded-segment path), scan kernel {b_scan:.3f} ms")
         if matrix_cores:
             # the same calls on the XOR/popcount kernel (what one query uses), against the vector-ALU roofline
             # (progressive scan off for the roofline figure: the 58-op model prices every plane of every pair)

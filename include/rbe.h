@@ -285,6 +285,14 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
  * copies did not fit in device memory).                                          */
 int rbe_debug_set_progressive(rbe_index *ix, int enabled);
 
+/* The last level of an exact search in two parts (an eighth of its items, a
+ * selection, then the rest, which starts from a much tighter threshold).  The
+ * library does this on its own once a one-query search has found the last level's
+ * usual threshold too loose for its pruning scan on this corpus (most rows read in
+ * full), and stops again if that does not help.  mode 0 = that automatic choice
+ * (and forget what was learnt), 1 = never, 2 = always.  Results do not depend on it. */
+int rbe_debug_set_plan_split(rbe_index *ix, int mode);
+
 /* The mass of one query as the progressive scan uses it (pure host function, for
  * tests).  With qhat = sum_i c_i rho_i (rho = +-1 per bit), M = sum_d |qhat_d| is the
  * largest value sum_i c_i (rho_i . rho) can take over all sign vectors rho.

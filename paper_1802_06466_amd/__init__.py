@@ -74,6 +74,7 @@ PROTOTYPES = {
     "rbe_debug_phys_to_tile": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_set_batch_path": (_i32, [_vp, _i32]),
     "rbe_debug_set_progressive": (_i32, [_vp, _i32]),
+    "rbe_debug_set_plan_split": (_i32, [_vp, _i32]),
     "rbe_debug_query_mass": (_i32, [_vp, _vp, _u32, _u32, _u32, _vp]),
     "rbe_debug_exact_plan": (_i32, [_u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_debug_batch_operands": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
@@ -404,6 +405,11 @@ def rbe_debug_query_mass(q_planes, q_scales, dim: int, dyadic: bool = False):
     if dyadic:
         return int(out[:1].view(np.uint32)[0]), 0.0
     return float(out[0]), float(out[1])
+
+
+def rbe_debug_set_plan_split(ix: Index, mode: int):
+    """0 = automatic, 1 = never, 2 = always take the last level of an exact search in two parts."""
+    _check(load_library().rbe_debug_set_plan_split(ix.handle, mode))
 
 
 def rbe_debug_set_progressive(ix: Index, enabled):

@@ -88,6 +88,8 @@ struct rbe_index {
     uint32_t* d_hints = nullptr;    // general scales, P >= 2: bfloat16 copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
     float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize),
                                     // followed by [n_tiles][4] largest scale sum per row
+    int plan_split = 0;             // last level in two parts: 0 = when the searches so far call for it, 1 = never, 2 = always
+    bool split_active = false, split_failed = false;   // state of the automatic choice (see run_search)
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
     float fq_mass[RBE_MAX_QUERIES][2] = {};   // fp32 queries: {x, 2^-19 x}, x >= sum_d |q_d| (1 + 2^-18): bounds any plane's table sum
@@ -898,7 +900,7 @@ struct SearchCtx {
 // The matrix-core scan spends such a level in its survivor path; unless it was asked for explicitly, batches of
 // binary queries take the XOR/popcount scan there and the matrix cores for the last, large level only (both
 // produce the same scores bit for bit, so the levels of one search may mix them).
-static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
+static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uint32_t level_slot)
 {
     rbe_index* ix = c.ix;
     if (r.end <= r.begin) return RBE_OK;
@@ -915,7 +917,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
             FqArgs fa;
             fa.tiles = ix->d_tiles; fa.layout = ix->layout; fa.n_items = ix->n_items;
             fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
-            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints;
+            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints;
             fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q, ix->d_kmax + q, c.cap};
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
@@ -924,6 +926,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         BatchArgs ba;
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
         ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.q_mass = ix->d_unscale + 2 * RBE_MAX_QUERIES; ba.tau = ix->d_tau;
+        ba.look_stats = ix->d_status + 12;
         ba.row_amax = ix->d_row_amax; ba.row_asum = ix->d_row_amax ? ix->d_row_amax + (size_t)ix->layout.n_tiles * (kTileItems / kRow) : nullptr; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
         ba.rescore = batch_rescore(ix, c.float_batch);
@@ -945,7 +948,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense)
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0;
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
-        sa.deep_rows = ix->d_status + 1; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints;
+        sa.deep_rows = ix->d_status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints;
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
         sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);
@@ -968,7 +971,7 @@ static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_
                      bool dense = false)
 {
     rbe_index* ix = c.ix;
-    int rc = launch_scan_round(c, r, dense);
+    int rc = launch_scan_round(c, r, dense, level_slot);
     if (rc) return rc;
     if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 1], c.st));
 
@@ -1017,8 +1020,23 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     const uint32_t n_units = mode == RBE_SELECT_EXACT ? ix->layout.n_tiles : (rows_total + c.I - 1) / c.I;
     const uint32_t per_unit = mode == RBE_SELECT_EXACT ? kTileItems : kRow * c.qlen;
     std::vector<Round> plan;
+    bool split = false;
     if (mode == RBE_SELECT_EXACT) {
         for (const Level& lv : make_plan(ix->layout, c.cap, k)) plan.push_back(Round{lv.p_begin, lv.p_end, 1, 0});
+        // The pruning scans of the last level need a threshold that lies inside the query's neighbourhood.  When the
+        // last level's own threshold (the k-th best of a 1/ratio sample) turned out too loose for that on this
+        // corpus, the level is taken in two parts: an eighth of it first, after which the rest starts from the k-th
+        // best of about an eighth of the corpus.  Costs a launch and a selection, so it is not the default.
+        split = ix->plan_split == 2 || (ix->plan_split == 0 && ix->split_active);
+        const uint32_t min_tiles = ix->plan_split == 2 ? 16u : 4096u;   // on its own only where a launch and a selection are small change
+        if (split && plan.size() >= 2 && plan.size() < RBE_MAX_LEVELS && plan.back().end - plan.back().begin >= min_tiles) {
+            const Round last = plan.back();
+            const uint32_t mid = last.begin + (last.end - last.begin) / 8;
+            plan.back() = Round{last.begin, mid, 1, 0};
+            plan.push_back(Round{mid, last.end, 1, 0});
+        } else {
+            split = false;
+        }
     } else {
         plan = make_group_plan(n_units, ix->layout.ratio, c.cap, per_unit);
     }
@@ -1037,7 +1055,13 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         if (!fallback) {
             if (prof) HIP_TRY(hipEventRecord(ix->ev[0], c.st));
             for (size_t l = 0; l < plan.size(); ++l) {
-                rc = run_round(c, plan[l], l + 1 == plan.size(), (uint32_t)l, prof, l + 1 != plan.size() || l == 0);
+                // A level is "dense" while a large share of its items passes the threshold it starts with: the k-th
+                // best of the items read so far, so about k * (its items) / (items before it) survive.  Above one
+                // survivor per 500 items the pruning scans (progressive, matrix-core) spend their time in their
+                // survivor paths (measured: at one per 1500 they are still well ahead, at one per 250 well behind).
+                const uint64_t before = mode == RBE_SELECT_EXACT ? (uint64_t)plan[l].begin * kTileItems : 0;
+                const bool dense = l == 0 || (uint64_t)k * 500u > before;
+                rc = run_round(c, plan[l], l + 1 == plan.size(), (uint32_t)l, prof, dense);
                 if (rc) return rc;
                 ix->stats.items_scanned[l] = (uint64_t)(plan[l].end - plan[l].begin) *
                                              (mode == RBE_SELECT_EXACT ? (uint64_t)kTileItems : (uint64_t)c.I * kRow);
@@ -1066,7 +1090,23 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         fallback = true;  // a level produced more survivors than the list holds: redo on the slow path
     }
 
-    ix->stats.deep_rows = ix->h_status[1];
+    ix->stats.deep_rows = 0;
+    for (uint32_t l = 0; l < RBE_MAX_LEVELS; ++l) ix->stats.deep_rows += ix->h_status[1 + l];
+    // one query, the pruning scan in use: did the last level's threshold let it prune?  If most rows were read in
+    // full, later searches split the last level; if that does not help either, they stop doing so for good.
+    if (!fallback && mode == RBE_SELECT_EXACT && c.Q == 1 && ix->progressive != 0 && ix->P >= 2 && plan.size() >= 2) {
+        const uint64_t rows_last = (uint64_t)(plan.back().end - plan.back().begin) * (kTileItems / kRow);
+        const bool loose = (uint64_t)ix->h_status[1 + plan.size() - 1] * 2 > rows_last;
+        if (!split) { if (loose && !ix->split_failed) ix->split_active = true; }
+        else if (loose && ix->plan_split == 0) { ix->split_active = false; ix->split_failed = true; }
+    }
+    // the same for a batch on the matrix cores: waves that ran and waves that gave up leaving the last plane out of
+    // their first look (with the split, the loose first part has an eighth of the work)
+    if (!fallback && mode == RBE_SELECT_EXACT && c.batch_mfma && !c.float_batch && ix->h_status[12] > 0 && plan.size() >= 2) {
+        const bool loose = (uint64_t)ix->h_status[13] * 2 > ix->h_status[12];
+        if (!split) { if (loose && !ix->split_failed) ix->split_active = true; }
+        else if (loose && ix->plan_split == 0) { ix->split_active = false; ix->split_failed = true; }
+    }
     if (!fallback) {
         for (uint32_t l = 0; l < ix->stats.n_levels; ++l) {
             uint32_t mx = 0;
@@ -1184,6 +1224,15 @@ int rbe_debug_query_mass(const uint64_t* q_planes, const float* q_scales, uint32
     if (!dyadic)
         for (uint32_t i = 0; i < q_n_planes; ++i) ARG_CHECK(std::isfinite(q_scales[i]), "q_scales[%u] is not finite", i);
     query_mass(q_planes, dyadic ? nullptr : q_scales, q_n_planes, dim, dyadic != 0, mass_out);
+    return RBE_OK;
+}
+
+int rbe_debug_set_plan_split(rbe_index* ix, int mode)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    ARG_CHECK(mode >= 0 && mode <= 2, "mode must be 0 (automatic), 1 (never) or 2 (always)");
+    ix->plan_split = mode;
+    if (mode == 0) { ix->split_active = false; ix->split_failed = false; }
     return RBE_OK;
 }
 

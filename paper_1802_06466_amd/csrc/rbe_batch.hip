@@ -441,6 +441,10 @@ void scan_batch_mfma(const BatchArgs a)
         seg = segn;
     }
     mstage_drain(ms, a.out, lane);
+    if (kCanSkip && a.look_stats && lane == 0 && blocks_seen) {
+        atomicAdd(&a.look_stats[0], 1u);
+        if (!skip_last) atomicAdd(&a.look_stats[1], 1u);
+    }
 }
 
 namespace {

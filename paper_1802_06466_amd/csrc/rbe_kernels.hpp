@@ -512,6 +512,7 @@ struct BatchArgs {
                               // the last plane's term can add to the accumulator, 2^-(P-1) (sum_d |v_d| + sum_d v_d)
     const float* row_amax;    // [physical tile][4 rows] largest last scale of the row, and ...
     const float* row_asum;    // ... largest sum of an item's scales in the row (general scales)
+    uint32_t* look_stats;     // [2] += waves that ran, waves that gave up leaving the last plane out (may be null)
     const uint64_t* tau;      // [Q] threshold keys
     uint32_t n_queries;       // Q
     uint32_t q_begin;         // first query of this launch (a multiple of 16); it handles 16 or 32 from there

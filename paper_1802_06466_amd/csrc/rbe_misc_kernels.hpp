@@ -221,7 +221,7 @@ __global__ void init_state(uint32_t* count, uint64_t* tau, uint64_t* kmax, uint3
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_queries) { count[i] = 0; tau[i] = 0; kmax[i] = 0; }
-    if (i < 4) status[i] = 0;     // flags, rows read in full by the progressive scan, spare
+    if (i < 16) status[i] = 0;    // flags; rows read in full by the progressive scan, per level
 }
 
 // ---------------------------------------------------------------- load path

@@ -1157,3 +1157,54 @@ def test_progressive_scan_with_extreme_scales():
     for q in range(4):
         check_topk(planes, scales, qp[q], qs[q], k, on[q][0][0], on[q][1][0])
     rbe.rbe_free(ix)
+
+
+def test_last_level_in_two_parts_gives_the_same_results():
+    """The last level taken whole or in two parts (an eighth first): same ids and scores, one query and a batch."""
+    N, d, P, k = 600_011, 64, 3, 20
+    planes, scales, qp, qs = clustered(N, d, P, 6000, 0.3, 6, 3, seed=181)
+    ix = load_with_ratio(planes, scales, 64)
+    res = {}
+    for mode in (1, 2):                       # never / always
+        rbe.rbe_debug_set_plan_split(ix, mode)
+        res[mode] = []
+        for q in range(6):
+            res[mode].append(rbe.rbe_search(ix, qp[q:q + 1], qs[q:q + 1], k))
+            st = rbe.rbe_get_search_stats(ix)
+            assert st["n_levels"] == (2 if mode == 1 else 3)
+        b16 = rbe.rbe_search(ix, qp, qs, k)
+        for q in range(6):
+            np.testing.assert_array_equal(b16[0][q], res[mode][q][0][0])
+    for (i1, s1), (i2, s2) in zip(res[1], res[2]):
+        np.testing.assert_array_equal(i1, i2); np.testing.assert_array_equal(s1, s2)
+    for q in range(6):
+        check_topk(planes, scales, qp[q], qs[q], k, res[2][q][0][0], res[2][q][1][0])
+    rbe.rbe_free(ix)
+
+
+def test_last_level_is_split_automatically_when_its_threshold_is_loose():
+    """5 M items in clusters of about 800: ratio * k = 64 * 30 lies outside the cluster, so the first search (unsplit)
+    reads most rows in full; from the second search on the last level is taken in two parts and the scan prunes."""
+    import torch
+    N, d, P, k = 5_000_000, 64, 3, 30
+    centres = rbe_synth.centres_torch(6000, d, torch.device("cuda:0"))
+    ix = rbe.rbe_index_create(N, d, P, 0)
+    for c_, z0 in enumerate(range(0, N, 1_000_000)):
+        v = rbe_synth.vectors_torch(1_000_000, centres, 0.3, rbe_synth.SEED_ITEMS, c_)
+        pl, sc = rbe_synth.pack_planes_torch(v, P)
+        rbe.rbe_load_chunk(ix, z0, pl, sc)
+    rbe.rbe_finalize(ix)
+    x = rbe_synth.vectors_torch(3, centres, 0.3, rbe_synth.SEED_QUERIES, 0).cpu().numpy()
+    enc = [rbe.rbe_encode_query(x[i], P) for i in range(3)]
+    qp = np.stack([e[0] for e in enc]); qs = np.stack([e[1] for e in enc])
+    r0 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    st0 = rbe.rbe_get_search_stats(ix)
+    r1 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    st1 = rbe.rbe_get_search_stats(ix)
+    assert st1["n_levels"] == st0["n_levels"] + 1, (st0["n_levels"], st1["n_levels"])
+    assert st1["deep_rows"] < st0["deep_rows"] // 2, (st0["deep_rows"], st1["deep_rows"])
+    np.testing.assert_array_equal(r0[0], r1[0]); np.testing.assert_array_equal(r0[1], r1[1])
+    rbe.rbe_debug_set_plan_split(ix, 1)
+    r2 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    np.testing.assert_array_equal(r0[0], r2[0]); np.testing.assert_array_equal(r0[1], r2[1])
+    rbe.rbe_free(ix)
