@@ -89,7 +89,12 @@ struct rbe_index {
     float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize),
                                     // followed by [n_tiles][4] largest scale sum per row
     int plan_split = 0;             // last level in two parts: 0 = when the searches so far call for it, 1 = never, 2 = always
-    bool split_active = false, split_failed = false;   // state of the automatic choice (see run_search)
+    // State of the automatic choices (see run_search), kept apart for searches on the XOR/popcount and table scans
+    // [0] and for batches on the matrix cores [1]: what prunes for one need not prune for the other.
+    struct PruneState {
+        bool split_active = false;
+        uint32_t holdoff = 0;       // searches left during which the pruning scans stay off / the level stays whole
+    } prune[2];
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
     float fq_mass[RBE_MAX_QUERIES][2] = {};   // fp32 queries: {x, 2^-19 x}, x >= sum_d |q_d| (1 + 2^-18): bounds any plane's table sum
@@ -910,7 +915,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
     hipError_t e;
     if (c.float_query) {
         e = hipSuccess;
-        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0;
+        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0;
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
         const size_t per_q = (size_t)8 * ix->W * 256;
         for (uint32_t q = 0; q < c.Q && e == hipSuccess; ++q) {   // one pass over the range per query
@@ -946,7 +951,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         sa.tau = ix->d_tau; sa.out = out;
         sa.p_begin = r.begin; sa.p_end = r.end;
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
-        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0;
+        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0;
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
         sa.deep_rows = ix->d_status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints;
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
@@ -1021,13 +1026,16 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     const uint32_t per_unit = mode == RBE_SELECT_EXACT ? kTileItems : kRow * c.qlen;
     std::vector<Round> plan;
     bool split = false;
+    rbe_index::PruneState& ps = ix->prune[c.batch_mfma ? 1 : 0];
+    if (mode == RBE_SELECT_EXACT && ps.holdoff > 0) --ps.holdoff;
+    const bool pruning = ix->progressive != 0 && ix->P >= 2 && ps.holdoff == 0;
     if (mode == RBE_SELECT_EXACT) {
         for (const Level& lv : make_plan(ix->layout, c.cap, k)) plan.push_back(Round{lv.p_begin, lv.p_end, 1, 0});
         // The pruning scans of the last level need a threshold that lies inside the query's neighbourhood.  When the
         // last level's own threshold (the k-th best of a 1/ratio sample) turned out too loose for that on this
         // corpus, the level is taken in two parts: an eighth of it first, after which the rest starts from the k-th
         // best of about an eighth of the corpus.  Costs a launch and a selection, so it is not the default.
-        split = ix->plan_split == 2 || (ix->plan_split == 0 && ix->split_active);
+        split = ix->plan_split == 2 || (ix->plan_split == 0 && ps.split_active);
         const uint32_t min_tiles = ix->plan_split == 2 ? 16u : 4096u;   // on its own only where a launch and a selection are small change
         if (split && plan.size() >= 2 && plan.size() < RBE_MAX_LEVELS && plan.back().end - plan.back().begin >= min_tiles) {
             const Round last = plan.back();
@@ -1094,18 +1102,28 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     for (uint32_t l = 0; l < RBE_MAX_LEVELS; ++l) ix->stats.deep_rows += ix->h_status[1 + l];
     // one query, the pruning scan in use: did the last level's threshold let it prune?  If most rows were read in
     // full, later searches split the last level; if that does not help either, they stop doing so for good.
-    if (!fallback && mode == RBE_SELECT_EXACT && c.Q == 1 && ix->progressive != 0 && ix->P >= 2 && plan.size() >= 2) {
-        const uint64_t rows_last = (uint64_t)(plan.back().end - plan.back().begin) * (kTileItems / kRow);
+    // (one launch per query with fp32 queries, one per call otherwise: rows_last counts them all)
+    if (!fallback && mode == RBE_SELECT_EXACT && !c.batch_mfma && pruning && plan.size() >= 2) {
+        const uint64_t rows_last = (uint64_t)(plan.back().end - plan.back().begin) * (kTileItems / kRow) * (c.float_query ? c.Q : 1u);
         const bool loose = (uint64_t)ix->h_status[1 + plan.size() - 1] * 2 > rows_last;
-        if (!split) { if (loose && !ix->split_failed) ix->split_active = true; }
-        else if (loose && ix->plan_split == 0) { ix->split_active = false; ix->split_failed = true; }
+        if (loose && ix->plan_split == 0) {
+            if (!split && !ps.split_active) {
+                ps.split_active = true;      // next search: the last level in two parts
+            } else {
+                // not even the tighter threshold lets them prune (or the level is too small to split): plain scans
+                // for a while, then another try
+                ps.split_active = false; ps.holdoff = 64;
+            }
+        }
     }
     // the same for a batch on the matrix cores: waves that ran and waves that gave up leaving the last plane out of
     // their first look (with the split, the loose first part has an eighth of the work)
     if (!fallback && mode == RBE_SELECT_EXACT && c.batch_mfma && !c.float_batch && ix->h_status[12] > 0 && plan.size() >= 2) {
         const bool loose = (uint64_t)ix->h_status[13] * 2 > ix->h_status[12];
-        if (!split) { if (loose && !ix->split_failed) ix->split_active = true; }
-        else if (loose && ix->plan_split == 0) { ix->split_active = false; ix->split_failed = true; }
+        if (loose && ix->plan_split == 0 && ps.holdoff == 0) {
+            if (!split && !ps.split_active) ps.split_active = true;
+            else { ps.split_active = false; ps.holdoff = 64; }   // the level stays whole for a while
+        }
     }
     if (!fallback) {
         for (uint32_t l = 0; l < ix->stats.n_levels; ++l) {
@@ -1232,7 +1250,7 @@ int rbe_debug_set_plan_split(rbe_index* ix, int mode)
     ARG_CHECK(ix != nullptr, "index is NULL");
     ARG_CHECK(mode >= 0 && mode <= 2, "mode must be 0 (automatic), 1 (never) or 2 (always)");
     ix->plan_split = mode;
-    if (mode == 0) { ix->split_active = false; ix->split_failed = false; }
+    if (mode == 0) ix->prune[0] = ix->prune[1] = rbe_index::PruneState{};
     return RBE_OK;
 }
 

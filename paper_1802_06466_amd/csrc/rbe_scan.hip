@@ -166,18 +166,35 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
     const size_t tile_bytes = geom.tile_bytes();
     const uint32_t nq = a.n_queries;
     const float* masses = a.qcoef + (size_t)nq * (PQ + 1);
-    uint32_t full_rows = 0, rows = 0;
+    uint32_t full_rows = 0, rows = 0, probed = 0, probe_full = 0;   // probed: rows taken the progressive way
     for (uint32_t p = a.p_begin + blockIdx.x; p < a.p_end; p += G) {
         const char* tile = a.tiles + (size_t)p * tile_bytes;
         RowRegs<W, P, S> cur;
         load_row_planes<W, P, S, 0, F>(cur, tile, wave, lane);
         load_row_scales<W, P, S>(cur, tile, wave, lane);
         // a wave that ends up reading the last plane of more than half of its rows (a loose threshold, many queries)
-        // asks for it together with the others
-        bool have_last = full_rows * 2 > rows + 16;     // wave-uniform
-        if (have_last) { load_row_planes<W, P, S, F, P>(cur, tile, wave, lane); ++full_rows; }
+        // asks for it together with the others and, bounds being of no use to it, scores like scan_exact; one row in
+        // sixteen still goes the progressive way, to notice when that changes
+        const bool plain = probe_full * 2 > probed + 16 && (rows & 15u) != 0u;     // wave-uniform
+        bool have_last = plain;
+        if (plain) { load_row_planes<W, P, S, F, P>(cur, tile, wave, lane); ++full_rows; }
         ++rows;
         __builtin_amdgcn_sched_barrier(0);
+        if (plain) {
+            QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+            uint64_t tau_n = a.tau[0];
+            for (uint32_t q = 0; q < nq; ++q) {
+                const QueryRegs<W, PQ> qr = qn;
+                const uint64_t tau = tau_n;
+                if (q + 1 < nq) {
+                    qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
+                    tau_n = a.tau[q + 1];
+                }
+                score_and_stage<W, P, PQ, false, MODE>(cur, qr, tau, threshold_score(tau), q, p, wave, lane, s_keys, ms, 0, a);
+            }
+            continue;
+        }
+        ++probed;
         QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
         uint64_t tau_n = a.tau[0];
         QueryMass mass_n{masses[0], masses[1]};
@@ -212,6 +229,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
                     load_row_planes<W, P, S, F, P>(cur, tile, wave, lane);
                     have_last = true;
                     ++full_rows;
+                    ++probe_full;
                 }
                 float s[kItemsPerLane];
                 bool any = false;
@@ -385,8 +403,10 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
         if (has_next) {
             const char* tn = a.tiles + (size_t)pn * tile_bytes;
             load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
-            load_hints(hn, pn);
-            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+            if (!whole_next || ((rows + 1u) & 7u) == 0u) {      // in the whole-row fallback only the rows that are probed
+                load_hints(hn, pn);
+                amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+            }
             if (whole_next) {
                 load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
                 load_row_scales<W, P, S>(nxt, tn, wave, lane);
@@ -697,8 +717,10 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
         if (has_next) {
             const char* tn = a.tiles + (size_t)pn * tile_bytes;
             load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
-            load_hints(hn, pn);
-            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+            if (!whole_next || ((rows + 1u) & 7u) == 0u) {      // in the whole-row fallback only the rows that are probed
+                load_hints(hn, pn);
+                amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+            }
             if (whole_next) {
                 load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
                 load_row_scales<W, P, S>(nxt, tn, wave, lane);

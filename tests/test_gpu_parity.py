@@ -964,6 +964,7 @@ def test_two_indexes_searched_from_two_threads_on_their_own_streams():
 def _search_both_ways(ix, qp, qs, k):
     """Every query alone, with the progressive scan on and off; returns the two result lists and the share of
     rows whose last plane was read."""
+    rbe.rbe_debug_set_plan_split(ix, 1)      # no automatic choices: the switch alone decides which scan runs
     out, shares = {}, []
     for prog in (1, 2, 0):           # on; on without the half-precision scale copies; off
         rbe.rbe_debug_set_progressive(ix, prog)
@@ -1054,6 +1055,7 @@ def test_progressive_scan_with_fp32_queries(d, P, flags):
             scales = oracle.fold_cosine(planes, scales)
         ix = load_with_ratio(planes, None, 8, flags=rbe.RBE_DYADIC | (rbe.RBE_COSINE if flags == "dyadic_cosine" else 0))
     rbe.rbe_debug_set_batch_path(ix, 1)         # the table path for every batch size
+    rbe.rbe_debug_set_plan_split(ix, 1)         # no automatic choices
     res = {}
     for prog in (1, 2, 0):           # on; on without the half-precision scale copies; off
         rbe.rbe_debug_set_progressive(ix, prog)
@@ -1092,6 +1094,7 @@ def test_progressive_scan_for_small_batches(d, P, Pq, flags):
         qs = None
     qs_o = qs if qs is not None else np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (16, 1))
     rbe.rbe_debug_set_batch_path(ix, 1)
+    rbe.rbe_debug_set_plan_split(ix, 1)         # no automatic choices
     for Q in (2, 5, 7, 16):
         res = {}
         for prog in (True, False):
@@ -1207,4 +1210,30 @@ def test_last_level_is_split_automatically_when_its_threshold_is_loose():
     rbe.rbe_debug_set_plan_split(ix, 1)
     r2 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
     np.testing.assert_array_equal(r0[0], r2[0]); np.testing.assert_array_equal(r0[1], r2[1])
+    rbe.rbe_free(ix)
+
+
+def test_pruning_scans_stand_down_on_a_corpus_they_cannot_prune():
+    """Unclustered corpus: every row has to be read in full.  The first search finds that out, the second tries the
+    last level in two parts, after that the pruning scans stay off for a while (plain scans, no rows counted) --
+    and every search returns the same result as the plain scan."""
+    N, d, P, k = 5_000_000, 64, 3, 30
+    import torch
+    centres = rbe_synth.centres_torch(64, d, torch.device("cuda:0"))
+    ix = rbe.rbe_index_create(N, d, P, 0)
+    for c_, z0 in enumerate(range(0, N, 1_000_000)):
+        v = rbe_synth.vectors_torch(1_000_000, centres, 10.0, rbe_synth.SEED_ITEMS, c_)      # sigma 10: no clusters left
+        pl, sc = rbe_synth.pack_planes_torch(v, P)
+        rbe.rbe_load_chunk(ix, z0, pl, sc)
+    rbe.rbe_finalize(ix)
+    x = rbe_synth.vectors_torch(1, centres, 10.0, rbe_synth.SEED_QUERIES, 0).cpu().numpy()
+    qp, qs = rbe.rbe_encode_query(x[0], P)
+    seen = []
+    for _ in range(4):
+        r = rbe.rbe_search(ix, qp[None], qs[None], k)
+        st = rbe.rbe_get_search_stats(ix)
+        seen.append((st["n_levels"], st["deep_rows"] > 0, r))
+    assert [s[:2] for s in seen] == [(3, True), (4, True), (3, False), (3, False)], [s[:2] for s in seen]
+    for s_ in seen[1:]:
+        np.testing.assert_array_equal(s_[2][0], seen[0][2][0]); np.testing.assert_array_equal(s_[2][1], seen[0][2][1])
     rbe.rbe_free(ix)
