@@ -289,8 +289,10 @@ int rbe_debug_set_progressive(rbe_index *ix, int enabled);
  * selection, then the rest, which starts from a much tighter threshold).  The
  * library does this on its own once a one-query search has found the last level's
  * usual threshold too loose for its pruning scan on this corpus (most rows read in
- * full), and stops again if that does not help.  mode 0 = that automatic choice
- * (and forget what was learnt), 1 = never, 2 = always.  Results do not depend on it. */
+ * full); if that does not help either, the pruning scans stay off for the next 64
+ * searches and are then tried again.  mode 0 = these automatic choices (and forget
+ * what was learnt), 1 = never split and never stand down, 2 = always split.
+ * Results do not depend on any of it.                                            */
 int rbe_debug_set_plan_split(rbe_index *ix, int mode);
 
 /* The mass of one query as the progressive scan uses it (pure host function, for
