@@ -99,7 +99,7 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_si
         qs = _NoScales()
     """Runs warmup + steps searches of Q queries each (different queries per call)."""
     import numpy as np
-    per_step, scan_ms, select_ms, total_gpu, all_ids, deep_rows = [], [], [], [], [], []
+    per_step, scan_ms, select_ms, total_gpu, all_ids, deep_rows, deep_units = [], [], [], [], [], [], []
     stats = None
     fallbacks = 0
     for s in range(warmup):
@@ -120,12 +120,13 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_si
             select_ms.append(sum(stats["select_ms"]))
             total_gpu.append(stats["total_gpu_ms"])
             deep_rows.append(stats["deep_rows"])
+            deep_units.append(stats["deep_units"])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin
     return {
         "wall_s": wall, "per_step_ms": np.array(per_step), "scan_ms": np.array(scan_ms),
         "select_ms": np.array(select_ms), "total_gpu_ms": np.array(total_gpu), "stats": stats,
-        "ids": all_ids, "deep_rows": np.array(deep_rows), "fallbacks": fallbacks,
+        "ids": all_ids, "deep_rows": np.array(deep_rows), "deep_units": np.array(deep_units), "fallbacks": fallbacks,
     }
 
 
@@ -192,14 +193,15 @@ def main():
     scan_avg_ms = float(r1["scan_ms"].mean()) if r1["scan_ms"].size else float("nan")
     # The finest-level scan of one query is progressive: of every item it reads every plane but the last and
     # bfloat16 copies of the matching scale arrays (plus one precomputed fp32 per row of 256 items, the row's
-    # largest last scale); of the rows that those cannot rule out (the library counts them) it also reads the last
-    # plane and the P fp32 scale arrays.  `achieved` is priced on the bytes the kernel reads; the rate on the bytes
-    # of all planes is reported beside it.
+    # largest last scale); for the items that those cannot rule out, the lanes that hold them also read the last
+    # plane and the P fp32 scales (the library counts the bytes they ask for, `deep_units` x 8).  `achieved` is
+    # priced on these bytes; the rate on the bytes of all planes is reported beside it.
     deep_avg = float(r1["deep_rows"].mean()) if r1["deep_rows"].size else 0.0
-    deep_row_bytes = 256 * (8 * W + 4 * P)
+    deep_bytes = float(r1["deep_units"].mean()) * 8.0 if r1["deep_units"].size else 0.0
+    deep_row_bytes = 256 * (8 * W + 4)        # (fp32-query scan: whole rows of the last plane and last scale)
     if P >= 2:
         stream_bytes_per_item = (P - 1) * (8 * W + 2)
-        bytes_read = last_items * stream_bytes_per_item + (last_items // 256) * 4 + deep_avg * deep_row_bytes
+        bytes_read = last_items * stream_bytes_per_item + (last_items // 256) * 4 + deep_bytes
     else:
         stream_bytes_per_item = bytes_per_item
         bytes_read = last_items * bytes_per_item
@@ -244,7 +246,8 @@ def main():
             "traffic": None,
             "bytes_per_launch": bytes_read,
             "bytes_per_item_streamed": stream_bytes_per_item,
-            "rows_read_in_full": deep_avg,
+            "rows_with_items_read_in_full": deep_avg,
+            "bytes_beyond_the_stream": deep_bytes,
             "rows": -(-last_items // 256),
             "bytes_per_launch_all_planes": last_items * bytes_per_item,
             "gbs_if_all_planes_counted": all_planes_gbs,
@@ -313,7 +316,7 @@ def main():
         torch.cuda.synchronize()
         h_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         # progressive like the binary-query scan: bytes read = streamed planes and scales + the last plane of some rows
-        h_bytes = (last_items * stream_bytes_per_item + (last_items // 256) * 4 + float(np.mean(h_deep)) * deep_row_bytes
+        h_bytes = (last_items * stream_bytes_per_item + (last_items // 256) * 4 + float(np.mean(h_deep)) * 256 * (8 * W + 4 * P)
                    if P >= 2 else last_items * bytes_per_item)
         h_gbs = h_bytes / (float(np.mean(h_scan)) * 1e-3) / 1e9
         out["hybrid_float_query"] = {"ms_per_step": h_ms, "value": N / (h_ms * 1e-3), "unit": "candidates/s",

@@ -46,6 +46,7 @@ class rbe_search_stats(ctypes.Structure):
         ("scan_ms", ctypes.c_float * RBE_MAX_LEVELS),
         ("select_ms", ctypes.c_float * RBE_MAX_LEVELS),
         ("total_gpu_ms", ctypes.c_float),
+        ("deep_units", ctypes.c_uint32),
     ]
 
 
@@ -341,7 +342,7 @@ def rbe_get_search_stats(ix: Index) -> dict:
         "n_levels": n, "fallback": st.fallback, "grid_blocks": st.grid_blocks, "deep_rows": st.deep_rows,
         "items_scanned": list(st.items_scanned)[:n], "candidates_max": list(st.candidates_max)[:n],
         "scan_ms": list(st.scan_ms)[:n], "select_ms": list(st.select_ms)[:n],
-        "total_gpu_ms": st.total_gpu_ms,
+        "total_gpu_ms": st.total_gpu_ms, "deep_units": st.deep_units,
     }
 
 

@@ -953,7 +953,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0;
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
-        sa.deep_rows = ix->d_status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints;
+        sa.deep_rows = ix->d_status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints; sa.deep_units = ix->d_status + 14;
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
         sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);
@@ -1098,6 +1098,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         fallback = true;  // a level produced more survivors than the list holds: redo on the slow path
     }
 
+    ix->stats.deep_units = ix->h_status[14];
     ix->stats.deep_rows = 0;
     for (uint32_t l = 0; l < RBE_MAX_LEVELS; ++l) ix->stats.deep_rows += ix->h_status[1 + l];
     // one query, the pruning scan in use: did the last level's threshold let it prune?  If most rows were read in

@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
                 part[m] = partial_item<W, P, PQ, MODE, F>(cur, m, qr);
-                reach |= (bound_item<W, P, PQ, MODE, F>(cur, m, part[m], mass) >= taus);
+                reach |= !(bound_item<W, P, PQ, MODE, F>(cur, m, part[m], mass) < taus);
                 if (m + 1 < kItemsPerLane) {     // one item's popcount chains at a time (see score_and_stage)
 #pragma unroll
                     for (int j = 0; j < F; ++j)
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 #pragma unroll
         for (int m = 0; m < kItemsPerLane; ++m) {
             part[m] = partial_item<W, P, PQ, MODE, F>(cur, m, q0);
-            reach |= (bound_item_rowmax<W, P, PQ, MODE>(cur, m, part[m], mass, amax) >= taus0);
+            reach |= !(bound_item_rowmax<W, P, PQ, MODE>(cur, m, part[m], mass, amax) < taus0);
         }
         reach = __ballot(reach) != 0;
         ++rows;
@@ -363,6 +363,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     uint32_t p = a.p_begin + blockIdx.x;
     if (p >= a.p_end) return;
     uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0;
+    uint32_t extra8 = 0;        // bytes / 8 asked for beyond the stream (wave total, kept in lane 0's terms)
     const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
     const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
     const QueryMass mass{pm[0], pm[1]};
@@ -410,11 +411,12 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
             if (whole_next) {
                 load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
                 load_row_scales<W, P, S>(nxt, tn, wave, lane);
+                extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item
             }
         }
         bool reach = true;
+        uint32_t mine = 0;     // which of this lane's items can still reach the threshold
         if (!whole || (rows & 7u) == 0u) {
-            reach = false;
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
                 float s = 0.0f, all = amax;
@@ -436,20 +438,68 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
                 // both per unit of the scale sum (slack_all).  A scale so small that its copy is subnormal is off by
                 // up to 2^-134 absolutely instead: the floor on the sum keeps the allowance above that.
                 const float ub = __fmaf_rn(__builtin_fmaxf(all, 0x1p-120f), slack_all, __fmaf_rn(amax, mass.x, s));
-                reach |= (ub >= taus0);
+                mine |= !(ub < taus0) ? (1u << m) : 0u;      // (a NaN bound does not prune)
             }
-            reach = __ballot(reach) != 0;
+            reach = __ballot(mine != 0u) != 0;
             ++probed;
             passed += reach ? 1u : 0u;
         }
         ++rows;
         full_rows += (whole || reach) ? 1u : 0u;
-        if (reach) {
-            if (!whole) {
-                load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
-                load_row_scales<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
-            }
+        if (reach && whole) {
             fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
+        } else if (reach) {
+            // only the lanes that hold such an item read the rest of their items' data (the memory system fetches
+            // the cache lines they touch, not the row) and score; an item whose bound is below the threshold cannot
+            // be a survivor
+            const char* tile = a.tiles + (size_t)p * tile_bytes;
+            const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
+            const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset()) + wave * kRow;
+            // what the lanes ask for: per pair of items (W = 1) or per item, the last plane and S scales
+            if constexpr (W == 1) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) extra8 += (uint32_t)__builtin_popcountll(__ballot((mine & (3u << (2 * h2))) != 0u)) * (2 + S);
+            } else {
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m)
+                    extra8 += ((uint32_t)__builtin_popcountll(__ballot((mine & (1u << m)) != 0u)) * (2 * W + S)) / 2;
+            }
+            if constexpr (W == 1) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2)
+                    if (mine & (3u << (2 * h2))) {
+                        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + h2 * 128 + 2 * lane));
+                        cur.w[P - 1][2 * h2][0] = v.x; cur.w[P - 1][2 * h2][1] = v.y;
+                        cur.w[P - 1][2 * h2 + 1][0] = v.z; cur.w[P - 1][2 * h2 + 1][1] = v.w;
+#pragma unroll
+                        for (int j = 0; j < S; ++j) {
+                            const f32x2 av = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sc + j * kTileItems + h2 * 128 + 2 * lane));
+                            cur.a[j][2 * h2] = av.x; cur.a[j][2 * h2 + 1] = av.y;
+                        }
+                    }
+            } else {
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m)
+                    if (mine & (1u << m)) {
+#pragma unroll
+                        for (int h = 0; h < W / 2; ++h) {
+                            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + (size_t)(m * 64 + lane) * W) + h);
+                            cur.w[P - 1][m][4 * h + 0] = v.x; cur.w[P - 1][m][4 * h + 1] = v.y;
+                            cur.w[P - 1][m][4 * h + 2] = v.z; cur.w[P - 1][m][4 * h + 3] = v.w;
+                        }
+#pragma unroll
+                        for (int j = 0; j < S; ++j) cur.a[j][m] = __builtin_nontemporal_load(sc + j * kTileItems + m * 64 + lane);
+                    }
+            }
+            float sv[kItemsPerLane];
+            bool any = false;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                sv[m] = -__builtin_inff();
+                if (mine & (1u << m)) sv[m] = score_item<W, P, PQ, MODE>(cur, m, q0);
+                any |= (sv[m] >= taus0);
+            }
+            if (__ballot(any)) fill = stage_scores<W, true>(sv, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
         }
         if (!has_next) break;
         cur = nxt;
@@ -460,6 +510,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+    if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
 }
 
 // ---------------------------------------------------------------- hybrid scoring (fp32 query)
@@ -616,7 +667,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
 #pragma unroll
         for (int m = 0; m < kItemsPerLane; ++m) {
             part[m] = fq_planes<W, P, MODE, 0, F>(cur, m, s_lut, 0.0f);
-            reach |= (bound_item_fq<W, P, MODE>(cur, m, part[m], mass, amax) >= taus);
+            reach |= !(bound_item_fq<W, P, MODE>(cur, m, part[m], mass, amax) < taus);
         }
         reach = __ballot(reach) != 0;
         ++rows;
@@ -748,7 +799,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
                     all += hj;
                 }
                 const float ub = __fmaf_rn(__builtin_fmaxf(all, 0x1p-120f), slack_all, __fmaf_rn(amax, mass.x, s));
-                reach |= (ub >= taus);
+                reach |= !(ub < taus);
             }
             reach = __ballot(reach) != 0;
             ++probed;
