@@ -275,6 +275,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
     if (p >= a.p_end) return;
     constexpr int F = P - 1;
     uint32_t fill = 0, rows = 0, deep = 0, full_rows = 0;   // rows seen, rows the bound let through, rows read in full
+    uint32_t extra8 = 0;                                    // bytes / 8 asked for beyond the stream
     const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
     const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
     const QueryMass mass{pm[0], pm[1]};
@@ -300,29 +301,70 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
             if (whole_next) {
                 load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
                 load_row_scales<W, P, S, SS, S>(nxt, tn, wave, lane);
+                extra8 += kRow * W + (S > 0 ? kRow / 2 : 0);
             }
         }
         PartialScore part[kItemsPerLane];
-        bool reach = false;
+        uint32_t mine = 0;     // which of this lane's items can still reach the threshold (a NaN bound does not prune)
 #pragma unroll
         for (int m = 0; m < kItemsPerLane; ++m) {
             part[m] = partial_item<W, P, PQ, MODE, F>(cur, m, q0);
-            reach |= !(bound_item_rowmax<W, P, PQ, MODE>(cur, m, part[m], mass, amax) < taus0);
+            mine |= !(bound_item_rowmax<W, P, PQ, MODE>(cur, m, part[m], mass, amax) < taus0) ? (1u << m) : 0u;
         }
-        reach = __ballot(reach) != 0;
+        const bool reach = __ballot(mine != 0u) != 0;
         ++rows;
         full_rows += (whole || reach) ? 1u : 0u;
         if (reach) {
             if (!whole) {
-                load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
-                load_row_scales<W, P, S, SS, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+                // only the lanes that hold such an item read the rest of their items' data: the memory system then
+                // fetches the cache lines they touch, not the row
+                const char* tile = a.tiles + (size_t)p * tile_bytes;
+                const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
+                const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset()) + (size_t)SS * kTileItems + wave * kRow;
+                if constexpr (W == 1) {
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2)
+                        extra8 += (uint32_t)__builtin_popcountll(__ballot((mine & (3u << (2 * h2))) != 0u)) * (2 + (S > 0 ? 1 : 0));
+                } else {
+#pragma unroll
+                    for (int m = 0; m < kItemsPerLane; ++m)
+                        extra8 += ((uint32_t)__builtin_popcountll(__ballot((mine & (1u << m)) != 0u)) * (2 * W + (S > 0 ? 1 : 0))) / 2;
+                }
+                if constexpr (W == 1) {
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2)
+                        if (mine & (3u << (2 * h2))) {
+                            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + h2 * 128 + 2 * lane));
+                            cur.w[P - 1][2 * h2][0] = v.x; cur.w[P - 1][2 * h2][1] = v.y;
+                            cur.w[P - 1][2 * h2 + 1][0] = v.z; cur.w[P - 1][2 * h2 + 1][1] = v.w;
+                            if constexpr (S > 0) {
+                                const f32x2 av = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sc + h2 * 128 + 2 * lane));
+                                cur.a[SS][2 * h2] = av.x; cur.a[SS][2 * h2 + 1] = av.y;
+                            }
+                        }
+                } else {
+#pragma unroll
+                    for (int m = 0; m < kItemsPerLane; ++m)
+                        if (mine & (1u << m)) {
+#pragma unroll
+                            for (int h = 0; h < W / 2; ++h) {
+                                const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + (size_t)(m * 64 + lane) * W) + h);
+                                cur.w[P - 1][m][4 * h + 0] = v.x; cur.w[P - 1][m][4 * h + 1] = v.y;
+                                cur.w[P - 1][m][4 * h + 2] = v.z; cur.w[P - 1][m][4 * h + 3] = v.w;
+                            }
+                            if constexpr (S > 0) cur.a[SS][m] = __builtin_nontemporal_load(sc + m * 64 + lane);
+                        }
+                }
             }
             ++deep;
             float s[kItemsPerLane];
             bool any = false;
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
-                s[m] = finish_item<W, P, PQ, MODE, F>(cur, m, q0, part[m]);
+                // an item whose bound is below the threshold cannot be a survivor (and in the lane-wise path its data
+                // was not read)
+                s[m] = -__builtin_inff();
+                if (mine & (1u << m)) s[m] = finish_item<W, P, PQ, MODE, F>(cur, m, q0, part[m]);
                 any |= (s[m] >= taus0);
             }
             if (__ballot(any)) fill = stage_scores<W, true>(s, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
@@ -335,6 +377,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+    if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
 }
 
 
