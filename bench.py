@@ -308,21 +308,21 @@ def main():
             rbe.rbe_search_float(ix, xq[s_:s_ + 1], k)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        h_scan, h_deep = [], []
+        h_scan, h_deep, h_units = [], [], []
         for s_ in range(args.warmup, args.warmup + args.steps):
             rbe.rbe_search_float(ix, xq[s_:s_ + 1], k)
             h_stats = rbe.rbe_get_search_stats(ix)
-            h_scan.append(h_stats["scan_ms"][-1]); h_deep.append(h_stats["deep_rows"])
+            h_scan.append(h_stats["scan_ms"][-1]); h_deep.append(h_stats["deep_rows"]); h_units.append(h_stats["deep_units"])
         torch.cuda.synchronize()
         h_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         # progressive like the binary-query scan: bytes read = streamed planes and scales + the last plane of some rows
-        h_bytes = (last_items * stream_bytes_per_item + (last_items // 256) * 4 + float(np.mean(h_deep)) * 256 * (8 * W + 4 * P)
+        h_bytes = (last_items * stream_bytes_per_item + (last_items // 256) * 4 + float(np.mean(h_units)) * 8.0
                    if P >= 2 else last_items * bytes_per_item)
         h_gbs = h_bytes / (float(np.mean(h_scan)) * 1e-3) / 1e9
         out["hybrid_float_query"] = {"ms_per_step": h_ms, "value": N / (h_ms * 1e-3), "unit": "candidates/s",
                                      "scan_kernel_ms": float(np.mean(h_scan)), "hbm_gbs": h_gbs,
                                      "hbm_frac": h_gbs / HBM_PEAK_GBS, "bytes_per_launch": h_bytes,
-                                     "rows_read_in_full": float(np.mean(h_deep))}
+                                     "rows_with_items_read_in_full": float(np.mean(h_deep))}
         log(f"hybrid fp32 query: {h_ms:.3f} ms/step, scan kernel {np.mean(h_scan):.3f} ms -> {h_gbs:.0f} GB/s read")
         if args.batch >= 3:
             B = args.batch

@@ -247,7 +247,7 @@ typedef struct rbe_search_stats {
     float scan_ms[RBE_MAX_LEVELS];            /* kernel time of each scan        */
     float select_ms[RBE_MAX_LEVELS];          /* kernel time of each select      */
     float total_gpu_ms;       /* first enqueue to results ready, on the stream   */
-    uint32_t deep_units;      /* one binary query: what the lanes of the
+    uint32_t deep_units;      /* one query per scan: what the lanes of the
                                  last scan asked for beyond its stream (last plane
                                  and fp32 scales of items that could still reach
                                  the threshold, whole rows in the fallback), in

@@ -922,7 +922,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
             FqArgs fa;
             fa.tiles = ix->d_tiles; fa.layout = ix->layout; fa.n_items = ix->n_items;
             fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
-            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints;
+            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints; fa.deep_units = ix->d_status + 14;
             fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q, ix->d_kmax + q, c.cap};
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);

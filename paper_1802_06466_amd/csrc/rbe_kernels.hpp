@@ -495,6 +495,7 @@ struct FqArgs {
     uint32_t* deep_rows;      // progressive scan: += rows whose last plane had to be read
     const float* row_amax;    // as in ScanArgs
     const uint32_t* hints;    // as in ScanArgs
+    uint32_t* deep_units;     // as in ScanArgs (counted by scan_exact_fq_prog_hint)
 };
 
 // Batched scan on the matrix cores (rbe_batch.hip).

@@ -776,7 +776,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
     const float taus = threshold_score(tau);
     const QueryMass mass = a.mass;
     const float slack_all = 1.0078125f * mass.y + 0.0078125f * mass.x;
-    uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0;
+    uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0, extra8 = 0;
 
     struct Hints { uint32_t w[NW]; };
     auto load_hints = [&](Hints& h, uint32_t tile_p) {
@@ -818,11 +818,12 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
             if (whole_next) {
                 load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
                 load_row_scales<W, P, S>(nxt, tn, wave, lane);
+                extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;
             }
         }
         bool reach = true;
+        uint32_t mine = 0;     // which of this lane's items can still reach the threshold
         if (!whole || (rows & 7u) == 0u) {
-            reach = false;
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
                 float s = 0.0f, all = amax;
@@ -842,24 +843,63 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
                     all += hj;
                 }
                 const float ub = __fmaf_rn(__builtin_fmaxf(all, 0x1p-120f), slack_all, __fmaf_rn(amax, mass.x, s));
-                reach |= !(ub < taus);
+                mine |= !(ub < taus) ? (1u << m) : 0u;      // (a NaN bound does not prune)
             }
-            reach = __ballot(reach) != 0;
+            reach = __ballot(mine != 0u) != 0;
             ++probed;
             passed += reach ? 1u : 0u;
         }
         ++rows;
         full_rows += (whole || reach) ? 1u : 0u;
         if (reach) {
+            if (whole) mine = 0xfu;
             if (!whole) {
-                load_row_planes<W, P, S, F, P>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
-                load_row_scales<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+                // lane-wise, as in scan_exact_prog_hint
+                const char* tile = a.tiles + (size_t)p * tile_bytes;
+                const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
+                const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset()) + wave * kRow;
+                if constexpr (W == 1) {
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2) extra8 += (uint32_t)__builtin_popcountll(__ballot((mine & (3u << (2 * h2))) != 0u)) * (2 + S);
+                } else {
+#pragma unroll
+                    for (int m = 0; m < kItemsPerLane; ++m)
+                        extra8 += ((uint32_t)__builtin_popcountll(__ballot((mine & (1u << m)) != 0u)) * (2 * W + S)) / 2;
+                }
+                if constexpr (W == 1) {
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2)
+                        if (mine & (3u << (2 * h2))) {
+                            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + h2 * 128 + 2 * lane));
+                            cur.w[P - 1][2 * h2][0] = v.x; cur.w[P - 1][2 * h2][1] = v.y;
+                            cur.w[P - 1][2 * h2 + 1][0] = v.z; cur.w[P - 1][2 * h2 + 1][1] = v.w;
+#pragma unroll
+                            for (int j = 0; j < S; ++j) {
+                                const f32x2 av = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sc + j * kTileItems + h2 * 128 + 2 * lane));
+                                cur.a[j][2 * h2] = av.x; cur.a[j][2 * h2 + 1] = av.y;
+                            }
+                        }
+                } else {
+#pragma unroll
+                    for (int m = 0; m < kItemsPerLane; ++m)
+                        if (mine & (1u << m)) {
+#pragma unroll
+                            for (int h = 0; h < W / 2; ++h) {
+                                const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + (size_t)(m * 64 + lane) * W) + h);
+                                cur.w[P - 1][m][4 * h + 0] = v.x; cur.w[P - 1][m][4 * h + 1] = v.y;
+                                cur.w[P - 1][m][4 * h + 2] = v.z; cur.w[P - 1][m][4 * h + 3] = v.w;
+                            }
+#pragma unroll
+                            for (int j = 0; j < S; ++j) cur.a[j][m] = __builtin_nontemporal_load(sc + j * kTileItems + m * 64 + lane);
+                        }
+                }
             }
             float s[kItemsPerLane];
             bool any = false;
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
-                s[m] = score_item_fq<W, P, MODE>(cur, m, s_lut);
+                s[m] = -__builtin_inff();
+                if (mine & (1u << m)) s[m] = score_item_fq<W, P, MODE>(cur, m, s_lut);
                 any |= (s[m] >= taus);
             }
             if (__ballot(any)) {
@@ -883,6 +923,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+    if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
 }
 
 template <int W, int P, int MODE>
