@@ -192,7 +192,7 @@ def main():
     last_items = st["items_scanned"][-1] if st["n_levels"] else N
     scan_avg_ms = float(r1["scan_ms"].mean()) if r1["scan_ms"].size else float("nan")
     # The finest-level scan of one query is progressive: of every item it reads every plane but the last and
-    # bfloat16 copies of the matching scale arrays (plus one precomputed fp32 per row of 256 items, the row's
+    # one-byte copies of the matching scale arrays (plus one precomputed fp32 per row of 256 items, the row's
     # largest last scale); for the items that those cannot rule out, the lanes that hold them also read the last
     # plane and the P fp32 scales (the library counts the bytes they ask for, `deep_units` x 8).  `achieved` is
     # priced on these bytes; the rate on the bytes of all planes is reported beside it.
@@ -200,7 +200,7 @@ def main():
     deep_bytes = float(r1["deep_units"].mean()) * 8.0 if r1["deep_units"].size else 0.0
     deep_row_bytes = 256 * (8 * W + 4)        # (fp32-query scan: whole rows of the last plane and last scale)
     if P >= 2:
-        stream_bytes_per_item = (P - 1) * (8 * W + 2)
+        stream_bytes_per_item = (P - 1) * 8 * W + (4 if P == 4 else P - 1)     # (three hint bytes travel as four)
         bytes_read = last_items * stream_bytes_per_item + (last_items // 256) * 4 + deep_bytes
     else:
         stream_bytes_per_item = bytes_per_item

@@ -85,7 +85,8 @@ struct rbe_index {
     float* d_unscale = nullptr;     // [Q]
     float* h_unscale = nullptr;
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
-    uint32_t* d_hints = nullptr;    // general scales, P >= 2: bfloat16 copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
+    uint32_t* d_hints = nullptr;    // general scales, P >= 2: one-byte copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
+    int hint_base[3] = {1, 1, 1};   // exponent base of each array's hints
     float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize),
                                     // followed by [n_tiles][4] largest scale sum per row
     int plan_split = 0;             // last level in two parts: 0 = when the searches so far call for it, 1 = never, 2 = always
@@ -786,14 +787,39 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
     }
     if (ix->mode == rbe::kModeScaled && ix->P >= 2) {
         // optional: without them the one-query scan streams the fp32 scale arrays 0 .. P-2 instead
-        const hipError_t eh = hipMalloc(&ix->d_hints, (size_t)ix->layout.n_tiles * kTileItems / 2 * (ix->P - 1) * sizeof(uint32_t));
+        const uint32_t nw = ix->P - 1 == 3 ? 4u : ix->P - 1;
+        const hipError_t eh = hipMalloc(&ix->d_hints, (size_t)ix->layout.n_tiles * (kTileItems / 4) * nw * sizeof(uint32_t));
         if (eh == hipErrorOutOfMemory) { (void)hipGetLastError(); ix->d_hints = nullptr; }
         else HIP_TRY(eh);
     }
     if (ix->d_hints) {
-        if (ix->W == 1) hipLaunchKernelGGL(rbe::scale_hints<1>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_hints);
-        else hipLaunchKernelGGL(rbe::scale_hints<2>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_hints);
+        // exponent base per array, from the array's largest value
+        uint32_t* d_max = nullptr;
+        uint32_t h_max[RBE_MAX_PLANES] = {};
+        int* d_base = nullptr;
+        HIP_TRY(hipMalloc(&d_max, RBE_MAX_PLANES * sizeof(uint32_t)));
+        HIP_TRY(hipMemsetAsync(d_max, 0, RBE_MAX_PLANES * sizeof(uint32_t), st));
+        hipLaunchKernelGGL(rbe::scale_array_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_max);
         HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpyAsync(h_max, d_max, sizeof(h_max), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        bool usable = true;     // the hints stand for finite, non-negative scales only
+        for (uint32_t j = 0; j < ix->P; ++j) usable = usable && h_max[j] < 0x7f800000u;
+        if (usable) {
+            // the largest value, rounded as scale_hints rounds it, gets the largest exponent field (7)
+            for (uint32_t j = 0; j + 1 < ix->P; ++j)
+                ix->hint_base[j] = std::max(1, (int)((h_max[j] + (1u << 17)) >> 23) - 7);
+            HIP_TRY(hipMalloc(&d_base, 3 * sizeof(int)));
+            HIP_TRY(hipMemcpyAsync(d_base, ix->hint_base, 3 * sizeof(int), hipMemcpyHostToDevice, st));
+            if (ix->W == 1) hipLaunchKernelGGL(rbe::scale_hints<1>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_base, ix->d_hints);
+            else hipLaunchKernelGGL(rbe::scale_hints<2>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_base, ix->d_hints);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(hipStreamSynchronize(st));
+            (void)hipFree(d_base);
+        } else {
+            (void)hipFree(ix->d_hints); ix->d_hints = nullptr;      // the scan that reads the fp32 scales serves instead
+        }
+        (void)hipFree(d_max);
     }
     HIP_TRY(hipStreamSynchronize(st));
     ix->ready = 1;
@@ -923,6 +949,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
             fa.tiles = ix->d_tiles; fa.layout = ix->layout; fa.n_items = ix->n_items;
             fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
             fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints; fa.deep_units = ix->d_status + 14;
+            for (int j = 0; j < 3; ++j) fa.hint_base[j] = ix->hint_base[j];
             fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q, ix->d_kmax + q, c.cap};
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
@@ -954,6 +981,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0;
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
         sa.deep_rows = ix->d_status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints; sa.deep_units = ix->d_status + 14;
+        for (int j = 0; j < 3; ++j) sa.hint_base[j] = ix->hint_base[j];
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
         sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);

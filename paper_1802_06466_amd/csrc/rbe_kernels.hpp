@@ -476,7 +476,8 @@ struct ScanArgs {
     uint32_t* deep_units;     // one-query progressive scans: += what the lanes asked for beyond the stream, in units of 8 bytes
     const float* row_amax;    // [physical tile][4 rows] largest value of the last scale array over the row (one-query
                               // progressive scans; unused where there is no scale array)
-    const uint32_t* hints;    // general scales: bfloat16 copies of the scale arrays 0 .. P-2 in lane order (scale_hints)
+    const uint32_t* hints;    // general scales: one-byte copies of the scale arrays 0 .. P-2 in lane order (scale_hints)
+    int hint_base[3];         // ... and the exponent base of each array's hints
     uint32_t stage_entries;   // several queries: LDS queue entries per wave (512..4096), split into sub-queues
 };
 
@@ -495,6 +496,7 @@ struct FqArgs {
     uint32_t* deep_rows;      // progressive scan: += rows whose last plane had to be read
     const float* row_amax;    // as in ScanArgs
     const uint32_t* hints;    // as in ScanArgs
+    int hint_base[3];         // as in ScanArgs
     uint32_t* deep_units;     // as in ScanArgs (counted by scan_exact_fq_prog_hint)
 };
 

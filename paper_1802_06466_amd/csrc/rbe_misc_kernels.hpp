@@ -439,27 +439,50 @@ __global__ void row_scale_max(const char* __restrict__ tiles, const TileGeom g, 
     }
 }
 
-// Half-precision copies (bfloat16, round to nearest even) of the scale arrays 0 .. S-2, in the order in which the
-// lanes of the one-query progressive scan want them: out[physical tile][wave][lane][2 (S-1) words], halfword
-// 4 j + m of a lane = array j, the lane's item m (lane_item).  The scan bounds the partial score with them and
-// reads the fp32 arrays only for the rows it scores in full.
+// Largest value of each scale array over the whole corpus, as fp32 bit patterns: out[j], zero-initialised by the
+// caller.  A negative or non-finite scale anywhere makes out[j] >= 0x7f800000 (patterns compare as unsigned).
+__global__ void scale_array_max(const char* __restrict__ tiles, const TileGeom g, uint32_t* __restrict__ out)
+{
+    const float* sc = reinterpret_cast<const float*>(tiles + (size_t)blockIdx.x * g.tile_bytes() + g.scales_offset());
+    for (uint32_t j = 0; j < g.S; ++j) {
+        uint32_t mx = 0;
+        for (uint32_t i = threadIdx.x; i < kTileItems; i += blockDim.x) {
+            const uint32_t b = __float_as_uint(sc[(size_t)j * kTileItems + i]);
+            mx = b > mx ? b : mx;
+        }
+        for (int d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(mx, d); mx = o > mx ? o : mx; }
+        if ((threadIdx.x & 63) == 0 && mx) atomicMax(&out[j], mx);
+    }
+}
+
+// One-byte copies ("hints") of the scale arrays 0 .. S-2, in the order in which the lanes of the one-query
+// progressive scan want them: out[physical tile][wave][lane][NW words], word j = array j, byte m = the lane's item
+// m (lane_item); NW = S - 1, or 4 when S - 1 = 3.  A hint c stands for the fp32 number with the bit pattern
+// (c + 32 base_j) << 18: a 3-bit exponent above base_j (a biased fp32 exponent, at least 1, chosen so that the
+// array's largest value fits) and the top 5 mantissa bits, rounded to nearest.  So hint = scale (1 +- 2^-6) for
+// scales of at least 2^(base_j - 127); smaller ones, zeros and subnormals become that smallest hint.  The scan's
+// bound allows for both; the fp32 arrays are read only for the items the bound cannot rule out.
+// Scales are finite and not negative here (the caller has looked at scale_array_max).
 template <int W>
-__global__ void scale_hints(const char* __restrict__ tiles, const TileGeom g, uint32_t* __restrict__ out)
+__global__ void scale_hints(const char* __restrict__ tiles, const TileGeom g, const int* __restrict__ base,
+                            uint32_t* __restrict__ out)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float* sc = reinterpret_cast<const float*>(tiles + (size_t)blockIdx.x * g.tile_bytes() + g.scales_offset()) + wave * kRow;
-    const uint32_t nw = 2u * (g.S - 1u);
+    const uint32_t nw = g.S - 1u == 3u ? 4u : g.S - 1u;
     uint32_t* dst = out + (((size_t)blockIdx.x * kWavesPerBlock + wave) * 64 + lane) * nw;
     for (uint32_t j = 0; j + 1 < g.S; ++j) {
-        uint32_t h[kItemsPerLane];
+        uint32_t word = 0;
+        const int lo = base[j] << 5;
         for (int m = 0; m < kItemsPerLane; ++m) {
             const uint32_t b = __float_as_uint(sc[(size_t)j * kTileItems + lane_item<W>(lane, m)]);
-            h[m] = (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;        // finite, non-negative inputs
-            if (h[m] > 0x7f7fu) h[m] = 0x7f7fu;                   // never round up to infinity (2^-8 below at most)
+            int c = (int)((b + (1u << 17)) >> 18) - lo;       // exponent and 5 mantissa bits, nearest (a carry moves up a binade)
+            c = c < 0 ? 0 : (c > 255 ? 255 : c);               // (above 255 cannot happen: base leaves room for the maximum)
+            word |= (uint32_t)c << (8 * m);
         }
-        dst[2 * j] = h[0] | (h[1] << 16);
-        dst[2 * j + 1] = h[2] | (h[3] << 16);
+        dst[j] = word;
     }
+    if (nw == 4u) dst[3] = 0;
 }
 
 }  // namespace rbe

@@ -382,10 +382,10 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 
 
 // scan_exact_prog for general scales: the stream carries no fp32 scale array at all.  The scale arrays 0 .. P-2
-// come as bfloat16 copies (a_j = h_j (1 +- 2^-9), so a_j t_j <= h_j t_j + 2^-8 h_j |t_j| <= h_j t_j + 2^-8 h_j M;
-// the kernel allows 2^-7), the last one as its largest value over the row.  A row that the bound lets through reads its last plane
+// come as one-byte copies h_j (scale_hints: a_j = h_j (1 +- 2^-6), so a_j t_j <= h_j t_j + 2^-6 h_j |t_j|
+// <= h_j t_j + 2^-6 h_j M, slightly more in the kernel), the last one as its largest value over the row.  A row that the bound lets through reads its last plane
 // and its P fp32 scale arrays and is scored from scratch by score_item, so what is appended is still exactly
-// what scan_exact appends.  16 + 4 instead of 16 + 8 streamed bytes per item at d = 64, P = 3.
+// what scan_exact appends.  16 + 2 instead of 16 + 8 streamed bytes per item at d = 64, P = 3.
 // In the whole-row fallback the bound is evaluated for one row in eight only (it shares nothing with the exact
 // score here), enough to notice when it starts to prune again.
 template <int W, int P, int PQ>
@@ -393,7 +393,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
 {
     constexpr int MODE = kModeScaled;
     constexpr int S = P, F = P - 1;
-    constexpr int NW = 2 * (S - 1);            // hint words per lane and row
+    constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
     __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -410,29 +410,34 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
     const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
     const QueryMass mass{pm[0], pm[1]};
-    const float slack_all = 1.0078125f * mass.y + 0.0078125f * mass.x;
+    const float slack_all = 2.0f * mass.y + 0.015875f * mass.x;
     const uint64_t tau0 = a.tau[0];
     const float taus0 = threshold_score(tau0);
 
     struct Hints { uint32_t w[NW]; };
     auto load_hints = [&](Hints& h, uint32_t tile_p) {
         const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
-        if constexpr (NW == 2) {
+        if constexpr (NW == 1) {
+            h.w[0] = __builtin_nontemporal_load(src);
+        } else if constexpr (NW == 2) {
             const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
             h.w[0] = v.x; h.w[1] = v.y;
         } else {
             const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
             h.w[0] = v.x; h.w[1] = v.y; h.w[2] = v.z; h.w[3] = v.w;
-            if constexpr (NW == 6) {
-                const u32x2 v2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src + 4));
-                h.w[4] = v2.x; h.w[5] = v2.y;
-            }
         }
     };
-    auto hint = [](const Hints& h, int j, int m) {   // bfloat16 -> fp32
-        const uint32_t w = h.w[2 * j + (m >> 1)];
-        return __uint_as_float((m & 1) ? (w & 0xffff0000u) : (w << 16));
+    // hint byte (3-bit exponent above base_j, 5-bit mantissa) -> fp32
+    const uint32_t hb0 = (uint32_t)a.hint_base[0] << 5, hb1 = (uint32_t)a.hint_base[1] << 5, hb2 = (uint32_t)a.hint_base[2] << 5;
+    auto hint = [&](const Hints& h, int j, int m) {
+        const uint32_t c = (h.w[j] >> (8 * m)) & 255u;
+        return __uint_as_float((c + (j == 0 ? hb0 : (j == 1 ? hb1 : hb2))) << 18);
     };
+    // a scale below the smallest hint of its array, 2^(base_j - 127), is off by up to that much instead
+    float floor_c = 0.0f;
+    for (int j = 0; j < F; ++j) floor_c += __uint_as_float((uint32_t)a.hint_base[j] << 23);
+    floor_c *= 1.0001f * mass.x;
+    const float mass_last = mass.x + 2.0f * mass.y;
 
     RowRegs<W, P, S> cur, nxt;
     Hints hc, hn;
@@ -462,7 +467,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
         if (!whole || (rows & 7u) == 0u) {
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
-                float s = 0.0f, all = amax;
+                float s = floor_c, all = 0.0f;
 #pragma unroll
                 for (int j = 0; j < F; ++j) {
                     float t = q0.bias;
@@ -477,10 +482,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
                     s = __fmaf_rn(hj, t, s);
                     all += hj;
                 }
-                // |a_j t_j - h_j t_j| <= 2^-8.9 h_j |t_j| <= 2^-8.9 h_j mass.x, and the roundings of either chain:
-                // both per unit of the scale sum (slack_all).  A scale so small that its copy is subnormal is off by
-                // up to 2^-134 absolutely instead: the floor on the sum keeps the allowance above that.
-                const float ub = __fmaf_rn(__builtin_fmaxf(all, 0x1p-120f), slack_all, __fmaf_rn(amax, mass.x, s));
+                // |a_j t_j - h_j t_j| <= 2^-6 (1 + 2^-6) h_j |t_j| <= 0.015875 h_j mass.x, and the roundings of
+                // either chain: both per unit of the scale sum (slack_all)
+                const float ub = __fmaf_rn(all, slack_all, __fmaf_rn(amax, mass_last, s));
                 mine |= !(ub < taus0) ? (1u << m) : 0u;      // (a NaN bound does not prune)
             }
             reach = __ballot(mine != 0u) != 0;
@@ -758,7 +762,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
 {
     constexpr int MODE = kModeScaled;
     constexpr int S = P, F = P - 1;
-    constexpr int NW = 2 * (S - 1);
+    constexpr int NW = S - 1 == 3 ? 4 : S - 1;
     __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
     __shared__ float s_lut[8 * W][256];
     const int lane = threadIdx.x & 63;
@@ -775,28 +779,33 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
     const uint64_t tau = a.tau_ptr[0];
     const float taus = threshold_score(tau);
     const QueryMass mass = a.mass;
-    const float slack_all = 1.0078125f * mass.y + 0.0078125f * mass.x;
+    const float slack_all = 2.0f * mass.y + 0.015875f * mass.x;
     uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0, extra8 = 0;
 
     struct Hints { uint32_t w[NW]; };
     auto load_hints = [&](Hints& h, uint32_t tile_p) {
         const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
-        if constexpr (NW == 2) {
+        if constexpr (NW == 1) {
+            h.w[0] = __builtin_nontemporal_load(src);
+        } else if constexpr (NW == 2) {
             const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
             h.w[0] = v.x; h.w[1] = v.y;
         } else {
             const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
             h.w[0] = v.x; h.w[1] = v.y; h.w[2] = v.z; h.w[3] = v.w;
-            if constexpr (NW == 6) {
-                const u32x2 v2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src + 4));
-                h.w[4] = v2.x; h.w[5] = v2.y;
-            }
         }
     };
-    auto hint = [](const Hints& h, int j, int m) {
-        const uint32_t w = h.w[2 * j + (m >> 1)];
-        return __uint_as_float((m & 1) ? (w & 0xffff0000u) : (w << 16));
+    // hint byte (3-bit exponent above base_j, 5-bit mantissa) -> fp32
+    const uint32_t hb0 = (uint32_t)a.hint_base[0] << 5, hb1 = (uint32_t)a.hint_base[1] << 5, hb2 = (uint32_t)a.hint_base[2] << 5;
+    auto hint = [&](const Hints& h, int j, int m) {
+        const uint32_t c = (h.w[j] >> (8 * m)) & 255u;
+        return __uint_as_float((c + (j == 0 ? hb0 : (j == 1 ? hb1 : hb2))) << 18);
     };
+    // a scale below the smallest hint of its array, 2^(base_j - 127), is off by up to that much instead
+    float floor_c = 0.0f;
+    for (int j = 0; j < F; ++j) floor_c += __uint_as_float((uint32_t)a.hint_base[j] << 23);
+    floor_c *= 1.0001f * mass.x;
+    const float mass_last = mass.x + 2.0f * mass.y;
 
     RowRegs<W, P, S> cur, nxt;
     Hints hc, hn;
@@ -826,7 +835,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
         if (!whole || (rows & 7u) == 0u) {
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
-                float s = 0.0f, all = amax;
+                float s = floor_c, all = 0.0f;
 #pragma unroll
                 for (int j = 0; j < F; ++j) {
                     float t = 0.0f;
@@ -842,7 +851,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
                     s = __fmaf_rn(hj, t, s);
                     all += hj;
                 }
-                const float ub = __fmaf_rn(__builtin_fmaxf(all, 0x1p-120f), slack_all, __fmaf_rn(amax, mass.x, s));
+                const float ub = __fmaf_rn(all, slack_all, __fmaf_rn(amax, mass_last, s));
                 mine |= !(ub < taus) ? (1u << m) : 0u;      // (a NaN bound does not prune)
             }
             reach = __ballot(mine != 0u) != 0;
