@@ -69,14 +69,14 @@ RBE_DECLARE_W(2)
 RBE_DECLARE_W(4)
 #undef RBE_DECLARE_W
 
-// Persistent workgroups per compute unit for a one-query streaming scan: about 44 KB of tile stream in flight
+// Persistent workgroups per compute unit for a one-query streaming scan: about 48 KB of tile stream in flight
 // per compute unit (a workgroup has one tile in flight; the progressive scan streams all planes and scale arrays but the last).
 inline uint32_t streaming_blocks_per_cu(uint32_t W, uint32_t P, uint32_t S, bool progressive, bool hints)
 {
     const bool prog = progressive && P >= 2;
     const uint32_t planes = prog ? P - 1 : P, scales = prog && S > 0 ? S - 1 : S;
     const uint32_t tile_stream = kTileItems * (8u * W * planes + (prog && hints ? 1u : 4u) * scales);
-    const uint32_t n = (44u * 1024u + tile_stream / 2) / tile_stream;
+    const uint32_t n = (48u * 1024u + tile_stream / 2) / tile_stream;
     return n < 1u ? 1u : (n > 4u ? 4u : n);
 }
 

@@ -966,7 +966,7 @@ def _search_both_ways(ix, qp, qs, k):
     rows whose last plane was read."""
     rbe.rbe_debug_set_plan_split(ix, 1)      # no automatic choices: the switch alone decides which scan runs
     out, shares = {}, []
-    for prog in (1, 2, 0):           # on; on without the half-precision scale copies; off
+    for prog in (1, 2, 0):           # on; on without the one-byte scale copies; off
         rbe.rbe_debug_set_progressive(ix, prog)
         res = []
         for q in range(qp.shape[0]):
@@ -1057,7 +1057,7 @@ def test_progressive_scan_with_fp32_queries(d, P, flags):
     rbe.rbe_debug_set_batch_path(ix, 1)         # the table path for every batch size
     rbe.rbe_debug_set_plan_split(ix, 1)         # no automatic choices
     res = {}
-    for prog in (1, 2, 0):           # on; on without the half-precision scale copies; off
+    for prog in (1, 2, 0):           # on; on without the one-byte scale copies; off
         rbe.rbe_debug_set_progressive(ix, prog)
         res[prog] = [rbe.rbe_search_float(ix, q[i:i + 1], k) for i in range(Q)] + [rbe.rbe_search_float(ix, q, k)]
         st = rbe.rbe_get_search_stats(ix)
@@ -1141,8 +1141,8 @@ def test_progressive_scan_honours_large_last_scales():
 
 
 def test_progressive_scan_with_extreme_scales():
-    """Scales across the fp32 range (1e-37 .. 1e30, zeros, subnormals): the half-precision copies stay valid bounds;
-    ids and scores equal the plain scan's."""
+    """Scales across the fp32 range (1e-37 .. 1e30, zeros, subnormals): the one-byte copies (most of them the
+    smallest code of their array here) still give valid bounds; ids and scores equal the plain scan's."""
     N, d, P, k = 200_003, 64, 3, 25
     rng = np.random.default_rng(171)
     planes = rng.integers(0, 2**64, size=(P, N, 1), dtype=np.uint64)
@@ -1160,6 +1160,29 @@ def test_progressive_scan_with_extreme_scales():
     for q in range(4):
         check_topk(planes, scales, qp[q], qs[q], k, on[q][0][0], on[q][1][0])
     rbe.rbe_free(ix)
+
+
+def test_progressive_scan_with_scales_below_the_range_of_their_copies():
+    """Clustered corpus whose scale arrays span twelve binades (half of the items scaled by 2^-9, below the smallest
+    one-byte code of their array, a quarter by 2^-3): ids and scores equal the plain scan's, and the bound still
+    prunes.  With a negative scale in the corpus no copies are made and the scan that reads the fp32 scales serves."""
+    N, d, P, k = 300_007, 64, 3, 12      # about 145 full-scale items per cluster: the sample's threshold (8 k) lies inside
+    planes, scales, qp, qs = clustered(N, d, P, 1024, 0.3, 4, 3, seed=175)
+    rng = np.random.default_rng(176)
+    factor = rng.choice(np.array([2.0 ** -9, 2.0 ** -3, 1.0, 1.0], dtype=np.float32), size=N)
+    scales = (scales * factor[None, :]).astype(np.float32)
+    scales[0, rng.choice(N, 3)] *= np.float32(1.9)           # and the largest value sits alone at the top
+    for negative in (False, True):
+        if negative:
+            scales[0, rng.choice(N, 2000, replace=False)] *= np.float32(-1.0)
+        ix = load_with_ratio(planes, scales, 8)
+        on, off, shares = _search_both_ways(ix, qp, qs, k)
+        for (i1, s1), (i0, s0) in zip(on, off):
+            np.testing.assert_array_equal(i1, i0); np.testing.assert_array_equal(s1, s0)
+        for q in range(4):
+            check_topk(planes, scales, qp[q], qs[q], k, on[q][0][0], on[q][1][0])
+        assert 0 < np.mean(shares) < 0.5, shares
+        rbe.rbe_free(ix)
 
 
 def test_last_level_in_two_parts_gives_the_same_results():
