@@ -161,12 +161,13 @@ int rbe_encode_corpus(rbe_index **out, const float *x, uint64_t n_items,
 
 /* Ends loading: applies RBE_COSINE if requested, derives the side arrays of the
  * one-query search (per row of 256 items the largest value of the last scale
- * array; for general scales with 2 or more planes also half-precision copies of
- * the other scale arrays: 2 * (n_planes - 1) bytes of device memory per item),
- * waits for the stream, and makes the index searchable.  Items never loaded
- * score as all-(-1) vectors with scale 0.  If the half-precision copies do not
- * fit in device memory the index works without them (the one-query search then
- * reads the fp32 arrays they stand for).                                      */
+ * array; for general scales with 2 or more planes also one-byte copies of the
+ * other scale arrays: n_planes - 1 bytes of device memory per item, 4 at 4
+ * planes), waits for the stream, and makes the index searchable.  Items never
+ * loaded score as all-(-1) vectors with scale 0.  If the one-byte copies do not
+ * fit in device memory, or a scale is negative or not finite, the index works
+ * without them (the one-query search then reads the fp32 arrays they stand
+ * for).                                                                       */
 int rbe_finalize(rbe_index *ix, void *hip_stream);
 
 /* rbe_index_create + one rbe_load_chunk of the whole corpus + rbe_finalize.
@@ -286,7 +287,7 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
  * largest value the remaining planes could add -- reaches the threshold; such rows
  * are then scored in full, so the results are those of the plain scan bit for bit.
  * enabled = 0 switches it off (every plane of every item is read); default 1;
- * 2 = on, but without the half-precision scale copies (what an index uses whose
+ * 2 = on, but without the one-byte scale copies (what an index uses whose
  * copies did not fit in device memory).                                          */
 int rbe_debug_set_progressive(rbe_index *ix, int enabled);
 

@@ -414,7 +414,7 @@ def rbe_debug_set_plan_split(ix: Index, mode: int):
 
 
 def rbe_debug_set_progressive(ix: Index, enabled):
-    """False/0 = off, True/1 = on, 2 = on without the half-precision scale copies."""
+    """False/0 = off, True/1 = on, 2 = on without the one-byte scale copies."""
     _check(load_library().rbe_debug_set_progressive(ix.handle, int(enabled)))
 
 

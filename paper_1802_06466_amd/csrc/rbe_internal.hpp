@@ -15,7 +15,7 @@ struct KernelSel {
     bool single;      // one query per call
     uint32_t qlen = 1;   // near-lossless mode: length of the per-group priority queue (1 or 2)
     bool progressive = false;   // exact mode, last level, P >= 2: read the last plane only where the others cannot rule a row out
-    bool hints = false;         // ... one query, general scales: the index holds half-precision copies of the scales
+    bool hints = false;         // ... one query, general scales: the index holds one-byte copies of the scales
 };
 
 // Grid = min(units, n_cu * per_cu); per_cu == 0 means "as many workgroups as are

@@ -451,7 +451,8 @@ __global__ void scale_array_max(const char* __restrict__ tiles, const TileGeom g
             mx = b > mx ? b : mx;
         }
         for (int d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(mx, d); mx = o > mx ? o : mx; }
-        if ((threadIdx.x & 63) == 0 && mx) atomicMax(&out[j], mx);
+        // (most waves find the maximum already there: a plain look first keeps the atomics few)
+        if ((threadIdx.x & 63) == 0 && mx > *reinterpret_cast<const volatile uint32_t*>(&out[j])) atomicMax(&out[j], mx);
     }
 }
 

@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
 // is tight: the rows that hold items of the query's own neighbourhood) and the partial scores continued to the
 // full ones, exactly as scan_exact forms them.  What is appended is therefore identical to scan_exact's; what is
 // read is (8W + 4)(P-1) of the (8W + 4) P bytes of most items (general scales; see scan_exact_prog_hint for the
-// variant that streams half-precision scale copies).  (The residual scales decay from plane to plane, so the last plane is the one
+// variant that streams one-byte scale copies).  (The residual scales decay from plane to plane, so the last plane is the one
 // whose absence costs the bound least; with fewer planes in the stream the bound let most rows through on
 // clustered data.)
 // A wave that finds itself fetching the last plane for more than a quarter of its rows (a loose threshold, or
@@ -755,7 +755,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
 }
 
-// scan_exact_fq_prog for general scales with the half-precision scale copies in the stream (see
+// scan_exact_fq_prog for general scales with the one-byte scale copies in the stream (see
 // scan_exact_prog_hint): rows that pass the bound are scored from scratch by score_item_fq.
 template <int W, int P>
 __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a)
