@@ -386,8 +386,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 // <= h_j t_j + 2^-6 h_j M, slightly more in the kernel), the last one as its largest value over the row.  A row that the bound lets through reads its last plane
 // and its P fp32 scale arrays and is scored from scratch by score_item, so what is appended is still exactly
 // what scan_exact appends.  16 + 2 instead of 16 + 8 streamed bytes per item at d = 64, P = 3.
-// In the whole-row fallback the bound is evaluated for one row in eight only (it shares nothing with the exact
-// score here), enough to notice when it starts to prune again.
+// A wave whose bound lets most rows through stops evaluating it (whole-row fallback: every lane reads and scores
+// all of its items) but for one row in eight, enough to notice when it starts to prune again.  The two register
+// sets (this row, the next one in flight) hold the streamed planes only and swap roles from row to row.
 template <int W, int P, int PQ>
 __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
 {
@@ -444,27 +445,23 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
     load_hints(hc, p);
     float amax = a.row_amax[(size_t)p * kWavesPerBlock + wave], amax_n = 0.0f;
-    bool whole = false;    // wave-uniform: cur holds every plane and scale already
-    for (;;) {
+    bool whole = false;    // wave-uniform: whole-row fallback, the bound is not evaluated for this row
+    // One row: start the loads of the next one into the other register set, judge and score this one.  The two
+    // register sets swap roles from row to row (two copies of the code) instead of being copied.
+    auto step = [&](RowRegs<W, P, S>& cur, Hints& hc, float& amax, RowRegs<W, P, S>& nxt, Hints& hn, float& amax_n)
+                    __attribute__((always_inline)) -> bool {
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
         const bool whole_next = passed * 4 > probed + 32;     // wave-uniform
         if (has_next) {
-            const char* tn = a.tiles + (size_t)pn * tile_bytes;
-            load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
-            if (!whole_next || ((rows + 1u) & 7u) == 0u) {      // in the whole-row fallback only the rows that are probed
-                load_hints(hn, pn);
-                amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
-            }
-            if (whole_next) {
-                load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
-                load_row_scales<W, P, S>(nxt, tn, wave, lane);
-                extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item
-            }
+            load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            load_hints(hn, pn);
+            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
         }
         bool reach = true;
-        uint32_t mine = 0;     // which of this lane's items can still reach the threshold
+        uint32_t mine = (1u << kItemsPerLane) - 1u;     // which of this lane's items can still reach the threshold
         if (!whole || (rows & 7u) == 0u) {
+            mine = 0;
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
                 float s = floor_c, all = 0.0f;
@@ -492,13 +489,11 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
             passed += reach ? 1u : 0u;
         }
         ++rows;
-        full_rows += (whole || reach) ? 1u : 0u;
-        if (reach && whole) {
-            fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
-        } else if (reach) {
+        full_rows += reach ? 1u : 0u;
+        if (reach) {
             // only the lanes that hold such an item read the rest of their items' data (the memory system fetches
             // the cache lines they touch, not the row) and score; an item whose bound is below the threshold cannot
-            // be a survivor
+            // be a survivor.  (Whole-row fallback, rows that are not probed: every lane, every item.)
             const char* tile = a.tiles + (size_t)p * tile_bytes;
             const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
             const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset()) + wave * kRow;
@@ -548,12 +543,13 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
             }
             if (__ballot(any)) fill = stage_scores<W, true>(sv, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
         }
-        if (!has_next) break;
-        cur = nxt;
-        hc = hn;
-        amax = amax_n;
         whole = whole_next;
         p = pn;
+        return has_next;
+    };
+    for (;;) {
+        if (!step(cur, hc, amax, nxt, hn, amax_n)) break;
+        if (!step(nxt, hn, amax_n, cur, hc, amax)) break;
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
