@@ -191,9 +191,9 @@ int ensure_fixed(rbe_index* ix)
 {
     if (ix->d_count) return RBE_OK;
     const size_t Q = RBE_MAX_QUERIES;
-    HIP_TRY(hipMalloc(&ix->d_count, Q * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ix->d_count, Q * rbe::kCountStride * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&ix->d_tau, Q * sizeof(uint64_t)));
-    HIP_TRY(hipMalloc(&ix->d_kmax, Q * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&ix->d_kmax, Q * rbe::kKmaxStride * sizeof(uint64_t)));
     // query words and coefficients share one block (coefficients at a fixed offset) so that one copy stages both
     const size_t words_bytes = Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t), coef_bytes = Q * (RBE_MAX_PLANES + 1 + 2) * sizeof(float);
     HIP_TRY(hipMalloc(&ix->d_qwords, words_bytes + coef_bytes));
@@ -925,6 +925,7 @@ struct SearchCtx {
     bool float_query;   // hybrid scoring: fp32 queries through byte tables
     bool batch_mfma;    // exact mode, several queries: matrix-core scan
     bool float_batch;   // ... of full-precision queries
+    uint32_t look_from = 0;   // matrix-core scan: the levels from this one on report how their first looks went
 };
 
 // dense: a coarse level of the plan, where a large share of the items passes the (still loose) threshold.
@@ -950,7 +951,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
             fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
             fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints; fa.deep_units = ix->d_status + 14;
             for (int j = 0; j < 3; ++j) fa.hint_base[j] = ix->hint_base[j];
-            fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q, ix->d_kmax + q, c.cap};
+            fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q * rbe::kCountStride, ix->d_kmax + q * rbe::kKmaxStride, c.cap};
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
         }
@@ -958,7 +959,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         BatchArgs ba;
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
         ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.q_mass = ix->d_unscale + 2 * RBE_MAX_QUERIES; ba.tau = ix->d_tau;
-        ba.look_stats = ix->d_status + 12;
+        ba.look_stats = level_slot >= c.look_from ? ix->d_status + 12 : nullptr;
         ba.row_amax = ix->d_row_amax; ba.row_asum = ix->d_row_amax ? ix->d_row_amax + (size_t)ix->layout.n_tiles * (kTileItems / kRow) : nullptr; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
         ba.rescore = batch_rescore(ix, c.float_batch);
@@ -1059,6 +1060,21 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     const bool pruning = ix->progressive != 0 && ix->P >= 2 && ps.holdoff == 0;
     if (mode == RBE_SELECT_EXACT) {
         for (const Level& lv : make_plan(ix->layout, c.cap, k)) plan.push_back(Round{lv.p_begin, lv.p_end, 1, 0});
+        // A batch on the matrix cores: the level before the last starts from the k-th best of a 1/ratio sample of
+        // itself, is dense by the rule below, and would go to the XOR/popcount scan at n_queries times the cost of
+        // one query (a tenth of a 16-query search at 1e9 items).  Taken in two parts, only its first eighth is
+        // dense; the rest starts from the k-th best of an eighth of it and runs on the matrix cores.
+        if (c.batch_mfma && !c.float_batch && ix->batch_path == 0 && ix->plan_split != 1 && plan.size() >= 2 &&
+            plan.size() + 2 <= RBE_MAX_LEVELS) {
+            const size_t l2 = plan.size() - 2;
+            const Round lv = plan[l2];
+            if (lv.end - lv.begin >= 4096u) {
+                const uint32_t mid = lv.begin + (lv.end - lv.begin) / 8;
+                plan[l2] = Round{lv.begin, mid, 1, 0};
+                plan.insert(plan.begin() + (std::ptrdiff_t)l2 + 1, Round{mid, lv.end, 1, 0});
+            }
+        }
+        c.look_from = plan.empty() ? 0u : (uint32_t)plan.size() - 1;     // the last level (both parts of it, if it is split below)
         // The pruning scans of the last level need a threshold that lies inside the query's neighbourhood.  When the
         // last level's own threshold (the k-th best of a 1/ratio sample) turned out too loose for that on this
         // corpus, the level is taken in two parts: an eighth of it first, after which the rest starts from the k-th

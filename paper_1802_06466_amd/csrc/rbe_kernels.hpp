@@ -329,8 +329,8 @@ constexpr int kStage = 512;  // entries per wave; an append adds at most 64
 
 struct CandList {
     uint64_t* cand;   // [Q][cap]
-    uint32_t* count;  // [Q]
-    uint64_t* kmax;   // [Q] largest key ever appended (the selection starts its radix descent below
+    uint32_t* count;  // [Q], kCountStride words apart
+    uint64_t* kmax;   // [Q], kKmaxStride words apart: largest key ever appended (the selection starts its radix descent below
                       //     the bits that the threshold and this maximum have in common)
     uint32_t cap;
 };
@@ -364,7 +364,7 @@ __device__ __forceinline__ void stage_flush1(uint64_t* s_keys, uint32_t fill, co
         }
     }
     mx = wave_max_u64(mx);
-    if (lane == 0) atomicMax((unsigned long long*)a.kmax, (unsigned long long)mx);
+    if (lane == 0 && mx > *reinterpret_cast<const volatile uint64_t*>(a.kmax)) atomicMax((unsigned long long*)a.kmax, (unsigned long long)mx);
     __builtin_amdgcn_wave_barrier();
 }
 
@@ -388,6 +388,12 @@ __device__ __forceinline__ uint32_t stage_append1(bool ok, uint64_t key, uint64_
 // the query's global list with ONE atomic.  With a queue shared by all queries every group
 // of 64 staged entries held up to 16 different queries and needed as many atomics; thousands
 // of waves then serialised on the few per-query counters.
+// Per-query counters (appended candidates, largest key) sit one to a 128-byte line: every wave of a scan adds to
+// them, and atomics on one line are served one after the other (16 queries' counters in one line made the coarse
+// levels of a 16-query search wait for 10^5 atomics in single file).
+constexpr uint32_t kCountStride = 32;   // in uint32_t
+constexpr uint32_t kKmaxStride = 16;    // in uint64_t
+
 struct MultiStage {
     uint64_t* keys;    // [n_sub][qcap] this wave's LDS
     uint32_t* cnt;     // [n_sub + 1]: fill of each sub-queue, then a spare word (see mstage_append)
@@ -404,7 +410,7 @@ __device__ __forceinline__ void mstage_flush_query(const MultiStage& ms, uint32_
     __builtin_amdgcn_wave_barrier();
     const uint32_t gq = ms.q_base + q;
     uint32_t base = 0;
-    if (lane == 0) base = atomicAdd(a.count + gq, n);
+    if (lane == 0) base = atomicAdd(a.count + gq * kCountStride, n);
     base = __shfl(base, 0);
     uint64_t mx = 0;
     if ((uint32_t)lane < n) {   // n <= qcap <= 64
@@ -413,7 +419,9 @@ __device__ __forceinline__ void mstage_flush_query(const MultiStage& ms, uint32_
         if (pos < a.cap) a.cand[(size_t)gq * a.cap + pos] = mx;
     }
     mx = wave_max_u64(mx);
-    if (lane == 0) atomicMax((unsigned long long*)(a.kmax + gq), (unsigned long long)mx);
+    // (most flushes do not raise the maximum: a plain look first saves the atomic)
+    if (lane == 0 && mx > *reinterpret_cast<const volatile uint64_t*>(a.kmax + gq * kKmaxStride))
+        atomicMax((unsigned long long*)(a.kmax + gq * kKmaxStride), (unsigned long long)mx);
     __builtin_amdgcn_wave_barrier();
 }
 

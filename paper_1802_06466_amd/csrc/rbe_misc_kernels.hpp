@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
     const uint32_t q = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     uint64_t* keys = a.cand + (size_t)q * a.cap;
-    const uint32_t appended = a.count[q];
+    const uint32_t appended = a.count[q * kCountStride];
     const uint32_t n = appended < a.cap ? appended : a.cap;
     const uint32_t k = a.k;
     if (tid == 0) {
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
         m = k;
         // ---- every key lies in [threshold used by the scan, largest key appended]: the bits
         //      these two have in common are common to all keys and need no radix round
-        const uint64_t lo_key = a.tau[q], hi_key = a.kmax[q];
+        const uint64_t lo_key = a.tau[q], hi_key = a.kmax[q * kKmaxStride];
         const uint64_t diff = lo_key ^ hi_key;
         int pos = diff ? 64 - __clzll((long long)diff) : 0;   // low `pos` bits are undetermined
         uint64_t mask = pos >= 64 ? 0ull : ~((1ull << pos) - 1ull);
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
 
     if (!a.final_pass) {
         for (uint32_t i = tid; i < m; i += kSelBlock) keys[i] = skeys[i];
-        if (tid == 0) a.count[q] = m;
+        if (tid == 0) a.count[q * kCountStride] = m;
         return;
     }
 
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
     for (uint32_t i = m + tid; i < pow2; i += kSelBlock) skeys[i] = 0;
     __syncthreads();
     bitonic_desc(skeys, pow2);
-    if (tid == 0) a.count[q] = m;
+    if (tid == 0) a.count[q * kCountStride] = m;
     for (uint32_t i = tid; i < k; i += kSelBlock) {
         int64_t id = -1;
         float sc = -__builtin_inff();
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
 __global__ void init_state(uint32_t* count, uint64_t* tau, uint64_t* kmax, uint32_t* status, uint32_t n_queries)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_queries) { count[i] = 0; tau[i] = 0; kmax[i] = 0; }
+    if (i < n_queries) { count[i * kCountStride] = 0; tau[i] = 0; kmax[i * kKmaxStride] = 0; }
     if (i < 16) status[i] = 0;    // flags; rows read in full by the progressive scan, per level
 }
 
