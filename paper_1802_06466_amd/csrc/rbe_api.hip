@@ -982,6 +982,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0;
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
         sa.deep_rows = ix->d_status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints; sa.deep_units = ix->d_status + 14;
+        sa.deep_pairs = level_slot >= c.look_from ? ix->d_status + 9 : nullptr;
         for (int j = 0; j < 3; ++j) sa.hint_base[j] = ix->hint_base[j];
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
@@ -1150,7 +1151,13 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     // (one launch per query with fp32 queries, one per call otherwise: rows_last counts them all)
     if (!fallback && mode == RBE_SELECT_EXACT && !c.batch_mfma && pruning && plan.size() >= 2) {
         const uint64_t rows_last = (uint64_t)(plan.back().end - plan.back().begin) * (kTileItems / kRow) * (c.float_query ? c.Q : 1u);
-        const bool loose = (uint64_t)ix->h_status[1 + plan.size() - 1] * 2 > rows_last;
+        bool loose = (uint64_t)ix->h_status[1 + plan.size() - 1] * 2 > rows_last;
+        if (c.Q > 1 && !c.float_query) {
+            // several binary queries on the XOR/popcount scan: what counts is the share of (query, row) pairs scored
+            // in full over the whole last level (most rows are needed by some query of a large batch)
+            const uint64_t pairs = (uint64_t)(plan.back().end - plan[c.look_from].begin) * (kTileItems / kRow) * c.Q;
+            loose = (uint64_t)ix->h_status[9] * 2 > pairs;
+        }
         if (loose && ix->plan_split == 0) {
             if (!split && !ps.split_active) {
                 ps.split_active = true;      // next search: the last level in two parts

@@ -482,6 +482,7 @@ struct ScanArgs {
     uint32_t p_begin, p_end;  // physical tile range this launch covers
     uint32_t* deep_rows;      // progressive scan: += rows whose planes 1.. had to be read
     uint32_t* deep_units;     // one-query progressive scans: += what the lanes asked for beyond the stream, in units of 8 bytes
+    uint32_t* deep_pairs;     // scan_exact_batch_prog: += (query, row) pairs that were scored in full (may be null)
     const float* row_amax;    // [physical tile][4 rows] largest value of the last scale array over the row (one-query
                               // progressive scans; unused where there is no scale array)
     const uint32_t* hints;    // general scales: one-byte copies of the scale arrays 0 .. P-2 in lane order (scale_hints)

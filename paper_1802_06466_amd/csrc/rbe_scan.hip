@@ -166,18 +166,20 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
     const size_t tile_bytes = geom.tile_bytes();
     const uint32_t nq = a.n_queries;
     const float* masses = a.qcoef + (size_t)nq * (PQ + 1);
-    uint32_t full_rows = 0, rows = 0, probed = 0, probe_full = 0;   // probed: rows taken the progressive way
+    uint32_t full_rows = 0, rows = 0, full_pairs = 0;
+    uint32_t probed = 0, probe_full = 0;   // (query, row) pairs taken the progressive way, and those of them scored in full
     for (uint32_t p = a.p_begin + blockIdx.x; p < a.p_end; p += G) {
         const char* tile = a.tiles + (size_t)p * tile_bytes;
         RowRegs<W, P, S> cur;
         load_row_planes<W, P, S, 0, F>(cur, tile, wave, lane);
         load_row_scales<W, P, S>(cur, tile, wave, lane);
-        // a wave that ends up reading the last plane of more than half of its rows (a loose threshold, many queries)
-        // asks for it together with the others and, bounds being of no use to it, scores like scan_exact; one row in
-        // sixteen still goes the progressive way, to notice when that changes
-        const bool plain = probe_full * 2 > probed + 16 && (rows & 15u) != 0u;     // wave-uniform
+        // a wave for which more than half of the (query, row) pairs go on to the full score (a loose threshold) asks
+        // for the last plane together with the others and, bounds being of no use to it, scores like scan_exact; one
+        // row in sixteen still goes the progressive way, to notice when that changes.  (Pairs, not rows: with many
+        // queries most rows are needed by some query while most pairs still stop at the bound.)
+        const bool plain = probe_full * 2 > probed + 16 * nq && (rows & 15u) != 0u;     // wave-uniform
         bool have_last = plain;
-        if (plain) { load_row_planes<W, P, S, F, P>(cur, tile, wave, lane); ++full_rows; }
+        if (plain) { load_row_planes<W, P, S, F, P>(cur, tile, wave, lane); ++full_rows; full_pairs += nq; }
         ++rows;
         __builtin_amdgcn_sched_barrier(0);
         if (plain) {
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
             }
             continue;
         }
-        ++probed;
+        probed += nq;
         QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
         uint64_t tau_n = a.tau[0];
         QueryMass mass_n{masses[0], masses[1]};
@@ -229,8 +231,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
                     load_row_planes<W, P, S, F, P>(cur, tile, wave, lane);
                     have_last = true;
                     ++full_rows;
-                    ++probe_full;
                 }
+                ++probe_full;
+                ++full_pairs;
                 float s[kItemsPerLane];
                 bool any = false;
 #pragma unroll
@@ -244,6 +247,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog(const ScanArgs a
     }
     mstage_drain(ms, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+    if (a.deep_pairs && lane == 0 && full_pairs) atomicAdd(a.deep_pairs, full_pairs);
 }
 
 // One query, P >= 2, progressive: the stream carries planes 0 .. F-1 (F = P - 1) and the scale arrays 0 .. S-2
