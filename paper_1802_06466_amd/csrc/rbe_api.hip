@@ -78,7 +78,8 @@ struct rbe_index {
     // (ids and scores packed for the Q and k of the current call).  The pointers below point into it.
     char* d_result = nullptr;
     char* h_result = nullptr;       // pinned mirror
-    uint32_t* d_status = nullptr;
+    uint32_t* d_status = nullptr;   // 16 words: [0] flags, [1..8] rows read in full per level, [9] (query, row) pairs scored in
+                                    // full by the batch progressive scan, [12] [13] first looks of the matrix-core scan, [14] deep units
     uint32_t* d_seen = nullptr;     // [RBE_MAX_LEVELS][RBE_MAX_QUERIES]
     uint32_t* d_aops = nullptr;     // matrix-core query operands (BatchArgs::a_ops)
     uint32_t* h_aops = nullptr;
