@@ -560,6 +560,218 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
 }
 
+// scan_exact_prog_hint for several queries per call (2 .. 7 in practice): the same stream (planes 0 .. P-2, their
+// one-byte scale copies, the row's largest last scale), every query's bound per item, and for the items that some
+// query's bound lets through the lanes that hold them read the last plane and the fp32 scales once; every query
+// then scores those items from scratch.  Appends what the batch form of scan_exact appends.  Against
+// scan_exact_batch_prog, which streams the fp32 scales (28 instead of 18 bytes per item at d = 64, P = 3), the gain
+// is in the small batches that are still bound by memory.
+template <int W, int P, int PQ>
+__global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanArgs a)
+{
+    constexpr int MODE = kModeScaled;
+    constexpr int S = P, F = P - 1;
+    constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
+    extern __shared__ __align__(16) unsigned char s_dynamic[];
+    __shared__ uint32_t s_cnt_all[kWavesPerBlock][65];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = reinterpret_cast<uint64_t*>(s_dynamic) + (size_t)wave * a.stage_entries;
+    const uint32_t n_sub = sub_queues_for(a.n_queries);
+    const uint32_t per_sub = a.stage_entries / n_sub;
+    const MultiStage ms{s_keys, s_cnt_all[wave], per_sub > 64u ? 64u : per_sub, 0u, n_sub};
+    s_cnt_all[wave][lane] = 0;
+    if (lane == 0) s_cnt_all[wave][64] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t nq = a.n_queries;
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    uint32_t rows = 0, full_rows = 0, full_pairs = 0;
+    uint32_t probed = 0, passed = 0;   // (query, row) pairs whose bound was evaluated, and those of them it let through
+    uint32_t extra8 = 0;        // bytes / 8 asked for beyond the stream (wave total, kept in lane 0's terms)
+    const float* masses = a.qcoef + (size_t)nq * (PQ + 1);
+
+    struct Hints { uint32_t w[NW]; };
+    auto load_hints = [&](Hints& h, uint32_t tile_p) {
+        const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
+        if constexpr (NW == 1) {
+            h.w[0] = __builtin_nontemporal_load(src);
+        } else if constexpr (NW == 2) {
+            const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+            h.w[0] = v.x; h.w[1] = v.y;
+        } else {
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+            h.w[0] = v.x; h.w[1] = v.y; h.w[2] = v.z; h.w[3] = v.w;
+        }
+    };
+    // hint byte (3-bit exponent above base_j, 5-bit mantissa) -> fp32
+    const uint32_t hb0 = (uint32_t)a.hint_base[0] << 5, hb1 = (uint32_t)a.hint_base[1] << 5, hb2 = (uint32_t)a.hint_base[2] << 5;
+    auto hint = [&](const Hints& h, int j, int m) {
+        const uint32_t c = (h.w[j] >> (8 * m)) & 255u;
+        return __uint_as_float((c + (j == 0 ? hb0 : (j == 1 ? hb1 : hb2))) << 18);
+    };
+    // a scale below the smallest hint of its array, 2^(base_j - 127), is off by up to that much instead
+    float floor_h = 0.0f;
+    for (int j = 0; j < F; ++j) floor_h += __uint_as_float((uint32_t)a.hint_base[j] << 23);
+    floor_h *= 1.0001f;
+
+    RowRegs<W, P, S> cur, nxt;
+    Hints hc, hn;
+    load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_hints(hc, p);
+    float amax = a.row_amax[(size_t)p * kWavesPerBlock + wave], amax_n = 0.0f;
+    bool whole = false;    // wave-uniform: whole-row fallback, the bound is not evaluated for this row
+    // One row: start the loads of the next one into the other register set, judge and score this one.  The two
+    // register sets swap roles from row to row (two copies of the code) instead of being copied.
+    auto step = [&](RowRegs<W, P, S>& cur, Hints& hc, float& amax, RowRegs<W, P, S>& nxt, Hints& hn, float& amax_n)
+                    __attribute__((always_inline)) -> bool {
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        const bool whole_next = passed * 4 > probed + 32 * nq;     // wave-uniform
+        if (has_next) {
+            load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            load_hints(hn, pn);
+            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
+        }
+        bool reach = true;
+        uint32_t mine = (1u << kItemsPerLane) - 1u;     // which of this lane's items can still reach some query's threshold
+        uint32_t row_pairs = nq;                         // queries for which some item of the row can
+        if (!whole || (rows & 7u) == 0u) {
+            mine = 0;
+            row_pairs = 0;
+            QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+            uint64_t tau_n = a.tau[0];
+            QueryMass mass_n{masses[0], masses[1]};
+            for (uint32_t q = 0; q < nq; ++q) {
+                const QueryRegs<W, PQ> q0 = qn;
+                const float taus0 = threshold_score(tau_n);
+                const QueryMass mass = mass_n;
+                if (q + 1 < nq) {
+                    qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
+                    tau_n = a.tau[q + 1];
+                    mass_n = QueryMass{masses[2 * (q + 1)], masses[2 * (q + 1) + 1]};
+                }
+                const float slack_all = 2.0f * mass.y + 0.015875f * mass.x;
+                const float floor_c = floor_h * mass.x;
+                const float mass_last = mass.x + 2.0f * mass.y;
+                uint32_t mine_q = 0;
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m) {
+                    float s = floor_c, all = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < F; ++j) {
+                        float t = q0.bias;
+#pragma unroll
+                        for (int i = 0; i < PQ; ++i) {
+                            uint32_t pc = 0;
+#pragma unroll
+                            for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[j][m][h] ^ q0.w[i][h]);
+                            t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                        }
+                        const float hj = hint(hc, j, m);
+                        s = __fmaf_rn(hj, t, s);
+                        all += hj;
+                    }
+                    // (the bound of scan_exact_prog_hint)
+                    const float ub = __fmaf_rn(all, slack_all, __fmaf_rn(amax, mass_last, s));
+                    mine_q |= !(ub < taus0) ? (1u << m) : 0u;      // (a NaN bound does not prune)
+                }
+                mine |= mine_q;
+                row_pairs += __ballot(mine_q != 0u) != 0 ? 1u : 0u;
+            }
+            reach = __ballot(mine != 0u) != 0;
+            probed += nq;
+            passed += row_pairs;
+        }
+        ++rows;
+        full_rows += reach ? 1u : 0u;
+        if (reach) {
+            full_pairs += row_pairs;
+            // only the lanes that hold such an item read the rest of their items' data (the memory system fetches
+            // the cache lines they touch, not the row) and score; an item whose bound is below the threshold cannot
+            // be a survivor.  (Whole-row fallback, rows that are not probed: every lane, every item.)
+            const char* tile = a.tiles + (size_t)p * tile_bytes;
+            const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
+            const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset()) + wave * kRow;
+            // what the lanes ask for: per pair of items (W = 1) or per item, the last plane and S scales
+            if constexpr (W == 1) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) extra8 += (uint32_t)__builtin_popcountll(__ballot((mine & (3u << (2 * h2))) != 0u)) * (2 + S);
+            } else {
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m)
+                    extra8 += ((uint32_t)__builtin_popcountll(__ballot((mine & (1u << m)) != 0u)) * (2 * W + S)) / 2;
+            }
+            if constexpr (W == 1) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2)
+                    if (mine & (3u << (2 * h2))) {
+                        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + h2 * 128 + 2 * lane));
+                        cur.w[P - 1][2 * h2][0] = v.x; cur.w[P - 1][2 * h2][1] = v.y;
+                        cur.w[P - 1][2 * h2 + 1][0] = v.z; cur.w[P - 1][2 * h2 + 1][1] = v.w;
+#pragma unroll
+                        for (int j = 0; j < S; ++j) {
+                            const f32x2 av = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sc + j * kTileItems + h2 * 128 + 2 * lane));
+                            cur.a[j][2 * h2] = av.x; cur.a[j][2 * h2 + 1] = av.y;
+                        }
+                    }
+            } else {
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m)
+                    if (mine & (1u << m)) {
+#pragma unroll
+                        for (int h = 0; h < W / 2; ++h) {
+                            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pj + (size_t)(m * 64 + lane) * W) + h);
+                            cur.w[P - 1][m][4 * h + 0] = v.x; cur.w[P - 1][m][4 * h + 1] = v.y;
+                            cur.w[P - 1][m][4 * h + 2] = v.z; cur.w[P - 1][m][4 * h + 3] = v.w;
+                        }
+#pragma unroll
+                        for (int j = 0; j < S; ++j) cur.a[j][m] = __builtin_nontemporal_load(sc + j * kTileItems + m * 64 + lane);
+                    }
+            }
+            // every query scores the items that some query's bound let through (an item whose own bound is below
+            // the threshold scores below it too, and is not appended)
+            QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+            uint64_t tau_n = a.tau[0];
+            for (uint32_t q = 0; q < nq; ++q) {
+                const QueryRegs<W, PQ> qr = qn;
+                const uint64_t tau = tau_n;
+                if (q + 1 < nq) {
+                    qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
+                    tau_n = a.tau[q + 1];
+                }
+                const float taus = threshold_score(tau);
+                float sv[kItemsPerLane];
+                bool any = false;
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane; ++m) {
+                    sv[m] = -__builtin_inff();
+                    if (mine & (1u << m)) sv[m] = score_item<W, P, PQ, MODE>(cur, m, qr);
+                    any |= (sv[m] >= taus);
+                }
+                if (__ballot(any)) stage_scores<W, false>(sv, tau, taus, q, p, wave, lane, s_keys, ms, 0, a);
+            }
+        }
+        whole = whole_next;
+        p = pn;
+        return has_next;
+    };
+    for (;;) {
+        if (!step(cur, hc, amax, nxt, hn, amax_n)) break;
+        if (!step(nxt, hn, amax_n, cur, hc, amax)) break;
+    }
+    mstage_drain(ms, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+    if (a.deep_pairs && lane == 0 && full_pairs) atomicAdd(a.deep_pairs, full_pairs);
+    if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
+}
+
+
 // ---------------------------------------------------------------- hybrid scoring (fp32 query)
 // t_j = sum over the 8W bytes of plane j of lut[p][byte], accumulated in fp32 in byte order;
 // kModeScaled: s = sum_j fma(a_j, t_j, s).  Dyadic modes: s = (sum_j 2^-j t_j) [* the item's scale].
@@ -995,7 +1207,7 @@ ScanFn prog_fn_m(int mode, bool single, bool hints)
 {
     if constexpr (P >= 2) {
         if (mode == kModeScaled) {
-            if (!single) return scan_exact_batch_prog<W, P, PQ, kModeScaled>;
+            if (!single) return hints ? scan_exact_batch_prog_hint<W, P, PQ> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
             return hints ? scan_exact_prog_hint<W, P, PQ> : scan_exact_prog<W, P, PQ, kModeScaled>;
         }
         if constexpr (dyadic_supported(W)) {

@@ -1095,7 +1095,7 @@ def test_progressive_scan_for_small_batches(d, P, Pq, flags):
     qs_o = qs if qs is not None else np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (16, 1))
     rbe.rbe_debug_set_batch_path(ix, 1)
     rbe.rbe_debug_set_plan_split(ix, 1)         # no automatic choices
-    for Q in (2, 5, 7, 16):
+    for Q in (2, 4, 5, 7, 16):       # up to 4: the scan that streams the one-byte scale copies; above: the fp32 scales
         res = {}
         for prog in (True, False):
             rbe.rbe_debug_set_progressive(ix, prog)
