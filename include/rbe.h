@@ -29,8 +29,8 @@
  * call.  (RBE_DYADIC: the half-precision form is exact and is the score.)  Such a
  * call reads the corpus once per 32 queries (once per 16 for RBE_DYADIC with dim
  * 128 and 3 or 4 planes).
- * With one query per call (exact mode, 2 or more planes) the last pass over the
- * corpus reads an item's last plane only where an upper bound on its score -- the
+ * With fewer than 8 queries per call (exact mode, 2 or more planes) the last pass
+ * over the corpus reads an item's last plane only where an upper bound on its score -- the
  * exact contribution of the other planes plus the largest value the last plane
  * could add -- reaches the current threshold; such items are then scored in full
  * by the formula above, so the results are unchanged (rbe_debug_set_progressive).
