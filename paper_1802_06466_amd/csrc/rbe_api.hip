@@ -100,6 +100,11 @@ struct rbe_index {
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
     float fq_mass[RBE_MAX_QUERIES][2] = {};   // fp32 queries: {x, 2^-19 x}, x >= sum_d |q_d| (1 + 2^-18): bounds any plane's table sum
+    // fp32 queries, one scan per query, general scales with scale copies: a 4-plane binary approximation of each
+    // query is staged as well (stage_float_approximations) and the last level's bound is formed from it
+    bool fq_binary = false;
+    float fq_bmass[RBE_MAX_QUERIES][2] = {};  // its mass (query_mass)
+    float fq_resid[RBE_MAX_QUERIES] = {};     // >= sum_d |q_d - qhat_d|
     float* d_lut = nullptr;         // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
     float* h_lut = nullptr;
     uint32_t* d_qwords = nullptr;   // [Q][PQ][2W]
@@ -329,6 +334,35 @@ int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t s
     }
     HIP_TRY(hipMemcpyAsync(ix->d_lut, ix->h_lut, (size_t)Q * per_q * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
+}
+
+// Binary approximations of fp32 queries for the bound of scan_exact_fq_prog_hint: the residual encoder of
+// rbe_encode_query with RBE_MAX_PLANES planes, staged like binary queries; per query the mass of the approximation
+// qhat and R >= sum_d |q_d - qhat_d| (in double, rounded up).
+int stage_float_approximations(rbe_index* ix, const float* q, uint32_t Q, hipStream_t st)
+{
+    const uint32_t PQ = RBE_MAX_PLANES, W = ix->W;
+    std::vector<uint64_t> planes((size_t)Q * PQ * W);
+    std::vector<float> scales((size_t)Q * PQ);
+    for (uint32_t n = 0; n < Q; ++n) {
+        const float* x = q + (size_t)n * ix->dim;
+        uint64_t* pl = planes.data() + (size_t)n * PQ * W;
+        float* sc = scales.data() + (size_t)n * PQ;
+        const int rc = rbe_encode_query(x, ix->dim, PQ, pl, sc);
+        if (rc) return rc;
+        double resid = 0.0;
+        for (uint32_t d = 0; d < ix->dim; ++d) {
+            double v = 0.0;
+            for (uint32_t i = 0; i < PQ; ++i) v += ((pl[(size_t)i * W + d / 64] >> (d % 64)) & 1ull) ? (double)sc[i] : -(double)sc[i];
+            resid += std::fabs((double)x[d] - v);
+        }
+        resid *= 1.0 + std::ldexp(1.0, -20);
+        float rf = (float)resid;
+        if ((double)rf < resid) rf = std::nextafter(rf, INFINITY);
+        ix->fq_resid[n] = rf;
+        query_mass(pl, sc, PQ, ix->dim, false, ix->fq_bmass[n]);
+    }
+    return stage_queries(ix, planes.data(), scales.data(), Q, PQ, st);
 }
 
 // 16-query tiles of a batch, and how many of them one launch of the matrix-core scan takes (1 or 2): two while
@@ -952,6 +986,13 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
             fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
             fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints; fa.deep_units = ix->d_status + 14;
             for (int j = 0; j < 3; ++j) fa.hint_base[j] = ix->hint_base[j];
+            fa.qwords = nullptr; fa.qcoef = nullptr; fa.bmass = rbe::QueryMass{0.0f, 0.0f}; fa.resid = 0.0f;
+            if (ix->fq_binary) {
+                fa.qwords = ix->d_qwords + (size_t)q * RBE_MAX_PLANES * 2 * ix->W;
+                fa.qcoef = ix->d_qcoef + (size_t)q * (RBE_MAX_PLANES + 1);
+                fa.bmass = rbe::QueryMass{ix->fq_bmass[q][0], ix->fq_bmass[q][1]};
+                fa.resid = ix->fq_resid[q];
+            }
             fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q * rbe::kCountStride, ix->d_kmax + q * rbe::kKmaxStride, c.cap};
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
@@ -1262,6 +1303,8 @@ int rbe_search_float(rbe_index* ix, const float* q, uint32_t n_queries, uint32_t
     } else {
         c.float_query = true;
         rc = stage_float_queries(ix, q, c.Q, c.st);
+        ix->fq_binary = !rc && ix->mode == rbe::kModeScaled && ix->P >= 2 && ix->d_hints != nullptr;
+        if (ix->fq_binary) rc = stage_float_approximations(ix, q, c.Q, c.st);
     }
     if (rc) return rc;
     return run_search(c, ids_out, scores_out);

@@ -507,6 +507,12 @@ struct FqArgs {
     const uint32_t* hints;    // as in ScanArgs
     int hint_base[3];         // as in ScanArgs
     uint32_t* deep_units;     // as in ScanArgs (counted by scan_exact_fq_prog_hint)
+    // scan_exact_fq_prog_hint<.., BIN = true>: the bound is formed from a 4-plane binary approximation qhat of the
+    // query with XOR/popcounts instead of table sums
+    const uint32_t* qwords;   // [4][2W] this query's approximation (pointers already offset)
+    const float* qcoef;       // [5]
+    QueryMass bmass;          // mass of qhat (query_mass)
+    float resid;              // >= sum_d |q_d - qhat_d|
 };
 
 // Batched scan on the matrix cores (rbe_batch.hip).

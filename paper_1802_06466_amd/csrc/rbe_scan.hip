@@ -969,9 +969,14 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
 
 // scan_exact_fq_prog for general scales with the one-byte scale copies in the stream (see
 // scan_exact_prog_hint): rows that pass the bound are scored from scratch by score_item_fq.
-template <int W, int P>
+// BIN: the bound is formed from a 4-plane binary approximation qhat of the query by XOR/popcounts, as in the
+// binary-query scan, instead of from table sums (8W LDS reads per plane and item).  A plane's table sum q . b is
+// qhat . b + (q - qhat) . b, and the second term is at most R = sum_d |q_d - qhat_d| (a.resid): the bound gains
+// R per unit of the scale sum, about 6 % of the query's mass against the 25 % that the left-out plane costs anyway.
+template <int W, int P, bool BIN>
 __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a)
 {
+    constexpr int PQB = 4;
     constexpr int MODE = kModeScaled;
     constexpr int S = P, F = P - 1;
     constexpr int NW = S - 1 == 3 ? 4 : S - 1;
@@ -991,7 +996,12 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
     const uint64_t tau = a.tau_ptr[0];
     const float taus = threshold_score(tau);
     const QueryMass mass = a.mass;
-    const float slack_all = 2.0f * mass.y + 0.015875f * mass.x;
+    // |a_j t_j - h_j t_j| <= 0.015875 h_j |t_j| with |t_j| at most the mass of what t_j is formed from; BIN: the
+    // roundings of both chains, and a_j R <= 1.04 h_j R
+    const float slack_all = BIN ? 2.0f * (mass.y + a.bmass.y) + 0.015875f * a.bmass.x + 1.04f * a.resid
+                                : 2.0f * mass.y + 0.015875f * mass.x;
+    QueryRegs<W, PQB> qb{};
+    if constexpr (BIN) qb = load_query<W, PQB>(a.qwords, a.qcoef, 0);
     uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0, extra8 = 0;
 
     struct Hints { uint32_t w[NW]; };
@@ -1016,8 +1026,8 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
     // a scale below the smallest hint of its array, 2^(base_j - 127), is off by up to that much instead
     float floor_c = 0.0f;
     for (int j = 0; j < F; ++j) floor_c += __uint_as_float((uint32_t)a.hint_base[j] << 23);
-    floor_c *= 1.0001f * mass.x;
-    const float mass_last = mass.x + 2.0f * mass.y;
+    floor_c *= 1.0001f * (BIN ? a.bmass.x + a.resid : mass.x);
+    const float mass_last = mass.x + 2.0f * mass.y;      // (the last plane's term is bounded by the query's own mass)
 
     RowRegs<W, P, S> cur, nxt;
     Hints hc, hn;
@@ -1051,13 +1061,24 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
 #pragma unroll
                 for (int j = 0; j < F; ++j) {
                     float t = 0.0f;
+                    if constexpr (BIN) {
+                        t = qb.bias;
 #pragma unroll
-                    for (int h = 0; h < 2 * W; ++h) {
-                        const uint32_t w = cur.w[j][m][h];
-                        t += s_lut[4 * h + 0][w & 255u];
-                        t += s_lut[4 * h + 1][(w >> 8) & 255u];
-                        t += s_lut[4 * h + 2][(w >> 16) & 255u];
-                        t += s_lut[4 * h + 3][w >> 24];
+                        for (int i = 0; i < PQB; ++i) {
+                            uint32_t pc = 0;
+#pragma unroll
+                            for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[j][m][h] ^ qb.w[i][h]);
+                            t = __fmaf_rn(qb.m2c[i], (float)pc, t);
+                        }
+                    } else {
+#pragma unroll
+                        for (int h = 0; h < 2 * W; ++h) {
+                            const uint32_t w = cur.w[j][m][h];
+                            t += s_lut[4 * h + 0][w & 255u];
+                            t += s_lut[4 * h + 1][(w >> 8) & 255u];
+                            t += s_lut[4 * h + 2][(w >> 16) & 255u];
+                            t += s_lut[4 * h + 3][w >> 24];
+                        }
                     }
                     const float hj = hint(hc, j, m);
                     s = __fmaf_rn(hj, t, s);
@@ -1293,10 +1314,13 @@ using FqFn = void (*)(const FqArgs);
 using DenseFqFn = void (*)(const char*, const Layout, const float*, uint64_t, uint64_t, float*);
 
 template <int W, int P>
-FqFn fq_prog_fn_m(int mode, bool hints)
+FqFn fq_prog_fn_m(int mode, bool hints, bool binary_bound)
 {
     if constexpr (P >= 2) {
-        if (mode == kModeScaled) return hints ? scan_exact_fq_prog_hint<W, P> : scan_exact_fq_prog<W, P, kModeScaled>;
+        if (mode == kModeScaled) {
+            if (!hints) return scan_exact_fq_prog<W, P, kModeScaled>;
+            return binary_bound ? scan_exact_fq_prog_hint<W, P, true> : scan_exact_fq_prog_hint<W, P, false>;
+        }
         if constexpr (dyadic_supported(W)) {
             if (mode == kModeDyadicNorm) return scan_exact_fq_prog<W, P, kModeDyadicNorm>;
             if (mode == kModeDyadic) return scan_exact_fq_prog<W, P, kModeDyadic>;
@@ -1335,9 +1359,9 @@ hipError_t launch_scan_exact_fq_w<RBE_W>(const KernelSel& k, const FqArgs& a, ui
     FqFn fn = nullptr;
     switch (k.P) {
         case 1: fn = fq_fn_m<RBE_W, 1>(k.mode); break;
-        case 2: fn = k.progressive ? fq_prog_fn_m<RBE_W, 2>(k.mode, k.hints) : fq_fn_m<RBE_W, 2>(k.mode); break;
-        case 3: fn = k.progressive ? fq_prog_fn_m<RBE_W, 3>(k.mode, k.hints) : fq_fn_m<RBE_W, 3>(k.mode); break;
-        case 4: fn = k.progressive ? fq_prog_fn_m<RBE_W, 4>(k.mode, k.hints) : fq_fn_m<RBE_W, 4>(k.mode); break;
+        case 2: fn = k.progressive ? fq_prog_fn_m<RBE_W, 2>(k.mode, k.hints, a.qwords != nullptr) : fq_fn_m<RBE_W, 2>(k.mode); break;
+        case 3: fn = k.progressive ? fq_prog_fn_m<RBE_W, 3>(k.mode, k.hints, a.qwords != nullptr) : fq_fn_m<RBE_W, 3>(k.mode); break;
+        case 4: fn = k.progressive ? fq_prog_fn_m<RBE_W, 4>(k.mode, k.hints, a.qwords != nullptr) : fq_fn_m<RBE_W, 4>(k.mode); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;
