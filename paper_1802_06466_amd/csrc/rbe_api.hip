@@ -46,6 +46,9 @@ void set_error(const char* fmt, ...)
     } while (0)
 
 constexpr uint32_t kMaxEvents = 2 * RBE_MAX_LEVELS + 2;
+// Searches during which the pruning scans stay off after two searches in a row found nothing to prune (a probing
+// search costs about twice a plain one on such a corpus: its waves end up reading whole rows without prefetch).
+constexpr uint32_t kPruneHoldoff = 256;
 // layout of the block a search sends back (rbe_index::d_result)
 constexpr size_t kResultStatusBytes = 256;
 constexpr size_t kResultHeaderBytes = kResultStatusBytes + (size_t)RBE_MAX_LEVELS * RBE_MAX_QUERIES * sizeof(uint32_t);
@@ -1208,7 +1211,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
             } else {
                 // not even the tighter threshold lets them prune (or the level is too small to split): plain scans
                 // for a while, then another try
-                ps.split_active = false; ps.holdoff = 64;
+                ps.split_active = false; ps.holdoff = kPruneHoldoff;
             }
         }
     }
@@ -1218,7 +1221,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         const bool loose = (uint64_t)ix->h_status[13] * 2 > ix->h_status[12];
         if (loose && ix->plan_split == 0 && ps.holdoff == 0) {
             if (!split && !ps.split_active) ps.split_active = true;
-            else { ps.split_active = false; ps.holdoff = 64; }   // the level stays whole for a while
+            else { ps.split_active = false; ps.holdoff = kPruneHoldoff; }   // the level stays whole for a while
         }
     }
     if (!fallback) {
