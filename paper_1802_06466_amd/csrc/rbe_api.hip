@@ -46,8 +46,7 @@ void set_error(const char* fmt, ...)
     } while (0)
 
 constexpr uint32_t kMaxEvents = 2 * RBE_MAX_LEVELS + 2;
-// Searches during which the pruning scans stay off after two searches in a row found nothing to prune (a probing
-// search costs about twice a plain one on such a corpus: its waves end up reading whole rows without prefetch).
+// Searches during which the pruning scans stay off after two searches in a row found nothing to prune.
 constexpr uint32_t kPruneHoldoff = 256;
 // layout of the block a search sends back (rbe_index::d_result)
 constexpr size_t kResultStatusBytes = 256;

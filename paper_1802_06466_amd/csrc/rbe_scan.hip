@@ -390,9 +390,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 // <= h_j t_j + 2^-6 h_j M, slightly more in the kernel), the last one as its largest value over the row.  A row that the bound lets through reads its last plane
 // and its P fp32 scale arrays and is scored from scratch by score_item, so what is appended is still exactly
 // what scan_exact appends.  16 + 2 instead of 16 + 8 streamed bytes per item at d = 64, P = 3.
-// A wave whose bound lets most rows through stops evaluating it (whole-row fallback: every lane reads and scores
-// all of its items) but for one row in eight, enough to notice when it starts to prune again.  The two register
-// sets (this row, the next one in flight) hold the streamed planes only and swap roles from row to row.
+// A wave whose bound lets more than a quarter of its rows through gives it up and takes the rest of its rows as
+// scan_exact does (whole rows, prefetched).  The two register sets (this row, the next one in flight) hold the
+// streamed planes only and swap roles from row to row.
 template <int W, int P, int PQ>
 __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
 {
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
 
     uint32_t p = a.p_begin + blockIdx.x;
     if (p >= a.p_end) return;
-    uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0;
+    uint32_t fill = 0, probed = 0, passed = 0, full_rows = 0;
     uint32_t extra8 = 0;        // bytes / 8 asked for beyond the stream (wave total, kept in lane 0's terms)
     const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
     const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
@@ -449,23 +449,22 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
     load_hints(hc, p);
     float amax = a.row_amax[(size_t)p * kWavesPerBlock + wave], amax_n = 0.0f;
-    bool whole = false;    // wave-uniform: whole-row fallback, the bound is not evaluated for this row
+    bool plain = false;    // wave-uniform: the bound lets most rows through; the rest of the wave's rows go the plain way
     // One row: start the loads of the next one into the other register set, judge and score this one.  The two
     // register sets swap roles from row to row (two copies of the code) instead of being copied.
     auto step = [&](RowRegs<W, P, S>& cur, Hints& hc, float& amax, RowRegs<W, P, S>& nxt, Hints& hn, float& amax_n)
                     __attribute__((always_inline)) -> bool {
+        if (passed * 4 > probed + 32) { plain = true; return false; }     // wave-uniform; this row is not done yet
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
-        const bool whole_next = passed * 4 > probed + 32;     // wave-uniform
         if (has_next) {
             load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
             load_hints(hn, pn);
             amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
         }
         bool reach = true;
-        uint32_t mine = (1u << kItemsPerLane) - 1u;     // which of this lane's items can still reach the threshold
-        if (!whole || (rows & 7u) == 0u) {
-            mine = 0;
+        uint32_t mine = 0;     // which of this lane's items can still reach the threshold
+        {
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
                 float s = floor_c, all = 0.0f;
@@ -492,12 +491,11 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
             ++probed;
             passed += reach ? 1u : 0u;
         }
-        ++rows;
         full_rows += reach ? 1u : 0u;
         if (reach) {
             // only the lanes that hold such an item read the rest of their items' data (the memory system fetches
             // the cache lines they touch, not the row) and score; an item whose bound is below the threshold cannot
-            // be a survivor.  (Whole-row fallback, rows that are not probed: every lane, every item.)
+            // be a survivor
             const char* tile = a.tiles + (size_t)p * tile_bytes;
             const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
             const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset()) + wave * kRow;
@@ -547,13 +545,27 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
             }
             if (__ballot(any)) fill = stage_scores<W, true>(sv, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
         }
-        whole = whole_next;
         p = pn;
         return has_next;
     };
     for (;;) {
         if (!step(cur, hc, amax, nxt, hn, amax_n)) break;
         if (!step(nxt, hn, amax_n, cur, hc, amax)) break;
+    }
+    if (plain) {
+        // from row p on as scan_exact does it: whole rows, the next one in flight while this one is scored
+        load_row<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+        for (;;) {
+            const uint32_t pn = p + G;
+            const bool has_next = pn < a.p_end;
+            if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
+            ++full_rows;
+            extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item beyond the stream's
+            if (!has_next) break;
+            cur = nxt;
+            p = pn;
+        }
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
