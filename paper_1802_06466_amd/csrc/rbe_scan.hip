@@ -1014,7 +1014,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
                                 : 2.0f * mass.y + 0.015875f * mass.x;
     QueryRegs<W, PQB> qb{};
     if constexpr (BIN) qb = load_query<W, PQB>(a.qwords, a.qcoef, 0);
-    uint32_t fill = 0, rows = 0, probed = 0, passed = 0, full_rows = 0, extra8 = 0;
+    uint32_t fill = 0, probed = 0, passed = 0, full_rows = 0, extra8 = 0;
 
     struct Hints { uint32_t w[NW]; };
     auto load_hints = [&](Hints& h, uint32_t tile_p) {
@@ -1046,27 +1046,44 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
     load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
     load_hints(hc, p);
     float amax = a.row_amax[(size_t)p * kWavesPerBlock + wave], amax_n = 0.0f;
-    bool whole = false;
-    for (;;) {
+    bool plain = false;    // wave-uniform: the bound lets most rows through; the rest of the wave's rows go the plain way
+    // scores the items `mine` of this lane in the row held by r (every plane and scale of them loaded) and queues
+    // what reaches the threshold
+    auto score_row = [&](const RowRegs<W, P, S>& r, uint32_t mine, uint32_t p) __attribute__((always_inline)) {
+        float s[kItemsPerLane];
+        bool any = false;
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            s[m] = -__builtin_inff();
+            if (mine & (1u << m)) s[m] = score_item_fq<W, P, MODE>(r, m, s_lut);
+            any |= (s[m] >= taus);
+        }
+        if (__ballot(any)) {
+            const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                const uint64_t id = row_id + lane_item<W>(lane, m);
+                bool ok = (s[m] >= taus) && (id < a.n_items);
+                uint64_t key = 0;
+                if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
+                fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
+            }
+        }
+    };
+    // one row, as in scan_exact_prog_hint: the two register sets swap roles from row to row
+    auto step = [&](RowRegs<W, P, S>& cur, Hints& hc, float& amax, RowRegs<W, P, S>& nxt, Hints& hn, float& amax_n)
+                    __attribute__((always_inline)) -> bool {
+        if (passed * 4 > probed + 32) { plain = true; return false; }     // wave-uniform; this row is not done yet
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
-        const bool whole_next = passed * 4 > probed + 32;
         if (has_next) {
-            const char* tn = a.tiles + (size_t)pn * tile_bytes;
-            load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
-            if (!whole_next || ((rows + 1u) & 7u) == 0u) {      // in the whole-row fallback only the rows that are probed
-                load_hints(hn, pn);
-                amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
-            }
-            if (whole_next) {
-                load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
-                load_row_scales<W, P, S>(nxt, tn, wave, lane);
-                extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;
-            }
+            load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            load_hints(hn, pn);
+            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
         }
         bool reach = true;
         uint32_t mine = 0;     // which of this lane's items can still reach the threshold
-        if (!whole || (rows & 7u) == 0u) {
+        {
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
                 float s = floor_c, all = 0.0f;
@@ -1103,11 +1120,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
             ++probed;
             passed += reach ? 1u : 0u;
         }
-        ++rows;
-        full_rows += (whole || reach) ? 1u : 0u;
+        full_rows += reach ? 1u : 0u;
         if (reach) {
-            if (whole) mine = 0xfu;
-            if (!whole) {
+            {
                 // lane-wise, as in scan_exact_prog_hint
                 const char* tile = a.tiles + (size_t)p * tile_bytes;
                 const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
@@ -1148,32 +1163,29 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
                         }
                 }
             }
-            float s[kItemsPerLane];
-            bool any = false;
-#pragma unroll
-            for (int m = 0; m < kItemsPerLane; ++m) {
-                s[m] = -__builtin_inff();
-                if (mine & (1u << m)) s[m] = score_item_fq<W, P, MODE>(cur, m, s_lut);
-                any |= (s[m] >= taus);
-            }
-            if (__ballot(any)) {
-                const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow;
-#pragma unroll
-                for (int m = 0; m < kItemsPerLane; ++m) {
-                    const uint64_t id = row_id + lane_item<W>(lane, m);
-                    bool ok = (s[m] >= taus) && (id < a.n_items);
-                    uint64_t key = 0;
-                    if (ok) { key = make_key(s[m], (uint32_t)id); ok = key >= tau; }
-                    fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
-                }
-            }
+            score_row(cur, mine, p);
         }
-        if (!has_next) break;
-        cur = nxt;
-        hc = hn;
-        amax = amax_n;
-        whole = whole_next;
         p = pn;
+        return has_next;
+    };
+    for (;;) {
+        if (!step(cur, hc, amax, nxt, hn, amax_n)) break;
+        if (!step(nxt, hn, amax_n, cur, hc, amax)) break;
+    }
+    if (plain) {
+        // from row p on as scan_exact_fq does it: whole rows, the next one in flight while this one is scored
+        load_row<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+        for (;;) {
+            const uint32_t pn = p + G;
+            const bool has_next = pn < a.p_end;
+            if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            score_row(cur, (1u << kItemsPerLane) - 1u, p);
+            ++full_rows;
+            extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item beyond the stream's
+            if (!has_next) break;
+            cur = nxt;
+            p = pn;
+        }
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
