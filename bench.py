@@ -347,7 +347,7 @@ def main():
         b_ms = rb["wall_s"] * 1e3 / args.batch_steps
         b_scan = float(rb["scan_ms"].mean()) if rb["scan_ms"].size else float("nan")
         b_items = rb["stats"]["items_scanned"][-1]
-        matrix_cores = B >= 8 and W <= 2     # the library's own choice of kernel for a batch
+        matrix_cores = B >= 7 and W <= 2     # the library's own choice of kernel for a batch
         if matrix_cores:
             # dense contraction [B x d] . [d x items] per corpus plane (one fp16 half per query component:
             # the contraction filters, survivors are rescored bitwise).  `achieved` prices the whole contraction;
@@ -459,7 +459,7 @@ def main():
         }
         log(f"paper point: exact {rp['wall_s'] * 1e3 / args.steps:.3f} ms/step ({p_gbs:.0f} GB/s), "
             f"near-lossless {rpn['wall_s'] * 1e3 / args.steps:.3f} ms/step, recall {np.mean(rec):.5f}")
-        if args.batch >= 8:
+        if args.batch >= 7:
             B = args.batch
             qpb, _ = make_queries(rbe, rbe_synth, torch, centres_p, (2 + args.batch_steps) * B, args.sigma, Pq, 3)
             rpb = timed_searches(rbe, torch, ixp, qpb, None, B, k, args.batch_steps, 2)

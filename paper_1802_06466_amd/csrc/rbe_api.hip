@@ -395,10 +395,11 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
     if (float_query && ix->mode != rbe::kModeScaled) return false;
     if (ix->batch_path == 1) return false;
     if (ix->batch_path == 2) return true;
-    // Measured crossover (1e9 items d=64 P=3, 1e8 items d=128 P=4): a 16-query tile costs the matrix-core scan
-    // about as much as 8 queries cost the XOR/popcount scan.  The byte-table scan of fp32 queries reads the
-    // corpus once per query, so there the matrix cores win from 3 queries on.
-    return Q >= (float_query ? 3u : 8u);
+    // Measured crossover (1e9 items d=64 P=3: 6 queries 9.3 ms either way, 7 queries 10.5 ms on the XOR/popcount
+    // scan and 9.5 ms here; 1e8 items d=128 P=4: further ahead): a 16-query tile costs the matrix-core scan about
+    // as much as 6 queries cost the XOR/popcount scan.  The byte-table scan of fp32 queries reads the corpus once
+    // per query, so there the matrix cores win from 3 queries on.
+    return Q >= (float_query ? 3u : 7u);
 }
 
 // Matrix-core operands of a batch (pure host arithmetic).  Each query is reconstructed in double as

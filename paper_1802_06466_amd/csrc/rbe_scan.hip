@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
     else mstage_drain(ms, a.out, lane);
 }
 
-// Several queries (2..7 in practice), P >= 2, progressive: one row in registers, planes 0 .. P-2 and the scales
+// Several queries (2..6 in practice), P >= 2, progressive: one row in registers, planes 0 .. P-2 and the scales
 // first; every query forms its partial scores and bounds from them, and the first query for which some item of
 // the row can still reach the threshold has the row's last plane read (once per row), after which it and any
 // later such query continue their partial chains to the full scores.  Most (query, row) pairs stop at the bound:
@@ -572,7 +572,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
 }
 
-// scan_exact_prog_hint for several queries per call (2 .. 7 in practice): the same stream (planes 0 .. P-2, their
+// scan_exact_prog_hint for several queries per call (2 .. 4 in practice): the same stream (planes 0 .. P-2, their
 // one-byte scale copies, the row's largest last scale), every query's bound per item, and for the items that some
 // query's bound lets through the lanes that hold them read the last plane and the fp32 scales once; every query
 // then scores those items from scratch.  Appends what the batch form of scan_exact appends.  Against
