@@ -3,7 +3,7 @@
 A plain, slow, single-threaded reference of what the GPU library computes:
 the stand-in encoder, the binary-dot-product score (Eq. 14 with the bit-wise
 identity of Sec. 5.1), exact top-k, the near-lossless selector of Algorithm 1
-(queue length 1) and the miss-probability model of Appendix A.
+(Sec. 6.2) and the miss-probability model of Appendix A.
 
 It shares nothing with the GPU library (no code, header, table or helper) and
 neither imports the other.  Only the tests, the smoke check and the benchmark's
@@ -188,9 +188,11 @@ def n_groups(N: int, I: int, Tb: int = 256) -> int:
 
 def nearlossless(planes, scales, q_planes, q_scales, k: int, I: int = 256, Tb: int = 256,
                  return_winners: bool = False, queue_len: int = 1):
-    """Algorithm 1 with a priority queue of `queue_len` entries per thread (the paper's
-    choice is 1), then exact top-k of everything the queues hold.  With return_winners the
-    queues themselves come back as [n_groups, queue_len] arrays (squeezed for length 1)."""
+    """Near-lossless selection (Algorithm 1, Sec. 6.2): ids z with equal
+    (z div (Tb*I)) * Tb + z mod Tb form a group, every group forwards its best `queue_len`
+    items (the paper's choice is 1), and the result is the exact top-k of what was forwarded.
+    With return_winners the forwarded items come back as [n_groups, queue_len] arrays
+    (squeezed for length 1)."""
     planes, scales, P, N, W = _corpus(planes, scales)
     q_planes, q_scales, Pq = _query(q_planes, q_scales, W)
     if queue_len < 1:

@@ -203,16 +203,19 @@ int64_t orc_topk_of_scores(const double *scores, const int64_t *ids, uint64_t n,
 }
 
 /* ------------------------------------------------------------------ */
-/* Near-lossless selection (Algorithm 1 with a priority queue of length 1,
- * Sec. 6.2 and Appendix A).  Thread y of block x visits items
- * z = x*Tb*I + y, then z += Tb, I times, keeping only its best item.  So the
- * items sharing one queue ("group") are
- *     g(z) = (z div (Tb*I)) * Tb + (z mod Tb).
- * Each group forwards its best item (its best qlen items for a queue of length
- * qlen) under (score desc, id asc); slots past N do not exist.  The answer is
- * the exact top-k of the forwarded items.
- * winners_ids/winners_scores (optional, length n_groups) receive every
- * group's winner (id -1 / -inf for an empty group).                         */
+/* Near-lossless selection (Algorithm 1, Sec. 6.2; miss model in Appendix A).
+ * The selector partitions the item ids into groups; every group forwards only
+ * its best qlen items (the paper runs it with qlen = 1) and the answer is the
+ * exact top-k of what was forwarded.  The partition follows from how the
+ * algorithm hands ids to its Tb threads per block, each thread taking I ids at
+ * a stride of Tb: consecutive spans of Tb*I ids form a block, and inside a
+ * block the ids congruent modulo Tb share a group.  Group number
+ *     g(z) = (z div (Tb*I)) * Tb + (z mod Tb),
+ * and conversely group g holds the ids
+ *     (g div Tb) * Tb*I + (g mod Tb) + m*Tb,   m = 0 .. I-1,   that are < N.
+ * Order inside a group and in the answer: score descending, id ascending.
+ * winners_ids / winners_scores (optional): [n_groups][qlen], best first,
+ * id -1 / score -inf where a group has fewer than qlen items.                */
 /* ------------------------------------------------------------------ */
 uint64_t orc_n_groups(uint64_t N, uint64_t Tb, uint64_t I)
 {
@@ -227,43 +230,37 @@ int64_t orc_nearlossless(const uint64_t *planes, const float *scales, uint64_t N
                          int64_t *ids_out, double *scores_out,
                          int64_t *winners_ids, double *winners_scores)
 {
-    /* Algorithm 1 with a priority queue of `qlen` entries per thread (the paper runs it with 1).
-     * winners_* (optional): [n_groups][qlen], best first, id -1 / -inf where a queue is not full. */
     const uint64_t G = orc_n_groups(N, Tb, I);
     if (qlen == 0) return -1;
-    cand_t *win = (cand_t *)malloc((G ? G : 1) * qlen * sizeof(cand_t));
-    if (!win) return -1;
-    for (uint64_t g = 0; g < G * qlen; ++g) { win[g].s = -INFINITY; win[g].id = -1; }
-
-    const uint64_t n_blocks = G / Tb;
-    for (uint64_t x = 0; x < n_blocks; ++x)
-        for (uint64_t y = 0; y < Tb; ++y) {
-            uint64_t z = x * Tb * I + y;
-            cand_t *p = &win[(x * Tb + y) * qlen];          /* this thread's queue, best first */
-            for (uint64_t it = 0; it < I; ++it, z += Tb) {
-                if (z >= N) continue;
-                cand_t c = { score_pair(planes, scales, N, d, P, z, q_planes, q_scales, Pq), (int64_t)z };
-                /* p.insert(s, z): the new entry enters before the first worse one; the last one drops out */
-                for (uint64_t e = 0; e < qlen; ++e) {
-                    if (p[e].id < 0 || better(&c, &p[e])) {
-                        for (uint64_t m = qlen - 1; m > e; --m) p[m] = p[m - 1];
-                        p[e] = c;
-                        break;
-                    }
-                }
-            }
-        }
-
+    cand_t *kept = (cand_t *)malloc(qlen * sizeof(cand_t));     /* one group's best, best first */
     topk_t t = { (cand_t *)malloc((k ? k : 1) * sizeof(cand_t)), 0, k };
-    if (!t.h) { free(win); return -1; }
-    for (uint64_t g = 0; g < G * qlen; ++g) {
-        if (winners_ids)    winners_ids[g] = win[g].id;
-        if (winners_scores) winners_scores[g] = win[g].s;
-        if (win[g].id >= 0) topk_offer(&t, win[g].s, win[g].id);
+    if (!kept || !t.h) { free(kept); free(t.h); return -1; }
+
+    for (uint64_t g = 0; g < G; ++g) {
+        const uint64_t first = (g / Tb) * Tb * I + (g % Tb);
+        uint64_t n_kept = 0;
+        for (uint64_t m = 0; m < I; ++m) {
+            const uint64_t z = first + m * Tb;
+            if (z >= N) break;
+            const cand_t c = { score_pair(planes, scales, N, d, P, z, q_planes, q_scales, Pq), (int64_t)z };
+            /* position of c among the kept entries; entries after it move down, the last may fall off */
+            uint64_t pos = n_kept;
+            while (pos > 0 && better(&c, &kept[pos - 1])) --pos;
+            if (pos >= qlen) continue;
+            if (n_kept < qlen) ++n_kept;
+            for (uint64_t e = n_kept - 1; e > pos; --e) kept[e] = kept[e - 1];
+            kept[pos] = c;
+        }
+        for (uint64_t e = 0; e < qlen; ++e) {
+            const int live = e < n_kept;
+            if (winners_ids)    winners_ids[g * qlen + e] = live ? kept[e].id : -1;
+            if (winners_scores) winners_scores[g * qlen + e] = live ? kept[e].s : -INFINITY;
+            if (live) topk_offer(&t, kept[e].s, kept[e].id);
+        }
     }
     uint64_t n = topk_finish(&t, ids_out, scores_out);
     free(t.h);
-    free(win);
+    free(kept);
     return (int64_t)n;
 }
 

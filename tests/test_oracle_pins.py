@@ -139,6 +139,67 @@ def test_scores_range_arguments():
     np.testing.assert_array_equal(oracle.scores(planes, scales, qp, qs, 17, 63), full[17:63])
 
 
+
+@pytest.mark.parametrize("d,P,Pq", [(64, 3, 3), (64, 2, 3), (128, 4, 4)])
+def test_scores_at_gathers_the_listed_ids(d, P, Pq):
+    """scores_at(ids)[r] is the score of item ids[r]: against the dense scores for shuffled, repeated
+    and boundary ids, and against the float64 dot product of the unpacked reconstructions (Eq. 14)
+    for a handful.  Items are made distinguishable (a wrong gather index cannot hit an equal score)."""
+    rng = np.random.default_rng(400 + d + P)
+    N = 777
+    planes, scales = random_corpus(rng, N, d, P)
+    qp, qs = random_query(rng, d, Pq)
+    dense = oracle.scores(planes, scales, qp, qs)
+    assert np.unique(dense).size == N
+    ids = np.concatenate([[0, N - 1, N - 1, 0, 1, N - 2], rng.permutation(N), rng.integers(0, N, size=300)]).astype(np.int64)
+    got = oracle.scores_at(planes, scales, qp, qs, ids)
+    np.testing.assert_array_equal(got, dense[ids])
+    qv = reconstruct_query(qp, qs, d)
+    for r in (0, 1, 5, 6, 400, ids.size - 1):
+        z = int(ids[r])
+        ref = float(np.dot(qv, reconstruct(planes, scales, z, d)))
+        assert abs(got[r] - ref) <= 1e-12 * max(1.0, abs(ref))
+    assert oracle.scores_at(planes, scales, qp, qs, np.empty(0, np.int64)).size == 0
+    # one id at a time agrees with the batch call (no dependence on the list's length or order)
+    for z in (0, 3, N - 1):
+        assert oracle.scores_at(planes, scales, qp, qs, [z])[0] == dense[z]
+    with pytest.raises(ValueError):
+        oracle.scores_at(planes, scales, qp, qs, [N])
+    with pytest.raises(ValueError):
+        oracle.scores_at(planes, scales, qp, qs, [-1])
+
+
+def test_scores_at_on_a_strided_corpus_view_uses_plane_major_indexing():
+    """Plane j of item z sits at planes[j][z]: a corpus whose planes differ per j and per z in a
+    known way (one plane equal to the query, the others its complement) gives hand-computable scores."""
+    d, P, N = 64, 3, 50
+    qp = np.array([[0x0123456789ABCDEF]], dtype=np.uint64)
+    qs = np.array([1.0], dtype=np.float32)
+    planes = np.empty((P, N, 1), dtype=np.uint64)
+    scales = np.empty((P, N), dtype=np.float32)
+    for z in range(N):
+        for j in range(P):
+            same = (z + j) % 3 == 0                      # exactly one plane of every item equals the query
+            planes[j, z, 0] = qp[0, 0] if same else ~qp[0, 0]
+            scales[j, z] = (j + 1) * 10 + z * 0.25       # exact in fp32
+    ids = np.array([49, 0, 17, 17, 3], dtype=np.int64)
+    expect = []
+    for z in ids:
+        expect.append(sum((1.0 if (z + j) % 3 == 0 else -1.0) * 64.0 * ((j + 1) * 10 + z * 0.25) for j in range(P)))
+    np.testing.assert_array_equal(oracle.scores_at(planes, scales, qp, qs, ids), np.array(expect))
+
+
+def test_recall_against_hand_counted_sets():
+    assert oracle.recall([1, 2, 3], [1, 2, 3]) == 1.0
+    assert oracle.recall([3, 2, 1], [1, 2, 3]) == 1.0                 # order does not matter
+    assert oracle.recall([1, 2, 9], [1, 2, 3]) == 2 / 3
+    assert oracle.recall([7, 8, 9], [1, 2, 3]) == 0.0
+    assert oracle.recall([1, -1, -1], [1, 2, -1]) == 0.5             # -1 padding is no item on either side
+    assert oracle.recall([-1, -1], [-1, -1]) == 1.0                  # nothing to find
+    assert oracle.recall([], [4, 5]) == 0.0
+    assert oracle.recall([4, 4, 4, 5], [4, 5, 6, 7]) == 0.5          # repeats count once
+    assert oracle.recall(np.array([0, 5], dtype=np.int64), np.array([0, 1, 2, 5], dtype=np.int64)) == 0.5   # id 0 is an item
+
 # ---------------------------------------------------------------- P3: the paper's worked expansions
 def test_two_ingredient_expansion_unweighted():
     """Sec. 3.2 example: (b0_q + d0_q).(b0_k + d0_k) is the sum of the four
@@ -397,45 +458,59 @@ def test_encoder_bit_order_lsb_first():
 
 
 # ---------------------------------------------------------------- O4: near-lossless selector
-def simulate_algorithm1(sc, Tb, I, k):
-    """Algorithm 1 executed literally with python loops: block x, thread y, I
-    strided visits, one-entry queue; then the best k of all queue contents."""
+def groups_by_reshape(sc, Tb, I, qlen):
+    """The selector's partition written as array reshapes, independently of the oracle's loops
+    (Algorithm 1, Sec. 6.2): pad the id axis to whole blocks of Tb*I ids, view it as
+    [block][visit][thread] (a thread's visits are Tb apart), and bring the visits of one
+    (block, thread) pair together.  Returns, per group, the ids of its best qlen existing items
+    under (score desc, id asc), best first."""
     N = len(sc)
     n_blocks = -(-N // (Tb * I))
-    queues = []
-    for x in range(n_blocks):
-        for y in range(Tb):
-            z = x * Tb * I + y
-            best = None
-            for _ in range(I):
-                if z < N and (best is None or (-sc[z], z) < (-sc[best], best)):
-                    best = z
-                z += Tb
-            queues.append(best)
-    alive = [z for z in queues if z is not None]
+    ids = np.arange(n_blocks * Tb * I, dtype=np.int64)
+    padded = np.full(ids.size, -np.inf)
+    padded[:N] = sc
+    member_ids = ids.reshape(n_blocks, I, Tb).transpose(0, 2, 1).reshape(n_blocks * Tb, I)
+    member_sc = padded.reshape(n_blocks, I, Tb).transpose(0, 2, 1).reshape(n_blocks * Tb, I)
+    # ids ascend along a group's row, so a stable sort by descending score breaks ties by id
+    order = np.argsort(-member_sc, axis=1, kind="stable")
+    best_ids = np.take_along_axis(member_ids, order, axis=1)[:, :qlen]
+    return [[int(z) for z in row if z < N] for row in best_ids]
+
+
+def forwarded_topk(sc, groups, k):
+    alive = [z for g in groups for z in g]
     alive.sort(key=lambda z: (-sc[z], z))
-    return alive[:k], queues
+    return alive[:k]
 
 
 @pytest.mark.parametrize("N,Tb,I,k", [(24, 4, 3, 5), (25, 4, 3, 8), (1000, 8, 16, 20), (1000, 256, 2, 600), (70000, 256, 256, 100)])
-def test_nearlossless_matches_literal_algorithm1(N, Tb, I, k):
+def test_nearlossless_matches_partition_by_reshape(N, Tb, I, k):
     rng = np.random.default_rng(16 + N)
     planes, scales = random_corpus(rng, N, 64, 2)
     scales = np.round(scales, 1).astype(np.float32)
     qp, qs = random_query(rng, 64, 2)
     s = oracle.scores(planes, scales, qp, qs)
     ids, sc, w_ids, w_sc = oracle.nearlossless(planes, scales, qp, qs, k, I=I, Tb=Tb, return_winners=True)
-    expect, queues = simulate_algorithm1(s, Tb, I, k)
+    groups = groups_by_reshape(s, Tb, I, 1)
+    expect = forwarded_topk(s, groups, k)
     m = len(expect)
     assert list(ids[:m]) == expect and np.all(ids[m:] == -1)
     np.testing.assert_array_equal(sc[:m], s[expect])
-    assert [int(w) for w in w_ids] == [(-1 if q is None else q) for q in queues]
-    assert oracle.n_groups(N, I, Tb) == len(queues)
+    assert [int(w) for w in w_ids] == [(g[0] if g else -1) for g in groups]
+    assert oracle.n_groups(N, I, Tb) == len(groups)
+    # the group of an id, from the id alone (the closed form the GPU tests use)
+    z = np.arange(N)
+    gz = (z // (Tb * I)) * Tb + (z % Tb)
+    for g in (0, len(groups) // 2, len(groups) - 1):
+        members = z[gz == g]
+        if members.size:
+            best = min(members, key=lambda m_: (-s[m_], m_))
+            assert groups[g] == [int(best)]
     # a subset of the exact top-k can only lose items, never invent better ones
-    exact, _ = oracle.topk(planes, scales, qp, qs, k)
-    assert oracle.recall(ids, exact) <= 1.0
-    if I == 1:
-        assert list(ids) == list(exact)
+    exact, exact_sc = oracle.topk(planes, scales, qp, qs, k)
+    hit = len(set(ids[:m].tolist()) & set(exact.tolist()))
+    assert oracle.recall(ids, exact) == hit / len([e for e in exact if e >= 0])
+    assert np.all(sc[:m] <= exact_sc[:m])
 
 
 def test_nearlossless_I1_is_exact():
@@ -447,43 +522,23 @@ def test_nearlossless_I1_is_exact():
     assert list(a) == list(b)
 
 
-def simulate_algorithm1_queue(sc, Tb, I, k, qlen):
-    """Literal Algorithm 1 with a sorted list of at most qlen entries as the priority queue."""
-    N = len(sc)
-    n_blocks = -(-N // (Tb * I))
-    kept = []
-    queues = []
-    for x in range(n_blocks):
-        for y in range(Tb):
-            z = x * Tb * I + y
-            q = []
-            for _ in range(I):
-                if z < N:
-                    q.append((-sc[z], z))
-                    q.sort()
-                    del q[qlen:]
-                z += Tb
-            queues.append([e[1] for e in q])
-            kept += q
-    kept.sort()
-    return [e[1] for e in kept[:k]], queues
-
-
 @pytest.mark.parametrize("N,Tb,I,k,qlen", [(24, 4, 3, 5, 2), (25, 4, 3, 30, 2), (1000, 8, 16, 40, 2), (1000, 8, 16, 40, 3),
                                            (1000, 256, 2, 600, 2), (70000, 256, 256, 100, 2), (500, 4, 5, 50, 5)])
-def test_nearlossless_longer_queue_matches_literal_algorithm1(N, Tb, I, k, qlen):
+def test_nearlossless_longer_queue_matches_partition_by_reshape(N, Tb, I, k, qlen):
     rng = np.random.default_rng(116 + N + qlen)
     planes, scales = random_corpus(rng, N, 64, 2)
     scales = np.round(scales, 1).astype(np.float32)       # many exact ties
     qp, qs = random_query(rng, 64, 2)
     s = oracle.scores(planes, scales, qp, qs)
     ids, sc, w_ids, w_sc = oracle.nearlossless(planes, scales, qp, qs, k, I=I, Tb=Tb, return_winners=True, queue_len=qlen)
-    expect, queues = simulate_algorithm1_queue(s, Tb, I, k, qlen)
+    groups = groups_by_reshape(s, Tb, I, qlen)
+    expect = forwarded_topk(s, groups, k)
     m = len(expect)
     assert list(ids[:m]) == expect and np.all(ids[m:] == -1)
     np.testing.assert_array_equal(sc[:m], s[expect])
-    for g, q in enumerate(queues):
+    for g, q in enumerate(groups):
         assert [int(v) for v in w_ids[g][:len(q)]] == q and np.all(w_ids[g][len(q):] == -1)
+        np.testing.assert_array_equal(w_sc[g][:len(q)], s[q])
     # a longer queue keeps a superset of what a shorter one keeps
     shorter, _ = oracle.nearlossless(planes, scales, qp, qs, k, I=I, Tb=Tb, queue_len=qlen - 1)
     exact, _ = oracle.topk(planes, scales, qp, qs, k)
