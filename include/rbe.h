@@ -33,7 +33,7 @@
  * over the corpus reads an item's last plane only where an upper bound on its score -- the
  * exact contribution of the other planes plus the largest value the last plane
  * could add -- reaches the current threshold; such items are then scored in full
- * by the formula above, so the results are unchanged (rbe_debug_set_progressive).
+ * by the formula above, so the results are unchanged.
  *
  * Selection (Sec. 6).  Results are ordered by (score descending, id
  * ascending).  RBE_SELECT_EXACT returns exactly the k best under that order.
@@ -65,7 +65,7 @@
 extern "C" {
 #endif
 
-typedef struct rbe_index rbe_index; /* opaque; owns its device memory */
+typedef struct rbe_index rbe_index; /* opaque; owns its device memory unless created with RBE_BORROW */
 
 enum {
     RBE_OK = 0,
@@ -79,6 +79,8 @@ enum {
 enum { RBE_MEM_HOST = 0, RBE_MEM_DEVICE = 1 }; /* where a caller's array lives */
 
 enum {
+    RBE_BORROW = 1u << 0, /* rbe_index_create_in() only: the index lives in device memory
+                            that the caller owns (e.g. a torch tensor) and never frees it  */
     RBE_COSINE = 1u << 1, /* at rbe_finalize(): divide every item's scales by the
                             norm of its reconstructed vector sum_j a_j b_j, so that
                             scores become the cosine of Eq. 14 up to the query's own
@@ -134,12 +136,33 @@ int rbe_index_create(rbe_index **out, uint64_t n_items, uint32_t dim,
 int rbe_index_create_ex(rbe_index **out, uint64_t n_items, uint32_t dim,
                         uint32_t n_planes, uint32_t flags, uint32_t sample_ratio);
 
+/* Caller-owned corpus storage.  The scans depend on the tile order described
+ * above, so a caller's plain [plane][item][word] arrays cannot be searched in
+ * place (every search would pay strided reads at about a tenth of the streaming
+ * rate); what a caller CAN own is the memory itself.  rbe_index_bytes() gives the
+ * device bytes an index of this shape needs (tiles plus the side arrays that
+ * rbe_finalize derives; 0 for an invalid shape; sample_ratio 0 = 64), and
+ * rbe_index_create_in() builds the index inside `storage_dev` (DEVICE pointer,
+ * 256-byte aligned, at least that many bytes; flags must include RBE_BORROW).
+ * The library then allocates no device memory for this index at create, finalize
+ * or free (rbe_load_chunk / rbe_encode_chunk from HOST arrays still stage through
+ * a temporary device buffer; from DEVICE arrays they allocate nothing), writes
+ * the storage only through its own calls, and never frees it: keep it alive and
+ * untouched until after rbe_free().                                             */
+size_t rbe_index_bytes(uint64_t n_items, uint32_t dim, uint32_t n_planes,
+                       uint32_t flags, uint32_t sample_ratio);
+int rbe_index_create_in(rbe_index **out, uint64_t n_items, uint32_t dim,
+                        uint32_t n_planes, uint32_t flags, uint32_t sample_ratio,
+                        void *storage_dev, size_t storage_bytes);
+
 /* Copies items [first_item, first_item + count) into the index.
  *   planes: [n_planes][count][dim/64] uint64, scales: [n_planes][count] float,
  *   both in host memory (mem_kind = RBE_MEM_HOST) or both in device memory
  *   (RBE_MEM_DEVICE; e.g. torch tensors).  The caller keeps ownership; the
  *   arrays may be released once the stream has passed the copies (host arrays:
- *   on return).  Scales must be finite and >= 0 (not checked).
+ *   on return).  Scales must be finite (checked at rbe_finalize) and should be
+ *   >= 0, as the method produces them: an index that holds a negative scale is
+ *   searched correctly, but by the plain scans only (see rbe_finalize).
  * Only valid while loading.                                                   */
 int rbe_load_chunk(rbe_index *ix, uint64_t first_item, uint64_t count,
                    const uint64_t *planes, const float *scales,
@@ -165,9 +188,14 @@ int rbe_encode_corpus(rbe_index **out, const float *x, uint64_t n_items,
  * other scale arrays: n_planes - 1 bytes of device memory per item, 4 at 4
  * planes), waits for the stream, and makes the index searchable.  Items never
  * loaded score as all-(-1) vectors with scale 0.  If the one-byte copies do not
- * fit in device memory, or a scale is negative or not finite, the index works
- * without them (the one-query search then reads the fp32 arrays they stand
- * for).                                                                       */
+ * fit in device memory the index works without them (the one-query search then
+ * reads the fp32 arrays they stand for).
+ * Scales are looked at here.  A scale that is not finite: RBE_EINVAL, and the
+ * index stays in the loading state (load the chunk again, then finalize).  A
+ * negative scale: every upper bound the pruning searches use (last plane left
+ * out, matrix-core filter) assumes scales >= 0, so such an index gets no side
+ * arrays and every search on it reads every plane of every item with the plain
+ * XOR/popcount (or byte-table) scans; results stay exact, searches are slower. */
 int rbe_finalize(rbe_index *ix, void *hip_stream);
 
 /* rbe_index_create + one rbe_load_chunk of the whole corpus + rbe_finalize.
@@ -203,11 +231,29 @@ int rbe_encode_query(const float *x, uint32_t dim, uint32_t n_planes,
  *              than k results exist (k > n_items, or k > number of groups) the
  *              tail holds id = -1, score = -INFINITY.
  * The call returns after the results are in the host arrays (it waits for the
- * stream).  Device scratch is grown on demand inside the call.               */
+ * stream).  Device scratch (candidate lists, counters, staged queries, results):
+ * the block set with rbe_set_workspace() if there is one -- then the call
+ * allocates nothing and fails with RBE_EINVAL if the block is too small -- else a
+ * block of the library's own, allocated when a call needs more than any call
+ * before it (steady-state searches allocate nothing).                          */
 int rbe_search(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
                uint32_t n_queries, uint32_t q_n_planes, uint32_t k,
                uint32_t mode, uint32_t group_size_I,
                int64_t *ids_out, float *scores_out, void *hip_stream);
+
+/* Caller-owned scratch (Sec. 5: everything a query touches stays in GPU memory;
+ * here the caller's allocator, e.g. a torch tensor, can own all of it).
+ * rbe_workspace_bytes(): device bytes that a search of up to n_queries queries
+ * for k results in `mode` needs on this index with its current tuning (0 for
+ * arguments out of range); the figure covers rbe_search and rbe_search_float.
+ * rbe_set_workspace(): every later search carves its scratch from dev_ptr (DEVICE
+ * pointer, 256-byte aligned, `bytes` long) instead of library-owned memory, which
+ * is released; the caller keeps ownership and must keep the block alive and
+ * otherwise unused while searches run.  dev_ptr = NULL returns to library-owned
+ * scratch.  A search that needs more than `bytes` fails with RBE_EINVAL and the
+ * required size in rbe_last_error().                                            */
+size_t rbe_workspace_bytes(const rbe_index *ix, uint32_t n_queries, uint32_t k, uint32_t mode);
+int rbe_set_workspace(rbe_index *ix, void *dev_ptr, size_t bytes);
 
 /* Hybrid scoring: full-precision queries against the binary items (the paper's
  * "hybrid rbe" model, Sec. 8.1, which bounds the accuracy of every RBE model with
@@ -264,125 +310,6 @@ int rbe_get_search_stats(const rbe_index *ix, rbe_search_stats *out);
  *   blocks_per_cu   : persistent workgroups per compute unit for the scan
  *                     (default: as many as the kernel's occupancy allows)      */
 int rbe_set_tuning(rbe_index *ix, uint32_t cand_capacity, uint32_t blocks_per_cu);
-
-/* ---------------------------------------------------------------------------
- * Test hooks (dense dumps for parity checks; small ranges only).
- * ------------------------------------------------------------------------- */
-
-/* popcount(Q_i XOR K_j[z]) for z in [first_item, first_item+count):
- *   q_planes [q_n_planes][dim/64] (host) -> out [count][n_planes][q_n_planes]
- *   int32 (host).                                                            */
-int rbe_debug_popcounts(rbe_index *ix, const uint64_t *q_planes, uint32_t q_n_planes,
-                        uint64_t first_item, uint64_t count, int32_t *out, void *hip_stream);
-
-/* fp32 scores s(q, z) of one query for z in [first_item, first_item+count):
- *   out [count] float (host).  Same arithmetic as rbe_search.                */
-int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
-                     uint32_t q_n_planes, uint64_t first_item, uint64_t count,
-                     float *out, void *hip_stream);
-
-/* One query per call, exact mode, 2 or more planes: the last (largest) level of
- * the search reads plane 0 and the scales of every item but the other planes only
- * of rows in which some item's upper bound -- plane 0's exact term plus the
- * largest value the remaining planes could add -- reaches the threshold; such rows
- * are then scored in full, so the results are those of the plain scan bit for bit.
- * enabled = 0 switches it off (every plane of every item is read); default 1;
- * 2 = on, but without the one-byte scale copies (what an index uses whose
- * copies did not fit in device memory).                                          */
-int rbe_debug_set_progressive(rbe_index *ix, int enabled);
-
-/* The last level of an exact search in two parts (an eighth of its items, a
- * selection, then the rest, which starts from a much tighter threshold).  The
- * library does this on its own once a one-query search has found the last level's
- * usual threshold too loose for its pruning scan on this corpus (most rows read in
- * full); if that does not help either, the pruning scans stay off for the next 64
- * searches and are then tried again.  mode 0 = these automatic choices (and forget
- * what was learnt), 1 = never split and never stand down, 2 = always split.
- * Results do not depend on any of it.                                            */
-int rbe_debug_set_plan_split(rbe_index *ix, int mode);
-
-/* The mass of one query as the progressive scan uses it (pure host function, for
- * tests).  With qhat = sum_i c_i rho_i (rho = +-1 per bit), M = sum_d |qhat_d| is the
- * largest value sum_i c_i (rho_i . rho) can take over all sign vectors rho.
- * dyadic = 0: mass_out[0] >= M, larger by a few 2^-20 of dim * sum_i |c_i| (rounding
- * allowance), mass_out[1] = 2^-19 mass_out[0].  dyadic = 1 (c_i = 2^-i, q_scales not
- * read): the bits of mass_out[0] are the integer h_min = (dim (2^Pq - 1) - M') / 2 with
- * M' = 2^(Pq-1) M, the least weighted mismatch count sum_i 2^(Pq-1-i) popcount(Q_i XOR K)
- * any plane K can have; mass_out[1] = 0.
- *   q_planes [q_n_planes][dim/64], q_scales [q_n_planes], mass_out [2]: host.    */
-int rbe_debug_query_mass(const uint64_t *q_planes, const float *q_scales, uint32_t q_n_planes,
-                         uint32_t dim, uint32_t dyadic, float *mass_out);
-
-/* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 8
- * queries per call on, dim <= 128), 1 = always the XOR/popcount kernel, 2 = the
- * matrix-core kernel for any number of queries (dim <= 128).                     */
-int rbe_debug_set_batch_path(rbe_index *ix, int path);
-
-/* fp32 hybrid scores (rbe_search_float arithmetic) of one fp32 query q [dim] for z in
- * [first_item, first_item+count): out [count] float (host).                  */
-int rbe_debug_scores_float(rbe_index *ix, const float *q, uint64_t first_item,
-                           uint64_t count, float *out, void *hip_stream);
-
-/* Copies the (possibly cosine-folded) scales of items [first_item,
- * first_item+count) back: out [n_planes][count] float (host).                */
-int rbe_debug_read_scales(rbe_index *ix, uint64_t first_item, uint64_t count,
-                          float *out, void *hip_stream);
-
-/* Copies the plane words of items [first_item, first_item+count) back:
- * out [n_planes][count][dim/64] uint64 (host).                               */
-int rbe_debug_read_planes(rbe_index *ix, uint64_t first_item, uint64_t count,
-                          uint64_t *out, void *hip_stream);
-
-/* Tile order (pure host functions, for tests): physical position of logical
- * tile `tile` in a corpus of n_tiles tiles with the given sample ratio, and the
- * inverse.                                                                     */
-uint32_t rbe_debug_tile_to_phys(uint32_t n_tiles, uint32_t sample_ratio, uint32_t tile);
-uint32_t rbe_debug_phys_to_tile(uint32_t n_tiles, uint32_t sample_ratio, uint32_t phys);
-
-/* Refinement plan of the exact mode (pure host function, for tests): the levels
- * rbe_search would run for such a corpus, each a range [first_tile, end_tile) of
- * PHYSICAL tile positions; arrays of RBE_MAX_LEVELS entries.  n_levels = 0 means
- * that no plan fits cand_capacity (the bounded-segment path is used instead).    */
-int rbe_debug_exact_plan(uint64_t n_items, uint32_t sample_ratio, uint32_t cand_capacity, uint32_t k,
-                         uint32_t *n_levels, uint32_t *first_tile, uint32_t *end_tile);
-
-/* Query operands of the matrix-core batch scan (pure host function, for tests).
- * The queries are binary (q_planes [Q][Pq][W] and, unless dyadic, q_scales
- * [Q][Pq]; q_float NULL) or fp32 (q_float [Q][dim]; general scales only, the
- * other two are not read).
- * halves_out [tile][plane copy][part][lane][8] fp16 bit patterns, where
- * tile = query / 16, lane = 16 g + query % 16, part = 32-dimension part of the
- * query and slot e = 2t + h of lane group g stands for bit (10 + 16h + t - 4g)
- * mod 32 of that part, weighted by 2 / val_t with val_t = 2^-14, 2^-13, 2^-11,
- * 2^-7 (the value of a half whose only set bit is bit 10 + t: the form in which
- * the kernel feeds item bits), times 2^-j in plane copy j (dyadic only; one copy
- * otherwise).  dyadic = 1: every half is exact and the contraction is the score.
- * dyadic = 0 (general scales): every component is rounded to one half and the
- * contraction is a filter whose distance from the score is at most
- * margin * sum_j a_j[item]; survivors are scored again exactly.
- * unscale_out[q] = 2^-k undoes the power-of-two scaling of query q; start_out[q]
- * is where its accumulators start (minus the weighted sum of what the halves hold).
- * shape_out = {tiles, plane copies, parts, margin (float bits)}: 4 entries.
- * halves_capacity in halves.                                                    */
-int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, const float *q_float,
-                             uint32_t n_queries, uint32_t q_n_planes, uint32_t dim, uint32_t n_planes,
-                             uint32_t dyadic, uint16_t *halves_out, size_t halves_capacity,
-                             float *unscale_out, float *start_out, uint32_t *shape_out);
-
-/* Measurement yardstick: enqueues a plain copy kernel ("calib_copy") of `bytes`
- * bytes from src_dev to dst_dev (DEVICE pointers, 16-byte aligned, bytes a
- * multiple of 16, non-overlapping).  It reads and writes exactly `bytes` each,
- * so hardware-counter readings of other kernels can be scaled by what the same
- * counters report for it.  Asynchronous on the stream.                         */
-int rbe_debug_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
-
-/* Measurement yardstick: enqueues a read-only kernel ("calib_read") that streams
- * `bytes` bytes from src_dev (DEVICE pointer, 16-byte aligned, bytes a multiple
- * of 16) with the scan's access shape and writes 16 bytes per thread to
- * sink_dev (DEVICE, 16-byte aligned, at least 3 * 256 * 16 bytes per compute
- * unit: 3 MiB covers 256 units; EINVAL if too small).  Its rate is the practical
- * read ceiling the scan is compared with.  Asynchronous on the stream.         */
-int rbe_debug_read(const void *src_dev, size_t bytes, void *sink_dev, size_t sink_bytes, void *hip_stream);
 
 const char *rbe_strerror(int code);
 const char *rbe_last_error(void);

@@ -1,0 +1,149 @@
+/*
+ * rbe_debug.h -- test and measurement hooks of the RBE retrieval library.
+ *
+ * Not part of the product interface (include/rbe.h): dense dumps that parity
+ * tests compare with a reference, switches that force a particular kernel so
+ * that two kernels can be compared on the same search, pure host functions that
+ * expose intermediate quantities, and two calibration kernels for measurements.
+ * Conventions as in rbe.h.
+ */
+#ifndef RBE_DEBUG_H
+#define RBE_DEBUG_H
+
+#include "rbe.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---------------------------------------------------------------------------
+ * Dense dumps for parity checks (small ranges only).
+ * ------------------------------------------------------------------------- */
+
+/* popcount(Q_i XOR K_j[z]) for z in [first_item, first_item+count):
+ *   q_planes [q_n_planes][dim/64] (host) -> out [count][n_planes][q_n_planes]
+ *   int32 (host).                                                            */
+int rbe_debug_popcounts(rbe_index *ix, const uint64_t *q_planes, uint32_t q_n_planes,
+                        uint64_t first_item, uint64_t count, int32_t *out, void *hip_stream);
+
+/* fp32 scores s(q, z) of one query for z in [first_item, first_item+count):
+ *   out [count] float (host).  Same arithmetic as rbe_search.                */
+int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
+                     uint32_t q_n_planes, uint64_t first_item, uint64_t count,
+                     float *out, void *hip_stream);
+
+/* Fewer than 7 queries per call, exact mode, 2 or more planes: the last (largest)
+ * level of the search streams every plane but the last (one query: with one-byte
+ * copies of their scales and the row's largest last scale in place of the fp32
+ * arrays) and reads an item's last plane and fp32 scales only where its upper
+ * bound -- the exact contribution of the other planes plus the largest value the
+ * last plane could add -- reaches the threshold; such items are then scored in
+ * full, so the results are those of the plain scan bit for bit.
+ * enabled = 0 switches it off (every plane of every item is read); default 1;
+ * 2 = on, but without the one-byte scale copies (what an index uses whose
+ * copies did not fit in device memory).                                          */
+int rbe_debug_set_progressive(rbe_index *ix, int enabled);
+
+/* The last level of an exact search in two parts (an eighth of its items, a
+ * selection, then the rest, which starts from a much tighter threshold).  The
+ * library does this on its own once a one-query search has found the last level's
+ * usual threshold too loose for its pruning scan on this corpus (most rows read in
+ * full); if that does not help either, the pruning scans stay off for the next 256
+ * searches and are then tried again.  mode 0 = these automatic choices (and forget
+ * what was learnt), 1 = never split and never stand down, 2 = always split.
+ * Results do not depend on any of it.                                            */
+int rbe_debug_set_plan_split(rbe_index *ix, int mode);
+
+/* The mass of one query as the progressive scan uses it (pure host function, for
+ * tests).  With qhat = sum_i c_i rho_i (rho = +-1 per bit), M = sum_d |qhat_d| is the
+ * largest value sum_i c_i (rho_i . rho) can take over all sign vectors rho.
+ * dyadic = 0: mass_out[0] >= M, larger by a few 2^-20 of dim * sum_i |c_i| (rounding
+ * allowance), mass_out[1] = 2^-19 mass_out[0].  dyadic = 1 (c_i = 2^-i, q_scales not
+ * read): the bits of mass_out[0] are the integer h_min = (dim (2^Pq - 1) - M') / 2 with
+ * M' = 2^(Pq-1) M, the least weighted mismatch count sum_i 2^(Pq-1-i) popcount(Q_i XOR K)
+ * any plane K can have; mass_out[1] = 0.
+ *   q_planes [q_n_planes][dim/64], q_scales [q_n_planes], mass_out [2]: host.    */
+int rbe_debug_query_mass(const uint64_t *q_planes, const float *q_scales, uint32_t q_n_planes,
+                         uint32_t dim, uint32_t dyadic, float *mass_out);
+
+/* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 7
+ * queries per call on, dim <= 128), 1 = always the XOR/popcount kernel, 2 = the
+ * matrix-core kernel for any number of queries (dim <= 128).                     */
+int rbe_debug_set_batch_path(rbe_index *ix, int path);
+
+/* fp32 hybrid scores (rbe_search_float arithmetic) of one fp32 query q [dim] for z in
+ * [first_item, first_item+count): out [count] float (host).                  */
+int rbe_debug_scores_float(rbe_index *ix, const float *q, uint64_t first_item,
+                           uint64_t count, float *out, void *hip_stream);
+
+/* Copies the (possibly cosine-folded) scales of items [first_item,
+ * first_item+count) back: out [n_planes][count] float (host).                */
+int rbe_debug_read_scales(rbe_index *ix, uint64_t first_item, uint64_t count,
+                          float *out, void *hip_stream);
+
+/* Copies the plane words of items [first_item, first_item+count) back:
+ * out [n_planes][count][dim/64] uint64 (host).                               */
+int rbe_debug_read_planes(rbe_index *ix, uint64_t first_item, uint64_t count,
+                          uint64_t *out, void *hip_stream);
+
+/* Tile order (pure host functions, for tests): physical position of logical
+ * tile `tile` in a corpus of n_tiles tiles with the given sample ratio, and the
+ * inverse.                                                                     */
+uint32_t rbe_debug_tile_to_phys(uint32_t n_tiles, uint32_t sample_ratio, uint32_t tile);
+uint32_t rbe_debug_phys_to_tile(uint32_t n_tiles, uint32_t sample_ratio, uint32_t phys);
+
+/* Refinement plan of the exact mode (pure host function, for tests): the levels
+ * rbe_search would run for such a corpus, each a range [first_tile, end_tile) of
+ * PHYSICAL tile positions; arrays of RBE_MAX_LEVELS entries.  n_levels = 0 means
+ * that no plan fits cand_capacity (the bounded-segment path is used instead).    */
+int rbe_debug_exact_plan(uint64_t n_items, uint32_t sample_ratio, uint32_t cand_capacity, uint32_t k,
+                         uint32_t *n_levels, uint32_t *first_tile, uint32_t *end_tile);
+
+/* Query operands of the matrix-core batch scan (pure host function, for tests).
+ * The queries are binary (q_planes [Q][Pq][W] and, unless dyadic, q_scales
+ * [Q][Pq]; q_float NULL) or fp32 (q_float [Q][dim]; general scales only, the
+ * other two are not read).
+ * halves_out [tile][plane copy][part][lane][8] fp16 bit patterns, where
+ * tile = query / 16, lane = 16 g + query % 16, part = 32-dimension part of the
+ * query and slot e = 2t + h of lane group g stands for bit (10 + 16h + t - 4g)
+ * mod 32 of that part, weighted by 2 / val_t with val_t = 2^-14, 2^-13, 2^-11,
+ * 2^-7 (the value of a half whose only set bit is bit 10 + t: the form in which
+ * the kernel feeds item bits), times 2^-j in plane copy j (dyadic only; one copy
+ * otherwise).  dyadic = 1: every half is exact and the contraction is the score.
+ * dyadic = 0 (general scales): every component is rounded to one half and the
+ * contraction is a filter whose distance from the score is at most
+ * margin * sum_j a_j[item]; survivors are scored again exactly.
+ * unscale_out[q] = 2^-k undoes the power-of-two scaling of query q; start_out[q]
+ * is where its accumulators start (minus the weighted sum of what the halves hold).
+ * shape_out = {tiles, plane copies, parts, margin (float bits)}: 4 entries.
+ * halves_capacity in halves.                                                    */
+int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, const float *q_float,
+                             uint32_t n_queries, uint32_t q_n_planes, uint32_t dim, uint32_t n_planes,
+                             uint32_t dyadic, uint16_t *halves_out, size_t halves_capacity,
+                             float *unscale_out, float *start_out, uint32_t *shape_out);
+
+/* Measurement yardstick: enqueues a plain copy kernel ("calib_copy") of `bytes`
+ * bytes from src_dev to dst_dev (DEVICE pointers, 16-byte aligned, bytes a
+ * multiple of 16, non-overlapping).  It reads and writes exactly `bytes` each,
+ * so hardware-counter readings of other kernels can be scaled by what the same
+ * counters report for it.  Asynchronous on the stream.                         */
+int rbe_debug_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
+
+/* Measurement yardstick: enqueues a read-only kernel ("calib_read") that streams
+ * `bytes` bytes from src_dev (DEVICE pointer, 16-byte aligned, bytes a multiple
+ * of 16) with the scan's access shape and writes 16 bytes per thread to
+ * sink_dev (DEVICE, 16-byte aligned, at least 3 * 256 * 16 bytes per compute
+ * unit: 3 MiB covers 256 units; EINVAL if too small).  Its rate is the practical
+ * read ceiling the scan is compared with.  Asynchronous on the stream.         */
+int rbe_debug_read(const void *src_dev, size_t bytes, void *sink_dev, size_t sink_bytes, void *hip_stream);
+
+/* What rbe_finalize decided for an index: out[0] = 1 if the pruning scans may be
+ * used (no negative scale), out[1] = 1 if it holds the one-byte scale copies,
+ * out[2] = 1 if it lives in caller-owned storage, out[3] = 1 if a caller-owned
+ * workspace is set.  out: 4 entries (host).                                     */
+int rbe_debug_index_info(const rbe_index *ix, uint32_t *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RBE_DEBUG_H */

@@ -1,4 +1,4 @@
-"""Thin Python binding of the RBE retrieval library (include/rbe.h).
+"""Thin Python binding of the RBE retrieval library (include/rbe.h, include/rbe_debug.h).
 
 Argument marshalling only: every step of the path runs in the HIP kernels of
 ``librbe_hip.so``.  There is no CPU fallback -- importing works without the
@@ -20,6 +20,7 @@ from . import _build
 
 RBE_OK, RBE_EINVAL, RBE_ENOMEM, RBE_EHIP, RBE_ESTATE, RBE_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 RBE_MEM_HOST, RBE_MEM_DEVICE = 0, 1
+RBE_BORROW = 1 << 0
 RBE_COSINE = 1 << 1
 RBE_DYADIC = 1 << 2
 RBE_SELECT_EXACT, RBE_SELECT_NEARLOSSLESS, RBE_SELECT_NEARLOSSLESS_Q2 = 0, 1, 2
@@ -58,6 +59,8 @@ _u64, _u32, _i32, _vp = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c
 PROTOTYPES = {
     "rbe_index_create": (_i32, [ctypes.POINTER(_vp), _u64, _u32, _u32, _u32]),
     "rbe_index_create_ex": (_i32, [ctypes.POINTER(_vp), _u64, _u32, _u32, _u32, _u32]),
+    "rbe_index_bytes": (ctypes.c_size_t, [_u64, _u32, _u32, _u32, _u32]),
+    "rbe_index_create_in": (_i32, [ctypes.POINTER(_vp), _u64, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t]),
     "rbe_load_chunk": (_i32, [_vp, _u64, _u64, _vp, _vp, _i32, _vp]),
     "rbe_encode_chunk": (_i32, [_vp, _u64, _u64, _vp, _i32, _vp]),
     "rbe_encode_corpus": (_i32, [ctypes.POINTER(_vp), _vp, _u64, _u32, _u32, _i32, _u32, _vp]),
@@ -66,6 +69,9 @@ PROTOTYPES = {
     "rbe_free": (None, [_vp]),
     "rbe_encode_query": (_i32, [_vp, _u32, _u32, _vp, _vp]),
     "rbe_search": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "rbe_workspace_bytes": (ctypes.c_size_t, [_vp, _u32, _u32, _u32]),
+    "rbe_set_workspace": (_i32, [_vp, _vp, ctypes.c_size_t]),
+    "rbe_debug_index_info": (_i32, [_vp, _vp]),
     "rbe_search_float": (_i32, [_vp, _vp, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_debug_scores_float": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
     "rbe_set_profiling": (_i32, [_vp, _i32]),
@@ -138,8 +144,10 @@ def _host(a, dtype):
 class Index:
     """Owner of an ``rbe_index*``."""
 
-    def __init__(self, handle: int):
+    def __init__(self, handle: int, keep=None):
         self._h = _vp(handle)
+        self._keep = keep           # tensors whose memory the index uses (caller-owned storage / workspace)
+        self._ws = None
 
     @property
     def handle(self):
@@ -211,6 +219,44 @@ def rbe_index_create_ex(n_items: int, dim: int, n_planes: int, flags: int = 0, s
     out = _vp(None)
     _check(load_library().rbe_index_create_ex(ctypes.byref(out), n_items, dim, n_planes, flags, sample_ratio))
     return Index(out.value)
+
+
+def rbe_index_bytes(n_items: int, dim: int, n_planes: int, flags: int = 0, sample_ratio: int = 0) -> int:
+    return int(load_library().rbe_index_bytes(n_items, dim, n_planes, flags, sample_ratio))
+
+
+def rbe_index_create_in(n_items: int, dim: int, n_planes: int, flags: int, sample_ratio: int, storage) -> Index:
+    """Index inside `storage`, a torch cuda tensor (any dtype) of at least rbe_index_bytes(...) bytes.
+    The Index object keeps a reference to the tensor."""
+    if not getattr(storage, "is_cuda", False):
+        raise RbeError(RBE_EINVAL, "storage must be a torch cuda tensor")
+    out = _vp(None)
+    _check(load_library().rbe_index_create_in(ctypes.byref(out), n_items, dim, n_planes, flags, sample_ratio,
+                                              _vp(storage.data_ptr()), storage.numel() * storage.element_size()))
+    return Index(out.value, keep=storage)
+
+
+def rbe_workspace_bytes(ix: Index, n_queries: int, k: int, mode: int = RBE_SELECT_EXACT) -> int:
+    return int(load_library().rbe_workspace_bytes(ix.handle, n_queries, k, mode))
+
+
+def rbe_set_workspace(ix: Index, workspace):
+    """workspace: a torch cuda tensor that will hold all device scratch of later searches, or None to
+    return to library-owned scratch.  The Index object keeps a reference to the tensor."""
+    if workspace is None:
+        _check(load_library().rbe_set_workspace(ix.handle, None, 0))
+    else:
+        if not getattr(workspace, "is_cuda", False):
+            raise RbeError(RBE_EINVAL, "workspace must be a torch cuda tensor")
+        _check(load_library().rbe_set_workspace(ix.handle, _vp(workspace.data_ptr()),
+                                                workspace.numel() * workspace.element_size()))
+    ix._ws = workspace
+
+
+def rbe_debug_index_info(ix: Index) -> dict:
+    out = np.zeros(4, dtype=np.uint32)
+    _check(load_library().rbe_debug_index_info(ix.handle, out.ctypes.data_as(_vp)))
+    return {"can_prune": bool(out[0]), "scale_copies": bool(out[1]), "borrowed": bool(out[2]), "caller_workspace": bool(out[3])}
 
 
 def rbe_load_chunk(ix: Index, first_item: int, planes, scales, stream=None):

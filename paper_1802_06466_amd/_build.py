@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librbe_hip.so")
 HEADERS = [os.path.join(CSRC, h) for h in ("rbe_kernels.hpp", "rbe_layout.hpp", "rbe_internal.hpp",
-                                           "rbe_misc_kernels.hpp")] + [os.path.join(ROOT, "include", "rbe.h")]
+                                           "rbe_misc_kernels.hpp")] + [os.path.join(ROOT, "include", "rbe.h"), os.path.join(ROOT, "include", "rbe_debug.h")]
 # (source, extra defines, object suffix)
 # The matrix-core kernel reads every accumulator with ordinary vector instructions right after the MFMAs:
 # keep the accumulators in the ordinary register file (gfx950 has one unified file) instead of copying

@@ -1,6 +1,7 @@
-// Host side of the RBE retrieval library: the C ABI declared in include/rbe.h,
+// Host side of the RBE retrieval library: the C ABI declared in include/rbe.h and include/rbe_debug.h,
 // argument checks, device storage, the refinement plan and kernel launches.
 #include "rbe.h"
+#include "rbe_debug.h"
 #include "rbe_internal.hpp"
 #include "rbe_misc_kernels.hpp"
 
@@ -69,24 +70,49 @@ struct rbe_index {
     // tuning
     uint32_t cap_override = 0, blocks_per_cu = 0;  // 0 = derived
 
-    // search workspace (grown on demand)
-    uint32_t ws_queries = 0, ws_cap = 0, ws_k = 0;
-    uint64_t* d_cand = nullptr;
-    uint32_t* d_count = nullptr;
-    uint64_t* d_tau = nullptr;
-    uint64_t* d_kmax = nullptr;
-    // One block holds everything a search sends back, so that one copy fetches it:
-    //   [status: kResultStatusBytes][seen: RBE_MAX_LEVELS x RBE_MAX_QUERIES u32][ids: Q x k i64][scores: Q x k f32]
-    // (ids and scores packed for the Q and k of the current call).  The pointers below point into it.
-    char* d_result = nullptr;
-    char* h_result = nullptr;       // pinned mirror
-    uint32_t* d_status = nullptr;   // 16 words: [0] flags, [1..8] rows read in full per level, [9] (query, row) pairs scored in
-                                    // full by the batch progressive scan, [12] [13] first looks of the matrix-core scan, [14] deep units
-    uint32_t* d_seen = nullptr;     // [RBE_MAX_LEVELS][RBE_MAX_QUERIES]
-    uint32_t* d_aops = nullptr;     // matrix-core query operands (BatchArgs::a_ops)
+    // Device scratch of a search (see carve_workspace for the layout of the block it lives in).
+    struct DevWs {
+        uint64_t* cand = nullptr;       // [Q][cap] candidate keys
+        uint32_t* count = nullptr;      // [Q] x kCountStride
+        uint64_t* tau = nullptr;        // [Q]
+        uint64_t* kmax = nullptr;       // [Q] x kKmaxStride
+        // One block holds everything a search sends back, so that one copy fetches it:
+        //   [status: kResultStatusBytes][seen: RBE_MAX_LEVELS x RBE_MAX_QUERIES u32][ids: Q x k i64][scores: Q x k f32]
+        // (ids and scores packed for the Q and k of the current call).  The pointers below point into it.
+        char* result = nullptr;
+        uint32_t* status = nullptr;     // 16 words: [0] flags, [1..8] rows read in full per level, [9] (query, row) pairs scored in
+                                        // full by the batch progressive scan, [12] [13] first looks of the matrix-core scan, [14] deep units
+        uint32_t* seen = nullptr;       // [RBE_MAX_LEVELS][RBE_MAX_QUERIES]
+        int64_t* ids = nullptr;
+        float* scores = nullptr;
+        uint32_t* qwords = nullptr;     // [RBE_MAX_QUERIES][PQ][2W], followed (fixed offset) by
+        float* qcoef = nullptr;         // [RBE_MAX_QUERIES][PQ+1] and the query masses
+        float* unscale = nullptr;       // [3][RBE_MAX_QUERIES]: matrix-core scan, per query 2^-k, start value, mass
+        uint32_t* aops = nullptr;       // matrix-core query operands (BatchArgs::a_ops)
+        float* lut = nullptr;           // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
+    };
+    DevWs ws;                       // the scratch the current search uses: carved from one of the two blocks below
+    char* own_ws = nullptr;         // grown on demand by the library (hipMalloc) ...
+    size_t own_ws_bytes = 0;
+    char* ext_ws = nullptr;         // ... or lent by the caller (rbe_set_workspace): never grown, never freed here
+    size_t ext_ws_bytes = 0;
+    // pinned host mirrors, allocated once at rbe_index_create for the largest call (RBE_MAX_QUERIES x RBE_MAX_K)
+    char* h_result = nullptr;
+    uint32_t* h_status = nullptr;
+    uint32_t* h_seen = nullptr;
+    int64_t* h_ids = nullptr;
+    float* h_scores = nullptr;
+    uint32_t* h_qwords = nullptr;
+    float* h_qcoef = nullptr;
     uint32_t* h_aops = nullptr;
-    float* d_unscale = nullptr;     // [Q]
     float* h_unscale = nullptr;
+    float* h_lut = nullptr;
+    int device = 0;                 // the GPU that owns the index
+    // corpus storage lent by the caller (rbe_index_create_in): tiles, side arrays and the scratch of rbe_finalize
+    bool borrowed = false;
+    char* fin_scratch = nullptr;    // borrowed storage: 256 bytes for rbe_finalize's reductions
+    // false if a scale is negative: every bound of the pruning scans assumes a_j >= 0, so they all stay off
+    bool nonneg = true;
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
     uint32_t* d_hints = nullptr;    // general scales, P >= 2: one-byte copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
     int hint_base[3] = {1, 1, 1};   // exponent base of each array's hints
@@ -107,19 +133,6 @@ struct rbe_index {
     bool fq_binary = false;
     float fq_bmass[RBE_MAX_QUERIES][2] = {};  // its mass (query_mass)
     float fq_resid[RBE_MAX_QUERIES] = {};     // >= sum_d |q_d - qhat_d|
-    float* d_lut = nullptr;         // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
-    float* h_lut = nullptr;
-    uint32_t* d_qwords = nullptr;   // [Q][PQ][2W]
-    float* d_qcoef = nullptr;       // [Q][PQ+1]
-    int64_t* d_ids = nullptr;
-    float* d_scores = nullptr;
-    // pinned host mirrors
-    uint32_t* h_qwords = nullptr;
-    float* h_qcoef = nullptr;
-    int64_t* h_ids = nullptr;
-    float* h_scores = nullptr;
-    uint32_t* h_status = nullptr;
-    uint32_t* h_seen = nullptr;
 
     int profiling = 0;
     hipEvent_t ev[kMaxEvents] = {};
@@ -184,53 +197,92 @@ hipError_t launch_dense_scores(uint32_t W, const KernelSel& k, const char* tiles
 }
 
 // ---------------------------------------------------------------- workspace
-void free_workspace(rbe_index* ix)
+// All device scratch of one search lives in one block, laid out for the call's n_queries, k and candidate
+// capacity: fixed-size state first, the large candidate lists last, every part 256-byte aligned.  With
+// base == nullptr only the size is computed.  The block is the library's own (grown on demand), the caller's
+// (rbe_set_workspace).
+constexpr size_t kWsAlign = 256;
+constexpr size_t kQueryWordsBytes = (size_t)RBE_MAX_QUERIES * RBE_MAX_PLANES * 8 * sizeof(uint32_t);
+constexpr size_t kQueryCoefBytes = (size_t)RBE_MAX_QUERIES * (RBE_MAX_PLANES + 1 + 2) * sizeof(float);
+constexpr size_t kHalvesPerQueryTile = (size_t)4 * 4 * 64 * 8;   // copies x parts <= 16, 64 lanes, 8 halves
+
+size_t carve_workspace(rbe_index::DevWs* ws, char* base, uint32_t W, uint32_t Q, uint32_t k, uint32_t cap)
 {
-    (void)hipFree(ix->d_cand);   ix->d_cand = nullptr;
-    (void)hipFree(ix->d_result);     ix->d_result = nullptr;
-    (void)hipHostFree(ix->h_result); ix->h_result = nullptr;
-    ix->d_status = ix->d_seen = ix->h_status = ix->h_seen = nullptr;
-    ix->d_ids = ix->h_ids = nullptr;
-    ix->d_scores = ix->h_scores = nullptr;
-    ix->ws_queries = ix->ws_cap = ix->ws_k = 0;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = base ? base + off : nullptr;
+        off += (bytes + kWsAlign - 1) / kWsAlign * kWsAlign;
+        return p;
+    };
+    rbe_index::DevWs w;
+    w.count = reinterpret_cast<uint32_t*>(take((size_t)Q * rbe::kCountStride * sizeof(uint32_t)));
+    w.tau = reinterpret_cast<uint64_t*>(take((size_t)Q * sizeof(uint64_t)));
+    w.kmax = reinterpret_cast<uint64_t*>(take((size_t)Q * rbe::kKmaxStride * sizeof(uint64_t)));
+    // query words and coefficients share one block (coefficients at a fixed offset) so that one copy stages both
+    w.qwords = reinterpret_cast<uint32_t*>(take(kQueryWordsBytes + kQueryCoefBytes));
+    w.qcoef = base ? reinterpret_cast<float*>(reinterpret_cast<char*>(w.qwords) + kQueryWordsBytes) : nullptr;
+    w.unscale = reinterpret_cast<float*>(take(3 * RBE_MAX_QUERIES * sizeof(float)));
+    w.aops = reinterpret_cast<uint32_t*>(take((size_t)((Q + 15u) / 16u) * kHalvesPerQueryTile * sizeof(uint16_t)));
+    w.lut = reinterpret_cast<float*>(take((size_t)Q * 8 * W * 256 * sizeof(float)));
+    w.result = take(kResultHeaderBytes + (size_t)Q * k * (sizeof(int64_t) + sizeof(float)));
+    w.cand = reinterpret_cast<uint64_t*>(take((size_t)Q * cap * sizeof(uint64_t)));
+    if (base) {
+        w.status = reinterpret_cast<uint32_t*>(w.result);
+        w.seen = reinterpret_cast<uint32_t*>(w.result + kResultStatusBytes);
+        w.ids = reinterpret_cast<int64_t*>(w.result + kResultHeaderBytes);
+        w.scores = reinterpret_cast<float*>(w.ids + (size_t)Q * k);   // this call's scores follow its ids directly
+        *ws = w;
+    }
+    return off;
 }
 
-int ensure_fixed(rbe_index* ix)
+// Candidate slots per query of a search for k results.
+uint32_t search_capacity(const rbe_index* ix, uint32_t k)
 {
-    if (ix->d_count) return RBE_OK;
-    const size_t Q = RBE_MAX_QUERIES;
-    HIP_TRY(hipMalloc(&ix->d_count, Q * rbe::kCountStride * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&ix->d_tau, Q * sizeof(uint64_t)));
-    HIP_TRY(hipMalloc(&ix->d_kmax, Q * rbe::kKmaxStride * sizeof(uint64_t)));
-    // query words and coefficients share one block (coefficients at a fixed offset) so that one copy stages both
-    const size_t words_bytes = Q * RBE_MAX_PLANES * 8 * sizeof(uint32_t), coef_bytes = Q * (RBE_MAX_PLANES + 1 + 2) * sizeof(float);
-    HIP_TRY(hipMalloc(&ix->d_qwords, words_bytes + coef_bytes));
-    HIP_TRY(hipHostMalloc(&ix->h_qwords, words_bytes + coef_bytes, hipHostMallocDefault));
-    ix->d_qcoef = reinterpret_cast<float*>(reinterpret_cast<char*>(ix->d_qwords) + words_bytes);
-    ix->h_qcoef = reinterpret_cast<float*>(reinterpret_cast<char*>(ix->h_qwords) + words_bytes);
-    for (uint32_t i = 0; i < kMaxEvents; ++i) HIP_TRY(hipEventCreate(&ix->ev[i]));
-    ix->ev_ok = true;
+    const uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->layout.ratio * k);
+    return std::max<uint32_t>(cap, k + 2 * kTileItems);
+}
+
+// Points ix->ws at scratch for this call: the caller's block if one was set (an error if it is too small),
+// else the library's own block, grown when this call needs more than any call before it.
+int acquire_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
+{
+    const size_t need = carve_workspace(nullptr, nullptr, ix->W, Q, k, cap);
+    if (ix->ext_ws) {
+        if (need > ix->ext_ws_bytes) {
+            set_error("the workspace set with rbe_set_workspace holds %zu bytes; this search needs %zu "
+                      "(rbe_workspace_bytes)", ix->ext_ws_bytes, need);
+            return RBE_EINVAL;
+        }
+        carve_workspace(&ix->ws, ix->ext_ws, ix->W, Q, k, cap);
+        return RBE_OK;
+    }
+    if (need > ix->own_ws_bytes) {
+        (void)hipFree(ix->own_ws);
+        ix->own_ws = nullptr; ix->own_ws_bytes = 0;
+        ix->ws = rbe_index::DevWs{};
+        HIP_TRY(hipMalloc(&ix->own_ws, need));
+        ix->own_ws_bytes = need;
+    }
+    carve_workspace(&ix->ws, ix->own_ws, ix->W, Q, k, cap);
     return RBE_OK;
 }
 
-int ensure_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
+// Pinned host mirrors and events: once per index, sized for the largest call.
+int allocate_host_side(rbe_index* ix)
 {
-    int rc = ensure_fixed(ix);
-    if (rc) return rc;
-    if (Q <= ix->ws_queries && cap <= ix->ws_cap && k <= ix->ws_k) return RBE_OK;
-    const uint32_t nQ = std::max(Q, ix->ws_queries), nC = std::max(cap, ix->ws_cap), nK = std::max(k, ix->ws_k);
-    free_workspace(ix);
-    HIP_TRY(hipMalloc(&ix->d_cand, (size_t)nQ * nC * sizeof(uint64_t)));
-    const size_t result_bytes = kResultHeaderBytes + (size_t)nQ * nK * (sizeof(int64_t) + sizeof(float));
-    HIP_TRY(hipMalloc(&ix->d_result, result_bytes));
+    const size_t result_bytes = kResultHeaderBytes + (size_t)RBE_MAX_QUERIES * RBE_MAX_K * (sizeof(int64_t) + sizeof(float));
     HIP_TRY(hipHostMalloc(&ix->h_result, result_bytes, hipHostMallocDefault));
-    ix->d_status = reinterpret_cast<uint32_t*>(ix->d_result);
     ix->h_status = reinterpret_cast<uint32_t*>(ix->h_result);
-    ix->d_seen = reinterpret_cast<uint32_t*>(ix->d_result + kResultStatusBytes);
     ix->h_seen = reinterpret_cast<uint32_t*>(ix->h_result + kResultStatusBytes);
-    ix->d_ids = reinterpret_cast<int64_t*>(ix->d_result + kResultHeaderBytes);
     ix->h_ids = reinterpret_cast<int64_t*>(ix->h_result + kResultHeaderBytes);
-    ix->ws_queries = nQ; ix->ws_cap = nC; ix->ws_k = nK;
+    HIP_TRY(hipHostMalloc(&ix->h_qwords, kQueryWordsBytes + kQueryCoefBytes, hipHostMallocDefault));
+    ix->h_qcoef = reinterpret_cast<float*>(reinterpret_cast<char*>(ix->h_qwords) + kQueryWordsBytes);
+    HIP_TRY(hipHostMalloc(&ix->h_aops, (RBE_MAX_QUERIES / 16) * kHalvesPerQueryTile * sizeof(uint16_t), hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc(&ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc(&ix->h_lut, (size_t)RBE_MAX_QUERIES * 8 * ix->W * 256 * sizeof(float), hipHostMallocDefault));
+    for (uint32_t i = 0; i < kMaxEvents; ++i) HIP_TRY(hipEventCreate(&ix->ev[i]));
+    ix->ev_ok = true;
     return RBE_OK;
 }
 
@@ -300,8 +352,8 @@ int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales
         query_mass(q_planes + (size_t)q * PQ * W, q_scales ? q_scales + (size_t)q * PQ : nullptr, PQ, ix->dim, dyadic,
                    ix->h_qcoef + (size_t)Q * (PQ + 1) + 2 * (size_t)q);
     }
-    const size_t staged = (size_t)((char*)ix->h_qcoef - (char*)ix->h_qwords) + (size_t)Q * (PQ + 1 + 2) * sizeof(float);
-    HIP_TRY(hipMemcpyAsync(ix->d_qwords, ix->h_qwords, staged, hipMemcpyHostToDevice, st));
+    const size_t staged = kQueryWordsBytes + (size_t)Q * (PQ + 1 + 2) * sizeof(float);
+    HIP_TRY(hipMemcpyAsync(ix->ws.qwords, ix->h_qwords, staged, hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
 
@@ -310,10 +362,6 @@ int stage_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales
 int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t st)
 {
     const size_t per_q = (size_t)8 * ix->W * 256;
-    if (!ix->d_lut) {
-        HIP_TRY(hipMalloc(&ix->d_lut, RBE_MAX_QUERIES * per_q * sizeof(float)));
-        HIP_TRY(hipHostMalloc(&ix->h_lut, RBE_MAX_QUERIES * per_q * sizeof(float), hipHostMallocDefault));
-    }
     for (uint32_t n = 0; n < Q; ++n) {
         const float* x = q + (size_t)n * ix->dim;
         double m_abs = 0.0;
@@ -334,7 +382,7 @@ int stage_float_queries(rbe_index* ix, const float* q, uint32_t Q, hipStream_t s
                 ix->h_lut[n * per_q + (size_t)p * 256 + v] = (float)acc;
             }
     }
-    HIP_TRY(hipMemcpyAsync(ix->d_lut, ix->h_lut, (size_t)Q * per_q * sizeof(float), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->ws.lut, ix->h_lut, (size_t)Q * per_q * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
 
@@ -388,9 +436,15 @@ uint32_t batch_rescore(const rbe_index* ix, bool float_query)
     return ix->mode != rbe::kModeScaled ? 0u : (float_query ? 2u : 1u);
 }
 
+// The pruning scans (progressive last level, first look and filter of the matrix-core scan) rest on upper bounds
+// of the form "partial score + largest scale x query mass", which hold for scales >= 0 only: an index that holds a
+// negative scale is searched by the plain scans alone.
+bool can_prune(const rbe_index* ix) { return ix->nonneg; }
+
 bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query)
 {
     if (mode != RBE_SELECT_EXACT || !rbe::batch_mfma_supported(ix->W)) return false;
+    if (!can_prune(ix)) return false;   // its filter slack is margin * sum_j a_j
     // full-precision queries need the filter; the dyadic kernels have none (their binary queries are exact)
     if (float_query && ix->mode != rbe::kModeScaled) return false;
     if (ix->batch_path == 1) return false;
@@ -527,20 +581,13 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
 int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
                         hipStream_t st, const float* q_float = nullptr)
 {
-    const size_t max_halves = (size_t)(RBE_MAX_QUERIES / 16) * 4 * 4 * 64 * 8;   // per tile: copies x parts <= 16
-    if (!ix->d_aops) {
-        HIP_TRY(hipMalloc(&ix->d_aops, max_halves * sizeof(uint16_t)));
-        HIP_TRY(hipHostMalloc(&ix->h_aops, max_halves * sizeof(uint16_t), hipHostMallocDefault));
-        HIP_TRY(hipMalloc(&ix->d_unscale, 3 * RBE_MAX_QUERIES * sizeof(float)));
-        HIP_TRY(hipHostMalloc(&ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipHostMallocDefault));
-    }
     const bool dyadic = ix->mode != rbe::kModeScaled;
     const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q);
     build_batch_operands(ix->W, ix->P, dyadic, q_planes, q_scales, Q, PQ, reinterpret_cast<uint16_t*>(ix->h_aops),
                          ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float, &ix->batch_margin,
                          ix->h_unscale + 2 * RBE_MAX_QUERIES);
-    HIP_TRY(hipMemcpyAsync(ix->d_aops, ix->h_aops, sh.n_halves * sizeof(uint16_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(ix->d_unscale, ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->ws.aops, ix->h_aops, sh.n_halves * sizeof(uint16_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->ws.unscale, ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
     return RBE_OK;
 }
 
@@ -594,21 +641,52 @@ uint64_t rbe_n_items(const rbe_index* ix) { return ix ? ix->n_items : 0; }
 uint32_t rbe_dim(const rbe_index* ix) { return ix ? ix->dim : 0; }
 uint32_t rbe_n_planes(const rbe_index* ix) { return ix ? ix->P : 0; }
 
-static int create_with_ratio(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags, uint32_t ratio)
+// Device memory of an index: [tiles][row maxima: 2 floats per row of 256 items, if the items carry scales]
+// [one-byte scale copies, general scales with 2 or more planes][256 bytes for rbe_finalize's reductions], every
+// part 256-byte aligned.  With base == nullptr only the size is computed.
+struct IndexStorage { char* tiles; float* row_amax; uint32_t* hints; char* fin_scratch; size_t bytes; };
+
+static size_t hint_bytes(const rbe_index* ix)
 {
-    ARG_CHECK(out != nullptr, "out is NULL");
+    if (!(ix->mode == rbe::kModeScaled && ix->P >= 2)) return 0;
+    const uint32_t nw = ix->P - 1 == 3 ? 4u : ix->P - 1;
+    return (size_t)ix->layout.n_tiles * (kTileItems / 4) * nw * sizeof(uint32_t);
+}
+
+static IndexStorage carve_index_storage(const rbe_index* ix, char* base)
+{
+    IndexStorage st{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = base && bytes ? base + off : nullptr;
+        off += (bytes + kWsAlign - 1) / kWsAlign * kWsAlign;
+        return p;
+    };
+    st.tiles = take((size_t)ix->layout.n_tiles * ix->geom.tile_bytes());
+    const size_t n_rows = (size_t)ix->layout.n_tiles * (kTileItems / kRow);
+    st.row_amax = reinterpret_cast<float*>(take(ix->geom.S > 0 ? 2 * n_rows * sizeof(float) : 0));
+    st.hints = reinterpret_cast<uint32_t*>(take(hint_bytes(ix)));
+    st.fin_scratch = take(256);
+    st.bytes = off;
+    return st;
+}
+
+static int check_shape(uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags, uint32_t ratio, uint32_t allowed_flags)
+{
     ARG_CHECK(dim == 64 || dim == 128 || dim == 256, "dim must be 64, 128 or 256 (got %u)", dim);
     ARG_CHECK(n_planes >= 1 && n_planes <= RBE_MAX_PLANES, "n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, n_planes);
     ARG_CHECK(n_items >= 1 && n_items <= RBE_MAX_ITEMS, "n_items must be 1..%llu", (unsigned long long)RBE_MAX_ITEMS);
-    ARG_CHECK((flags & ~(uint32_t)(RBE_COSINE | RBE_DYADIC)) == 0, "unknown flags 0x%x", flags);
+    ARG_CHECK((flags & ~allowed_flags) == 0, "unknown or misplaced flags 0x%x", flags & ~allowed_flags);
     if ((flags & RBE_DYADIC) && !rbe::dyadic_supported(dim / 64)) {
         set_error("RBE_DYADIC is built for dim 64 and 128 only (got %u)", dim);
         return RBE_EUNSUPPORTED;
     }
     ARG_CHECK(ratio >= 2 && ratio <= 4096, "sample ratio must be 2..4096 (got %u)", ratio);
+    return RBE_OK;
+}
 
-    rbe_index* ix = new (std::nothrow) rbe_index();
-    if (!ix) { set_error("host allocation failed"); return RBE_ENOMEM; }
+static void describe_shape(rbe_index* ix, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags, uint32_t ratio)
+{
     ix->n_items = n_items;
     ix->dim = dim;
     ix->W = dim / 64;
@@ -617,11 +695,23 @@ static int create_with_ratio(rbe_index** out, uint64_t n_items, uint32_t dim, ui
     ix->mode = (flags & RBE_DYADIC) ? ((flags & RBE_COSINE) ? rbe::kModeDyadicNorm : rbe::kModeDyadic) : rbe::kModeScaled;
     ix->geom = rbe::TileGeom{ix->W, ix->P, (uint32_t)rbe::scale_arrays(ix->mode, (int)ix->P)};
     ix->layout = rbe::make_layout((uint32_t)((n_items + kTileItems - 1) / kTileItems), ratio);
+}
 
-    int dev = 0;
+// storage == nullptr: the library allocates the tiles (and, at rbe_finalize, the side arrays) itself.
+static int create_with_ratio(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags, uint32_t ratio,
+                             void* storage = nullptr, size_t storage_bytes = 0)
+{
+    ARG_CHECK(out != nullptr, "out is NULL");
+    int rc = check_shape(n_items, dim, n_planes, flags, ratio, (uint32_t)(RBE_COSINE | RBE_DYADIC) | (storage ? (uint32_t)RBE_BORROW : 0u));
+    if (rc) return rc;
+
+    rbe_index* ix = new (std::nothrow) rbe_index();
+    if (!ix) { set_error("host allocation failed"); return RBE_ENOMEM; }
+    describe_shape(ix, n_items, dim, n_planes, flags & ~(uint32_t)RBE_BORROW, ratio);
+
     hipDeviceProp_t prop;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    hipError_t e = hipGetDevice(&ix->device);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, ix->device);
     if (e != hipSuccess) {
         set_error("no usable HIP device: %s", hipGetErrorString(e));
         delete ix;
@@ -630,14 +720,30 @@ static int create_with_ratio(rbe_index** out, uint64_t n_items, uint32_t dim, ui
     ix->n_cu = prop.multiProcessorCount;
 
     const size_t bytes = (size_t)ix->layout.n_tiles * ix->geom.tile_bytes();
-    e = hipMalloc(&ix->d_tiles, bytes);
-    if (e == hipSuccess) e = hipMemset(ix->d_tiles, 0, bytes);
+    if (storage) {
+        const IndexStorage need = carve_index_storage(ix, nullptr);
+        if (storage_bytes < need.bytes || ((uintptr_t)storage % kWsAlign) != 0) {
+            set_error("storage must be 256-byte aligned and hold %zu bytes (rbe_index_bytes); got %zu", need.bytes, storage_bytes);
+            delete ix;
+            return RBE_EINVAL;
+        }
+        const IndexStorage st = carve_index_storage(ix, static_cast<char*>(storage));
+        ix->borrowed = true;
+        ix->d_tiles = st.tiles;
+        ix->fin_scratch = st.fin_scratch;
+        e = hipMemset(ix->d_tiles, 0, bytes);
+    } else {
+        e = hipMalloc(&ix->d_tiles, bytes);
+        if (e == hipSuccess) e = hipMemset(ix->d_tiles, 0, bytes);
+    }
     if (e != hipSuccess) {
         set_error("device allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
-        (void)hipFree(ix->d_tiles);
+        if (!ix->borrowed) (void)hipFree(ix->d_tiles);
         delete ix;
         return e == hipErrorOutOfMemory ? RBE_ENOMEM : RBE_EHIP;
     }
+    rc = allocate_host_side(ix);
+    if (rc) { rbe_free(ix); return rc; }
     *out = ix;
     return RBE_OK;
 }
@@ -651,6 +757,23 @@ int rbe_index_create_ex(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_
                         uint32_t sample_ratio)
 {
     return create_with_ratio(out, n_items, dim, n_planes, flags, sample_ratio ? sample_ratio : 64);
+}
+
+size_t rbe_index_bytes(uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags, uint32_t sample_ratio)
+{
+    const uint32_t ratio = sample_ratio ? sample_ratio : 64;
+    if (check_shape(n_items, dim, n_planes, flags, ratio, (uint32_t)(RBE_COSINE | RBE_DYADIC | RBE_BORROW))) return 0;
+    rbe_index shape;
+    describe_shape(&shape, n_items, dim, n_planes, flags & ~(uint32_t)RBE_BORROW, ratio);
+    return carve_index_storage(&shape, nullptr).bytes;
+}
+
+int rbe_index_create_in(rbe_index** out, uint64_t n_items, uint32_t dim, uint32_t n_planes, uint32_t flags,
+                        uint32_t sample_ratio, void* storage_dev, size_t storage_bytes)
+{
+    ARG_CHECK(flags & RBE_BORROW, "rbe_index_create_in takes caller-owned storage: pass RBE_BORROW in flags");
+    ARG_CHECK(storage_dev != nullptr, "storage_dev is NULL");
+    return create_with_ratio(out, n_items, dim, n_planes, flags, sample_ratio ? sample_ratio : 64, storage_dev, storage_bytes);
 }
 
 uint32_t rbe_debug_tile_to_phys(uint32_t n_tiles, uint32_t sample_ratio, uint32_t tile)
@@ -810,54 +933,89 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
     ARG_CHECK(ix != nullptr, "index is NULL");
     if (ix->ready) { set_error("rbe_finalize called twice"); return RBE_ESTATE; }
     hipStream_t st = (hipStream_t)hip_stream;
+    const IndexStorage lent = ix->borrowed ? carve_index_storage(ix, ix->d_tiles) : IndexStorage{};
+
+    // What the caller's scales look like (general scales only; the dyadic modes store none of the caller's):
+    // per array the largest magnitude, and whether any sign bit is set.
+    static_assert(RBE_MAX_PLANES == 4, "scale_array_max writes its sign flags at out[4 + j]");
+    uint32_t h_max[2 * RBE_MAX_PLANES] = {};
+    if (ix->mode == rbe::kModeScaled) {
+        uint32_t* d_max = reinterpret_cast<uint32_t*>(ix->fin_scratch);
+        if (!ix->borrowed) HIP_TRY(hipMalloc(&d_max, sizeof(h_max)));
+        hipError_t e = hipMemsetAsync(d_max, 0, sizeof(h_max), st);
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(rbe::scale_array_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_max);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipMemcpyAsync(h_max, d_max, sizeof(h_max), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (!ix->borrowed) (void)hipFree(d_max);
+        HIP_TRY(e);
+        ix->nonneg = true;
+        for (uint32_t j = 0; j < ix->P; ++j) {
+            if (h_max[j] >= 0x7f800000u) {
+                set_error("scale array %u holds a value that is not finite", j);
+                return RBE_EINVAL;      // the index stays in the loading state: the chunk can be loaded again
+            }
+            ix->nonneg = ix->nonneg && h_max[RBE_MAX_PLANES + j] == 0;
+        }
+    }
     if (ix->flags & RBE_COSINE) {
         const uint64_t n_slots = (uint64_t)ix->layout.n_tiles * kTileItems;
         hipLaunchKernelGGL(rbe::fold_cosine, dim3((uint32_t)((n_slots + 255) / 256)), dim3(256), 0, st,
                            ix->d_tiles, ix->geom, n_slots);
         HIP_TRY(hipGetLastError());
     }
-    if (ix->geom.S > 0) {
+    // Side arrays of the pruning scans.  Their bounds hold for scales >= 0 only, so an index with a negative scale
+    // gets none and is searched by the plain scans (see can_prune).
+    if (ix->geom.S > 0 && ix->nonneg) {
         const size_t n_rows = (size_t)ix->layout.n_tiles * (kTileItems / kRow);
-        HIP_TRY(hipMalloc(&ix->d_row_amax, 2 * n_rows * sizeof(float)));
+        if (ix->borrowed) ix->d_row_amax = lent.row_amax;
+        else HIP_TRY(hipMalloc(&ix->d_row_amax, 2 * n_rows * sizeof(float)));
         hipLaunchKernelGGL(rbe::row_scale_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, ix->d_row_amax,
                            ix->d_row_amax + n_rows);
         HIP_TRY(hipGetLastError());
     }
-    if (ix->mode == rbe::kModeScaled && ix->P >= 2) {
-        // optional: without them the one-query scan streams the fp32 scale arrays 0 .. P-2 instead
-        const uint32_t nw = ix->P - 1 == 3 ? 4u : ix->P - 1;
-        const hipError_t eh = hipMalloc(&ix->d_hints, (size_t)ix->layout.n_tiles * (kTileItems / 4) * nw * sizeof(uint32_t));
-        if (eh == hipErrorOutOfMemory) { (void)hipGetLastError(); ix->d_hints = nullptr; }
-        else HIP_TRY(eh);
+    if (ix->mode == rbe::kModeScaled && ix->P >= 2 && ix->nonneg) {
+        if (ix->borrowed) {
+            ix->d_hints = lent.hints;
+        } else {
+            // optional: without them the one-query scan streams the fp32 scale arrays 0 .. P-2 instead
+            const hipError_t eh = hipMalloc(&ix->d_hints, hint_bytes(ix));
+            if (eh == hipErrorOutOfMemory) { (void)hipGetLastError(); ix->d_hints = nullptr; }
+            else HIP_TRY(eh);
+        }
     }
     if (ix->d_hints) {
-        // exponent base per array, from the array's largest value
-        uint32_t* d_max = nullptr;
-        uint32_t h_max[RBE_MAX_PLANES] = {};
-        int* d_base = nullptr;
-        HIP_TRY(hipMalloc(&d_max, RBE_MAX_PLANES * sizeof(uint32_t)));
-        HIP_TRY(hipMemsetAsync(d_max, 0, RBE_MAX_PLANES * sizeof(uint32_t), st));
-        hipLaunchKernelGGL(rbe::scale_array_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_max);
-        HIP_TRY(hipGetLastError());
-        HIP_TRY(hipMemcpyAsync(h_max, d_max, sizeof(h_max), hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipStreamSynchronize(st));
-        bool usable = true;     // the hints stand for finite, non-negative scales only
-        for (uint32_t j = 0; j < ix->P; ++j) usable = usable && h_max[j] < 0x7f800000u;
-        if (usable) {
-            // the largest value, rounded as scale_hints rounds it, gets the largest exponent field (7)
-            for (uint32_t j = 0; j + 1 < ix->P; ++j)
-                ix->hint_base[j] = std::max(1, (int)((h_max[j] + (1u << 17)) >> 23) - 7);
-            HIP_TRY(hipMalloc(&d_base, 3 * sizeof(int)));
-            HIP_TRY(hipMemcpyAsync(d_base, ix->hint_base, 3 * sizeof(int), hipMemcpyHostToDevice, st));
+        // exponent base per array, from the array's largest value (the cosine fold has changed the scales: take the
+        // maxima again)
+        if (ix->flags & RBE_COSINE) {
+            uint32_t* d_max = reinterpret_cast<uint32_t*>(ix->fin_scratch);
+            if (!ix->borrowed) HIP_TRY(hipMalloc(&d_max, sizeof(h_max)));
+            hipError_t e = hipMemsetAsync(d_max, 0, sizeof(h_max), st);
+            if (e == hipSuccess) {
+                hipLaunchKernelGGL(rbe::scale_array_max, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_max);
+                e = hipGetLastError();
+            }
+            if (e == hipSuccess) e = hipMemcpyAsync(h_max, d_max, sizeof(h_max), hipMemcpyDeviceToHost, st);
+            if (e == hipSuccess) e = hipStreamSynchronize(st);
+            if (!ix->borrowed) (void)hipFree(d_max);
+            HIP_TRY(e);
+        }
+        // the largest value, rounded as scale_hints rounds it, gets the largest exponent field (7)
+        for (uint32_t j = 0; j + 1 < ix->P; ++j)
+            ix->hint_base[j] = std::max(1, (int)((h_max[j] + (1u << 17)) >> 23) - 7);
+        int* d_base = reinterpret_cast<int*>(ix->fin_scratch ? ix->fin_scratch + 128 : nullptr);
+        if (!ix->borrowed) HIP_TRY(hipMalloc(&d_base, 3 * sizeof(int)));
+        hipError_t e = hipMemcpyAsync(d_base, ix->hint_base, 3 * sizeof(int), hipMemcpyHostToDevice, st);
+        if (e == hipSuccess) {
             if (ix->W == 1) hipLaunchKernelGGL(rbe::scale_hints<1>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_base, ix->d_hints);
             else hipLaunchKernelGGL(rbe::scale_hints<2>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_base, ix->d_hints);
-            HIP_TRY(hipGetLastError());
-            HIP_TRY(hipStreamSynchronize(st));
-            (void)hipFree(d_base);
-        } else {
-            (void)hipFree(ix->d_hints); ix->d_hints = nullptr;      // the scan that reads the fp32 scales serves instead
+            e = hipGetLastError();
         }
-        (void)hipFree(d_max);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (!ix->borrowed) (void)hipFree(d_base);
+        HIP_TRY(e);
     }
     HIP_TRY(hipStreamSynchronize(st));
     ix->ready = 1;
@@ -881,17 +1039,13 @@ int rbe_load_corpus(rbe_index** out, const uint64_t* planes, const float* scales
 void rbe_free(rbe_index* ix)
 {
     if (!ix) return;
-    free_workspace(ix);
-    (void)hipFree(ix->d_tiles);
-    (void)hipFree(ix->d_row_amax);
-    (void)hipFree(ix->d_hints);
-    (void)hipFree(ix->d_count);
-    (void)hipFree(ix->d_tau);
-    (void)hipFree(ix->d_kmax);
-    (void)hipFree(ix->d_qwords);
-    (void)hipFree(ix->d_lut);
-    (void)hipFree(ix->d_aops);
-    (void)hipFree(ix->d_unscale);
+    (void)hipFree(ix->own_ws);
+    if (!ix->borrowed) {
+        (void)hipFree(ix->d_tiles);
+        (void)hipFree(ix->d_row_amax);
+        (void)hipFree(ix->d_hints);
+    }
+    (void)hipHostFree(ix->h_result);
     (void)hipHostFree(ix->h_aops);
     (void)hipHostFree(ix->h_unscale);
     (void)hipHostFree(ix->h_lut);
@@ -975,40 +1129,40 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
     rbe_index* ix = c.ix;
     if (r.end <= r.begin) return RBE_OK;
     KernelSel sel{ix->P, c.PQ, ix->mode, c.Q == 1, c.qlen};
-    const CandList out{ix->d_cand, ix->d_count, ix->d_kmax, c.cap};
+    const CandList out{ix->ws.cand, ix->ws.count, ix->ws.kmax, c.cap};
     uint32_t grid = 0;
     hipError_t e;
     if (c.float_query) {
         e = hipSuccess;
-        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0;
+        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0 && can_prune(ix);
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
         const size_t per_q = (size_t)8 * ix->W * 256;
         for (uint32_t q = 0; q < c.Q && e == hipSuccess; ++q) {   // one pass over the range per query
             FqArgs fa;
             fa.tiles = ix->d_tiles; fa.layout = ix->layout; fa.n_items = ix->n_items;
-            fa.lut = ix->d_lut + q * per_q; fa.tau_ptr = ix->d_tau + q;
-            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->d_status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints; fa.deep_units = ix->d_status + 14;
+            fa.lut = ix->ws.lut + q * per_q; fa.tau_ptr = ix->ws.tau + q;
+            fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->ws.status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints; fa.deep_units = ix->ws.status + 14;
             for (int j = 0; j < 3; ++j) fa.hint_base[j] = ix->hint_base[j];
             fa.qwords = nullptr; fa.qcoef = nullptr; fa.bmass = rbe::QueryMass{0.0f, 0.0f}; fa.resid = 0.0f;
             if (ix->fq_binary) {
-                fa.qwords = ix->d_qwords + (size_t)q * RBE_MAX_PLANES * 2 * ix->W;
-                fa.qcoef = ix->d_qcoef + (size_t)q * (RBE_MAX_PLANES + 1);
+                fa.qwords = ix->ws.qwords + (size_t)q * RBE_MAX_PLANES * 2 * ix->W;
+                fa.qcoef = ix->ws.qcoef + (size_t)q * (RBE_MAX_PLANES + 1);
                 fa.bmass = rbe::QueryMass{ix->fq_bmass[q][0], ix->fq_bmass[q][1]};
                 fa.resid = ix->fq_resid[q];
             }
-            fa.out = CandList{ix->d_cand + (size_t)q * c.cap, ix->d_count + q * rbe::kCountStride, ix->d_kmax + q * rbe::kKmaxStride, c.cap};
+            fa.out = CandList{ix->ws.cand + (size_t)q * c.cap, ix->ws.count + q * rbe::kCountStride, ix->ws.kmax + q * rbe::kKmaxStride, c.cap};
             fa.p_begin = r.begin; fa.p_end = r.end;
             e = launch_scan_exact_fq(ix->W, sel, fa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
         }
     } else if (c.batch_mfma && !(dense && !c.float_batch && ix->batch_path == 0)) {
         BatchArgs ba;
         ba.tiles = ix->d_tiles; ba.layout = ix->layout; ba.n_items = ix->n_items;
-        ba.a_ops = ix->d_aops; ba.q_unscale = ix->d_unscale; ba.q_bias = ix->d_unscale + RBE_MAX_QUERIES; ba.q_mass = ix->d_unscale + 2 * RBE_MAX_QUERIES; ba.tau = ix->d_tau;
-        ba.look_stats = level_slot >= c.look_from ? ix->d_status + 12 : nullptr;
+        ba.a_ops = ix->ws.aops; ba.q_unscale = ix->ws.unscale; ba.q_bias = ix->ws.unscale + RBE_MAX_QUERIES; ba.q_mass = ix->ws.unscale + 2 * RBE_MAX_QUERIES; ba.tau = ix->ws.tau;
+        ba.look_stats = level_slot >= c.look_from ? ix->ws.status + 12 : nullptr;
         ba.row_amax = ix->d_row_amax; ba.row_asum = ix->d_row_amax ? ix->d_row_amax + (size_t)ix->layout.n_tiles * (kTileItems / kRow) : nullptr; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
         ba.rescore = batch_rescore(ix, c.float_batch);
-        ba.PQ = c.PQ; ba.qwords = ix->d_qwords; ba.qcoef = ix->d_qcoef; ba.lut = ix->d_lut; ba.margin = ix->batch_margin;
+        ba.PQ = c.PQ; ba.qwords = ix->ws.qwords; ba.qcoef = ix->ws.qcoef; ba.lut = ix->ws.lut; ba.margin = ix->batch_margin;
         e = hipSuccess;
         const uint32_t tiles = batch_tiles(c.Q), per_launch = batch_tiles_per_launch(ix, c.float_batch);
         for (uint32_t t0 = 0; t0 < tiles && e == hipSuccess; t0 += per_launch) {   // one pass over the range per launch
@@ -1020,16 +1174,16 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
     } else if (c.mode == RBE_SELECT_EXACT) {
         ScanArgs sa;
         sa.tiles = ix->d_tiles; sa.layout = ix->layout; sa.n_items = ix->n_items;
-        sa.qwords = ix->d_qwords; sa.qcoef = ix->d_qcoef; sa.n_queries = c.Q;
-        sa.tau = ix->d_tau; sa.out = out;
+        sa.qwords = ix->ws.qwords; sa.qcoef = ix->ws.qcoef; sa.n_queries = c.Q;
+        sa.tau = ix->ws.tau; sa.out = out;
         sa.p_begin = r.begin; sa.p_end = r.end;
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
-        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0;
+        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0 && can_prune(ix);
         // (several queries: the scan that streams the scale copies is ahead up to four queries per call, 4.3 against
         // 5.2 ms for two, level with the one that streams the fp32 scales at five, behind from six on)
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2 && c.Q <= 4;
-        sa.deep_rows = ix->d_status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints; sa.deep_units = ix->d_status + 14;
-        sa.deep_pairs = level_slot >= c.look_from ? ix->d_status + 9 : nullptr;
+        sa.deep_rows = ix->ws.status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints; sa.deep_units = ix->ws.status + 14;
+        sa.deep_pairs = level_slot >= c.look_from ? ix->ws.status + 9 : nullptr;
         for (int j = 0; j < 3; ++j) sa.hint_base[j] = ix->hint_base[j];
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
@@ -1039,8 +1193,8 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         GroupArgs ga;
         ga.tiles = ix->d_tiles; ga.layout = ix->layout; ga.n_items = ix->n_items;
         ga.rows_total = (uint32_t)((ix->n_items + kRow - 1) / kRow); ga.I = c.I;
-        ga.qwords = ix->d_qwords; ga.qcoef = ix->d_qcoef; ga.q_begin = 0; ga.nq = 0;
-        ga.tau = ix->d_tau; ga.out = out;
+        ga.qwords = ix->ws.qwords; ga.qcoef = ix->ws.qcoef; ga.q_begin = 0; ga.nq = 0;
+        ga.tau = ix->ws.tau; ga.out = out;
         ga.v_begin = r.begin; ga.v_end = r.end; ga.stride = r.stride; ga.skip = r.skip;
         e = launch_scan_groupmax(ix->W, sel, ga, c.Q, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
     }
@@ -1058,9 +1212,9 @@ static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_
     if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 1], c.st));
 
     SelectArgs se;
-    se.cand = ix->d_cand; se.count = ix->d_count; se.tau = ix->d_tau; se.kmax = ix->d_kmax; se.cap = c.cap; se.k = c.k;
-    se.status = ix->d_status; se.count_seen = ix->d_seen + (size_t)level_slot * RBE_MAX_QUERIES;
-    se.final_pass = final_pass; se.ids_out = ix->d_ids; se.scores_out = ix->d_scores;
+    se.cand = ix->ws.cand; se.count = ix->ws.count; se.tau = ix->ws.tau; se.kmax = ix->ws.kmax; se.cap = c.cap; se.k = c.k;
+    se.status = ix->ws.status; se.count_seen = ix->ws.seen + (size_t)level_slot * RBE_MAX_QUERIES;
+    se.final_pass = final_pass; se.ids_out = ix->ws.ids; se.scores_out = ix->ws.scores;
     hipLaunchKernelGGL(rbe::select_topk, dim3(c.Q), dim3(kSelBlock), 0, c.st, se);
     HIP_TRY(hipGetLastError());
     if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 2], c.st));
@@ -1105,7 +1259,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     bool split = false;
     rbe_index::PruneState& ps = ix->prune[c.batch_mfma ? 1 : 0];
     if (mode == RBE_SELECT_EXACT && ps.holdoff > 0) --ps.holdoff;
-    const bool pruning = ix->progressive != 0 && ix->P >= 2 && ps.holdoff == 0;
+    const bool pruning = ix->progressive != 0 && ix->P >= 2 && ps.holdoff == 0 && can_prune(ix);
     if (mode == RBE_SELECT_EXACT) {
         for (const Level& lv : make_plan(ix->layout, c.cap, k)) plan.push_back(Round{lv.p_begin, lv.p_end, 1, 0});
         // A batch on the matrix cores: the level before the last starts from the k-th best of a 1/ratio sample of
@@ -1141,8 +1295,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         plan = make_group_plan(n_units, ix->layout.ratio, c.cap, per_unit);
     }
 
-    // this call's scores follow its ids directly, so that the results are one contiguous range
-    ix->d_scores = reinterpret_cast<float*>(ix->d_ids + (size_t)c.Q * k);
+    // this call's scores follow its ids directly, so that the results are one contiguous range (carve_workspace)
     ix->h_scores = reinterpret_cast<float*>(ix->h_ids + (size_t)c.Q * k);
 
     ix->stats = rbe_search_stats{};
@@ -1150,7 +1303,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     bool fallback = plan.empty();
 
     for (int attempt = 0; attempt < 2; ++attempt) {
-        hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, c.st, ix->d_count, ix->d_tau, ix->d_kmax, ix->d_status, c.Q);
+        hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, c.st, ix->ws.count, ix->ws.tau, ix->ws.kmax, ix->ws.status, c.Q);
         HIP_TRY(hipGetLastError());
         if (!fallback) {
             if (prof) HIP_TRY(hipEventRecord(ix->ev[0], c.st));
@@ -1180,7 +1333,7 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
             ix->stats.fallback = 1;
             ix->stats.items_scanned[0] = (uint64_t)ix->layout.n_tiles * kTileItems;
         }
-        HIP_TRY(hipMemcpyAsync(ix->h_result, ix->d_result,
+        HIP_TRY(hipMemcpyAsync(ix->h_result, ix->ws.result,
                                kResultHeaderBytes + (size_t)c.Q * k * (sizeof(int64_t) + sizeof(float)),
                                hipMemcpyDeviceToHost, c.st));
         if (prof && !fallback) HIP_TRY(hipEventRecord(ix->ev[kMaxEvents - 1], c.st));
@@ -1259,14 +1412,13 @@ static int search_prologue(rbe_index* ix, SearchCtx& c, uint32_t n_queries, uint
     c.float_query = false;
     c.batch_mfma = false;
     c.float_batch = false;
-    const uint32_t cap = ix->cap_override ? ix->cap_override : std::max<uint32_t>(65536u, 4u * ix->layout.ratio * k);
-    c.cap = std::max<uint32_t>(cap, k + 2 * kTileItems);
-    return ensure_workspace(ix, c.Q, k, c.cap);
+    c.cap = search_capacity(ix, k);
+    return acquire_workspace(ix, c.Q, k, c.cap);
 }
 
-int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
-               uint32_t q_n_planes, uint32_t k, uint32_t mode, uint32_t group_size_I,
-               int64_t* ids_out, float* scores_out, void* hip_stream)
+static int search_binary(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
+                         uint32_t q_n_planes, uint32_t k, uint32_t mode, uint32_t group_size_I,
+                         int64_t* ids_out, float* scores_out, void* hip_stream)
 {
     SearchCtx c;
     int rc = search_prologue(ix, c, n_queries, k, mode, group_size_I, ids_out, scores_out, hip_stream);
@@ -1282,6 +1434,36 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
         if (rc) return rc;
     }
     return run_search(c, ids_out, scores_out);
+}
+
+int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
+               uint32_t q_n_planes, uint32_t k, uint32_t mode, uint32_t group_size_I,
+               int64_t* ids_out, float* scores_out, void* hip_stream)
+{
+    return search_binary(ix, q_planes, q_scales, n_queries, q_n_planes, k, mode, group_size_I, ids_out, scores_out,
+                         hip_stream);
+}
+
+size_t rbe_workspace_bytes(const rbe_index* ix, uint32_t n_queries, uint32_t k, uint32_t mode)
+{
+    if (!ix || n_queries < 1 || n_queries > RBE_MAX_QUERIES || k < 1 || k > RBE_MAX_K || mode > RBE_SELECT_NEARLOSSLESS_Q2)
+        return 0;
+    return carve_workspace(nullptr, nullptr, ix->W, n_queries, k, search_capacity(ix, k));
+}
+
+int rbe_set_workspace(rbe_index* ix, void* dev_ptr, size_t bytes)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    ARG_CHECK(dev_ptr != nullptr || bytes == 0, "NULL workspace with a size");
+    ARG_CHECK(((uintptr_t)dev_ptr % kWsAlign) == 0, "the workspace must be 256-byte aligned");
+    ix->ext_ws = static_cast<char*>(dev_ptr);
+    ix->ext_ws_bytes = dev_ptr ? bytes : 0;
+    ix->ws = rbe_index::DevWs{};
+    if (dev_ptr) {          // the library's own block is not needed while the caller's is in use
+        (void)hipFree(ix->own_ws);
+        ix->own_ws = nullptr; ix->own_ws_bytes = 0;
+    }
+    return RBE_OK;
 }
 
 int rbe_search_float(rbe_index* ix, const float* q, uint32_t n_queries, uint32_t k, uint32_t mode,
@@ -1321,12 +1503,14 @@ int rbe_debug_scores_float(rbe_index* ix, const float* q, uint64_t first_item, u
     ARG_CHECK(count <= (1ull << 28), "count too large for a debug dump");
     if (count == 0) return RBE_OK;
     hipStream_t st = (hipStream_t)hip_stream;
-    int rc = stage_float_queries(ix, q, 1, st);
+    int rc = acquire_workspace(ix, 1, 1, search_capacity(ix, 1));
+    if (rc) return rc;
+    rc = stage_float_queries(ix, q, 1, st);
     if (rc) return rc;
     float* d_out = nullptr;
     HIP_TRY(hipMalloc(&d_out, (size_t)count * sizeof(float)));
     hipError_t e = launch_dense_scores_fq(ix->W, KernelSel{ix->P, 1, ix->mode, true}, ix->d_tiles, ix->layout,
-                                          ix->d_lut, first_item, count, d_out, st);
+                                          ix->ws.lut, first_item, count, d_out, st);
     if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, (size_t)count * sizeof(float), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(d_out);
@@ -1343,6 +1527,16 @@ int rbe_debug_query_mass(const uint64_t* q_planes, const float* q_scales, uint32
     if (!dyadic)
         for (uint32_t i = 0; i < q_n_planes; ++i) ARG_CHECK(std::isfinite(q_scales[i]), "q_scales[%u] is not finite", i);
     query_mass(q_planes, dyadic ? nullptr : q_scales, q_n_planes, dim, dyadic != 0, mass_out);
+    return RBE_OK;
+}
+
+int rbe_debug_index_info(const rbe_index* ix, uint32_t* out)
+{
+    ARG_CHECK(ix != nullptr && out != nullptr, "NULL argument");
+    out[0] = can_prune(ix) ? 1u : 0u;
+    out[1] = ix->d_hints ? 1u : 0u;
+    out[2] = ix->borrowed ? 1u : 0u;
+    out[3] = ix->ext_ws ? 1u : 0u;
     return RBE_OK;
 }
 
@@ -1408,14 +1602,14 @@ int rbe_debug_scores(rbe_index* ix, const uint64_t* q_planes, const float* q_sca
     ARG_CHECK(count <= (1ull << 28), "count too large for a debug dump");
     if (count == 0) return RBE_OK;
     hipStream_t st = (hipStream_t)hip_stream;
-    int rc = ensure_fixed(ix);
+    int rc = acquire_workspace(ix, 1, 1, search_capacity(ix, 1));
     if (rc) return rc;
     rc = stage_queries(ix, q_planes, q_scales, 1, q_n_planes, st);
     if (rc) return rc;
     float* d_out = nullptr;
     HIP_TRY(hipMalloc(&d_out, (size_t)count * sizeof(float)));
     hipError_t e = launch_dense_scores(ix->W, KernelSel{ix->P, q_n_planes, ix->mode, true}, ix->d_tiles, ix->layout,
-                                       ix->d_qwords, ix->d_qcoef, first_item, count, d_out, st);
+                                       ix->ws.qwords, ix->ws.qcoef, first_item, count, d_out, st);
     if (e == hipSuccess) e = hipMemcpyAsync(out, d_out, (size_t)count * sizeof(float), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(d_out);

@@ -439,20 +439,26 @@ __global__ void row_scale_max(const char* __restrict__ tiles, const TileGeom g, 
     }
 }
 
-// Largest value of each scale array over the whole corpus, as fp32 bit patterns: out[j], zero-initialised by the
-// caller.  A negative or non-finite scale anywhere makes out[j] >= 0x7f800000 (patterns compare as unsigned).
+// What each scale array holds, over the whole corpus: out[j] = largest magnitude as an fp32 bit pattern (sign bit
+// cleared; >= 0x7f800000 means that the array holds an infinity or a NaN), out[4 + j] = 1 if any value is below
+// zero.  out[0..7] zero-initialised by the caller.
 __global__ void scale_array_max(const char* __restrict__ tiles, const TileGeom g, uint32_t* __restrict__ out)
 {
     const float* sc = reinterpret_cast<const float*>(tiles + (size_t)blockIdx.x * g.tile_bytes() + g.scales_offset());
     for (uint32_t j = 0; j < g.S; ++j) {
-        uint32_t mx = 0;
+        uint32_t mx = 0, neg = 0;
         for (uint32_t i = threadIdx.x; i < kTileItems; i += blockDim.x) {
             const uint32_t b = __float_as_uint(sc[(size_t)j * kTileItems + i]);
-            mx = b > mx ? b : mx;
+            const uint32_t mag = b & 0x7fffffffu;
+            mx = mag > mx ? mag : mx;
+            neg |= (b >> 31) & (mag != 0u ? 1u : 0u);
         }
-        for (int d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(mx, d); mx = o > mx ? o : mx; }
+        for (int d = 32; d > 0; d >>= 1) { const uint32_t o = __shfl_xor(mx, d); mx = o > mx ? o : mx; neg |= __shfl_xor(neg, d); }
         // (most waves find the maximum already there: a plain look first keeps the atomics few)
-        if ((threadIdx.x & 63) == 0 && mx > *reinterpret_cast<const volatile uint32_t*>(&out[j])) atomicMax(&out[j], mx);
+        if ((threadIdx.x & 63) == 0) {
+            if (mx > *reinterpret_cast<const volatile uint32_t*>(&out[j])) atomicMax(&out[j], mx);
+            if (neg && *reinterpret_cast<const volatile uint32_t*>(&out[4 + j]) == 0u) atomicOr(&out[4 + j], 1u);
+        }
     }
 }
 

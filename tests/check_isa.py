@@ -1,4 +1,4 @@
-"""Developer check: the scan kernels must keep whole waves inside their wave-wide steps.
+"""Compiled-code check (test infrastructure): the scan kernels must keep whole waves inside their wave-wide steps.
 
 The survivor queues of the scan kernels use wave-wide operations (ballots, lane broadcasts,
 "lane 0 reserves, everybody copies") inside loops.  They are written so that every loop
@@ -12,7 +12,7 @@ such a lane-peeling loop.  Kernels whose loops are per-lane by design (the dense
 the table load at the start of the hybrid scan) are expected and named below; anything else
 is reported and makes the script exit with status 1.
 
-    python -m paper_1802_06466_amd._check_isa        # takes a few minutes
+    python tests/check_isa.py        # takes a few minutes; tests/test_binding_cpu.py runs it
 """
 from __future__ import annotations
 
@@ -22,7 +22,11 @@ import subprocess
 import sys
 import tempfile
 
-from . import _build
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_1802_06466_amd import _build  # noqa: E402
 
 # kernel name prefixes whose lane-peeling loops are intended, with the number allowed per kernel
 EXPECTED = {"dense_scores": 1, "dense_scores_fq": 1, "scan_exact_fq": 1, "scan_exact_fq_prog": 1, "scan_exact_fq_prog_hint": 1}

@@ -22,17 +22,25 @@ def lib():
     return rbe.load_library()
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "rbe.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(rbe_[a-z_0-9]+)\s*\(", text)))
+HEADERS = ("rbe.h", "rbe_debug.h")
+
+
+def declared_functions(headers=HEADERS):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(rbe_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
-    assert {"rbe_load_corpus", "rbe_encode_query", "rbe_search"} <= set(names)
+    assert {"rbe_load_corpus", "rbe_encode_query", "rbe_search", "rbe_workspace_bytes", "rbe_set_workspace",
+            "rbe_index_create_in"} <= set(declared_functions(("rbe.h",)))
+    assert not [n for n in declared_functions(("rbe.h",)) if n.startswith("rbe_debug_")], "test hooks belong in rbe_debug.h"
     for n in names:
-        assert hasattr(lib, n), f"{n} declared in rbe.h but not exported"
+        assert hasattr(lib, n), f"{n} declared in a header but not exported"
     assert set(names) == set(rbe.PROTOTYPES), "binding prototypes and header disagree"
 
 
@@ -44,9 +52,10 @@ def test_binding_has_same_names():
 
 
 def test_no_torch_types_in_header():
-    text = open(os.path.join(ROOT, "include", "rbe.h")).read()
-    assert "torch" not in re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    assert "at::" not in text and "#include <hip" not in text
+    for h in HEADERS:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        assert "torch" not in re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        assert "at::" not in text and "#include <hip" not in text
 
 
 def test_constants_match_header():
@@ -54,7 +63,7 @@ def test_constants_match_header():
     for name in ("RBE_MAX_PLANES", "RBE_MAX_QUERIES", "RBE_MAX_K", "RBE_MAX_ITEMS", "RBE_MAX_LEVELS"):
         m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
         assert m and int(m.group(1)) == getattr(rbe, name), name
-    for name in ("RBE_COSINE", "RBE_DYADIC"):
+    for name in ("RBE_BORROW", "RBE_COSINE", "RBE_DYADIC"):
         m = re.search(r"%s\s*=\s*1u\s*<<\s*(\d+)" % name, text)
         assert m and (1 << int(m.group(1))) == getattr(rbe, name), name
     assert ctypes.sizeof(rbe.rbe_search_stats) == 16 + 8 * 8 * 2 + 4 * 8 * 2 + 8
@@ -70,6 +79,37 @@ def test_argument_validation_needs_no_gpu(lib):
     assert lib.rbe_strerror(rbe.RBE_EINVAL) == b"invalid argument"
     assert lib.rbe_strerror(0) == b"ok"
     lib.rbe_free(None)
+
+
+def test_caller_owned_memory_entry_points_validate_without_a_gpu(lib):
+    """rbe_index_bytes is a pure host function; the other calls reject bad arguments before any GPU work."""
+    def expect(N, d, P, flags):
+        tiles = -(-N // 1024)
+        W = d // 64
+        dyadic, cosine = bool(flags & rbe.RBE_DYADIC), bool(flags & rbe.RBE_COSINE)
+        S = (1 if cosine else 0) if dyadic else P
+        up = lambda b: -(-b // 256) * 256
+        total = up(tiles * 1024 * (8 * W * P + 4 * S))
+        total += up(2 * tiles * 4 * 4 if S else 0)                      # two floats per row of 256 items
+        nw = 0 if (dyadic or P < 2) else (4 if P - 1 == 3 else P - 1)   # one-byte scale copies, a word per 4 items and array
+        total += up(tiles * 256 * nw * 4)
+        return total + 256
+    for N, d, P, flags in [(1, 64, 1, 0), (1_000_000_000, 64, 3, 0), (100_000_000, 128, 4, 0), (1025, 256, 2, 0),
+                           (1_212_153_856, 64, 2, rbe.RBE_DYADIC | rbe.RBE_COSINE), (5000, 128, 3, rbe.RBE_DYADIC),
+                           (5000, 64, 3, rbe.RBE_COSINE | rbe.RBE_BORROW)]:
+        assert rbe.rbe_index_bytes(N, d, P, flags) == expect(N, d, P, flags), (N, d, P, flags)
+    assert rbe.rbe_index_bytes(0, 64, 3) == 0 and rbe.rbe_index_bytes(10, 65, 3) == 0 and rbe.rbe_index_bytes(10, 64, 5) == 0
+    assert rbe.rbe_index_bytes(10, 256, 2, rbe.RBE_DYADIC) == 0
+    assert rbe.rbe_index_bytes(10, 64, 3, 0, 1) == 0 and rbe.rbe_index_bytes(10, 64, 3, 0, 8) == rbe.rbe_index_bytes(10, 64, 3)
+    out = ctypes.c_void_p(None)
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.rbe_index_create_in(ctypes.byref(out), 10, 64, 3, 0, 0, fake, 1 << 20) == rbe.RBE_EINVAL      # RBE_BORROW missing
+    assert lib.rbe_index_create_in(ctypes.byref(out), 10, 64, 3, rbe.RBE_BORROW, 0, None, 1 << 20) == rbe.RBE_EINVAL
+    assert lib.rbe_index_create_in(ctypes.byref(out), 10, 65, 3, rbe.RBE_BORROW, 0, fake, 1 << 20) == rbe.RBE_EINVAL
+    assert out.value is None
+    assert lib.rbe_workspace_bytes(None, 1, 10, 0) == 0
+    assert lib.rbe_set_workspace(None, None, 0) == rbe.RBE_EINVAL
+    assert lib.rbe_debug_index_info(None, None) == rbe.RBE_EINVAL
 
 
 @pytest.mark.parametrize("d,P", [(64, 1), (64, 3), (128, 4), (256, 2)])
@@ -257,8 +297,8 @@ def test_scan_kernels_have_no_lane_peeling_loops():
     wave-wide survivor staging contains a loop that removes lanes from the execution mask: such a
     loop once made the two halves of a wave run their ballots and flushes separately and lose
     entries.  Kernels whose per-lane loops are intended are listed in the checker."""
-    from paper_1802_06466_amd import _check_isa
-    assert _check_isa.main() == 0
+    import check_isa
+    assert check_isa.main() == 0
 
 
 @pytest.mark.parametrize("kind", ["binary", "fp32", "fp32_wide_range"])
@@ -326,6 +366,43 @@ def test_query_mass_bounds_every_plane(lib, dim, Pq):
         planes = np.concatenate([best, rng.integers(0, 2**64, size=(1, 200, W), dtype=np.uint64)], axis=1)
         s = oracle.scores(planes, np.ones((1, 201), dtype=np.float32), qp, qs)
         assert abs(s[0] - M) <= 1e-9 * B and np.all(np.abs(s) <= M + 1e-9 * B)
+
+
+def test_last_plane_bound_holds_for_scales_at_least_zero_and_fails_below(lib):
+    """Host-side evaluation of the pruning scans' bound, written out in float64:
+        bound(z) = sum_{j < P-1} a_j[z] t_j(z) + max(0, largest last scale of the row) * M,
+    t_j = sum_i c_i (b_q^i . b_z^j), M = the library's query mass.  For scales >= 0 it is never below the
+    oracle's score.  With a negative last scale it can be: the last plane then adds up to |a| M while the
+    bound allows for nothing.  That is why an index holding a negative scale gets no pruning scan
+    (rbe_finalize marks it; the GPU tests check that the plain scans find such items)."""
+    rng = np.random.default_rng(91)
+    d, P, Pq, N = 64, 3, 3, 2000
+    planes = rng.integers(0, 2**64, size=(P, N, 1), dtype=np.uint64)
+    scales = rng.uniform(0.0, 1.0, size=(P, N)).astype(np.float32)
+    qp = rng.integers(0, 2**64, size=(Pq, 1), dtype=np.uint64)
+    qs = rng.uniform(0.05, 1.0, size=Pq).astype(np.float32)
+    M, _ = rbe.rbe_debug_query_mass(qp, qs, d)
+
+    def bound(planes, scales):
+        part = oracle.scores(planes[:P - 1], scales[:P - 1], qp, qs)           # planes 0 .. P-2, exactly
+        return part + max(0.0, float(scales[P - 1].max())) * M                  # one row: the whole corpus here
+
+    true = oracle.scores(planes, scales, qp, qs)
+    assert np.all(bound(planes, scales) >= true)
+    # item 0: last plane = complement of the sign pattern of qhat, last scale -0.9 -> contributes +0.9 M
+    qbits = ((qp[:, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64).reshape(Pq, d)
+    qhat = (qs.astype(np.float64)[:, None] * (2 * qbits - 1)).sum(axis=0)
+    word = np.uint64(0)
+    for i in range(d):
+        if qhat[i] <= 0:
+            word |= np.uint64(1) << np.uint64(i)
+    planes[P - 1, 0, 0] = word
+    scales[:, 0] = 0.0
+    scales[P - 1, 0] = -0.9
+    scales[P - 1, 1:] = np.minimum(scales[P - 1, 1:], np.float32(0.1))          # the row's largest last scale is small
+    true = oracle.scores(planes, scales, qp, qs)
+    assert true[0] == pytest.approx(0.9 * np.abs(qhat).sum(), rel=1e-6)
+    assert bound(planes, scales)[0] < true[0] - 0.5 * M, "the bound no longer covers the last plane"
 
 
 @pytest.mark.parametrize("dim,Pq", [(64, 1), (64, 3), (128, 4)])

@@ -1165,7 +1165,8 @@ def test_progressive_scan_with_extreme_scales():
 def test_progressive_scan_with_scales_below_the_range_of_their_copies():
     """Clustered corpus whose scale arrays span twelve binades (half of the items scaled by 2^-9, below the smallest
     one-byte code of their array, a quarter by 2^-3): ids and scores equal the plain scan's, and the bound still
-    prunes.  With a negative scale in the corpus no copies are made and the scan that reads the fp32 scales serves."""
+    prunes.  With a negative scale in the corpus the index stands every pruning scan down (their bounds assume
+    scales >= 0) and the plain scan serves."""
     N, d, P, k = 300_007, 64, 3, 12      # about 145 full-scale items per cluster: the sample's threshold (8 k) lies inside
     planes, scales, qp, qs = clustered(N, d, P, 1024, 0.3, 4, 3, seed=175)
     rng = np.random.default_rng(176)
@@ -1176,12 +1177,17 @@ def test_progressive_scan_with_scales_below_the_range_of_their_copies():
         if negative:
             scales[0, rng.choice(N, 2000, replace=False)] *= np.float32(-1.0)
         ix = load_with_ratio(planes, scales, 8)
+        info = rbe.rbe_debug_index_info(ix)
+        assert info["can_prune"] == (not negative) and info["scale_copies"] == (not negative)
         on, off, shares = _search_both_ways(ix, qp, qs, k)
         for (i1, s1), (i0, s0) in zip(on, off):
             np.testing.assert_array_equal(i1, i0); np.testing.assert_array_equal(s1, s0)
         for q in range(4):
             check_topk(planes, scales, qp[q], qs[q], k, on[q][0][0], on[q][1][0])
-        assert 0 < np.mean(shares) < 0.5, shares
+        if negative:
+            assert np.all(np.array(shares) == 0), shares
+        else:
+            assert 0 < np.mean(shares) < 0.5, shares
         rbe.rbe_free(ix)
 
 
@@ -1260,3 +1266,172 @@ def test_pruning_scans_stand_down_on_a_corpus_they_cannot_prune():
     for s_ in seen[1:]:
         np.testing.assert_array_equal(s_[2][0], seen[0][2][0]); np.testing.assert_array_equal(s_[2][1], seen[0][2][1])
     rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ negative scales: no pruning path may run
+@pytest.mark.parametrize("d,P", [(64, 3), (128, 4), (64, 1)])
+def test_negative_scales_in_the_last_array_are_searched_exactly(d, P):
+    """The pruning scans bound the last plane's contribution by (largest last scale) x (query mass), and the
+    matrix-core filter's slack is margin x (sum of scales): both under-estimate when a scale is negative.  Items
+    whose LAST scale is negative and large in magnitude, planted next to the queries, must still be found: one
+    query, a small batch, a batch that would go to the matrix cores, and fp32 queries."""
+    N, k = 200_003, 25
+    planes, scales, qp, qs = clustered(N, d, P, 512, 0.3, 16, P, seed=300 + d + P)
+    rng = np.random.default_rng(301 + P)
+    # planted items: every plane the complement of query q's base plane, last scale strongly negative, so the last
+    # plane's true contribution is large and positive while any bound that takes max(a, 0) sees none of it
+    for q in range(16):
+        for z in rng.choice(N, 3, replace=False):
+            for j in range(P):
+                planes[j, z] = ~qp[q, 0]
+            scales[:, z] = 0.0
+            scales[P - 1, z] = -3.0
+    scales[P - 1, rng.choice(N, N // 50, replace=False)] *= np.float32(-1.0)
+    ix = load_with_ratio(planes, scales, 8)
+    info = rbe.rbe_debug_index_info(ix)
+    assert not info["can_prune"] and not info["scale_copies"]
+    ids1, sc1 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    assert rbe.rbe_get_search_stats(ix)["n_levels"] >= 2 and rbe.rbe_get_search_stats(ix)["deep_rows"] == 0
+    ids3, sc3 = rbe.rbe_search(ix, qp[1:4], qs[1:4], k)
+    ids12, sc12 = rbe.rbe_search(ix, qp[4:], qs[4:], k)
+    ids = np.concatenate([ids1, ids3, ids12]); sc = np.concatenate([sc1, sc3, sc12])
+    check_batch(planes, scales, qp, qs, k, ids, sc)
+    for q in range(16):                      # the planted items lead every list
+        assert sc[q][0] > 0 and scales[P - 1, ids[q][0]] == np.float32(-3.0)
+    # forcing the matrix-core path cannot bring its filter back either
+    rbe.rbe_debug_set_batch_path(ix, 2)
+    ids12b, sc12b = rbe.rbe_search(ix, qp[4:], qs[4:], k)
+    np.testing.assert_array_equal(ids12b, ids12); np.testing.assert_array_equal(sc12b, sc12)
+    rbe.rbe_debug_set_batch_path(ix, 0)
+    # fp32 queries (one scan per query, and the would-be matrix-core batch)
+    qf = rbe_synth.vectors_numpy(5, rbe_synth.centres_numpy(512, d), 0.3, seed=rbe_synth.SEED_QUERIES + 300 + d + P)
+    for lo, hi in ((0, 1), (1, 5)):
+        fi, fs = rbe.rbe_search_float(ix, qf[lo:hi], k)
+        for q in range(lo, hi):
+            o_ids, o_sc = oracle.topk_fq(planes, scales, qf[q], k)
+            eps = 1e-5 * abs(o_sc[-1]) + 1e-6
+            got = oracle.scores_at_fq(planes, scales, qf[q], fi[q - lo])
+            np.testing.assert_allclose(fs[q - lo], got, rtol=1e-5, atol=1e-6)
+            assert np.all(got >= o_sc[-1] - eps)
+            assert set(o_ids[o_sc > o_sc[-1] + eps].tolist()) <= set(fi[q - lo].tolist())
+    rbe.rbe_free(ix)
+
+
+def test_non_finite_scale_is_rejected_at_finalize_and_can_be_repaired():
+    rng = np.random.default_rng(311)
+    planes, scales = random_corpus(rng, 5000, 64, 3)
+    bad = scales.copy()
+    bad[1, 4321] = np.inf
+    ix = rbe.rbe_index_create(5000, 64, 3)
+    rbe.rbe_load_chunk(ix, 0, planes, bad)
+    with pytest.raises(rbe.RbeError) as e:
+        rbe.rbe_finalize(ix)
+    assert e.value.code == rbe.RBE_EINVAL and "not finite" in str(e.value)
+    bad[2, 17] = np.nan; bad[1, 4321] = 1.0
+    rbe.rbe_load_chunk(ix, 0, planes, bad)
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_finalize(ix)
+    rbe.rbe_load_chunk(ix, 0, planes, scales)          # still loading: the chunk can be replaced
+    rbe.rbe_finalize(ix)
+    qp, qs = random_queries(rng, 1, 64, 3)
+    ids, sc = rbe.rbe_search(ix, qp, qs, 10)
+    check_topk(planes, scales, qp[0], qs[0], 10, ids[0], sc[0])
+    rbe.rbe_free(ix)
+
+
+# ------------------------------------------------------------------ caller-owned memory
+def test_search_with_caller_supplied_workspace_matches_the_oracle():
+    """All device scratch of a search in a torch tensor (rbe_workspace_bytes / rbe_set_workspace): one query, a
+    batch on the matrix cores, fp32 queries and the near-lossless mode give the results of library-owned scratch and
+    pass the oracle; a workspace that is too small is refused with the required size, and nothing is overwritten
+    outside the tensor."""
+    import torch
+    N, d, P, k = 150_001, 64, 3, 100
+    planes, scales, qp, qs = clustered(N, d, P, 256, 0.3, 9, P, seed=320)
+    ix = load_with_ratio(planes, scales, 8)
+    ref1 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    ref9 = rbe.rbe_search(ix, qp, qs, k)
+    refn = rbe.rbe_search(ix, qp[:2], qs[:2], k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=16)
+    qf = rbe_synth.vectors_numpy(3, rbe_synth.centres_numpy(256, d), 0.3, seed=rbe_synth.SEED_QUERIES + 321)
+    reff = rbe.rbe_search_float(ix, qf, k)
+    need1 = rbe.rbe_workspace_bytes(ix, 1, k)
+    need9 = rbe.rbe_workspace_bytes(ix, 9, k)
+    assert 0 < need1 < need9 and need9 % 256 == 0
+    assert rbe.rbe_workspace_bytes(ix, 9, k, rbe.RBE_SELECT_NEARLOSSLESS) == need9
+    assert rbe.rbe_workspace_bytes(ix, 0, k) == 0 and rbe.rbe_workspace_bytes(ix, 65, k) == 0 and rbe.rbe_workspace_bytes(ix, 1, 4097) == 0
+    guard = 4096
+    buf = torch.full((guard + need9 + guard,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    assert buf.data_ptr() % 256 == 0
+    ws = buf[guard:guard + need9]
+    rbe.rbe_set_workspace(ix, ws)
+    assert rbe.rbe_debug_index_info(ix)["caller_workspace"]
+    for _ in range(2):                                   # a second round reuses the same block
+        got1 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+        got9 = rbe.rbe_search(ix, qp, qs, k)
+        gotn = rbe.rbe_search(ix, qp[:2], qs[:2], k, mode=rbe.RBE_SELECT_NEARLOSSLESS, group_size_I=16)
+        gotf = rbe.rbe_search_float(ix, qf, k)
+        for got, ref in ((got1, ref1), (got9, ref9), (gotn, refn), (gotf, reff)):
+            np.testing.assert_array_equal(got[0], ref[0]); np.testing.assert_array_equal(got[1], ref[1])
+    check_batch(planes, scales, qp, qs, k, got9[0], got9[1])
+    for q in range(2):
+        check_nearlossless(planes, scales, qp[q], qs[q], k, 16, gotn[0][q], gotn[1][q])
+    torch.cuda.synchronize()
+    assert bool((buf[:guard] == 0xA5).all()) and bool((buf[guard + need9:] == 0xA5).all()), "wrote outside the workspace"
+    # too small for nine queries, large enough for one
+    rbe.rbe_set_workspace(ix, buf[guard:guard + need1])
+    with pytest.raises(rbe.RbeError) as e:
+        rbe.rbe_search(ix, qp, qs, k)
+    assert e.value.code == rbe.RBE_EINVAL and str(need9) in str(e.value)
+    got1 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    np.testing.assert_array_equal(got1[0], ref1[0])
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_set_workspace(ix, buf[guard + 8:guard + need1])      # not 256-byte aligned
+    rbe.rbe_set_workspace(ix, None)                      # back to library-owned scratch
+    assert not rbe.rbe_debug_index_info(ix)["caller_workspace"]
+    got9 = rbe.rbe_search(ix, qp, qs, k)
+    np.testing.assert_array_equal(got9[0], ref9[0])
+    rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("flags", [0, "dyadic_cosine"])
+def test_index_in_caller_owned_storage(flags):
+    """RBE_BORROW: tiles and side arrays inside a torch tensor of rbe_index_bytes() bytes; same results as an index
+    the library allocates, pruning scans included; nothing written outside the tensor; the tensor survives rbe_free."""
+    import torch
+    N, d, P, k = 120_007, 64, 3, 20       # k * 500 below the items read before the last level: it runs the pruning scan
+    planes, scales, qp, qs = clustered(N, d, P, 256, 0.3, 8, P, seed=330)
+    fl = (rbe.RBE_DYADIC | rbe.RBE_COSINE) if flags else 0
+    if fl:
+        scales_in, qs_in = None, None
+    else:
+        scales_in, qs_in = scales, qs
+    own = rbe.rbe_index_create_ex(N, d, P, fl, 8)
+    rbe.rbe_load_chunk(own, 0, planes, scales_in)
+    rbe.rbe_finalize(own)
+    ref1 = rbe.rbe_search(own, qp[:1], qs_in[:1] if qs_in is not None else None, k)
+    ref8 = rbe.rbe_search(own, qp, qs_in, k)
+    assert rbe.rbe_get_search_stats(own)["n_levels"] >= 2
+    rbe.rbe_free(own)
+    need = rbe.rbe_index_bytes(N, d, P, fl | rbe.RBE_BORROW, 8)
+    guard = 4096
+    buf = torch.full((guard + need + guard,), 0x5A, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_index_create_in(N, d, P, fl | rbe.RBE_BORROW, 8, buf[guard:guard + need - 256])     # too small
+    ix = rbe.rbe_index_create_in(N, d, P, fl | rbe.RBE_BORROW, 8, buf[guard:guard + need])
+    dev_planes = torch.from_numpy(planes.view(np.int64)).cuda()
+    dev_scales = None if scales_in is None else torch.from_numpy(scales).cuda()
+    rbe.rbe_load_chunk(ix, 0, dev_planes, dev_scales)
+    rbe.rbe_finalize(ix)
+    info = rbe.rbe_debug_index_info(ix)
+    assert info["borrowed"] and info["can_prune"] and info["scale_copies"] == (fl == 0)
+    got1 = rbe.rbe_search(ix, qp[:1], qs_in[:1] if qs_in is not None else None, k)
+    assert rbe.rbe_get_search_stats(ix)["deep_rows"] > 0          # the progressive last level ran on the lent side arrays
+    got8 = rbe.rbe_search(ix, qp, qs_in, k)
+    for got, ref in ((got1, ref1), (got8, ref8)):
+        np.testing.assert_array_equal(got[0], ref[0]); np.testing.assert_array_equal(got[1], ref[1])
+    if not fl:
+        check_batch(planes, scales, qp, qs, k, got8[0], got8[1])
+    rbe.rbe_free(ix)
+    torch.cuda.synchronize()
+    assert bool((buf[:guard] == 0x5A).all()) and bool((buf[guard + need:] == 0x5A).all()), "wrote outside the storage"
+    assert int(buf[guard:guard + need].to(torch.int64).sum()) != 0x5A * need       # still readable, and was written
