@@ -255,6 +255,23 @@ int rbe_search(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
 size_t rbe_workspace_bytes(const rbe_index *ix, uint32_t n_queries, uint32_t k, uint32_t mode);
 int rbe_set_workspace(rbe_index *ix, void *dev_ptr, size_t bytes);
 
+/* rbe_search for callers that cannot allocate device memory at all -- code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc: same
+ * arguments, same results, but the device scratch is a fixed array inside the
+ * library (RBE_STATIC_SCRATCH_BYTES per GPU, held until the process ends) and the
+ * call makes no allocation of any kind on the device or in pinned host memory.
+ * Limit: rbe_workspace_bytes(ix, n_queries, k, mode) <= RBE_STATIC_SCRATCH_BYTES
+ * (e.g. 4 queries for k = 1000, or 1 query for k = 4096, at the default tuning),
+ * else RBE_EINVAL.  The device that owns the index must be current.  All calls on
+ * one GPU share the array: calls that overlap in time on one GPU -- from several
+ * threads, or for several indexes -- race; serialise them.  What a call needs
+ * cleared it clears itself.                                                     */
+#define RBE_STATIC_SCRATCH_BYTES 16777216u
+int rbe_search_static(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
+                      uint32_t n_queries, uint32_t q_n_planes, uint32_t k,
+                      uint32_t mode, uint32_t group_size_I,
+                      int64_t *ids_out, float *scores_out, void *hip_stream);
+
 /* Hybrid scoring: full-precision queries against the binary items (the paper's
  * "hybrid rbe" model, Sec. 8.1, which bounds the accuracy of every RBE model with
  * the same keyword bits):

@@ -26,6 +26,7 @@ RBE_DYADIC = 1 << 2
 RBE_SELECT_EXACT, RBE_SELECT_NEARLOSSLESS, RBE_SELECT_NEARLOSSLESS_Q2 = 0, 1, 2
 RBE_MAX_PLANES, RBE_MAX_QUERIES, RBE_MAX_K, RBE_MAX_LEVELS = 4, 64, 4096, 8
 RBE_MAX_ITEMS = 4294966272
+RBE_STATIC_SCRATCH_BYTES = 16777216
 
 LIB_PATH = os.environ.get("RBE_HIP_LIB", _build.LIB)   # override: experiments with alternative builds
 
@@ -69,6 +70,7 @@ PROTOTYPES = {
     "rbe_free": (None, [_vp]),
     "rbe_encode_query": (_i32, [_vp, _u32, _u32, _vp, _vp]),
     "rbe_search": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
+    "rbe_search_static": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_workspace_bytes": (ctypes.c_size_t, [_vp, _u32, _u32, _u32]),
     "rbe_set_workspace": (_i32, [_vp, _vp, ctypes.c_size_t]),
     "rbe_debug_index_info": (_i32, [_vp, _vp]),
@@ -334,8 +336,14 @@ def rbe_encode_query(x, n_planes: int):
     return planes, scales
 
 
+def rbe_search_static(ix: Index, q_planes, q_scales, k: int, mode: int = RBE_SELECT_EXACT, group_size_I: int = 0,
+                      stream=None):
+    """rbe_search on the library's fixed scratch array (no device allocation in the call)."""
+    return rbe_search(ix, q_planes, q_scales, k, mode, group_size_I, stream, _entry="rbe_search_static")
+
+
 def rbe_search(ix: Index, q_planes, q_scales, k: int, mode: int = RBE_SELECT_EXACT, group_size_I: int = 0,
-               stream=None):
+               stream=None, _entry: str = "rbe_search"):
     """q_planes [Q][Pq][W] uint64, q_scales [Q][Pq] float32 -> (ids int64 [Q][k], scores float32 [Q][k])."""
     qp, qpp = _host(q_planes, np.uint64)
     if qp.ndim != 3 or qp.shape[2] != ix.dim // 64:
@@ -348,8 +356,8 @@ def rbe_search(ix: Index, q_planes, q_scales, k: int, mode: int = RBE_SELECT_EXA
             raise RbeError(RBE_EINVAL, f"expected q_scales {(Q, Pq)}, got {qs.shape}")
     ids = np.empty((Q, max(k, 0)), dtype=np.int64)
     scores = np.empty((Q, max(k, 0)), dtype=np.float32)
-    _check(load_library().rbe_search(ix.handle, qpp, qsp, Q, Pq, k, mode, group_size_I,
-                                     ids.ctypes.data_as(_vp), scores.ctypes.data_as(_vp), _stream_ptr(stream)))
+    _check(getattr(load_library(), _entry)(ix.handle, qpp, qsp, Q, Pq, k, mode, group_size_I,
+                                           ids.ctypes.data_as(_vp), scores.ctypes.data_as(_vp), _stream_ptr(stream)))
     return ids, scores
 
 

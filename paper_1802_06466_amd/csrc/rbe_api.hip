@@ -13,6 +13,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -55,6 +56,10 @@ constexpr size_t kResultHeaderBytes = kResultStatusBytes + (size_t)RBE_MAX_LEVEL
 
 }  // namespace
 
+// Scratch of rbe_search_static: one copy per GPU, held until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; the device address it yields (per device) is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[RBE_STATIC_SCRATCH_BYTES];
+
 struct rbe_index {
     uint64_t n_items = 0;
     uint32_t dim = 0, W = 0, P = 0, flags = 0;
@@ -91,7 +96,7 @@ struct rbe_index {
         uint32_t* aops = nullptr;       // matrix-core query operands (BatchArgs::a_ops)
         float* lut = nullptr;           // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
     };
-    DevWs ws;                       // the scratch the current search uses: carved from one of the two blocks below
+    DevWs ws;                       // the scratch the current search uses: carved from one of the three blocks below
     char* own_ws = nullptr;         // grown on demand by the library (hipMalloc) ...
     size_t own_ws_bytes = 0;
     char* ext_ws = nullptr;         // ... or lent by the caller (rbe_set_workspace): never grown, never freed here
@@ -200,7 +205,7 @@ hipError_t launch_dense_scores(uint32_t W, const KernelSel& k, const char* tiles
 // All device scratch of one search lives in one block, laid out for the call's n_queries, k and candidate
 // capacity: fixed-size state first, the large candidate lists last, every part 256-byte aligned.  With
 // base == nullptr only the size is computed.  The block is the library's own (grown on demand), the caller's
-// (rbe_set_workspace).
+// (rbe_set_workspace) or the static array of rbe_search_static.
 constexpr size_t kWsAlign = 256;
 constexpr size_t kQueryWordsBytes = (size_t)RBE_MAX_QUERIES * RBE_MAX_PLANES * 8 * sizeof(uint32_t);
 constexpr size_t kQueryCoefBytes = (size_t)RBE_MAX_QUERIES * (RBE_MAX_PLANES + 1 + 2) * sizeof(float);
@@ -265,6 +270,42 @@ int acquire_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
         ix->own_ws_bytes = need;
     }
     carve_workspace(&ix->ws, ix->own_ws, ix->W, Q, k, cap);
+    return RBE_OK;
+}
+
+// Points ix->ws into this GPU's copy of the static scratch array.  Allocates nothing: the address of the array is
+// looked up once per device (with that device current) and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[kMaxDevices] = {};
+
+int acquire_static_scratch(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != ix->device) {
+        set_error("the index lives on device %d but device %d is current", ix->device, dev);
+        return RBE_EINVAL;
+    }
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device %d: no static scratch slot", dev); return RBE_EUNSUPPORTED; }
+    const size_t need = carve_workspace(nullptr, nullptr, ix->W, Q, k, cap);
+    if (need > (size_t)RBE_STATIC_SCRATCH_BYTES) {
+        set_error("rbe_search_static: %u queries with k = %u need %zu bytes of scratch, the static array holds %zu "
+                  "(fewer queries per call, a smaller k, or a smaller cand_capacity via rbe_set_tuning)",
+                  Q, k, need, (size_t)RBE_STATIC_SCRATCH_BYTES);
+        return RBE_EINVAL;
+    }
+    char* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            g_scratch_ptr[dev] = static_cast<char*>(p);
+        }
+        base = g_scratch_ptr[dev];
+    }
+    carve_workspace(&ix->ws, base, ix->W, Q, k, cap);
     return RBE_OK;
 }
 
@@ -1395,7 +1436,8 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
 }
 
 static int search_prologue(rbe_index* ix, SearchCtx& c, uint32_t n_queries, uint32_t k, uint32_t mode,
-                           uint32_t group_size_I, const void* ids_out, const void* scores_out, void* hip_stream)
+                           uint32_t group_size_I, const void* ids_out, const void* scores_out, void* hip_stream,
+                           bool static_scratch = false)
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
     if (!ix->ready) { set_error("search before rbe_finalize"); return RBE_ESTATE; }
@@ -1413,15 +1455,15 @@ static int search_prologue(rbe_index* ix, SearchCtx& c, uint32_t n_queries, uint
     c.batch_mfma = false;
     c.float_batch = false;
     c.cap = search_capacity(ix, k);
-    return acquire_workspace(ix, c.Q, k, c.cap);
+    return static_scratch ? acquire_static_scratch(ix, c.Q, k, c.cap) : acquire_workspace(ix, c.Q, k, c.cap);
 }
 
 static int search_binary(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
                          uint32_t q_n_planes, uint32_t k, uint32_t mode, uint32_t group_size_I,
-                         int64_t* ids_out, float* scores_out, void* hip_stream)
+                         int64_t* ids_out, float* scores_out, void* hip_stream, bool static_scratch)
 {
     SearchCtx c;
-    int rc = search_prologue(ix, c, n_queries, k, mode, group_size_I, ids_out, scores_out, hip_stream);
+    int rc = search_prologue(ix, c, n_queries, k, mode, group_size_I, ids_out, scores_out, hip_stream, static_scratch);
     if (rc) return rc;
     ARG_CHECK(q_planes != nullptr, "q_planes is NULL");
     ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u (got %u)", RBE_MAX_PLANES, q_n_planes);
@@ -1441,7 +1483,15 @@ int rbe_search(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, u
                int64_t* ids_out, float* scores_out, void* hip_stream)
 {
     return search_binary(ix, q_planes, q_scales, n_queries, q_n_planes, k, mode, group_size_I, ids_out, scores_out,
-                         hip_stream);
+                         hip_stream, false);
+}
+
+int rbe_search_static(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
+                      uint32_t q_n_planes, uint32_t k, uint32_t mode, uint32_t group_size_I,
+                      int64_t* ids_out, float* scores_out, void* hip_stream)
+{
+    return search_binary(ix, q_planes, q_scales, n_queries, q_n_planes, k, mode, group_size_I, ids_out, scores_out,
+                         hip_stream, true);
 }
 
 size_t rbe_workspace_bytes(const rbe_index* ix, uint32_t n_queries, uint32_t k, uint32_t mode)

@@ -37,7 +37,7 @@ def declared_functions(headers=HEADERS):
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert {"rbe_load_corpus", "rbe_encode_query", "rbe_search", "rbe_workspace_bytes", "rbe_set_workspace",
-            "rbe_index_create_in"} <= set(declared_functions(("rbe.h",)))
+            "rbe_index_create_in", "rbe_search_static"} <= set(declared_functions(("rbe.h",)))
     assert not [n for n in declared_functions(("rbe.h",)) if n.startswith("rbe_debug_")], "test hooks belong in rbe_debug.h"
     for n in names:
         assert hasattr(lib, n), f"{n} declared in a header but not exported"
@@ -63,6 +63,8 @@ def test_constants_match_header():
     for name in ("RBE_MAX_PLANES", "RBE_MAX_QUERIES", "RBE_MAX_K", "RBE_MAX_ITEMS", "RBE_MAX_LEVELS"):
         m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
         assert m and int(m.group(1)) == getattr(rbe, name), name
+    m = re.search(r"#define\s+RBE_STATIC_SCRATCH_BYTES\s+(\d+)u", text)
+    assert m and int(m.group(1)) == rbe.RBE_STATIC_SCRATCH_BYTES
     for name in ("RBE_BORROW", "RBE_COSINE", "RBE_DYADIC"):
         m = re.search(r"%s\s*=\s*1u\s*<<\s*(\d+)" % name, text)
         assert m and (1 << int(m.group(1))) == getattr(rbe, name), name
@@ -109,6 +111,7 @@ def test_caller_owned_memory_entry_points_validate_without_a_gpu(lib):
     assert out.value is None
     assert lib.rbe_workspace_bytes(None, 1, 10, 0) == 0
     assert lib.rbe_set_workspace(None, None, 0) == rbe.RBE_EINVAL
+    assert lib.rbe_search_static(None, None, None, 1, 1, 1, 0, 0, None, None, None) == rbe.RBE_EINVAL
     assert lib.rbe_debug_index_info(None, None) == rbe.RBE_EINVAL
 
 
