@@ -6,7 +6,12 @@ per item (36 B/item, 36 GB resident in HBM), clustered synthetic corpus, exact
 top-1000.  A step is one whole search -- stage the query, score every item,
 select, copy the k results to the host -- for ONE query (the paper's latency
 experiment); `value` is items scored and selected per second over the timed
-steps.  A batch-of-16 throughput figure is reported in the same line.
+steps.  Further legs in the same line: the same searches with every plane read,
+the near-lossless selector, fp32 queries, 16 queries per call, the paper's own
+operating point, and the two other large configurations of the workload table
+(1e9 near-duplicate items with 8 queries and k = 4000; 1e8 items of d = 128 with
+4 planes and 64 queries), each with its own roofline figures.  `--only` runs a
+subset (for profiling one kernel under rocprofv3).
 
 Prints exactly one JSON line on stdout; progress goes to stderr.
 """
@@ -33,7 +38,8 @@ def log(msg: str):
 
 def measured_traffic(workload: str):
     """HBM bytes per finest-level scan launch from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE scaled by the plain-copy yardstick), if it covers this workload."""
+    (FETCH_SIZE + WRITE_SIZE scaled by the plain-copy yardstick), if it covers this workload.
+    Hardware counters cannot be read from inside this process; the figure is the profile's."""
     path = os.path.join(ROOT, "profiles", "scan_exact_1e9_d64_p3_q1.json")
     try:
         with open(path) as f:
@@ -43,6 +49,49 @@ def measured_traffic(workload: str):
     except (OSError, ValueError):
         pass
     return None
+
+
+def oracle_all_cores(oracle, np, planes, scales, qp, qs, k, n_threads):
+    """oracle.topk of one query from n_threads host threads over disjoint item ranges (the C call
+    releases the interpreter lock), per-range results merged with oracle.topk_of_scores."""
+    from concurrent.futures import ThreadPoolExecutor
+    n = planes.shape[1]
+    edges = np.linspace(0, n, n_threads + 1).astype(np.int64)
+    with ThreadPoolExecutor(n_threads) as pool:
+        jobs = [pool.submit(oracle.topk, planes, scales, qp, qs, k, int(a), int(b)) for a, b in zip(edges[:-1], edges[1:]) if b > a]
+        got = [j.result() for j in jobs]
+    ids = np.concatenate([g[0][g[0] >= 0] for g in got])
+    sc = np.concatenate([g[1][g[0] >= 0] for g in got])
+    return oracle.topk_of_scores(sc, ids, k)
+
+
+def finest_level_roofline(np, r, W, P, Q, d, kernel):
+    """Roofline figures of the finest-level scan of a leg from its search statistics: bytes the method has to
+    move per pass (every plane and scale of every item), matrix-core flops of the dense contraction, 32-bit lane
+    operations of the XOR/popcount arithmetic, each over the HIP-event time of that launch."""
+    items = r["stats"]["items_scanned"][-1]
+    ms = float(r["scan_ms"].mean())
+    bytes_per_item = P * (8 * W + 4)
+    passes = -(-Q // 32) if kernel == "scan_batch_mfma" else 1
+    out = {"kernel": f"{kernel} (finest level)", "kernel_ms": ms, "items": items,
+           "algorithmic_bytes_per_item_per_pass": bytes_per_item, "passes_over_the_level": passes,
+           "hbm_gbs": items * bytes_per_item * passes / (ms * 1e-3) / 1e9}
+    out["hbm_frac"] = out["hbm_gbs"] / HBM_PEAK_GBS
+    if kernel == "scan_batch_mfma":
+        ach = 2.0 * Q * items * d * P / (ms * 1e-3) / 1e12
+        out.update({"bound": "mfma", "achieved": ach, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / MFMA_F16_PEAK_TFLOPS, "flops_per_pair": 2 * d * P, "traffic": None,
+                    "note": "priced against the fp16 matrix-core peak as a dense contraction; the kernel is held by "
+                            "vector-instruction issue (bits to halves, thresholds), see profiles/"})
+    elif Q >= 3:
+        ops = lane_ops_per_pair(W, P, P)
+        ach = ops * Q * items / (ms * 1e-3) / 1e12
+        out.update({"bound": "alu", "achieved": ach, "peak": VALU_PEAK_TLANEOPS, "unit": "T lane-ops/s",
+                    "frac": ach / VALU_PEAK_TLANEOPS, "lane_ops_per_pair": ops, "traffic": None})
+    else:
+        out.update({"bound": "hbm", "achieved": out["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": out["hbm_frac"], "traffic": None})
+    return out
 
 
 def lane_ops_per_pair(W: int, P: int, Pq: int) -> int:
@@ -153,7 +202,21 @@ def main():
     ap.add_argument("--paper-items", type=int, default=136 * 136 * 256 * 256)
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also launch the plain copy kernel of this size 5 times (yardstick for rocprofv3 counters)")
+    ap.add_argument("--no-config5", action="store_true", help="skip the 1e9 near-duplicate leg (8 queries, k=4000)")
+    ap.add_argument("--no-config3", action="store_true", help="skip the 1e8 d=128 4-plane leg (64 queries)")
+    ap.add_argument("--config-steps", type=int, default=6, help="timed calls of the config-3 and config-5 legs")
+    ap.add_argument("--only", default="", help="comma list of legs to run instead of all: headline, all_planes, near, "
+                    "hybrid, batch, batch_popcount, cpu, paper, config5, config3 (headline alone = the contract's steps)")
     args = ap.parse_args()
+    only = {x for x in args.only.split(",") if x}
+    known = {"headline", "all_planes", "near", "hybrid", "batch", "batch_popcount", "cpu", "paper", "config5", "config3"}
+    if only - known:
+        print(f"bench.py: unknown legs {sorted(only - known)}", file=sys.stderr)
+        sys.exit(2)
+
+    def want(leg: str) -> bool:
+        return leg in only if only else True
+    main_corpus = not only or bool(only & {"headline", "all_planes", "near", "hybrid", "batch", "batch_popcount", "cpu"})
 
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the whole 1e9-item corpus fits one MI355X); "
@@ -176,7 +239,15 @@ def main():
     N, d, P, k = args.items, args.dim, args.planes, args.k
     W = d // 64
     bytes_per_item = P * (8 * W + 4)
-    cpu_items = 0 if args.no_cpu_baseline else min(args.cpu_sample_items, N)
+    cpu_items = 0 if (args.no_cpu_baseline or not want("cpu")) else min(args.cpu_sample_items, N)
+
+    if not main_corpus:
+        out = {"metric": "candidates scored+selected/sec and p50 query latency at 1B items, k=1000", "value": None,
+               "unit": "candidates/s", "n_gpus": 1, "steps": 0, "warmup": 0, "data": "synthetic",
+               "config": {"workload": "subset run (--only %s): no headline steps" % args.only}}
+        extra_legs(out, args, want, rbe, rbe_synth, torch, np)
+        print(json.dumps(out), flush=True)
+        return
 
     ix, centres, host_planes, host_scales = build_corpus(
         rbe, rbe_synth, torch, N, d, P, args.clusters, args.sigma, args.chunk_items, cpu_items)
@@ -253,11 +324,22 @@ def main():
             "gbs_if_all_planes_counted": all_planes_gbs,
             "kernel_ms": scan_avg_ms,
             "grid_blocks": st["grid_blocks"],
+            "algorithmic_bytes_per_item": bytes_per_item,
+            "algorithmic_bytes_per_launch": last_items * bytes_per_item,
+            "frac_of_algorithmic": all_planes_gbs / HBM_PEAK_GBS,
+            "note": "achieved/frac price the bytes this kernel MOVES (it prunes: the last plane and the fp32 scales are "
+                    "read only for items whose upper bound reaches the threshold), not the method's %d B/item; "
+                    "frac_of_algorithmic prices all %d B/item over the same time and can exceed 1 for that reason. "
+                    "The share pruned depends on the corpus: on one with no cluster structure the library falls back "
+                    "to the all-planes scan, whose fraction is worst_case." % (bytes_per_item, bytes_per_item),
+            "worst_case": None,
         },
     }
+    if st["n_levels"]:
+        out["scan_kernel_per_level"] = st["scan_kernel"]
 
     # ---------------- the same searches with every plane of every item read (progressive scan off)
-    if P >= 2:
+    if P >= 2 and want("all_planes"):
         rbe.rbe_debug_set_progressive(ix, False)
         steps_a = max(2, args.steps // 4)
         ra = timed_searches(rbe, torch, ix, qp1, qs1, 1, k, steps_a, args.warmup)
@@ -270,11 +352,14 @@ def main():
             "hbm_gbs": a_gbs, "hbm_frac": a_gbs / HBM_PEAK_GBS, "bytes_per_launch": last_items * bytes_per_item,
             "same_ids_as_progressive": bool(same),
         }
+        out["roofline"]["worst_case"] = {"kernel": "scan_exact (finest level, every plane of every item read)",
+                                         "achieved": a_gbs, "frac": a_gbs / HBM_PEAK_GBS, "kernel_ms": a_scan,
+                                         "ms_per_step": ra["wall_s"] * 1e3 / steps_a}
         log(f"Q=1, every plane read: {ra['wall_s'] * 1e3 / steps_a:.3f} ms/step, scan kernel {a_scan:.3f} ms -> {a_gbs:.0f} GB/s, "
             f"same ids: {same}")
 
     # ---------------- near-lossless selector (Algorithm 1, queue length 1, I = 256) on the same queries
-    if not args.no_nearlossless:
+    if not args.no_nearlossless and want("near"):
         I = 256
         rn = timed_searches(rbe, torch, ix, qp1, qs1, 1, k, args.steps, args.warmup, rbe.RBE_SELECT_NEARLOSSLESS, I)
         recalls = [len(set(a[0].tolist()) & set(b[0].tolist()) - {-1}) / k for a, b in zip(rn["ids"], r1["ids"])]
@@ -302,7 +387,7 @@ def main():
         log(f"near-lossless I={I}, queue length 2: {rn2['wall_s'] * 1e3 / steps2:.3f} ms/step, recall {np.mean(rec2):.5f}")
 
     # ---------------- hybrid scoring: fp32 query against the binary items (the paper's model m_5)
-    if not args.no_hybrid:
+    if not args.no_hybrid and want("hybrid"):
         xq = rbe_synth.vectors_torch(args.warmup + args.steps, centres, args.sigma, rbe_synth.SEED_QUERIES, 0).cpu().numpy()
         for s_ in range(args.warmup):
             rbe.rbe_search_float(ix, xq[s_:s_ + 1], k)
@@ -339,7 +424,7 @@ def main():
             log(f"hybrid fp32 queries, Q={B}: {hb_ms:.3f} ms/step")
 
     # ---------------- batch leg
-    if args.batch > 0:
+    if args.batch > 0 and want("batch"):
         B = args.batch
         bw = 2
         qpb, qsb = make_queries(rbe, rbe_synth, torch, centres, (bw + args.batch_steps) * B, args.sigma, P, 1)
@@ -381,7 +466,7 @@ def main():
         }
         log(f"Q={B}: {b_ms:.3f} ms/step (per step {np.round(rb['per_step_ms'], 2).tolist()}, "
             f"{rb['fallbacks']} on the bounded-segment path), scan kernel {b_scan:.3f} ms")
-        if matrix_cores:
+        if matrix_cores and want("batch_popcount"):
             # the same calls on the XOR/popcount kernel (what one query uses), against the vector-ALU roofline
             # (progressive scan off for the roofline figure: the 58-op model prices every plane of every pair)
             rbe.rbe_debug_set_batch_path(ix, 1)
@@ -410,27 +495,83 @@ def main():
             log(f"Q={B}, XOR/popcount kernel, every plane: {v_ms:.3f} ms/step (per step {np.round(rv['per_step_ms'], 2).tolist()}), scan kernel {v_scan:.3f} ms "
                 f"-> {v_ach:.1f} T lane-ops/s")
 
-    # ---------------- CPU baseline: the oracle, as it stands, on a bounded sample
+    # ---------------- CPU baseline: the oracle, as it stands, on a bounded sample: one thread, then one thread per
+    # host core over disjoint item ranges (the oracle's own code is unchanged and single-threaded)
     if cpu_items > 0:
         import oracle
         nq = min(args.cpu_sample_queries, n_q1)
         t0 = time.perf_counter()
-        for i in range(nq):
-            oracle.topk(host_planes, host_scales, qp1[i], qs1[i], k)
+        single = [oracle.topk(host_planes, host_scales, qp1[i], qs1[i], k) for i in range(nq)]
         dt = time.perf_counter() - t0
+        n_threads = max(1, min(16, os.cpu_count() or 1))      # a one-GPU machine has a share of 16 host cores
+        t0 = time.perf_counter()
+        multi = [oracle_all_cores(oracle, np, host_planes, host_scales, qp1[i], qs1[i], k, n_threads) for i in range(nq)]
+        dt_all = time.perf_counter() - t0
+        agree = all(np.array_equal(a[0], b[0]) for a, b in zip(single, multi))
         out["cpu_baseline"] = {
-            "value": cpu_items * nq / dt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {cpu_items} items of the same corpus x {nq} of the same queries, exact top-{k}, "
-                      f"{dt:.1f} s single-threaded C scan",
+            "value": cpu_items * nq / dt_all, "unit": "candidates/s", "cores": n_threads, "kind": "oracle",
+            "sample": f"first {cpu_items} items of the same corpus x {nq} of the same queries, exact top-{k}: "
+                      f"{dt_all:.1f} s with one oracle call per host thread over disjoint item ranges "
+                      f"({n_threads} threads), {dt:.1f} s single-threaded",
+            "single_thread": {"value": cpu_items * nq / dt, "unit": "candidates/s", "cores": 1, "seconds": dt},
+            "all_cores_seconds": dt_all, "same_ids_as_single_thread": bool(agree),
             "host_cpus": os.cpu_count(),
         }
-        log(f"oracle: {cpu_items * nq / dt / 1e6:.1f} M candidates/s on 1 core ({dt:.1f}s)")
+        log(f"oracle: {cpu_items * nq / dt / 1e6:.1f} M candidates/s on 1 core ({dt:.1f}s), "
+            f"{cpu_items * nq / dt_all / 1e6:.1f} M candidates/s on {n_threads} threads ({dt_all:.1f}s)")
 
+    rbe.rbe_free(ix)
+    ix = None
+    host_planes = host_scales = None
+    if args.calibrate_copy > 0:
+        calibrate(out, args, rbe, torch)
+    extra_legs(out, args, want, rbe, rbe_synth, torch, np)
+    out["roofline"]["traffic"] = measured_traffic(out["config"]["workload"])
+    out["roofline"]["traffic_source"] = ("profiles/scan_exact_1e9_d64_p3_q1.md: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE of "
+                                         "this kernel on this workload, scaled by the plain-copy yardstick; not measured in this run")
+    print(json.dumps(out), flush=True)
+
+
+def calibrate(out, args, rbe, torch):
+    """Yardsticks for hardware-counter readings and for the practical read ceiling of the box."""
+    nbytes = args.calibrate_copy << 20
+    src = torch.full((nbytes // 4,), 1.0, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rbe.rbe_debug_copy(dst, src)
+    ev0.record()
+    for _ in range(5):
+        rbe.rbe_debug_copy(dst, src)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / 5
+    out["calib_copy"] = {"bytes_read": nbytes, "bytes_written": nbytes, "kernel_ms": ms,
+                         "gbs_read_plus_write": 2 * nbytes / (ms * 1e-3) / 1e9}
+    log(f"calib_copy {args.calibrate_copy} MiB: {ms:.3f} ms -> {2 * nbytes / (ms * 1e-3) / 1e9:.0f} GB/s (r+w)")
+    # read-only yardstick over a buffer several times the 256 MB last-level cache
+    del dst
+    big = torch.full((max(nbytes, 16 << 30) // 4,), 1.0, dtype=torch.float32, device="cuda:0")
+    sink = torch.empty(8 << 20, dtype=torch.uint8, device="cuda:0")
+    rbe.rbe_debug_read(big, sink)
+    ev0.record()
+    for _ in range(5):
+        rbe.rbe_debug_read(big, sink)
+    ev1.record()
+    torch.cuda.synchronize()
+    rms = ev0.elapsed_time(ev1) / 5
+    rbytes = big.numel() * 4
+    out["calib_read"] = {"bytes_read": rbytes, "kernel_ms": rms, "gbs_read": rbytes / (rms * 1e-3) / 1e9}
+    log(f"calib_read {rbytes >> 20} MiB: {rms:.3f} ms -> {rbytes / (rms * 1e-3) / 1e9:.0f} GB/s")
+
+
+
+def extra_legs(out, args, want, rbe, rbe_synth, torch, np):
+    """Legs on corpora of their own: the paper's operating point and configurations 3 and 5 of the workload table."""
+    k = args.k
+    n_q1 = args.warmup + args.steps
     # ---------------- the paper's own operating point: 2 keyword bits, 3 query bits per dimension,
     # residual weights 2^-t by shift-adds, one stored inverse norm per keyword (20 B/item)
-    if not args.no_paper_point:
-        rbe.rbe_free(ix)
-        ix = None
+    if not args.no_paper_point and want("paper"):
         Np, Pk, Pq = args.paper_items, 2, 3
         ixp, centres_p, _, _ = build_corpus(rbe, rbe_synth, torch, Np, 64, Pk, args.clusters, args.sigma,
                                             args.chunk_items, 0, rbe.RBE_DYADIC | rbe.RBE_COSINE)
@@ -478,40 +619,58 @@ def main():
             log(f"paper point Q={B}: {pb_ms:.3f} ms/step, scan kernel {pb_scan:.3f} ms")
         rbe.rbe_free(ixp)
 
-    if args.calibrate_copy > 0:
-        nbytes = args.calibrate_copy << 20
-        src = torch.full((nbytes // 4,), 1.0, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        rbe.rbe_debug_copy(dst, src)
-        ev0.record()
-        for _ in range(5):
-            rbe.rbe_debug_copy(dst, src)
-        ev1.record()
-        torch.cuda.synchronize()
-        ms = ev0.elapsed_time(ev1) / 5
-        out["calib_copy"] = {"bytes_read": nbytes, "bytes_written": nbytes, "kernel_ms": ms,
-                             "gbs_read_plus_write": 2 * nbytes / (ms * 1e-3) / 1e9}
-        log(f"calib_copy {args.calibrate_copy} MiB: {ms:.3f} ms -> {2 * nbytes / (ms * 1e-3) / 1e9:.0f} GB/s (r+w)")
-        # read-only yardstick over a buffer several times the 256 MB last-level cache
-        del dst
-        big = torch.full((max(nbytes, 16 << 30) // 4,), 1.0, dtype=torch.float32, device="cuda:0")
-        sink = torch.empty(8 << 20, dtype=torch.uint8, device="cuda:0")
-        rbe.rbe_debug_read(big, sink)
-        ev0.record()
-        for _ in range(5):
-            rbe.rbe_debug_read(big, sink)
-        ev1.record()
-        torch.cuda.synchronize()
-        rms = ev0.elapsed_time(ev1) / 5
-        rbytes = big.numel() * 4
-        out["calib_read"] = {"bytes_read": rbytes, "kernel_ms": rms, "gbs_read": rbytes / (rms * 1e-3) / 1e9}
-        log(f"calib_read {rbytes >> 20} MiB: {rms:.3f} ms -> {rbytes / (rms * 1e-3) / 1e9:.0f} GB/s")
+    # ---------------- configuration 5: 1e9 near-duplicate items (sigma 0.05), 8 queries per call, k = 4000:
+    # stresses pruning (cluster-mates share bit planes and have nearly equal scales) and the merge
+    if not args.no_config5 and want("config5"):
+        out["config5_near_duplicates"] = config_leg(
+            rbe, rbe_synth, torch, np, args, N=1_000_000_000, d=64, P=3, clusters=4096, sigma=0.05, Q=8, k=4000,
+            seed_chunk=11, label="config 5", near_lossless=True)
+    # ---------------- configuration 3: 1e8 items, d = 128, 4 planes (80 B/item), 64 queries per call, k = 1000
+    if not args.no_config3 and want("config3"):
+        out["config3_d128_4planes"] = config_leg(
+            rbe, rbe_synth, torch, np, args, N=100_000_000, d=128, P=4, clusters=4096, sigma=0.3, Q=64, k=1000,
+            seed_chunk=12, label="config 3", near_lossless=False)
 
-    out["roofline"]["traffic"] = measured_traffic(out["config"]["workload"])
-    if ix is not None:
-        rbe.rbe_free(ix)
-    print(json.dumps(out), flush=True)
+
+def config_leg(rbe, rbe_synth, torch, np, args, *, N, d, P, clusters, sigma, Q, k, seed_chunk, label, near_lossless):
+    """One more configuration of the workload table on a corpus of its own: Q queries per call, exact top-k, timed
+    like the headline steps (different queries per call, results in host memory), with the roofline figures of its
+    finest-level scan; optionally the near-lossless selector's time and recall against the exact result."""
+    W = d // 64
+    ix, centres, _, _ = build_corpus(rbe, rbe_synth, torch, N, d, P, clusters, sigma, args.chunk_items, 0)
+    rbe.rbe_set_profiling(ix, True)
+    steps, warm = args.config_steps, 2
+    qp, qs = make_queries(rbe, rbe_synth, torch, centres, (warm + steps) * Q, sigma, P, seed_chunk)
+    r = timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warm)
+    ms = r["wall_s"] * 1e3 / steps
+    st = r["stats"]
+    leg = {
+        "workload": f"{N} items, d={d}, {P} bit-planes + {P} fp32 scales ({P * (8 * W + 4)} B/item), {clusters}-cluster "
+                    f"Gaussian mixture sigma={sigma}, exact top-{k}, {Q} queries per call",
+        "queries_per_step": Q, "k": k, "steps": steps, "warmup": warm, "ms_per_step": ms,
+        "p50_ms": float(np.percentile(r["per_step_ms"], 50)), "value": N * Q * steps / r["wall_s"], "unit": "candidates/s",
+        "levels": st["n_levels"], "scan_kernel_per_level": st["scan_kernel"], "candidates_max": st["candidates_max"],
+        "last_search_level_ms": {"scan": st["scan_ms"], "select": st["select_ms"]},
+        "gpu_ms_per_search": float(r["total_gpu_ms"].mean()) if r["total_gpu_ms"].size else None,
+        "fallbacks": r["fallbacks"],
+        "roofline": finest_level_roofline(np, r, W, P, Q, d, st["scan_kernel"][-1]) if st["n_levels"] and r["scan_ms"].size else None,
+    }
+    log(f"{label}: Q={Q}, k={k}: {ms:.3f} ms/step (per step {np.round(r['per_step_ms'], 2).tolist()}), "
+        f"levels {st['scan_kernel']}, scan {np.round(st['scan_ms'], 3).tolist()} ms, select {np.round(st['select_ms'], 3).tolist()} ms")
+    if near_lossless:
+        I = 256
+        rn = timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warm, rbe.RBE_SELECT_NEARLOSSLESS, I)
+        rec = [len(set(a[q].tolist()) & set(b[q].tolist()) - {-1}) / k for a, b in zip(rn["ids"], r["ids"]) for q in range(Q)]
+        slots = -(-N // (256 * I)) * 256 * I
+        predicted = 1.0 - (k - 1) * (I - 1) / (2.0 * (slots - 1))      # Appendix A, expected recall
+        leg["near_lossless"] = {"group_size_I": I, "ms_per_step": rn["wall_s"] * 1e3 / steps,
+                                "recall_vs_exact_mean": float(np.mean(rec)), "recall_vs_exact_min": float(np.min(rec)),
+                                "recall_predicted_appendix_a": predicted, "queries": len(rec)}
+        log(f"{label}: near-lossless I={I}: {rn['wall_s'] * 1e3 / steps:.3f} ms/step, recall {np.mean(rec):.5f} "
+            f"(Appendix A: {predicted:.5f})")
+    rbe.rbe_free(ix)
+    torch.cuda.empty_cache()
+    return leg
 
 
 if __name__ == "__main__":

@@ -316,7 +316,19 @@ typedef struct rbe_search_stats {
                                  and fp32 scales of items that could still reach
                                  the threshold, whole rows in the fallback), in
                                  units of 8 bytes                                 */
+    uint32_t scan_kernel[RBE_MAX_LEVELS];     /* which scan each level ran: RBE_KERNEL_* */
 } rbe_search_stats;
+
+enum {                        /* rbe_search_stats.scan_kernel                      */
+    RBE_KERNEL_NONE = 0,
+    RBE_KERNEL_SCAN_EXACT = 1,        /* XOR/popcount, every plane of every item    */
+    RBE_KERNEL_SCAN_PROG = 2,         /* ... last plane only where the bound passes */
+    RBE_KERNEL_SCAN_PROG_HINT = 3,    /* ... streaming one-byte scale copies        */
+    RBE_KERNEL_SCAN_BATCH_MFMA = 4,   /* matrix-core filter + XOR/popcount rescoring */
+    RBE_KERNEL_SCAN_GROUPMAX = 5,     /* near-lossless group maxima (Algorithm 1)   */
+    RBE_KERNEL_SCAN_FLOAT = 6,        /* fp32 query through byte tables, every plane */
+    RBE_KERNEL_SCAN_FLOAT_PROG = 7    /* ... last plane only where the bound passes */
+};
 
 int rbe_set_profiling(rbe_index *ix, int enabled);
 int rbe_get_search_stats(const rbe_index *ix, rbe_search_stats *out);

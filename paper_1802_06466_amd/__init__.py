@@ -49,7 +49,12 @@ class rbe_search_stats(ctypes.Structure):
         ("select_ms", ctypes.c_float * RBE_MAX_LEVELS),
         ("total_gpu_ms", ctypes.c_float),
         ("deep_units", ctypes.c_uint32),
+        ("scan_kernel", ctypes.c_uint32 * RBE_MAX_LEVELS),
     ]
+
+
+KERNEL_NAMES = {0: "none", 1: "scan_exact", 2: "scan_exact_prog", 3: "scan_exact_prog_hint", 4: "scan_batch_mfma",
+                5: "scan_groupmax", 6: "scan_exact_fq", 7: "scan_exact_fq_prog"}
 
 
 _lib = None
@@ -397,6 +402,7 @@ def rbe_get_search_stats(ix: Index) -> dict:
         "items_scanned": list(st.items_scanned)[:n], "candidates_max": list(st.candidates_max)[:n],
         "scan_ms": list(st.scan_ms)[:n], "select_ms": list(st.select_ms)[:n],
         "total_gpu_ms": st.total_gpu_ms, "deep_units": st.deep_units,
+        "scan_kernel": [KERNEL_NAMES.get(v, str(v)) for v in list(st.scan_kernel)[:n]],
     }
 
 

@@ -1240,6 +1240,14 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         e = launch_scan_groupmax(ix->W, sel, ga, c.Q, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
     }
     if (e != hipSuccess) { set_error("scan launch failed: %s", hipGetErrorString(e)); return RBE_EHIP; }
+    if (level_slot < RBE_MAX_LEVELS) {
+        uint32_t which = RBE_KERNEL_SCAN_GROUPMAX;
+        if (c.float_query) which = sel.progressive ? RBE_KERNEL_SCAN_FLOAT_PROG : RBE_KERNEL_SCAN_FLOAT;
+        else if (c.batch_mfma && !(dense && !c.float_batch && ix->batch_path == 0)) which = RBE_KERNEL_SCAN_BATCH_MFMA;
+        else if (c.mode == RBE_SELECT_EXACT)
+            which = !sel.progressive ? RBE_KERNEL_SCAN_EXACT : (sel.hints ? RBE_KERNEL_SCAN_PROG_HINT : RBE_KERNEL_SCAN_PROG);
+        ix->stats.scan_kernel[level_slot] = which;
+    }
     ix->stats.grid_blocks = std::max(ix->stats.grid_blocks, grid);
     return RBE_OK;
 }
