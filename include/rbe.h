@@ -245,7 +245,8 @@ int rbe_search(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
  * here the caller's allocator, e.g. a torch tensor, can own all of it).
  * rbe_workspace_bytes(): device bytes that a search of up to n_queries queries
  * for k results in `mode` needs on this index with its current tuning (0 for
- * arguments out of range); the figure covers rbe_search and rbe_search_float.
+ * arguments out of range; the near-lossless modes need about three times the
+ * exact mode's); the figure covers rbe_search and rbe_search_float.
  * rbe_set_workspace(): every later search carves its scratch from dev_ptr (DEVICE
  * pointer, 256-byte aligned, `bytes` long) instead of library-owned memory, which
  * is released; the caller keeps ownership and must keep the block alive and
@@ -261,7 +262,8 @@ int rbe_set_workspace(rbe_index *ix, void *dev_ptr, size_t bytes);
  * library (RBE_STATIC_SCRATCH_BYTES per GPU, held until the process ends) and the
  * call makes no allocation of any kind on the device or in pinned host memory.
  * Limit: rbe_workspace_bytes(ix, n_queries, k, mode) <= RBE_STATIC_SCRATCH_BYTES
- * (e.g. 4 queries for k = 1000, or 1 query for k = 4096, at the default tuning),
+ * (exact mode at the default tuning: e.g. 4 queries for k = 1000, or 1 query for
+ * k = 4096; near-lossless modes: 2 queries for k = 1000),
  * else RBE_EINVAL.  The device that owns the index must be current.  All calls on
  * one GPU share the array: calls that overlap in time on one GPU -- from several
  * threads, or for several indexes -- race; serialise them.  What a call needs
@@ -287,7 +289,7 @@ int rbe_search_static(rbe_index *ix, const uint64_t *q_planes, const float *q_sc
  * do not depend on the number of queries per call, and the corpus is read once per
  * 32 queries; otherwise it is read once per query.
  *   q: [n_queries][dim] float (host), finite.  Other arguments as rbe_search.
- * Only RBE_SELECT_EXACT is built.                                               */
+ * Every selection mode of rbe_search is available.                              */
 int rbe_search_float(rbe_index *ix, const float *q, uint32_t n_queries, uint32_t k,
                      uint32_t mode, uint32_t group_size_I,
                      int64_t *ids_out, float *scores_out, void *hip_stream);

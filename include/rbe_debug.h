@@ -71,6 +71,15 @@ int rbe_debug_query_mass(const uint64_t *q_planes, const float *q_scales, uint32
  * matrix-core kernel for any number of queries (dim <= 128).                     */
 int rbe_debug_set_batch_path(rbe_index *ix, int path);
 
+/* How the near-lossless modes are computed.  0 (default): the scans and the
+ * refinement plan of the exact mode, with the candidates reduced to the best item
+ * (or two) of every group of Algorithm 1 before each selection -- the same result,
+ * since an item below a lower bound of the k-th best forwarded item can neither be
+ * returned nor change what another group forwards.  1: a scan that keeps one queue
+ * per thread as Algorithm 1 is written (every plane of every item read; binary
+ * queries only).  Both are tested against the oracle and against each other.     */
+int rbe_debug_set_nearlossless_path(rbe_index *ix, int path);
+
 /* fp32 hybrid scores (rbe_search_float arithmetic) of one fp32 query q [dim] for z in
  * [first_item, first_item+count): out [count] float (host).                  */
 int rbe_debug_scores_float(rbe_index *ix, const float *q, uint64_t first_item,

@@ -87,6 +87,7 @@ PROTOTYPES = {
     "rbe_debug_tile_to_phys": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_phys_to_tile": (_u32, [_u32, _u32, _u32]),
     "rbe_debug_set_batch_path": (_i32, [_vp, _i32]),
+    "rbe_debug_set_nearlossless_path": (_i32, [_vp, _i32]),
     "rbe_debug_set_progressive": (_i32, [_vp, _i32]),
     "rbe_debug_set_plan_split": (_i32, [_vp, _i32]),
     "rbe_debug_query_mass": (_i32, [_vp, _vp, _u32, _u32, _u32, _vp]),
@@ -476,6 +477,11 @@ def rbe_debug_set_plan_split(ix: Index, mode: int):
 def rbe_debug_set_progressive(ix: Index, enabled):
     """False/0 = off, True/1 = on, 2 = on without the one-byte scale copies."""
     _check(load_library().rbe_debug_set_progressive(ix.handle, int(enabled)))
+
+
+def rbe_debug_set_nearlossless_path(ix: Index, path: int):
+    """0 = exact scans + selection by groups (default), 1 = the per-thread-queue scan of Algorithm 1."""
+    _check(load_library().rbe_debug_set_nearlossless_path(ix.handle, path))
 
 
 def rbe_debug_set_batch_path(ix: Index, path: int):

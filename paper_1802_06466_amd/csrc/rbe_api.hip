@@ -95,6 +95,9 @@ struct rbe_index {
         float* unscale = nullptr;       // [3][RBE_MAX_QUERIES]: matrix-core scan, per query 2^-k, start value, mass
         uint32_t* aops = nullptr;       // matrix-core query operands (BatchArgs::a_ops)
         float* lut = nullptr;           // [Q][8W][256] byte tables of fp32 queries (hybrid scoring)
+        uint64_t* gtable = nullptr;     // near-lossless modes: [Q][gslots][2] group table of group_best_build
+        uint32_t* gaux = nullptr;       // ... [Q][4] its counters
+        uint32_t gslots = 0;
     };
     DevWs ws;                       // the scratch the current search uses: carved from one of the three blocks below
     char* own_ws = nullptr;         // grown on demand by the library (hipMalloc) ...
@@ -119,6 +122,7 @@ struct rbe_index {
     // false if a scale is negative: every bound of the pruning scans assumes a_j >= 0, so they all stay off
     bool nonneg = true;
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
+    int nl_path = 0;                // near-lossless modes: 0 = exact scans + selection by groups, 1 = the per-thread-queue scan
     uint32_t* d_hints = nullptr;    // general scales, P >= 2: one-byte copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
     int hint_base[3] = {1, 1, 1};   // exponent base of each array's hints
     float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize),
@@ -203,7 +207,8 @@ hipError_t launch_dense_scores(uint32_t W, const KernelSel& k, const char* tiles
 
 // ---------------------------------------------------------------- workspace
 // All device scratch of one search lives in one block, laid out for the call's n_queries, k and candidate
-// capacity: fixed-size state first, the large candidate lists last, every part 256-byte aligned.  With
+// capacity: fixed-size state first, the large candidate lists (and, for the near-lossless modes, the group tables)
+// last, every part 256-byte aligned.  With
 // base == nullptr only the size is computed.  The block is the library's own (grown on demand), the caller's
 // (rbe_set_workspace) or the static array of rbe_search_static.
 constexpr size_t kWsAlign = 256;
@@ -211,7 +216,7 @@ constexpr size_t kQueryWordsBytes = (size_t)RBE_MAX_QUERIES * RBE_MAX_PLANES * 8
 constexpr size_t kQueryCoefBytes = (size_t)RBE_MAX_QUERIES * (RBE_MAX_PLANES + 1 + 2) * sizeof(float);
 constexpr size_t kHalvesPerQueryTile = (size_t)4 * 4 * 64 * 8;   // copies x parts <= 16, 64 lanes, 8 halves
 
-size_t carve_workspace(rbe_index::DevWs* ws, char* base, uint32_t W, uint32_t Q, uint32_t k, uint32_t cap)
+size_t carve_workspace(rbe_index::DevWs* ws, char* base, uint32_t W, uint32_t Q, uint32_t k, uint32_t cap, bool groups)
 {
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -231,6 +236,12 @@ size_t carve_workspace(rbe_index::DevWs* ws, char* base, uint32_t W, uint32_t Q,
     w.lut = reinterpret_cast<float*>(take((size_t)Q * 8 * W * 256 * sizeof(float)));
     w.result = take(kResultHeaderBytes + (size_t)Q * k * (sizeof(int64_t) + sizeof(float)));
     w.cand = reinterpret_cast<uint64_t*>(take((size_t)Q * cap * sizeof(uint64_t)));
+    if (groups) {       // near-lossless modes: a table of twice as many slots as a query has candidate slots, two keys each
+        w.gslots = 1u;
+        while (w.gslots < 2u * cap) w.gslots <<= 1;
+        w.gaux = reinterpret_cast<uint32_t*>(take((size_t)Q * 4 * sizeof(uint32_t)));
+        w.gtable = reinterpret_cast<uint64_t*>(take((size_t)Q * w.gslots * 2 * sizeof(uint64_t)));
+    }
     if (base) {
         w.status = reinterpret_cast<uint32_t*>(w.result);
         w.seen = reinterpret_cast<uint32_t*>(w.result + kResultStatusBytes);
@@ -250,16 +261,16 @@ uint32_t search_capacity(const rbe_index* ix, uint32_t k)
 
 // Points ix->ws at scratch for this call: the caller's block if one was set (an error if it is too small),
 // else the library's own block, grown when this call needs more than any call before it.
-int acquire_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
+int acquire_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap, bool groups = false)
 {
-    const size_t need = carve_workspace(nullptr, nullptr, ix->W, Q, k, cap);
+    const size_t need = carve_workspace(nullptr, nullptr, ix->W, Q, k, cap, groups);
     if (ix->ext_ws) {
         if (need > ix->ext_ws_bytes) {
             set_error("the workspace set with rbe_set_workspace holds %zu bytes; this search needs %zu "
                       "(rbe_workspace_bytes)", ix->ext_ws_bytes, need);
             return RBE_EINVAL;
         }
-        carve_workspace(&ix->ws, ix->ext_ws, ix->W, Q, k, cap);
+        carve_workspace(&ix->ws, ix->ext_ws, ix->W, Q, k, cap, groups);
         return RBE_OK;
     }
     if (need > ix->own_ws_bytes) {
@@ -269,7 +280,7 @@ int acquire_workspace(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
         HIP_TRY(hipMalloc(&ix->own_ws, need));
         ix->own_ws_bytes = need;
     }
-    carve_workspace(&ix->ws, ix->own_ws, ix->W, Q, k, cap);
+    carve_workspace(&ix->ws, ix->own_ws, ix->W, Q, k, cap, groups);
     return RBE_OK;
 }
 
@@ -279,7 +290,7 @@ constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 char* g_scratch_ptr[kMaxDevices] = {};
 
-int acquire_static_scratch(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
+int acquire_static_scratch(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap, bool groups)
 {
     int dev = -1;
     HIP_TRY(hipGetDevice(&dev));
@@ -288,7 +299,7 @@ int acquire_static_scratch(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
         return RBE_EINVAL;
     }
     if (dev < 0 || dev >= kMaxDevices) { set_error("device %d: no static scratch slot", dev); return RBE_EUNSUPPORTED; }
-    const size_t need = carve_workspace(nullptr, nullptr, ix->W, Q, k, cap);
+    const size_t need = carve_workspace(nullptr, nullptr, ix->W, Q, k, cap, groups);
     if (need > (size_t)RBE_STATIC_SCRATCH_BYTES) {
         set_error("rbe_search_static: %u queries with k = %u need %zu bytes of scratch, the static array holds %zu "
                   "(fewer queries per call, a smaller k, or a smaller cand_capacity via rbe_set_tuning)",
@@ -305,7 +316,7 @@ int acquire_static_scratch(rbe_index* ix, uint32_t Q, uint32_t k, uint32_t cap)
         }
         base = g_scratch_ptr[dev];
     }
-    carve_workspace(&ix->ws, base, ix->W, Q, k, cap);
+    carve_workspace(&ix->ws, base, ix->W, Q, k, cap, groups);
     return RBE_OK;
 }
 
@@ -1155,6 +1166,9 @@ struct Round { uint32_t begin, end, stride, skip; };
 struct SearchCtx {
     rbe_index* ix; hipStream_t st; uint32_t Q, PQ, k, cap, mode, I;
     uint32_t qlen;      // near-lossless: entries per group queue (1 or 2); mode holds RBE_SELECT_NEARLOSSLESS for both
+    // near-lossless result through the scans and the plan of the exact mode (mode holds RBE_SELECT_EXACT): before each
+    // selection the candidates are reduced to the best qlen per group of Algorithm 1 (group_best_build / _compact)
+    bool group_select = false;
     bool float_query;   // hybrid scoring: fp32 queries through byte tables
     bool batch_mfma;    // exact mode, several queries: matrix-core scan
     bool float_batch;   // ... of full-precision queries
@@ -1260,6 +1274,18 @@ static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_
     if (rc) return rc;
     if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 1], c.st));
 
+    if (c.group_select) {
+        GroupBestArgs ga;
+        ga.cand = ix->ws.cand; ga.count = ix->ws.count; ga.cap = c.cap; ga.table = ix->ws.gtable; ga.slots = ix->ws.gslots;
+        ga.aux = ix->ws.gaux; ga.group_span = kRow * c.I; ga.qlen = c.qlen; ga.status = ix->ws.status;
+        const uint32_t blocks = std::min<uint32_t>((uint32_t)ix->n_cu * 4u, (c.cap + 255u) / 256u);
+        hipLaunchKernelGGL(rbe::group_best_build, dim3(blocks, c.Q), dim3(256), 0, c.st, ga);
+        HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(rbe::group_best_compact, dim3(std::min<uint32_t>((uint32_t)ix->n_cu * 4u, ga.slots / 256u), c.Q), dim3(256),
+                           0, c.st, ga);
+        HIP_TRY(hipGetLastError());
+    }
+
     SelectArgs se;
     se.cand = ix->ws.cand; se.count = ix->ws.count; se.tau = ix->ws.tau; se.kmax = ix->ws.kmax; se.cap = c.cap; se.k = c.k;
     se.status = ix->ws.status; se.count_seen = ix->ws.seen + (size_t)level_slot * RBE_MAX_QUERIES;
@@ -1354,6 +1380,14 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     for (int attempt = 0; attempt < 2; ++attempt) {
         hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, c.st, ix->ws.count, ix->ws.tau, ix->ws.kmax, ix->ws.status, c.Q);
         HIP_TRY(hipGetLastError());
+        if (c.group_select) {
+            // the group tables start empty (group_best_compact leaves them so after every level) and so do the
+            // counters that sit in front of them; both parts are multiples of 256 bytes
+            const size_t bytes = (size_t)((char*)ix->ws.gtable - (char*)ix->ws.gaux) + (size_t)c.Q * ix->ws.gslots * 2 * sizeof(uint64_t);
+            hipLaunchKernelGGL(rbe::fill_zero16, dim3((uint32_t)std::min<size_t>((size_t)ix->n_cu * 8, (bytes / 16 + 255) / 256)), dim3(256),
+                               0, c.st, reinterpret_cast<rbe::u32x4*>(ix->ws.gaux), bytes / 16);
+            HIP_TRY(hipGetLastError());
+        }
         if (!fallback) {
             if (prof) HIP_TRY(hipEventRecord(ix->ev[0], c.st));
             for (size_t l = 0; l < plan.size(); ++l) {
@@ -1456,14 +1490,16 @@ static int search_prologue(rbe_index* ix, SearchCtx& c, uint32_t n_queries, uint
               "unknown mode %u", mode);
     ARG_CHECK(group_size_I <= 65535, "group_size_I must be <= 65535");
     c.ix = ix; c.st = (hipStream_t)hip_stream; c.Q = n_queries; c.PQ = 1; c.k = k;
-    c.mode = mode == RBE_SELECT_NEARLOSSLESS_Q2 ? (uint32_t)RBE_SELECT_NEARLOSSLESS : mode;
+    c.group_select = mode != RBE_SELECT_EXACT && ix->nl_path == 0;
+    c.mode = c.group_select ? (uint32_t)RBE_SELECT_EXACT : (mode == RBE_SELECT_NEARLOSSLESS_Q2 ? (uint32_t)RBE_SELECT_NEARLOSSLESS : mode);
     c.qlen = mode == RBE_SELECT_NEARLOSSLESS_Q2 ? 2u : 1u;
     c.I = group_size_I ? group_size_I : 256;
     c.float_query = false;
     c.batch_mfma = false;
     c.float_batch = false;
     c.cap = search_capacity(ix, k);
-    return static_scratch ? acquire_static_scratch(ix, c.Q, k, c.cap) : acquire_workspace(ix, c.Q, k, c.cap);
+    const bool groups = mode != RBE_SELECT_EXACT;
+    return static_scratch ? acquire_static_scratch(ix, c.Q, k, c.cap, groups) : acquire_workspace(ix, c.Q, k, c.cap, groups);
 }
 
 static int search_binary(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
@@ -1478,7 +1514,7 @@ static int search_binary(rbe_index* ix, const uint64_t* q_planes, const float* q
     c.PQ = q_n_planes;
     rc = stage_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
     if (rc) return rc;
-    c.batch_mfma = use_batch_mfma(ix, c.Q, mode, false);
+    c.batch_mfma = use_batch_mfma(ix, c.Q, c.mode, false);
     if (c.batch_mfma) {
         rc = stage_batch_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
         if (rc) return rc;
@@ -1506,7 +1542,7 @@ size_t rbe_workspace_bytes(const rbe_index* ix, uint32_t n_queries, uint32_t k, 
 {
     if (!ix || n_queries < 1 || n_queries > RBE_MAX_QUERIES || k < 1 || k > RBE_MAX_K || mode > RBE_SELECT_NEARLOSSLESS_Q2)
         return 0;
-    return carve_workspace(nullptr, nullptr, ix->W, n_queries, k, search_capacity(ix, k));
+    return carve_workspace(nullptr, nullptr, ix->W, n_queries, k, search_capacity(ix, k), mode != RBE_SELECT_EXACT);
 }
 
 int rbe_set_workspace(rbe_index* ix, void* dev_ptr, size_t bytes)
@@ -1531,13 +1567,13 @@ int rbe_search_float(rbe_index* ix, const float* q, uint32_t n_queries, uint32_t
     int rc = search_prologue(ix, c, n_queries, k, mode, group_size_I, ids_out, scores_out, hip_stream);
     if (rc) return rc;
     ARG_CHECK(q != nullptr, "q is NULL");
-    if (mode != RBE_SELECT_EXACT) {
-        set_error("rbe_search_float is built for RBE_SELECT_EXACT only");
+    if (c.mode != RBE_SELECT_EXACT) {
+        set_error("fp32 queries have no per-thread-queue scan: use the default near-lossless path (rbe_debug_set_nearlossless_path 0)");
         return RBE_EUNSUPPORTED;
     }
     for (size_t i = 0; i < (size_t)c.Q * ix->dim; ++i)
         if (!std::isfinite(q[i])) { set_error("q[%zu][%zu] is not finite", i / ix->dim, i % ix->dim); return RBE_EINVAL; }
-    c.batch_mfma = use_batch_mfma(ix, c.Q, mode, true);
+    c.batch_mfma = use_batch_mfma(ix, c.Q, c.mode, true);
     if (c.batch_mfma) {
         // several queries: the same dense contraction as for binary queries, with the query itself as operand
         c.float_batch = true;
@@ -1611,6 +1647,14 @@ int rbe_debug_set_progressive(rbe_index* ix, int enabled)
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
     ix->progressive = enabled == 2 ? 2 : (enabled ? 1 : 0);
+    return RBE_OK;
+}
+
+int rbe_debug_set_nearlossless_path(rbe_index* ix, int path)
+{
+    ARG_CHECK(ix != nullptr, "index is NULL");
+    ARG_CHECK(path == 0 || path == 1, "path must be 0 (exact scans + selection by groups) or 1 (per-thread-queue scan)");
+    ix->nl_path = path;
     return RBE_OK;
 }
 

@@ -217,6 +217,122 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
     }
 }
 
+// ---------------------------------------------------------------- near-lossless selection by groups
+// Algorithm 1 (Sec. 6.2) forwards, from every group of ids g(z) = (z div (256 I)) * 256 + (z mod 256), only the
+// best QL items (QL = 1 in the paper) and returns the best k of what was forwarded.  An item below a lower bound
+// tau of the k-th best forwarded item can be neither in the result nor change what another group forwards, so the
+// candidates of the exact scans (every item >= tau) hold everything that matters, and the selector reduces to:
+// keep the best QL candidates of every group, then select as usual.  Two kernels do the first part on the
+// candidate list of each query, in place:
+//   group_best_build    every candidate goes into an open-addressing table keyed by its group (the group follows
+//                       from the id inside the key); a slot keeps the largest and second largest key of its group
+//   group_best_compact  the table's entries become the new candidate list; slots are zeroed on the way, so the
+//                       table is clean for the next level
+// Keys are distinct and ordered by (score desc, id asc), so "largest key" is the group's best item with the lowest
+// id among equal scores, as the per-thread queue of Algorithm 1 keeps it.
+struct GroupBestArgs {
+    uint64_t* cand;        // [Q][cap]
+    uint32_t* count;       // [Q] x kCountStride: in: appended so far; out: entries after the reduction
+    uint32_t cap;
+    uint64_t* table;       // [Q][slots][2]: best, second best key of the group that owns the slot (0 = empty)
+    uint32_t slots;        // power of two, at least 2 x cap
+    uint32_t* aux;         // [Q][4]: [0] entries written by group_best_compact, [1] workgroups finished
+    uint32_t group_span;   // 256 x I
+    uint32_t qlen;         // 1 or 2
+    uint32_t* status;      // bit 0 set if a query's count exceeded cap
+};
+
+__device__ __forceinline__ uint32_t key_group(uint64_t key, uint32_t span)
+{
+    const uint32_t id = ~(uint32_t)key;
+    return (id / span) * 256u + (id & 255u);
+}
+
+__global__ __launch_bounds__(256) void group_best_build(const GroupBestArgs a)
+{
+    const uint32_t q = blockIdx.y;
+    const uint32_t appended = a.count[q * kCountStride];
+    const uint32_t n = appended < a.cap ? appended : a.cap;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && appended > a.cap) atomicOr(a.status, kStatusOverflow);
+    const uint64_t* keys = a.cand + (size_t)q * a.cap;
+    unsigned long long* tbl = reinterpret_cast<unsigned long long*>(a.table + (size_t)q * a.slots * 2);
+    const uint32_t mask = a.slots - 1u;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        const unsigned long long key = keys[i];
+        const uint32_t g = key_group(key, a.group_span);
+        uint32_t slot = (g * 2654435761u) >> 7 & mask;
+        // at most `slots` probes: the table has twice as many slots as there are candidates
+        for (uint32_t probe = 0; probe < a.slots; ++probe, slot = (slot + 1u) & mask) {
+            unsigned long long cur = *reinterpret_cast<volatile unsigned long long*>(&tbl[2 * (size_t)slot]);
+            if (cur == 0ull) {
+                cur = atomicCAS(&tbl[2 * (size_t)slot], 0ull, key);
+                if (cur == 0ull) break;                                   // claimed the slot for this group
+            }
+            if (key_group(cur, a.group_span) != g) continue;              // another group's slot (it never changes hands)
+            const unsigned long long old = atomicMax(&tbl[2 * (size_t)slot], key);
+            // every key of the group except its largest is offered to the second place exactly once: here when it
+            // loses on arrival, or when a later key displaces it
+            if (a.qlen == 2) atomicMax(&tbl[2 * (size_t)slot + 1], old < key ? old : key);
+            break;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void group_best_compact(const GroupBestArgs a)
+{
+    const uint32_t q = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    uint64_t* keys = a.cand + (size_t)q * a.cap;
+    uint64_t* tbl = a.table + (size_t)q * a.slots * 2;
+    uint32_t* aux = a.aux + q * 4;
+    for (uint32_t base = blockIdx.x * blockDim.x; base < a.slots; base += gridDim.x * blockDim.x) {   // whole waves together
+        const uint32_t slot = base + threadIdx.x;
+        uint64_t k0 = 0, k1 = 0;
+        if (slot < a.slots) {
+            k0 = tbl[2 * (size_t)slot];
+            if (k0) {
+                tbl[2 * (size_t)slot] = 0;
+                if (a.qlen == 2) { k1 = tbl[2 * (size_t)slot + 1]; tbl[2 * (size_t)slot + 1] = 0; }
+            }
+        }
+        const uint32_t mine = (k0 ? 1u : 0u) + (k1 ? 1u : 0u);
+        // wave-wide: one atomic reserves room for the entries of all 64 lanes
+        uint32_t incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(incl, d);
+            if (lane >= d) incl += o;
+        }
+        const uint32_t total = __shfl(incl, 63);
+        uint32_t start = 0;
+        if (total) {
+            if (lane == 63) start = atomicAdd(&aux[0], total);
+            start = __shfl(start, 63);
+            uint32_t pos = start + incl - mine;      // never beyond cap: at most one entry per candidate read
+            if (k0) keys[pos++] = k0;
+            if (k1) keys[pos] = k1;
+        }
+    }
+    // the workgroup that finishes last publishes the new count and leaves the counters clean
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t done = atomicAdd(&aux[1], 1u);
+        if (done == gridDim.x - 1) {
+            __threadfence();
+            a.count[q * kCountStride] = atomicExch(&aux[0], 0u);
+            aux[1] = 0;
+        }
+    }
+}
+
+// Zeroes `n` 16-byte units (the group tables and their counters at the start of a search).
+__global__ __launch_bounds__(256) void fill_zero16(u32x4* __restrict__ dst, size_t n)
+{
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = z;
+}
+
 __global__ void init_state(uint32_t* count, uint64_t* tau, uint64_t* kmax, uint32_t* status, uint32_t n_queries)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
