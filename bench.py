@@ -375,7 +375,18 @@ def main():
             "recall_vs_exact_mean": float(np.mean(recalls)), "recall_vs_exact_min": float(np.min(recalls)),
             "recall_predicted_appendix_a": predicted, "queries": len(recalls),
         }
+        out["near_lossless"]["scan_kernel_per_level"] = rn["stats"]["scan_kernel"]
         log(f"near-lossless I={I}: {n_ms:.3f} ms/step, recall {np.mean(recalls):.5f} (Appendix A: {predicted:.5f})")
+        # the same searches on the scan that keeps one queue per thread as Algorithm 1 is written (every plane read)
+        rbe.rbe_debug_set_nearlossless_path(ix, 1)
+        steps_q = max(2, args.steps // 4)
+        rq = timed_searches(rbe, torch, ix, qp1, qs1, 1, k, steps_q, args.warmup, rbe.RBE_SELECT_NEARLOSSLESS, I)
+        rbe.rbe_debug_set_nearlossless_path(ix, 0)
+        out["near_lossless"]["per_thread_queue_scan"] = {
+            "steps": steps_q, "ms_per_step": rq["wall_s"] * 1e3 / steps_q,
+            "scan_kernel_ms": float(rq["scan_ms"].mean()) if rq["scan_ms"].size else None,
+            "same_ids": bool(all(np.array_equal(x, y) for x, y in zip(rq["ids"], rn["ids"])))}
+        log(f"near-lossless I={I}, per-thread-queue scan: {rq['wall_s'] * 1e3 / steps_q:.3f} ms/step")
         # the same selector with priority queues of length 2 (Algorithm 1 leaves the length open)
         steps2 = max(2, args.steps // 2)
         rn2 = timed_searches(rbe, torch, ix, qp1, qs1, 1, k, steps2, args.warmup, rbe.RBE_SELECT_NEARLOSSLESS_Q2, I)
@@ -494,6 +505,41 @@ def main():
             log(f"Q={B}, XOR/popcount kernel, progressive: {rvp['wall_s'] * 1e3 / steps_v:.3f} ms/step, scan kernel {rvp['scan_ms'].mean():.3f} ms")
             log(f"Q={B}, XOR/popcount kernel, every plane: {v_ms:.3f} ms/step (per step {np.round(rv['per_step_ms'], 2).tolist()}), scan kernel {v_scan:.3f} ms "
                 f"-> {v_ach:.1f} T lane-ops/s")
+
+    # ---------------- what instruction issue alone allows the two batch kernels (no memory traffic: every tile is
+    # gone over 200 times from registers / LDS), as the ceiling their rooflines are priced against
+    if args.batch >= 3 and want("batch"):
+        B = args.batch
+        qpi, qsi = make_queries(rbe, rbe_synth, torch, centres, B, args.sigma, P, 9)
+        ceil = {}
+        for kernel, name in ((0, "scan_exact"), (1, "scan_batch_mfma")):
+            if kernel == 1 and not (B >= 7 and W <= 2):
+                continue
+            rbe.rbe_debug_issue_rate(ix, qpi, qsi, kernel, 20)                      # warm-up
+            runs = [rbe.rbe_debug_issue_rate(ix, qpi, qsi, kernel, 200) for _ in range(3)]
+            ms_i, pairs_i = min(runs)
+            ceil[name] = {"ms": ms_i, "pairs": pairs_i, "pairs_per_s": pairs_i / (ms_i * 1e-3)}
+        if "scan_exact" in ceil:
+            c0 = ceil["scan_exact"]
+            c0["lane_ops_per_pair"] = lane_ops_per_pair(W, P, P)
+            c0["t_lane_ops_per_s"] = c0["pairs_per_s"] * c0["lane_ops_per_pair"] / 1e12
+            c0["modelled_peak_t_lane_ops_per_s"] = VALU_PEAK_TLANEOPS
+            log(f"issue ceiling, XOR/popcount batch scan: {c0['t_lane_ops_per_s']:.2f} T lane-ops/s "
+                f"({c0['pairs_per_s'] / 1e9:.1f} G pairs/s; modelled {VALU_PEAK_TLANEOPS:.2f})")
+            if "batch_popcount_kernel" in out:
+                rf = out["batch_popcount_kernel"]["roofline"]
+                rf["issue_ceiling_t_lane_ops_per_s"] = c0["t_lane_ops_per_s"]
+                rf["frac_of_issue_ceiling"] = rf["achieved"] / c0["t_lane_ops_per_s"]
+        if "scan_batch_mfma" in ceil:
+            c1 = ceil["scan_batch_mfma"]
+            c1["tflops_algorithmic"] = c1["pairs_per_s"] * 2 * d * P / 1e12
+            log(f"issue ceiling, matrix-core scan (first look): {c1['pairs_per_s'] / 1e9:.1f} G pairs/s = "
+                f"{c1['tflops_algorithmic']:.0f} TFLOP/s algorithmic")
+            if "batch" in out and out["batch"]["roofline"].get("bound") == "mfma":
+                rf = out["batch"]["roofline"]
+                rf["issue_ceiling_tflops"] = c1["tflops_algorithmic"]
+                rf["frac_of_issue_ceiling"] = rf["achieved"] / c1["tflops_algorithmic"]
+        out["issue_ceilings"] = ceil
 
     # ---------------- CPU baseline: the oracle, as it stands, on a bounded sample: one thread, then one thread per
     # host core over disjoint item ranges (the oracle's own code is unchanged and single-threaded)

@@ -146,6 +146,20 @@ int rbe_debug_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_s
  * read ceiling the scan is compared with.  Asynchronous on the stream.         */
 int rbe_debug_read(const void *src_dev, size_t bytes, void *sink_dev, size_t sink_bytes, void *hip_stream);
 
+/* Measurement yardstick for the batch scans: the instruction mix of a scan free of
+ * memory traffic.  Launches the last-level kernel of a batched exact search --
+ * kernel 0: the XOR/popcount scan, every plane of every pair; kernel 1: the
+ * matrix-core scan (its first look; general scales leave the last plane out) --
+ * with one tile per workgroup of a full grid, thresholds that no score reaches (so
+ * nothing is queued), and every tile gone over 1 + repeat times from registers / LDS
+ * without being loaded again.  *ms_out = HIP-event time of the launch(es) on the
+ * stream, *pairs_out = (query, item) pairs scored.  The rate is the ceiling that
+ * vector- and matrix-instruction issue put on that kernel; the same kernel over a
+ * corpus in HBM is compared with it.  Queries as for rbe_search (3..64 of them).   */
+int rbe_debug_issue_rate(rbe_index *ix, const uint64_t *q_planes, const float *q_scales,
+                         uint32_t n_queries, uint32_t q_n_planes, uint32_t kernel,
+                         uint32_t repeat, float *ms_out, uint64_t *pairs_out, void *hip_stream);
+
 /* What rbe_finalize decided for an index: out[0] = 1 if the pruning scans may be
  * used (no negative scale), out[1] = 1 if it holds the one-byte scale copies,
  * out[2] = 1 if it lives in caller-owned storage, out[3] = 1 if a caller-owned

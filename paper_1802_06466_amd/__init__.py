@@ -79,6 +79,7 @@ PROTOTYPES = {
     "rbe_workspace_bytes": (ctypes.c_size_t, [_vp, _u32, _u32, _u32]),
     "rbe_set_workspace": (_i32, [_vp, _vp, ctypes.c_size_t]),
     "rbe_debug_index_info": (_i32, [_vp, _vp]),
+    "rbe_debug_issue_rate": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_search_float": (_i32, [_vp, _vp, _u32, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_debug_scores_float": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
     "rbe_set_profiling": (_i32, [_vp, _i32]),
@@ -259,6 +260,21 @@ def rbe_set_workspace(ix: Index, workspace):
         _check(load_library().rbe_set_workspace(ix.handle, _vp(workspace.data_ptr()),
                                                 workspace.numel() * workspace.element_size()))
     ix._ws = workspace
+
+
+def rbe_debug_issue_rate(ix: Index, q_planes, q_scales, kernel: int, repeat: int, stream=None):
+    """(ms, pairs) of one launch of a batch scan going over its tiles 1 + repeat times without reloading them
+    (kernel 0 = XOR/popcount batch scan, 1 = matrix-core scan): the kernel's instruction mix free of memory traffic."""
+    qp, qpp = _host(q_planes, np.uint64)
+    Q, Pq = qp.shape[:2]
+    qsp = None
+    if q_scales is not None:
+        qs, qsp = _host(q_scales, np.float32)
+    ms = ctypes.c_float(0.0)
+    pairs = ctypes.c_uint64(0)
+    _check(load_library().rbe_debug_issue_rate(ix.handle, qpp, qsp, Q, Pq, kernel, repeat, ctypes.byref(ms),
+                                               ctypes.byref(pairs), _stream_ptr(stream)))
+    return float(ms.value), int(pairs.value)
 
 
 def rbe_debug_index_info(ix: Index) -> dict:

@@ -1173,6 +1173,7 @@ struct SearchCtx {
     bool batch_mfma;    // exact mode, several queries: matrix-core scan
     bool float_batch;   // ... of full-precision queries
     uint32_t look_from = 0;   // matrix-core scan: the levels from this one on report how their first looks went
+    uint32_t calib_repeat = 0;   // rbe_debug_issue_rate: the batch scans go over what they loaded this many more times
 };
 
 // dense: a coarse level of the plan, where a large share of the items passes the (still loose) threshold.
@@ -1215,7 +1216,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         ba.a_ops = ix->ws.aops; ba.q_unscale = ix->ws.unscale; ba.q_bias = ix->ws.unscale + RBE_MAX_QUERIES; ba.q_mass = ix->ws.unscale + 2 * RBE_MAX_QUERIES; ba.tau = ix->ws.tau;
         ba.look_stats = level_slot >= c.look_from ? ix->ws.status + 12 : nullptr;
         ba.row_amax = ix->d_row_amax; ba.row_asum = ix->d_row_amax ? ix->d_row_amax + (size_t)ix->layout.n_tiles * (kTileItems / kRow) : nullptr; ba.n_queries = c.Q;
-        ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end;
+        ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end; ba.calib_repeat = c.calib_repeat;
         ba.rescore = batch_rescore(ix, c.float_batch);
         ba.PQ = c.PQ; ba.qwords = ix->ws.qwords; ba.qcoef = ix->ws.qcoef; ba.lut = ix->ws.lut; ba.margin = ix->batch_margin;
         e = hipSuccess;
@@ -1243,6 +1244,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
         sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);
+        sa.calib_repeat = c.calib_repeat;
         e = launch_scan_exact(ix->W, sel, sa, (uint32_t)ix->n_cu, ix->blocks_per_cu, c.st, &grid);
     } else {
         GroupArgs ga;
@@ -1281,8 +1283,8 @@ static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_
         const uint32_t blocks = std::min<uint32_t>((uint32_t)ix->n_cu * 4u, (c.cap + 255u) / 256u);
         hipLaunchKernelGGL(rbe::group_best_build, dim3(blocks, c.Q), dim3(256), 0, c.st, ga);
         HIP_TRY(hipGetLastError());
-        hipLaunchKernelGGL(rbe::group_best_compact, dim3(std::min<uint32_t>((uint32_t)ix->n_cu * 4u, ga.slots / 256u), c.Q), dim3(256),
-                           0, c.st, ga);
+        hipLaunchKernelGGL(rbe::group_best_compact, dim3(std::min<uint32_t>((uint32_t)ix->n_cu * 2u, (ga.slots + 2047u) / 2048u), c.Q),
+                           dim3(256), 0, c.st, ga);
         HIP_TRY(hipGetLastError());
     }
 
@@ -1290,6 +1292,7 @@ static int run_round(const SearchCtx& c, const Round& r, int final_pass, uint32_
     se.cand = ix->ws.cand; se.count = ix->ws.count; se.tau = ix->ws.tau; se.kmax = ix->ws.kmax; se.cap = c.cap; se.k = c.k;
     se.status = ix->ws.status; se.count_seen = ix->ws.seen + (size_t)level_slot * RBE_MAX_QUERIES;
     se.final_pass = final_pass; se.ids_out = ix->ws.ids; se.scores_out = ix->ws.scores;
+    se.group_aux = c.group_select ? ix->ws.gaux : nullptr;
     hipLaunchKernelGGL(rbe::select_topk, dim3(c.Q), dim3(kSelBlock), 0, c.st, se);
     HIP_TRY(hipGetLastError());
     if (record) HIP_TRY(hipEventRecord(ix->ev[2 * level_slot + 2], c.st));
@@ -1621,6 +1624,58 @@ int rbe_debug_query_mass(const uint64_t* q_planes, const float* q_scales, uint32
     if (!dyadic)
         for (uint32_t i = 0; i < q_n_planes; ++i) ARG_CHECK(std::isfinite(q_scales[i]), "q_scales[%u] is not finite", i);
     query_mass(q_planes, dyadic ? nullptr : q_scales, q_n_planes, dim, dyadic != 0, mass_out);
+    return RBE_OK;
+}
+
+int rbe_debug_issue_rate(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t n_queries,
+                         uint32_t q_n_planes, uint32_t kernel, uint32_t repeat, float* ms_out, uint64_t* pairs_out,
+                         void* hip_stream)
+{
+    ARG_CHECK(ms_out && pairs_out, "NULL output argument");
+    ARG_CHECK(kernel <= 1, "kernel must be 0 (XOR/popcount batch scan) or 1 (matrix-core scan)");
+    ARG_CHECK(repeat >= 1 && repeat <= 100000, "repeat must be 1..100000");
+    SearchCtx c;
+    int64_t ids_dummy = 0;
+    float scores_dummy = 0.0f;
+    int rc = search_prologue(ix, c, n_queries, 1, RBE_SELECT_EXACT, 0, &ids_dummy, &scores_dummy, hip_stream);
+    if (rc) return rc;
+    ARG_CHECK(q_planes != nullptr, "q_planes is NULL");
+    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes must be 1..%u", RBE_MAX_PLANES);
+    ARG_CHECK(n_queries >= 3, "the batch scans take 3 or more queries here");
+    if (kernel == 1 && (!rbe::batch_mfma_supported(ix->W) || !can_prune(ix))) {
+        set_error("no matrix-core scan for this index");
+        return RBE_EUNSUPPORTED;
+    }
+    c.PQ = q_n_planes;
+    rc = stage_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
+    if (rc) return rc;
+    c.batch_mfma = kernel == 1;
+    if (c.batch_mfma) {
+        rc = stage_batch_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
+        if (rc) return rc;
+    }
+    c.calib_repeat = repeat;
+    hipLaunchKernelGGL(rbe::init_state, dim3(1), dim3(64), 0, c.st, ix->ws.count, ix->ws.tau, ix->ws.kmax, ix->ws.status, c.Q);
+    HIP_TRY(hipGetLastError());
+    // thresholds no score reaches: the launch runs the scoring arithmetic and queues nothing
+    hipLaunchKernelGGL(rbe::fill_u64, dim3(1), dim3(64), 0, c.st, ix->ws.tau, (uint32_t)c.Q, 0xFF800000FFFFFFFFull);   // the key of +infinity
+    HIP_TRY(hipGetLastError());
+    // one tile per workgroup of a full grid (fewer if the corpus is smaller), each gone over 1 + repeat times
+    const uint32_t want = (uint32_t)ix->n_cu * 4u;
+    const Round r{0u, std::min(ix->layout.n_tiles, want), 1u, 0u};
+    const int saved_path = ix->batch_path, saved_prog = ix->progressive;
+    ix->batch_path = kernel == 1 ? 2 : 1;
+    ix->progressive = 0;            // the plain batch form of scan_exact (every plane of every pair)
+    ix->stats = rbe_search_stats{};
+    hipError_t e = hipEventRecord(ix->ev[0], c.st);
+    if (e == hipSuccess) { rc = launch_scan_round(c, r, false, 0); }
+    if (e == hipSuccess && !rc) e = hipEventRecord(ix->ev[1], c.st);
+    if (e == hipSuccess && !rc) e = hipStreamSynchronize(c.st);
+    ix->batch_path = saved_path; ix->progressive = saved_prog;
+    if (rc) return rc;
+    HIP_TRY(e);
+    HIP_TRY(hipEventElapsedTime(ms_out, ix->ev[0], ix->ev[1]));
+    *pairs_out = (uint64_t)(r.end - r.begin) * kTileItems * (1ull + repeat) * c.Q;
     return RBE_OK;
 }
 

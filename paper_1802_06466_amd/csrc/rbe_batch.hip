@@ -103,7 +103,9 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
 // scan scores it: RS = 1, binary queries, in the arithmetic of the XOR/popcount scan; RS = 2, fp32 queries, from
 // the byte tables of the hybrid scan.  Half the MFMAs, and results that do not depend on how many queries share
 // a call.
-template <int W, int P, int MODE, int NQT, int RS>
+// CALIB: the measurement variant (BatchArgs::calib_repeat), a separate instantiation so that the scan proper carries
+// none of it.
+template <int W, int P, int MODE, int NQT, int RS, bool CALIB = false>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu((NQT == 1 && W == 1 && P <= 3) ? 3 : 1)))
 void scan_batch_mfma(const BatchArgs a)
 {
@@ -195,11 +197,14 @@ void scan_batch_mfma(const BatchArgs a)
     RawRow<W, P, S> cur, nxt;
     int seg = 0;
     load_raw<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, seg, lane);
+    uint32_t calib_left = CALIB ? a.calib_repeat : 0u;   // measurement variant: segments to go through again without loading them
     for (;;) {
-        const int segn = seg + 1 == SEG ? 0 : seg + 1;
-        const uint32_t pn = segn == 0 ? p + G : p;
-        const bool has_next = pn < a.p_end;
-        if (has_next) load_raw<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, segn, lane);
+        const bool again = CALIB && calib_left != 0;     // wave-uniform
+        const int segn = again ? seg : (seg + 1 == SEG ? 0 : seg + 1);
+        const uint32_t pn = again ? p : (segn == 0 ? p + G : p);
+        const bool has_next = again || pn < a.p_end;
+        if (again) { --calib_left; nxt = cur; }
+        else if (has_next) load_raw<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, segn, lane);
 
         // stage the segment in this wave's LDS area, in item order
 #pragma unroll
@@ -451,9 +456,13 @@ namespace {
 using BatchFn = void (*)(const BatchArgs);
 
 template <int W, int P, int MODE>
-BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore)
+BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, bool calib)
 {
     if constexpr (MODE == kModeScaled) {
+        if (calib) {            // built for binary queries on general scales
+            if (rescore != 1) return nullptr;
+            return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1, true> : (nqt == 2 ? scan_batch_mfma<W, P, MODE, 2, 1, true> : nullptr);
+        }
         if (rescore == 1) {
             switch (nqt) {
                 case 1: return scan_batch_mfma<W, P, MODE, 1, 1>;
@@ -470,7 +479,7 @@ BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore)
         }
         return nullptr;
     } else {
-        if (rescore != 0) return nullptr;
+        if (rescore != 0 || calib) return nullptr;
         switch (nqt) {
             case 1: return scan_batch_mfma<W, P, MODE, 1, 0>;
             case 2: return scan_batch_mfma<W, P, MODE, 2, 0>;
@@ -480,12 +489,12 @@ BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore)
 }
 
 template <int W, int P>
-BatchFn batch_fn_m(int mode, uint32_t nqt, uint32_t rescore)
+BatchFn batch_fn_m(int mode, uint32_t nqt, uint32_t rescore, bool calib)
 {
     switch (mode) {
-        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore);
-        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0);
-        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0);
+        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore, calib);
+        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0, calib);
+        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0, calib);
         default: return nullptr;
     }
 }
@@ -497,10 +506,10 @@ hipError_t launch_scan_batch_w<RBE_W>(const KernelSel& k, const BatchArgs& a, ui
 {
     BatchFn fn = nullptr;
     switch (k.P) {
-        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore); break;
-        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore); break;
-        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore); break;
-        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore); break;
+        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore, a.calib_repeat != 0); break;
+        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore, a.calib_repeat != 0); break;
+        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore, a.calib_repeat != 0); break;
+        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore, a.calib_repeat != 0); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;

@@ -488,6 +488,8 @@ struct ScanArgs {
     const uint32_t* hints;    // general scales: one-byte copies of the scale arrays 0 .. P-2 in lane order (scale_hints)
     int hint_base[3];         // ... and the exponent base of each array's hints
     uint32_t stage_entries;   // several queries: LDS queue entries per wave (512..4096), split into sub-queues
+    uint32_t calib_repeat;    // measurement only (batch form of scan_exact): every tile is scored this many more times
+                              // without being loaded again, so the launch runs the scan's arithmetic free of memory traffic
 };
 
 // Hybrid scoring (fp32 query against RBE items, the paper's model m_5, Sec. 8.1): one query per
@@ -546,6 +548,8 @@ struct BatchArgs {
     float margin;
     CandList out;
     uint32_t p_begin, p_end;
+    uint32_t calib_repeat;    // measurement only: every row is staged and contracted this many more times without being
+                              // loaded again (the kernel's instruction mix free of memory traffic)
 };
 
 struct GroupArgs {

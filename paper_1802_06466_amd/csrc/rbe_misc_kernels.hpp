@@ -27,6 +27,8 @@ struct SelectArgs {
     int final_pass;
     int64_t* ids_out;    // [Q][k]   (final pass; sorted)
     float* scores_out;   // [Q][k]
+    uint32_t* group_aux; // near-lossless modes: [Q][4], [0] = entries group_best_compact left in the list (read in place of
+                         // `count` and zeroed here); null otherwise
 };
 
 // Inclusive prefix sum over the 1024 threads of the select workgroup.
@@ -84,9 +86,13 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
     const uint32_t q = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     uint64_t* keys = a.cand + (size_t)q * a.cap;
-    const uint32_t appended = a.count[q * kCountStride];
+    const uint32_t appended = a.group_aux ? a.group_aux[q * 4] : a.count[q * kCountStride];
     const uint32_t n = appended < a.cap ? appended : a.cap;
     const uint32_t k = a.k;
+    if (a.group_aux) {
+        __syncthreads();                          // every thread has read the counter
+        if (tid == 0) { a.group_aux[q * 4] = 0; a.count[q * kCountStride] = n; }
+    }
     if (tid == 0) {
         a.count_seen[q] = appended;
         if (appended > a.cap) atomicOr(a.status, kStatusOverflow);
@@ -226,8 +232,8 @@ __global__ __launch_bounds__(kSelBlock) void select_topk(const SelectArgs a)
 // candidate list of each query, in place:
 //   group_best_build    every candidate goes into an open-addressing table keyed by its group (the group follows
 //                       from the id inside the key); a slot keeps the largest and second largest key of its group
-//   group_best_compact  the table's entries become the new candidate list; slots are zeroed on the way, so the
-//                       table is clean for the next level
+//   group_best_compact  the table's entries become the new candidate list (its length goes to select_topk through a
+//                       counter); slots are zeroed on the way, so the table is clean for the next level
 // Keys are distinct and ordered by (score desc, id asc), so "largest key" is the group's best item with the lowest
 // id among equal scores, as the per-thread queue of Algorithm 1 keeps it.
 struct GroupBestArgs {
@@ -236,7 +242,7 @@ struct GroupBestArgs {
     uint32_t cap;
     uint64_t* table;       // [Q][slots][2]: best, second best key of the group that owns the slot (0 = empty)
     uint32_t slots;        // power of two, at least 2 x cap
-    uint32_t* aux;         // [Q][4]: [0] entries written by group_best_compact, [1] workgroups finished
+    uint32_t* aux;         // [Q][4]: [0] entries written by group_best_compact (select_topk takes the count from there)
     uint32_t group_span;   // 256 x I
     uint32_t qlen;         // 1 or 2
     uint32_t* status;      // bit 0 set if a query's count exceeded cap
@@ -280,50 +286,61 @@ __global__ __launch_bounds__(256) void group_best_build(const GroupBestArgs a)
 
 __global__ __launch_bounds__(256) void group_best_compact(const GroupBestArgs a)
 {
+    constexpr int kPer = 8;                      // slots per thread and step: 2048 per workgroup
+    __shared__ uint32_t s_wave[4];
+    __shared__ uint32_t s_start;
     const uint32_t q = blockIdx.y;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint64_t* keys = a.cand + (size_t)q * a.cap;
     uint64_t* tbl = a.table + (size_t)q * a.slots * 2;
     uint32_t* aux = a.aux + q * 4;
-    for (uint32_t base = blockIdx.x * blockDim.x; base < a.slots; base += gridDim.x * blockDim.x) {   // whole waves together
-        const uint32_t slot = base + threadIdx.x;
-        uint64_t k0 = 0, k1 = 0;
-        if (slot < a.slots) {
-            k0 = tbl[2 * (size_t)slot];
-            if (k0) {
-                tbl[2 * (size_t)slot] = 0;
-                if (a.qlen == 2) { k1 = tbl[2 * (size_t)slot + 1]; tbl[2 * (size_t)slot + 1] = 0; }
+    // one returning atomic per 2048 slots: with one per wave, the 8192 atomics on this one counter were the
+    // kernel's whole run time
+    for (uint32_t base = blockIdx.x * (256u * kPer); base < a.slots; base += gridDim.x * (256u * kPer)) {
+        uint64_t k0[kPer], k1[kPer];
+        uint32_t mine = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const uint32_t slot = base + (uint32_t)i * 256u + threadIdx.x;
+            k0[i] = 0; k1[i] = 0;
+            if (slot < a.slots) {
+                k0[i] = tbl[2 * (size_t)slot];
+                if (k0[i]) {
+                    tbl[2 * (size_t)slot] = 0;
+                    if (a.qlen == 2) { k1[i] = tbl[2 * (size_t)slot + 1]; tbl[2 * (size_t)slot + 1] = 0; }
+                }
             }
+            mine += (k0[i] ? 1u : 0u) + (k1[i] ? 1u : 0u);
         }
-        const uint32_t mine = (k0 ? 1u : 0u) + (k1 ? 1u : 0u);
-        // wave-wide: one atomic reserves room for the entries of all 64 lanes
         uint32_t incl = mine;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const uint32_t o = __shfl_up(incl, d);
             if (lane >= d) incl += o;
         }
-        const uint32_t total = __shfl(incl, 63);
-        uint32_t start = 0;
-        if (total) {
-            if (lane == 63) start = atomicAdd(&aux[0], total);
-            start = __shfl(start, 63);
-            uint32_t pos = start + incl - mine;      // never beyond cap: at most one entry per candidate read
-            if (k0) keys[pos++] = k0;
-            if (k1) keys[pos] = k1;
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { before += w < wave ? s_wave[w] : 0u; total += s_wave[w]; }
+        if (threadIdx.x == 0) s_start = total ? atomicAdd(&aux[0], total) : 0u;
+        __syncthreads();
+        uint32_t pos = s_start + before + incl - mine;      // never beyond cap: at most one entry per candidate read
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            if (k0[i]) keys[pos++] = k0[i];
+            if (k1[i]) keys[pos++] = k1[i];
         }
+        __syncthreads();                                    // s_wave and s_start are reused by the next step
     }
-    // the workgroup that finishes last publishes the new count and leaves the counters clean
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t done = atomicAdd(&aux[1], 1u);
-        if (done == gridDim.x - 1) {
-            __threadfence();
-            a.count[q * kCountStride] = atomicExch(&aux[0], 0u);
-            aux[1] = 0;
-        }
-    }
+    // (no hand-off inside the kernel: a device-wide fence per workgroup costs a write-back of the whole L2 on this
+    // chip; the selection that follows reads aux[0] as the new count and zeroes it)
+}
+
+__global__ void fill_u64(uint64_t* __restrict__ dst, uint32_t n, uint64_t value)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = value;
 }
 
 // Zeroes `n` 16-byte units (the group tables and their counters at the start of a search).

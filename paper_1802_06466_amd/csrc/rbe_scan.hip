@@ -119,17 +119,19 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
             // do not start scoring piecemeal as individual loads land: that keeps every partial
             // popcount of the tile alive at once and overflows the register file
             __builtin_amdgcn_sched_barrier(0);
-            QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
-            uint64_t tau_n = a.tau[0];
-            for (uint32_t q = 0; q < nq; ++q) {
-                const QueryRegs<W, PQ> qr = qn;
-                const uint64_t tau = tau_n;
-                if (q + 1 < nq) {
-                    qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
-                    tau_n = a.tau[q + 1];
+            for (uint32_t rep = 0; rep <= a.calib_repeat; ++rep) {      // (once, except in the measurement mode)
+                QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+                uint64_t tau_n = a.tau[0];
+                for (uint32_t q = 0; q < nq; ++q) {
+                    const QueryRegs<W, PQ> qr = qn;
+                    const uint64_t tau = tau_n;
+                    if (q + 1 < nq) {
+                        qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
+                        tau_n = a.tau[q + 1];
+                    }
+                    fill = score_and_stage<W, P, PQ, SINGLE, MODE>(cur, qr, tau, threshold_score(tau), q, p, wave, lane,
+                                                             s_keys, ms, fill, a);
                 }
-                fill = score_and_stage<W, P, PQ, SINGLE, MODE>(cur, qr, tau, threshold_score(tau), q, p, wave, lane,
-                                                         s_keys, ms, fill, a);
             }
         }
     }

@@ -343,6 +343,62 @@ def test_matrix_core_filter_operands_stay_within_their_margin(lib, kind):
     assert worst > 0                                     # the halves really are roundings
 
 
+@pytest.mark.parametrize("kind", ["binary", "fp32"])
+def test_matrix_core_filter_at_the_margin_never_drops_a_survivor(lib, kind):
+    """Adversarial case for the matrix-core filter (general scales).  The contraction is linear in the item bits,
+    so per dimension its coefficient can be read off, and the item plane that makes (contraction - true value) as
+    negative as possible can be written down: the filter then under-estimates by nearly the whole margin.  Such
+    planes in positions 0 .. P-2, the plane that attains the query's mass in the last position, the row's largest
+    last scale on that item, and a threshold EQUAL to the item's own score: the first look (last plane left out,
+    row-wide threshold in fp32 as the kernel forms it) and the second look must both let the pair through."""
+    rng = np.random.default_rng(77)
+    dim, P, Pq, Q = 64, 3, 3, 16
+    W = dim // 64
+    if kind == "binary":
+        qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
+        qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
+        halves, unscale, start, margin = rbe.rbe_debug_batch_operands(qp, qs, dim, P, False)
+        qbits = ((qp[:, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
+        qhat = (qs.astype(np.float64)[:, :, None, None] * (2 * qbits - 1)).sum(axis=1).reshape(Q, dim)
+    else:
+        qf = rng.standard_normal((Q, dim)).astype(np.float32)
+        halves, unscale, start, margin = rbe.rbe_debug_batch_operands(None, None, dim, P, False, q_float=qf)
+        qhat = qf.astype(np.float64)
+    A = _halves_to_float(halves)
+    f32 = np.float32
+    tight = []
+    for q in range(Q):
+        v = qhat[q] / float(unscale[q])
+        zero = float(start[q]) + _emulated_contraction(A, start, q, np.zeros(dim, dtype=np.int64), 2 * W)
+        coef = np.array([float(start[q]) + _emulated_contraction(A, start, q, np.eye(dim, dtype=np.int64)[i], 2 * W) - zero
+                         for i in range(dim)])
+        # contraction(b) - true(b) = (zero + sum v) + sum_d (coef_d - 2 v_d) b_d : most negative with b_d = [coef_d < 2 v_d]
+        low = (coef < 2 * v).astype(np.int64)
+        worst_under = (zero + v.sum()) + ((coef - 2 * v) * low).sum()
+        assert -margin <= worst_under <= 0
+        tight.append(-worst_under / margin)
+        best_last = (v > 0).astype(np.int64)                      # attains sum_d |v_d|
+        mass = np.abs(v).sum()
+        qmass = f32(mass * (1 + 2.0 ** -20)); qmass = np.nextafter(qmass, f32(np.inf)) if float(qmass) < mass * (1 + 2.0 ** -20) else qmass
+        a = np.array([0.11, 0.052, 0.027], dtype=f32)            # decaying scales, the last one the row's largest
+        amax, smax = a[P - 1], f32(float(a.astype(np.float64).sum()) * (1 + 1e-6))
+        D = [f32(zero + (coef * low).sum())] * (P - 1)            # what the MFMAs deliver for the adversarial planes
+        DL = f32(zero + (coef * best_last).sum())
+        true = sum(float(a[j]) * float(v @ (2 * low - 1)) for j in range(P - 1)) + float(a[P - 1]) * mass
+        taus = f32(true)                                          # threshold = the pair's own score (scaled domain)
+        row_tau = f32(taus - f32(1.000001) * f32(np.float64(amax) * np.float64(qmass) + np.float64(f32(margin)) * np.float64(smax)))
+        first = f32(0.0)
+        for j in range(P - 1):
+            first = f32(np.float64(a[j]) * np.float64(D[j]) + np.float64(first))      # one rounding per fused multiply-add
+        assert first >= row_tau, (q, float(first), float(row_tau))
+        asum = f32(f32(a[P - 1] + a[0]) + a[1])
+        second = f32(f32(np.float64(a[P - 1]) * np.float64(DL) + np.float64(first)) + f32(f32(margin) * asum))
+        assert second >= taus, (q, float(second), float(taus))
+        # and it is a near miss: without the slack the first look would have dropped the pair
+        assert first < f32(taus - f32(np.float64(amax) * np.float64(qmass)) * f32(0.999)) or -worst_under < 0.02 * margin
+    assert max(tight) > 0.3, tight          # the adversarial plane comes within a factor of the margin: the bound is not slack by orders
+
+
 # ------------------------------------------------------------------ host logic: query mass of the progressive scan
 @pytest.mark.parametrize("dim,Pq", [(64, 1), (64, 3), (128, 4), (256, 2)])
 def test_query_mass_bounds_every_plane(lib, dim, Pq):

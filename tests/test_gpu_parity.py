@@ -1502,3 +1502,25 @@ def test_index_in_caller_owned_storage(flags):
     torch.cuda.synchronize()
     assert bool((buf[:guard] == 0x5A).all()) and bool((buf[guard + need:] == 0x5A).all()), "wrote outside the storage"
     assert int(buf[guard:guard + need].to(torch.int64).sum()) != 0x5A * need       # still readable, and was written
+
+
+def test_issue_rate_yardstick_runs_and_leaves_searches_untouched():
+    """rbe_debug_issue_rate launches the batch scans with unreachable thresholds over tiles they go over again and
+    again: it reports a time and the pairs scored, queues nothing, and later searches are unaffected."""
+    N, d, P, k = 300_000, 64, 3, 50
+    planes, scales, qp, qs = clustered(N, d, P, 256, 0.3, 16, P, seed=350)
+    ix = load_with_ratio(planes, scales, 8)
+    ref = rbe.rbe_search(ix, qp, qs, k)
+    n_tiles = -(-N // 1024)
+    for kernel in (0, 1):
+        ms, pairs = rbe.rbe_debug_issue_rate(ix, qp, qs, kernel, 7)
+        assert ms > 0 and pairs == min(n_tiles, 1024) * 1024 * 8 * 16
+        ms2, pairs2 = rbe.rbe_debug_issue_rate(ix, qp, qs, kernel, 15)
+        assert pairs2 == 2 * pairs and ms2 > 0
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_debug_issue_rate(ix, qp[:2], qs[:2], 0, 7)
+    got = rbe.rbe_search(ix, qp, qs, k)
+    np.testing.assert_array_equal(got[0], ref[0]); np.testing.assert_array_equal(got[1], ref[1])
+    got1 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    np.testing.assert_array_equal(got1[0][0], ref[0][0])
+    rbe.rbe_free(ix)
