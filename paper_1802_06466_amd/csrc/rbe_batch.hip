@@ -194,7 +194,7 @@ void scan_batch_mfma(const BatchArgs a)
 
     bool skip_last = kCanSkip;              // wave-uniform
     uint32_t blocks_seen = 0, second_looks = 0;
-    RawRow<W, P, S> cur, nxt;
+    RawRow<W, P, S> cur;
     int seg = 0;
     load_raw<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, seg, lane);
     uint32_t calib_left = CALIB ? a.calib_repeat : 0u;   // measurement variant: segments to go through again without loading them
@@ -203,9 +203,6 @@ void scan_batch_mfma(const BatchArgs a)
         const int segn = again ? seg : (seg + 1 == SEG ? 0 : seg + 1);
         const uint32_t pn = again ? p : (segn == 0 ? p + G : p);
         const bool has_next = again || pn < a.p_end;
-        if (again) { --calib_left; nxt = cur; }
-        else if (has_next) load_raw<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, segn, lane);
-
         // stage the segment in this wave's LDS area, in item order
 #pragma unroll
         for (int j = 0; j < P; ++j)
@@ -221,6 +218,11 @@ void scan_batch_mfma(const BatchArgs a)
                 s_sc[wave][j][SEG == 1 ? lane_item<W>(lane, m) : m * 64 + lane] = cur.sc[j][m];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        // the staged copy is what the segment is worked from: its registers are free for the next segment, whose
+        // loads stay in flight while this one is contracted (one register set instead of two)
+        __builtin_amdgcn_sched_barrier(0);
+        if (again) --calib_left;                // (the registers still hold the segment)
+        else if (has_next) load_raw<W, P, S>(cur, a.tiles + (size_t)pn * tile_bytes, wave, segn, lane);
 
         const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow +
                                 (uint64_t)seg * kSegItems;
@@ -441,7 +443,6 @@ void scan_batch_mfma(const BatchArgs a)
         __builtin_amdgcn_wave_barrier();
 
         if (!has_next) break;
-        cur = nxt;
         p = pn;
         seg = segn;
     }
