@@ -75,7 +75,10 @@ __global__ __launch_bounds__(kBlock) void scan_groupmax(const GroupArgs a)
         if (r < n_rows) load_row<W, P, S>(cur, row_tile(a, geom, row0 + r), (int)((row0 + r) & 3), lane);
         while (r < n_rows) {
             const uint32_t rn = r + kWavesPerBlock;
-            if (rn < n_rows) load_row<W, P, S>(nxt, row_tile(a, geom, row0 + rn), (int)((row0 + rn) & 3), lane);
+            // (prefetch not under a branch: the last step fetches its own row again, and the waits for this row's
+            // registers leave the loads just issued in flight)
+            const uint32_t rl = rn < n_rows ? rn : r;
+            load_row<W, P, S>(nxt, row_tile(a, geom, row0 + rl), (int)((row0 + rl) & 3), lane);
             const uint64_t row_id = (uint64_t)(row0 + r) * kRow;
             const bool tail = row_id + kRow > a.n_items;   // only the corpus' last row can hold missing slots
 #pragma unroll

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
         for (;;) {
             const uint32_t pn = p + G;
             const bool has_next = pn < a.p_end;
-            if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            load_row<W, P, S>(nxt, a.tiles + (size_t)(has_next ? pn : p) * tile_bytes, wave, lane);   // unconditional: see scan_exact_prog_hint
             fill = score_and_stage<W, P, PQ, SINGLE, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
             if (!has_next) break;
             cur = nxt;
@@ -299,16 +299,15 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
         const bool whole_next = deep * 4 > rows + 32;     // wave-uniform
-        if (has_next) {
-            const char* tn = a.tiles + (size_t)pn * tile_bytes;
-            load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
-            load_row_scales<W, P, S, 0, SS>(nxt, tn, wave, lane);
-            if (S > 0) amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
-            if (whole_next) {
-                load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
-                load_row_scales<W, P, S, SS, S>(nxt, tn, wave, lane);
-                extra8 += kRow * W + (S > 0 ? kRow / 2 : 0);
-            }
+        const uint32_t pl = has_next ? pn : p;      // prefetch not under a branch: see scan_exact_prog_hint
+        const char* tn = a.tiles + (size_t)pl * tile_bytes;
+        load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
+        load_row_scales<W, P, S, 0, SS>(nxt, tn, wave, lane);
+        if (S > 0) amax_n = a.row_amax[(size_t)pl * kWavesPerBlock + wave];
+        if (whole_next) {
+            load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+            load_row_scales<W, P, S, SS, S>(nxt, tn, wave, lane);
+            extra8 += has_next ? kRow * W + (S > 0 ? kRow / 2 : 0) : 0;
         }
         PartialScore part[kItemsPerLane];
         uint32_t mine = 0;     // which of this lane's items can still reach the threshold (a NaN bound does not prune)
@@ -459,11 +458,14 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
         if (passed * 4 > probed + 32) { plain = true; return false; }     // wave-uniform; this row is not done yet
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
-        if (has_next) {
-            load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
-            load_hints(hn, pn);
-            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
-        }
+        // The prefetch is not under a branch (a workgroup's last step fetches its own row once more): with
+        // `if (has_next)` around it the compiler, merging the path that loaded with the one that did not, makes
+        // the first use of THIS row's registers wait for half of the loads just issued -- every step then stalls
+        // for a memory round trip and nothing is prefetched.
+        const uint32_t pl = has_next ? pn : p;
+        load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_hints(hn, pl);
+        amax_n = a.row_amax[(size_t)pl * kWavesPerBlock + wave];
         bool reach = true;
         uint32_t mine = 0;     // which of this lane's items can still reach the threshold
         {
@@ -560,7 +562,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
         for (;;) {
             const uint32_t pn = p + G;
             const bool has_next = pn < a.p_end;
-            if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            load_row<W, P, S>(nxt, a.tiles + (size_t)(has_next ? pn : p) * tile_bytes, wave, lane);   // unconditional: see scan_exact_prog_hint
             fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
             ++full_rows;
             extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item beyond the stream's
@@ -647,11 +649,10 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanA
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
         const bool whole_next = passed * 4 > probed + 32 * nq;     // wave-uniform
-        if (has_next) {
-            load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
-            load_hints(hn, pn);
-            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
-        }
+        const uint32_t pl = has_next ? pn : p;      // prefetch not under a branch: see scan_exact_prog_hint
+        load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_hints(hn, pl);
+        amax_n = a.row_amax[(size_t)pl * kWavesPerBlock + wave];
         bool reach = true;
         uint32_t mine = (1u << kItemsPerLane) - 1u;     // which of this lane's items can still reach some query's threshold
         uint32_t row_pairs = nq;                         // queries for which some item of the row can
@@ -866,7 +867,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq(const FqArgs a)
     for (;;) {
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
-        if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+        load_row<W, P, S>(nxt, a.tiles + (size_t)(has_next ? pn : p) * tile_bytes, wave, lane);   // unconditional: see scan_exact_prog_hint
         float s[kItemsPerLane];
         bool any = false;
 #pragma unroll
@@ -925,15 +926,14 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
         const bool whole_next = deep * 4 > rows + 32;
-        if (has_next) {
-            const char* tn = a.tiles + (size_t)pn * tile_bytes;
-            load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
-            load_row_scales<W, P, S, 0, SS>(nxt, tn, wave, lane);
-            if (S > 0) amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
-            if (whole_next) {
-                load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
-                load_row_scales<W, P, S, SS, S>(nxt, tn, wave, lane);
-            }
+        const uint32_t pl = has_next ? pn : p;      // prefetch not under a branch: see scan_exact_prog_hint
+        const char* tn = a.tiles + (size_t)pl * tile_bytes;
+        load_row_planes<W, P, S, 0, F>(nxt, tn, wave, lane);
+        load_row_scales<W, P, S, 0, SS>(nxt, tn, wave, lane);
+        if (S > 0) amax_n = a.row_amax[(size_t)pl * kWavesPerBlock + wave];
+        if (whole_next) {
+            load_row_planes<W, P, S, F, P>(nxt, tn, wave, lane);
+            load_row_scales<W, P, S, SS, S>(nxt, tn, wave, lane);
         }
         float part[kItemsPerLane];
         bool reach = false;
@@ -1078,11 +1078,14 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
         if (passed * 4 > probed + 32) { plain = true; return false; }     // wave-uniform; this row is not done yet
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
-        if (has_next) {
-            load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
-            load_hints(hn, pn);
-            amax_n = a.row_amax[(size_t)pn * kWavesPerBlock + wave];
-        }
+        // The prefetch is not under a branch (a workgroup's last step fetches its own row once more): with
+        // `if (has_next)` around it the compiler, merging the path that loaded with the one that did not, makes
+        // the first use of THIS row's registers wait for half of the loads just issued -- every step then stalls
+        // for a memory round trip and nothing is prefetched.
+        const uint32_t pl = has_next ? pn : p;
+        load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_hints(hn, pl);
+        amax_n = a.row_amax[(size_t)pl * kWavesPerBlock + wave];
         bool reach = true;
         uint32_t mine = 0;     // which of this lane's items can still reach the threshold
         {
@@ -1180,7 +1183,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
         for (;;) {
             const uint32_t pn = p + G;
             const bool has_next = pn < a.p_end;
-            if (has_next) load_row<W, P, S>(nxt, a.tiles + (size_t)pn * tile_bytes, wave, lane);
+            load_row<W, P, S>(nxt, a.tiles + (size_t)(has_next ? pn : p) * tile_bytes, wave, lane);   // unconditional: see scan_exact_prog_hint
             score_row(cur, (1u << kItemsPerLane) - 1u, p);
             ++full_rows;
             extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item beyond the stream's
