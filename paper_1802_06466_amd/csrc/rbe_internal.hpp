@@ -69,15 +69,18 @@ RBE_DECLARE_W(2)
 RBE_DECLARE_W(4)
 #undef RBE_DECLARE_W
 
-// Persistent workgroups per compute unit for a one-query streaming scan: about 48 KB of tile stream in flight
-// per compute unit (a workgroup has one tile in flight; the progressive scan streams all planes and scale arrays but the last).
+// Persistent workgroups per compute unit for a one-query streaming scan: about 32 KB of tile stream per compute
+// unit and step (a workgroup has this step's tile and the next one's in flight; the progressive scan streams all
+// planes and scale arrays but the last).  Measured on 1e9 items (ms of the finest-level scan at 1 / 2 / 3 / 4
+// workgroups per unit): 18 KB per tile 2.92 / 2.58 / 2.82 / 2.61, 8 KB 2.57 / 1.56 / 1.25 / 1.28, 24 KB 3.41 / 3.43 /
+// 3.43 / 3.47, 36 KB 5.04 / 5.04 / 5.10 / 5.14, 52 KB (1e8 items) 0.69 / 0.70 / 0.71 / 0.72.
 inline uint32_t streaming_blocks_per_cu(uint32_t W, uint32_t P, uint32_t S, bool progressive, bool hints)
 {
     const bool prog = progressive && P >= 2;
     const uint32_t planes = prog ? P - 1 : P, scales = prog && S > 0 ? S - 1 : S;
     const uint32_t tile_stream = kTileItems * (8u * W * planes + (prog && hints ? 1u : 4u) * scales);
-    const uint32_t n = (48u * 1024u + tile_stream / 2) / tile_stream;
-    return n < 1u ? 1u : (n > 4u ? 4u : n);
+    const uint32_t n = (32u * 1024u + tile_stream / 2) / tile_stream;
+    return n < 1u ? 1u : (n > 3u ? 3u : n);
 }
 
 // Dyadic modes are built for d = 64 and d = 128.

@@ -1444,7 +1444,7 @@ hipError_t launch_scan_exact_w<RBE_W>(const KernelSel& k, const ScanArgs& a, uin
         if (e != hipSuccess) return e;
         per_cu = (uint32_t)(nb > 0 ? nb : 1);
         // One query is a pure stream: what matters is the bytes in flight per compute unit, and more workgroups
-        // than that needs only spread the accesses (measured: 36 KB tiles 1 per CU, 20..28 KB 2, 18 KB 3, 12 KB 3..4).
+        // than that needs only spread the accesses (measurements at streaming_blocks_per_cu).
         if (k.single) per_cu = std::min(per_cu, streaming_blocks_per_cu(RBE_W, k.P, scale_arrays(k.mode, k.P), k.progressive, k.hints));
     }
     const uint32_t units = a.p_end - a.p_begin;
