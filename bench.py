@@ -30,6 +30,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 VALU_PEAK_TLANEOPS = 39.3216     # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz, one 32-bit lane-op per lane per clock
 MFMA_F16_PEAK_TFLOPS = 2500.0    # dense fp16 matrix-core peak
+MFMA_I8_PEAK_TOPS = 5000.0       # dense int8 matrix-core peak (binary queries on general scales are contracted in int8)
 
 
 def log(msg: str):
@@ -79,10 +80,11 @@ def finest_level_roofline(np, r, W, P, Q, d, kernel):
     out["hbm_frac"] = out["hbm_gbs"] / HBM_PEAK_GBS
     if kernel == "scan_batch_mfma":
         ach = 2.0 * Q * items * d * P / (ms * 1e-3) / 1e12
-        out.update({"bound": "mfma", "achieved": ach, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / MFMA_F16_PEAK_TFLOPS, "flops_per_pair": 2 * d * P, "traffic": None,
-                    "note": "priced against the fp16 matrix-core peak as a dense contraction; the kernel is held by "
-                            "vector-instruction issue (bits to halves, thresholds), see profiles/"})
+        out.update({"bound": "mfma", "achieved": ach, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
+                    "frac": ach / MFMA_I8_PEAK_TOPS, "flops_per_pair": 2 * d * P, "traffic": None,
+                    "note": "priced against the int8 matrix-core peak as a dense contraction (the kernel contracts "
+                            "eight-bit integer operands); it is held by vector-instruction issue (bits to operand "
+                            "bytes, scale multiply-adds, thresholds) at the clock the chip sustains, see profiles/"})
     elif Q >= 3:
         ops = lane_ops_per_pair(W, P, P)
         ach = ops * Q * items / (ms * 1e-3) / 1e12
@@ -445,7 +447,7 @@ def main():
         b_items = rb["stats"]["items_scanned"][-1]
         matrix_cores = B >= 7 and W <= 2     # the library's own choice of kernel for a batch
         if matrix_cores:
-            # dense contraction [B x d] . [d x items] per corpus plane (one fp16 half per query component:
+            # dense contraction [B x d] . [d x items] per corpus plane (one eight-bit integer per query component:
             # the contraction filters, survivors are rescored bitwise).  `achieved` prices the whole contraction;
             # the kernel issues less of it -- the last plane is contracted only for the blocks of items that the
             # other planes cannot rule out -- and more of it, by padding the batch to a multiple of 16 queries.
@@ -453,9 +455,10 @@ def main():
             issued = 2.0 * 16 * -(-B // 16) * b_items * d * (P - 1 if P >= 2 else P)
             ach = flops / (b_scan * 1e-3) / 1e12
             roof = {"kernel": "scan_batch_mfma (finest level)", "bound": "mfma", "achieved": ach,
-                    "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_F16_PEAK_TFLOPS,
+                    "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s", "frac": ach / MFMA_I8_PEAK_TOPS,
+                    "frac_of_f16_peak": ach / MFMA_F16_PEAK_TFLOPS,
                     "kernel_ms": b_scan, "flops_per_pair": 2 * d * P,
-                    "issued_tflops_first_look": issued / (b_scan * 1e-3) / 1e12, "traffic": None,
+                    "issued_tops_first_look": issued / (b_scan * 1e-3) / 1e12, "traffic": None,
                     "hbm_gbs": b_items * bytes_per_item / (b_scan * 1e-3) / 1e9}
         else:
             lane_ops = lane_ops_per_pair(W, P, P) * B * b_items
@@ -470,7 +473,7 @@ def main():
             "queries_per_step": B, "steps": args.batch_steps, "ms_per_step": b_ms,
             "p50_ms": float(np.percentile(rb["per_step_ms"], 50)),
             "value": N * B * args.batch_steps / rb["wall_s"], "unit": "candidates/s",
-            "dtype": "f16 x f16 -> f32 filter, u64 xor/popcount + f32 scores" if matrix_cores else "u64 xor/popcount + f32",
+            "dtype": "i8 x i8 -> i32 filter, u64 xor/popcount + f32 scores" if matrix_cores else "u64 xor/popcount + f32",
             "last_search_level_ms": {"scan": rb["stats"]["scan_ms"], "select": rb["stats"]["select_ms"]},
             "gpu_ms_per_search": float(rb["total_gpu_ms"].mean()) if rb["total_gpu_ms"].size else None,
             "roofline": roof,
@@ -480,6 +483,11 @@ def main():
         if matrix_cores and want("batch_popcount"):
             # the same calls on the XOR/popcount kernel (what one query uses), against the vector-ALU roofline
             # (progressive scan off for the roofline figure: the 58-op model prices every plane of every pair)
+            rbe.rbe_debug_set_batch_path(ix, 3)                 # matrix cores with half operands (v_mfma_f32_16x16x32_f16)
+            rh = timed_searches(rbe, torch, ix, qpb, qsb, B, k, args.batch_steps, bw)
+            out["batch"]["half_operands"] = {"ms_per_step": rh["wall_s"] * 1e3 / args.batch_steps, "scan_kernel_ms": float(rh["scan_ms"].mean()),
+                                             "same_ids": bool(all(np.array_equal(x, y) for x, y in zip(rh["ids"], rb["ids"])))}
+            log(f"Q={B}, matrix cores with half operands: {rh['wall_s'] * 1e3 / args.batch_steps:.3f} ms/step, scan kernel {rh['scan_ms'].mean():.3f} ms")
             rbe.rbe_debug_set_batch_path(ix, 1)
             steps_v = max(2, args.batch_steps // 2)
             rvp = timed_searches(rbe, torch, ix, qpb, qsb, B, k, steps_v, 1)
@@ -534,7 +542,7 @@ def main():
             c1 = ceil["scan_batch_mfma"]
             c1["tflops_algorithmic"] = c1["pairs_per_s"] * 2 * d * P / 1e12
             log(f"issue ceiling, matrix-core scan (first look): {c1['pairs_per_s'] / 1e9:.1f} G pairs/s = "
-                f"{c1['tflops_algorithmic']:.0f} TFLOP/s algorithmic")
+                f"{c1['tflops_algorithmic']:.0f} TOP/s algorithmic")
             if "batch" in out and out["batch"]["roofline"].get("bound") == "mfma":
                 rf = out["batch"]["roofline"]
                 rf["issue_ceiling_tflops"] = c1["tflops_algorithmic"]

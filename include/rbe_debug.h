@@ -68,7 +68,9 @@ int rbe_debug_query_mass(const uint64_t *q_planes, const float *q_scales, uint32
 
 /* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 7
  * queries per call on, dim <= 128), 1 = always the XOR/popcount kernel, 2 = the
- * matrix-core kernel for any number of queries (dim <= 128).                     */
+ * matrix-core kernel for any number of queries (dim <= 128), 3 = as 2, with half
+ * operands also where eight-bit integer operands are the default (binary queries
+ * on general scales).                                                            */
 int rbe_debug_set_batch_path(rbe_index *ix, int path);
 
 /* How the near-lossless modes are computed.  0 (default): the scans and the
@@ -130,6 +132,23 @@ int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, co
                              uint32_t n_queries, uint32_t q_n_planes, uint32_t dim, uint32_t n_planes,
                              uint32_t dyadic, uint16_t *halves_out, size_t halves_capacity,
                              float *unscale_out, float *start_out, uint32_t *shape_out);
+
+/* The eight-bit integer operands the matrix-core scan filters binary queries on
+ * general scales with (Eq. 14 as a dense contraction; pure host arithmetic, no GPU
+ * needed).  qhat = sum_i c_i b_q^i is rounded to T_d 2^e with integers |T_d| <= 126;
+ * bytes_out [tile = query / 16][dim / 64 parts][lane = 16 g + query % 16][16]: byte
+ * 4 t + m of a lane belongs to dimension 64 part + 32 (t / 2) + 8 m + 2 g + (t % 2)
+ * and holds T_d for even t, -T_d / 2 for odd t (T_d is even there).  unscale_out [Q]
+ * = 2^e / 32, the unit of the filter's scores; start_out [Q] = the float 1.5 * 2^23
+ * - 32 sum_d T_d whose bit pattern the accumulators start from; mass_out [Q] =
+ * sum_d |qhat_d| in those units, rounded up; *margin_out = the bound, per unit of
+ * an item's scale sum and in those units, on |filter value - score| for every
+ * query of the batch.  bytes_capacity: bytes available at bytes_out (EINVAL and
+ * the count needed in rbe_last_error() if too small).  All pointers: host.       */
+int rbe_debug_batch_operands_i8(const uint64_t *q_planes, const float *q_scales, uint32_t n_queries,
+                                uint32_t q_n_planes, uint32_t dim, int8_t *bytes_out,
+                                size_t bytes_capacity, float *unscale_out, float *start_out,
+                                float *mass_out, float *margin_out);
 
 /* Measurement yardstick: enqueues a plain copy kernel ("calib_copy") of `bytes`
  * bytes from src_dev to dst_dev (DEVICE pointers, 16-byte aligned, bytes a

@@ -94,6 +94,7 @@ PROTOTYPES = {
     "rbe_debug_query_mass": (_i32, [_vp, _vp, _u32, _u32, _u32, _vp]),
     "rbe_debug_exact_plan": (_i32, [_u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_debug_batch_operands": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
+    "rbe_debug_batch_operands_i8": (_i32, [_vp, _vp, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp, _vp]),
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
@@ -471,6 +472,22 @@ def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic
     return out, unscale, start, float(shape[3:4].view(np.float32)[0])
 
 
+def rbe_debug_batch_operands_i8(q_planes, q_scales, dim: int):
+    """Eight-bit integer query operands of the matrix-core batch scan (host only; binary queries on general
+    scales): int8 [tile][part][lane][16], unscale [Q], start [Q], mass [Q] and the filter margin."""
+    q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
+    q_scales = np.ascontiguousarray(q_scales, dtype=np.float32)
+    Q, Pq = q_planes.shape[0], q_planes.shape[1]
+    tiles, parts = (Q + 15) // 16, dim // 64
+    ops = np.zeros((tiles, parts, 64, 16), dtype=np.int8)
+    unscale, start, mass = (np.zeros(Q, dtype=np.float32) for _ in range(3))
+    margin = np.zeros(1, dtype=np.float32)
+    _check(load_library().rbe_debug_batch_operands_i8(q_planes.ctypes.data, q_scales.ctypes.data, Q, Pq, dim, ops.ctypes.data,
+                                                      ops.nbytes, unscale.ctypes.data, start.ctypes.data, mass.ctypes.data,
+                                                      margin.ctypes.data))
+    return ops, unscale, start, mass, float(margin[0])
+
+
 def rbe_debug_query_mass(q_planes, q_scales, dim: int, dyadic: bool = False):
     """Mass of one query ([Pq][W] planes, [Pq] scales) as the progressive scan uses it (host only):
     (x, y) floats for general scales, (h_min, 0) with h_min an int for a dyadic index."""
@@ -501,6 +518,7 @@ def rbe_debug_set_nearlossless_path(ix: Index, path: int):
 
 
 def rbe_debug_set_batch_path(ix: Index, path: int):
+    """0 = automatic, 1 = XOR/popcount kernel, 2 = matrix-core kernel, 3 = matrix-core kernel with half operands only."""
     _check(load_library().rbe_debug_set_batch_path(ix.handle, path))
 
 

@@ -121,6 +121,7 @@ struct rbe_index {
     char* fin_scratch = nullptr;    // borrowed storage: 256 bytes for rbe_finalize's reductions
     // false if a scale is negative: every bound of the pruning scans assumes a_j >= 0, so they all stay off
     bool nonneg = true;
+    float scale_max = 0.0f;         // largest magnitude in the stored scale arrays (general scales), set by rbe_finalize
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
     int nl_path = 0;                // near-lossless modes: 0 = exact scans + selection by groups, 1 = the per-thread-queue scan
     uint32_t* d_hints = nullptr;    // general scales, P >= 2: one-byte copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
@@ -136,6 +137,7 @@ struct rbe_index {
     } prune[2];
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
+    bool batch_i8 = false;          // the staged operands are eight-bit integers (BatchArgs::operand = 1)
     float fq_mass[RBE_MAX_QUERIES][2] = {};   // fp32 queries: {x, 2^-19 x}, x >= sum_d |q_d| (1 + 2^-18): bounds any plane's table sum
     // fp32 queries, one scan per query, general scales with scale copies: a 4-plane binary approximation of each
     // query is staged as well (stage_float_approximations) and the last level's bound is formed from it
@@ -500,7 +502,7 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
     // full-precision queries need the filter; the dyadic kernels have none (their binary queries are exact)
     if (float_query && ix->mode != rbe::kModeScaled) return false;
     if (ix->batch_path == 1) return false;
-    if (ix->batch_path == 2) return true;
+    if (ix->batch_path >= 2) return true;
     // Measured crossover (1e9 items d=64 P=3: 6 queries 9.3 ms either way, 7 queries 10.5 ms on the XOR/popcount
     // scan and 9.5 ms here; 1e8 items d=128 P=4: further ahead): a 16-query tile costs the matrix-core scan about
     // as much as 6 queries cost the XOR/popcount scan.  The byte-table scan of fp32 queries reads the corpus once
@@ -630,10 +632,95 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
     if (margin) *margin = dyadic ? 0.0f : (float)(worst * (1.0 + std::ldexp(1.0, -10)));
 }
 
+// Eight-bit integer operands of a batch of binary queries on general scales (pure host arithmetic).
+// qhat = sum_i c_i b^i is rounded to T_d * 2^e, T_d an integer of magnitude <= 126 (e the least exponent that
+// allows it).  The kernel's B operand holds, for item bit b_d, a byte that is 0 or 64 (dimensions 2g of every
+// byte of the plane word, lane group g) or 0 or -128 (dimensions 2g + 1); the A operand holds T_d against the
+// 64s and M_d = -round(qhat_d / 2^(e+1)) against the -128s (T_d = -2 M_d there: one bit less).  With rho = 2b - 1
+//     64 sum_even T_d b_d - 128 sum_odd M_d b_d - 32 sum_d T_d = 32 sum_d T_d rho_d,
+// so the accumulators start at (the bit pattern of the float) 1.5 * 2^23 - 32 sum_d T_d and end at the bit
+// pattern of 1.5 * 2^23 + 32 sum_d T_d rho_d: scores are formed in units of 2^e / 32 = unscale.
+//   bytes   [tile][64-dim part][lane][16]   (tile = query / 16, lane = 16 g + query % 16; byte 4t + m of a lane
+//           is dimension 64 part + 32 (t / 2) + 8 m + 2 g + (t % 2))
+// *margin bounds, for every query of the batch and per unit of sum_j a_j[item], the distance between the filter's
+// value and the score as the XOR/popcount arithmetic forms it, in those units: the rounding of the query
+// (sum_d |qhat_d - 2^e T_d|), the multiply-adds through which the start constant leaves again (its product with
+// the item's scale sum is rounded once, and each of two multiply-adds rounds at that magnitude: <= 3 units; 4
+// are allowed), and the roundings of the XOR/popcount arithmetic (<= 2^-20 d sum_i |c_i|).
+void build_batch_operands_i8(uint32_t W, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
+                             int8_t* bytes, float* unscale, float* bias, float* margin, float* qmass)
+{
+    const uint32_t dim = 64 * W, tiles = batch_tiles(Q);
+    std::memset(bytes, 0, (size_t)tiles * W * 64 * 16);
+    std::vector<double> qhat(dim);
+    double worst = 0.0;
+    for (uint32_t q = 0; q < Q; ++q) {
+        double biggest = 0.0, coef = 0.0;
+        for (uint32_t d = 0; d < dim; ++d) {
+            double v = 0.0;
+            for (uint32_t i = 0; i < PQ; ++i) {
+                const double c = (double)q_scales[(size_t)q * PQ + i];
+                const uint64_t word = q_planes[((size_t)q * PQ + i) * W + d / 64];
+                v += ((word >> (d % 64)) & 1ull) ? c : -c;
+            }
+            qhat[d] = v;
+            biggest = std::max(biggest, std::fabs(v));
+        }
+        for (uint32_t i = 0; i < PQ; ++i) coef += std::fabs((double)q_scales[(size_t)q * PQ + i]);
+        int e = 0;
+        if (biggest > 0.0) {
+            e = std::ilogb(biggest) - 6;                        // biggest / 2^e in [64, 128)
+            if (std::ldexp(biggest, -e) > 126.0) ++e;
+        }
+        const double unit = std::ldexp(1.0, e - 5);             // 2^e / 32
+        unscale[q] = (float)unit;
+        const uint32_t qt = q / 16, row = q % 16;
+        double lost = 0.0, mass = 0.0;
+        long sum_t = 0;
+        for (uint32_t part = 0; part < W; ++part)
+            for (uint32_t grp = 0; grp < 4; ++grp)
+                for (uint32_t t = 0; t < 4; ++t)
+                    for (uint32_t m = 0; m < 4; ++m) {
+                        const uint32_t d = 64 * part + 32 * (t / 2) + 8 * m + 2 * grp + (t % 2);
+                        long T, stored;
+                        if (t % 2 == 0) { T = std::lrint(std::ldexp(qhat[d], -e)); stored = T; }
+                        else { stored = -std::lrint(std::ldexp(qhat[d], -e - 1)); T = -2 * stored; }
+                        sum_t += T;
+                        lost += std::fabs(qhat[d] - std::ldexp((double)T, e));
+                        mass += std::fabs(qhat[d]);
+                        bytes[(((size_t)qt * W + part) * 64 + grp * 16 + row) * 16 + 4 * t + m] = (int8_t)stored;
+                    }
+        bias[q] = (float)(12582912.0 - 32.0 * (double)sum_t);    // exact: |32 sum T| < 2^22
+        // sum_d |qhat_d| in the units of the scores, rounded up: the largest value qhat . rho can take
+        const double m_abs = mass / unit * (1.0 + std::ldexp(1.0, -20));
+        float mf = (float)m_abs;
+        if ((double)mf < m_abs) mf = std::nextafter(mf, INFINITY);
+        qmass[q] = mf;
+        worst = std::max(worst, lost / unit + 4.0 + std::ldexp(coef * dim / unit, -20));
+    }
+    *margin = (float)(worst * (1.0 + std::ldexp(1.0, -10)));
+}
+
+// Integer operands serve binary queries on general scales; path 3 of rbe_debug_set_batch_path keeps the halves.
+bool batch_operand_i8(const rbe_index* ix, bool float_query)
+{
+    // (the accumulators' start constant, 1.5 * 2^23, is multiplied by the item's scale sum on its way out: scales
+    // beyond 2^80 -- which would bring that product near the end of the fp32 range -- keep the halves)
+    return ix->mode == rbe::kModeScaled && !float_query && ix->batch_path != 3 && ix->scale_max <= 0x1p80f;
+}
+
 int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
                         hipStream_t st, const float* q_float = nullptr)
 {
     const bool dyadic = ix->mode != rbe::kModeScaled;
+    ix->batch_i8 = batch_operand_i8(ix, q_float != nullptr);
+    if (ix->batch_i8) {
+        build_batch_operands_i8(ix->W, q_planes, q_scales, Q, PQ, reinterpret_cast<int8_t*>(ix->h_aops), ix->h_unscale,
+                                ix->h_unscale + RBE_MAX_QUERIES, &ix->batch_margin, ix->h_unscale + 2 * RBE_MAX_QUERIES);
+        HIP_TRY(hipMemcpyAsync(ix->ws.aops, ix->h_aops, (size_t)batch_tiles(Q) * ix->W * 64 * 16, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipMemcpyAsync(ix->ws.unscale, ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
+        return RBE_OK;
+    }
     const BatchOperandShape sh = batch_operand_shape(ix->W, ix->P, dyadic, Q);
     build_batch_operands(ix->W, ix->P, dyadic, q_planes, q_scales, Q, PQ, reinterpret_cast<uint16_t*>(ix->h_aops),
                          ix->h_unscale, ix->h_unscale + RBE_MAX_QUERIES, q_float, &ix->batch_margin,
@@ -877,6 +964,22 @@ int rbe_debug_batch_operands(const uint64_t* q_planes, const float* q_scales, co
     return RBE_OK;
 }
 
+int rbe_debug_batch_operands_i8(const uint64_t* q_planes, const float* q_scales, uint32_t n_queries, uint32_t q_n_planes,
+                                uint32_t dim, int8_t* bytes_out, size_t bytes_capacity, float* unscale_out,
+                                float* start_out, float* mass_out, float* margin_out)
+{
+    ARG_CHECK(q_planes && q_scales && bytes_out && unscale_out && start_out && mass_out && margin_out, "NULL argument");
+    ARG_CHECK(dim == 64 || dim == 128, "dim must be 64 or 128");
+    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes out of range");
+    ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries out of range");
+    for (size_t i = 0; i < (size_t)n_queries * q_n_planes; ++i) ARG_CHECK(std::isfinite(q_scales[i]), "q_scales[%zu] is not finite", i);
+    const size_t need = (size_t)batch_tiles(n_queries) * (dim / 64) * 64 * 16;
+    ARG_CHECK(bytes_capacity >= need, "bytes_out too small: %zu needed", need);
+    build_batch_operands_i8(dim / 64, q_planes, q_scales, n_queries, q_n_planes, bytes_out, unscale_out, start_out,
+                            margin_out, mass_out);
+    return RBE_OK;
+}
+
 int rbe_load_chunk(rbe_index* ix, uint64_t first_item, uint64_t count, const uint64_t* planes,
                    const float* scales, int mem_kind, void* hip_stream)
 {
@@ -991,7 +1094,7 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
     // per array the largest magnitude, and whether any sign bit is set.
     static_assert(RBE_MAX_PLANES == 4, "scale_array_max writes its sign flags at out[4 + j]");
     uint32_t h_max[2 * RBE_MAX_PLANES] = {};
-    if (ix->mode == rbe::kModeScaled) {
+    auto measure_scales = [&]() -> int {
         uint32_t* d_max = reinterpret_cast<uint32_t*>(ix->fin_scratch);
         if (!ix->borrowed) HIP_TRY(hipMalloc(&d_max, sizeof(h_max)));
         hipError_t e = hipMemsetAsync(d_max, 0, sizeof(h_max), st);
@@ -1003,6 +1106,14 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
         if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (!ix->borrowed) (void)hipFree(d_max);
         HIP_TRY(e);
+        uint32_t top = 0;
+        for (uint32_t j = 0; j < ix->P; ++j) top = std::max(top, h_max[j]);
+        std::memcpy(&ix->scale_max, &top, sizeof(float));
+        return RBE_OK;
+    };
+    if (ix->mode == rbe::kModeScaled) {
+        const int rc = measure_scales();
+        if (rc != RBE_OK) return rc;
         ix->nonneg = true;
         for (uint32_t j = 0; j < ix->P; ++j) {
             if (h_max[j] >= 0x7f800000u) {
@@ -1017,6 +1128,10 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
         hipLaunchKernelGGL(rbe::fold_cosine, dim3((uint32_t)((n_slots + 255) / 256)), dim3(256), 0, st,
                            ix->d_tiles, ix->geom, n_slots);
         HIP_TRY(hipGetLastError());
+        if (ix->mode == rbe::kModeScaled) {     // the scales the scans will see are the folded ones
+            const int rc = measure_scales();
+            if (rc != RBE_OK) return rc;
+        }
     }
     // Side arrays of the pruning scans.  Their bounds hold for scales >= 0 only, so an index with a negative scale
     // gets none and is searched by the plain scans (see can_prune).
@@ -1217,7 +1332,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         ba.look_stats = level_slot >= c.look_from ? ix->ws.status + 12 : nullptr;
         ba.row_amax = ix->d_row_amax; ba.row_asum = ix->d_row_amax ? ix->d_row_amax + (size_t)ix->layout.n_tiles * (kTileItems / kRow) : nullptr; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end; ba.calib_repeat = c.calib_repeat;
-        ba.rescore = batch_rescore(ix, c.float_batch);
+        ba.rescore = batch_rescore(ix, c.float_batch); ba.operand = ix->batch_i8 ? 1u : 0u;
         ba.PQ = c.PQ; ba.qwords = ix->ws.qwords; ba.qcoef = ix->ws.qcoef; ba.lut = ix->ws.lut; ba.margin = ix->batch_margin;
         e = hipSuccess;
         const uint32_t tiles = batch_tiles(c.Q), per_launch = batch_tiles_per_launch(ix, c.float_batch);
@@ -1716,7 +1831,7 @@ int rbe_debug_set_nearlossless_path(rbe_index* ix, int path)
 int rbe_debug_set_batch_path(rbe_index* ix, int path)
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
-    ARG_CHECK(path >= 0 && path <= 2, "path must be 0 (auto), 1 (XOR/popcount) or 2 (matrix cores)");
+    ARG_CHECK(path >= 0 && path <= 3, "path must be 0 (auto), 1 (XOR/popcount), 2 (matrix cores) or 3 (matrix cores, half operands)");
     ix->batch_path = path;
     return RBE_OK;
 }

@@ -35,6 +35,16 @@
 // carry no trace of the half precision.  The per-pair VALU work drops from ~58
 // lane-ops to P fused multiply-adds and one compare; bit expansion is paid once per
 // item, whatever the number of queries.
+//
+// Integer operands (OP = 1; binary queries on general scales).  The filter needs no more than a few bits of the
+// query: with qhat rounded to eight-bit integers T_d (times a power of two), v_mfma_i32_16x16x64_i8 contracts a
+// whole 64-dimension plane per instruction -- half the matrix instructions -- and a dword of four operand BYTES
+// comes out of one AND: lane group g shifts the plane's two 32-bit parts left by 6 - 2g, and the masks
+// 0x40404040 / 0x80808080 then leave bits 2g / 2g + 1 of every byte as the byte values 64 / -128.  The query
+// operand holds T_d against the 64s and -T_d / 2 against the -128s, the accumulators start at the bit pattern
+// of the float 1.5 * 2^23 minus 32 sum_d T_d, and so they END as the bit pattern of the float
+// 1.5 * 2^23 + 32 sum_d T_d rho_d: no conversion instruction; the constant leaves through the multiply-adds
+// that apply the item's scales.  The rounding of the query and of those multiply-adds is part of the margin.
 #include <type_traits>
 
 #include "rbe_internal.hpp"
@@ -50,6 +60,11 @@ constexpr int kMaxPlanes = 4;      // query planes (RBE_MAX_PLANES of the C inte
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+
+// Where the integer accumulators start, as a float: adding an integer n (|n| < 2^22) to its bit pattern gives the
+// bit pattern of kAccBase + n.
+constexpr float kAccBase = 12582912.0f;   // 1.5 * 2^23
 
 // A wave works through its row of 256 items in SEG segments.  One segment (d = 64) keeps the loads widest; at
 // d = 128 a whole row in flight costs 160 registers and 80 KB of LDS per workgroup with 4 planes -- one wave per
@@ -105,12 +120,16 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
 // a call.
 // CALIB: the measurement variant (BatchArgs::calib_repeat), a separate instantiation so that the scan proper carries
 // none of it.
-template <int W, int P, int MODE, int NQT, int RS, bool CALIB = false>
+// OP: 0 = half operands (v_mfma_f32_16x16x32_f16), 1 = eight-bit integer operands (v_mfma_i32_16x16x64_i8).
+template <int W, int P, int MODE, int NQT, int RS, int OP = 0, bool CALIB = false>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu((NQT == 1 && W == 1 && P <= 3) ? 3 : 1)))
 void scan_batch_mfma(const BatchArgs a)
 {
     constexpr int S = scale_arrays(MODE, P);
     constexpr int KP = 2 * W;                          // 32-dimension parts of a plane
+    constexpr bool kI8 = OP == 1;
+    static_assert(!kI8 || (MODE == kModeScaled && RS == 1), "integer operands: the filter of binary queries on general scales");
+    using acc_t = std::conditional_t<kI8, intx4, floatx4>;
     // General scales: one accumulator per plane (the item's a_j is applied afterwards); the query's hi half
     // filters.  Dyadic modes: the plane weight 2^-j is folded into a per-plane copy of the query operand, all
     // planes add into one accumulator, and the query (a short dyadic fraction) is exact in one half.
@@ -167,17 +186,28 @@ void scan_batch_mfma(const BatchArgs a)
     if (p >= a.p_end) return;
 
     // query operands (16 queries per tile, one half per component, KP parts), already in lane order
-    half8 A[NQT][PA][KP];
+    // (integer operands: one 16-byte operand per 64-dimension part, [tile][part][lane])
+    half8 A[kI8 ? 1 : NQT][PA][KP];
+    intx4 A8[kI8 ? NQT : 1][W];
+    if constexpr (kI8) {
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt)
+        for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-        for (int pa = 0; pa < PA; ++pa)
+            for (int kp = 0; kp < W; ++kp)
+                A8[qt][kp] = __builtin_bit_cast(
+                    intx4, reinterpret_cast<const u32x4*>(a.a_ops)[((a.q_begin / 16 + qt) * W + kp) * 64 + lane]);
+    } else {
 #pragma unroll
-            for (int kp = 0; kp < KP; ++kp) {
-                const u32x4 v =
-                    reinterpret_cast<const u32x4*>(a.a_ops)[(((a.q_begin / 16 + qt) * PA + pa) * KP + kp) * 64 + lane];
-                A[qt][pa][kp] = __builtin_bit_cast(half8, v);
-            }
+        for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+            for (int pa = 0; pa < PA; ++pa)
+#pragma unroll
+                for (int kp = 0; kp < KP; ++kp) {
+                    const u32x4 v =
+                        reinterpret_cast<const u32x4*>(a.a_ops)[(((a.q_begin / 16 + qt) * PA + pa) * KP + kp) * 64 + lane];
+                    A[qt][pa][kp] = __builtin_bit_cast(half8, v);
+                }
+    }
     // this lane's queries: tile qt, rows 4g .. 4g+3 (query a.q_begin + 16 qt + 4g + r).  Scores are formed in the
     // query's scaled domain (qhat * 2^k); thresholds are moved there, survivors are moved back (both exact).
     // Only what the common path needs stays in registers; the rare survivor path re-reads the rest.
@@ -191,6 +221,46 @@ void scan_batch_mfma(const BatchArgs a)
             bias[qt][r] = q < a.n_queries ? a.q_bias[q] : 0.0f;
             qmass[qt][r] = (kCanSkip && q < a.n_queries) ? a.q_mass[q] : 0.0f;
         }
+
+    const uint32_t i8_shift = 6u - 2u * (uint32_t)g;
+    // the accumulators' start value, and what a finished accumulator reads as (integer operands: the same bits)
+    auto acc_start = [&](int qt) {
+        if constexpr (kI8)
+            return intx4{__float_as_int(bias[qt][0]), __float_as_int(bias[qt][1]), __float_as_int(bias[qt][2]), __float_as_int(bias[qt][3])};
+        else
+            return floatx4{bias[qt][0], bias[qt][1], bias[qt][2], bias[qt][3]};
+    };
+    auto acc_value = [](const acc_t& d, int r) {
+        if constexpr (kI8) return __int_as_float(d[r]);
+        else return d[r];
+    };
+    // contracts one plane of one item group into the accumulators D[qt]
+    auto contract_plane = [&](acc_t (&D)[NQT], const uint32_t (&part)[KP], int pa) {
+        if constexpr (kI8) {
+#pragma unroll
+            for (int kp = 0; kp < W; ++kp) {
+                // item bits as bytes: 0 or 64 (bit 2g of every byte), 0 or -128 (bit 2g + 1)
+                const uint32_t lo = part[2 * kp] << i8_shift, hi = part[2 * kp + 1] << i8_shift;
+                const intx4 B = {(int)(lo & 0x40404040u), (int)(lo & 0x80808080u), (int)(hi & 0x40404040u), (int)(hi & 0x80808080u)};
+#pragma unroll
+                for (int qt = 0; qt < NQT; ++qt)
+                    D[qt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A8[qt][kp], B, D[qt], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int kp = 0; kp < KP; ++kp) {
+                // item bits as halves: 0, or the power of two whose only set bit is bit 10 + t
+                const uint32_t xr = __builtin_rotateleft32(part[kp], 4u * (uint32_t)g);
+                u32x4 bw;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) bw[t] = xr & (0x04000400u << t);
+                const half8 B = __builtin_bit_cast(half8, bw);
+#pragma unroll
+                for (int qt = 0; qt < NQT; ++qt)
+                    D[qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][pa][kp], B, D[qt], 0, 0, 0);
+            }
+        }
+    };
 
     bool skip_last = kCanSkip;              // wave-uniform
     uint32_t blocks_seen = 0, second_looks = 0;
@@ -253,11 +323,11 @@ void scan_batch_mfma(const BatchArgs a)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int item = 16 * (cb * U + u) + col;
-                floatx4 D[NQT][PD];
+                acc_t D[PD][NQT];
 #pragma unroll
-                for (int qt = 0; qt < NQT; ++qt)
+                for (int j = 0; j < PD; ++j)
 #pragma unroll
-                    for (int j = 0; j < PD; ++j) D[qt][j] = floatx4{bias[qt][0], bias[qt][1], bias[qt][2], bias[qt][3]};
+                    for (int qt = 0; qt < NQT; ++qt) D[j][qt] = acc_start(qt);
 #pragma unroll
                 for (int j = 0; j < F; ++j) {
                     uint32_t part[KP];
@@ -268,19 +338,7 @@ void scan_batch_mfma(const BatchArgs a)
                         const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][j][item * 2]);
                         part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
                     }
-#pragma unroll
-                    for (int kp = 0; kp < KP; ++kp) {
-                        // item bits as halves: 0, or the power of two whose only set bit is bit 10 + t
-                        const uint32_t xr = __builtin_rotateleft32(part[kp], 4u * (uint32_t)g);
-                        u32x4 bw;
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) bw[t] = xr & (0x04000400u << t);
-                        const half8 B = __builtin_bit_cast(half8, bw);
-#pragma unroll
-                        for (int qt = 0; qt < NQT; ++qt)
-                            D[qt][kDy ? 0 : j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                                A[qt][kDy ? j : 0][kp], B, D[qt][kDy ? 0 : j], 0, 0, 0);
-                    }
+                    contract_plane(D[kDy ? 0 : j], part, kDy ? j : 0);
                 }
                 float aj[P];
                 float adj = 0.0f;      // filter slack of this item (general scales)
@@ -289,11 +347,13 @@ void scan_batch_mfma(const BatchArgs a)
                     // are taken with the row's largest last scale and scale sum and sit in row_taus already
 #pragma unroll
                     for (int j = 0; j < F; ++j) aj[j] = s_sc[wave][j][item];
-                    if (kRescore && F == P) {
+                    if ((kRescore && F == P) || kI8) {
                         float asum = aj[0];
 #pragma unroll
-                        for (int j = 1; j < P; ++j) asum += aj[j];
-                        adj = a.margin * asum;
+                        for (int j = 1; j < F; ++j) asum += aj[j];
+                        if (kRescore && F == P) adj = a.margin * asum;
+                        // integer operands: every accumulator reads kAccBase too high
+                        if (kI8) adj = __fmaf_rn(-kAccBase, asum, adj);
                     }
                 } else if (MODE == kModeDyadicNorm) {
                     aj[0] = s_sc[wave][0][item];
@@ -306,11 +366,11 @@ void scan_batch_mfma(const BatchArgs a)
                         if (MODE == kModeScaled) {
                             v = adj;
 #pragma unroll
-                            for (int j = 0; j < F; ++j) v = __fmaf_rn(aj[j], D[qt][j][r], v);
+                            for (int j = 0; j < F; ++j) v = __fmaf_rn(aj[j], acc_value(D[j][qt], r), v);
                         } else if (MODE == kModeDyadicNorm) {
-                            v = aj[0] * (F < P ? D[qt][0][r] + qmass[qt][r] : D[qt][0][r]);
+                            v = aj[0] * (F < P ? D[0][qt][r] + qmass[qt][r] : D[0][qt][r]);
                         } else {
-                            v = F < P ? D[qt][0][r] + qmass[qt][r] : D[qt][0][r];
+                            v = F < P ? D[0][qt][r] + qmass[qt][r] : D[0][qt][r];
                         }
                         s[u][qt][r] = v;
                         any |= (v >= ((MODE == kModeScaled && F < P) ? row_taus[qt][r] : taus[qt][r]));
@@ -326,9 +386,9 @@ void scan_batch_mfma(const BatchArgs a)
                 for (int u = 0; u < U; ++u) {
                     const int item = 16 * (cb * U + u) + col;
                     // general scales: the last plane alone; dyadic modes: every plane again (the exact score)
-                    floatx4 DL[NQT];
+                    acc_t DL[NQT];
 #pragma unroll
-                    for (int qt = 0; qt < NQT; ++qt) DL[qt] = floatx4{bias[qt][0], bias[qt][1], bias[qt][2], bias[qt][3]};
+                    for (int qt = 0; qt < NQT; ++qt) DL[qt] = acc_start(qt);
 #pragma unroll
                     for (int j = kDy ? 0 : P - 1; j < P; ++j) {
                         uint32_t part[KP];
@@ -339,17 +399,7 @@ void scan_batch_mfma(const BatchArgs a)
                             const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][j][item * 2]);
                             part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
                         }
-#pragma unroll
-                        for (int kp = 0; kp < KP; ++kp) {
-                            const uint32_t xr = __builtin_rotateleft32(part[kp], 4u * (uint32_t)g);
-                            u32x4 bw;
-#pragma unroll
-                            for (int t = 0; t < 4; ++t) bw[t] = xr & (0x04000400u << t);
-                            const half8 B = __builtin_bit_cast(half8, bw);
-#pragma unroll
-                            for (int qt = 0; qt < NQT; ++qt)
-                                DL[qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[qt][kDy ? j : 0][kp], B, DL[qt], 0, 0, 0);
-                        }
+                        contract_plane(DL, part, kDy ? j : 0);
                     }
                     float a_item = 1.0f, adj2 = 0.0f;
                     if constexpr (MODE == kModeScaled) {
@@ -365,8 +415,12 @@ void scan_batch_mfma(const BatchArgs a)
                     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            if (MODE == kModeScaled) s[u][qt][r] = __fmaf_rn(a_item, DL[qt][r], s[u][qt][r]) + adj2;
-                            else s[u][qt][r] = MODE == kModeDyadicNorm ? a_item * DL[qt][r] : DL[qt][r];
+                            if (MODE == kModeScaled) {
+                                const float sofar = kI8 ? __fmaf_rn(-kAccBase, a_item, s[u][qt][r]) : s[u][qt][r];
+                                s[u][qt][r] = __fmaf_rn(a_item, acc_value(DL[qt], r), sofar) + adj2;
+                            } else {
+                                s[u][qt][r] = MODE == kModeDyadicNorm ? a_item * acc_value(DL[qt], r) : acc_value(DL[qt], r);
+                            }
                             any2 |= (s[u][qt][r] >= taus[qt][r]);
                         }
                 }
@@ -457,45 +511,32 @@ namespace {
 using BatchFn = void (*)(const BatchArgs);
 
 template <int W, int P, int MODE>
-BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, bool calib)
+BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib)
 {
+    if (nqt != 1 && nqt != 2) return nullptr;
     if constexpr (MODE == kModeScaled) {
-        if (calib) {            // built for binary queries on general scales
+        if (operand == 1) {     // eight-bit integer operands: binary queries
             if (rescore != 1) return nullptr;
-            return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1, true> : (nqt == 2 ? scan_batch_mfma<W, P, MODE, 2, 1, true> : nullptr);
+            if (calib) return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1, 1, true> : scan_batch_mfma<W, P, MODE, 2, 1, 1, true>;
+            return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1, 1> : scan_batch_mfma<W, P, MODE, 2, 1, 1>;
         }
-        if (rescore == 1) {
-            switch (nqt) {
-                case 1: return scan_batch_mfma<W, P, MODE, 1, 1>;
-                case 2: return scan_batch_mfma<W, P, MODE, 2, 1>;
-                default: return nullptr;
-            }
-        }
-        if (rescore == 2) {
-            switch (nqt) {
-                case 1: return scan_batch_mfma<W, P, MODE, 1, 2>;
-                case 2: return scan_batch_mfma<W, P, MODE, 2, 2>;
-                default: return nullptr;
-            }
-        }
+        if (calib) return nullptr;      // the measurement variant is built for the default operands only
+        if (rescore == 1) return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1> : scan_batch_mfma<W, P, MODE, 2, 1>;
+        if (rescore == 2) return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 2> : scan_batch_mfma<W, P, MODE, 2, 2>;
         return nullptr;
     } else {
-        if (rescore != 0 || calib) return nullptr;
-        switch (nqt) {
-            case 1: return scan_batch_mfma<W, P, MODE, 1, 0>;
-            case 2: return scan_batch_mfma<W, P, MODE, 2, 0>;
-            default: return nullptr;
-        }
+        if (rescore != 0 || operand != 0 || calib) return nullptr;
+        return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 0> : scan_batch_mfma<W, P, MODE, 2, 0>;
     }
 }
 
 template <int W, int P>
-BatchFn batch_fn_m(int mode, uint32_t nqt, uint32_t rescore, bool calib)
+BatchFn batch_fn_m(int mode, uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib)
 {
     switch (mode) {
-        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore, calib);
-        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0, calib);
-        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0, calib);
+        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore, operand, calib);
+        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0, operand, calib);
+        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0, operand, calib);
         default: return nullptr;
     }
 }
@@ -507,10 +548,10 @@ hipError_t launch_scan_batch_w<RBE_W>(const KernelSel& k, const BatchArgs& a, ui
 {
     BatchFn fn = nullptr;
     switch (k.P) {
-        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore, a.calib_repeat != 0); break;
-        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore, a.calib_repeat != 0); break;
-        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore, a.calib_repeat != 0); break;
-        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore, a.calib_repeat != 0); break;
+        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0); break;
+        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0); break;
+        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0); break;
+        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;

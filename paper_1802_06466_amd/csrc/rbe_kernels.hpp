@@ -522,9 +522,13 @@ struct BatchArgs {
     const char* tiles;
     Layout layout;
     uint64_t n_items;
-    const uint32_t* a_ops;    // [query tile][plane copy][32-dim part][lane][4 dwords = 8 halves]: the scaled
+    const uint32_t* a_ops;    // operand 0: [query tile][plane copy][32-dim part][lane][4 dwords = 8 halves]: the scaled
                               // reconstructed queries in the A-operand order of v_mfma_f32_16x16x32_f16,
-                              // dimensions permuted and weighted to match the kernel's B operand
+                              // dimensions permuted and weighted to match the kernel's B operand.
+                              // operand 1: [query tile][64-dim part][lane][4 dwords = 16 bytes], eight-bit integers in
+                              // the A-operand order of v_mfma_i32_16x16x64_i8; q_bias then holds the float whose bit
+                              // pattern the accumulators start from
+    uint32_t operand;         // 0: halves; 1: eight-bit integers (rescore = 1 only)
     const float* q_unscale;   // [Q] 2^-k: what a score formed from the scaled query is multiplied by
     const float* q_bias;      // [Q] minus the (plane-weighted) sum of the scaled query's components: where
                               // every accumulator starts

@@ -399,6 +399,125 @@ def test_matrix_core_filter_at_the_margin_never_drops_a_survivor(lib, kind):
     assert max(tight) > 0.3, tight          # the adversarial plane comes within a factor of the margin: the bound is not slack by orders
 
 
+# ------------------------------------------------------------------ host logic: eight-bit integer operands of the batch scan
+K_ACC = 12582912.0          # 1.5 * 2^23: the float whose bit pattern the integer accumulators start from
+
+
+def _i8_operand_view(ops, q, dim):
+    """(T [dim], stored [dim], odd [dim]) of query q from the operand bytes, through the documented placement:
+    byte 4t + m of lane (g, q % 16) is dimension 64 part + 32 (t // 2) + 8 m + 2 g + (t % 2)."""
+    T = np.zeros(dim, dtype=np.int64); stored = np.zeros(dim, dtype=np.int64); odd = np.zeros(dim, dtype=bool)
+    for part in range(dim // 64):
+        for g in range(4):
+            for t in range(4):
+                for m in range(4):
+                    d = 64 * part + 32 * (t // 2) + 8 * m + 2 * g + (t % 2)
+                    v = int(ops[q // 16, part, 16 * g + q % 16, 4 * t + m])
+                    stored[d] = v; odd[d] = bool(t % 2); T[d] = -2 * v if t % 2 else v
+    return T, stored, odd
+
+
+def _i8_accumulator(start_q, stored, odd, bits):
+    """The accumulator of v_mfma_i32_16x16x64_i8 read as a float: it starts at the bit pattern of start_q and adds
+    stored_d times the item byte (64 where an even-slot bit is set, -128 where an odd-slot bit is set)."""
+    acc = int(np.float32(start_q).view(np.int32)) + int((stored * np.where(odd, -128, 64) * bits).sum())
+    return np.array([acc], dtype=np.int32).view(np.float32)[0]
+
+
+@pytest.mark.parametrize("dim,Pq,Q", [(64, 3, 16), (128, 4, 33), (64, 1, 3)])
+def test_integer_operands_contract_to_the_rounded_query(lib, dim, Pq, Q):
+    """The integer contraction, emulated from the operand bytes alone, equals 1.5 2^23 + 32 sum_d T_d rho_d for
+    every plane tried; T is qhat rounded to integers times a power of two, |T| <= 126 (odd slots even); and the
+    value is within the margin of qhat . rho in the filter's units."""
+    rng = np.random.default_rng(dim + Pq)
+    W = dim // 64
+    qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
+    qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
+    qs[0] *= np.float32(2.0 ** -40); qs[1 % Q] *= np.float32(2.0 ** 30)       # the unit follows the query's size
+    ops, unscale, start, mass, margin = rbe.rbe_debug_batch_operands_i8(qp, qs, dim)
+    qbits = ((qp[:, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
+    qhat = (qs.astype(np.float64)[:, :, None, None] * (2 * qbits - 1)).sum(axis=1).reshape(Q, dim)
+    lg = np.log2(unscale.astype(np.float64))
+    assert np.array_equal(lg, np.round(lg))
+    for q in range(Q):
+        T, stored, odd = _i8_operand_view(ops, q, dim)
+        unit = float(unscale[q])
+        assert np.abs(stored).max() <= 126 and np.abs(T).max() <= 126 and np.abs(T).max() >= 32
+        assert np.abs(qhat[q] / (32 * unit) - T).max() <= 1.0 and np.abs(qhat[q] / (32 * unit) - T)[~odd].max() <= 0.5
+        assert float(start[q]) == K_ACC - 32 * T.sum()
+        assert np.abs(qhat[q]).sum() / unit <= float(mass[q]) <= np.abs(qhat[q]).sum() / unit * (1 + 2.0 ** -18)
+        lost = np.abs(qhat[q] / unit - 32 * T).sum()
+        assert lost + 4 <= margin
+        for trial in range(6):
+            bits = rng.integers(0, 2, size=dim) if trial else (T * 32 < qhat[q] / unit).astype(np.int64)
+            rho = 2 * bits - 1
+            f = 0.0
+            for part in range(W):        # one instruction per 64-dimension part, chained through the accumulator
+                sl = slice(64 * part, 64 * part + 64)
+                f = _i8_accumulator(start[q] if part == 0 else f, stored[sl], odd[sl], bits[sl])
+            assert float(f) == K_ACC + 32 * int((T * rho).sum())
+            assert abs((float(f) - K_ACC) - float(qhat[q] @ rho) / unit) <= lost * (1 + 1e-12)
+
+
+@pytest.mark.parametrize("exact_query", [False, True])
+def test_integer_filter_at_the_margin_never_drops_a_survivor(lib, exact_query):
+    """Adversarial case for the integer filter.  The item plane that makes (contraction - true value) as negative
+    as possible is rho_d = -sign(32 T_d - qhat_d / unit); with such planes in positions 0 .. P-2, the plane that
+    attains the query's mass last, and a threshold EQUAL to the pair's own score, the first look (row-wide
+    threshold, fp32 steps as the kernel takes them: the start constant leaves through a multiply-add with the
+    scale sum) and the second look must both let the pair through.  exact_query: coefficients the integers hold
+    exactly, so that the margin is the arithmetic allowance alone and the multiply-adds' rounding is what is tested,
+    over scale triples of very different sizes."""
+    rng = np.random.default_rng(99 if exact_query else 98)
+    dim, P, Pq, Q = 64, 3, 3, 16
+    f32, f64 = np.float32, np.float64
+    qp = rng.integers(0, 2**64, size=(Q, Pq, 1), dtype=np.uint64)
+    if exact_query:
+        qs = np.tile(np.array([64, 32, 16], dtype=np.float32) * np.float32(2.0 ** -9), (Q, 1))    # qhat / 2^-9 in {+-16 .. +-112}, even
+    else:
+        qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
+    ops, unscale, start, mass, margin = rbe.rbe_debug_batch_operands_i8(qp, qs, dim)
+    qbits = ((qp[:, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
+    qhat = (qs.astype(np.float64)[:, :, None, None] * (2 * qbits - 1)).sum(axis=1).reshape(Q, dim)
+    worst_seen = 0.0
+    for q in range(Q):
+        T, stored, odd = _i8_operand_view(ops, q, dim)
+        unit = float(unscale[q])
+        v = qhat[q] / unit
+        if exact_query:
+            assert np.array_equal(32 * T, v)
+        low = np.where(32 * T - v > 0, 0, 1)                                          # rho = -sign(32 T - v); ties: +1
+        under = float(((32 * T - v) * (2 * low - 1)).sum())
+        assert -margin <= under <= 0
+        best_last = (v > 0).astype(np.int64)
+        fa = _i8_accumulator(start[q], stored, odd, low)
+        fl = _i8_accumulator(start[q], stored, odd, best_last)
+        for trial in range(40):
+            a = (rng.uniform(0.02, 1.0, size=P) * 10.0 ** rng.uniform(-6, 6) * np.array([1.0, 10.0 ** rng.uniform(-4, 1), 10.0 ** rng.uniform(-6, 1)])).astype(f32)
+            amax = a[P - 1]
+            smax = f32(float(a.astype(f64).sum()) * (1 + 1e-6))
+            true = sum(float(a[j]) * float(v @ (2 * low - 1)) for j in range(P - 1)) + float(a[P - 1]) * float(v @ (2 * best_last - 1))
+            taus = f32(true)
+            row_tau = f32(taus - f32(1.000001) * f32(f64(amax) * f64(mass[q]) + f64(f32(margin)) * f64(smax)))
+            asum_f = f32(a[0] + a[1])
+            first = f32(f64(-K_ACC) * f64(asum_f))                                   # fma(-K, asum, 0)
+            for j in range(P - 1):
+                first = f32(f64(a[j]) * f64(fa) + f64(first))
+            assert first >= row_tau, (q, trial, float(first), float(row_tau))
+            # the constant is gone, up to the allowance of 4 units per unit of scale sum
+            ideal = sum(float(a[j]) * (float(fa) - K_ACC) for j in range(P - 1))
+            worst_seen = max(worst_seen, abs(float(first) - ideal) / float(a.astype(f64).sum()))
+            asum = f32(f32(a[P - 1] + a[0]) + a[1])
+            sofar = f32(f64(-K_ACC) * f64(a[P - 1]) + f64(first))
+            second = f32(f32(f64(a[P - 1]) * f64(fl) + f64(sofar)) + f32(f32(margin) * asum))
+            assert second >= taus, (q, trial, float(second), float(taus))
+            ideal2 = ideal + float(a[P - 1]) * (float(fl) - K_ACC)
+            worst_seen = max(worst_seen, abs(float(f32(f64(a[P - 1]) * f64(fl) + f64(sofar))) - ideal2) / float(a.astype(f64).sum()))
+    assert worst_seen <= 3.0, worst_seen        # what the multiply-adds lose stays inside the allowance of 4
+    if exact_query:
+        assert margin < 4.5                      # nothing but the arithmetic allowances (multiply-adds, XOR/popcount score)
+
+
 # ------------------------------------------------------------------ host logic: query mass of the progressive scan
 @pytest.mark.parametrize("dim,Pq", [(64, 1), (64, 3), (128, 4), (256, 2)])
 def test_query_mass_bounds_every_plane(lib, dim, Pq):

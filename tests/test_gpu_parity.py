@@ -709,6 +709,10 @@ def test_matrix_core_batch_path_matches_oracle_and_popcount_path(d, P, Pq, Q, k)
     # so a query's result does not depend on the kernel or on how many queries share the call
     np.testing.assert_array_equal(sc_m, sc_v)
     np.testing.assert_array_equal(ids_m, ids_v)
+    rbe.rbe_debug_set_batch_path(ix, 3)          # half operands (path 2 takes eight-bit integers for these queries)
+    ids_h, sc_h = rbe.rbe_search(ix, qp, qs, k)
+    np.testing.assert_array_equal(sc_h, sc_v)
+    np.testing.assert_array_equal(ids_h, ids_v)
     rbe.rbe_debug_set_batch_path(ix, 0)          # automatic: popcount scan on the coarse levels, matrix cores last
     ids_a, sc_a = rbe.rbe_search(ix, qp, qs, k)
     np.testing.assert_array_equal(sc_a, sc_v)
