@@ -445,7 +445,7 @@ def main():
         b_ms = rb["wall_s"] * 1e3 / args.batch_steps
         b_scan = float(rb["scan_ms"].mean()) if rb["scan_ms"].size else float("nan")
         b_items = rb["stats"]["items_scanned"][-1]
-        matrix_cores = B >= 7 and W <= 2     # the library's own choice of kernel for a batch
+        matrix_cores = B >= 5 and W <= 2     # the library's own choice of kernel for a batch (binary queries, general scales)
         if matrix_cores:
             # dense contraction [B x d] . [d x items] per corpus plane (one eight-bit integer per query component:
             # the contraction filters, survivors are rescored bitwise).  `achieved` prices the whole contraction;
@@ -521,7 +521,7 @@ def main():
         qpi, qsi = make_queries(rbe, rbe_synth, torch, centres, B, args.sigma, P, 9)
         ceil = {}
         for kernel, name in ((0, "scan_exact"), (1, "scan_batch_mfma")):
-            if kernel == 1 and not (B >= 7 and W <= 2):
+            if kernel == 1 and not (B >= 5 and W <= 2):
                 continue
             rbe.rbe_debug_issue_rate(ix, qpi, qsi, kernel, 20)                      # warm-up
             runs = [rbe.rbe_debug_issue_rate(ix, qpi, qsi, kernel, 200) for _ in range(3)]

@@ -21,15 +21,16 @@
  * The popcounts are exact integers; the combination is evaluated in fp32 in
  * the order written (i inner, j outer), each inner sum starting from
  * dim * sum_i c_i and accumulating -2 c_i * popcount with fused multiply-adds.
- * With 7 or more queries per call (exact mode, dim <= 128) the pairs are first
- * filtered on the matrix cores: sum_j a_j[z] * (qhat . b_z^j), qhat = sum_i c_i b_q^i
- * reconstructed on the host in double and carried as half-precision numbers, with
- * a slack that covers the rounding; what can reach the threshold is then scored by
- * the formula above, so the results do not depend on the number of queries per
- * call.  (RBE_DYADIC: the half-precision form is exact and is the score.)  Such a
- * call reads the corpus once per 32 queries (once per 16 for RBE_DYADIC with dim
- * 128 and 3 or 4 planes).
- * With fewer than 7 queries per call (exact mode, 2 or more planes) the last pass
+ * With 5 or more queries per call (7 or more for RBE_DYADIC; exact mode, dim <= 128)
+ * the pairs are first filtered on the matrix cores: sum_j a_j[z] * (qhat . b_z^j),
+ * qhat = sum_i c_i b_q^i reconstructed on the host in double and carried as eight-bit
+ * integers times a power of two (half-precision numbers for fp32 queries and for
+ * indexes whose scales exceed 2^80), with a slack that covers the rounding; what
+ * can reach the threshold is then scored by the formula above, so the results do
+ * not depend on the number of queries per call.  (RBE_DYADIC: the half-precision
+ * form is exact and is the score.)  Such a call reads the corpus once per 32
+ * queries (once per 16 for RBE_DYADIC with dim 128 and 3 or 4 planes).
+ * With fewer queries per call (exact mode, 2 or more planes) the last pass
  * over the corpus reads an item's last plane only where an upper bound on its score -- the
  * exact contribution of the other planes plus the largest value the last plane
  * could add -- reaches the current threshold; such items are then scored in full

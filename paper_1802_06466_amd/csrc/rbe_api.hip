@@ -495,6 +495,8 @@ uint32_t batch_rescore(const rbe_index* ix, bool float_query)
 // negative scale is searched by the plain scans alone.
 bool can_prune(const rbe_index* ix) { return ix->nonneg; }
 
+bool batch_operand_i8(const rbe_index* ix, bool float_query);
+
 bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query)
 {
     if (mode != RBE_SELECT_EXACT || !rbe::batch_mfma_supported(ix->W)) return false;
@@ -503,11 +505,13 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
     if (float_query && ix->mode != rbe::kModeScaled) return false;
     if (ix->batch_path == 1) return false;
     if (ix->batch_path >= 2) return true;
-    // Measured crossover (1e9 items d=64 P=3: 6 queries 9.3 ms either way, 7 queries 10.5 ms on the XOR/popcount
-    // scan and 9.5 ms here; 1e8 items d=128 P=4: further ahead): a 16-query tile costs the matrix-core scan about
-    // as much as 6 queries cost the XOR/popcount scan.  The byte-table scan of fp32 queries reads the corpus once
-    // per query, so there the matrix cores win from 3 queries on.
-    return Q >= (float_query ? 3u : 7u);
+    // Measured crossover, 1e9 items d=64 P=3, whole search.  Integer operands (binary queries on general scales):
+    // 4 queries 6.7 ms on the XOR/popcount scan and 7.2 ms here, 5 queries 8.1 and 7.3 ms; a 16-query tile costs
+    // this scan about as much as 4.5 queries cost the other.  Half operands (the dyadic modes): 6 queries 9.3 ms
+    // either way, 7 queries 10.5 ms there and 9.5 ms here.  The byte-table scan of fp32 queries reads the corpus
+    // once per query, so there the matrix cores win from 3 queries on.
+    if (float_query) return Q >= 3u;
+    return Q >= (batch_operand_i8(ix, false) ? 5u : 7u);
 }
 
 // Matrix-core operands of a batch (pure host arithmetic).  Each query is reconstructed in double as

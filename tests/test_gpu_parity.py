@@ -1144,7 +1144,7 @@ def test_progressive_scan_with_fp32_queries(d, P, flags):
 
 @pytest.mark.parametrize("d,P,Pq,flags", [(64, 3, 3, 0), (128, 4, 2, 0), (64, 2, 3, "dyadic"), (128, 3, 3, "dyadic_cosine")])
 def test_progressive_scan_for_small_batches(d, P, Pq, flags):
-    """2..7 queries per call (and any batch on the XOR/popcount kernel): the last level forms partial scores from all
+    """A few queries per call (and any batch on the XOR/popcount kernel): the last level forms partial scores from all
     planes but the last for every query and reads a row's last plane once, for the first query that needs it.
     Same ids and scores with the switch on and off, and against the oracle."""
     N, k = 350_003, 30
