@@ -456,14 +456,38 @@ __device__ __forceinline__ void mstage_append(bool ok, uint64_t key, uint32_t q,
 }
 
 // End of kernel: flush whatever is left.  All lanes of the wave.
+// Every sub-queue reserves its place in its query's list at once (lane q for sub-queue q: one round trip for all
+// of them; taken one after the other, 64 returning atomics were 0.1 ms at the end of every wave), then the entries
+// are copied queue by queue, and the largest keys are raised together at the end.
 __device__ __forceinline__ void mstage_drain(const MultiStage& ms, const CandList& a, int lane)
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    for (uint32_t q = 0; q < ms.n_sub; ++q) {
-        const uint32_t n = ms.cnt[q];
-        if (n) mstage_flush_query(ms, q, n < ms.qcap ? n : ms.qcap, a, lane);
+    uint32_t n = 0;
+    if ((uint32_t)lane < ms.n_sub) {
+        n = ms.cnt[lane];
+        n = n < ms.qcap ? n : ms.qcap;
     }
+    const uint32_t gq_lane = ms.q_base + (uint32_t)lane;
+    uint32_t base = 0;
+    if (n) base = atomicAdd(a.count + gq_lane * kCountStride, n);
+    uint64_t mx_lane = 0;
+    uint64_t live = __ballot(n != 0);      // wave-uniform loop state
+    while (live) {
+        const int q = __ffsll((long long)live) - 1;
+        live &= live - 1;
+        const uint32_t n_q = __shfl(n, q), base_q = __shfl(base, q);
+        uint64_t key = 0;
+        if ((uint32_t)lane < n_q) {   // n_q <= qcap <= 64
+            key = ms.keys[(uint32_t)q * ms.qcap + (uint32_t)lane];
+            const uint32_t pos = base_q + (uint32_t)lane;
+            if (pos < a.cap) a.cand[(size_t)(ms.q_base + (uint32_t)q) * a.cap + pos] = key;
+        }
+        const uint64_t mx = wave_max_u64(key);
+        if (lane == q) mx_lane = mx;
+    }
+    if (n && mx_lane > *reinterpret_cast<const volatile uint64_t*>(a.kmax + gq_lane * kKmaxStride))
+        atomicMax((unsigned long long*)(a.kmax + gq_lane * kKmaxStride), (unsigned long long)mx_lane);
 }
 
 // Sub-queue count for n queries: 16, 32 or 64 (power of two so that qcap is one too).
@@ -488,6 +512,8 @@ struct ScanArgs {
     const uint32_t* hints;    // general scales: one-byte copies of the scale arrays 0 .. P-2 in lane order (scale_hints)
     int hint_base[3];         // ... and the exponent base of each array's hints
     uint32_t stage_entries;   // several queries: LDS queue entries per wave (512..4096), split into sub-queues
+    uint32_t q_slice;         // batch form of scan_exact: queries per workgroup row (blockIdx.y takes queries
+                              // [y * q_slice, (y + 1) * q_slice)); 0 = every workgroup applies all queries.  Set by the launcher
     uint32_t calib_repeat;    // measurement only (batch form of scan_exact): every tile is scored this many more times
                               // without being loaded again, so the launch runs the scan's arithmetic free of memory traffic
 };

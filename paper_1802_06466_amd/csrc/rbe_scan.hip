@@ -112,7 +112,10 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
             p = pn;
         }
     } else {
-        const uint32_t nq = a.n_queries;
+        // (a short range is given to several rows of workgroups, each with a slice of the queries: see the launcher)
+        const uint32_t q_lo = a.q_slice ? blockIdx.y * a.q_slice : 0u;
+        const uint32_t nq = a.q_slice && q_lo + a.q_slice < a.n_queries ? q_lo + a.q_slice : a.n_queries;
+        if (q_lo >= nq) return;
         for (; p < a.p_end; p += G) {
             RowRegs<W, P, S> cur;
             load_row<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
@@ -120,9 +123,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
             // popcount of the tile alive at once and overflows the register file
             __builtin_amdgcn_sched_barrier(0);
             for (uint32_t rep = 0; rep <= a.calib_repeat; ++rep) {      // (once, except in the measurement mode)
-                QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
-                uint64_t tau_n = a.tau[0];
-                for (uint32_t q = 0; q < nq; ++q) {
+                QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, q_lo);
+                uint64_t tau_n = a.tau[q_lo];
+                for (uint32_t q = q_lo; q < nq; ++q) {
                     const QueryRegs<W, PQ> qr = qn;
                     const uint64_t tau = tau_n;
                     if (q + 1 < nq) {
@@ -1450,7 +1453,20 @@ hipError_t launch_scan_exact_w<RBE_W>(const KernelSel& k, const ScanArgs& a, uin
     const uint32_t units = a.p_end - a.p_begin;
     const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;
     if (grid_out) *grid_out = grid;
-    fn<<<dim3(grid), dim3(kBlock), dyn_lds, st>>>(a);
+    // A batch over a range too short to fill the chip (the coarsest levels of a search: a few tiles, of which most
+    // items survive) is bound by the waves' queue flushes -- one returning atomic per 64 survivors, one after the
+    // other, for every query in turn.  Rows of workgroups with a slice of the queries each shorten that chain; the
+    // tiles they share come from the cache.
+    ScanArgs b = a;
+    uint32_t rows = 1;
+    b.q_slice = 0;
+    if (!k.single && !k.progressive && a.calib_repeat == 0 && a.n_queries > 1 && units < n_cu * per_cu) {
+        const uint32_t want = (n_cu * per_cu + units - 1) / units;
+        rows = want < a.n_queries ? want : a.n_queries;
+        b.q_slice = (a.n_queries + rows - 1) / rows;
+        rows = (a.n_queries + b.q_slice - 1) / b.q_slice;
+    }
+    fn<<<dim3(grid, rows), dim3(kBlock), dyn_lds, st>>>(b);
     return hipGetLastError();
 }
 
