@@ -18,6 +18,7 @@ Prints exactly one JSON line on stdout; progress goes to stderr.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -70,7 +71,7 @@ def finest_level_roofline(np, r, W, P, Q, d, kernel):
     """Roofline figures of the finest-level scan of a leg from its search statistics: bytes the method has to
     move per pass (every plane and scale of every item), matrix-core flops of the dense contraction, 32-bit lane
     operations of the XOR/popcount arithmetic, each over the HIP-event time of that launch."""
-    items = r["stats"]["items_scanned"][-1]
+    items = r["last_items"]
     ms = float(r["scan_ms"].mean())
     bytes_per_item = P * (8 * W + 4)
     passes = -(-Q // 32) if kernel == "scan_batch_mfma" else 1
@@ -135,6 +136,20 @@ def build_corpus(rbe, rbe_synth, torch, n_items, d, P, n_clusters, sigma, chunk_
     return ix, centres, hp, hs
 
 
+def settle(rbe, rbe_synth, torch, ix, centres, sigma, Pq, k, seconds, binary_scales=True):
+    """Untimed searches for `seconds` after a corpus has been built (part of the set-up, before any warm-up step):
+    for the first 0.2 s after the build -- generation and encoding of 1e9 items on the GPU -- searches run about
+    4 % slower than the rate they then settle at.  Returns the number of searches made."""
+    if seconds <= 0:
+        return 0
+    qp, qs = make_queries(rbe, rbe_synth, torch, centres, 8, sigma, Pq, 99)
+    n, t0 = 0, time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        rbe.rbe_search(ix, qp[n % 8:n % 8 + 1], qs[n % 8:n % 8 + 1] if binary_scales else None, k)
+        n += 1
+    return n
+
+
 def make_queries(rbe, rbe_synth, torch, centres, n, sigma, P, seed_chunk):
     import numpy as np
     x = rbe_synth.vectors_torch(n, centres, sigma, rbe_synth.SEED_QUERIES, seed_chunk).cpu().numpy()
@@ -150,13 +165,17 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_si
         qs = _NoScales()
     """Runs warmup + steps searches of Q queries each (different queries per call)."""
     import numpy as np
-    per_step, scan_ms, select_ms, total_gpu, all_ids, deep_rows, deep_units = [], [], [], [], [], [], []
+    per_step, scan_ms, select_ms, total_gpu, all_ids, deep_rows, deep_units, last_items, split_steps = [], [], [], [], [], [], [], [], 0
     stats = None
     fallbacks = 0
     for s in range(warmup):
         sl = slice(s * Q, (s + 1) * Q)
         rbe.rbe_search(ix, qp[sl], qs[sl], k, mode, group_size_I)
     torch.cuda.synchronize()
+    # (the interpreter's cyclic collector stays out of the timed steps: with torch imported a full collection takes
+    # about 40 ms, a dozen steps' worth, and comes about once in a thousand searches)
+    gc.collect()
+    gc.disable()
     t_begin = time.perf_counter()
     for s in range(warmup, warmup + steps):
         sl = slice(s * Q, (s + 1) * Q)
@@ -167,17 +186,23 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_si
         stats = rbe.rbe_get_search_stats(ix)
         fallbacks += int(stats["fallback"])
         if stats["n_levels"] and not stats["fallback"]:
-            scan_ms.append(stats["scan_ms"][-1])
+            # the last (largest) level of the plan: one launch, or two when the library takes it in two parts
+            parts = stats["last_level_parts"]
+            scan_ms.append(sum(stats["scan_ms"][-parts:]))
+            last_items.append(sum(stats["items_scanned"][-parts:]))
+            split_steps += int(parts == 2)
             select_ms.append(sum(stats["select_ms"]))
             total_gpu.append(stats["total_gpu_ms"])
             deep_rows.append(stats["deep_rows"])
             deep_units.append(stats["deep_units"])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin
+    gc.enable()
     return {
         "wall_s": wall, "per_step_ms": np.array(per_step), "scan_ms": np.array(scan_ms),
         "select_ms": np.array(select_ms), "total_gpu_ms": np.array(total_gpu), "stats": stats,
         "ids": all_ids, "deep_rows": np.array(deep_rows), "deep_units": np.array(deep_units), "fallbacks": fallbacks,
+        "last_items": int(last_items[-1]) if last_items else 0, "split_steps": split_steps,
     }
 
 
@@ -186,6 +211,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--settle-seconds", type=float, default=0.4,
+                    help="untimed one-query searches after each corpus build, before the warm-up steps (0 = none)")
     ap.add_argument("--items", type=int, default=1_000_000_000)
     ap.add_argument("--dim", type=int, default=64)
     ap.add_argument("--planes", type=int, default=3)
@@ -211,14 +238,14 @@ def main():
                     "hybrid, batch, batch_popcount, cpu, paper, config5, config3 (headline alone = the contract's steps)")
     args = ap.parse_args()
     only = {x for x in args.only.split(",") if x}
-    known = {"headline", "all_planes", "near", "hybrid", "batch", "batch_popcount", "cpu", "paper", "config5", "config3"}
+    known = {"headline", "all_planes", "near", "mixed", "hybrid", "batch", "batch_popcount", "cpu", "paper", "config5", "config3"}
     if only - known:
         print(f"bench.py: unknown legs {sorted(only - known)}", file=sys.stderr)
         sys.exit(2)
 
     def want(leg: str) -> bool:
         return leg in only if only else True
-    main_corpus = not only or bool(only & {"headline", "all_planes", "near", "hybrid", "batch", "batch_popcount", "cpu"})
+    main_corpus = not only or bool(only & {"headline", "all_planes", "near", "mixed", "hybrid", "batch", "batch_popcount", "cpu"})
 
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the whole 1e9-item corpus fits one MI355X); "
@@ -254,6 +281,7 @@ def main():
     ix, centres, host_planes, host_scales = build_corpus(
         rbe, rbe_synth, torch, N, d, P, args.clusters, args.sigma, args.chunk_items, cpu_items)
     rbe.rbe_set_profiling(ix, True)
+    settled = settle(rbe, rbe_synth, torch, ix, centres, args.sigma, P, k, args.settle_seconds)
 
     # ---------------- single-query leg (the timed steps of the contract)
     n_q1 = args.warmup + args.steps
@@ -262,7 +290,7 @@ def main():
     ms_per_step = r1["wall_s"] * 1e3 / args.steps
     value = N * args.steps / r1["wall_s"]
     st = r1["stats"]
-    last_items = st["items_scanned"][-1] if st["n_levels"] else N
+    last_items = r1["last_items"] if st["n_levels"] else N
     scan_avg_ms = float(r1["scan_ms"].mean()) if r1["scan_ms"].size else float("nan")
     # The finest-level scan of one query is progressive: of every item it reads every plane but the last and
     # one-byte copies of the matching scale arrays (plus one precomputed fp32 per row of 256 items, the row's
@@ -291,6 +319,9 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settle": {"seconds": args.settle_seconds, "searches": settled,
+                   "note": "untimed one-query searches between the corpus build and the warm-up steps (set-up): the first 0.2 s "
+                           "of searches after the build run about 4 % slower than the rate they settle at"},
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -325,6 +356,9 @@ def main():
             "bytes_per_launch_all_planes": last_items * bytes_per_item,
             "gbs_if_all_planes_counted": all_planes_gbs,
             "kernel_ms": scan_avg_ms,
+            "launches": "kernel_ms, bytes_per_launch and rows cover the last level of the plan: one launch of the kernel, or, in the "
+                        "steps where the library takes that level in two parts, its two launches together (same bytes, times added)",
+            "steps_with_the_level_in_two_launches": r1["split_steps"],
             "grid_blocks": st["grid_blocks"],
             "algorithmic_bytes_per_item": bytes_per_item,
             "algorithmic_bytes_per_launch": last_items * bytes_per_item,
@@ -399,6 +433,37 @@ def main():
         }
         log(f"near-lossless I={I}, queue length 2: {rn2['wall_s'] * 1e3 / steps2:.3f} ms/step, recall {np.mean(rec2):.5f}")
 
+    # ---------------- mixed workload: one query per call, a share of the queries far from every cluster (their
+    # k-th best score is so low that the last level's bound prunes nothing and the scan reads every plane).  The
+    # one thing a one-query search takes from earlier searches is whether its last level goes in one launch or two,
+    # so the latency of the ordinary queries is reported for the mix, by class.
+    if want("mixed"):
+        n_mix, share = 200, 0.1
+        rng_mix = np.random.default_rng(12345)
+        far = rng_mix.random(n_mix) < share
+        qn_p, qn_s = make_queries(rbe, rbe_synth, torch, centres, n_mix, args.sigma, P, 11)
+        qf_p, qf_s = make_queries(rbe, rbe_synth, torch, centres, n_mix, 10.0, P, 12)      # sigma 10: no cluster left
+        lat, rows_full, lv = [], [], []
+        for i in range(n_mix):
+            qp_i, qs_i = (qf_p, qf_s) if far[i] else (qn_p, qn_s)
+            t0 = time.perf_counter()
+            rbe.rbe_search(ix, qp_i[i:i + 1], qs_i[i:i + 1], k)
+            lat.append((time.perf_counter() - t0) * 1e3)
+            st = rbe.rbe_get_search_stats(ix)
+            rows_full.append(st["deep_rows"]); lv.append(st["last_level_parts"])
+        lat = np.array(lat); lv = np.array(lv)
+        def dist(x):
+            return {"n": int(x.size), "p50_ms": float(np.percentile(x, 50)), "p95_ms": float(np.percentile(x, 95)),
+                    "p99_ms": float(np.percentile(x, 99)), "max_ms": float(x.max()), "mean_ms": float(x.mean())}
+        out["mixed_workload"] = {"queries": n_mix, "share_far_from_every_cluster": share,
+                                 "ordinary": dist(lat[~far][2:]), "far": dist(lat[far]),
+                                 "searches_with_the_last_level_in_two_parts": int((lv == 2).sum())}
+        rbe.rbe_debug_set_plan_split(ix, 0)          # forget what this leg taught the index
+        log(f"mixed workload ({share:.0%} of {n_mix} queries far from every cluster): ordinary queries p50 "
+            f"{out['mixed_workload']['ordinary']['p50_ms']:.3f} p95 {out['mixed_workload']['ordinary']['p95_ms']:.3f} p99 "
+            f"{out['mixed_workload']['ordinary']['p99_ms']:.3f} ms; far queries p50 {out['mixed_workload']['far']['p50_ms']:.3f} ms; "
+            f"{out['mixed_workload']['searches_with_the_last_level_in_two_parts']} searches took the last level in two parts")
+
     # ---------------- hybrid scoring: fp32 query against the binary items (the paper's model m_5)
     if not args.no_hybrid and want("hybrid"):
         xq = rbe_synth.vectors_torch(args.warmup + args.steps, centres, args.sigma, rbe_synth.SEED_QUERIES, 0).cpu().numpy()
@@ -410,7 +475,7 @@ def main():
         for s_ in range(args.warmup, args.warmup + args.steps):
             rbe.rbe_search_float(ix, xq[s_:s_ + 1], k)
             h_stats = rbe.rbe_get_search_stats(ix)
-            h_scan.append(h_stats["scan_ms"][-1]); h_deep.append(h_stats["deep_rows"]); h_units.append(h_stats["deep_units"])
+            h_scan.append(sum(h_stats["scan_ms"][-h_stats["last_level_parts"]:])); h_deep.append(h_stats["deep_rows"]); h_units.append(h_stats["deep_units"])
         torch.cuda.synchronize()
         h_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         # progressive like the binary-query scan: bytes read = streamed planes and scales + the last plane of some rows
@@ -444,7 +509,7 @@ def main():
         rb = timed_searches(rbe, torch, ix, qpb, qsb, B, k, args.batch_steps, bw)
         b_ms = rb["wall_s"] * 1e3 / args.batch_steps
         b_scan = float(rb["scan_ms"].mean()) if rb["scan_ms"].size else float("nan")
-        b_items = rb["stats"]["items_scanned"][-1]
+        b_items = rb["last_items"]
         matrix_cores = B >= 5 and W <= 2     # the library's own choice of kernel for a batch (binary queries, general scales)
         if matrix_cores:
             # dense contraction [B x d] . [d x items] per corpus plane (one eight-bit integer per query component:
@@ -497,7 +562,7 @@ def main():
             rbe.rbe_debug_set_batch_path(ix, 0)
             v_ms = rv["wall_s"] * 1e3 / steps_v
             v_scan = float(rv["scan_ms"].mean())
-            v_ach = lane_ops_per_pair(W, P, P) * B * rv["stats"]["items_scanned"][-1] / (v_scan * 1e-3) / 1e12
+            v_ach = lane_ops_per_pair(W, P, P) * B * rv["last_items"] / (v_scan * 1e-3) / 1e12
             out["batch_popcount_kernel"] = {
                 "queries_per_step": B, "steps": steps_v, "ms_per_step": v_ms,
                 "ms_per_step_progressive": rvp["wall_s"] * 1e3 / steps_v,
@@ -630,10 +695,11 @@ def extra_legs(out, args, want, rbe, rbe_synth, torch, np):
         ixp, centres_p, _, _ = build_corpus(rbe, rbe_synth, torch, Np, 64, Pk, args.clusters, args.sigma,
                                             args.chunk_items, 0, rbe.RBE_DYADIC | rbe.RBE_COSINE)
         rbe.rbe_set_profiling(ixp, True)
+        settle(rbe, rbe_synth, torch, ixp, centres_p, args.sigma, Pq, k, args.settle_seconds, binary_scales=False)
         qpp, _ = make_queries(rbe, rbe_synth, torch, centres_p, n_q1, args.sigma, Pq, 2)
         rp = timed_searches(rbe, torch, ixp, qpp, None, 1, k, args.steps, args.warmup)
         rpn = timed_searches(rbe, torch, ixp, qpp, None, 1, k, args.steps, args.warmup, rbe.RBE_SELECT_NEARLOSSLESS, 256)
-        p_items = rp["stats"]["items_scanned"][-1]
+        p_items = rp["last_items"]
         p_scan = float(rp["scan_ms"].mean())
         p_deep = float(rp["deep_rows"].mean()) if rp["deep_rows"].size else 0.0
         # plane 0 of every item, one fp32 per row, and what the lanes asked for beyond that (plane 1 + inverse norm)
@@ -659,7 +725,7 @@ def extra_legs(out, args, want, rbe, rbe_synth, torch, np):
             qpb, _ = make_queries(rbe, rbe_synth, torch, centres_p, (2 + args.batch_steps) * B, args.sigma, Pq, 3)
             rpb = timed_searches(rbe, torch, ixp, qpb, None, B, k, args.batch_steps, 2)
             pb_scan = float(rpb["scan_ms"].mean())
-            pb_items = rpb["stats"]["items_scanned"][-1]
+            pb_items = rpb["last_items"]
             pb_ms = rpb["wall_s"] * 1e3 / args.batch_steps
             pb_ach = 2.0 * B * pb_items * 64 * Pk / (pb_scan * 1e-3) / 1e12
             out["paper_operating_point"]["batch"] = {
@@ -693,6 +759,7 @@ def config_leg(rbe, rbe_synth, torch, np, args, *, N, d, P, clusters, sigma, Q, 
     W = d // 64
     ix, centres, _, _ = build_corpus(rbe, rbe_synth, torch, N, d, P, clusters, sigma, args.chunk_items, 0)
     rbe.rbe_set_profiling(ix, True)
+    settle(rbe, rbe_synth, torch, ix, centres, sigma, P, k, args.settle_seconds)
     steps, warm = args.config_steps, 2
     qp, qs = make_queries(rbe, rbe_synth, torch, centres, (warm + steps) * Q, sigma, P, seed_chunk)
     r = timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warm)

@@ -305,9 +305,9 @@ typedef struct rbe_search_stats {
     uint32_t n_levels;        /* scan+select rounds of the last search           */
     uint32_t fallback;        /* 1 if the bounded-segment slow path was taken    */
     uint32_t grid_blocks;     /* workgroups of the widest scan launch            */
-    uint32_t deep_rows;       /* one query, exact mode: rows of 256 items whose
-                                 last plane the last scan had to read (the others
-                                 were ruled out by the other planes and the scales)  */
+    uint32_t deep_rows;       /* exact mode, pruning scans: rows of 256 items whose
+                                 last plane had to be read (the others were ruled
+                                 out by the other planes and the scales), all rounds */
     uint64_t items_scanned[RBE_MAX_LEVELS];   /* items read by each scan         */
     uint64_t candidates_max[RBE_MAX_LEVELS];  /* largest per-query candidate
                                                  count handed to each select     */
@@ -320,6 +320,10 @@ typedef struct rbe_search_stats {
                                  the threshold, whole rows in the fallback), in
                                  units of 8 bytes                                 */
     uint32_t scan_kernel[RBE_MAX_LEVELS];     /* which scan each level ran: RBE_KERNEL_* */
+    uint32_t last_level_parts;                /* 1, or 2 if the last (largest) level was taken
+                                                 in two parts, the last two rounds       */
+    uint32_t deep_rows_level[RBE_MAX_LEVELS]; /* deep_rows, round by round               */
+    uint32_t reserved;
 } rbe_search_stats;
 
 enum {                        /* rbe_search_stats.scan_kernel                      */

@@ -45,13 +45,15 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
 int rbe_debug_set_progressive(rbe_index *ix, int enabled);
 
 /* The last level of an exact search in two parts (an eighth of its items, a
- * selection, then the rest, which starts from a much tighter threshold).  The
- * library does this on its own once a one-query search has found the last level's
- * usual threshold too loose for its pruning scan on this corpus (most rows read in
- * full); if that does not help either, the pruning scans stay off for the next 256
- * searches and are then tried again.  mode 0 = these automatic choices (and forget
- * what was learnt), 1 = never split and never stand down, 2 = always split.
- * Results do not depend on any of it.                                            */
+ * selection, then the rest, which starts from a much tighter threshold, so that
+ * the pruning scans rule out more).  mode 0 = the library's rule: every search on
+ * an index that can prune whose last level has 4096 tiles or more -- except that
+ * searches of ONE binary query, the one case where the split can cost more than
+ * it saves (1 %), take the level whole for 64 searches after 4 split searches in a
+ * row whose second part let through no smaller a share of its rows than the
+ * first, and then ask again (setting mode 0 also forgets that count);
+ * 1 = never split; 2 = always (from 16 tiles on).  Results do not depend on any
+ * of it.                                                                         */
 int rbe_debug_set_plan_split(rbe_index *ix, int mode);
 
 /* The mass of one query as the progressive scan uses it (pure host function, for

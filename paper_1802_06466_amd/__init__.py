@@ -50,6 +50,9 @@ class rbe_search_stats(ctypes.Structure):
         ("total_gpu_ms", ctypes.c_float),
         ("deep_units", ctypes.c_uint32),
         ("scan_kernel", ctypes.c_uint32 * RBE_MAX_LEVELS),
+        ("last_level_parts", ctypes.c_uint32),
+        ("deep_rows_level", ctypes.c_uint32 * RBE_MAX_LEVELS),
+        ("reserved", ctypes.c_uint32),
     ]
 
 
@@ -421,6 +424,7 @@ def rbe_get_search_stats(ix: Index) -> dict:
         "scan_ms": list(st.scan_ms)[:n], "select_ms": list(st.select_ms)[:n],
         "total_gpu_ms": st.total_gpu_ms, "deep_units": st.deep_units,
         "scan_kernel": [KERNEL_NAMES.get(v, str(v)) for v in list(st.scan_kernel)[:n]],
+        "last_level_parts": st.last_level_parts, "deep_rows_level": list(st.deep_rows_level)[:n],
     }
 
 

@@ -48,8 +48,11 @@ void set_error(const char* fmt, ...)
     } while (0)
 
 constexpr uint32_t kMaxEvents = 2 * RBE_MAX_LEVELS + 2;
-// Searches during which the pruning scans stay off after two searches in a row found nothing to prune.
-constexpr uint32_t kPruneHoldoff = 256;
+// Last level in two parts (see run_search), one binary query per call: split searches in a row that the tighter
+// threshold did not help before the level is taken whole, and the searches it then stays whole.
+constexpr uint32_t kSplitStreak = 4;
+constexpr uint32_t kWholeSearches = 64;
+constexpr uint32_t kSplitMinTiles = 4096;     // smaller last levels are not split: a launch and a selection would show
 // layout of the block a search sends back (rbe_index::d_result)
 constexpr size_t kResultStatusBytes = 256;
 constexpr size_t kResultHeaderBytes = kResultStatusBytes + (size_t)RBE_MAX_LEVELS * RBE_MAX_QUERIES * sizeof(uint32_t);
@@ -128,13 +131,13 @@ struct rbe_index {
     int hint_base[3] = {1, 1, 1};   // exponent base of each array's hints
     float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize),
                                     // followed by [n_tiles][4] largest scale sum per row
-    int plan_split = 0;             // last level in two parts: 0 = when the searches so far call for it, 1 = never, 2 = always
-    // State of the automatic choices (see run_search), kept apart for searches on the XOR/popcount and table scans
-    // [0] and for batches on the matrix cores [1]: what prunes for one need not prune for the other.
-    struct PruneState {
-        bool split_active = false;
-        uint32_t holdoff = 0;       // searches left during which the pruning scans stay off / the level stays whole
-    } prune[2];
+    int plan_split = 0;             // last level in two parts: 0 = if it has kSplitMinTiles tiles (see run_search), 1 = never, 2 = always
+    // One binary query per call: the only searches for which the split can cost more than it saves (1 %, where
+    // the last level's own threshold already lies inside the query's neighbourhood).  See run_search.
+    struct SplitState {
+        uint32_t streak = 0;        // split searches in a row whose second part pruned no better than the first
+        uint32_t whole_left = 0;    // searches left that take the level whole
+    } split1;
     int progressive = 1;            // one query, exact mode, last level: read planes 1.. only where plane 0 leaves a chance
     float batch_margin = 0.0f;      // BatchArgs::margin of the staged batch
     bool batch_i8 = false;          // the staged operands are eight-bit integers (BatchArgs::operand = 1)
@@ -1309,7 +1312,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
     hipError_t e;
     if (c.float_query) {
         e = hipSuccess;
-        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0 && can_prune(ix);
+        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && can_prune(ix);
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
         const size_t per_q = (size_t)8 * ix->W * 256;
         for (uint32_t q = 0; q < c.Q && e == hipSuccess; ++q) {   // one pass over the range per query
@@ -1353,7 +1356,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         sa.tau = ix->ws.tau; sa.out = out;
         sa.p_begin = r.begin; sa.p_end = r.end;
         // one query against a level that has a threshold: plane 0 and the scales decide which rows need the rest
-        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && ix->prune[0].holdoff == 0 && can_prune(ix);
+        sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && can_prune(ix);
         // (several queries: the scan that streams the scale copies is ahead up to four queries per call, 4.3 against
         // 5.2 ms for two, level with the one that streams the fp32 scales at five, behind from six on)
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2 && c.Q <= 4;
@@ -1454,9 +1457,8 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     const uint32_t per_unit = mode == RBE_SELECT_EXACT ? kTileItems : kRow * c.qlen;
     std::vector<Round> plan;
     bool split = false;
-    rbe_index::PruneState& ps = ix->prune[c.batch_mfma ? 1 : 0];
-    if (mode == RBE_SELECT_EXACT && ps.holdoff > 0) --ps.holdoff;
-    const bool pruning = ix->progressive != 0 && ix->P >= 2 && ps.holdoff == 0 && can_prune(ix);
+    rbe_index::SplitState& ss = ix->split1;
+    const bool pruning = ix->progressive != 0 && ix->P >= 2 && can_prune(ix);
     if (mode == RBE_SELECT_EXACT) {
         for (const Level& lv : make_plan(ix->layout, c.cap, k)) plan.push_back(Round{lv.p_begin, lv.p_end, 1, 0});
         // A batch on the matrix cores: the level before the last starts from the k-th best of a 1/ratio sample of
@@ -1474,12 +1476,19 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
             }
         }
         c.look_from = plan.empty() ? 0u : (uint32_t)plan.size() - 1;     // the last level (both parts of it, if it is split below)
-        // The pruning scans of the last level need a threshold that lies inside the query's neighbourhood.  When the
-        // last level's own threshold (the k-th best of a 1/ratio sample) turned out too loose for that on this
-        // corpus, the level is taken in two parts: an eighth of it first, after which the rest starts from the k-th
-        // best of about an eighth of the corpus.  Costs a launch and a selection, so it is not the default.
-        split = ix->plan_split == 2 || (ix->plan_split == 0 && ps.split_active);
-        const uint32_t min_tiles = ix->plan_split == 2 ? 16u : 4096u;   // on its own only where a launch and a selection are small change
+        // The pruning scans of the last level need a threshold that lies inside the query's neighbourhood, and the
+        // level's own threshold (the k-th best of a 1/ratio sample of the corpus) often does not: the level is taken
+        // in two parts, an eighth of it first, after which the rest starts from the k-th best of about an eighth of
+        // the corpus.  Costs a launch and a selection; measured whole / split: 16 queries over 1e9 items 7.97 / 7.20
+        // ms, 8 queries k = 4000 9.2 / 7.7, 64 queries over 1e8 items (d = 128) 11.8 / 7.1, one query there 1.35 /
+        // 1.03, the 1.2e9-item dyadic point 1.95 / 1.80 (mean), 3 queries and one fp32 query over 1e9 items 5.26 /
+        // 5.23 and 3.03 / 3.02 -- and one binary query over 1e9 items 2.87 / 2.90, the one case that loses.  So the
+        // split is the rule, and no search's plan depends on earlier searches, except that one-binary-query
+        // searches take the level whole for kWholeSearches searches after kSplitStreak split searches in a row
+        // whose second part let through no fewer rows than the first (rate for rate); then they ask again.
+        const bool one_binary = c.Q == 1 && !c.float_query && !c.batch_mfma;
+        split = ix->plan_split == 2 || (ix->plan_split == 0 && pruning && !(one_binary && ss.whole_left > 0));
+        const uint32_t min_tiles = ix->plan_split == 2 ? 16u : kSplitMinTiles;
         if (split && plan.size() >= 2 && plan.size() < RBE_MAX_LEVELS && plan.back().end - plan.back().begin >= min_tiles) {
             const Round last = plan.back();
             const uint32_t mid = last.begin + (last.end - last.begin) / 8;
@@ -1550,36 +1559,23 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
 
     ix->stats.deep_units = ix->h_status[14];
     ix->stats.deep_rows = 0;
-    for (uint32_t l = 0; l < RBE_MAX_LEVELS; ++l) ix->stats.deep_rows += ix->h_status[1 + l];
-    // one query, the pruning scan in use: did the last level's threshold let it prune?  If most rows were read in
-    // full, later searches split the last level; if that does not help either, they stop doing so for good.
-    // (one launch per query with fp32 queries, one per call otherwise: rows_last counts them all)
-    if (!fallback && mode == RBE_SELECT_EXACT && !c.batch_mfma && pruning && plan.size() >= 2) {
-        const uint64_t rows_last = (uint64_t)(plan.back().end - plan.back().begin) * (kTileItems / kRow) * (c.float_query ? c.Q : 1u);
-        bool loose = (uint64_t)ix->h_status[1 + plan.size() - 1] * 2 > rows_last;
-        if (c.Q > 1 && !c.float_query) {
-            // several binary queries on the XOR/popcount scan: what counts is the share of (query, row) pairs scored
-            // in full over the whole last level (most rows are needed by some query of a large batch)
-            const uint64_t pairs = (uint64_t)(plan.back().end - plan[c.look_from].begin) * (kTileItems / kRow) * c.Q;
-            loose = (uint64_t)ix->h_status[9] * 2 > pairs;
-        }
-        if (loose && ix->plan_split == 0) {
-            if (!split && !ps.split_active) {
-                ps.split_active = true;      // next search: the last level in two parts
-            } else {
-                // not even the tighter threshold lets them prune (or the level is too small to split): plain scans
-                // for a while, then another try
-                ps.split_active = false; ps.holdoff = kPruneHoldoff;
-            }
-        }
+    for (uint32_t l = 0; l < RBE_MAX_LEVELS; ++l) {
+        ix->stats.deep_rows_level[l] = ix->h_status[1 + l];
+        ix->stats.deep_rows += ix->h_status[1 + l];
     }
-    // the same for a batch on the matrix cores: waves that ran and waves that gave up leaving the last plane out of
-    // their first look (with the split, the loose first part has an eighth of the work)
-    if (!fallback && mode == RBE_SELECT_EXACT && c.batch_mfma && !c.float_batch && ix->h_status[12] > 0 && plan.size() >= 2) {
-        const bool loose = (uint64_t)ix->h_status[13] * 2 > ix->h_status[12];
-        if (loose && ix->plan_split == 0 && ps.holdoff == 0) {
-            if (!split && !ps.split_active) ps.split_active = true;
-            else { ps.split_active = false; ps.holdoff = kPruneHoldoff; }   // the level stays whole for a while
+    ix->stats.last_level_parts = (!fallback && split) ? 2u : 1u;
+    // one binary query, the pruning scan in use (see the plan above): did the second part of the last level let
+    // through a smaller share of its rows than the first?
+    if (!fallback && mode == RBE_SELECT_EXACT && c.Q == 1 && !c.float_query && !c.batch_mfma && pruning && ix->plan_split == 0) {
+        if (!split) {
+            if (ss.whole_left > 0) --ss.whole_left;
+        } else {
+            const size_t L = plan.size();
+            const uint64_t rows1 = (uint64_t)(plan[L - 2].end - plan[L - 2].begin), rows2 = (uint64_t)(plan[L - 1].end - plan[L - 1].begin);
+            const uint64_t deep1 = ix->h_status[1 + (L - 2)], deep2 = ix->h_status[1 + (L - 1)];
+            const bool helped = deep2 * rows1 * 4 < deep1 * rows2 * 3;       // a quarter fewer, rate for rate
+            ss.streak = helped ? 0u : ss.streak + 1u;
+            if (ss.streak >= kSplitStreak) { ss.streak = 0; ss.whole_left = kWholeSearches; }
         }
     }
     if (!fallback) {
@@ -1813,7 +1809,7 @@ int rbe_debug_set_plan_split(rbe_index* ix, int mode)
     ARG_CHECK(ix != nullptr, "index is NULL");
     ARG_CHECK(mode >= 0 && mode <= 2, "mode must be 0 (automatic), 1 (never) or 2 (always)");
     ix->plan_split = mode;
-    if (mode == 0) ix->prune[0] = ix->prune[1] = rbe_index::PruneState{};
+    if (mode == 0) ix->split1 = rbe_index::SplitState{};
     return RBE_OK;
 }
 

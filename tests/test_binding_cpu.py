@@ -68,7 +68,7 @@ def test_constants_match_header():
     for name in ("RBE_BORROW", "RBE_COSINE", "RBE_DYADIC"):
         m = re.search(r"%s\s*=\s*1u\s*<<\s*(\d+)" % name, text)
         assert m and (1 << int(m.group(1))) == getattr(rbe, name), name
-    assert ctypes.sizeof(rbe.rbe_search_stats) == 16 + 8 * 8 * 2 + 4 * 8 * 2 + 8 + 4 * 8
+    assert ctypes.sizeof(rbe.rbe_search_stats) == 16 + 8 * 8 * 2 + 4 * 8 * 2 + 8 + 4 * 8 + 4 + 4 * 8 + 4
     for code, name in rbe.KERNEL_NAMES.items():
         assert re.search(r"RBE_KERNEL_[A-Z_]+\s*=\s*%d\b" % code, text), name
 

@@ -1283,9 +1283,10 @@ def test_last_level_in_two_parts_gives_the_same_results():
     rbe.rbe_free(ix)
 
 
-def test_last_level_is_split_automatically_when_its_threshold_is_loose():
-    """5 M items in clusters of about 800: ratio * k = 64 * 30 lies outside the cluster, so the first search (unsplit)
-    reads most rows in full; from the second search on the last level is taken in two parts and the scan prunes."""
+def test_last_level_in_two_parts_prunes_where_its_own_threshold_is_loose():
+    """5 M items in clusters of about 800: ratio * k = 64 * 30 lies outside the cluster, so with the last level whole
+    most rows are read in full; taken in two parts (the default for a level of this size) the scan prunes.  Same
+    results either way."""
     import torch
     N, d, P, k = 5_000_000, 64, 3, 30
     centres = rbe_synth.centres_torch(6000, d, torch.device("cuda:0"))
@@ -1298,23 +1299,30 @@ def test_last_level_is_split_automatically_when_its_threshold_is_loose():
     x = rbe_synth.vectors_torch(3, centres, 0.3, rbe_synth.SEED_QUERIES, 0).cpu().numpy()
     enc = [rbe.rbe_encode_query(x[i], P) for i in range(3)]
     qp = np.stack([e[0] for e in enc]); qs = np.stack([e[1] for e in enc])
-    r0 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
-    st0 = rbe.rbe_get_search_stats(ix)
     r1 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
     st1 = rbe.rbe_get_search_stats(ix)
+    rbe.rbe_debug_set_plan_split(ix, 1)
+    r0 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    st0 = rbe.rbe_get_search_stats(ix)
+    assert st0["last_level_parts"] == 1 and st1["last_level_parts"] == 2
     assert st1["n_levels"] == st0["n_levels"] + 1, (st0["n_levels"], st1["n_levels"])
     assert st1["deep_rows"] < st0["deep_rows"] // 2, (st0["deep_rows"], st1["deep_rows"])
+    assert sum(st1["deep_rows_level"]) == st1["deep_rows"]
     np.testing.assert_array_equal(r0[0], r1[0]); np.testing.assert_array_equal(r0[1], r1[1])
-    rbe.rbe_debug_set_plan_split(ix, 1)
-    r2 = rbe.rbe_search(ix, qp[:1], qs[:1], k)
-    np.testing.assert_array_equal(r0[0], r2[0]); np.testing.assert_array_equal(r0[1], r2[1])
+    # it helped, so it stays: one-query searches drop the split only after several in a row that it did not help
+    rbe.rbe_debug_set_plan_split(ix, 0)
+    for i in range(8):
+        rbe.rbe_search(ix, qp[i % 3:i % 3 + 1], qs[i % 3:i % 3 + 1], k)
+        assert rbe.rbe_get_search_stats(ix)["last_level_parts"] == 2
     rbe.rbe_free(ix)
 
 
-def test_pruning_scans_stand_down_on_a_corpus_they_cannot_prune():
-    """Unclustered corpus: every row has to be read in full.  The first search finds that out, the second tries the
-    last level in two parts, after that the pruning scans stay off for a while (plain scans, no rows counted) --
-    and every search returns the same result as the plain scan."""
+def test_a_corpus_that_cannot_be_pruned_keeps_its_pruning_scans_and_drops_the_split_for_one_query_only():
+    """Unclustered corpus: every row has to be read in full, split or not.  One-query searches take the last level
+    in two parts four times, find the second part no better than the first each time, and then take it whole (for
+    the next 64 searches); batches and fp32 queries keep the split, whatever came before them.  The pruning scans
+    stay on throughout (their waves read like the plain scan once their bound has failed them; rows are still
+    counted), and every search returns what the plain scan returns."""
     N, d, P, k = 5_000_000, 64, 3, 30
     import torch
     centres = rbe_synth.centres_torch(64, d, torch.device("cuda:0"))
@@ -1324,16 +1332,33 @@ def test_pruning_scans_stand_down_on_a_corpus_they_cannot_prune():
         pl, sc = rbe_synth.pack_planes_torch(v, P)
         rbe.rbe_load_chunk(ix, z0, pl, sc)
     rbe.rbe_finalize(ix)
-    x = rbe_synth.vectors_torch(1, centres, 10.0, rbe_synth.SEED_QUERIES, 0).cpu().numpy()
-    qp, qs = rbe.rbe_encode_query(x[0], P)
+    x = rbe_synth.vectors_torch(4, centres, 10.0, rbe_synth.SEED_QUERIES, 0).cpu().numpy()
+    enc = [rbe.rbe_encode_query(x[i], P) for i in range(4)]
+    qp = np.stack([e[0] for e in enc]); qs = np.stack([e[1] for e in enc])
     seen = []
-    for _ in range(4):
-        r = rbe.rbe_search(ix, qp[None], qs[None], k)
+    for _ in range(7):
+        r = rbe.rbe_search(ix, qp[:1], qs[:1], k)
         st = rbe.rbe_get_search_stats(ix)
-        seen.append((st["n_levels"], st["deep_rows"] > 0, r))
-    assert [s[:2] for s in seen] == [(3, True), (4, True), (3, False), (3, False)], [s[:2] for s in seen]
-    for s_ in seen[1:]:
-        np.testing.assert_array_equal(s_[2][0], seen[0][2][0]); np.testing.assert_array_equal(s_[2][1], seen[0][2][1])
+        seen.append((st["last_level_parts"], st["deep_rows"] > 0, st["scan_kernel"][st["n_levels"] - 1], r))
+    assert [s[:2] for s in seen] == [(2, True)] * 4 + [(1, True)] * 3, [s[:2] for s in seen]
+    assert all(s[2] != "scan_exact" for s in seen), [s[2] for s in seen]
+    r3 = rbe.rbe_search(ix, qp[1:4], qs[1:4], k)                 # a small batch: split, as always
+    assert rbe.rbe_get_search_stats(ix)["last_level_parts"] == 2
+    rf = rbe.rbe_search_float(ix, x[:1], k)                      # an fp32 query: split, as always
+    assert rbe.rbe_get_search_stats(ix)["last_level_parts"] == 2
+    r_again = rbe.rbe_search(ix, qp[:1], qs[:1], k)              # and the one-query searches are where they were
+    assert rbe.rbe_get_search_stats(ix)["last_level_parts"] == 1
+    rbe.rbe_debug_set_progressive(ix, False)
+    plain = rbe.rbe_search(ix, qp[:1], qs[:1], k)
+    st = rbe.rbe_get_search_stats(ix)
+    assert st["scan_kernel"][st["n_levels"] - 1] == "scan_exact" and st["last_level_parts"] == 1
+    for s_ in seen:
+        np.testing.assert_array_equal(s_[3][0], plain[0]); np.testing.assert_array_equal(s_[3][1], plain[1])
+    np.testing.assert_array_equal(r_again[0], plain[0])
+    plain3 = rbe.rbe_search(ix, qp[1:4], qs[1:4], k)
+    np.testing.assert_array_equal(r3[0], plain3[0]); np.testing.assert_array_equal(r3[1], plain3[1])
+    plainf = rbe.rbe_search_float(ix, x[:1], k)
+    np.testing.assert_array_equal(rf[0], plainf[0]); np.testing.assert_array_equal(rf[1], plainf[1])
     rbe.rbe_free(ix)
 
 
