@@ -24,8 +24,8 @@
  * With 5 or more queries per call (7 or more for RBE_DYADIC; exact mode, dim <= 128)
  * the pairs are first filtered on the matrix cores: sum_j a_j[z] * (qhat . b_z^j),
  * qhat = sum_i c_i b_q^i reconstructed on the host in double and carried as eight-bit
- * integers times a power of two (half-precision numbers for fp32 queries and for
- * indexes whose scales exceed 2^80), with a slack that covers the rounding; what
+ * integers times a power of two (half-precision numbers for indexes whose scales
+ * exceed 2^80), with a slack that covers the rounding; what
  * can reach the threshold is then scored by the formula above, so the results do
  * not depend on the number of queries per call.  (RBE_DYADIC: the half-precision
  * form is exact and is the score.)  Such a call reads the corpus once per 32

@@ -135,7 +135,7 @@ int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, co
                              uint32_t dyadic, uint16_t *halves_out, size_t halves_capacity,
                              float *unscale_out, float *start_out, uint32_t *shape_out);
 
-/* The eight-bit integer operands the matrix-core scan filters binary queries on
+/* The eight-bit integer operands the matrix-core scan filters queries on
  * general scales with (Eq. 14 as a dense contraction; pure host arithmetic, no GPU
  * needed).  qhat = sum_i c_i b_q^i is rounded to T_d 2^e with integers |T_d| <= 126;
  * bytes_out [tile = query / 16][dim / 64 parts][lane = 16 g + query % 16][16]: byte
@@ -145,12 +145,14 @@ int rbe_debug_batch_operands(const uint64_t *q_planes, const float *q_scales, co
  * - 32 sum_d T_d whose bit pattern the accumulators start from; mass_out [Q] =
  * sum_d |qhat_d| in those units, rounded up; *margin_out = the bound, per unit of
  * an item's scale sum and in those units, on |filter value - score| for every
- * query of the batch.  bytes_capacity: bytes available at bytes_out (EINVAL and
- * the count needed in rbe_last_error() if too small).  All pointers: host.       */
-int rbe_debug_batch_operands_i8(const uint64_t *q_planes, const float *q_scales, uint32_t n_queries,
-                                uint32_t q_n_planes, uint32_t dim, int8_t *bytes_out,
-                                size_t bytes_capacity, float *unscale_out, float *start_out,
-                                float *mass_out, float *margin_out);
+ * query of the batch.  q_float != NULL: [n_queries][dim] fp32 queries (hybrid
+ * scoring) take the place of qhat and q_planes / q_scales / q_n_planes are not
+ * read.  bytes_capacity: bytes available at bytes_out (EINVAL and the count needed
+ * in rbe_last_error() if too small).  All pointers: host.                        */
+int rbe_debug_batch_operands_i8(const uint64_t *q_planes, const float *q_scales, const float *q_float,
+                                uint32_t n_queries, uint32_t q_n_planes, uint32_t dim,
+                                int8_t *bytes_out, size_t bytes_capacity, float *unscale_out,
+                                float *start_out, float *mass_out, float *margin_out);
 
 /* Measurement yardstick: enqueues a plain copy kernel ("calib_copy") of `bytes`
  * bytes from src_dev to dst_dev (DEVICE pointers, 16-byte aligned, bytes a

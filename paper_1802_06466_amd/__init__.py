@@ -97,7 +97,7 @@ PROTOTYPES = {
     "rbe_debug_query_mass": (_i32, [_vp, _vp, _u32, _u32, _u32, _vp]),
     "rbe_debug_exact_plan": (_i32, [_u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_debug_batch_operands": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
-    "rbe_debug_batch_operands_i8": (_i32, [_vp, _vp, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp, _vp]),
+    "rbe_debug_batch_operands_i8": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp, _vp]),
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
@@ -476,19 +476,25 @@ def rbe_debug_batch_operands(q_planes, q_scales, dim: int, n_planes: int, dyadic
     return out, unscale, start, float(shape[3:4].view(np.float32)[0])
 
 
-def rbe_debug_batch_operands_i8(q_planes, q_scales, dim: int):
-    """Eight-bit integer query operands of the matrix-core batch scan (host only; binary queries on general
-    scales): int8 [tile][part][lane][16], unscale [Q], start [Q], mass [Q] and the filter margin."""
-    q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
-    q_scales = np.ascontiguousarray(q_scales, dtype=np.float32)
-    Q, Pq = q_planes.shape[0], q_planes.shape[1]
+def rbe_debug_batch_operands_i8(q_planes, q_scales, dim: int, q_float=None):
+    """Eight-bit integer query operands of the matrix-core batch scan (host only; general scales): int8
+    [tile][part][lane][16], unscale [Q], start [Q], mass [Q] and the filter margin.  q_float [Q][dim] replaces
+    the binary queries."""
+    if q_float is not None:
+        q_float = np.ascontiguousarray(q_float, dtype=np.float32)
+        Q, Pq = q_float.shape[0], 0
+    else:
+        q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
+        q_scales = np.ascontiguousarray(q_scales, dtype=np.float32)
+        Q, Pq = q_planes.shape[0], q_planes.shape[1]
     tiles, parts = (Q + 15) // 16, dim // 64
     ops = np.zeros((tiles, parts, 64, 16), dtype=np.int8)
     unscale, start, mass = (np.zeros(Q, dtype=np.float32) for _ in range(3))
     margin = np.zeros(1, dtype=np.float32)
-    _check(load_library().rbe_debug_batch_operands_i8(q_planes.ctypes.data, q_scales.ctypes.data, Q, Pq, dim, ops.ctypes.data,
-                                                      ops.nbytes, unscale.ctypes.data, start.ctypes.data, mass.ctypes.data,
-                                                      margin.ctypes.data))
+    _check(load_library().rbe_debug_batch_operands_i8(
+        None if q_float is not None else q_planes.ctypes.data, None if q_float is not None else q_scales.ctypes.data,
+        None if q_float is None else q_float.ctypes.data, Q, Pq, dim, ops.ctypes.data, ops.nbytes,
+        unscale.ctypes.data, start.ctypes.data, mass.ctypes.data, margin.ctypes.data))
     return ops, unscale, start, mass, float(margin[0])
 
 

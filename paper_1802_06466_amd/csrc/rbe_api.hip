@@ -654,8 +654,11 @@ void build_batch_operands(uint32_t W, uint32_t P, bool dyadic, const uint64_t* q
 // (sum_d |qhat_d - 2^e T_d|), the multiply-adds through which the start constant leaves again (its product with
 // the item's scale sum is rounded once, and each of two multiply-adds rounds at that magnitude: <= 3 units; 4
 // are allowed), and the roundings of the XOR/popcount arithmetic (<= 2^-20 d sum_i |c_i|).
+// q_float != nullptr: the queries are given in full precision ([Q][dim], hybrid scoring), q_planes / q_scales are
+// not read, and the margin allows for the byte-table arithmetic (<= 2^-19 sum_d |q_d|) in place of the XOR/popcount one.
 void build_batch_operands_i8(uint32_t W, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
-                             int8_t* bytes, float* unscale, float* bias, float* margin, float* qmass)
+                             int8_t* bytes, float* unscale, float* bias, float* margin, float* qmass,
+                             const float* q_float = nullptr)
 {
     const uint32_t dim = 64 * W, tiles = batch_tiles(Q);
     std::memset(bytes, 0, (size_t)tiles * W * 64 * 16);
@@ -665,15 +668,20 @@ void build_batch_operands_i8(uint32_t W, const uint64_t* q_planes, const float* 
         double biggest = 0.0, coef = 0.0;
         for (uint32_t d = 0; d < dim; ++d) {
             double v = 0.0;
-            for (uint32_t i = 0; i < PQ; ++i) {
-                const double c = (double)q_scales[(size_t)q * PQ + i];
-                const uint64_t word = q_planes[((size_t)q * PQ + i) * W + d / 64];
-                v += ((word >> (d % 64)) & 1ull) ? c : -c;
+            if (q_float) {
+                v = (double)q_float[(size_t)q * dim + d];
+            } else {
+                for (uint32_t i = 0; i < PQ; ++i) {
+                    const double c = (double)q_scales[(size_t)q * PQ + i];
+                    const uint64_t word = q_planes[((size_t)q * PQ + i) * W + d / 64];
+                    v += ((word >> (d % 64)) & 1ull) ? c : -c;
+                }
             }
             qhat[d] = v;
             biggest = std::max(biggest, std::fabs(v));
         }
-        for (uint32_t i = 0; i < PQ; ++i) coef += std::fabs((double)q_scales[(size_t)q * PQ + i]);
+        if (!q_float)
+            for (uint32_t i = 0; i < PQ; ++i) coef += std::fabs((double)q_scales[(size_t)q * PQ + i]);
         int e = 0;
         if (biggest > 0.0) {
             e = std::ilogb(biggest) - 6;                        // biggest / 2^e in [64, 128)
@@ -703,17 +711,18 @@ void build_batch_operands_i8(uint32_t W, const uint64_t* q_planes, const float* 
         float mf = (float)m_abs;
         if ((double)mf < m_abs) mf = std::nextafter(mf, INFINITY);
         qmass[q] = mf;
-        worst = std::max(worst, lost / unit + 4.0 + std::ldexp(coef * dim / unit, -20));
+        worst = std::max(worst, lost / unit + 4.0 + std::ldexp(coef * dim / unit, -20) + (q_float ? std::ldexp(mass / unit, -19) : 0.0));
     }
     *margin = (float)(worst * (1.0 + std::ldexp(1.0, -10)));
 }
 
-// Integer operands serve binary queries on general scales; path 3 of rbe_debug_set_batch_path keeps the halves.
+// Integer operands serve general scales (binary and fp32 queries); path 3 of rbe_debug_set_batch_path keeps the halves.
 bool batch_operand_i8(const rbe_index* ix, bool float_query)
 {
+    (void)float_query;
     // (the accumulators' start constant, 1.5 * 2^23, is multiplied by the item's scale sum on its way out: scales
     // beyond 2^80 -- which would bring that product near the end of the fp32 range -- keep the halves)
-    return ix->mode == rbe::kModeScaled && !float_query && ix->batch_path != 3 && ix->scale_max <= 0x1p80f;
+    return ix->mode == rbe::kModeScaled && ix->batch_path != 3 && ix->scale_max <= 0x1p80f;
 }
 
 int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
@@ -723,7 +732,7 @@ int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_
     ix->batch_i8 = batch_operand_i8(ix, q_float != nullptr);
     if (ix->batch_i8) {
         build_batch_operands_i8(ix->W, q_planes, q_scales, Q, PQ, reinterpret_cast<int8_t*>(ix->h_aops), ix->h_unscale,
-                                ix->h_unscale + RBE_MAX_QUERIES, &ix->batch_margin, ix->h_unscale + 2 * RBE_MAX_QUERIES);
+                                ix->h_unscale + RBE_MAX_QUERIES, &ix->batch_margin, ix->h_unscale + 2 * RBE_MAX_QUERIES, q_float);
         HIP_TRY(hipMemcpyAsync(ix->ws.aops, ix->h_aops, (size_t)batch_tiles(Q) * ix->W * 64 * 16, hipMemcpyHostToDevice, st));
         HIP_TRY(hipMemcpyAsync(ix->ws.unscale, ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
         return RBE_OK;
@@ -971,19 +980,23 @@ int rbe_debug_batch_operands(const uint64_t* q_planes, const float* q_scales, co
     return RBE_OK;
 }
 
-int rbe_debug_batch_operands_i8(const uint64_t* q_planes, const float* q_scales, uint32_t n_queries, uint32_t q_n_planes,
-                                uint32_t dim, int8_t* bytes_out, size_t bytes_capacity, float* unscale_out,
-                                float* start_out, float* mass_out, float* margin_out)
+int rbe_debug_batch_operands_i8(const uint64_t* q_planes, const float* q_scales, const float* q_float, uint32_t n_queries,
+                                uint32_t q_n_planes, uint32_t dim, int8_t* bytes_out, size_t bytes_capacity,
+                                float* unscale_out, float* start_out, float* mass_out, float* margin_out)
 {
-    ARG_CHECK(q_planes && q_scales && bytes_out && unscale_out && start_out && mass_out && margin_out, "NULL argument");
+    ARG_CHECK(bytes_out && unscale_out && start_out && mass_out && margin_out, "NULL argument");
+    ARG_CHECK(q_float || (q_planes && q_scales), "queries missing");
     ARG_CHECK(dim == 64 || dim == 128, "dim must be 64 or 128");
-    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes out of range");
+    ARG_CHECK(q_float || (q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES), "q_n_planes out of range");
     ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries out of range");
-    for (size_t i = 0; i < (size_t)n_queries * q_n_planes; ++i) ARG_CHECK(std::isfinite(q_scales[i]), "q_scales[%zu] is not finite", i);
+    if (q_float)
+        for (size_t i = 0; i < (size_t)n_queries * dim; ++i) ARG_CHECK(std::isfinite(q_float[i]), "q_float[%zu] is not finite", i);
+    else
+        for (size_t i = 0; i < (size_t)n_queries * q_n_planes; ++i) ARG_CHECK(std::isfinite(q_scales[i]), "q_scales[%zu] is not finite", i);
     const size_t need = (size_t)batch_tiles(n_queries) * (dim / 64) * 64 * 16;
     ARG_CHECK(bytes_capacity >= need, "bytes_out too small: %zu needed", need);
     build_batch_operands_i8(dim / 64, q_planes, q_scales, n_queries, q_n_planes, bytes_out, unscale_out, start_out,
-                            margin_out, mass_out);
+                            margin_out, mass_out, q_float);
     return RBE_OK;
 }
 

@@ -36,7 +36,7 @@
 // lane-ops to P fused multiply-adds and one compare; bit expansion is paid once per
 // item, whatever the number of queries.
 //
-// Integer operands (OP = 1; binary queries on general scales).  The filter needs no more than a few bits of the
+// Integer operands (OP = 1; general scales, binary and fp32 queries).  The filter needs no more than a few bits of the
 // query: with qhat rounded to eight-bit integers T_d (times a power of two), v_mfma_i32_16x16x64_i8 contracts a
 // whole 64-dimension plane per instruction -- half the matrix instructions -- and a dword of four operand BYTES
 // comes out of one AND: lane group g shifts the plane's two 32-bit parts left by 6 - 2g, and the masks
@@ -128,7 +128,7 @@ void scan_batch_mfma(const BatchArgs a)
     constexpr int S = scale_arrays(MODE, P);
     constexpr int KP = 2 * W;                          // 32-dimension parts of a plane
     constexpr bool kI8 = OP == 1;
-    static_assert(!kI8 || (MODE == kModeScaled && RS == 1), "integer operands: the filter of binary queries on general scales");
+    static_assert(!kI8 || (MODE == kModeScaled && (RS == 1 || RS == 2)), "integer operands: the filter on general scales");
     using acc_t = std::conditional_t<kI8, intx4, floatx4>;
     // General scales: one accumulator per plane (the item's a_j is applied afterwards); the query's hi half
     // filters.  Dyadic modes: the plane weight 2^-j is folded into a per-plane copy of the query operand, all
@@ -515,7 +515,11 @@ BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib)
 {
     if (nqt != 1 && nqt != 2) return nullptr;
     if constexpr (MODE == kModeScaled) {
-        if (operand == 1) {     // eight-bit integer operands: binary queries
+        if (operand == 1) {     // eight-bit integer operands
+            if (rescore == 2) {
+                if (calib) return nullptr;
+                return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 2, 1> : scan_batch_mfma<W, P, MODE, 2, 2, 1>;
+            }
             if (rescore != 1) return nullptr;
             if (calib) return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1, 1, true> : scan_batch_mfma<W, P, MODE, 2, 1, 1, true>;
             return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1, 1> : scan_batch_mfma<W, P, MODE, 2, 1, 1>;

@@ -424,19 +424,25 @@ def _i8_accumulator(start_q, stored, odd, bits):
     return np.array([acc], dtype=np.int32).view(np.float32)[0]
 
 
-@pytest.mark.parametrize("dim,Pq,Q", [(64, 3, 16), (128, 4, 33), (64, 1, 3)])
+@pytest.mark.parametrize("dim,Pq,Q", [(64, 3, 16), (128, 4, 33), (64, 1, 3), (64, 0, 5), (128, 0, 17)])
 def test_integer_operands_contract_to_the_rounded_query(lib, dim, Pq, Q):
     """The integer contraction, emulated from the operand bytes alone, equals 1.5 2^23 + 32 sum_d T_d rho_d for
     every plane tried; T is qhat rounded to integers times a power of two, |T| <= 126 (odd slots even); and the
     value is within the margin of qhat . rho in the filter's units."""
     rng = np.random.default_rng(dim + Pq)
     W = dim // 64
-    qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
-    qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
-    qs[0] *= np.float32(2.0 ** -40); qs[1 % Q] *= np.float32(2.0 ** 30)       # the unit follows the query's size
-    ops, unscale, start, mass, margin = rbe.rbe_debug_batch_operands_i8(qp, qs, dim)
-    qbits = ((qp[:, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
-    qhat = (qs.astype(np.float64)[:, :, None, None] * (2 * qbits - 1)).sum(axis=1).reshape(Q, dim)
+    if Pq == 0:         # fp32 queries (hybrid scoring): the query itself takes the place of qhat
+        qf = rng.standard_normal((Q, dim)).astype(np.float32)
+        qf[0] *= np.float32(2.0 ** -40); qf[1] *= np.float32(2.0 ** 30)
+        ops, unscale, start, mass, margin = rbe.rbe_debug_batch_operands_i8(None, None, dim, q_float=qf)
+        qhat = qf.astype(np.float64)
+    else:
+        qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
+        qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
+        qs[0] *= np.float32(2.0 ** -40); qs[1 % Q] *= np.float32(2.0 ** 30)       # the unit follows the query's size
+        ops, unscale, start, mass, margin = rbe.rbe_debug_batch_operands_i8(qp, qs, dim)
+        qbits = ((qp[:, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
+        qhat = (qs.astype(np.float64)[:, :, None, None] * (2 * qbits - 1)).sum(axis=1).reshape(Q, dim)
     lg = np.log2(unscale.astype(np.float64))
     assert np.array_equal(lg, np.round(lg))
     for q in range(Q):

@@ -870,6 +870,11 @@ def test_float_query_batches_use_the_matrix_cores_and_match_the_table_path(N, d,
     # the contraction only filters; what passes is scored from the byte tables, so both paths agree bit for bit
     np.testing.assert_array_equal(sc_m, sc_t)
     np.testing.assert_array_equal(ids_m, ids_t)
+    rbe.rbe_debug_set_batch_path(ix, 3)            # half operands (the default contracts eight-bit integers)
+    ids_h, sc_h = rbe.rbe_search_float(ix, q, k)
+    np.testing.assert_array_equal(sc_h, sc_t)
+    np.testing.assert_array_equal(ids_h, ids_t)
+    rbe.rbe_debug_set_batch_path(ix, 0)
     # components 2^-30 of the largest one (their operand halves would be subnormal) and a zero query
     q2 = q.copy()
     q2[1, ::3] *= 2.0 ** -30
