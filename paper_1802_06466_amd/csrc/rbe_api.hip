@@ -508,11 +508,11 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
     if (float_query && ix->mode != rbe::kModeScaled) return false;
     if (ix->batch_path == 1) return false;
     if (ix->batch_path >= 2) return true;
-    // Measured crossover, 1e9 items d=64 P=3, whole search.  Integer operands (binary queries on general scales):
-    // 4 queries 6.7 ms on the XOR/popcount scan and 7.2 ms here, 5 queries 8.1 and 7.3 ms; a 16-query tile costs
-    // this scan about as much as 4.5 queries cost the other.  Half operands (the dyadic modes): 6 queries 9.3 ms
-    // either way, 7 queries 10.5 ms there and 9.5 ms here.  The byte-table scan of fp32 queries reads the corpus
-    // once per query, so there the matrix cores win from 3 queries on.
+    // Measured crossover, 1e9 items d=64 P=3, whole search, XOR/popcount scan / this scan.  Integer operands
+    // (general scales): 4 queries 6.5 / 6.7 ms, 5 queries 8.0 / 6.8 ms; a 16-query tile costs this scan about as
+    // much as 4.3 queries cost the other.  Half operands (the dyadic modes), before the last level was taken in two
+    // parts: 6 queries 9.3 ms either way, 7 queries 10.5 / 9.5 ms.  The byte-table scan of fp32 queries reads the
+    // corpus once per query (3.0 ms each), so there the matrix cores win from 3 queries on (7.8 ms).
     if (float_query) return Q >= 3u;
     return Q >= (batch_operand_i8(ix, false) ? 5u : 7u);
 }

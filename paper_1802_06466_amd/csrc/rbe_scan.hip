@@ -142,7 +142,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact(const ScanArgs a)
     else mstage_drain(ms, a.out, lane);
 }
 
-// Several queries (2..6 in practice), P >= 2, progressive: one row in registers, planes 0 .. P-2 and the scales
+// Several queries (a few in practice: larger batches go to the matrix cores), P >= 2, progressive: one row in registers, planes 0 .. P-2 and the scales
 // first; every query forms its partial scores and bounds from them, and the first query for which some item of
 // the row can still reach the threshold has the row's last plane read (once per row), after which it and any
 // later such query continue their partial chains to the full scores.  Most (query, row) pairs stop at the bound:
