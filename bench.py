@@ -292,16 +292,21 @@ def main():
     st = r1["stats"]
     last_items = r1["last_items"] if st["n_levels"] else N
     scan_avg_ms = float(r1["scan_ms"].mean()) if r1["scan_ms"].size else float("nan")
-    # The finest-level scan of one query is progressive: of every item it reads every plane but the last and
-    # one-byte copies of the matching scale arrays (plus one precomputed fp32 per row of 256 items, the row's
-    # largest last scale); for the items that those cannot rule out, the lanes that hold them also read the last
-    # plane and the P fp32 scales (the library counts the bytes they ask for, `deep_units` x 8).  `achieved` is
-    # priced on these bytes; the rate on the bytes of all planes is reported beside it.
+    # The finest-level scan of one query is progressive.  In two stages (three or more planes): of every item it
+    # streams plane 0 and one-byte copies of all its scales; for the items that a bound from those cannot rule out
+    # (gathered 64 at a time) a lane reads the planes 1 .. P-2, and for what a second bound still lets through the
+    # last plane and the P fp32 scales.  With two planes (or the first stage switched off): every plane but the
+    # last and the copies of the matching scales are streamed (plus one fp32 per row of 256 items, the row's largest
+    # last scale).  The library counts the bytes asked for beyond the stream (`deep_units` x 8).  `achieved` is
+    # priced on the bytes moved; the rate on the bytes of all planes is reported beside it.
     deep_avg = float(r1["deep_rows"].mean()) if r1["deep_rows"].size else 0.0
     deep_bytes = float(r1["deep_units"].mean()) * 8.0 if r1["deep_units"].size else 0.0
     deep_row_bytes = 256 * (8 * W + 4)        # (fp32-query scan: whole rows of the last plane and last scale)
+    two_stage = bool(st["n_levels"]) and st["scan_kernel"][-1] == "scan_exact_prog2_hint"
     if P >= 2:
-        stream_bytes_per_item = (P - 1) * 8 * W + (4 if P == 4 else P - 1)     # (three hint bytes travel as four)
+        # (three hint bytes travel as four; the two-stage scan streams plane 0 alone and counts what its lanes ask
+        # for beyond that -- the other planes of the items its first bound lets through -- in deep_units)
+        stream_bytes_per_item = (1 if two_stage else P - 1) * 8 * W + (4 if P == 4 else P - 1) + (1 if two_stage else 0)
         bytes_read = last_items * stream_bytes_per_item + (last_items // 256) * 4 + deep_bytes
     else:
         stream_bytes_per_item = bytes_per_item
@@ -341,7 +346,7 @@ def main():
         "select_ms_total": float(r1["select_ms"].mean()) if r1["select_ms"].size else None,
         "last_search_level_ms": {"scan": st["scan_ms"], "select": st["select_ms"]},
         "roofline": {
-            "kernel": "scan_exact_prog_hint (finest level)" if P >= 2 else "scan_exact (finest level)",
+            "kernel": (st["scan_kernel"][-1] if st["n_levels"] else "scan_exact") + " (finest level)",
             "bound": "hbm",
             "achieved": achieved_gbs,
             "peak": HBM_PEAK_GBS,
@@ -363,8 +368,9 @@ def main():
             "algorithmic_bytes_per_item": bytes_per_item,
             "algorithmic_bytes_per_launch": last_items * bytes_per_item,
             "frac_of_algorithmic": all_planes_gbs / HBM_PEAK_GBS,
-            "note": "achieved/frac price the bytes this kernel MOVES (it prunes: the last plane and the fp32 scales are "
-                    "read only for items whose upper bound reaches the threshold), not the method's %d B/item; "
+            "note": "achieved/frac price the bytes this kernel MOVES (it prunes: of every item it streams plane 0 and one-byte "
+                    "copies of its scales; the other planes are read, lane by lane, only for items whose upper bound "
+                    "reaches the threshold, and the fp32 scales only for those that pass a second bound), not the method's %d B/item; "
                     "frac_of_algorithmic prices all %d B/item over the same time and can exceed 1 for that reason. "
                     "The share pruned depends on the corpus: on one with no cluster structure the library falls back "
                     "to the all-planes scan, whose fraction is worst_case." % (bytes_per_item, bytes_per_item),
@@ -479,7 +485,7 @@ def main():
         torch.cuda.synchronize()
         h_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         # progressive like the binary-query scan: bytes read = streamed planes and scales + the last plane of some rows
-        h_bytes = (last_items * stream_bytes_per_item + (last_items // 256) * 4 + float(np.mean(h_units)) * 8.0
+        h_bytes = (last_items * ((P - 1) * 8 * W + (4 if P == 4 else P - 1)) + (last_items // 256) * 4 + float(np.mean(h_units)) * 8.0
                    if P >= 2 else last_items * bytes_per_item)
         h_gbs = h_bytes / (float(np.mean(h_scan)) * 1e-3) / 1e9
         out["hybrid_float_query"] = {"ms_per_step": h_ms, "value": N / (h_ms * 1e-3), "unit": "candidates/s",

@@ -57,7 +57,7 @@ class rbe_search_stats(ctypes.Structure):
 
 
 KERNEL_NAMES = {0: "none", 1: "scan_exact", 2: "scan_exact_prog", 3: "scan_exact_prog_hint", 4: "scan_batch_mfma",
-                5: "scan_groupmax", 6: "scan_exact_fq", 7: "scan_exact_fq_prog"}
+                5: "scan_groupmax", 6: "scan_exact_fq", 7: "scan_exact_fq_prog", 8: "scan_exact_prog2_hint"}
 
 
 _lib = None
@@ -518,7 +518,7 @@ def rbe_debug_set_plan_split(ix: Index, mode: int):
 
 
 def rbe_debug_set_progressive(ix: Index, enabled):
-    """False/0 = off, True/1 = on, 2 = on without the one-byte scale copies."""
+    """False/0 = off, True/1 = on, 2 = on without the one-byte scale copies, 3 = on without the first stage on plane 0 alone."""
     _check(load_library().rbe_debug_set_progressive(ix.handle, int(enabled)))
 
 

@@ -128,7 +128,8 @@ struct rbe_index {
     int batch_path = 0;             // 0 auto, 1 XOR/popcount kernel always, 2 matrix-core kernel whenever built
     int nl_path = 0;                // near-lossless modes: 0 = exact scans + selection by groups, 1 = the per-thread-queue scan
     uint32_t* d_hints = nullptr;    // general scales, P >= 2: one-byte copies of the scale arrays 0 .. P-2 in lane order (rbe_finalize)
-    int hint_base[3] = {1, 1, 1};   // exponent base of each array's hints
+    int hint_base[4] = {1, 1, 1, 1};   // exponent base of each array's hints ([3]: the last array's, see d_hints_last)
+    uint32_t* d_hints_last = nullptr;  // three or more planes: one-byte copies of the last scale array (inside the d_hints block)
     float* d_row_amax = nullptr;    // [n_tiles][4] largest value of the last scale array per row (set by rbe_finalize),
                                     // followed by [n_tiles][4] largest scale sum per row
     int plan_split = 0;             // last level in two parts: 0 = if it has kSplitMinTiles tiles (see run_search), 1 = never, 2 = always
@@ -805,7 +806,15 @@ static size_t hint_bytes(const rbe_index* ix)
 {
     if (!(ix->mode == rbe::kModeScaled && ix->P >= 2)) return 0;
     const uint32_t nw = ix->P - 1 == 3 ? 4u : ix->P - 1;
-    return (size_t)ix->layout.n_tiles * (kTileItems / 4) * nw * sizeof(uint32_t);
+    return (size_t)ix->layout.n_tiles * (kTileItems / 4) * (nw + (ix->P >= 3 ? 1u : 0u)) * sizeof(uint32_t);
+}
+
+// The copies of the last scale array follow those of the others in the same block.
+static uint32_t* last_hints_of(const rbe_index* ix, uint32_t* hints)
+{
+    if (!hints || ix->P < 3) return nullptr;
+    const uint32_t nw = ix->P - 1 == 3 ? 4u : ix->P - 1;
+    return hints + (size_t)ix->layout.n_tiles * (kTileItems / 4) * nw;
 }
 
 static IndexStorage carve_index_storage(const rbe_index* ix, char* base)
@@ -940,7 +949,8 @@ uint32_t rbe_debug_tile_to_phys(uint32_t n_tiles, uint32_t sample_ratio, uint32_
 uint32_t rbe_debug_phys_to_tile(uint32_t n_tiles, uint32_t sample_ratio, uint32_t phys)
 {
     const rbe::Layout l = rbe::make_layout(n_tiles, sample_ratio);
-    return rbe::phys_to_tile(l, phys);
+    const uint32_t t = rbe::phys_to_tile(l, phys);
+    return t == rbe::phys_to_tile_per_lane(l, phys) ? t : 0xFFFFFFFFu;     // (the two forms must agree)
 }
 
 int rbe_debug_exact_plan(uint64_t n_items, uint32_t sample_ratio, uint32_t cand_capacity, uint32_t k,
@@ -1192,12 +1202,14 @@ int rbe_finalize(rbe_index* ix, void* hip_stream)
         // the largest value, rounded as scale_hints rounds it, gets the largest exponent field (7)
         for (uint32_t j = 0; j + 1 < ix->P; ++j)
             ix->hint_base[j] = std::max(1, (int)((h_max[j] + (1u << 17)) >> 23) - 7);
+        ix->hint_base[3] = std::max(1, (int)((h_max[ix->P - 1] + (1u << 17)) >> 23) - 7);
+        ix->d_hints_last = last_hints_of(ix, ix->d_hints);
         int* d_base = reinterpret_cast<int*>(ix->fin_scratch ? ix->fin_scratch + 128 : nullptr);
-        if (!ix->borrowed) HIP_TRY(hipMalloc(&d_base, 3 * sizeof(int)));
-        hipError_t e = hipMemcpyAsync(d_base, ix->hint_base, 3 * sizeof(int), hipMemcpyHostToDevice, st);
+        if (!ix->borrowed) HIP_TRY(hipMalloc(&d_base, 4 * sizeof(int)));
+        hipError_t e = hipMemcpyAsync(d_base, ix->hint_base, 4 * sizeof(int), hipMemcpyHostToDevice, st);
         if (e == hipSuccess) {
-            if (ix->W == 1) hipLaunchKernelGGL(rbe::scale_hints<1>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_base, ix->d_hints);
-            else hipLaunchKernelGGL(rbe::scale_hints<2>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_base, ix->d_hints);
+            if (ix->W == 1) hipLaunchKernelGGL(rbe::scale_hints<1>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_base, ix->d_hints, ix->d_hints_last);
+            else hipLaunchKernelGGL(rbe::scale_hints<2>, dim3(ix->layout.n_tiles), dim3(256), 0, st, ix->d_tiles, ix->geom, d_base, ix->d_hints, ix->d_hints_last);
             e = hipGetLastError();
         }
         if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -1373,9 +1385,11 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         // (several queries: the scan that streams the scale copies is ahead up to four queries per call, 4.3 against
         // 5.2 ms for two, level with the one that streams the fp32 scales at five, behind from six on)
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2 && c.Q <= 4;
+        sel.two_stage = ix->progressive == 1 && c.Q == 1 && ix->P >= 3 && ix->d_hints_last != nullptr;
         sa.deep_rows = ix->ws.status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints; sa.deep_units = ix->ws.status + 14;
         sa.deep_pairs = level_slot >= c.look_from ? ix->ws.status + 9 : nullptr;
         for (int j = 0; j < 3; ++j) sa.hint_base[j] = ix->hint_base[j];
+        sa.hints_last = ix->d_hints_last; sa.hint_base_last = ix->hint_base[3];
         // survivor queues in LDS: small batches keep the occupancy the HBM-bound scan wants, large ones trade
         // it for sub-queues of 32..64 entries (fewer, larger flushes)
         sa.stage_entries = c.Q <= 8 ? 512u : (c.Q <= 16 ? 1024u : 2048u);
@@ -1396,7 +1410,9 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         if (c.float_query) which = sel.progressive ? RBE_KERNEL_SCAN_FLOAT_PROG : RBE_KERNEL_SCAN_FLOAT;
         else if (c.batch_mfma && !(dense && !c.float_batch && ix->batch_path == 0)) which = RBE_KERNEL_SCAN_BATCH_MFMA;
         else if (c.mode == RBE_SELECT_EXACT)
-            which = !sel.progressive ? RBE_KERNEL_SCAN_EXACT : (sel.hints ? RBE_KERNEL_SCAN_PROG_HINT : RBE_KERNEL_SCAN_PROG);
+            which = !sel.progressive ? RBE_KERNEL_SCAN_EXACT
+                                     : (sel.hints ? (sel.two_stage && c.Q == 1 && ix->mode == rbe::kModeScaled ? RBE_KERNEL_SCAN_PROG2_HINT : RBE_KERNEL_SCAN_PROG_HINT)
+                                                  : RBE_KERNEL_SCAN_PROG);
         ix->stats.scan_kernel[level_slot] = which;
     }
     ix->stats.grid_blocks = std::max(ix->stats.grid_blocks, grid);
@@ -1499,7 +1515,9 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
         // split is the rule, and no search's plan depends on earlier searches, except that one-binary-query
         // searches take the level whole for kWholeSearches searches after kSplitStreak split searches in a row
         // whose second part let through no fewer rows than the first (rate for rate); then they ask again.
-        const bool one_binary = c.Q == 1 && !c.float_query && !c.batch_mfma;
+        // (a one-query scan in two stages gains from every tightening of the threshold: no exception there)
+        const bool two_stage = ix->progressive == 1 && ix->P >= 3 && ix->d_hints_last != nullptr;
+        const bool one_binary = c.Q == 1 && !c.float_query && !c.batch_mfma && !two_stage;
         split = ix->plan_split == 2 || (ix->plan_split == 0 && pruning && !(one_binary && ss.whole_left > 0));
         const uint32_t min_tiles = ix->plan_split == 2 ? 16u : kSplitMinTiles;
         if (split && plan.size() >= 2 && plan.size() < RBE_MAX_LEVELS && plan.back().end - plan.back().begin >= min_tiles) {
@@ -1579,7 +1597,8 @@ static int run_search(SearchCtx& c, int64_t* ids_out, float* scores_out)
     ix->stats.last_level_parts = (!fallback && split) ? 2u : 1u;
     // one binary query, the pruning scan in use (see the plan above): did the second part of the last level let
     // through a smaller share of its rows than the first?
-    if (!fallback && mode == RBE_SELECT_EXACT && c.Q == 1 && !c.float_query && !c.batch_mfma && pruning && ix->plan_split == 0) {
+    if (!fallback && mode == RBE_SELECT_EXACT && c.Q == 1 && !c.float_query && !c.batch_mfma && pruning && ix->plan_split == 0 &&
+        !(ix->progressive == 1 && ix->P >= 3 && ix->d_hints_last != nullptr)) {
         if (!split) {
             if (ss.whole_left > 0) --ss.whole_left;
         } else {
@@ -1829,7 +1848,7 @@ int rbe_debug_set_plan_split(rbe_index* ix, int mode)
 int rbe_debug_set_progressive(rbe_index* ix, int enabled)
 {
     ARG_CHECK(ix != nullptr, "index is NULL");
-    ix->progressive = enabled == 2 ? 2 : (enabled ? 1 : 0);
+    ix->progressive = (enabled == 2 || enabled == 3) ? enabled : (enabled ? 1 : 0);
     return RBE_OK;
 }
 

@@ -16,6 +16,7 @@ struct KernelSel {
     uint32_t qlen = 1;   // near-lossless mode: length of the per-group priority queue (1 or 2)
     bool progressive = false;   // exact mode, last level, P >= 2: read the last plane only where the others cannot rule a row out
     bool hints = false;         // ... one query, general scales: the index holds one-byte copies of the scales
+    bool two_stage = false;     // ... and three or more planes: the stream carries plane 0 only (scan_exact_prog2_hint)
 };
 
 // Grid = min(units, n_cu * per_cu); per_cu == 0 means "as many workgroups as are
@@ -74,10 +75,11 @@ RBE_DECLARE_W(4)
 // planes and scale arrays but the last).  Measured on 1e9 items (ms of the finest-level scan at 1 / 2 / 3 / 4
 // workgroups per unit): 18 KB per tile 2.92 / 2.58 / 2.82 / 2.61, 8 KB 2.57 / 1.56 / 1.25 / 1.28, 24 KB 3.41 / 3.43 /
 // 3.43 / 3.47, 36 KB 5.04 / 5.04 / 5.10 / 5.14, 52 KB (1e8 items) 0.69 / 0.70 / 0.71 / 0.72.
-inline uint32_t streaming_blocks_per_cu(uint32_t W, uint32_t P, uint32_t S, bool progressive, bool hints)
+inline uint32_t streaming_blocks_per_cu(uint32_t W, uint32_t P, uint32_t S, bool progressive, bool hints, bool two_stage = false)
 {
     const bool prog = progressive && P >= 2;
-    const uint32_t planes = prog ? P - 1 : P, scales = prog && S > 0 ? S - 1 : S;
+    const bool two = prog && hints && two_stage && P >= 3;
+    const uint32_t planes = two ? 1u : (prog ? P - 1 : P), scales = prog && S > 0 ? S - 1 : S;
     const uint32_t tile_stream = kTileItems * (8u * W * planes + (prog && hints ? 1u : 4u) * scales);
     const uint32_t n = (32u * 1024u + tile_stream / 2) / tile_stream;
     return n < 1u ? 1u : (n > 3u ? 3u : n);

@@ -511,6 +511,9 @@ struct ScanArgs {
                               // progressive scans; unused where there is no scale array)
     const uint32_t* hints;    // general scales: one-byte copies of the scale arrays 0 .. P-2 in lane order (scale_hints)
     int hint_base[3];         // ... and the exponent base of each array's hints
+    const uint32_t* hints_last;  // three or more planes: one-byte copies of the LAST scale array, [tile][wave][lane] (a byte
+                                 // per item of the lane), for the first stage of scan_exact_prog2_hint
+    int hint_base_last;          // ... and their exponent base
     uint32_t stage_entries;   // several queries: LDS queue entries per wave (512..4096), split into sub-queues
     uint32_t q_slice;         // batch form of scan_exact: queries per workgroup row (blockIdx.y takes queries
                               // [y * q_slice, (y + 1) * q_slice)); 0 = every workgroup applies all queries.  Set by the launcher

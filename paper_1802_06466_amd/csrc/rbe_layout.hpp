@@ -79,6 +79,17 @@ RBE_HD uint32_t phys_to_tile(const Layout& l, uint32_t p)
     return nth_non_multiple(p - l.n_ge[c + 1], l.ratio) * l.pow_r[c];
 }
 
+// phys_to_tile for a physical tile that differs from lane to lane: the same class, found by a loop whose trip
+// count is the same for all lanes (n_ge decreases with the class, so the class of p is the number of classes
+// c >= 1 with p < n_ge[c]).
+RBE_HD uint32_t phys_to_tile_per_lane(const Layout& l, uint32_t p)
+{
+    uint32_t c = 0;
+    for (uint32_t i = 1; i <= l.top; ++i) c += p < l.n_ge[i] ? 1u : 0u;
+    if (c == l.top) return p * l.pow_r[c];
+    return nth_non_multiple(p - l.n_ge[c + 1], l.ratio) * l.pow_r[c];
+}
+
 // Scoring modes (compile-time parameter of the kernels).
 enum : int {
     kModeScaled = 0,      // per-item fp32 scale per plane, fp32 query scales

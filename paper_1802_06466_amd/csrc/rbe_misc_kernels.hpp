@@ -605,7 +605,7 @@ __global__ void scale_array_max(const char* __restrict__ tiles, const TileGeom g
 // Scales are finite and not negative here (the caller has looked at scale_array_max).
 template <int W>
 __global__ void scale_hints(const char* __restrict__ tiles, const TileGeom g, const int* __restrict__ base,
-                            uint32_t* __restrict__ out)
+                            uint32_t* __restrict__ out, uint32_t* __restrict__ out_last)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float* sc = reinterpret_cast<const float*>(tiles + (size_t)blockIdx.x * g.tile_bytes() + g.scales_offset()) + wave * kRow;
@@ -623,6 +623,17 @@ __global__ void scale_hints(const char* __restrict__ tiles, const TileGeom g, co
         dst[j] = word;
     }
     if (nw == 4u) dst[3] = 0;
+    if (out_last) {     // the last array, one word per lane (base[3] is its exponent base)
+        uint32_t word = 0;
+        const int lo = base[3] << 5;
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            const uint32_t b = __float_as_uint(sc[(size_t)(g.S - 1u) * kTileItems + lane_item<W>(lane, m)]);
+            int c = (int)((b + (1u << 17)) >> 18) - lo;
+            c = c < 0 ? 0 : (c > 255 ? 255 : c);
+            word |= (uint32_t)c << (8 * m);
+        }
+        out_last[((size_t)blockIdx.x * kWavesPerBlock + wave) * 64 + lane] = word;
+    }
 }
 
 }  // namespace rbe

@@ -397,25 +397,21 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 // A wave whose bound lets more than a quarter of its rows through gives it up and takes the rest of its rows as
 // scan_exact does (whole rows, prefetched).  The two register sets (this row, the next one in flight) hold the
 // streamed planes only and swap roles from row to row.
-template <int W, int P, int PQ>
-__global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
+// The rows of a wave from tile p on (p, p + grid, ...), with what the wave has queued and counted so far: the whole
+// of scan_exact_prog_hint, and what scan_exact_prog2_hint falls back to.  STREAM_EXTRA: count the planes 1 .. P-2
+// that this stream carries as bytes beyond the (plane 0 only) stream of the caller.
+template <int W, int P, int PQ, bool STREAM_EXTRA>
+__device__ __forceinline__ void prog_hint_rows(const ScanArgs& a, uint32_t p, uint32_t fill, uint32_t full_rows, uint32_t extra8,
+                                               uint64_t* s_keys, int wave, int lane)
 {
     constexpr int MODE = kModeScaled;
     constexpr int S = P, F = P - 1;
     constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
-    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    uint64_t* s_keys = s_keys_all[wave];
     const MultiStage ms{};
     const uint32_t G = gridDim.x;
     const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
     const size_t tile_bytes = geom.tile_bytes();
-
-    uint32_t p = a.p_begin + blockIdx.x;
-    if (p >= a.p_end) return;
-    uint32_t fill = 0, probed = 0, passed = 0, full_rows = 0;
-    uint32_t extra8 = 0;        // bytes / 8 asked for beyond the stream (wave total, kept in lane 0's terms)
+    uint32_t probed = 0, passed = 0;
     const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
     const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
     const QueryMass mass{pm[0], pm[1]};
@@ -499,6 +495,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
             passed += reach ? 1u : 0u;
         }
         full_rows += reach ? 1u : 0u;
+        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
         if (reach) {
             // only the lanes that hold such an item read the rest of their items' data (the memory system fetches
             // the cache lines they touch, not the row) and score; an item whose bound is below the threshold cannot
@@ -569,10 +566,250 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
             fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
             ++full_rows;
             extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item beyond the stream's
+            if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
             if (!has_next) break;
             cur = nxt;
             p = pn;
         }
+    }
+    if (fill) stage_flush1(s_keys, fill, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+    if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
+}
+
+template <int W, int P, int PQ>
+__global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
+{
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    prog_hint_rows<W, P, PQ, false>(a, p, 0u, 0u, 0u, s_keys_all[wave], wave, lane);
+}
+
+// scan_exact_prog_hint in two stages (P >= 3): the stream carries plane 0 and the one-byte scale copies only
+// -- here of ALL P scale arrays, the last one from a side array of its own -- (8W + P bytes per item: 11 instead of
+// 18 at d = 64, P = 3).  Stage A bounds an item's score from plane 0 alone: h_0 t_0 plus the most the other planes
+// (their scale copies times the query's mass) could add.  A plane of 64 signs already tells most items of a corpus
+// apart from a query: about one item in 100 to 200 passes on clustered data, but nearly every ROW of 256 holds one,
+// so what passes is not followed up row by row: it goes to a queue in the wave's LDS area (item, partial score,
+// scale copies, row maximum), and whenever 64 entries have gathered, stage B takes one per lane: the lane reads the
+// item's words of planes 1 .. P-2 (8W bytes each: 64 loads in flight for one round trip) and forms the bound of
+// scan_exact_prog_hint -- the same operations in the same order.  What passes that too (stage C: a few items in
+// 10^4) has all its planes and fp32 scales read by the same lane and is scored from scratch by score_item, so what
+// is appended is still exactly what scan_exact appends.  A wave of whose items more than one in 16 pass stage A
+// gives the first stage up and takes the rest of its rows as scan_exact_prog_hint does (which has its own
+// fallback to whole rows).
+template <int W, int P, int PQ>
+__global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a)
+{
+    static_assert(P >= 3, "with two planes scan_exact_prog_hint streams plane 0 alone already");
+    constexpr int MODE = kModeScaled;
+    constexpr int S = P, F = P - 1;
+    constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
+    constexpr int kQueue = 128;                  // entries per wave: a batch of 64 leaves when 64 have gathered
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ uint32_t s_qid[kWavesPerBlock][kQueue];    // physical tile * 1024 + item of the tile
+    __shared__ float s_qs0[kWavesPerBlock][kQueue];       // floor + h_0 t_0: where the bound's chain stands after plane 0
+    __shared__ uint32_t s_qhb[kWavesPerBlock][kQueue];    // the item's scale copies, array j in byte j
+    __shared__ float s_qam[kWavesPerBlock][kQueue];       // the copy of the item's last scale
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    uint32_t fill = 0, full_rows = 0, extra8 = 0;
+    uint32_t qfill = 0;                       // entries waiting for stage B (wave-uniform)
+    uint32_t last_row = 0xFFFFFFFFu;          // row of the last item that reached stage C (wave-uniform)
+    uint32_t probed = 0, passed = 0;          // items judged by stage A, items it let through (wave-uniform)
+    const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);
+    const float* pm = a.qcoef + (size_t)a.n_queries * (PQ + 1);
+    const QueryMass mass{pm[0], pm[1]};
+    const float slack_all = 2.0f * mass.y + 0.015875f * mass.x;      // as in scan_exact_prog_hint
+    const uint64_t tau0 = a.tau[0];
+    const float taus0 = threshold_score(tau0);
+    const uint32_t hb[3] = {(uint32_t)a.hint_base[0] << 5, (uint32_t)a.hint_base[1] << 5, (uint32_t)a.hint_base[2] << 5};
+    auto decode = [&](uint32_t byte, int j) { return __uint_as_float((byte + hb[j]) << 18); };
+    // a scale below the smallest copy of its array, 2^(base - 127), is off by up to that much instead (all P arrays here)
+    float floor_c = __uint_as_float((uint32_t)a.hint_base_last << 23);
+    for (int j = 0; j < F; ++j) floor_c += __uint_as_float((uint32_t)a.hint_base[j] << 23);
+    floor_c *= 1.0001f * mass.x;
+    const float mass_last = mass.x + 2.0f * mass.y;
+    const float mass_hint = mass_last + slack_all;      // what a plane whose scale is known by its copy can add, per unit of the copy
+    const uint32_t hb_last = (uint32_t)a.hint_base_last << 5;
+
+    struct Hints { uint32_t w[NW]; uint32_t last; };
+    auto load_hints = [&](Hints& h, uint32_t tile_p) {
+        h.last = __builtin_nontemporal_load(a.hints_last + ((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane);
+        const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
+        if constexpr (NW == 2) {
+            const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+            h.w[0] = v.x; h.w[1] = v.y;
+        } else {
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+            h.w[0] = v.x; h.w[1] = v.y; h.w[2] = v.z; h.w[3] = v.w;
+        }
+    };
+
+    // Stage B (and C) for the entries [base, base + n) of the wave's queue, one per lane.  All lanes of the wave.
+    auto follow_up = [&](uint32_t base, uint32_t n) __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const bool act = (uint32_t)lane < n;
+        const uint32_t e = base + (act ? (uint32_t)lane : 0u);
+        const uint32_t id = s_qid[wave][e], hbytes = s_qhb[wave][e];
+        const float h_last = s_qam[wave][e];
+        float s = s_qs0[wave][e];
+        const uint32_t tp = id >> 10, idx = id & 1023u;
+        const char* tile = a.tiles + (size_t)tp * tile_bytes;
+        RowRegs<W, P, S> it;          // this lane's item, in slot 0
+        bool pass2 = false;
+        if (act) {
+            float all = decode(hbytes & 255u, 0);
+#pragma unroll
+            for (int j = 1; j < F; ++j) {
+                const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
+                if constexpr (W == 1) {
+                    const u32x2 v = *reinterpret_cast<const u32x2*>(kw);
+                    it.w[j][0][0] = v.x; it.w[j][0][1] = v.y;
+                } else {
+#pragma unroll
+                    for (int h = 0; h < W / 2; ++h) {
+                        const u32x4 v = reinterpret_cast<const u32x4*>(kw)[h];
+                        it.w[j][0][4 * h + 0] = v.x; it.w[j][0][4 * h + 1] = v.y; it.w[j][0][4 * h + 2] = v.z; it.w[j][0][4 * h + 3] = v.w;
+                    }
+                }
+                float t = q0.bias;
+#pragma unroll
+                for (int i = 0; i < PQ; ++i) {
+                    uint32_t pc = 0;
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(it.w[j][0][h] ^ q0.w[i][h]);
+                    t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                }
+                const float hj = decode((hbytes >> (8 * j)) & 255u, j);
+                s = __fmaf_rn(hj, t, s);
+                all += hj;
+            }
+            // the bound of scan_exact_prog_hint, with the item's own last scale (by its copy) for the row's largest
+            const float ub = __fmaf_rn(all, slack_all, __fmaf_rn(h_last, mass_hint, s));
+            pass2 = !(ub < taus0);
+        }
+        extra8 += n * (uint32_t)W * (uint32_t)(F - 1);
+        const uint64_t m2 = __ballot(pass2);
+        if (m2) {
+            float score = -__builtin_inff();
+            uint64_t logical = 0;
+            if (pass2) {
+                // the rest of the item: plane 0 again (another lane streamed it), the last plane, the fp32 scales
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = jj == 0 ? 0 : P - 1;
+                    const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) it.w[j][0][h] = kw[h];
+                }
+                const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset());
+#pragma unroll
+                for (int j = 0; j < S; ++j) it.a[j][0] = sc[j * kTileItems + idx];
+                score = score_item<W, P, PQ, MODE>(it, 0, q0);
+                logical = (uint64_t)phys_to_tile_per_lane(a.layout, tp) * kTileItems + idx;
+            }
+            bool ok = pass2 && (score >= taus0) && (logical < a.n_items);
+            uint64_t key = 0;
+            if (ok) { key = make_key(score, (uint32_t)logical); ok = key >= tau0; }
+            fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
+            const uint32_t n2 = (uint32_t)__builtin_popcountll(m2);
+            extra8 += n2 * (2u * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
+            // rows that hold such an item: entries leave the queue in the order of their rows, so an item opens a
+            // new row if the nearest lower lane with such an item (or, for the lowest, the last batch) holds another one
+            const uint64_t below = m2 & ((1ull << lane) - 1ull);
+            const int prev = below ? 63 - __builtin_clzll(below) : lane;
+            const uint32_t row = id >> 8, row_prev = __shfl(row, prev);
+            full_rows += (uint32_t)__builtin_popcountll(__ballot(pass2 && row != (below ? row_prev : last_row)));
+            last_row = __shfl(row, 63 - __builtin_clzll(m2));
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    RowRegs<W, P, S> cur, nxt;
+    Hints hc, hn;
+    load_row_planes<W, P, S, 0, 1>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_hints(hc, p);
+    bool give_up = false;
+    for (;;) {
+        if (passed * 10 > probed + 4096) { give_up = true; break; }         // wave-uniform; row p is not done yet
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        const uint32_t pl = has_next ? pn : p;          // (unconditional prefetch: see scan_exact_prog_hint)
+        load_row_planes<W, P, S, 0, 1>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_hints(hn, pl);
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            float t = q0.bias;
+#pragma unroll
+            for (int i = 0; i < PQ; ++i) {
+                uint32_t pc = 0;
+#pragma unroll
+                for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[0][m][h] ^ q0.w[i][h]);
+                t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+            }
+            uint32_t hbytes = 0;
+            float rest = 0.0f;
+#pragma unroll
+            for (int j = 0; j < F; ++j) {
+                const uint32_t c = (hc.w[j] >> (8 * m)) & 255u;
+                hbytes |= c << (8 * j);
+                if (j >= 1) rest += decode(c, j);
+            }
+            const float h0 = decode(hbytes & 255u, 0);
+            const float h_last = __uint_as_float((((hc.last >> (8 * m)) & 255u) + hb_last) << 18);
+            const float s0 = __fmaf_rn(h0, t, floor_c);
+            // a_0 t_0 <= h_0 t_0 + 0.015875 h_0 |t_0| (the copy is within 2^-6 of the scale; t_0 is known here, so
+            // its own size stands where scan_exact_prog_hint has the query's mass); every other plane adds at most
+            // (its copy) x (mass + slack), |t_j| <= mass_last; the roundings of this line and of the chains it
+            // stands for are inside 2 mass.y per unit of the scale sum, as there
+            const float ub = __fmaf_rn(rest + h_last, mass_hint, __fmaf_rn(h0, __fmaf_rn(0.015875f, __builtin_fabsf(t), 2.0f * mass.y), s0));
+            const bool pass = !(ub < taus0);            // (a NaN bound does not prune)
+            const uint64_t mk = __ballot(pass);
+            if (mk) {
+                if (pass) {
+                    const uint32_t at = qfill + (uint32_t)__builtin_popcountll(mk & ((1ull << lane) - 1ull));
+                    s_qid[wave][at] = p * (uint32_t)kTileItems + (uint32_t)wave * kRow + lane_item<W>(lane, m);
+                    s_qs0[wave][at] = s0;
+                    s_qhb[wave][at] = hbytes;
+                    s_qam[wave][at] = h_last;
+                }
+                const uint32_t n = (uint32_t)__builtin_popcountll(mk);
+                qfill += n;
+                passed += n;
+                if (qfill >= 64) {
+                    // the 64 oldest entries leave; the rest (fewer than 64) move to the front
+                    follow_up(0, 64);
+                    qfill -= 64;
+                    const bool mv = (uint32_t)lane < qfill;
+                    const uint32_t from = 64u + (mv ? (uint32_t)lane : 0u);
+                    const uint32_t e_id = s_qid[wave][from], e_hb = s_qhb[wave][from];
+                    const float e_s0 = s_qs0[wave][from], e_am = s_qam[wave][from];
+                    __builtin_amdgcn_wave_barrier();
+                    if (mv) { s_qid[wave][lane] = e_id; s_qhb[wave][lane] = e_hb; s_qs0[wave][lane] = e_s0; s_qam[wave][lane] = e_am; }
+                }
+            }
+        }
+        probed += kRow;
+        if (!has_next) { p = pn; break; }
+        cur = nxt; hc = hn;
+        p = pn;
+    }
+    if (qfill) follow_up(0, qfill);
+    if (give_up) {
+        prog_hint_rows<W, P, PQ, true>(a, p, fill, full_rows, extra8, s_keys, wave, lane);
+        return;
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
@@ -1256,11 +1493,14 @@ using ScanFn = void (*)(const ScanArgs);
 using DenseFn = void (*)(const char*, const Layout, const uint32_t*, const float*, uint64_t, uint64_t, float*);
 
 template <int W, int P, int PQ>
-ScanFn prog_fn_m(int mode, bool single, bool hints)
+ScanFn prog_fn_m(int mode, bool single, bool hints, bool two_stage)
 {
     if constexpr (P >= 2) {
         if (mode == kModeScaled) {
             if (!single) return hints ? scan_exact_batch_prog_hint<W, P, PQ> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
+            if constexpr (P >= 3) {
+                if (hints && two_stage) return scan_exact_prog2_hint<W, P, PQ>;
+            }
             return hints ? scan_exact_prog_hint<W, P, PQ> : scan_exact_prog<W, P, PQ, kModeScaled>;
         }
         if constexpr (dyadic_supported(W)) {
@@ -1309,9 +1549,9 @@ DenseFn dense_fn_m(int mode)
 ScanFn prog_fn(const KernelSel& k)
 {
     switch (k.P) {
-        case 2: RBE_SWITCH_PQ(prog_fn_m, 2, k.mode, k.single, k.hints)
-        case 3: RBE_SWITCH_PQ(prog_fn_m, 3, k.mode, k.single, k.hints)
-        case 4: RBE_SWITCH_PQ(prog_fn_m, 4, k.mode, k.single, k.hints)
+        case 2: RBE_SWITCH_PQ(prog_fn_m, 2, k.mode, k.single, k.hints, k.two_stage)
+        case 3: RBE_SWITCH_PQ(prog_fn_m, 3, k.mode, k.single, k.hints, k.two_stage)
+        case 4: RBE_SWITCH_PQ(prog_fn_m, 4, k.mode, k.single, k.hints, k.two_stage)
         default: return nullptr;
     }
 }
@@ -1448,7 +1688,7 @@ hipError_t launch_scan_exact_w<RBE_W>(const KernelSel& k, const ScanArgs& a, uin
         per_cu = (uint32_t)(nb > 0 ? nb : 1);
         // One query is a pure stream: what matters is the bytes in flight per compute unit, and more workgroups
         // than that needs only spread the accesses (measurements at streaming_blocks_per_cu).
-        if (k.single) per_cu = std::min(per_cu, streaming_blocks_per_cu(RBE_W, k.P, scale_arrays(k.mode, k.P), k.progressive, k.hints));
+        if (k.single) per_cu = std::min(per_cu, streaming_blocks_per_cu(RBE_W, k.P, scale_arrays(k.mode, k.P), k.progressive, k.hints, k.two_stage));
     }
     const uint32_t units = a.p_end - a.p_begin;
     const uint32_t grid = units < n_cu * per_cu ? units : n_cu * per_cu;

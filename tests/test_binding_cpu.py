@@ -70,7 +70,7 @@ def test_constants_match_header():
         assert m and (1 << int(m.group(1))) == getattr(rbe, name), name
     assert ctypes.sizeof(rbe.rbe_search_stats) == 16 + 8 * 8 * 2 + 4 * 8 * 2 + 8 + 4 * 8 + 4 + 4 * 8 + 4
     for code, name in rbe.KERNEL_NAMES.items():
-        assert re.search(r"RBE_KERNEL_[A-Z_]+\s*=\s*%d\b" % code, text), name
+        assert re.search(r"RBE_KERNEL_[A-Z0-9_]+\s*=\s*%d\b" % code, text), name
 
 
 def test_argument_validation_needs_no_gpu(lib):
@@ -96,6 +96,7 @@ def test_caller_owned_memory_entry_points_validate_without_a_gpu(lib):
         total = up(tiles * 1024 * (8 * W * P + 4 * S))
         total += up(2 * tiles * 4 * 4 if S else 0)                      # two floats per row of 256 items
         nw = 0 if (dyadic or P < 2) else (4 if P - 1 == 3 else P - 1)   # one-byte scale copies, a word per 4 items and array
+        nw += 1 if (nw and P >= 3) else 0                               # ... and of the last array, for the two-stage scan
         total += up(tiles * 256 * nw * 4)
         return total + 256
     for N, d, P, flags in [(1, 64, 1, 0), (1_000_000_000, 64, 3, 0), (100_000_000, 128, 4, 0), (1025, 256, 2, 0),

@@ -1040,7 +1040,7 @@ def _search_both_ways(ix, qp, qs, k):
     rows whose last plane was read."""
     rbe.rbe_debug_set_plan_split(ix, 1)      # no automatic choices: the switch alone decides which scan runs
     out, shares = {}, []
-    for prog in (1, 2, 0):           # on; on without the one-byte scale copies; off
+    for prog in (1, 2, 3, 0):        # on; on without the one-byte scale copies; on without the first stage on plane 0; off
         rbe.rbe_debug_set_progressive(ix, prog)
         res = []
         for q in range(qp.shape[0]):
@@ -1053,8 +1053,9 @@ def _search_both_ways(ix, qp, qs, k):
                 assert st["deep_rows"] == 0
         out[prog] = res
     rbe.rbe_debug_set_progressive(ix, True)
-    for (i1, s1), (i2, s2) in zip(out[1], out[2]):
+    for (i1, s1), (i2, s2), (i3, s3) in zip(out[1], out[2], out[3]):
         np.testing.assert_array_equal(i1, i2); np.testing.assert_array_equal(s1, s2)
+        np.testing.assert_array_equal(i1, i3); np.testing.assert_array_equal(s1, s3)
     return out[1], out[0], shares
 
 
@@ -1322,13 +1323,15 @@ def test_last_level_in_two_parts_prunes_where_its_own_threshold_is_loose():
     rbe.rbe_free(ix)
 
 
-def test_a_corpus_that_cannot_be_pruned_keeps_its_pruning_scans_and_drops_the_split_for_one_query_only():
-    """Unclustered corpus: every row has to be read in full, split or not.  One-query searches take the last level
-    in two parts four times, find the second part no better than the first each time, and then take it whole (for
-    the next 64 searches); batches and fp32 queries keep the split, whatever came before them.  The pruning scans
-    stay on throughout (their waves read like the plain scan once their bound has failed them; rows are still
-    counted), and every search returns what the plain scan returns."""
-    N, d, P, k = 5_000_000, 64, 3, 30
+@pytest.mark.parametrize("P", [2, 3])
+def test_a_corpus_that_cannot_be_pruned_keeps_its_pruning_scans_and_drops_the_split_for_one_query_only(P):
+    """Unclustered corpus: every row has to be read in full, split or not.  With two planes, one-query searches take
+    the last level in two parts four times, find the second part no better than the first each time, and then take
+    it whole (for the next 64 searches); with three planes their scan has a first stage on plane 0 alone, which
+    gains from any tighter threshold, and the split stays.  Batches and fp32 queries keep the split, whatever came
+    before them.  The pruning scans stay on throughout (their waves read like the plain scan once their bound has
+    failed them; rows are still counted), and every search returns what the plain scan returns."""
+    N, d, k = 5_000_000, 64, 30
     import torch
     centres = rbe_synth.centres_torch(64, d, torch.device("cuda:0"))
     ix = rbe.rbe_index_create(N, d, P, 0)
@@ -1345,14 +1348,15 @@ def test_a_corpus_that_cannot_be_pruned_keeps_its_pruning_scans_and_drops_the_sp
         r = rbe.rbe_search(ix, qp[:1], qs[:1], k)
         st = rbe.rbe_get_search_stats(ix)
         seen.append((st["last_level_parts"], st["deep_rows"] > 0, st["scan_kernel"][st["n_levels"] - 1], r))
-    assert [s[:2] for s in seen] == [(2, True)] * 4 + [(1, True)] * 3, [s[:2] for s in seen]
-    assert all(s[2] != "scan_exact" for s in seen), [s[2] for s in seen]
+    want = [(2, True)] * 7 if P == 3 else [(2, True)] * 4 + [(1, True)] * 3
+    assert [s[:2] for s in seen] == want, [s[:2] for s in seen]
+    assert all(s[2] == ("scan_exact_prog2_hint" if P == 3 else "scan_exact_prog_hint") for s in seen), [s[2] for s in seen]
     r3 = rbe.rbe_search(ix, qp[1:4], qs[1:4], k)                 # a small batch: split, as always
     assert rbe.rbe_get_search_stats(ix)["last_level_parts"] == 2
     rf = rbe.rbe_search_float(ix, x[:1], k)                      # an fp32 query: split, as always
     assert rbe.rbe_get_search_stats(ix)["last_level_parts"] == 2
     r_again = rbe.rbe_search(ix, qp[:1], qs[:1], k)              # and the one-query searches are where they were
-    assert rbe.rbe_get_search_stats(ix)["last_level_parts"] == 1
+    assert rbe.rbe_get_search_stats(ix)["last_level_parts"] == (2 if P == 3 else 1)
     rbe.rbe_debug_set_progressive(ix, False)
     plain = rbe.rbe_search(ix, qp[:1], qs[:1], k)
     st = rbe.rbe_get_search_stats(ix)
