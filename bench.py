@@ -510,7 +510,7 @@ def main():
     # ---------------- batch leg
     if args.batch > 0 and want("batch"):
         B = args.batch
-        bw = 2
+        bw = 4
         qpb, qsb = make_queries(rbe, rbe_synth, torch, centres, (bw + args.batch_steps) * B, args.sigma, P, 1)
         rb = timed_searches(rbe, torch, ix, qpb, qsb, B, k, args.batch_steps, bw)
         b_ms = rb["wall_s"] * 1e3 / args.batch_steps
@@ -654,6 +654,11 @@ def main():
     out["roofline"]["traffic"] = measured_traffic(out["config"]["workload"])
     out["roofline"]["traffic_source"] = ("profiles/scan_exact_1e9_d64_p3_q1.md: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE of "
                                          "this kernel on this workload, scaled by the plain-copy yardstick; not measured in this run")
+    if out["roofline"]["traffic"] and out["roofline"].get("kernel_ms"):
+        # what the memory system moved for those bytes (the lane-wise reads bring whole lines), over this run's time
+        t_gbs = out["roofline"]["traffic"] / (out["roofline"]["kernel_ms"] * 1e-3) / 1e9
+        out["roofline"]["traffic_gbs"] = t_gbs
+        out["roofline"]["traffic_frac"] = t_gbs / HBM_PEAK_GBS
     print(json.dumps(out), flush=True)
 
 
@@ -728,8 +733,8 @@ def extra_legs(out, args, want, rbe, rbe_synth, torch, np):
             f"near-lossless {rpn['wall_s'] * 1e3 / args.steps:.3f} ms/step, recall {np.mean(rec):.5f}")
         if args.batch >= 7:
             B = args.batch
-            qpb, _ = make_queries(rbe, rbe_synth, torch, centres_p, (2 + args.batch_steps) * B, args.sigma, Pq, 3)
-            rpb = timed_searches(rbe, torch, ixp, qpb, None, B, k, args.batch_steps, 2)
+            qpb, _ = make_queries(rbe, rbe_synth, torch, centres_p, (4 + args.batch_steps) * B, args.sigma, Pq, 3)
+            rpb = timed_searches(rbe, torch, ixp, qpb, None, B, k, args.batch_steps, 4)
             pb_scan = float(rpb["scan_ms"].mean())
             pb_items = rpb["last_items"]
             pb_ms = rpb["wall_s"] * 1e3 / args.batch_steps
@@ -766,7 +771,7 @@ def config_leg(rbe, rbe_synth, torch, np, args, *, N, d, P, clusters, sigma, Q, 
     ix, centres, _, _ = build_corpus(rbe, rbe_synth, torch, N, d, P, clusters, sigma, args.chunk_items, 0)
     rbe.rbe_set_profiling(ix, True)
     settle(rbe, rbe_synth, torch, ix, centres, sigma, P, k, args.settle_seconds)
-    steps, warm = args.config_steps, 2
+    steps, warm = args.config_steps, 4
     qp, qs = make_queries(rbe, rbe_synth, torch, centres, (warm + steps) * Q, sigma, P, seed_chunk)
     r = timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warm)
     ms = r["wall_s"] * 1e3 / steps
