@@ -641,6 +641,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
     floor_c *= 1.0001f * mass.x;
     const float mass_last = mass.x + 2.0f * mass.y;
     const float mass_hint = mass_last + slack_all;      // what a plane whose scale is known by its copy can add, per unit of the copy
+    const float floor_0 = 1.0001f * __uint_as_float((uint32_t)a.hint_base[0] << 23);
     const uint32_t hb_last = (uint32_t)a.hint_base_last << 5;
 
     struct Hints { uint32_t w[NW]; uint32_t last; };
@@ -769,12 +770,16 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
             }
             const float h0 = decode(hbytes & 255u, 0);
             const float h_last = __uint_as_float((((hc.last >> (8 * m)) & 255u) + hb_last) << 18);
-            const float s0 = __fmaf_rn(h0, t, floor_c);
-            // a_0 t_0 <= h_0 t_0 + 0.015875 h_0 |t_0| (the copy is within 2^-6 of the scale; t_0 is known here, so
-            // its own size stands where scan_exact_prog_hint has the query's mass); every other plane adds at most
-            // (its copy) x (mass + slack), |t_j| <= mass_last; the roundings of this line and of the chains it
-            // stands for are inside 2 mass.y per unit of the scale sum, as there
-            const float ub = __fmaf_rn(rest + h_last, mass_hint, __fmaf_rn(h0, __fmaf_rn(0.015875f, __builtin_fabsf(t), 2.0f * mass.y), s0));
+            const float s0 = __fmaf_rn(h0, t, floor_c);         // (where stage B takes the chain up)
+            // a_0 t_0 <= h_0 t_0 + (0.015875 h_0 + floor_0) |t_0|: the copy is within 2^-6 of the scale, or, for a
+            // scale below the smallest copy, above it by less than that copy (floor_0); t_0 is known here, so its
+            // own size stands where scan_exact_prog_hint has the query's mass.  Every other plane adds at most
+            // (its copy) x (mass + slack): |t_j| <= mass_last, and a copy that is not within 2^-6 of its scale is
+            // above it.  The roundings of this line and of the chains it stands for are inside 2 mass.y per unit
+            // of the scale sum, as there.
+            const float at = __builtin_fabsf(t);
+            const float ub = __fmaf_rn(rest + h_last, mass_hint,
+                                       __fmaf_rn(at, __fmaf_rn(0.015875f, h0, floor_0), __fmaf_rn(h0, t, 2.0f * mass.y * h0)));
             const bool pass = !(ub < taus0);            // (a NaN bound does not prune)
             const uint64_t mk = __ballot(pass);
             if (mk) {

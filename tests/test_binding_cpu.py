@@ -592,6 +592,67 @@ def test_last_plane_bound_holds_for_scales_at_least_zero_and_fails_below(lib):
     assert bound(planes, scales)[0] < true[0] - 0.5 * M, "the bound no longer covers the last plane"
 
 
+def _scale_copy_codec(a):
+    """One-byte copies of a scale array as rbe_finalize makes them (written out from their description: a 3-bit
+    exponent above a per-array base -- the array's largest value gets exponent field 7 -- and the top 5 mantissa
+    bits, rounded to nearest; smaller values, zeros included, get the smallest code).  Returns (decoded copies, base)."""
+    bits = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.int64)
+    base = max(1, int((bits.max() + (1 << 17)) >> 23) - 7)
+    code = np.clip(((bits + (1 << 17)) >> 18) - (base << 5), 0, 255)
+    return ((code + (base << 5)) << 18).astype(np.uint32).view(np.float32).astype(np.float64), base
+
+
+def test_first_stage_bound_of_the_two_stage_scan_is_an_upper_bound(lib):
+    """Host-side evaluation, in float64, of the bound the two-stage one-query scan forms from plane 0 and the
+    one-byte scale copies:
+        bound(z) = h_0 t_0 + (e h_0 + 2^(base_0 - 127)) |t_0| + (1 + e) M sum_{j>=1} h_j,   e = 0.015875,
+    h_j the decoded copies, t_0 = qhat . rho_0, M the library's query mass.  It is never below the oracle's score:
+    on random items with scales spread over many binades (zeros and values far below the smallest code included),
+    and on the items that attain it -- every residual plane the sign pattern of qhat.  And it is not slack by
+    more than the copies' precision on those."""
+    rng = np.random.default_rng(123)
+    d, P, Pq, N = 64, 3, 3, 4000
+    planes = rng.integers(0, 2**64, size=(P, N, 1), dtype=np.uint64)
+    scales = (rng.uniform(0.0, 1.0, size=(P, N)) * 10.0 ** rng.uniform(-12, 0, size=(P, N))).astype(np.float32)
+    scales[:, :50] = 0.0
+    scales[0, 50:100] = np.float32(0.93)
+    qp = rng.integers(0, 2**64, size=(Pq, 1), dtype=np.uint64)
+    qs = rng.uniform(0.05, 1.0, size=Pq).astype(np.float32)
+    M, _ = rbe.rbe_debug_query_mass(qp, qs, d)
+    qbits = ((qp[:, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64).reshape(Pq, d)
+    qhat = (qs.astype(np.float64)[:, None] * (2 * qbits - 1)).sum(axis=0)
+    best = np.uint64(0)
+    for i in range(d):
+        if qhat[i] > 0:
+            best |= np.uint64(1) << np.uint64(i)
+    planes[1:, 100:600, 0] = best                      # residual planes that attain +M each
+    scales[:, 100:600] = rng.uniform(0.05, 1.0, size=(P, 500)).astype(np.float32)
+
+    def bound(planes, scales):
+        e = 0.015875
+        copies = [_scale_copy_codec(scales[j]) for j in range(P)]
+        bits0 = ((planes[0, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64).reshape(-1, d)
+        t0 = (2 * bits0 - 1) @ qhat
+        h = [c[0] for c in copies]
+        floor0 = 2.0 ** (copies[0][1] - 127)          # a scale of array 0 below its smallest copy is above it by less than this
+        return h[0] * t0 + (e * h[0] + floor0) * np.abs(t0) + (1 + e) * M * sum(h[1:]), h, [c[1] for c in copies]
+
+    true = oracle.scores(planes, scales, qp, qs)
+    b, h, bases = bound(planes, scales)
+    assert np.all(b >= true), float((true - b).max())
+    # the copies are what their description says: within 2^-6 of every scale that is at least the smallest code
+    for j in range(P):
+        a = scales[j].astype(np.float64)
+        big = a >= 2.0 ** (bases[j] - 127)
+        assert np.all(np.abs(h[j][big] - a[big]) <= 2.0 ** -6 * 1.016 * h[j][big])
+        assert np.all(h[j][~big] >= a[~big])
+    # attained up to the copies' precision where the residual planes are the best ones and the scales are not tiny
+    sel = np.arange(100, 600)
+    sel = sel[(scales[:, sel] > 1e-3).all(axis=0)]
+    assert sel.size > 20
+    assert np.all(b[sel] - true[sel] <= 0.035 * scales[:, sel].astype(np.float64).sum(axis=0) * M + 2.0 ** (bases[0] - 127) * M)
+
+
 @pytest.mark.parametrize("dim,Pq", [(64, 1), (64, 3), (128, 4)])
 def test_query_mass_dyadic_is_the_least_mismatch_count(lib, dim, Pq):
     """Dyadic index: h_min = min over planes K of sum_i 2^(Pq-1-i) popcount(Q_i XOR K).  The minimum
