@@ -485,13 +485,16 @@ def main():
         torch.cuda.synchronize()
         h_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         # progressive like the binary-query scan: bytes read = streamed planes and scales + the last plane of some rows
-        h_bytes = (last_items * ((P - 1) * 8 * W + (4 if P == 4 else P - 1)) + (last_items // 256) * 4 + float(np.mean(h_units)) * 8.0
+        h_two = h_stats["scan_kernel"][-1] == "scan_exact_fq_prog2_hint"      # plane 0 and the copies of all scales in the stream
+        h_bytes = (last_items * ((1 if h_two else P - 1) * 8 * W + (4 if P == 4 else P - 1) + (1 if h_two else 0))
+                   + (last_items // 256) * 4 + float(np.mean(h_units)) * 8.0
                    if P >= 2 else last_items * bytes_per_item)
         h_gbs = h_bytes / (float(np.mean(h_scan)) * 1e-3) / 1e9
         out["hybrid_float_query"] = {"ms_per_step": h_ms, "value": N / (h_ms * 1e-3), "unit": "candidates/s",
                                      "scan_kernel_ms": float(np.mean(h_scan)), "hbm_gbs": h_gbs,
                                      "hbm_frac": h_gbs / HBM_PEAK_GBS, "bytes_per_launch": h_bytes,
-                                     "rows_with_items_read_in_full": float(np.mean(h_deep))}
+                                     "rows_with_items_read_in_full": float(np.mean(h_deep)),
+                                     "scan_kernel": h_stats["scan_kernel"][-1]}
         log(f"hybrid fp32 query: {h_ms:.3f} ms/step, scan kernel {np.mean(h_scan):.3f} ms -> {h_gbs:.0f} GB/s read")
         if args.batch >= 3:
             B = args.batch

@@ -57,7 +57,7 @@ class rbe_search_stats(ctypes.Structure):
 
 
 KERNEL_NAMES = {0: "none", 1: "scan_exact", 2: "scan_exact_prog", 3: "scan_exact_prog_hint", 4: "scan_batch_mfma",
-                5: "scan_groupmax", 6: "scan_exact_fq", 7: "scan_exact_fq_prog", 8: "scan_exact_prog2_hint"}
+                5: "scan_groupmax", 6: "scan_exact_fq", 7: "scan_exact_fq_prog", 8: "scan_exact_prog2_hint", 9: "scan_exact_fq_prog2_hint"}
 
 
 _lib = None

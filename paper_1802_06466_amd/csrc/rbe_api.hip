@@ -1339,6 +1339,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         e = hipSuccess;
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && can_prune(ix);
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
+        sel.two_stage = ix->progressive == 1 && ix->P >= 3 && ix->d_hints_last != nullptr && ix->fq_binary;
         const size_t per_q = (size_t)8 * ix->W * 256;
         for (uint32_t q = 0; q < c.Q && e == hipSuccess; ++q) {   // one pass over the range per query
             FqArgs fa;
@@ -1346,6 +1347,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
             fa.lut = ix->ws.lut + q * per_q; fa.tau_ptr = ix->ws.tau + q;
             fa.mass = rbe::QueryMass{ix->fq_mass[q][0], ix->fq_mass[q][1]}; fa.deep_rows = ix->ws.status + 1 + level_slot; fa.row_amax = ix->d_row_amax; fa.hints = ix->d_hints; fa.deep_units = ix->ws.status + 14;
             for (int j = 0; j < 3; ++j) fa.hint_base[j] = ix->hint_base[j];
+            fa.hints_last = ix->d_hints_last; fa.hint_base_last = ix->hint_base[3];
             fa.qwords = nullptr; fa.qcoef = nullptr; fa.bmass = rbe::QueryMass{0.0f, 0.0f}; fa.resid = 0.0f;
             if (ix->fq_binary) {
                 fa.qwords = ix->ws.qwords + (size_t)q * RBE_MAX_PLANES * 2 * ix->W;
@@ -1407,7 +1409,9 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
     if (e != hipSuccess) { set_error("scan launch failed: %s", hipGetErrorString(e)); return RBE_EHIP; }
     if (level_slot < RBE_MAX_LEVELS) {
         uint32_t which = RBE_KERNEL_SCAN_GROUPMAX;
-        if (c.float_query) which = sel.progressive ? RBE_KERNEL_SCAN_FLOAT_PROG : RBE_KERNEL_SCAN_FLOAT;
+        if (c.float_query)
+            which = !sel.progressive ? RBE_KERNEL_SCAN_FLOAT
+                                     : (sel.hints && sel.two_stage && ix->mode == rbe::kModeScaled ? RBE_KERNEL_SCAN_FLOAT_PROG2 : RBE_KERNEL_SCAN_FLOAT_PROG);
         else if (c.batch_mfma && !(dense && !c.float_batch && ix->batch_path == 0)) which = RBE_KERNEL_SCAN_BATCH_MFMA;
         else if (c.mode == RBE_SELECT_EXACT)
             which = !sel.progressive ? RBE_KERNEL_SCAN_EXACT

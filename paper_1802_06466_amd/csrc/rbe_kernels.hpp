@@ -544,6 +544,8 @@ struct FqArgs {
     const float* qcoef;       // [5]
     QueryMass bmass;          // mass of qhat (query_mass)
     float resid;              // >= sum_d |q_d - qhat_d|
+    const uint32_t* hints_last;  // as in ScanArgs (scan_exact_fq_prog2_hint)
+    int hint_base_last;
 };
 
 // Batched scan on the matrix cores (rbe_batch.hip).

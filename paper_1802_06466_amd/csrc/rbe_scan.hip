@@ -1232,26 +1232,19 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
 // binary-query scan, instead of from table sums (8W LDS reads per plane and item).  A plane's table sum q . b is
 // qhat . b + (q - qhat) . b, and the second term is at most R = sum_d |q_d - qhat_d| (a.resid): the bound gains
 // R per unit of the scale sum, about 6 % of the query's mass against the 25 % that the left-out plane costs anyway.
-template <int W, int P, bool BIN>
-__global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a)
+// The rows of a wave from tile p on, with what the wave has queued and counted so far (see prog_hint_rows): the whole
+// of scan_exact_fq_prog_hint, and what scan_exact_fq_prog2_hint falls back to.
+template <int W, int P, bool BIN, bool STREAM_EXTRA>
+__device__ __forceinline__ void fq_prog_hint_rows(const FqArgs& a, uint32_t p, uint32_t fill, uint32_t full_rows, uint32_t extra8,
+                                                  uint64_t* s_keys, const float (&s_lut)[8 * W][256], int wave, int lane)
 {
     constexpr int PQB = 4;
     constexpr int MODE = kModeScaled;
     constexpr int S = P, F = P - 1;
     constexpr int NW = S - 1 == 3 ? 4 : S - 1;
-    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
-    __shared__ float s_lut[8 * W][256];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    uint64_t* s_keys = s_keys_all[wave];
-    for (int i = threadIdx.x; i < 8 * W * 256; i += kBlock) (&s_lut[0][0])[i] = a.lut[i];
-    __syncthreads();
-
     const uint32_t G = gridDim.x;
     const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
     const size_t tile_bytes = geom.tile_bytes();
-    uint32_t p = a.p_begin + blockIdx.x;
-    if (p >= a.p_end) return;
     const uint64_t tau = a.tau_ptr[0];
     const float taus = threshold_score(tau);
     const QueryMass mass = a.mass;
@@ -1261,7 +1254,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
                                 : 2.0f * mass.y + 0.015875f * mass.x;
     QueryRegs<W, PQB> qb{};
     if constexpr (BIN) qb = load_query<W, PQB>(a.qwords, a.qcoef, 0);
-    uint32_t fill = 0, probed = 0, passed = 0, full_rows = 0, extra8 = 0;
+    uint32_t probed = 0, passed = 0;
 
     struct Hints { uint32_t w[NW]; };
     auto load_hints = [&](Hints& h, uint32_t tile_p) {
@@ -1371,6 +1364,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
             passed += reach ? 1u : 0u;
         }
         full_rows += reach ? 1u : 0u;
+        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
         if (reach) {
             {
                 // lane-wise, as in scan_exact_prog_hint
@@ -1432,10 +1426,256 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
             score_row(cur, (1u << kItemsPerLane) - 1u, p);
             ++full_rows;
             extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item beyond the stream's
+            if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
             if (!has_next) break;
             cur = nxt;
             p = pn;
         }
+    }
+    if (fill) stage_flush1(s_keys, fill, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+    if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
+}
+
+template <int W, int P, bool BIN>
+__global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a)
+{
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ float s_lut[8 * W][256];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < 8 * W * 256; i += kBlock) (&s_lut[0][0])[i] = a.lut[i];
+    __syncthreads();
+    const uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    fq_prog_hint_rows<W, P, BIN, false>(a, p, 0u, 0u, 0u, s_keys_all[wave], s_lut, wave, lane);
+}
+
+// scan_exact_prog2_hint for an fp32 query (hybrid scoring): the bounds of both stages are formed from the 4-plane
+// binary approximation qhat of the query by XOR/popcounts, as in scan_exact_fq_prog_hint<.., true> (the query's own
+// sums differ from qhat's by at most a.resid per plane); what passes both is scored from the byte tables.
+template <int W, int P>
+__global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs a)
+{
+    static_assert(P >= 3, "with two planes scan_exact_fq_prog_hint streams plane 0 alone already");
+    constexpr int MODE = kModeScaled;
+    constexpr int PQ = 4;                        // planes of the query's binary approximation
+    constexpr int S = P, F = P - 1;
+    constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
+    constexpr int kQueue = 128;                  // entries per wave: a batch of 64 leaves when 64 have gathered
+    __shared__ uint64_t s_keys_all[kWavesPerBlock][kStage];
+    __shared__ uint32_t s_qid[kWavesPerBlock][kQueue];    // physical tile * 1024 + item of the tile
+    __shared__ float s_qs0[kWavesPerBlock][kQueue];       // floor + h_0 t_0: where the bound's chain stands after plane 0
+    __shared__ uint32_t s_qhb[kWavesPerBlock][kQueue];    // the item's scale copies, array j in byte j
+    __shared__ float s_qam[kWavesPerBlock][kQueue];       // the copy of the item's last scale
+    __shared__ float s_lut[8 * W][256];
+    for (int i = threadIdx.x; i < 8 * W * 256; i += kBlock) (&s_lut[0][0])[i] = a.lut[i];
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    uint64_t* s_keys = s_keys_all[wave];
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    uint32_t fill = 0, full_rows = 0, extra8 = 0;
+    uint32_t qfill = 0;                       // entries waiting for stage B (wave-uniform)
+    uint32_t last_row = 0xFFFFFFFFu;          // row of the last item that reached stage C (wave-uniform)
+    uint32_t probed = 0, passed = 0;          // items judged by stage A, items it let through (wave-uniform)
+    const QueryRegs<W, PQ> q0 = load_query<W, PQ>(a.qwords, a.qcoef, 0);     // qhat, the binary approximation
+    const QueryMass mass = a.mass;                                            // of the query itself
+    // per unit of a scale copy whose plane's sum was formed from qhat (as in scan_exact_fq_prog_hint<.., true>) ...
+    const float slack_all = 2.0f * (mass.y + a.bmass.y) + 0.015875f * a.bmass.x + 1.04f * a.resid;
+    // ... and of one whose plane has not been looked at: its table sum is at most the query's own mass
+    const float slack_mass = 2.0f * mass.y + 0.015875f * mass.x;
+    const uint64_t tau0 = a.tau_ptr[0];
+    const float taus0 = threshold_score(tau0);
+    const uint32_t hb[3] = {(uint32_t)a.hint_base[0] << 5, (uint32_t)a.hint_base[1] << 5, (uint32_t)a.hint_base[2] << 5};
+    auto decode = [&](uint32_t byte, int j) { return __uint_as_float((byte + hb[j]) << 18); };
+    // a scale below the smallest copy of its array, 2^(base - 127), is off by up to that much instead (all P arrays here)
+    float floor_c = __uint_as_float((uint32_t)a.hint_base_last << 23);
+    for (int j = 0; j < F; ++j) floor_c += __uint_as_float((uint32_t)a.hint_base[j] << 23);
+    floor_c *= 1.0001f * (a.bmass.x + a.resid + mass.x);
+    const float mass_last = mass.x + 2.0f * mass.y;
+    const float mass_hint = mass_last + slack_mass;     // what a plane whose scale is known by its copy can add, per unit of the copy
+    const float floor_0 = 1.0001f * __uint_as_float((uint32_t)a.hint_base[0] << 23);
+    const uint32_t hb_last = (uint32_t)a.hint_base_last << 5;
+
+    struct Hints { uint32_t w[NW]; uint32_t last; };
+    auto load_hints = [&](Hints& h, uint32_t tile_p) {
+        h.last = __builtin_nontemporal_load(a.hints_last + ((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane);
+        const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
+        if constexpr (NW == 2) {
+            const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+            h.w[0] = v.x; h.w[1] = v.y;
+        } else {
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+            h.w[0] = v.x; h.w[1] = v.y; h.w[2] = v.z; h.w[3] = v.w;
+        }
+    };
+
+    // Stage B (and C) for the entries [base, base + n) of the wave's queue, one per lane.  All lanes of the wave.
+    auto follow_up = [&](uint32_t base, uint32_t n) __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const bool act = (uint32_t)lane < n;
+        const uint32_t e = base + (act ? (uint32_t)lane : 0u);
+        const uint32_t id = s_qid[wave][e], hbytes = s_qhb[wave][e];
+        const float h_last = s_qam[wave][e];
+        float s = s_qs0[wave][e];
+        const uint32_t tp = id >> 10, idx = id & 1023u;
+        const char* tile = a.tiles + (size_t)tp * tile_bytes;
+        RowRegs<W, P, S> it;          // this lane's item, in slot 0
+        bool pass2 = false;
+        if (act) {
+            float all = decode(hbytes & 255u, 0);
+#pragma unroll
+            for (int j = 1; j < F; ++j) {
+                const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
+                if constexpr (W == 1) {
+                    const u32x2 v = *reinterpret_cast<const u32x2*>(kw);
+                    it.w[j][0][0] = v.x; it.w[j][0][1] = v.y;
+                } else {
+#pragma unroll
+                    for (int h = 0; h < W / 2; ++h) {
+                        const u32x4 v = reinterpret_cast<const u32x4*>(kw)[h];
+                        it.w[j][0][4 * h + 0] = v.x; it.w[j][0][4 * h + 1] = v.y; it.w[j][0][4 * h + 2] = v.z; it.w[j][0][4 * h + 3] = v.w;
+                    }
+                }
+                float t = q0.bias;
+#pragma unroll
+                for (int i = 0; i < PQ; ++i) {
+                    uint32_t pc = 0;
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(it.w[j][0][h] ^ q0.w[i][h]);
+                    t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                }
+                const float hj = decode((hbytes >> (8 * j)) & 255u, j);
+                s = __fmaf_rn(hj, t, s);
+                all += hj;
+            }
+            // the bound of scan_exact_prog_hint, with the item's own last scale (by its copy) for the row's largest
+            const float ub = __fmaf_rn(all, slack_all, __fmaf_rn(h_last, mass_hint, s));
+            pass2 = !(ub < taus0);
+        }
+        extra8 += n * (uint32_t)W * (uint32_t)(F - 1);
+        const uint64_t m2 = __ballot(pass2);
+        if (m2) {
+            float score = -__builtin_inff();
+            uint64_t logical = 0;
+            if (pass2) {
+                // the rest of the item: plane 0 again (another lane streamed it), the last plane, the fp32 scales
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = jj == 0 ? 0 : P - 1;
+                    const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) it.w[j][0][h] = kw[h];
+                }
+                const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset());
+#pragma unroll
+                for (int j = 0; j < S; ++j) it.a[j][0] = sc[j * kTileItems + idx];
+                score = score_item_fq<W, P, MODE>(it, 0, s_lut);
+                logical = (uint64_t)phys_to_tile_per_lane(a.layout, tp) * kTileItems + idx;
+            }
+            bool ok = pass2 && (score >= taus0) && (logical < a.n_items);
+            uint64_t key = 0;
+            if (ok) { key = make_key(score, (uint32_t)logical); ok = key >= tau0; }
+            fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
+            const uint32_t n2 = (uint32_t)__builtin_popcountll(m2);
+            extra8 += n2 * (2u * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
+            // rows that hold such an item: entries leave the queue in the order of their rows, so an item opens a
+            // new row if the nearest lower lane with such an item (or, for the lowest, the last batch) holds another one
+            const uint64_t below = m2 & ((1ull << lane) - 1ull);
+            const int prev = below ? 63 - __builtin_clzll(below) : lane;
+            const uint32_t row = id >> 8, row_prev = __shfl(row, prev);
+            full_rows += (uint32_t)__builtin_popcountll(__ballot(pass2 && row != (below ? row_prev : last_row)));
+            last_row = __shfl(row, 63 - __builtin_clzll(m2));
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    RowRegs<W, P, S> cur, nxt;
+    Hints hc, hn;
+    load_row_planes<W, P, S, 0, 1>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_hints(hc, p);
+    bool give_up = false;
+    for (;;) {
+        if (passed * 10 > probed + 4096) { give_up = true; break; }         // wave-uniform; row p is not done yet
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        const uint32_t pl = has_next ? pn : p;          // (unconditional prefetch: see scan_exact_prog_hint)
+        load_row_planes<W, P, S, 0, 1>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_hints(hn, pl);
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            float t = q0.bias;
+#pragma unroll
+            for (int i = 0; i < PQ; ++i) {
+                uint32_t pc = 0;
+#pragma unroll
+                for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[0][m][h] ^ q0.w[i][h]);
+                t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+            }
+            uint32_t hbytes = 0;
+            float rest = 0.0f;
+#pragma unroll
+            for (int j = 0; j < F; ++j) {
+                const uint32_t c = (hc.w[j] >> (8 * m)) & 255u;
+                hbytes |= c << (8 * j);
+                if (j >= 1) rest += decode(c, j);
+            }
+            const float h0 = decode(hbytes & 255u, 0);
+            const float h_last = __uint_as_float((((hc.last >> (8 * m)) & 255u) + hb_last) << 18);
+            const float s0 = __fmaf_rn(h0, t, floor_c);         // (where stage B takes the chain up)
+            // a_0 t_0 <= h_0 t_0 + (0.015875 h_0 + floor_0) |t_0|: the copy is within 2^-6 of the scale, or, for a
+            // scale below the smallest copy, above it by less than that copy (floor_0); t_0 is known here, so its
+            // own size stands where scan_exact_prog_hint has the query's mass.  Every other plane adds at most
+            // (its copy) x (mass + slack): |t_j| <= mass_last, and a copy that is not within 2^-6 of its scale is
+            // above it.  The roundings of this line and of the chains it stands for are inside 2 mass.y per unit
+            // of the scale sum, as there.
+            const float at = __builtin_fabsf(t);
+            // (fp32 query: t is qhat's sum; the query's own differs from it by at most a.resid)
+            const float ub = __fmaf_rn(rest + h_last, mass_hint,
+                                       __fmaf_rn(at, __fmaf_rn(0.015875f, h0, floor_0),
+                                                 __fmaf_rn(h0, t, (2.0f * (mass.y + a.bmass.y) + 1.04f * a.resid) * h0)));
+            const bool pass = !(ub < taus0);            // (a NaN bound does not prune)
+            const uint64_t mk = __ballot(pass);
+            if (mk) {
+                if (pass) {
+                    const uint32_t at = qfill + (uint32_t)__builtin_popcountll(mk & ((1ull << lane) - 1ull));
+                    s_qid[wave][at] = p * (uint32_t)kTileItems + (uint32_t)wave * kRow + lane_item<W>(lane, m);
+                    s_qs0[wave][at] = s0;
+                    s_qhb[wave][at] = hbytes;
+                    s_qam[wave][at] = h_last;
+                }
+                const uint32_t n = (uint32_t)__builtin_popcountll(mk);
+                qfill += n;
+                passed += n;
+                if (qfill >= 64) {
+                    // the 64 oldest entries leave; the rest (fewer than 64) move to the front
+                    follow_up(0, 64);
+                    qfill -= 64;
+                    const bool mv = (uint32_t)lane < qfill;
+                    const uint32_t from = 64u + (mv ? (uint32_t)lane : 0u);
+                    const uint32_t e_id = s_qid[wave][from], e_hb = s_qhb[wave][from];
+                    const float e_s0 = s_qs0[wave][from], e_am = s_qam[wave][from];
+                    __builtin_amdgcn_wave_barrier();
+                    if (mv) { s_qid[wave][lane] = e_id; s_qhb[wave][lane] = e_hb; s_qs0[wave][lane] = e_s0; s_qam[wave][lane] = e_am; }
+                }
+            }
+        }
+        probed += kRow;
+        if (!has_next) { p = pn; break; }
+        cur = nxt; hc = hn;
+        p = pn;
+    }
+    if (qfill) follow_up(0, qfill);
+    if (give_up) {
+        fq_prog_hint_rows<W, P, true, true>(a, p, fill, full_rows, extra8, s_keys, s_lut, wave, lane);
+        return;
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
@@ -1591,11 +1831,14 @@ using FqFn = void (*)(const FqArgs);
 using DenseFqFn = void (*)(const char*, const Layout, const float*, uint64_t, uint64_t, float*);
 
 template <int W, int P>
-FqFn fq_prog_fn_m(int mode, bool hints, bool binary_bound)
+FqFn fq_prog_fn_m(int mode, bool hints, bool binary_bound, bool two_stage)
 {
     if constexpr (P >= 2) {
         if (mode == kModeScaled) {
             if (!hints) return scan_exact_fq_prog<W, P, kModeScaled>;
+            if constexpr (P >= 3) {
+                if (binary_bound && two_stage) return scan_exact_fq_prog2_hint<W, P>;
+            }
             return binary_bound ? scan_exact_fq_prog_hint<W, P, true> : scan_exact_fq_prog_hint<W, P, false>;
         }
         if constexpr (dyadic_supported(W)) {
@@ -1636,9 +1879,9 @@ hipError_t launch_scan_exact_fq_w<RBE_W>(const KernelSel& k, const FqArgs& a, ui
     FqFn fn = nullptr;
     switch (k.P) {
         case 1: fn = fq_fn_m<RBE_W, 1>(k.mode); break;
-        case 2: fn = k.progressive ? fq_prog_fn_m<RBE_W, 2>(k.mode, k.hints, a.qwords != nullptr) : fq_fn_m<RBE_W, 2>(k.mode); break;
-        case 3: fn = k.progressive ? fq_prog_fn_m<RBE_W, 3>(k.mode, k.hints, a.qwords != nullptr) : fq_fn_m<RBE_W, 3>(k.mode); break;
-        case 4: fn = k.progressive ? fq_prog_fn_m<RBE_W, 4>(k.mode, k.hints, a.qwords != nullptr) : fq_fn_m<RBE_W, 4>(k.mode); break;
+        case 2: fn = k.progressive ? fq_prog_fn_m<RBE_W, 2>(k.mode, k.hints, a.qwords != nullptr, k.two_stage && a.hints_last != nullptr) : fq_fn_m<RBE_W, 2>(k.mode); break;
+        case 3: fn = k.progressive ? fq_prog_fn_m<RBE_W, 3>(k.mode, k.hints, a.qwords != nullptr, k.two_stage && a.hints_last != nullptr) : fq_fn_m<RBE_W, 3>(k.mode); break;
+        case 4: fn = k.progressive ? fq_prog_fn_m<RBE_W, 4>(k.mode, k.hints, a.qwords != nullptr, k.two_stage && a.hints_last != nullptr) : fq_fn_m<RBE_W, 4>(k.mode); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;

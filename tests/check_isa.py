@@ -29,7 +29,8 @@ if ROOT not in sys.path:
 from paper_1802_06466_amd import _build  # noqa: E402
 
 # kernel name prefixes whose lane-peeling loops are intended, with the number allowed per kernel
-EXPECTED = {"dense_scores": 1, "dense_scores_fq": 1, "scan_exact_fq": 1, "scan_exact_fq_prog": 1, "scan_exact_fq_prog_hint": 1}
+EXPECTED = {"dense_scores": 1, "dense_scores_fq": 1, "scan_exact_fq": 1, "scan_exact_fq_prog": 1, "scan_exact_fq_prog_hint": 1,
+            "scan_exact_fq_prog2_hint": 1}
 
 
 def kernel_family(mangled: str) -> str:

@@ -1132,16 +1132,17 @@ def test_progressive_scan_with_fp32_queries(d, P, flags):
     rbe.rbe_debug_set_batch_path(ix, 1)         # the table path for every batch size
     rbe.rbe_debug_set_plan_split(ix, 1)         # no automatic choices
     res = {}
-    for prog in (1, 2, 0):           # on; on without the one-byte scale copies; off
+    for prog in (1, 2, 3, 0):        # on; on without the one-byte scale copies; on without the first stage on plane 0; off
         rbe.rbe_debug_set_progressive(ix, prog)
         res[prog] = [rbe.rbe_search_float(ix, q[i:i + 1], k) for i in range(Q)] + [rbe.rbe_search_float(ix, q, k)]
         st = rbe.rbe_get_search_stats(ix)
         assert (st["deep_rows"] > 0) == (prog != 0)
     rbe.rbe_debug_set_progressive(ix, 1)
     res[True], res[False] = res[1], res[0]
-    for (i1, s1), (i2, s2), (i0, s0) in zip(res[1], res[2], res[0]):
+    for (i1, s1), (i2, s2), (i3, s3), (i0, s0) in zip(res[1], res[2], res[3], res[0]):
         np.testing.assert_array_equal(i1, i0); np.testing.assert_array_equal(s1, s0)
         np.testing.assert_array_equal(i2, i0); np.testing.assert_array_equal(s2, s0)
+        np.testing.assert_array_equal(i3, i0); np.testing.assert_array_equal(s3, s0)
     for i in range(Q):
         check_topk_float(planes, scales, q[i], k, res[True][i][0][0], res[True][i][1][0])
         np.testing.assert_array_equal(res[True][Q][0][i], res[True][i][0][0])
