@@ -400,6 +400,27 @@ def main():
         log(f"Q=1, every plane read: {ra['wall_s'] * 1e3 / steps_a:.3f} ms/step, scan kernel {a_scan:.3f} ms -> {a_gbs:.0f} GB/s, "
             f"same ids: {same}")
 
+    # ---------------- the same searches on the one-stage progressive scan (planes 0 .. P-2 and their scale copies in
+    # the stream): more bytes, moved at a higher rate, in more time
+    if two_stage and want("all_planes"):
+        rbe.rbe_debug_set_progressive(ix, 3)
+        steps_o = max(2, args.steps // 2)
+        ro = timed_searches(rbe, torch, ix, qp1, qs1, 1, k, steps_o, args.warmup)
+        rbe.rbe_debug_set_progressive(ix, True)
+        o_scan = float(ro["scan_ms"].mean())
+        o_bytes = (last_items * ((P - 1) * 8 * W + (4 if P == 4 else P - 1)) + (last_items // 256) * 4
+                   + float(ro["deep_units"].mean()) * 8.0)
+        out["roofline"]["one_stage_scan"] = {
+            "kernel": ro["stats"]["scan_kernel"][-1] + " (finest level; planes 0 .. P-2 streamed)", "kernel_ms": o_scan,
+            "bytes_per_launch": o_bytes, "achieved": o_bytes / (o_scan * 1e-3) / 1e9, "frac": o_bytes / (o_scan * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "ms_per_step": ro["wall_s"] * 1e3 / steps_o,
+            "same_ids": bool(all(np.array_equal(x, y) for x, y in zip(ro["ids"], r1["ids"]))),
+            "note": "the two-stage scan asks for fewer bytes and needs less time, but its lane-wise reads bring whole lines, so "
+                    "its fraction on the bytes asked for is the lower one",
+        }
+        log(f"Q=1, one-stage progressive scan: {ro['wall_s'] * 1e3 / steps_o:.3f} ms/step, scan kernel {o_scan:.3f} ms -> "
+            f"{o_bytes / (o_scan * 1e-3) / 1e9:.0f} GB/s")
+
     # ---------------- near-lossless selector (Algorithm 1, queue length 1, I = 256) on the same queries
     if not args.no_nearlossless and want("near"):
         I = 256

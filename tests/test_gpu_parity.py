@@ -1060,7 +1060,7 @@ def _search_both_ways(ix, qp, qs, k):
 
 
 @pytest.mark.parametrize("d,P,Pq,flags", [(64, 3, 3, 0), (64, 2, 3, 0), (128, 4, 4, 0), (256, 2, 2, 0), (64, 2, 3, "dyadic"),
-                                          (128, 3, 2, "dyadic_cosine"), (64, 4, 1, "dyadic")])
+                                          (128, 3, 2, "dyadic_cosine"), (64, 4, 1, "dyadic"), (256, 3, 2, 0), (128, 3, 1, 0), (64, 4, 2, 0)])
 def test_progressive_scan_changes_nothing_but_the_bytes_read(d, P, Pq, flags):
     """One query, several levels: the last level reads the last plane only of rows that the other planes and the
     scales cannot rule out.  Ids and scores are those of the plain scan bit for bit (and pass the oracle); on a
@@ -1111,7 +1111,7 @@ def test_progressive_scan_on_corpora_where_the_bound_cannot_help():
     rbe.rbe_free(ix)
 
 
-@pytest.mark.parametrize("d,P,flags", [(64, 3, 0), (128, 4, 0), (64, 2, "dyadic"), (128, 3, "dyadic_cosine")])
+@pytest.mark.parametrize("d,P,flags", [(64, 3, 0), (128, 4, 0), (64, 2, "dyadic"), (128, 3, "dyadic_cosine"), (64, 4, 0), (128, 3, 0)])
 def test_progressive_scan_with_fp32_queries(d, P, flags):
     """Hybrid scoring, one table pass per query: the last level is progressive too, with the table sums in place of
     the popcounts; same ids and scores as with every plane read, and the oracle's hybrid score."""
