@@ -235,10 +235,10 @@ def main():
     ap.add_argument("--no-config3", action="store_true", help="skip the 1e8 d=128 4-plane leg (64 queries)")
     ap.add_argument("--config-steps", type=int, default=6, help="timed calls of the config-3 and config-5 legs")
     ap.add_argument("--only", default="", help="comma list of legs to run instead of all: headline, all_planes, near, "
-                    "hybrid, batch, batch_popcount, cpu, paper, config5, config3 (headline alone = the contract's steps)")
+                    "mixed, hybrid, small_batch, batch, batch_popcount, cpu, paper, config5, config3 (headline alone = the contract's steps)")
     args = ap.parse_args()
     only = {x for x in args.only.split(",") if x}
-    known = {"headline", "all_planes", "near", "mixed", "hybrid", "batch", "batch_popcount", "cpu", "paper", "config5", "config3"}
+    known = {"headline", "all_planes", "near", "mixed", "hybrid", "small_batch", "batch", "batch_popcount", "cpu", "paper", "config5", "config3"}
     if only - known:
         print(f"bench.py: unknown legs {sorted(only - known)}", file=sys.stderr)
         sys.exit(2)
@@ -532,6 +532,23 @@ def main():
             log(f"hybrid fp32 queries, Q={B}: {hb_ms:.3f} ms/step")
 
     # ---------------- batch leg
+    # ---------------- a few queries per call (below the batch size from which the matrix cores take over): the
+    # XOR/popcount scans with a loop over the queries, two-stage from three planes on
+    if want("small_batch"):
+        sb = {}
+        for B in (2, 4):
+            steps_s, warm_s = 12, 6
+            qps, qss = make_queries(rbe, rbe_synth, torch, centres, (warm_s + steps_s) * B, args.sigma, P, 5)
+            rs = timed_searches(rbe, torch, ix, qps, qss, B, k, steps_s, warm_s)
+            s_ms = rs["wall_s"] * 1e3 / steps_s
+            s_scan = float(rs["scan_ms"].mean()) if rs["scan_ms"].size else float("nan")
+            sb[f"Q{B}"] = {"queries_per_step": B, "steps": steps_s, "ms_per_step": s_ms,
+                           "p50_ms": float(np.percentile(rs["per_step_ms"], 50)),
+                           "value": N * B / (s_ms * 1e-3), "unit": "candidates/s",
+                           "last_level_ms": s_scan, "last_level_kernel": rs["stats"]["scan_kernel"][-1]}
+            log(f"Q={B}: {s_ms:.3f} ms/step, last level {s_scan:.3f} ms on {rs['stats']['scan_kernel'][-1]}")
+        out["small_batch"] = sb
+
     if args.batch > 0 and want("batch"):
         B = args.batch
         bw = 8

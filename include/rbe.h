@@ -335,7 +335,7 @@ enum {                        /* rbe_search_stats.scan_kernel                   
     RBE_KERNEL_SCAN_GROUPMAX = 5,     /* near-lossless group maxima (Algorithm 1)   */
     RBE_KERNEL_SCAN_FLOAT = 6,        /* fp32 query through byte tables, every plane */
     RBE_KERNEL_SCAN_FLOAT_PROG = 7,   /* ... last plane only where the bound passes */
-    RBE_KERNEL_SCAN_PROG2_HINT = 8,   /* as PROG_HINT with plane 0 alone in the stream */
+    RBE_KERNEL_SCAN_PROG2_HINT = 8,   /* as PROG_HINT with plane 0 alone in the stream (1-4 queries) */
     RBE_KERNEL_SCAN_FLOAT_PROG2 = 9   /* the same for an fp32 query                    */
 };
 

@@ -1387,7 +1387,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         // (several queries: the scan that streams the scale copies is ahead up to four queries per call, 4.3 against
         // 5.2 ms for two, level with the one that streams the fp32 scales at five, behind from six on)
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2 && c.Q <= 4;
-        sel.two_stage = ix->progressive == 1 && c.Q == 1 && ix->P >= 3 && ix->d_hints_last != nullptr;
+        sel.two_stage = ix->progressive == 1 && c.Q <= 4 && ix->P >= 3 && ix->d_hints_last != nullptr;
         sa.deep_rows = ix->ws.status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints; sa.deep_units = ix->ws.status + 14;
         sa.deep_pairs = level_slot >= c.look_from ? ix->ws.status + 9 : nullptr;
         for (int j = 0; j < 3; ++j) sa.hint_base[j] = ix->hint_base[j];
@@ -1415,7 +1415,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         else if (c.batch_mfma && !(dense && !c.float_batch && ix->batch_path == 0)) which = RBE_KERNEL_SCAN_BATCH_MFMA;
         else if (c.mode == RBE_SELECT_EXACT)
             which = !sel.progressive ? RBE_KERNEL_SCAN_EXACT
-                                     : (sel.hints ? (sel.two_stage && c.Q == 1 && ix->mode == rbe::kModeScaled ? RBE_KERNEL_SCAN_PROG2_HINT : RBE_KERNEL_SCAN_PROG_HINT)
+                                     : (sel.hints ? (sel.two_stage && ix->mode == rbe::kModeScaled ? RBE_KERNEL_SCAN_PROG2_HINT : RBE_KERNEL_SCAN_PROG_HINT)
                                                   : RBE_KERNEL_SCAN_PROG);
         ix->stats.scan_kernel[level_slot] = which;
     }

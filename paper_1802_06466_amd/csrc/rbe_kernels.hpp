@@ -81,6 +81,56 @@ __device__ __forceinline__ QueryRegs<W, PQ> load_query(const uint32_t* __restric
     return r;
 }
 
+// A query's registers and its two masses, kept in LDS by the scans that take a few queries per row.  A load from
+// global memory inside a loop that also stores cannot go through the scalar cache, so it becomes a vector load, and
+// waiting for it waits for every vector load asked for before it -- the next row's prefetch included.  LDS reads are
+// counted apart from those.
+template <int W, int PQ>
+struct alignas(16) QuerySlot {
+    uint32_t w[PQ][2 * W];
+    float m2c[PQ];
+    float bias;
+    float mass_x, mass_y;
+};
+
+// Fills slots[0 .. nq) from the query arrays (thread q fills slot q; nq <= blockDim.x) and synchronises the workgroup.
+// All threads of the workgroup.
+template <int W, int PQ>
+__device__ __forceinline__ void stage_queries(QuerySlot<W, PQ>* slots, const uint32_t* __restrict__ qwords,
+                                              const float* __restrict__ qcoef, const float* __restrict__ masses,
+                                              uint32_t nq)
+{
+    const uint32_t q = threadIdx.x;
+    if (q < nq) {
+        const QueryRegs<W, PQ> r = load_query<W, PQ>(qwords, qcoef, q);
+        QuerySlot<W, PQ>& d = slots[q];
+#pragma unroll
+        for (int i = 0; i < PQ; ++i) {
+#pragma unroll
+            for (int h = 0; h < 2 * W; ++h) d.w[i][h] = r.w[i][h];
+            d.m2c[i] = r.m2c[i];
+        }
+        d.bias = r.bias;
+        d.mass_x = masses[2 * q];
+        d.mass_y = masses[2 * q + 1];
+    }
+    __syncthreads();
+}
+
+template <int W, int PQ>
+__device__ __forceinline__ QueryRegs<W, PQ> slot_query(const QuerySlot<W, PQ>& s)
+{
+    QueryRegs<W, PQ> r;
+#pragma unroll
+    for (int i = 0; i < PQ; ++i) {
+#pragma unroll
+        for (int h = 0; h < 2 * W; ++h) r.w[i][h] = s.w[i][h];
+        r.m2c[i] = s.m2c[i];
+    }
+    r.bias = s.bias;
+    return r;
+}
+
 // ---------------------------------------------------------------- one lane's share of a row
 template <int W, int P, int S>
 struct RowRegs {

@@ -827,35 +827,22 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
 // then scores those items from scratch.  Appends what the batch form of scan_exact appends.  Against
 // scan_exact_batch_prog, which streams the fp32 scales (28 instead of 18 bytes per item at d = 64, P = 3), the gain
 // is in the small batches that are still bound by memory.
-template <int W, int P, int PQ>
-__global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanArgs a)
+// The rows of a wave from tile p on, with what the wave has counted so far (see prog_hint_rows): the whole of
+// scan_exact_batch_prog_hint, and what scan_exact_batch_prog2_hint falls back to.
+template <int W, int P, int PQ, bool STREAM_EXTRA>
+__device__ __forceinline__ void batch_prog_hint_rows(const ScanArgs& a, uint32_t p, uint32_t full_rows, uint32_t full_pairs, uint32_t extra8,
+                                                     uint64_t* s_keys, const MultiStage& ms, const QuerySlot<W, PQ>* slots,
+                                                     int wave, int lane)
 {
     constexpr int MODE = kModeScaled;
     constexpr int S = P, F = P - 1;
     constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
-    extern __shared__ __align__(16) unsigned char s_dynamic[];
-    __shared__ uint32_t s_cnt_all[kWavesPerBlock][65];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    uint64_t* s_keys = reinterpret_cast<uint64_t*>(s_dynamic) + (size_t)wave * a.stage_entries;
-    const uint32_t n_sub = sub_queues_for(a.n_queries);
-    const uint32_t per_sub = a.stage_entries / n_sub;
-    const MultiStage ms{s_keys, s_cnt_all[wave], per_sub > 64u ? 64u : per_sub, 0u, n_sub};
-    s_cnt_all[wave][lane] = 0;
-    if (lane == 0) s_cnt_all[wave][64] = 0;
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    const uint32_t nq = a.n_queries;
+    const uint32_t nq = __builtin_amdgcn_readfirstlane(a.n_queries);     // (kept in a scalar register: the loops over the queries are the wave's, not the lanes')
     const uint32_t G = gridDim.x;
     const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
     const size_t tile_bytes = geom.tile_bytes();
-
-    uint32_t p = a.p_begin + blockIdx.x;
-    if (p >= a.p_end) return;
-    uint32_t rows = 0, full_rows = 0, full_pairs = 0;
+    uint32_t rows = 0;
     uint32_t probed = 0, passed = 0;   // (query, row) pairs whose bound was evaluated, and those of them it let through
-    uint32_t extra8 = 0;        // bytes / 8 asked for beyond the stream (wave total, kept in lane 0's terms)
-    const float* masses = a.qcoef + (size_t)nq * (PQ + 1);
 
     struct Hints { uint32_t w[NW]; };
     auto load_hints = [&](Hints& h, uint32_t tile_p) {
@@ -886,36 +873,37 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanA
     load_row_planes<W, P, S, 0, F>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
     load_hints(hc, p);
     float amax = a.row_amax[(size_t)p * kWavesPerBlock + wave], amax_n = 0.0f;
+    // The thresholds a row is judged by are asked for while the row BEFORE it is judged, along with that row's
+    // prefetch (the host sends at most four queries to this scan): loads return in order, so waiting for a threshold
+    // asked for after the prefetch would wait for all of it, and nothing would be in flight while the row is judged.
+    uint64_t tau_a[4], tau_b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) tau_a[q] = a.tau[(uint32_t)q < nq ? q : 0];
     bool whole = false;    // wave-uniform: whole-row fallback, the bound is not evaluated for this row
     // One row: start the loads of the next one into the other register set, judge and score this one.  The two
     // register sets swap roles from row to row (two copies of the code) instead of being copied.
-    auto step = [&](RowRegs<W, P, S>& cur, Hints& hc, float& amax, RowRegs<W, P, S>& nxt, Hints& hn, float& amax_n)
-                    __attribute__((always_inline)) -> bool {
+    auto step = [&](RowRegs<W, P, S>& cur, Hints& hc, float& amax, const uint64_t (&tau_c)[4],
+                    RowRegs<W, P, S>& nxt, Hints& hn, float& amax_n, uint64_t (&tau_n)[4]) __attribute__((always_inline)) -> bool {
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
         const bool whole_next = passed * 4 > probed + 32 * nq;     // wave-uniform
         const uint32_t pl = has_next ? pn : p;      // prefetch not under a branch: see scan_exact_prog_hint
+        auto tau_of = [&](uint32_t q) { return q == 0 ? tau_c[0] : (q == 1 ? tau_c[1] : (q == 2 ? tau_c[2] : tau_c[3])); };
         load_row_planes<W, P, S, 0, F>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
         load_hints(hn, pl);
         amax_n = a.row_amax[(size_t)pl * kWavesPerBlock + wave];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) tau_n[q] = a.tau[(uint32_t)q < nq ? q : 0];
         bool reach = true;
         uint32_t mine = (1u << kItemsPerLane) - 1u;     // which of this lane's items can still reach some query's threshold
         uint32_t row_pairs = nq;                         // queries for which some item of the row can
         if (!whole || (rows & 7u) == 0u) {
             mine = 0;
             row_pairs = 0;
-            QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
-            uint64_t tau_n = a.tau[0];
-            QueryMass mass_n{masses[0], masses[1]};
             for (uint32_t q = 0; q < nq; ++q) {
-                const QueryRegs<W, PQ> q0 = qn;
-                const float taus0 = threshold_score(tau_n);
-                const QueryMass mass = mass_n;
-                if (q + 1 < nq) {
-                    qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
-                    tau_n = a.tau[q + 1];
-                    mass_n = QueryMass{masses[2 * (q + 1)], masses[2 * (q + 1) + 1]};
-                }
+                const QueryRegs<W, PQ> q0 = slot_query(slots[q]);
+                const float taus0 = threshold_score(tau_of(q));
+                const QueryMass mass{slots[q].mass_x, slots[q].mass_y};
                 const float slack_all = 2.0f * mass.y + 0.015875f * mass.x;
                 const float floor_c = floor_h * mass.x;
                 const float mass_last = mass.x + 2.0f * mass.y;
@@ -950,6 +938,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanA
         }
         ++rows;
         full_rows += reach ? 1u : 0u;
+        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
         if (reach) {
             full_pairs += row_pairs;
             // only the lanes that hold such an item read the rest of their items' data (the memory system fetches
@@ -996,15 +985,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanA
             }
             // every query scores the items that some query's bound let through (an item whose own bound is below
             // the threshold scores below it too, and is not appended)
-            QueryRegs<W, PQ> qn = load_query<W, PQ>(a.qwords, a.qcoef, 0);
-            uint64_t tau_n = a.tau[0];
             for (uint32_t q = 0; q < nq; ++q) {
-                const QueryRegs<W, PQ> qr = qn;
-                const uint64_t tau = tau_n;
-                if (q + 1 < nq) {
-                    qn = load_query<W, PQ>(a.qwords, a.qcoef, q + 1);
-                    tau_n = a.tau[q + 1];
-                }
+                const QueryRegs<W, PQ> qr = slot_query(slots[q]);
+                const uint64_t tau = a.tau[q];
                 const float taus = threshold_score(tau);
                 float sv[kItemsPerLane];
                 bool any = false;
@@ -1022,8 +1005,332 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanA
         return has_next;
     };
     for (;;) {
-        if (!step(cur, hc, amax, nxt, hn, amax_n)) break;
-        if (!step(nxt, hn, amax_n, cur, hc, amax)) break;
+        if (!step(cur, hc, amax, tau_a, nxt, hn, amax_n, tau_b)) break;
+        if (!step(nxt, hn, amax_n, tau_b, cur, hc, amax, tau_a)) break;
+    }
+    mstage_drain(ms, a.out, lane);
+    if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
+    if (a.deep_pairs && lane == 0 && full_pairs) atomicAdd(a.deep_pairs, full_pairs);
+    if (a.deep_units && lane == 0 && extra8) atomicAdd(a.deep_units, extra8);
+}
+
+
+template <int W, int P, int PQ>
+__global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanArgs a)
+{
+    extern __shared__ __align__(16) unsigned char s_dynamic[];
+    __shared__ uint32_t s_cnt_all[kWavesPerBlock][65];
+    __shared__ QuerySlot<W, PQ> s_query[4];           // (the host sends at most four queries to this scan)
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    if (a.n_queries > 4u) return;                     // (every thread alike)
+    stage_queries<W, PQ>(s_query, a.qwords, a.qcoef, a.qcoef + (size_t)a.n_queries * (PQ + 1), a.n_queries);
+    uint64_t* s_keys = reinterpret_cast<uint64_t*>(s_dynamic) + (size_t)wave * a.stage_entries;
+    const uint32_t n_sub = sub_queues_for(a.n_queries);
+    const uint32_t per_sub = a.stage_entries / n_sub;
+    const MultiStage ms{s_keys, s_cnt_all[wave], per_sub > 64u ? 64u : per_sub, 0u, n_sub};
+    s_cnt_all[wave][lane] = 0;
+    if (lane == 0) s_cnt_all[wave][64] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    batch_prog_hint_rows<W, P, PQ, false>(a, p, 0u, 0u, 0u, s_keys, ms, s_query, wave, lane);
+}
+
+
+// scan_exact_prog2_hint for 2 .. 4 queries per call: the stream is the same (plane 0, the one-byte copies of all P
+// scale arrays), stage A forms every query's bound from the one popcount pass per query over plane 0, and an item
+// that some query's bound lets through is queued once, with each query's partial score and the set of queries that
+// still want it.  Stage B reads the item's planes 1 .. P-2 once and continues the chains of those queries; stage C
+// reads the rest once and scores the item from scratch for each query whose second bound it passed.  What is
+// appended is what the batch form of scan_exact appends.  A wave of whose items more than one in 10 pass stage A
+// takes the rest of its rows as scan_exact_batch_prog_hint does.
+template <int W, int P, int PQ>
+__global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const ScanArgs a)
+{
+    static_assert(P >= 3, "with two planes scan_exact_batch_prog_hint streams plane 0 alone already");
+    constexpr int MODE = kModeScaled;
+    constexpr int S = P, F = P - 1;
+    constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
+    constexpr int kQueue = 128;                  // entries per wave: a batch of 64 leaves when 64 have gathered
+    constexpr int QB = 4;                        // most queries per call
+    extern __shared__ __align__(16) unsigned char s_dynamic[];
+    __shared__ uint32_t s_cnt_all[kWavesPerBlock][65];
+    __shared__ uint32_t s_qid[kWavesPerBlock][kQueue];      // physical tile * 1024 + item of the tile
+    __shared__ float s_qs0[kWavesPerBlock][QB][kQueue];     // per query: floor + h_0 t_0
+    __shared__ uint32_t s_qhb[kWavesPerBlock][kQueue];      // scale copies of arrays 0 .. P-2 in bytes 0 .. P-2, the queries that want the item in byte 3
+    __shared__ float s_qam[kWavesPerBlock][kQueue];         // the copy of the item's last scale
+    __shared__ QuerySlot<W, PQ> s_query[QB];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    if (a.n_queries > (uint32_t)QB) return;                 // (the host sends at most QB; every thread alike)
+    stage_queries<W, PQ>(s_query, a.qwords, a.qcoef, a.qcoef + (size_t)a.n_queries * (PQ + 1), a.n_queries);
+    uint64_t* s_keys = reinterpret_cast<uint64_t*>(s_dynamic) + (size_t)wave * a.stage_entries;
+    const uint32_t n_sub = sub_queues_for(a.n_queries);
+    const uint32_t per_sub = a.stage_entries / n_sub;
+    const MultiStage ms{s_keys, s_cnt_all[wave], per_sub > 64u ? 64u : per_sub, 0u, n_sub};
+    s_cnt_all[wave][lane] = 0;
+    if (lane == 0) s_cnt_all[wave][64] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t nq = __builtin_amdgcn_readfirstlane(a.n_queries);     // (kept in a scalar register: the loops over the queries are the wave's, not the lanes')
+    const uint32_t G = gridDim.x;
+    const TileGeom geom{(uint32_t)W, (uint32_t)P, (uint32_t)S};
+    const size_t tile_bytes = geom.tile_bytes();
+
+    uint32_t p = a.p_begin + blockIdx.x;
+    if (p >= a.p_end) return;
+    uint32_t full_rows = 0, full_pairs = 0, extra8 = 0;
+    uint32_t qfill = 0;                       // entries waiting for stage B (wave-uniform)
+    uint32_t last_row = 0xFFFFFFFFu;          // row of the last item that reached stage C (wave-uniform)
+    uint32_t probed = 0, passed = 0;          // items judged by stage A, items it let through for some query (wave-uniform)
+    const uint32_t hb[3] = {(uint32_t)a.hint_base[0] << 5, (uint32_t)a.hint_base[1] << 5, (uint32_t)a.hint_base[2] << 5};
+    auto decode = [&](uint32_t byte, int j) { return __uint_as_float((byte + hb[j]) << 18); };
+    // (the constants of scan_exact_prog2_hint, per unit of a query's mass where they depend on it)
+    float floor_all = __uint_as_float((uint32_t)a.hint_base_last << 23);
+    for (int j = 0; j < F; ++j) floor_all += __uint_as_float((uint32_t)a.hint_base[j] << 23);
+    floor_all *= 1.0001f;
+    const float floor_0 = 1.0001f * __uint_as_float((uint32_t)a.hint_base[0] << 23);
+    const uint32_t hb_last = (uint32_t)a.hint_base_last << 5;
+
+    struct Hints { uint32_t w[NW]; uint32_t last; };
+    auto load_hints = [&](Hints& h, uint32_t tile_p) {
+        h.last = __builtin_nontemporal_load(a.hints_last + ((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane);
+        const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
+        if constexpr (NW == 2) {
+            const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+            h.w[0] = v.x; h.w[1] = v.y;
+        } else {
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+            h.w[0] = v.x; h.w[1] = v.y; h.w[2] = v.z; h.w[3] = v.w;
+        }
+    };
+
+    // Stages B and C for the entries [base, base + n) of the wave's queue, one per lane.  All lanes of the wave.
+    auto follow_up = [&](uint32_t base, uint32_t n) __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const bool act = (uint32_t)lane < n;
+        const uint32_t e = base + (act ? (uint32_t)lane : 0u);
+        const uint32_t id = s_qid[wave][e], hbytes = s_qhb[wave][e];
+        const float h_last = s_qam[wave][e];
+        const uint32_t want = act ? hbytes >> 24 : 0u;        // queries whose first bound the item passed
+        const uint32_t tp = id >> 10, idx = id & 1023u;
+        const char* tile = a.tiles + (size_t)tp * tile_bytes;
+        RowRegs<W, P, S> it;          // this lane's item, in slot 0
+        float all = decode(hbytes & 255u, 0);
+        float hj[F];
+        if (act) {
+#pragma unroll
+            for (int j = 1; j < F; ++j) {
+                const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
+                if constexpr (W == 1) {
+                    const u32x2 v = *reinterpret_cast<const u32x2*>(kw);
+                    it.w[j][0][0] = v.x; it.w[j][0][1] = v.y;
+                } else {
+#pragma unroll
+                    for (int h = 0; h < W / 2; ++h) {
+                        const u32x4 v = reinterpret_cast<const u32x4*>(kw)[h];
+                        it.w[j][0][4 * h + 0] = v.x; it.w[j][0][4 * h + 1] = v.y; it.w[j][0][4 * h + 2] = v.z; it.w[j][0][4 * h + 3] = v.w;
+                    }
+                }
+                hj[j] = decode((hbytes >> (8 * j)) & 255u, j);
+                all += hj[j];
+            }
+        }
+        extra8 += n * (uint32_t)W * (uint32_t)(F - 1);
+        uint32_t want2 = 0;           // queries whose second bound it passed too
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            if ((uint32_t)q >= nq) break;                     // wave-uniform
+            const QueryRegs<W, PQ> q0 = slot_query(s_query[q]);
+            const QueryMass mass{s_query[q].mass_x, s_query[q].mass_y};
+            const float taus = threshold_score(a.tau[q]);
+            const float slack_all = 2.0f * mass.y + 0.015875f * mass.x;
+            const float mass_hint = mass.x + 2.0f * mass.y + slack_all;
+            if ((want >> q) & 1u) {
+                float s = s_qs0[wave][q][e];
+#pragma unroll
+                for (int j = 1; j < F; ++j) {
+                    float t = q0.bias;
+#pragma unroll
+                    for (int i = 0; i < PQ; ++i) {
+                        uint32_t pc = 0;
+#pragma unroll
+                        for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(it.w[j][0][h] ^ q0.w[i][h]);
+                        t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                    }
+                    s = __fmaf_rn(hj[j], t, s);
+                }
+                // (the second bound of scan_exact_prog2_hint)
+                const float ub = __fmaf_rn(all, slack_all, __fmaf_rn(h_last, mass_hint, s));
+                want2 |= !(ub < taus) ? (1u << q) : 0u;
+            }
+        }
+        const uint64_t m2 = __ballot(want2 != 0u);
+        if (m2) {
+            uint64_t logical = 0;
+            if (want2) {
+                // the rest of the item: plane 0 again (another lane streamed it), the last plane, the fp32 scales
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = jj == 0 ? 0 : P - 1;
+                    const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) it.w[j][0][h] = kw[h];
+                }
+                const float* sc = reinterpret_cast<const float*>(tile + geom.scales_offset());
+#pragma unroll
+                for (int j = 0; j < S; ++j) it.a[j][0] = sc[j * kTileItems + idx];
+                logical = (uint64_t)phys_to_tile_per_lane(a.layout, tp) * kTileItems + idx;
+            }
+#pragma unroll
+            for (int q = 0; q < QB; ++q) {
+                if ((uint32_t)q >= nq) break;                 // wave-uniform
+                const QueryRegs<W, PQ> qr = slot_query(s_query[q]);
+                const uint64_t tau = a.tau[q];
+                const float taus = threshold_score(tau);
+                const bool mine = ((want2 >> q) & 1u) != 0u;
+                float score = -__builtin_inff();
+                if (mine) score = score_item<W, P, PQ, MODE>(it, 0, qr);
+                bool ok = mine && (score >= taus) && (logical < a.n_items);
+                uint64_t key = 0;
+                if (ok) { key = make_key(score, (uint32_t)logical); ok = key >= tau; }
+                mstage_append(ok, key, (uint32_t)q, ms, a.out, lane);
+                full_pairs += (uint32_t)__builtin_popcountll(__ballot(mine));
+            }
+            const uint32_t n2 = (uint32_t)__builtin_popcountll(m2);
+            extra8 += n2 * (2u * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
+            // rows that hold such an item (see scan_exact_prog2_hint)
+            const uint64_t below = m2 & ((1ull << lane) - 1ull);
+            const int prev = below ? 63 - __builtin_clzll(below) : lane;
+            const uint32_t row = id >> 8, row_prev = __shfl(row, prev);
+            full_rows += (uint32_t)__builtin_popcountll(__ballot(want2 != 0u && row != (below ? row_prev : last_row)));
+            last_row = __shfl(row, 63 - __builtin_clzll(m2));
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    RowRegs<W, P, S> cur, nxt;
+    Hints hc, hn;
+    load_row_planes<W, P, S, 0, 1>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_hints(hc, p);
+    // The thresholds a row is judged by are asked for while the row BEFORE it is judged, along with that row's
+    // prefetch: loads return in order, so waiting for a threshold asked for after the prefetch would wait for all of
+    // it, and nothing would be in flight while the row is judged.
+    uint64_t tau_c[QB], tau_n[QB];
+#pragma unroll
+    for (int q = 0; q < QB; ++q) tau_c[q] = a.tau[(uint32_t)q < nq ? q : 0];
+    bool give_up = false;
+    for (;;) {
+        if (passed * 10 > probed + 4096) { give_up = true; break; }         // wave-uniform; row p is not done yet
+        const uint32_t pn = p + G;
+        const bool has_next = pn < a.p_end;
+        const uint32_t pl = has_next ? pn : p;          // (unconditional prefetch: see scan_exact_prog_hint)
+        load_row_planes<W, P, S, 0, 1>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_hints(hn, pl);
+#pragma unroll
+        for (int q = 0; q < QB; ++q) tau_n[q] = a.tau[(uint32_t)q < nq ? q : 0];
+        // what does not depend on the query
+        uint32_t hbytes[kItemsPerLane];
+        float h0[kItemsPerLane], h_last[kItemsPerLane], others[kItemsPerLane];
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            hbytes[m] = 0;
+            float rest = 0.0f;
+#pragma unroll
+            for (int j = 0; j < F; ++j) {
+                const uint32_t c = (hc.w[j] >> (8 * m)) & 255u;
+                hbytes[m] |= c << (8 * j);
+                if (j >= 1) rest += decode(c, j);
+            }
+            h0[m] = decode(hbytes[m] & 255u, 0);
+            h_last[m] = __uint_as_float((((hc.last >> (8 * m)) & 255u) + hb_last) << 18);
+            others[m] = rest + h_last[m];
+        }
+        float s0[kItemsPerLane][QB];
+        uint32_t want[kItemsPerLane];
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            want[m] = 0;
+#pragma unroll
+            for (int q = 0; q < QB; ++q) s0[m][q] = 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            if ((uint32_t)q >= nq) break;                     // wave-uniform
+            const QueryRegs<W, PQ> q0 = slot_query(s_query[q]);
+            const QueryMass mass{s_query[q].mass_x, s_query[q].mass_y};
+            const float taus = threshold_score(tau_c[q]);
+            const float slack_all = 2.0f * mass.y + 0.015875f * mass.x;
+            const float mass_hint = mass.x + 2.0f * mass.y + slack_all;
+            const float floor_c = floor_all * mass.x;
+#pragma unroll
+            for (int m = 0; m < kItemsPerLane; ++m) {
+                float t = q0.bias;
+#pragma unroll
+                for (int i = 0; i < PQ; ++i) {
+                    uint32_t pc = 0;
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[0][m][h] ^ q0.w[i][h]);
+                    t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                }
+                s0[m][q] = __fmaf_rn(h0[m], t, floor_c);      // (where stage B takes the chain up)
+                // (the first bound of scan_exact_prog2_hint)
+                const float at = __builtin_fabsf(t);
+                const float ub = __fmaf_rn(others[m], mass_hint,
+                                           __fmaf_rn(at, __fmaf_rn(0.015875f, h0[m], floor_0), __fmaf_rn(h0[m], t, 2.0f * mass.y * h0[m])));
+                want[m] |= !(ub < taus) ? (1u << q) : 0u;     // (a NaN bound does not prune)
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < kItemsPerLane; ++m) {
+            const bool pass = want[m] != 0u;
+            const uint64_t mk = __ballot(pass);
+            if (mk) {
+                if (pass) {
+                    const uint32_t at = qfill + (uint32_t)__builtin_popcountll(mk & ((1ull << lane) - 1ull));
+                    s_qid[wave][at] = p * (uint32_t)kTileItems + (uint32_t)wave * kRow + lane_item<W>(lane, m);
+#pragma unroll
+                    for (int q = 0; q < QB; ++q) s_qs0[wave][q][at] = s0[m][q];
+                    s_qhb[wave][at] = hbytes[m] | (want[m] << 24);
+                    s_qam[wave][at] = h_last[m];
+                }
+                const uint32_t n = (uint32_t)__builtin_popcountll(mk);
+                qfill += n;
+                passed += n;
+                if (qfill >= 64) {
+                    // the 64 oldest entries leave; the rest (fewer than 64) move to the front
+                    follow_up(0, 64);
+                    qfill -= 64;
+                    const bool mv = (uint32_t)lane < qfill;
+                    const uint32_t from = 64u + (mv ? (uint32_t)lane : 0u);
+                    const uint32_t e_id = s_qid[wave][from], e_hb = s_qhb[wave][from];
+                    const float e_am = s_qam[wave][from];
+                    float e_s0[QB];
+#pragma unroll
+                    for (int q = 0; q < QB; ++q) e_s0[q] = s_qs0[wave][q][from];
+                    __builtin_amdgcn_wave_barrier();
+                    if (mv) {
+                        s_qid[wave][lane] = e_id; s_qhb[wave][lane] = e_hb; s_qam[wave][lane] = e_am;
+#pragma unroll
+                        for (int q = 0; q < QB; ++q) s_qs0[wave][q][lane] = e_s0[q];
+                    }
+                }
+            }
+        }
+        probed += kRow;
+        if (!has_next) { p = pn; break; }
+        cur = nxt; hc = hn;
+#pragma unroll
+        for (int q = 0; q < QB; ++q) tau_c[q] = tau_n[q];
+        p = pn;
+    }
+    if (qfill) follow_up(0, qfill);
+    if (give_up) {
+        batch_prog_hint_rows<W, P, PQ, true>(a, p, full_rows, full_pairs, extra8, s_keys, ms, s_query, wave, lane);
+        return;
     }
     mstage_drain(ms, a.out, lane);
     if (a.deep_rows && lane == 0 && full_rows) atomicAdd(a.deep_rows, full_rows);
@@ -1742,7 +2049,11 @@ ScanFn prog_fn_m(int mode, bool single, bool hints, bool two_stage)
 {
     if constexpr (P >= 2) {
         if (mode == kModeScaled) {
-            if (!single) return hints ? scan_exact_batch_prog_hint<W, P, PQ> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
+            if (!single) {
+                if constexpr (P >= 3)
+                    if (hints && two_stage) return scan_exact_batch_prog2_hint<W, P, PQ>;
+                return hints ? scan_exact_batch_prog_hint<W, P, PQ> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
+            }
             if constexpr (P >= 3) {
                 if (hints && two_stage) return scan_exact_prog2_hint<W, P, PQ>;
             }

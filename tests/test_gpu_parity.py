@@ -1051,6 +1051,16 @@ def _search_both_ways(ix, qp, qs, k):
                 shares.append(st["deep_rows"] / rows)
             elif prog == 0:
                 assert st["deep_rows"] == 0
+        # the same queries two, three and four to a call (the small-batch forms of the same scans): same lists
+        nq = qp.shape[0]
+        for Q in (2, 3, 4):
+            if Q > nq:
+                break
+            for b in range(0, nq - Q + 1, Q):
+                ib, sb = rbe.rbe_search(ix, qp[b:b + Q], None if qs is None else qs[b:b + Q], k)
+                for j in range(Q):
+                    np.testing.assert_array_equal(ib[j], res[b + j][0][0], err_msg=f"prog {prog} Q {Q} query {b + j}")
+                    np.testing.assert_array_equal(sb[j], res[b + j][1][0], err_msg=f"prog {prog} Q {Q} query {b + j}")
         out[prog] = res
     rbe.rbe_debug_set_progressive(ix, True)
     for (i1, s1), (i2, s2), (i3, s3) in zip(out[1], out[2], out[3]):
@@ -1149,7 +1159,8 @@ def test_progressive_scan_with_fp32_queries(d, P, flags):
     rbe.rbe_free(ix)
 
 
-@pytest.mark.parametrize("d,P,Pq,flags", [(64, 3, 3, 0), (128, 4, 2, 0), (64, 2, 3, "dyadic"), (128, 3, 3, "dyadic_cosine")])
+@pytest.mark.parametrize("d,P,Pq,flags", [(64, 3, 3, 0), (128, 4, 2, 0), (64, 2, 3, "dyadic"), (128, 3, 3, "dyadic_cosine"),
+                                          (64, 4, 4, 0), (128, 3, 1, 0), (256, 3, 2, 0)])
 def test_progressive_scan_for_small_batches(d, P, Pq, flags):
     """A few queries per call (and any batch on the XOR/popcount kernel): the last level forms partial scores from all
     planes but the last for every query and reads a row's last plane once, for the first query that needs it.
@@ -1173,13 +1184,18 @@ def test_progressive_scan_for_small_batches(d, P, Pq, flags):
     rbe.rbe_debug_set_plan_split(ix, 1)         # no automatic choices
     for Q in (2, 4, 5, 7, 16):       # up to 4: the scan that streams the one-byte scale copies; above: the fp32 scales
         res = {}
-        for prog in (True, False):
+        for prog in (1, 3, 0):       # on (up to 4 queries and from three planes on: first stage on plane 0); on without that stage; off
             rbe.rbe_debug_set_progressive(ix, prog)
             res[prog] = rbe.rbe_search(ix, qp[:Q], None if qs is None else qs[:Q], k)
-            assert (rbe.rbe_get_search_stats(ix)["deep_rows"] > 0) == prog
-        np.testing.assert_array_equal(res[True][0], res[False][0])
-        np.testing.assert_array_equal(res[True][1], res[False][1])
-        check_batch(planes, scales, qp[:Q], qs_o[:Q], k, res[True][0], res[True][1])
+            st = rbe.rbe_get_search_stats(ix)
+            assert (st["deep_rows"] > 0) == (prog != 0)
+            if prog == 1 and flags == 0 and P >= 3 and Q <= 4:
+                assert st["scan_kernel"][st["n_levels"] - 1] == "scan_exact_prog2_hint"
+        for prog in (1, 3):
+            np.testing.assert_array_equal(res[prog][0], res[0][0])
+            np.testing.assert_array_equal(res[prog][1], res[0][1])
+        check_batch(planes, scales, qp[:Q], qs_o[:Q], k, res[1][0], res[1][1])
+    rbe.rbe_debug_set_progressive(ix, 1)
     rbe.rbe_free(ix)
 
 
