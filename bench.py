@@ -558,6 +558,10 @@ def main():
         b_scan = float(rb["scan_ms"].mean()) if rb["scan_ms"].size else float("nan")
         b_items = rb["last_items"]
         matrix_cores = B >= 5 and W <= 2     # the library's own choice of kernel for a batch (binary queries, general scales)
+        # bytes the finest-level launches ask for: whole rows, or (up to 16 queries per launch, an index with one-byte
+        # scale copies) planes 0 .. P-2 and the copies, plus what the second looks read
+        b_deep = float(rb["deep_units"].mean()) * 8.0 if rb["deep_units"].size else 0.0
+        b_bytes = b_items * (8 * W * (P - 1) + (P - 1)) + b_deep if (matrix_cores and b_deep > 0) else b_items * bytes_per_item
         if matrix_cores:
             # dense contraction [B x d] . [d x items] per corpus plane (one eight-bit integer per query component:
             # the contraction filters, survivors are rescored bitwise).  `achieved` prices the whole contraction;
@@ -571,7 +575,8 @@ def main():
                     "frac_of_f16_peak": ach / MFMA_F16_PEAK_TFLOPS,
                     "kernel_ms": b_scan, "flops_per_pair": 2 * d * P,
                     "issued_tops_first_look": issued / (b_scan * 1e-3) / 1e12, "traffic": None,
-                    "hbm_gbs": b_items * bytes_per_item / (b_scan * 1e-3) / 1e9}
+                    "hbm_gbs": b_bytes / (b_scan * 1e-3) / 1e9, "bytes_per_launch": b_bytes,
+                    "lean_stream": bool(b_deep > 0)}
         else:
             lane_ops = lane_ops_per_pair(W, P, P) * B * b_items
             ach = lane_ops / (b_scan * 1e-3) / 1e12

@@ -80,13 +80,14 @@ struct RawRow {
     float sc[S > 0 ? S : 1][kItemsPerLane / SEG];
 };
 
-template <int W, int P, int S>
+// JP, JS: planes 0 .. JP-1 and scale arrays 0 .. JS-1 only (the lean stream leaves the last plane and the fp32 scales out).
+template <int W, int P, int S, int JP = P, int JS = S>
 __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restrict__ tile, int wave, int seg, int lane)
 {
     constexpr int SEG = row_segments<W>();
     const TileGeom g{(uint32_t)W, (uint32_t)P, (uint32_t)S};
 #pragma unroll
-    for (int j = 0; j < P; ++j) {
+    for (int j = 0; j < JP; ++j) {
         const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + j * g.plane_bytes()) + (size_t)wave * kRow * W;
 #pragma unroll
         for (int s = 0; s < 2 * W / SEG; ++s) {
@@ -96,7 +97,7 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
         }
     }
 #pragma unroll
-    for (int j = 0; j < S; ++j) {
+    for (int j = 0; j < JS; ++j) {
         const float* sj = reinterpret_cast<const float*>(tile + g.scales_offset()) + j * kTileItems + wave * kRow;
         if (W == 1) {
 #pragma unroll
@@ -121,7 +122,15 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
 // CALIB: the measurement variant (BatchArgs::calib_repeat), a separate instantiation so that the scan proper carries
 // none of it.
 // OP: 0 = half operands (v_mfma_f32_16x16x32_f16), 1 = eight-bit integer operands (v_mfma_i32_16x16x64_i8).
-template <int W, int P, int MODE, int NQT, int RS, int OP = 0, bool CALIB = false>
+// LEAN (integer operands, binary queries, two or more planes, an index that holds one-byte copies of its scales):
+// the stream carries planes 0 .. P-2 and the one-byte copies of their scale arrays only -- 8W(P-1) + P-1 instead
+// of (8W + 4)P bytes per item.  The first look is formed with the copies in place of the scales (its threshold
+// lowered by the most the copies can be off, per row), over the whole segment; the blocks of 32 items in which
+// some pair passes it then have their last plane and their fp32 scales read, all at once, and are looked at again
+// with every plane and the true scales -- the look a wave takes that has given the first look up.  What passes
+// that is scored exactly as before, so the results do not change.  A wave that looks again at more than half of
+// its blocks goes back to whole rows.
+template <int W, int P, int MODE, int NQT, int RS, int OP = 0, bool CALIB = false, bool LEAN = false>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu((NQT == 1 && W == 1 && P <= 3) ? 3 : 1)))
 void scan_batch_mfma(const BatchArgs a)
 {
@@ -143,6 +152,7 @@ void scan_batch_mfma(const BatchArgs a)
     // last plane as well (dyadic modes: that is then the exact score) before anything is queued or scored exactly.
     // (With fp32 queries the saving did not pay for the extra table reads.)
     constexpr bool kCanSkip = (kBinary || kDy) && P >= 2;
+    static_assert(!LEAN || (kI8 && kBinary && P >= 2 && !CALIB), "the lean stream: integer operands, binary queries, two or more planes");
     constexpr int PA = kDy ? P : 1;
     constexpr int PD_MAX = kDy ? 1 : P;
     constexpr int SEG = row_segments<W>();
@@ -264,9 +274,45 @@ void scan_batch_mfma(const BatchArgs a)
 
     bool skip_last = kCanSkip;              // wave-uniform
     uint32_t blocks_seen = 0, second_looks = 0;
+    uint32_t lean_units = 0;
     RawRow<W, P, S> cur;
     int seg = 0;
-    load_raw<W, P, S>(cur, a.tiles + (size_t)p * tile_bytes, wave, seg, lane);
+    // LEAN: the lane's one-byte scale copies of the row in `cur` (word j = array j, byte m = the lane's item m), what
+    // a copy decodes to, and the most the copies of arrays 0 .. P-2 can be off for scales below their smallest code
+    constexpr int NW = P - 1 == 3 ? 4 : (P >= 2 ? P - 1 : 1);
+    uint32_t hw[NW] = {};
+    uint32_t hint_lo[3] = {0u, 0u, 0u};
+    float hint_floor = 0.0f;
+    if constexpr (LEAN) {
+#pragma unroll
+        for (int j = 0; j < P - 1; ++j) {
+            hint_lo[j] = (uint32_t)a.hint_base[j] << 5;
+            hint_floor += __uint_as_float((uint32_t)a.hint_base[j] << 23);
+        }
+        hint_floor *= 1.0001f;
+    }
+    // loads a segment into `cur`: everything, or (LEAN, while the wave leaves the last plane out) the lean stream
+    auto load_segment = [&](uint32_t tile_p, int sg, bool full) __attribute__((always_inline)) {
+        if constexpr (LEAN) {
+            if (!full) {
+                load_raw<W, P, S, P - 1, 0>(cur, a.tiles + (size_t)tile_p * tile_bytes, wave, sg, lane);
+                const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
+                if constexpr (NW == 1) {
+                    hw[0] = __builtin_nontemporal_load(src);
+                } else if constexpr (NW == 2) {
+                    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+                    hw[0] = v.x; hw[1] = v.y;
+                } else {
+                    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+                    hw[0] = v.x; hw[1] = v.y; hw[2] = v.z; hw[3] = v.w;
+                }
+                return;
+            }
+        }
+        load_raw<W, P, S>(cur, a.tiles + (size_t)tile_p * tile_bytes, wave, sg, lane);
+    };
+    bool cur_full = !(LEAN && skip_last);     // wave-uniform: what `cur` holds
+    load_segment(p, seg, cur_full);
     uint32_t calib_left = CALIB ? a.calib_repeat : 0u;   // measurement variant: segments to go through again without loading them
     for (;;) {
         const bool again = CALIB && calib_left != 0;     // wave-uniform
@@ -274,36 +320,59 @@ void scan_batch_mfma(const BatchArgs a)
         const uint32_t pn = again ? p : (segn == 0 ? p + G : p);
         const bool has_next = again || pn < a.p_end;
         // stage the segment in this wave's LDS area, in item order
+        const bool lean_now = LEAN && !cur_full;        // wave-uniform: this segment came by the lean stream
 #pragma unroll
         for (int j = 0; j < P; ++j)
+            if (j < P - 1 || !lean_now) {
 #pragma unroll
-            for (int s = 0; s < 2 * W / SEG; ++s) {
-                uint64_t* dst = (W == 1) ? &s_pl[wave][j][s * 128 + 2 * lane] : &s_pl[wave][j][(s * 64 + lane) * 2];
-                *reinterpret_cast<u32x4*>(dst) = cur.pl[j][s];
+                for (int s = 0; s < 2 * W / SEG; ++s) {
+                    uint64_t* dst = (W == 1) ? &s_pl[wave][j][s * 128 + 2 * lane] : &s_pl[wave][j][(s * 64 + lane) * 2];
+                    *reinterpret_cast<u32x4*>(dst) = cur.pl[j][s];
+                }
             }
+        if (lean_now) {
+            // (the one-byte copies stand where the first look expects the scales)
 #pragma unroll
-        for (int j = 0; j < S; ++j)
+            for (int j = 0; j < P - 1; ++j)
 #pragma unroll
-            for (int m = 0; m < kItemsPerLane / SEG; ++m)
-                s_sc[wave][j][SEG == 1 ? lane_item<W>(lane, m) : m * 64 + lane] = cur.sc[j][m];
+                for (int m = 0; m < kItemsPerLane / SEG; ++m) {
+                    const uint32_t c = (hw[j] >> (8 * (SEG == 1 ? m : seg))) & 255u;
+                    s_sc[wave][j][SEG == 1 ? lane_item<W>(lane, m) : m * 64 + lane] = __uint_as_float((c + hint_lo[j]) << 18);
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < S; ++j)
+#pragma unroll
+                for (int m = 0; m < kItemsPerLane / SEG; ++m)
+                    s_sc[wave][j][SEG == 1 ? lane_item<W>(lane, m) : m * 64 + lane] = cur.sc[j][m];
+        }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         // the staged copy is what the segment is worked from: its registers are free for the next segment, whose
         // loads stay in flight while this one is contracted (one register set instead of two)
         __builtin_amdgcn_sched_barrier(0);
         if (again) --calib_left;                // (the registers still hold the segment)
-        else if (has_next) load_raw<W, P, S>(cur, a.tiles + (size_t)pn * tile_bytes, wave, segn, lane);
+        else if (has_next) {
+            cur_full = !(LEAN && skip_last);
+            load_segment(pn, segn, cur_full);
+        }
 
         const uint64_t row_id = (uint64_t)phys_to_tile(a.layout, p) * kTileItems + (uint64_t)wave * kRow +
                                 (uint64_t)seg * kSegItems;
         constexpr int U = 2;   // item groups per straight-line block
         // the segment's blocks, with the last plane left out of the first look (SKIP) or not: two copies of the
         // code, one of which runs per segment
-        auto blocks = [&](auto skip_tag) {
+        // PHASE 0: first look, second look where it is needed, survivors.  PHASE 1 (lean stream, SKIP): the first look
+        // alone, with the one-byte copies for scales; returns the set of blocks to look at again.  PHASE 2 (lean
+        // stream, not SKIP): the blocks of `only`, with everything read for them by now; they were counted in phase 1.
+        auto blocks = [&](auto skip_tag, auto phase_tag, uint32_t only) -> uint32_t {
         constexpr bool SKIP = decltype(skip_tag)::value;
+        constexpr int PHASE = decltype(phase_tag)::value;
+        static_assert(PHASE == 0 || (LEAN && SKIP == (PHASE == 1)), "phases of the lean stream");
         constexpr int F = SKIP ? P - 1 : P;
         constexpr int PD = kDy ? 1 : F;
         static_assert(PD <= PD_MAX, "accumulators");
+        uint32_t look_again = 0;
         // General scales, last plane left out: a pair can only reach its threshold if
         //     sum_{j<P-1} a_j D_j  >=  tau - a_{P-1} mass_q - margin sum_j a_j,
         // and with the row's largest last scale and largest scale sum the right-hand side is the same for every item
@@ -314,10 +383,21 @@ void scan_batch_mfma(const BatchArgs a)
 #pragma unroll
             for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    row_taus[qt][r] = taus[qt][r] - 1.000001f * __fmaf_rn(amax, qmass[qt][r], a.margin * smax);
+                for (int r = 0; r < 4; ++r) {
+                    if constexpr (PHASE == 1) {
+                        // the copies of arrays 0 .. P-2 add up to hs at most; each is within 2^-6 * 1.016 of its
+                        // scale, or (a scale below the smallest code) above it by less than that code; a plane's
+                        // contraction of the rounded query stays within mass_q + margin
+                        const float hs = __fmaf_rn(1.016f, smax, hint_floor);
+                        const float off = __fmaf_rn(0.015875f, hs, hint_floor);
+                        row_taus[qt][r] = taus[qt][r] - 1.000001f * (__fmaf_rn(amax, qmass[qt][r], a.margin * hs) + off * (qmass[qt][r] + a.margin));
+                    } else {
+                        row_taus[qt][r] = taus[qt][r] - 1.000001f * __fmaf_rn(amax, qmass[qt][r], a.margin * smax);
+                    }
+                }
         }
         for (int cb = 0; cb < kSegItems / (16 * U); ++cb) {
+            if (PHASE == 2 && !((only >> cb) & 1u)) continue;       // wave-uniform
             float s[U][NQT][4];
             bool any = false;
 #pragma unroll
@@ -377,7 +457,11 @@ void scan_batch_mfma(const BatchArgs a)
                     }
             }
             bool go = __ballot(any) != 0;
-            ++blocks_seen;
+            if (PHASE != 2) ++blocks_seen;
+            if constexpr (PHASE == 1) {
+                look_again |= go ? (1u << cb) : 0u;
+                continue;
+            }
             if (F < P && go) {
                 ++second_looks;
                 // second look, with the last plane contracted too
@@ -483,15 +567,74 @@ void scan_batch_mfma(const BatchArgs a)
                 }
             }
         }
+        return look_again;
         };
-        if constexpr (kCanSkip) {
-            if (skip_last) blocks(std::true_type{});
-            else blocks(std::false_type{});
+        using phase0 = std::integral_constant<int, 0>;
+        if constexpr (LEAN) {
+            if (lean_now) {
+                const uint32_t again_mask = blocks(std::true_type{}, std::integral_constant<int, 1>{}, 0u);
+                if (again_mask) {
+                    second_looks += (uint32_t)__builtin_popcount(again_mask);
+                    lean_units += (uint32_t)__builtin_popcount(again_mask) * (32u * W + 16u * S);       // 8-byte units asked for beyond the stream
+                    // the last plane and the fp32 scales of the blocks to look at again: every lane asks for what it
+                    // would have staged of them, all loads in flight together, then they take their places in LDS
+                    const char* tile = a.tiles + (size_t)p * tile_bytes;
+                    const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
+                    const float* sj0 = reinterpret_cast<const float*>(tile + geom.scales_offset()) + wave * kRow;
+                    constexpr int SLOTS = 2 * W / SEG, PER = kItemsPerLane / SEG / SLOTS;     // item slots of a lane, items per slot
+                    u32x4 gpl[SLOTS];
+                    float gsc[S][SLOTS][PER];
+                    bool mine[SLOTS];
+#pragma unroll
+                    for (int sl = 0; sl < SLOTS; ++sl) {
+                        const int item0 = (W == 1) ? sl * 128 + 2 * lane : sl * 64 + lane;        // (first) item of the slot, in the segment
+                        mine[sl] = ((again_mask >> (item0 >> 5)) & 1u) != 0u;
+                        gpl[sl] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                        for (int j = 0; j < S; ++j)
+#pragma unroll
+                            for (int e = 0; e < PER; ++e) gsc[j][sl][e] = 0.0f;
+                        if (mine[sl]) {
+                            const uint64_t* src = (W == 1) ? pj + sl * 128 + 2 * lane : pj + (size_t)((seg * (4 / SEG) + sl) * 64 + lane) * 2;
+                            gpl[sl] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+#pragma unroll
+                            for (int j = 0; j < S; ++j) {
+                                const float* sj = sj0 + j * kTileItems;
+                                if constexpr (W == 1) {
+                                    const f32x2 v = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sj + sl * 128 + 2 * lane));
+                                    gsc[j][sl][0] = v.x; gsc[j][sl][1] = v.y;
+                                } else {
+                                    gsc[j][sl][0] = __builtin_nontemporal_load(sj + (seg * (kItemsPerLane / SEG) + sl) * 64 + lane);
+                                }
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int sl = 0; sl < SLOTS; ++sl)
+                        if (mine[sl]) {
+                            const int item0 = (W == 1) ? sl * 128 + 2 * lane : sl * 64 + lane;
+                            *reinterpret_cast<u32x4*>(&s_pl[wave][P - 1][item0 * W]) = gpl[sl];
+#pragma unroll
+                            for (int j = 0; j < S; ++j)
+#pragma unroll
+                                for (int e = 0; e < PER; ++e) s_sc[wave][j][item0 + e] = gsc[j][sl][e];
+                        }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    blocks(std::false_type{}, std::integral_constant<int, 2>{}, again_mask);
+                }
+                if (second_looks * 2 > blocks_seen + 16) skip_last = false;
+            } else {
+                blocks(std::false_type{}, phase0{}, 0u);
+            }
+        } else if constexpr (kCanSkip) {
+            if (skip_last) blocks(std::true_type{}, phase0{}, 0u);
+            else blocks(std::false_type{}, phase0{}, 0u);
             // a wave that takes the second look for more than half of its blocks (a loose threshold, or weights
             // that do not decay) contracts every plane in the first look from then on
             if (skip_last && second_looks * 2 > blocks_seen + 16) skip_last = false;
         } else {
-            blocks(std::false_type{});
+            blocks(std::false_type{}, phase0{}, 0u);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -501,6 +644,7 @@ void scan_batch_mfma(const BatchArgs a)
         seg = segn;
     }
     mstage_drain(ms, a.out, lane);
+    if (LEAN && a.deep_units && lane == 0 && lean_units) atomicAdd(a.deep_units, lean_units);
     if (kCanSkip && a.look_stats && lane == 0 && blocks_seen) {
         atomicAdd(&a.look_stats[0], 1u);
         if (!skip_last) atomicAdd(&a.look_stats[1], 1u);
@@ -511,7 +655,7 @@ namespace {
 using BatchFn = void (*)(const BatchArgs);
 
 template <int W, int P, int MODE>
-BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib)
+BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib, bool lean)
 {
     if (nqt != 1 && nqt != 2) return nullptr;
     if constexpr (MODE == kModeScaled) {
@@ -522,6 +666,11 @@ BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib)
             }
             if (rescore != 1) return nullptr;
             if (calib) return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1, 1, true> : scan_batch_mfma<W, P, MODE, 2, 1, 1, true>;
+            // (one query tile per launch only: with two, 32 queries share every byte read, and the second set of
+            // loads and the two-phase segment cost more than the bytes they save -- 1e9 items, 32 queries: 10.9 ms
+            // with whole rows, 12.0 ms with the lean stream)
+            if constexpr (P >= 2)
+                if (lean && nqt == 1) return scan_batch_mfma<W, P, MODE, 1, 1, 1, false, true>;
             return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 1, 1> : scan_batch_mfma<W, P, MODE, 2, 1, 1>;
         }
         if (calib) return nullptr;      // the measurement variant is built for the default operands only
@@ -535,12 +684,12 @@ BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib)
 }
 
 template <int W, int P>
-BatchFn batch_fn_m(int mode, uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib)
+BatchFn batch_fn_m(int mode, uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib, bool lean)
 {
     switch (mode) {
-        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore, operand, calib);
-        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0, operand, calib);
-        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0, operand, calib);
+        case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore, operand, calib, lean);
+        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0, operand, calib, false);
+        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0, operand, calib, false);
         default: return nullptr;
     }
 }
@@ -551,11 +700,13 @@ hipError_t launch_scan_batch_w<RBE_W>(const KernelSel& k, const BatchArgs& a, ui
                                       uint32_t per_cu, hipStream_t st, uint32_t* grid_out)
 {
     BatchFn fn = nullptr;
+    // the lean stream: where the index holds one-byte copies of its scales (and so the rows' largest values too)
+    const bool lean = a.hints != nullptr && a.row_amax != nullptr && a.row_asum != nullptr && a.operand == 1 && a.rescore == 1 && a.calib_repeat == 0;
     switch (k.P) {
-        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0); break;
-        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0); break;
-        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0); break;
-        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0); break;
+        case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0, lean); break;
+        case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0, lean); break;
+        case 3: fn = batch_fn_m<RBE_W, 3>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0, lean); break;
+        case 4: fn = batch_fn_m<RBE_W, 4>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0, lean); break;
         default: break;
     }
     if (!fn) return hipErrorInvalidValue;

@@ -618,6 +618,10 @@ struct BatchArgs {
                               // the last plane's term can add to the accumulator, 2^-(P-1) (sum_d |v_d| + sum_d v_d)
     const float* row_amax;    // [physical tile][4 rows] largest last scale of the row, and ...
     const float* row_asum;    // ... largest sum of an item's scales in the row (general scales)
+    const uint32_t* hints;    // one-byte copies of the scale arrays 0 .. P-2 (see scale_hints), or null: integer operands
+                              // and binary queries then take the lean stream (planes 0 .. P-2 and these copies)
+    uint8_t hint_base[3];     // exponent base of each array's copies
+    uint32_t* deep_units;     // += bytes / 8 that the lean stream's second looks asked for (may be null)
     uint32_t* look_stats;     // [2] += waves that ran, waves that gave up leaving the last plane out (may be null)
     const uint64_t* tau;      // [Q] threshold keys
     uint32_t n_queries;       // Q

@@ -525,6 +525,73 @@ def test_integer_filter_at_the_margin_never_drops_a_survivor(lib, exact_query):
         assert margin < 4.5                      # nothing but the arithmetic allowances (multiply-adds, XOR/popcount score)
 
 
+def test_lean_first_look_with_scale_copies_never_drops_a_survivor(lib):
+    """The matrix-core scan's lean stream forms its first look with the one-byte copies h_j of the scales of planes
+    0 .. P-2 and lowers the row's threshold by the most the copies can be off:
+        hs = 1.016 smax + floor,  off = 0.015875 hs + floor,
+        row_tau = tau - 1.000001 (amax mass + margin hs + off (mass + margin)),
+    floor the sum of the arrays' smallest codes.  With the planes that make the integer contraction fall short of
+    the true value most, the last plane attaining the query's mass, scales spread over many binades (zeros and values
+    far below the smallest code included) and a threshold equal to the pair's own score, the first look -- fp32
+    steps as the kernel takes them -- lets every pair through."""
+    rng = np.random.default_rng(321)
+    dim, P, Pq, Q, N = 64, 3, 3, 16, 600
+    f32, f64 = np.float32, np.float64
+    qp = rng.integers(0, 2**64, size=(Q, Pq, 1), dtype=np.uint64)
+    qs = rng.uniform(0.01, 3.0, size=(Q, Pq)).astype(np.float32)
+    ops, unscale, start, mass, margin = rbe.rbe_debug_batch_operands_i8(qp, qs, dim)
+    qbits = ((qp[:, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64)
+    qhat = (qs.astype(np.float64)[:, :, None, None] * (2 * qbits - 1)).sum(axis=1).reshape(Q, dim)
+    scales = (rng.uniform(0.02, 1.0, size=(P, N)) * 10.0 ** rng.uniform(-9, 0, size=(P, N))).astype(f32)
+    scales[:, :20] = 0.0
+    scales[0, 20:60] = f32(0.97)
+    scales[1, 40:80] = f32(0.5)
+    # items whose copies read as low as copies can (scales just under the midpoint of two codes) and whose last scale
+    # is the row's largest: with planes that agree with the query, nothing but the allowance for the copies lets them pass
+    under = np.arange(N) % 5 == 0
+    for j in range(P - 1):
+        m = 1.0 + (rng.integers(0, 32, size=N) + 0.49) / 32.0
+        scales[j, under] = (m * 2.0 ** rng.integers(-3, 0, size=N)).astype(f32)[under]
+    scales[P - 1, under] = f32(0.25)
+    scales[P - 1, ~under] = np.minimum(scales[P - 1, ~under], f32(0.25))
+    h = np.zeros((P - 1, N)); floor = 0.0
+    for j in range(P - 1):
+        h[j], base = _scale_copy_codec(scales[j])
+        floor += 2.0 ** (base - 127)
+    h = h.astype(f32)
+    floor = f32(f32(floor) * f32(1.0001))
+    closest = np.inf
+    for rows in np.array_split(np.arange(N), 12):            # a row of the corpus: its largest last scale and scale sum
+        a = scales[:, rows]
+        amax = a[P - 1].max()
+        smax = f32(float(a.astype(f64).sum(axis=0).max()) * (1 + 1e-6))
+        hs = f32(f64(f32(1.016)) * f64(smax) + f64(floor))
+        off = f32(f64(f32(0.015875)) * f64(hs) + f64(floor))
+        for q in range(Q):
+            T, stored, odd = _i8_operand_view(ops, q, dim)
+            v = qhat[q] / float(unscale[q])
+            low = np.where(32 * T - v > 0, 0, 1)
+            best_last = (v > 0).astype(np.int64)
+            fa_low = _i8_accumulator(start[q], stored, odd, low)
+            fa_best = _i8_accumulator(start[q], stored, odd, best_last)
+            slack = f32(f32(f64(amax) * f64(mass[q]) + f64(f32(f32(margin) * hs))) + f32(off * f32(mass[q] + f32(margin))))
+            for z in range(a.shape[1]):
+                first_planes = best_last if under[rows[z]] else low
+                fa = fa_best if under[rows[z]] else fa_low
+                true = sum(float(a[j, z]) * float(v @ (2 * first_planes - 1)) for j in range(P - 1)) + float(a[P - 1, z]) * float(v @ (2 * best_last - 1))
+                taus = f32(true)
+                if float(taus) < true:
+                    taus = np.nextafter(taus, f32(np.inf))
+                row_tau = f32(taus - f32(f32(1.000001) * slack))
+                hz = h[:, rows[z]]
+                first = f32(f64(-K_ACC) * f64(f32(hz[0] + hz[1])))
+                for j in range(P - 1):
+                    first = f32(f64(hz[j]) * f64(fa) + f64(first))
+                assert first >= row_tau, (q, int(rows[z]), float(first), float(row_tau))
+                closest = min(closest, (float(first) - float(row_tau)) / max(float(slack), 1e-30))
+    assert closest < 1.0           # (the cases do come within the allowance: it is not idle)
+
+
 # ------------------------------------------------------------------ host logic: query mass of the progressive scan
 @pytest.mark.parametrize("dim,Pq", [(64, 1), (64, 3), (128, 4), (256, 2)])
 def test_query_mass_bounds_every_plane(lib, dim, Pq):

@@ -723,6 +723,73 @@ def test_matrix_core_batch_path_matches_oracle_and_popcount_path(d, P, Pq, Q, k)
     rbe.rbe_free(ix)
 
 
+@pytest.mark.parametrize("d,P,Pq,Q,k", [(64, 3, 3, 16, 100), (64, 2, 3, 7, 50), (64, 4, 2, 9, 100), (128, 3, 3, 12, 60),
+                                        (128, 4, 4, 16, 40), (64, 3, 3, 20, 30)])
+def test_matrix_core_scan_on_the_lean_stream(d, P, Pq, Q, k):
+    """Integer operands, up to 16 queries per launch, an index with one-byte scale copies: the last levels stream all
+    planes but the last and the copies only, and read the rest for the blocks of 32 items that the first look cannot
+    rule out.  Same ids and scores as with whole rows streamed (switch 2), as the XOR/popcount scan's, and the
+    oracle's; the extra reads are counted.  (20 queries: a launch of two query tiles, which streams whole rows.)"""
+    N = 400_003
+    planes, scales, qp, qs = clustered(N, d, P, 2048, 0.3, Q, Pq, seed=300 + d + P)
+    ix = load_with_ratio(planes, scales, 8)
+    rbe.rbe_debug_set_plan_split(ix, 1)
+    rbe.rbe_debug_set_batch_path(ix, 2)
+    res = {}
+    for prog in (1, 2, 0):
+        rbe.rbe_debug_set_progressive(ix, prog)
+        res[prog] = rbe.rbe_search(ix, qp, qs, k)
+        st = rbe.rbe_get_search_stats(ix)
+        assert st["scan_kernel"][-1] == "scan_batch_mfma"
+        assert (st["deep_units"] > 0) == (prog == 1 and Q <= 16), (prog, st["deep_units"])
+        if prog == 1 and Q <= 16:
+            # 32 items of (8W + 4P) bytes per block looked at again: no block more than once
+            seen = sum(st["items_scanned"]) + 32 * len(st["items_scanned"])
+            assert st["deep_units"] * 8 <= seen * (8 * (d // 64) + 4 * P), (st["deep_units"], seen)
+    rbe.rbe_debug_set_progressive(ix, 1)
+    rbe.rbe_debug_set_batch_path(ix, 1)
+    res["xor"] = rbe.rbe_search(ix, qp, qs, k)
+    for key in (2, 0, "xor"):
+        np.testing.assert_array_equal(res[1][0], res[key][0])
+        np.testing.assert_array_equal(res[1][1], res[key][1])
+    check_batch(planes, scales, qp, qs, k, res[1][0], res[1][1])
+    rbe.rbe_free(ix)
+
+
+def test_matrix_core_scan_on_the_lean_stream_with_scales_outside_their_copies_range():
+    """Scale arrays that span twelve binades (items below the smallest one-byte code of their array) and a corpus
+    that cannot be pruned (random bits, scales that do not decay: waves go back to whole rows): ids and scores equal
+    those of the scan that streams whole rows."""
+    N, d, P, k, Q = 300_007, 64, 3, 12, 8
+    planes, scales, qp, qs = clustered(N, d, P, 1024, 0.3, Q, 3, seed=375)
+    rng = np.random.default_rng(376)
+    factor = rng.choice(np.array([2.0 ** -9, 2.0 ** -3, 1.0, 1.0], dtype=np.float32), size=N)
+    scales = (scales * factor[None, :]).astype(np.float32)
+    scales[0, rng.choice(N, 3)] *= np.float32(1.9)
+    N_r = 2_000_003                  # (at one workgroup per compute unit every wave has seven or eight rows of it)
+    planes_r, scales_r = random_corpus(rng, N_r, d, P)
+    qp_r, qs_r = random_queries(rng, Q, d, 3)
+    for pl, sc, q1, q2, hard in ((planes, scales, qp, qs, False), (planes_r, scales_r, qp_r, qs_r, True)):
+        ix = load_with_ratio(pl, sc, 8)
+        rbe.rbe_debug_set_plan_split(ix, 1)
+        rbe.rbe_debug_set_batch_path(ix, 2)
+        if hard:
+            rbe.rbe_set_tuning(ix, 0, 1)
+        res = {}
+        for prog in (1, 2):
+            rbe.rbe_debug_set_progressive(ix, prog)
+            res[prog] = rbe.rbe_search(ix, q1, q2, k)
+            if hard and prog == 1:
+                # nearly every block is looked at again, so the waves give the lean stream up after their first rows
+                st = rbe.rbe_get_search_stats(ix)
+                share = st["deep_units"] * 8 / (sum(st["items_scanned"]) * (8 + 4 * P))
+                assert 0.05 < share < 0.75, share
+        np.testing.assert_array_equal(res[1][0], res[2][0])
+        np.testing.assert_array_equal(res[1][1], res[2][1])
+        check_batch(pl, sc, q1, q2, k, res[1][0], res[1][1])
+        rbe.rbe_free(ix)
+
+
 def test_matrix_core_batch_path_random_corpus_multi_level_and_dyadic():
     rng = np.random.default_rng(41)
     planes, scales = random_corpus(rng, 300_000, 64, 3)
