@@ -79,6 +79,12 @@ def finest_level_roofline(np, r, W, P, Q, d, kernel):
            "algorithmic_bytes_per_item_per_pass": bytes_per_item, "passes_over_the_level": passes,
            "hbm_gbs": items * bytes_per_item * passes / (ms * 1e-3) / 1e9}
     out["hbm_frac"] = out["hbm_gbs"] / HBM_PEAK_GBS
+    deep = float(r["deep_units"].mean()) * 8.0 if r["deep_units"].size else 0.0
+    if kernel == "scan_batch_mfma" and Q <= 16 and P >= 2 and deep > 0:
+        # the lean stream: planes 0 .. P-2 and one-byte scale copies, plus what the library counted beyond them
+        asked = items * (8 * W * (P - 1) + (P - 1)) + deep
+        out["bytes_asked_for"] = asked
+        out["hbm_gbs_asked_for"] = asked / (ms * 1e-3) / 1e9
     if kernel == "scan_batch_mfma":
         ach = 2.0 * Q * items * d * P / (ms * 1e-3) / 1e12
         out.update({"bound": "mfma", "achieved": ach, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
