@@ -39,14 +39,18 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
  * bound -- the exact contribution of the other planes plus the largest value the
  * last plane could add -- reaches the threshold; such items are then scored in
  * full, so the results are those of the plain scan bit for bit.
- * With three or more planes a one-query scan goes one step further: its stream
- * carries plane 0 and the scale copies alone, items that a bound from plane 0
- * cannot rule out are gathered 64 at a time, and only those have their planes
- * 1 .. P-2 read (then the last plane, as above).
- * enabled = 0 switches it off (every plane of every item is read); default 1;
+ * With three or more planes a scan of one to four queries goes one step further:
+ * its stream carries plane 0 and the scale copies alone, items that a bound from
+ * plane 0 cannot rule out (for some query) are gathered 64 at a time, and only
+ * those have their planes 1 .. P-2 read (then the last plane, as above).
+ * Larger batches on general scales (the matrix-core scan, up to 16 queries per
+ * launch) stream planes 0 .. P-2 and the scale copies and read the last plane
+ * and the fp32 scales for the blocks of 32 items their first look cannot rule out.
+ * enabled = 0 switches all of it off (every plane of every item is read); default 1;
  * 2 = on, but without the one-byte scale copies (what an index uses whose
- * copies did not fit in device memory); 3 = on, with planes 0 .. P-2 in the
- * stream (no first stage on plane 0 alone).                                      */
+ * copies did not fit in device memory; the matrix-core scan then streams whole
+ * rows); 3 = on, with planes 0 .. P-2 in the stream (no first stage on plane 0
+ * alone; the matrix-core scan streams whole rows).                              */
 int rbe_debug_set_progressive(rbe_index *ix, int enabled);
 
 /* The last level of an exact search in two parts (an eighth of its items, a
