@@ -32,7 +32,7 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
                      uint32_t q_n_planes, uint64_t first_item, uint64_t count,
                      float *out, void *hip_stream);
 
-/* Fewer than 5 queries per call (7 for RBE_DYADIC), exact mode, 2 or more planes:
+/* Fewer than 5 queries per call (6 for RBE_DYADIC), exact mode, 2 or more planes:
  * the last (largest) level of the search streams every plane but the last (one query: with one-byte
  * copies of their scales and the row's largest last scale in place of the fp32
  * arrays) and reads an item's last plane and fp32 scales only where its upper
@@ -78,7 +78,7 @@ int rbe_debug_query_mass(const uint64_t *q_planes, const float *q_scales, uint32
                          uint32_t dim, uint32_t dyadic, float *mass_out);
 
 /* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 5
- * queries per call on, 7 for RBE_DYADIC; dim <= 128), 1 = always the
+ * queries per call on, 6 for RBE_DYADIC; dim <= 128), 1 = always the
  * XOR/popcount kernel, 2 = the matrix-core kernel for any number of queries
  * (dim <= 128), 3 = as 2, with half operands also where eight-bit integer
  * operands are the default (binary queries on general scales).                 */

@@ -511,11 +511,12 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
     if (ix->batch_path >= 2) return true;
     // Measured crossover, 1e9 items d=64 P=3, whole search, XOR/popcount scan / this scan.  Integer operands
     // (general scales): 4 queries 6.5 / 6.7 ms, 5 queries 8.0 / 6.8 ms; a 16-query tile costs this scan about as
-    // much as 4.3 queries cost the other.  Half operands (the dyadic modes), before the last level was taken in two
-    // parts: 6 queries 9.3 ms either way, 7 queries 10.5 / 9.5 ms.  The byte-table scan of fp32 queries reads the
-    // corpus once per query (3.0 ms each), so there the matrix cores win from 3 queries on (7.8 ms).
+    // much as 4.3 queries cost the other.  Half operands (the dyadic modes), 1e9 items, 2 / 3 / 4 (6e8 items) planes:
+    // 5 queries 4.9 / 5.0, 7.1 / 6.9, 5.8 / 6.0 ms; 6 queries 5.6 / 5.1, 8.2 / 7.0, 6.6 / 6.1 ms.  The byte-table scan
+    // of fp32 queries reads the corpus once per query (3.0 ms each), so there the matrix cores win from 3 queries on
+    // (7.8 ms).
     if (float_query) return Q >= 3u;
-    return Q >= (batch_operand_i8(ix, false) ? 5u : 7u);
+    return Q >= (batch_operand_i8(ix, false) ? 5u : 6u);
 }
 
 // Matrix-core operands of a batch (pure host arithmetic).  Each query is reconstructed in double as
