@@ -312,7 +312,7 @@ def main():
     if P >= 2:
         # (three hint bytes travel as four; the two-stage scan streams plane 0 alone and counts what its lanes ask
         # for beyond that -- the other planes of the items its first bound lets through -- in deep_units)
-        stream_bytes_per_item = (1 if two_stage else P - 1) * 8 * W + (4 if P == 4 else P - 1) + (1 if two_stage else 0)
+        stream_bytes_per_item = ((2 if P >= 4 else 1) if two_stage else P - 1) * 8 * W + (4 if P == 4 else P - 1) + (1 if two_stage else 0)
         bytes_read = last_items * stream_bytes_per_item + (last_items // 256) * 4 + deep_bytes
     else:
         stream_bytes_per_item = bytes_per_item

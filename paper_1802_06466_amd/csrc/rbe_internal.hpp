@@ -79,7 +79,7 @@ inline uint32_t streaming_blocks_per_cu(uint32_t W, uint32_t P, uint32_t S, bool
 {
     const bool prog = progressive && P >= 2;
     const bool two = prog && hints && two_stage && P >= 3;
-    const uint32_t planes = two ? 1u : (prog ? P - 1 : P), scales = prog && S > 0 ? S - 1 : S;
+    const uint32_t planes = two ? (P >= 4 ? 2u : 1u) : (prog ? P - 1 : P), scales = prog && S > 0 ? S - 1 : S;     // (see scan_exact_prog2_hint for the planes of its stream)
     const uint32_t tile_stream = kTileItems * (8u * W * planes + (prog && hints ? 1u : 4u) * scales);
     const uint32_t n = (32u * 1024u + tile_stream / 2) / tile_stream;
     return n < 1u ? 1u : (n > 3u ? 3u : n);

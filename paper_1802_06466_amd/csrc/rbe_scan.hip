@@ -398,9 +398,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog(const ScanArgs a)
 // scan_exact does (whole rows, prefetched).  The two register sets (this row, the next one in flight) hold the
 // streamed planes only and swap roles from row to row.
 // The rows of a wave from tile p on (p, p + grid, ...), with what the wave has queued and counted so far: the whole
-// of scan_exact_prog_hint, and what scan_exact_prog2_hint falls back to.  STREAM_EXTRA: count the planes 1 .. P-2
+// of scan_exact_prog_hint, and what scan_exact_prog2_hint falls back to.  STREAM_EXTRA (a number of planes): count the planes A .. P-2
 // that this stream carries as bytes beyond the (plane 0 only) stream of the caller.
-template <int W, int P, int PQ, bool STREAM_EXTRA>
+template <int W, int P, int PQ, int STREAM_EXTRA>
 __device__ __forceinline__ void prog_hint_rows(const ScanArgs& a, uint32_t p, uint32_t fill, uint32_t full_rows, uint32_t extra8,
                                                uint64_t* s_keys, int wave, int lane)
 {
@@ -495,7 +495,7 @@ __device__ __forceinline__ void prog_hint_rows(const ScanArgs& a, uint32_t p, ui
             passed += reach ? 1u : 0u;
         }
         full_rows += reach ? 1u : 0u;
-        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
+        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)STREAM_EXTRA;
         if (reach) {
             // only the lanes that hold such an item read the rest of their items' data (the memory system fetches
             // the cache lines they touch, not the row) and score; an item whose bound is below the threshold cannot
@@ -566,7 +566,7 @@ __device__ __forceinline__ void prog_hint_rows(const ScanArgs& a, uint32_t p, ui
             fill = score_and_stage<W, P, PQ, true, MODE>(cur, q0, tau0, taus0, 0, p, wave, lane, s_keys, ms, fill, a);
             ++full_rows;
             extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item beyond the stream's
-            if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
+            if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)STREAM_EXTRA;
             if (!has_next) break;
             cur = nxt;
             p = pn;
@@ -585,7 +585,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
     const int wave = threadIdx.x >> 6;
     const uint32_t p = a.p_begin + blockIdx.x;
     if (p >= a.p_end) return;
-    prog_hint_rows<W, P, PQ, false>(a, p, 0u, 0u, 0u, s_keys_all[wave], wave, lane);
+    prog_hint_rows<W, P, PQ, 0>(a, p, 0u, 0u, 0u, s_keys_all[wave], wave, lane);
 }
 
 // scan_exact_prog_hint in two stages (P >= 3): the stream carries plane 0 and the one-byte scale copies only
@@ -601,10 +601,15 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog_hint(const ScanArgs a)
 // is appended is still exactly what scan_exact appends.  A wave of whose items more than one in 16 pass stage A
 // gives the first stage up and takes the rest of its rows as scan_exact_prog_hint does (which has its own
 // fallback to whole rows).
-template <int W, int P, int PQ>
+// A: planes in the stream (written above for A = 1).  With three planes the sign plane and the two other scale
+// copies rule out 98 of 100 items; with four, what three residual planes could still add lets one item in ten
+// through, and the first stage is formed from planes 0 and 1 (A = 2: 16W + 4 bytes per item instead of 24W + 3,
+// next to no item passes), stage B reads plane 2.
+template <int W, int P, int PQ, int A = 1>
 __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a)
 {
     static_assert(P >= 3, "with two planes scan_exact_prog_hint streams plane 0 alone already");
+    static_assert(A >= 1 && A <= P - 2, "stage B reads planes A .. P-2");
     constexpr int MODE = kModeScaled;
     constexpr int S = P, F = P - 1;
     constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
@@ -641,7 +646,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
     floor_c *= 1.0001f * mass.x;
     const float mass_last = mass.x + 2.0f * mass.y;
     const float mass_hint = mass_last + slack_all;      // what a plane whose scale is known by its copy can add, per unit of the copy
-    const float floor_0 = 1.0001f * __uint_as_float((uint32_t)a.hint_base[0] << 23);
+    float floor_j[A];      // (the smallest copy of each streamed plane's array)
+#pragma unroll
+    for (int j = 0; j < A; ++j) floor_j[j] = 1.0001f * __uint_as_float((uint32_t)a.hint_base[j] << 23);
     const uint32_t hb_last = (uint32_t)a.hint_base_last << 5;
 
     struct Hints { uint32_t w[NW]; uint32_t last; };
@@ -671,9 +678,11 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
         RowRegs<W, P, S> it;          // this lane's item, in slot 0
         bool pass2 = false;
         if (act) {
-            float all = decode(hbytes & 255u, 0);
+            float all = 0.0f;
 #pragma unroll
-            for (int j = 1; j < F; ++j) {
+            for (int j = 0; j < A; ++j) all += decode((hbytes >> (8 * j)) & 255u, j);
+#pragma unroll
+            for (int j = A; j < F; ++j) {
                 const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
                 if constexpr (W == 1) {
                     const u32x2 v = *reinterpret_cast<const u32x2*>(kw);
@@ -701,16 +710,16 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
             const float ub = __fmaf_rn(all, slack_all, __fmaf_rn(h_last, mass_hint, s));
             pass2 = !(ub < taus0);
         }
-        extra8 += n * (uint32_t)W * (uint32_t)(F - 1);
+        extra8 += n * (uint32_t)W * (uint32_t)(F - A);
         const uint64_t m2 = __ballot(pass2);
         if (m2) {
             float score = -__builtin_inff();
             uint64_t logical = 0;
             if (pass2) {
-                // the rest of the item: plane 0 again (another lane streamed it), the last plane, the fp32 scales
+                // the rest of the item: the streamed planes again (another lane had them), the last plane, the fp32 scales
 #pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int j = jj == 0 ? 0 : P - 1;
+                for (int jj = 0; jj <= A; ++jj) {
+                    const int j = jj < A ? jj : P - 1;
                     const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
 #pragma unroll
                     for (int h = 0; h < 2 * W; ++h) it.w[j][0][h] = kw[h];
@@ -726,7 +735,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
             if (ok) { key = make_key(score, (uint32_t)logical); ok = key >= tau0; }
             fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
             const uint32_t n2 = (uint32_t)__builtin_popcountll(m2);
-            extra8 += n2 * (2u * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
+            extra8 += n2 * ((uint32_t)(A + 1) * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
             // rows that hold such an item: entries leave the queue in the order of their rows, so an item opens a
             // new row if the nearest lower lane with such an item (or, for the lowest, the last batch) holds another one
             const uint64_t below = m2 & ((1ull << lane) - 1ull);
@@ -740,7 +749,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
 
     RowRegs<W, P, S> cur, nxt;
     Hints hc, hn;
-    load_row_planes<W, P, S, 0, 1>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_row_planes<W, P, S, 0, A>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
     load_hints(hc, p);
     bool give_up = false;
     for (;;) {
@@ -748,38 +757,44 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
         const uint32_t pl = has_next ? pn : p;          // (unconditional prefetch: see scan_exact_prog_hint)
-        load_row_planes<W, P, S, 0, 1>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_row_planes<W, P, S, 0, A>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
         load_hints(hn, pl);
 #pragma unroll
         for (int m = 0; m < kItemsPerLane; ++m) {
-            float t = q0.bias;
-#pragma unroll
-            for (int i = 0; i < PQ; ++i) {
-                uint32_t pc = 0;
-#pragma unroll
-                for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[0][m][h] ^ q0.w[i][h]);
-                t = __fmaf_rn(q0.m2c[i], (float)pc, t);
-            }
             uint32_t hbytes = 0;
             float rest = 0.0f;
 #pragma unroll
             for (int j = 0; j < F; ++j) {
                 const uint32_t c = (hc.w[j] >> (8 * m)) & 255u;
                 hbytes |= c << (8 * j);
-                if (j >= 1) rest += decode(c, j);
+                if (j >= A) rest += decode(c, j);
             }
-            const float h0 = decode(hbytes & 255u, 0);
             const float h_last = __uint_as_float((((hc.last >> (8 * m)) & 255u) + hb_last) << 18);
-            const float s0 = __fmaf_rn(h0, t, floor_c);         // (where stage B takes the chain up)
-            // a_0 t_0 <= h_0 t_0 + (0.015875 h_0 + floor_0) |t_0|: the copy is within 2^-6 of the scale, or, for a
-            // scale below the smallest copy, above it by less than that copy (floor_0); t_0 is known here, so its
-            // own size stands where scan_exact_prog_hint has the query's mass.  Every other plane adds at most
-            // (its copy) x (mass + slack): |t_j| <= mass_last, and a copy that is not within 2^-6 of its scale is
+            float s0 = floor_c;          // the chain of scan_exact_prog_hint's bound after the streamed planes (stage B takes it up)
+            float seen = 0.0f;           // what the streamed planes add to this stage's bound
+            float h_seen = 0.0f;         // their scale copies, added up
+#pragma unroll
+            for (int j = 0; j < A; ++j) {
+                float t = q0.bias;
+#pragma unroll
+                for (int i = 0; i < PQ; ++i) {
+                    uint32_t pc = 0;
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[j][m][h] ^ q0.w[i][h]);
+                    t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                }
+                const float hj = decode((hbytes >> (8 * j)) & 255u, j);
+                s0 = __fmaf_rn(hj, t, s0);
+                seen = __fmaf_rn(__builtin_fabsf(t), __fmaf_rn(0.015875f, hj, floor_j[j]), __fmaf_rn(hj, t, seen));
+                h_seen += hj;
+            }
+            // For a streamed plane, a_j t_j <= h_j t_j + (0.015875 h_j + floor_j) |t_j|: the copy is within 2^-6 of the
+            // scale, or, for a scale below the smallest copy, above it by less than that copy (floor_j); t_j is known
+            // here, so its own size stands where scan_exact_prog_hint has the query's mass.  Every other plane adds at
+            // most (its copy) x (mass + slack): |t_j| <= mass_last, and a copy that is not within 2^-6 of its scale is
             // above it.  The roundings of this line and of the chains it stands for are inside 2 mass.y per unit
             // of the scale sum, as there.
-            const float at = __builtin_fabsf(t);
-            const float ub = __fmaf_rn(rest + h_last, mass_hint,
-                                       __fmaf_rn(at, __fmaf_rn(0.015875f, h0, floor_0), __fmaf_rn(h0, t, 2.0f * mass.y * h0)));
+            const float ub = __fmaf_rn(rest + h_last, mass_hint, __fmaf_rn(2.0f * mass.y, h_seen, seen));
             const bool pass = !(ub < taus0);            // (a NaN bound does not prune)
             const uint64_t mk = __ballot(pass);
             if (mk) {
@@ -813,7 +828,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
     }
     if (qfill) follow_up(0, qfill);
     if (give_up) {
-        prog_hint_rows<W, P, PQ, true>(a, p, fill, full_rows, extra8, s_keys, wave, lane);
+        prog_hint_rows<W, P, PQ, P - 1 - A>(a, p, fill, full_rows, extra8, s_keys, wave, lane);
         return;
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
@@ -2050,12 +2065,12 @@ ScanFn prog_fn_m(int mode, bool single, bool hints, bool two_stage)
     if constexpr (P >= 2) {
         if (mode == kModeScaled) {
             if (!single) {
-                if constexpr (P >= 3)
+                if constexpr (P == 3)
                     if (hints && two_stage) return scan_exact_batch_prog2_hint<W, P, PQ>;
                 return hints ? scan_exact_batch_prog_hint<W, P, PQ> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
             }
             if constexpr (P >= 3) {
-                if (hints && two_stage) return scan_exact_prog2_hint<W, P, PQ>;
+                if (hints && two_stage) return scan_exact_prog2_hint<W, P, PQ, (P >= 4 ? 2 : 1)>;
             }
             return hints ? scan_exact_prog_hint<W, P, PQ> : scan_exact_prog<W, P, PQ, kModeScaled>;
         }
@@ -2147,7 +2162,7 @@ FqFn fq_prog_fn_m(int mode, bool hints, bool binary_bound, bool two_stage)
     if constexpr (P >= 2) {
         if (mode == kModeScaled) {
             if (!hints) return scan_exact_fq_prog<W, P, kModeScaled>;
-            if constexpr (P >= 3) {
+            if constexpr (P == 3) {       // (four planes: plane 0 alone rules out too little, see scan_exact_prog2_hint)
                 if (binary_bound && two_stage) return scan_exact_fq_prog2_hint<W, P>;
             }
             return binary_bound ? scan_exact_fq_prog_hint<W, P, true> : scan_exact_fq_prog_hint<W, P, false>;
