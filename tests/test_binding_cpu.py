@@ -669,16 +669,17 @@ def _scale_copy_codec(a):
     return ((code + (base << 5)) << 18).astype(np.uint32).view(np.float32).astype(np.float64), base
 
 
-def test_first_stage_bound_of_the_two_stage_scan_is_an_upper_bound(lib):
-    """Host-side evaluation, in float64, of the bound the two-stage one-query scan forms from plane 0 and the
-    one-byte scale copies:
-        bound(z) = h_0 t_0 + (e h_0 + 2^(base_0 - 127)) |t_0| + (1 + e) M sum_{j>=1} h_j,   e = 0.015875,
-    h_j the decoded copies, t_0 = qhat . rho_0, M the library's query mass.  It is never below the oracle's score:
+@pytest.mark.parametrize("P,A", [(3, 1), (4, 2)])
+def test_first_stage_bound_of_the_two_stage_scan_is_an_upper_bound(lib, P, A):
+    """Host-side evaluation, in float64, of the bound the two-stage one-query scan forms from the planes of its
+    stream (plane 0 with three planes, planes 0 and 1 with four) and the one-byte scale copies:
+        bound(z) = sum_{j<A} [h_j t_j + (e h_j + 2^(base_j - 127)) |t_j|] + (1 + e) M sum_{j>=A} h_j,   e = 0.015875,
+    h_j the decoded copies, t_j = qhat . rho_j, M the library's query mass.  It is never below the oracle's score:
     on random items with scales spread over many binades (zeros and values far below the smallest code included),
-    and on the items that attain it -- every residual plane the sign pattern of qhat.  And it is not slack by
-    more than the copies' precision on those."""
-    rng = np.random.default_rng(123)
-    d, P, Pq, N = 64, 3, 3, 4000
+    and on the items that attain it -- every plane outside the stream the sign pattern of qhat.  And it is not
+    slack by more than the copies' precision on those."""
+    rng = np.random.default_rng(123 + P)
+    d, Pq, N = 64, 3, 4000
     planes = rng.integers(0, 2**64, size=(P, N, 1), dtype=np.uint64)
     scales = (rng.uniform(0.0, 1.0, size=(P, N)) * 10.0 ** rng.uniform(-12, 0, size=(P, N))).astype(np.float32)
     scales[:, :50] = 0.0
@@ -692,17 +693,20 @@ def test_first_stage_bound_of_the_two_stage_scan_is_an_upper_bound(lib):
     for i in range(d):
         if qhat[i] > 0:
             best |= np.uint64(1) << np.uint64(i)
-    planes[1:, 100:600, 0] = best                      # residual planes that attain +M each
+    planes[A:, 100:600, 0] = best                      # planes outside the stream that attain +M each
     scales[:, 100:600] = rng.uniform(0.05, 1.0, size=(P, 500)).astype(np.float32)
 
     def bound(planes, scales):
         e = 0.015875
         copies = [_scale_copy_codec(scales[j]) for j in range(P)]
-        bits0 = ((planes[0, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64).reshape(-1, d)
-        t0 = (2 * bits0 - 1) @ qhat
         h = [c[0] for c in copies]
-        floor0 = 2.0 ** (copies[0][1] - 127)          # a scale of array 0 below its smallest copy is above it by less than this
-        return h[0] * t0 + (e * h[0] + floor0) * np.abs(t0) + (1 + e) * M * sum(h[1:]), h, [c[1] for c in copies]
+        out = (1 + e) * M * sum(h[A:])
+        for j in range(A):
+            bits = ((planes[j, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64).reshape(-1, d)
+            t = (2 * bits - 1) @ qhat
+            floor_j = 2.0 ** (copies[j][1] - 127)     # a scale of array j below its smallest copy is above it by less than this
+            out = out + h[j] * t + (e * h[j] + floor_j) * np.abs(t)
+        return out, h, [c[1] for c in copies]
 
     true = oracle.scores(planes, scales, qp, qs)
     b, h, bases = bound(planes, scales)
@@ -717,7 +721,7 @@ def test_first_stage_bound_of_the_two_stage_scan_is_an_upper_bound(lib):
     sel = np.arange(100, 600)
     sel = sel[(scales[:, sel] > 1e-3).all(axis=0)]
     assert sel.size > 20
-    assert np.all(b[sel] - true[sel] <= 0.035 * scales[:, sel].astype(np.float64).sum(axis=0) * M + 2.0 ** (bases[0] - 127) * M)
+    assert np.all(b[sel] - true[sel] <= 0.035 * scales[:, sel].astype(np.float64).sum(axis=0) * M + sum(2.0 ** (bases[j] - 127) for j in range(A)) * M)
 
 
 @pytest.mark.parametrize("dim,Pq", [(64, 1), (64, 3), (128, 4)])
