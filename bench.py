@@ -557,7 +557,7 @@ def main():
 
     if args.batch > 0 and want("batch"):
         B = args.batch
-        bw = 8
+        bw = 16      # (the first dozen batch calls after the one-query legs run up to 15 % slower: the clock settles)
         qpb, qsb = make_queries(rbe, rbe_synth, torch, centres, (bw + args.batch_steps) * B, args.sigma, P, 1)
         rb = timed_searches(rbe, torch, ix, qpb, qsb, B, k, args.batch_steps, bw)
         b_ms = rb["wall_s"] * 1e3 / args.batch_steps
@@ -785,8 +785,8 @@ def extra_legs(out, args, want, rbe, rbe_synth, torch, np):
             f"near-lossless {rpn['wall_s'] * 1e3 / args.steps:.3f} ms/step, recall {np.mean(rec):.5f}")
         if args.batch >= 7:
             B = args.batch
-            qpb, _ = make_queries(rbe, rbe_synth, torch, centres_p, (8 + args.batch_steps) * B, args.sigma, Pq, 3)
-            rpb = timed_searches(rbe, torch, ixp, qpb, None, B, k, args.batch_steps, 8)
+            qpb, _ = make_queries(rbe, rbe_synth, torch, centres_p, (16 + args.batch_steps) * B, args.sigma, Pq, 3)
+            rpb = timed_searches(rbe, torch, ixp, qpb, None, B, k, args.batch_steps, 16)
             pb_scan = float(rpb["scan_ms"].mean())
             pb_items = rpb["last_items"]
             pb_ms = rpb["wall_s"] * 1e3 / args.batch_steps
@@ -823,7 +823,7 @@ def config_leg(rbe, rbe_synth, torch, np, args, *, N, d, P, clusters, sigma, Q, 
     ix, centres, _, _ = build_corpus(rbe, rbe_synth, torch, N, d, P, clusters, sigma, args.chunk_items, 0)
     rbe.rbe_set_profiling(ix, True)
     settle(rbe, rbe_synth, torch, ix, centres, sigma, P, k, args.settle_seconds)
-    steps, warm = args.config_steps, 8
+    steps, warm = args.config_steps, 16
     qp, qs = make_queries(rbe, rbe_synth, torch, centres, (warm + steps) * Q, sigma, P, seed_chunk)
     r = timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warm)
     ms = r["wall_s"] * 1e3 / steps
