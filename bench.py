@@ -593,7 +593,7 @@ def main():
                             "plane of most pairs, so this figure can exceed the modelled peak",
                     "hbm_gbs": b_items * bytes_per_item / (b_scan * 1e-3) / 1e9}
         out["batch"] = {
-            "queries_per_step": B, "steps": args.batch_steps, "ms_per_step": b_ms,
+            "queries_per_step": B, "steps": args.batch_steps, "warmup": bw, "ms_per_step": b_ms,
             "p50_ms": float(np.percentile(rb["per_step_ms"], 50)),
             "value": N * B * args.batch_steps / rb["wall_s"], "unit": "candidates/s",
             "dtype": "i8 x i8 -> i32 filter, u64 xor/popcount + f32 scores" if matrix_cores else "u64 xor/popcount + f32",
