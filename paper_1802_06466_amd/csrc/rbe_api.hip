@@ -1392,9 +1392,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         // (several queries: the scan that streams the scale copies is ahead up to four queries per call, 4.3 against
         // 5.2 ms for two, level with the one that streams the fp32 scales at five, behind from six on)
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2 && c.Q <= 4;
-        // (plane 0 alone in the stream pays with three planes; with four, one item in ten passes its bound, and
-        // only the one-query scan has the form with planes 0 and 1 in the stream)
-        sel.two_stage = ix->progressive == 1 && ix->d_hints_last != nullptr && (ix->P == 3 ? c.Q <= 4 : (ix->P >= 4 && c.Q == 1));
+        sel.two_stage = ix->progressive == 1 && c.Q <= 4 && ix->P >= 3 && ix->d_hints_last != nullptr;
         sa.deep_rows = ix->ws.status + 1 + level_slot; sa.row_amax = ix->d_row_amax; sa.hints = ix->d_hints; sa.deep_units = ix->ws.status + 14;
         sa.deep_pairs = level_slot >= c.look_from ? ix->ws.status + 9 : nullptr;
         for (int j = 0; j < 3; ++j) sa.hint_base[j] = ix->hint_base[j];

@@ -844,7 +844,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_prog2_hint(const ScanArgs a
 // is in the small batches that are still bound by memory.
 // The rows of a wave from tile p on, with what the wave has counted so far (see prog_hint_rows): the whole of
 // scan_exact_batch_prog_hint, and what scan_exact_batch_prog2_hint falls back to.
-template <int W, int P, int PQ, bool STREAM_EXTRA>
+template <int W, int P, int PQ, int STREAM_EXTRA>
 __device__ __forceinline__ void batch_prog_hint_rows(const ScanArgs& a, uint32_t p, uint32_t full_rows, uint32_t full_pairs, uint32_t extra8,
                                                      uint64_t* s_keys, const MultiStage& ms, const QuerySlot<W, PQ>* slots,
                                                      int wave, int lane)
@@ -953,7 +953,7 @@ __device__ __forceinline__ void batch_prog_hint_rows(const ScanArgs& a, uint32_t
         }
         ++rows;
         full_rows += reach ? 1u : 0u;
-        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
+        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)STREAM_EXTRA;       // (planes that the caller's stream left out)
         if (reach) {
             full_pairs += row_pairs;
             // only the lanes that hold such an item read the rest of their items' data (the memory system fetches
@@ -1050,7 +1050,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanA
     __builtin_amdgcn_wave_barrier();
     const uint32_t p = a.p_begin + blockIdx.x;
     if (p >= a.p_end) return;
-    batch_prog_hint_rows<W, P, PQ, false>(a, p, 0u, 0u, 0u, s_keys, ms, s_query, wave, lane);
+    batch_prog_hint_rows<W, P, PQ, 0>(a, p, 0u, 0u, 0u, s_keys, ms, s_query, wave, lane);
 }
 
 
@@ -1060,11 +1060,13 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog_hint(const ScanA
 // still want it.  Stage B reads the item's planes 1 .. P-2 once and continues the chains of those queries; stage C
 // reads the rest once and scores the item from scratch for each query whose second bound it passed.  What is
 // appended is what the batch form of scan_exact appends.  A wave of whose items more than one in 10 pass stage A
-// takes the rest of its rows as scan_exact_batch_prog_hint does.
-template <int W, int P, int PQ>
+// takes the rest of its rows as scan_exact_batch_prog_hint does.  A: planes in the stream, as there (1 with three
+// planes, 2 with four).
+template <int W, int P, int PQ, int A = 1>
 __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const ScanArgs a)
 {
     static_assert(P >= 3, "with two planes scan_exact_batch_prog_hint streams plane 0 alone already");
+    static_assert(A >= 1 && A <= P - 2, "stage B reads planes A .. P-2");
     constexpr int MODE = kModeScaled;
     constexpr int S = P, F = P - 1;
     constexpr int NW = S - 1 == 3 ? 4 : S - 1;   // hint words per lane and row (one byte per item and array)
@@ -1073,7 +1075,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
     extern __shared__ __align__(16) unsigned char s_dynamic[];
     __shared__ uint32_t s_cnt_all[kWavesPerBlock][65];
     __shared__ uint32_t s_qid[kWavesPerBlock][kQueue];      // physical tile * 1024 + item of the tile
-    __shared__ float s_qs0[kWavesPerBlock][QB][kQueue];     // per query: floor + h_0 t_0
+    __shared__ float s_qs0[kWavesPerBlock][QB][kQueue];     // per query: where the bound's chain stands after the streamed planes
     __shared__ uint32_t s_qhb[kWavesPerBlock][kQueue];      // scale copies of arrays 0 .. P-2 in bytes 0 .. P-2, the queries that want the item in byte 3
     __shared__ float s_qam[kWavesPerBlock][kQueue];         // the copy of the item's last scale
     __shared__ QuerySlot<W, PQ> s_query[QB];
@@ -1106,7 +1108,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
     float floor_all = __uint_as_float((uint32_t)a.hint_base_last << 23);
     for (int j = 0; j < F; ++j) floor_all += __uint_as_float((uint32_t)a.hint_base[j] << 23);
     floor_all *= 1.0001f;
-    const float floor_0 = 1.0001f * __uint_as_float((uint32_t)a.hint_base[0] << 23);
+    float floor_j[A];      // (the smallest copy of each streamed plane's array)
+#pragma unroll
+    for (int j = 0; j < A; ++j) floor_j[j] = 1.0001f * __uint_as_float((uint32_t)a.hint_base[j] << 23);
     const uint32_t hb_last = (uint32_t)a.hint_base_last << 5;
 
     struct Hints { uint32_t w[NW]; uint32_t last; };
@@ -1134,11 +1138,13 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
         const uint32_t tp = id >> 10, idx = id & 1023u;
         const char* tile = a.tiles + (size_t)tp * tile_bytes;
         RowRegs<W, P, S> it;          // this lane's item, in slot 0
-        float all = decode(hbytes & 255u, 0);
+        float all = 0.0f;
+#pragma unroll
+        for (int j = 0; j < A; ++j) all += decode((hbytes >> (8 * j)) & 255u, j);
         float hj[F];
         if (act) {
 #pragma unroll
-            for (int j = 1; j < F; ++j) {
+            for (int j = A; j < F; ++j) {
                 const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
                 if constexpr (W == 1) {
                     const u32x2 v = *reinterpret_cast<const u32x2*>(kw);
@@ -1154,7 +1160,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
                 all += hj[j];
             }
         }
-        extra8 += n * (uint32_t)W * (uint32_t)(F - 1);
+        extra8 += n * (uint32_t)W * (uint32_t)(F - A);
         uint32_t want2 = 0;           // queries whose second bound it passed too
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
@@ -1167,7 +1173,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
             if ((want >> q) & 1u) {
                 float s = s_qs0[wave][q][e];
 #pragma unroll
-                for (int j = 1; j < F; ++j) {
+                for (int j = A; j < F; ++j) {
                     float t = q0.bias;
 #pragma unroll
                     for (int i = 0; i < PQ; ++i) {
@@ -1187,10 +1193,10 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
         if (m2) {
             uint64_t logical = 0;
             if (want2) {
-                // the rest of the item: plane 0 again (another lane streamed it), the last plane, the fp32 scales
+                // the rest of the item: the streamed planes again (another lane had them), the last plane, the fp32 scales
 #pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int j = jj == 0 ? 0 : P - 1;
+                for (int jj = 0; jj <= A; ++jj) {
+                    const int j = jj < A ? jj : P - 1;
                     const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
 #pragma unroll
                     for (int h = 0; h < 2 * W; ++h) it.w[j][0][h] = kw[h];
@@ -1216,7 +1222,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
                 full_pairs += (uint32_t)__builtin_popcountll(__ballot(mine));
             }
             const uint32_t n2 = (uint32_t)__builtin_popcountll(m2);
-            extra8 += n2 * (2u * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
+            extra8 += n2 * ((uint32_t)(A + 1) * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
             // rows that hold such an item (see scan_exact_prog2_hint)
             const uint64_t below = m2 & ((1ull << lane) - 1ull);
             const int prev = below ? 63 - __builtin_clzll(below) : lane;
@@ -1229,7 +1235,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
 
     RowRegs<W, P, S> cur, nxt;
     Hints hc, hn;
-    load_row_planes<W, P, S, 0, 1>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_row_planes<W, P, S, 0, A>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
     load_hints(hc, p);
     // The thresholds a row is judged by are asked for while the row BEFORE it is judged, along with that row's
     // prefetch: loads return in order, so waiting for a threshold asked for after the prefetch would wait for all of
@@ -1243,24 +1249,25 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
         const uint32_t pl = has_next ? pn : p;          // (unconditional prefetch: see scan_exact_prog_hint)
-        load_row_planes<W, P, S, 0, 1>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_row_planes<W, P, S, 0, A>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
         load_hints(hn, pl);
 #pragma unroll
         for (int q = 0; q < QB; ++q) tau_n[q] = a.tau[(uint32_t)q < nq ? q : 0];
         // what does not depend on the query
         uint32_t hbytes[kItemsPerLane];
-        float h0[kItemsPerLane], h_last[kItemsPerLane], others[kItemsPerLane];
+        float hs[kItemsPerLane][A], h_seen[kItemsPerLane], h_last[kItemsPerLane], others[kItemsPerLane];
 #pragma unroll
         for (int m = 0; m < kItemsPerLane; ++m) {
             hbytes[m] = 0;
             float rest = 0.0f;
+            h_seen[m] = 0.0f;
 #pragma unroll
             for (int j = 0; j < F; ++j) {
                 const uint32_t c = (hc.w[j] >> (8 * m)) & 255u;
                 hbytes[m] |= c << (8 * j);
-                if (j >= 1) rest += decode(c, j);
+                if (j >= A) rest += decode(c, j);
+                else { hs[m][j] = decode(c, j); h_seen[m] += hs[m][j]; }
             }
-            h0[m] = decode(hbytes[m] & 255u, 0);
             h_last[m] = __uint_as_float((((hc.last >> (8 * m)) & 255u) + hb_last) << 18);
             others[m] = rest + h_last[m];
         }
@@ -1283,19 +1290,24 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
             const float floor_c = floor_all * mass.x;
 #pragma unroll
             for (int m = 0; m < kItemsPerLane; ++m) {
-                float t = q0.bias;
+                float chain = floor_c;       // (where stage B takes the chain up)
+                float seen = 0.0f;
 #pragma unroll
-                for (int i = 0; i < PQ; ++i) {
-                    uint32_t pc = 0;
+                for (int j = 0; j < A; ++j) {
+                    float t = q0.bias;
 #pragma unroll
-                    for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[0][m][h] ^ q0.w[i][h]);
-                    t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                    for (int i = 0; i < PQ; ++i) {
+                        uint32_t pc = 0;
+#pragma unroll
+                        for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[j][m][h] ^ q0.w[i][h]);
+                        t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                    }
+                    chain = __fmaf_rn(hs[m][j], t, chain);
+                    seen = __fmaf_rn(__builtin_fabsf(t), __fmaf_rn(0.015875f, hs[m][j], floor_j[j]), __fmaf_rn(hs[m][j], t, seen));
                 }
-                s0[m][q] = __fmaf_rn(h0[m], t, floor_c);      // (where stage B takes the chain up)
+                s0[m][q] = chain;
                 // (the first bound of scan_exact_prog2_hint)
-                const float at = __builtin_fabsf(t);
-                const float ub = __fmaf_rn(others[m], mass_hint,
-                                           __fmaf_rn(at, __fmaf_rn(0.015875f, h0[m], floor_0), __fmaf_rn(h0[m], t, 2.0f * mass.y * h0[m])));
+                const float ub = __fmaf_rn(others[m], mass_hint, __fmaf_rn(2.0f * mass.y, h_seen[m], seen));
                 want[m] |= !(ub < taus) ? (1u << q) : 0u;     // (a NaN bound does not prune)
             }
         }
@@ -1344,7 +1356,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_batch_prog2_hint(const Scan
     }
     if (qfill) follow_up(0, qfill);
     if (give_up) {
-        batch_prog_hint_rows<W, P, PQ, true>(a, p, full_rows, full_pairs, extra8, s_keys, ms, s_query, wave, lane);
+        batch_prog_hint_rows<W, P, PQ, P - 1 - A>(a, p, full_rows, full_pairs, extra8, s_keys, ms, s_query, wave, lane);
         return;
     }
     mstage_drain(ms, a.out, lane);
@@ -2065,8 +2077,8 @@ ScanFn prog_fn_m(int mode, bool single, bool hints, bool two_stage)
     if constexpr (P >= 2) {
         if (mode == kModeScaled) {
             if (!single) {
-                if constexpr (P == 3)
-                    if (hints && two_stage) return scan_exact_batch_prog2_hint<W, P, PQ>;
+                if constexpr (P >= 3)
+                    if (hints && two_stage) return scan_exact_batch_prog2_hint<W, P, PQ, (P >= 4 ? 2 : 1)>;
                 return hints ? scan_exact_batch_prog_hint<W, P, PQ> : scan_exact_batch_prog<W, P, PQ, kModeScaled>;
             }
             if constexpr (P >= 3) {

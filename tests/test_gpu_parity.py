@@ -1256,7 +1256,7 @@ def test_progressive_scan_for_small_batches(d, P, Pq, flags):
             res[prog] = rbe.rbe_search(ix, qp[:Q], None if qs is None else qs[:Q], k)
             st = rbe.rbe_get_search_stats(ix)
             assert (st["deep_rows"] > 0) == (prog != 0)
-            if prog == 1 and flags == 0 and P == 3 and Q <= 4:
+            if prog == 1 and flags == 0 and P >= 3 and Q <= 4:
                 assert st["scan_kernel"][st["n_levels"] - 1] == "scan_exact_prog2_hint"
         for prog in (1, 3):
             np.testing.assert_array_equal(res[prog][0], res[0][0])
