@@ -1340,7 +1340,7 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         e = hipSuccess;
         sel.progressive = !dense && ix->P >= 2 && ix->progressive != 0 && can_prune(ix);
         sel.hints = ix->d_hints != nullptr && ix->progressive != 2;
-        sel.two_stage = ix->progressive == 1 && ix->P == 3 && ix->d_hints_last != nullptr && ix->fq_binary;     // (four planes: see below)
+        sel.two_stage = ix->progressive == 1 && ix->P >= 3 && ix->d_hints_last != nullptr && ix->fq_binary;
         const size_t per_q = (size_t)8 * ix->W * 256;
         for (uint32_t q = 0; q < c.Q && e == hipSuccess; ++q) {   // one pass over the range per query
             FqArgs fa;

@@ -1568,7 +1568,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog(const FqArgs a)
 // R per unit of the scale sum, about 6 % of the query's mass against the 25 % that the left-out plane costs anyway.
 // The rows of a wave from tile p on, with what the wave has queued and counted so far (see prog_hint_rows): the whole
 // of scan_exact_fq_prog_hint, and what scan_exact_fq_prog2_hint falls back to.
-template <int W, int P, bool BIN, bool STREAM_EXTRA>
+template <int W, int P, bool BIN, int STREAM_EXTRA>
 __device__ __forceinline__ void fq_prog_hint_rows(const FqArgs& a, uint32_t p, uint32_t fill, uint32_t full_rows, uint32_t extra8,
                                                   uint64_t* s_keys, const float (&s_lut)[8 * W][256], int wave, int lane)
 {
@@ -1698,7 +1698,7 @@ __device__ __forceinline__ void fq_prog_hint_rows(const FqArgs& a, uint32_t p, u
             passed += reach ? 1u : 0u;
         }
         full_rows += reach ? 1u : 0u;
-        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
+        if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)STREAM_EXTRA;
         if (reach) {
             {
                 // lane-wise, as in scan_exact_prog_hint
@@ -1760,7 +1760,7 @@ __device__ __forceinline__ void fq_prog_hint_rows(const FqArgs& a, uint32_t p, u
             score_row(cur, (1u << kItemsPerLane) - 1u, p);
             ++full_rows;
             extra8 += kRow * (W + S / 2) + (kRow * (S & 1)) / 2;     // 8W + 4S bytes per item beyond the stream's
-            if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)(F - 1);
+            if (STREAM_EXTRA) extra8 += kRow * (uint32_t)W * (uint32_t)STREAM_EXTRA;
             if (!has_next) break;
             cur = nxt;
             p = pn;
@@ -1782,16 +1782,18 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog_hint(const FqArgs a
     __syncthreads();
     const uint32_t p = a.p_begin + blockIdx.x;
     if (p >= a.p_end) return;
-    fq_prog_hint_rows<W, P, BIN, false>(a, p, 0u, 0u, 0u, s_keys_all[wave], s_lut, wave, lane);
+    fq_prog_hint_rows<W, P, BIN, 0>(a, p, 0u, 0u, 0u, s_keys_all[wave], s_lut, wave, lane);
 }
 
 // scan_exact_prog2_hint for an fp32 query (hybrid scoring): the bounds of both stages are formed from the 4-plane
 // binary approximation qhat of the query by XOR/popcounts, as in scan_exact_fq_prog_hint<.., true> (the query's own
 // sums differ from qhat's by at most a.resid per plane); what passes both is scored from the byte tables.
-template <int W, int P>
+// A: planes in the stream (1 with three planes, 2 with four: see scan_exact_prog2_hint).
+template <int W, int P, int A = 1>
 __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs a)
 {
     static_assert(P >= 3, "with two planes scan_exact_fq_prog_hint streams plane 0 alone already");
+    static_assert(A >= 1 && A <= P - 2, "stage B reads planes A .. P-2");
     constexpr int MODE = kModeScaled;
     constexpr int PQ = 4;                        // planes of the query's binary approximation
     constexpr int S = P, F = P - 1;
@@ -1834,7 +1836,9 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs 
     floor_c *= 1.0001f * (a.bmass.x + a.resid + mass.x);
     const float mass_last = mass.x + 2.0f * mass.y;
     const float mass_hint = mass_last + slack_mass;     // what a plane whose scale is known by its copy can add, per unit of the copy
-    const float floor_0 = 1.0001f * __uint_as_float((uint32_t)a.hint_base[0] << 23);
+    float floor_j[A];      // (the smallest copy of each streamed plane's array)
+#pragma unroll
+    for (int j = 0; j < A; ++j) floor_j[j] = 1.0001f * __uint_as_float((uint32_t)a.hint_base[j] << 23);
     const uint32_t hb_last = (uint32_t)a.hint_base_last << 5;
 
     struct Hints { uint32_t w[NW]; uint32_t last; };
@@ -1864,9 +1868,11 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs 
         RowRegs<W, P, S> it;          // this lane's item, in slot 0
         bool pass2 = false;
         if (act) {
-            float all = decode(hbytes & 255u, 0);
+            float all = 0.0f;
 #pragma unroll
-            for (int j = 1; j < F; ++j) {
+            for (int j = 0; j < A; ++j) all += decode((hbytes >> (8 * j)) & 255u, j);
+#pragma unroll
+            for (int j = A; j < F; ++j) {
                 const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
                 if constexpr (W == 1) {
                     const u32x2 v = *reinterpret_cast<const u32x2*>(kw);
@@ -1894,16 +1900,16 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs 
             const float ub = __fmaf_rn(all, slack_all, __fmaf_rn(h_last, mass_hint, s));
             pass2 = !(ub < taus0);
         }
-        extra8 += n * (uint32_t)W * (uint32_t)(F - 1);
+        extra8 += n * (uint32_t)W * (uint32_t)(F - A);
         const uint64_t m2 = __ballot(pass2);
         if (m2) {
             float score = -__builtin_inff();
             uint64_t logical = 0;
             if (pass2) {
-                // the rest of the item: plane 0 again (another lane streamed it), the last plane, the fp32 scales
+                // the rest of the item: the streamed planes again (another lane had them), the last plane, the fp32 scales
 #pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int j = jj == 0 ? 0 : P - 1;
+                for (int jj = 0; jj <= A; ++jj) {
+                    const int j = jj < A ? jj : P - 1;
                     const uint32_t* kw = reinterpret_cast<const uint32_t*>(tile + (size_t)j * geom.plane_bytes() + (size_t)idx * 8 * W);
 #pragma unroll
                     for (int h = 0; h < 2 * W; ++h) it.w[j][0][h] = kw[h];
@@ -1919,7 +1925,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs 
             if (ok) { key = make_key(score, (uint32_t)logical); ok = key >= tau0; }
             fill = stage_append1(ok, key, s_keys, fill, a.out, lane);
             const uint32_t n2 = (uint32_t)__builtin_popcountll(m2);
-            extra8 += n2 * (2u * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
+            extra8 += n2 * ((uint32_t)(A + 1) * W + (uint32_t)S / 2u) + (n2 * ((uint32_t)S & 1u)) / 2u;
             // rows that hold such an item: entries leave the queue in the order of their rows, so an item opens a
             // new row if the nearest lower lane with such an item (or, for the lowest, the last batch) holds another one
             const uint64_t below = m2 & ((1ull << lane) - 1ull);
@@ -1933,7 +1939,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs 
 
     RowRegs<W, P, S> cur, nxt;
     Hints hc, hn;
-    load_row_planes<W, P, S, 0, 1>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
+    load_row_planes<W, P, S, 0, A>(cur, a.tiles + (size_t)p * tile_bytes, wave, lane);
     load_hints(hc, p);
     bool give_up = false;
     for (;;) {
@@ -1941,40 +1947,43 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs 
         const uint32_t pn = p + G;
         const bool has_next = pn < a.p_end;
         const uint32_t pl = has_next ? pn : p;          // (unconditional prefetch: see scan_exact_prog_hint)
-        load_row_planes<W, P, S, 0, 1>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
+        load_row_planes<W, P, S, 0, A>(nxt, a.tiles + (size_t)pl * tile_bytes, wave, lane);
         load_hints(hn, pl);
 #pragma unroll
         for (int m = 0; m < kItemsPerLane; ++m) {
-            float t = q0.bias;
-#pragma unroll
-            for (int i = 0; i < PQ; ++i) {
-                uint32_t pc = 0;
-#pragma unroll
-                for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[0][m][h] ^ q0.w[i][h]);
-                t = __fmaf_rn(q0.m2c[i], (float)pc, t);
-            }
             uint32_t hbytes = 0;
             float rest = 0.0f;
 #pragma unroll
             for (int j = 0; j < F; ++j) {
                 const uint32_t c = (hc.w[j] >> (8 * m)) & 255u;
                 hbytes |= c << (8 * j);
-                if (j >= 1) rest += decode(c, j);
+                if (j >= A) rest += decode(c, j);
             }
-            const float h0 = decode(hbytes & 255u, 0);
             const float h_last = __uint_as_float((((hc.last >> (8 * m)) & 255u) + hb_last) << 18);
-            const float s0 = __fmaf_rn(h0, t, floor_c);         // (where stage B takes the chain up)
-            // a_0 t_0 <= h_0 t_0 + (0.015875 h_0 + floor_0) |t_0|: the copy is within 2^-6 of the scale, or, for a
-            // scale below the smallest copy, above it by less than that copy (floor_0); t_0 is known here, so its
-            // own size stands where scan_exact_prog_hint has the query's mass.  Every other plane adds at most
-            // (its copy) x (mass + slack): |t_j| <= mass_last, and a copy that is not within 2^-6 of its scale is
-            // above it.  The roundings of this line and of the chains it stands for are inside 2 mass.y per unit
-            // of the scale sum, as there.
-            const float at = __builtin_fabsf(t);
-            // (fp32 query: t is qhat's sum; the query's own differs from it by at most a.resid)
+            float s0 = floor_c;          // the chain of the one-stage bound after the streamed planes (stage B takes it up)
+            float seen = 0.0f;           // what the streamed planes add to this stage's bound
+            float h_seen = 0.0f;         // their scale copies, added up
+#pragma unroll
+            for (int j = 0; j < A; ++j) {
+                float t = q0.bias;
+#pragma unroll
+                for (int i = 0; i < PQ; ++i) {
+                    uint32_t pc = 0;
+#pragma unroll
+                    for (int h = 0; h < 2 * W; ++h) pc += __builtin_popcount(cur.w[j][m][h] ^ q0.w[i][h]);
+                    t = __fmaf_rn(q0.m2c[i], (float)pc, t);
+                }
+                const float hj = decode((hbytes >> (8 * j)) & 255u, j);
+                s0 = __fmaf_rn(hj, t, s0);
+                seen = __fmaf_rn(__builtin_fabsf(t), __fmaf_rn(0.015875f, hj, floor_j[j]), __fmaf_rn(hj, t, seen));
+                h_seen += hj;
+            }
+            // The first bound of scan_exact_prog2_hint, plane by plane of the stream: a_j t_j <= h_j t_j +
+            // (0.015875 h_j + floor_j) |t_j|, every other plane at most (its copy) x (mass + slack).  fp32 query: t_j
+            // is qhat's sum; the query's own differs from it by at most a.resid, and the roundings of both sums
+            // are allowed for per unit of the streamed planes' copies.
             const float ub = __fmaf_rn(rest + h_last, mass_hint,
-                                       __fmaf_rn(at, __fmaf_rn(0.015875f, h0, floor_0),
-                                                 __fmaf_rn(h0, t, (2.0f * (mass.y + a.bmass.y) + 1.04f * a.resid) * h0)));
+                                       __fmaf_rn(2.0f * (mass.y + a.bmass.y) + 1.04f * a.resid, h_seen, seen));
             const bool pass = !(ub < taus0);            // (a NaN bound does not prune)
             const uint64_t mk = __ballot(pass);
             if (mk) {
@@ -2008,7 +2017,7 @@ __global__ __launch_bounds__(kBlock) void scan_exact_fq_prog2_hint(const FqArgs 
     }
     if (qfill) follow_up(0, qfill);
     if (give_up) {
-        fq_prog_hint_rows<W, P, true, true>(a, p, fill, full_rows, extra8, s_keys, s_lut, wave, lane);
+        fq_prog_hint_rows<W, P, true, P - 1 - A>(a, p, fill, full_rows, extra8, s_keys, s_lut, wave, lane);
         return;
     }
     if (fill) stage_flush1(s_keys, fill, a.out, lane);
@@ -2174,8 +2183,8 @@ FqFn fq_prog_fn_m(int mode, bool hints, bool binary_bound, bool two_stage)
     if constexpr (P >= 2) {
         if (mode == kModeScaled) {
             if (!hints) return scan_exact_fq_prog<W, P, kModeScaled>;
-            if constexpr (P == 3) {       // (four planes: plane 0 alone rules out too little, see scan_exact_prog2_hint)
-                if (binary_bound && two_stage) return scan_exact_fq_prog2_hint<W, P>;
+            if constexpr (P >= 3) {
+                if (binary_bound && two_stage) return scan_exact_fq_prog2_hint<W, P, (P >= 4 ? 2 : 1)>;
             }
             return binary_bound ? scan_exact_fq_prog_hint<W, P, true> : scan_exact_fq_prog_hint<W, P, false>;
         }
