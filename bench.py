@@ -793,9 +793,9 @@ def extra_legs(out, args, want, rbe, rbe_synth, torch, np):
             pb_ach = 2.0 * B * pb_items * 64 * Pk / (pb_scan * 1e-3) / 1e12
             out["paper_operating_point"]["batch"] = {
                 "queries_per_step": B, "ms_per_step": pb_ms, "value": Np * B / (pb_ms * 1e-3), "unit": "candidates/s",
-                "dtype": "f16 x f16 -> f32 (dyadic queries are exact in one half)",
+                "dtype": "i8 x i8 -> i32 (3 query and 2 keyword planes with dyadic weights are exact in eight-bit integers)",
                 "roofline": {"kernel": "scan_batch_mfma (finest level)", "bound": "mfma", "achieved": pb_ach,
-                             "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": pb_ach / MFMA_F16_PEAK_TFLOPS,
+                             "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s", "frac": pb_ach / MFMA_I8_PEAK_TOPS,
                              "kernel_ms": pb_scan, "traffic": None,
                              "hbm_gbs": pb_items * 20 / (pb_scan * 1e-3) / 1e9},
             }

@@ -32,7 +32,7 @@ int rbe_debug_scores(rbe_index *ix, const uint64_t *q_planes, const float *q_sca
                      uint32_t q_n_planes, uint64_t first_item, uint64_t count,
                      float *out, void *hip_stream);
 
-/* Fewer than 5 queries per call (6 for RBE_DYADIC), exact mode, 2 or more planes:
+/* Calls that do not go to the matrix cores (see rbe_debug_set_batch_path), exact mode, 2 or more planes:
  * the last (largest) level of the search streams every plane but the last (one query: with one-byte
  * copies of their scales and the row's largest last scale in place of the fp32
  * arrays) and reads an item's last plane and fp32 scales only where its upper
@@ -78,10 +78,11 @@ int rbe_debug_query_mass(const uint64_t *q_planes, const float *q_scales, uint32
                          uint32_t dim, uint32_t dyadic, float *mass_out);
 
 /* Which kernel rbe_search uses in exact mode: 0 = automatic (matrix cores from 5
- * queries per call on, 6 for RBE_DYADIC; dim <= 128), 1 = always the
- * XOR/popcount kernel, 2 = the matrix-core kernel for any number of queries
- * (dim <= 128), 3 = as 2, with half operands also where eight-bit integer
- * operands are the default (binary queries on general scales).                 */
+ * queries per call on; RBE_DYADIC: from 4 while the query fits eight-bit
+ * integer operands, 2 (2^q_n_planes - 1) 2^(n_planes - 1) <= 127, else from 6;
+ * dim <= 128), 1 = always the XOR/popcount kernel, 2 = the matrix-core kernel
+ * for any number of queries (dim <= 128), 3 = as 2, with half operands also
+ * where eight-bit integer operands are the default.                            */
 int rbe_debug_set_batch_path(rbe_index *ix, int path);
 
 /* How the near-lossless modes are computed.  0 (default): the scans and the
@@ -162,6 +163,21 @@ int rbe_debug_batch_operands_i8(const uint64_t *q_planes, const float *q_scales,
                                 uint32_t n_queries, uint32_t q_n_planes, uint32_t dim,
                                 int8_t *bytes_out, size_t bytes_capacity, float *unscale_out,
                                 float *start_out, float *mass_out, float *margin_out);
+
+/* The same for a dyadic index (host only): binary queries with the weights 2^-i,
+ * n_item_planes item planes with the weights 2^-j; every number is an exact
+ * integer.  bytes_out [tile = query / 16][item plane j][dim / 64 parts][lane][16],
+ * laid out within a lane as above, holds X_d = 2 T_d 2^(n_item_planes - 1 - j)
+ * (T_d = 2^(q_n_planes - 1) qhat_d, an odd integer) for even t and -X_d / 2 for
+ * odd t; unscale_out [Q] = 2^-(n_item_planes + q_n_planes + 4); start_out [Q] =
+ * the float 1.5 * 2^23 - 32 sum_j sum_d X_d; mass_out [Q] = the most the last
+ * item plane can add to an accumulator that holds the start value already.
+ * EINVAL if 2 (2^q_n_planes - 1) 2^(n_item_planes - 1) exceeds 127 (such queries
+ * keep half operands).                                                          */
+int rbe_debug_batch_operands_i8_dyadic(const uint64_t *q_planes, uint32_t n_queries, uint32_t q_n_planes,
+                                       uint32_t dim, uint32_t n_item_planes, int8_t *bytes_out,
+                                       size_t bytes_capacity, float *unscale_out, float *start_out,
+                                       float *mass_out);
 
 /* Measurement yardstick: enqueues a plain copy kernel ("calib_copy") of `bytes`
  * bytes from src_dev to dst_dev (DEVICE pointers, 16-byte aligned, bytes a

@@ -98,6 +98,7 @@ PROTOTYPES = {
     "rbe_debug_exact_plan": (_i32, [_u64, _u32, _u32, _u32, _vp, _vp, _vp]),
     "rbe_debug_batch_operands": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
     "rbe_debug_batch_operands_i8": (_i32, [_vp, _vp, _vp, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp, _vp]),
+    "rbe_debug_batch_operands_i8_dyadic": (_i32, [_vp, _u32, _u32, _u32, _u32, _vp, ctypes.c_size_t, _vp, _vp, _vp]),
     "rbe_debug_popcounts": (_i32, [_vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_scores": (_i32, [_vp, _vp, _vp, _u32, _u64, _u64, _vp, _vp]),
     "rbe_debug_read_scales": (_i32, [_vp, _u64, _u64, _vp, _vp]),
@@ -496,6 +497,20 @@ def rbe_debug_batch_operands_i8(q_planes, q_scales, dim: int, q_float=None):
         None if q_float is None else q_float.ctypes.data, Q, Pq, dim, ops.ctypes.data, ops.nbytes,
         unscale.ctypes.data, start.ctypes.data, mass.ctypes.data, margin.ctypes.data))
     return ops, unscale, start, mass, float(margin[0])
+
+
+def rbe_debug_batch_operands_i8_dyadic(q_planes, dim: int, n_item_planes: int):
+    """Eight-bit integer query operands of the matrix-core batch scan on a dyadic index (host only): int8
+    [tile][item plane][part][lane][16], unscale [Q], start [Q], mass [Q]."""
+    q_planes = np.ascontiguousarray(q_planes, dtype=np.uint64)
+    Q, Pq = q_planes.shape[0], q_planes.shape[1]
+    tiles, parts = (Q + 15) // 16, dim // 64
+    ops = np.zeros((tiles, n_item_planes, parts, 64, 16), dtype=np.int8)
+    unscale, start, mass = (np.zeros(Q, dtype=np.float32) for _ in range(3))
+    _check(load_library().rbe_debug_batch_operands_i8_dyadic(
+        q_planes.ctypes.data, Q, Pq, dim, n_item_planes, ops.ctypes.data, ops.nbytes,
+        unscale.ctypes.data, start.ctypes.data, mass.ctypes.data))
+    return ops, unscale, start, mass
 
 
 def rbe_debug_query_mass(q_planes, q_scales, dim: int, dyadic: bool = False):

@@ -499,9 +499,9 @@ uint32_t batch_rescore(const rbe_index* ix, bool float_query)
 // negative scale is searched by the plain scans alone.
 bool can_prune(const rbe_index* ix) { return ix->nonneg; }
 
-bool batch_operand_i8(const rbe_index* ix, bool float_query);
+bool batch_operand_i8(const rbe_index* ix, bool float_query, uint32_t q_n_planes = 0);
 
-bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query)
+bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_query, uint32_t q_n_planes = 0)
 {
     if (mode != RBE_SELECT_EXACT || !rbe::batch_mfma_supported(ix->W)) return false;
     if (!can_prune(ix)) return false;   // its filter slack is margin * sum_j a_j
@@ -511,12 +511,14 @@ bool use_batch_mfma(const rbe_index* ix, uint32_t Q, uint32_t mode, bool float_q
     if (ix->batch_path >= 2) return true;
     // Measured crossover, 1e9 items d=64 P=3, whole search, XOR/popcount scan / this scan.  Integer operands
     // (general scales): 4 queries 6.5 / 6.7 ms, 5 queries 8.0 / 6.8 ms; a 16-query tile costs this scan about as
-    // much as 4.3 queries cost the other.  Half operands (the dyadic modes), 1e9 items, 2 / 3 / 4 (6e8 items) planes:
-    // 5 queries 4.9 / 5.0, 7.1 / 6.9, 5.8 / 6.0 ms; 6 queries 5.6 / 5.1, 8.2 / 7.0, 6.6 / 6.1 ms.  The byte-table scan
-    // of fp32 queries reads the corpus once per query (3.0 ms each), so there the matrix cores win from 3 queries on
-    // (7.8 ms).
+    // much as 4.3 queries cost the other.  The dyadic modes, 1e9 items, 2 / 3 / 4 (6e8 items) planes, half operands:
+    // 5 queries 4.9 / 5.0, 7.1 / 6.9, 5.8 / 6.0 ms; 6 queries 5.6 / 5.1, 8.2 / 7.0, 6.6 / 6.1 ms; integer operands
+    // (while the query fits them): 4 queries 4.1 / 4.1, 5.7 / 4.9, 4.7 / 4.0 ms, 5 queries 4.8 / 4.2, 6.8 / 5.0,
+    // 5.6 / 4.0 ms.  The byte-table scan of fp32 queries reads the corpus once per query (3.0 ms each), so there the
+    // matrix cores win from 3 queries on (7.8 ms).
     if (float_query) return Q >= 3u;
-    return Q >= (batch_operand_i8(ix, false) ? 5u : 6u);
+    if (ix->mode != rbe::kModeScaled) return Q >= (batch_operand_i8(ix, false, q_n_planes) ? 4u : 6u);
+    return Q >= (batch_operand_i8(ix, false) ? 5u : 7u);
 }
 
 // Matrix-core operands of a batch (pure host arithmetic).  Each query is reconstructed in double as
@@ -718,24 +720,80 @@ void build_batch_operands_i8(uint32_t W, const uint64_t* q_planes, const float* 
     *margin = (float)(worst * (1.0 + std::ldexp(1.0, -10)));
 }
 
-// Integer operands serve general scales (binary and fp32 queries); path 3 of rbe_debug_set_batch_path keeps the halves.
-bool batch_operand_i8(const rbe_index* ix, bool float_query)
+// Eight-bit integer operands of a batch of binary queries on a dyadic index (pure host arithmetic; exact).
+// qhat_d = sum_i +-2^-i, so T_d = 2^(PQ-1) qhat_d is an odd integer of magnitude below 2^PQ; item plane j weighs
+// 2^-j, and its copy of the query operand holds X_d = 2 T_d 2^(P-1-j) against the 64s of the kernel's item operand
+// and -X_d / 2 against the -128s (see build_batch_operands_i8; the factor 2 keeps the halves whole).  All planes add
+// into one accumulator, which starts at (the bit pattern of the float) 1.5 * 2^23 - 32 sum_j sum_d X_d and ends at
+// 1.5 * 2^23 + 2^(P + PQ + 4) s(q, z): no rounding anywhere, unscale = 2^-(P + PQ + 4).
+//   bytes   [tile][plane copy][64-dim part][lane][16]
+// qmass: the most the last plane's term can add to an accumulator that already holds its start value,
+// 32 (sum_d |X_d| + sum_d X_d) for the last plane's copy.
+// Fits eight bits while 2 (2^PQ - 1) 2^(P-1) <= 127 (batch_operand_i8).
+void build_batch_operands_i8_dyadic(uint32_t W, uint32_t P, const uint64_t* q_planes, uint32_t Q, uint32_t PQ,
+                                    int8_t* bytes, float* unscale, float* bias, float* qmass)
 {
-    (void)float_query;
+    const uint32_t dim = 64 * W, tiles = batch_tiles(Q);
+    std::memset(bytes, 0, (size_t)tiles * P * W * 64 * 16);
+    std::vector<long> T(dim);
+    for (uint32_t q = 0; q < Q; ++q) {
+        for (uint32_t d = 0; d < dim; ++d) {
+            long v = 0;
+            for (uint32_t i = 0; i < PQ; ++i) {
+                const uint64_t word = q_planes[((size_t)q * PQ + i) * W + d / 64];
+                const long c = 1l << (PQ - 1 - i);
+                v += ((word >> (d % 64)) & 1ull) ? c : -c;
+            }
+            T[d] = v;
+        }
+        const uint32_t qt = q / 16, row = q % 16;
+        long sum_all = 0, last_abs = 0, last_sum = 0;
+        for (uint32_t pa = 0; pa < P; ++pa)
+            for (uint32_t part = 0; part < W; ++part)
+                for (uint32_t grp = 0; grp < 4; ++grp)
+                    for (uint32_t t = 0; t < 4; ++t)
+                        for (uint32_t m = 0; m < 4; ++m) {
+                            const uint32_t d = 64 * part + 32 * (t / 2) + 8 * m + 2 * grp + (t % 2);
+                            const long X = 2 * T[d] * (1l << (P - 1 - pa));
+                            const long stored = (t % 2 == 0) ? X : -X / 2;
+                            sum_all += X;
+                            if (pa + 1 == P) { last_abs += std::labs(X); last_sum += X; }
+                            bytes[((((size_t)qt * P + pa) * W + part) * 64 + grp * 16 + row) * 16 + 4 * t + m] = (int8_t)stored;
+                        }
+        bias[q] = (float)(12582912.0 - 32.0 * (double)sum_all);      // exact: |32 sum X| < 2^22
+        unscale[q] = std::ldexp(1.0f, -(int)(P + PQ + 4));
+        qmass[q] = (float)(32.0 * (double)(last_abs + last_sum));    // exact
+    }
+}
+
+// Integer operands serve general scales (binary and fp32 queries) and, while they fit eight bits, the binary queries
+// of the dyadic modes (q_n_planes = 0: not known yet, taken as "no"); path 3 of rbe_debug_set_batch_path keeps the halves.
+bool batch_operand_i8(const rbe_index* ix, bool float_query, uint32_t q_n_planes)
+{
+    if (ix->batch_path == 3) return false;
+    if (ix->mode != rbe::kModeScaled)
+        return !float_query && q_n_planes >= 1 && 2u * ((1u << q_n_planes) - 1u) * (1u << (ix->P - 1)) <= 127u;
     // (the accumulators' start constant, 1.5 * 2^23, is multiplied by the item's scale sum on its way out: scales
     // beyond 2^80 -- which would bring that product near the end of the fp32 range -- keep the halves)
-    return ix->mode == rbe::kModeScaled && ix->batch_path != 3 && ix->scale_max <= 0x1p80f;
+    return ix->scale_max <= 0x1p80f;
 }
 
 int stage_batch_queries(rbe_index* ix, const uint64_t* q_planes, const float* q_scales, uint32_t Q, uint32_t PQ,
                         hipStream_t st, const float* q_float = nullptr)
 {
     const bool dyadic = ix->mode != rbe::kModeScaled;
-    ix->batch_i8 = batch_operand_i8(ix, q_float != nullptr);
+    ix->batch_i8 = batch_operand_i8(ix, q_float != nullptr, PQ);
     if (ix->batch_i8) {
-        build_batch_operands_i8(ix->W, q_planes, q_scales, Q, PQ, reinterpret_cast<int8_t*>(ix->h_aops), ix->h_unscale,
-                                ix->h_unscale + RBE_MAX_QUERIES, &ix->batch_margin, ix->h_unscale + 2 * RBE_MAX_QUERIES, q_float);
-        HIP_TRY(hipMemcpyAsync(ix->ws.aops, ix->h_aops, (size_t)batch_tiles(Q) * ix->W * 64 * 16, hipMemcpyHostToDevice, st));
+        const uint32_t copies = dyadic ? ix->P : 1u;
+        if (dyadic) {
+            build_batch_operands_i8_dyadic(ix->W, ix->P, q_planes, Q, PQ, reinterpret_cast<int8_t*>(ix->h_aops), ix->h_unscale,
+                                           ix->h_unscale + RBE_MAX_QUERIES, ix->h_unscale + 2 * RBE_MAX_QUERIES);
+            ix->batch_margin = 0.0f;
+        } else {
+            build_batch_operands_i8(ix->W, q_planes, q_scales, Q, PQ, reinterpret_cast<int8_t*>(ix->h_aops), ix->h_unscale,
+                                    ix->h_unscale + RBE_MAX_QUERIES, &ix->batch_margin, ix->h_unscale + 2 * RBE_MAX_QUERIES, q_float);
+        }
+        HIP_TRY(hipMemcpyAsync(ix->ws.aops, ix->h_aops, (size_t)batch_tiles(Q) * copies * ix->W * 64 * 16, hipMemcpyHostToDevice, st));
         HIP_TRY(hipMemcpyAsync(ix->ws.unscale, ix->h_unscale, 3 * RBE_MAX_QUERIES * sizeof(float), hipMemcpyHostToDevice, st));
         return RBE_OK;
     }
@@ -1008,6 +1066,24 @@ int rbe_debug_batch_operands_i8(const uint64_t* q_planes, const float* q_scales,
     ARG_CHECK(bytes_capacity >= need, "bytes_out too small: %zu needed", need);
     build_batch_operands_i8(dim / 64, q_planes, q_scales, n_queries, q_n_planes, bytes_out, unscale_out, start_out,
                             margin_out, mass_out, q_float);
+    return RBE_OK;
+}
+
+int rbe_debug_batch_operands_i8_dyadic(const uint64_t* q_planes, uint32_t n_queries, uint32_t q_n_planes, uint32_t dim,
+                                       uint32_t n_item_planes, int8_t* bytes_out, size_t bytes_capacity,
+                                       float* unscale_out, float* start_out, float* mass_out)
+{
+    ARG_CHECK(q_planes && bytes_out && unscale_out && start_out && mass_out, "NULL argument");
+    ARG_CHECK(dim == 64 || dim == 128, "dim must be 64 or 128");
+    ARG_CHECK(q_n_planes >= 1 && q_n_planes <= RBE_MAX_PLANES, "q_n_planes out of range");
+    ARG_CHECK(n_item_planes >= 1 && n_item_planes <= RBE_MAX_PLANES, "n_item_planes out of range");
+    ARG_CHECK(n_queries >= 1 && n_queries <= RBE_MAX_QUERIES, "n_queries out of range");
+    ARG_CHECK(2u * ((1u << q_n_planes) - 1u) * (1u << (n_item_planes - 1)) <= 127u,
+              "%u query planes against %u item planes do not fit eight-bit integer operands", q_n_planes, n_item_planes);
+    const size_t need = (size_t)batch_tiles(n_queries) * n_item_planes * (dim / 64) * 64 * 16;
+    ARG_CHECK(bytes_capacity >= need, "bytes_out too small: %zu needed", need);
+    build_batch_operands_i8_dyadic(dim / 64, n_item_planes, q_planes, n_queries, q_n_planes, bytes_out, unscale_out,
+                                   start_out, mass_out);
     return RBE_OK;
 }
 
@@ -1673,7 +1749,7 @@ static int search_binary(rbe_index* ix, const uint64_t* q_planes, const float* q
     c.PQ = q_n_planes;
     rc = stage_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
     if (rc) return rc;
-    c.batch_mfma = use_batch_mfma(ix, c.Q, c.mode, false);
+    c.batch_mfma = use_batch_mfma(ix, c.Q, c.mode, false, c.PQ);
     if (c.batch_mfma) {
         rc = stage_batch_queries(ix, q_planes, q_scales, c.Q, c.PQ, c.st);
         if (rc) return rc;

@@ -137,7 +137,7 @@ void scan_batch_mfma(const BatchArgs a)
     constexpr int S = scale_arrays(MODE, P);
     constexpr int KP = 2 * W;                          // 32-dimension parts of a plane
     constexpr bool kI8 = OP == 1;
-    static_assert(!kI8 || (MODE == kModeScaled && (RS == 1 || RS == 2)), "integer operands: the filter on general scales");
+    static_assert(!kI8 || (MODE == kModeScaled ? (RS == 1 || RS == 2) : RS == 0), "integer operands: the filter on general scales, the exact score in the dyadic modes");
     using acc_t = std::conditional_t<kI8, intx4, floatx4>;
     // General scales: one accumulator per plane (the item's a_j is applied afterwards); the query's hi half
     // filters.  Dyadic modes: the plane weight 2^-j is folded into a per-plane copy of the query operand, all
@@ -198,14 +198,16 @@ void scan_batch_mfma(const BatchArgs a)
     // query operands (16 queries per tile, one half per component, KP parts), already in lane order
     // (integer operands: one 16-byte operand per 64-dimension part, [tile][part][lane])
     half8 A[kI8 ? 1 : NQT][PA][KP];
-    intx4 A8[kI8 ? NQT : 1][W];
+    intx4 A8[kI8 ? NQT : 1][PA][W];
     if constexpr (kI8) {
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-            for (int kp = 0; kp < W; ++kp)
-                A8[qt][kp] = __builtin_bit_cast(
-                    intx4, reinterpret_cast<const u32x4*>(a.a_ops)[((a.q_begin / 16 + qt) * W + kp) * 64 + lane]);
+            for (int pa = 0; pa < PA; ++pa)
+#pragma unroll
+                for (int kp = 0; kp < W; ++kp)
+                    A8[qt][pa][kp] = __builtin_bit_cast(
+                        intx4, reinterpret_cast<const u32x4*>(a.a_ops)[(((a.q_begin / 16 + qt) * PA + pa) * W + kp) * 64 + lane]);
     } else {
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt)
@@ -254,7 +256,7 @@ void scan_batch_mfma(const BatchArgs a)
                 const intx4 B = {(int)(lo & 0x40404040u), (int)(lo & 0x80808080u), (int)(hi & 0x40404040u), (int)(hi & 0x80808080u)};
 #pragma unroll
                 for (int qt = 0; qt < NQT; ++qt)
-                    D[qt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A8[qt][kp], B, D[qt], 0, 0, 0);
+                    D[qt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A8[qt][pa][kp], B, D[qt], 0, 0, 0);
             }
         } else {
 #pragma unroll
@@ -447,10 +449,11 @@ void scan_batch_mfma(const BatchArgs a)
                             v = adj;
 #pragma unroll
                             for (int j = 0; j < F; ++j) v = __fmaf_rn(aj[j], acc_value(D[j][qt], r), v);
-                        } else if (MODE == kModeDyadicNorm) {
-                            v = aj[0] * (F < P ? D[0][qt][r] + qmass[qt][r] : D[0][qt][r]);
                         } else {
-                            v = F < P ? D[0][qt][r] + qmass[qt][r] : D[0][qt][r];
+                            // (integer operands: the accumulator reads kAccBase too high; all terms are integers
+                            // below 2^24 in magnitude, so the sum in brackets and the addition are exact)
+                            const float dv = acc_value(D[0][qt], r) + ((F < P ? qmass[qt][r] : 0.0f) - (kI8 ? kAccBase : 0.0f));
+                            v = MODE == kModeDyadicNorm ? aj[0] * dv : dv;
                         }
                         s[u][qt][r] = v;
                         any |= (v >= ((MODE == kModeScaled && F < P) ? row_taus[qt][r] : taus[qt][r]));
@@ -503,7 +506,8 @@ void scan_batch_mfma(const BatchArgs a)
                                 const float sofar = kI8 ? __fmaf_rn(-kAccBase, a_item, s[u][qt][r]) : s[u][qt][r];
                                 s[u][qt][r] = __fmaf_rn(a_item, acc_value(DL[qt], r), sofar) + adj2;
                             } else {
-                                s[u][qt][r] = MODE == kModeDyadicNorm ? a_item * acc_value(DL[qt], r) : acc_value(DL[qt], r);
+                                const float dv = acc_value(DL[qt], r) - (kI8 ? kAccBase : 0.0f);      // (exact)
+                                s[u][qt][r] = MODE == kModeDyadicNorm ? a_item * dv : dv;
                             }
                             any2 |= (s[u][qt][r] >= taus[qt][r]);
                         }
@@ -678,7 +682,8 @@ BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib,
         if (rescore == 2) return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 2> : scan_batch_mfma<W, P, MODE, 2, 2>;
         return nullptr;
     } else {
-        if (rescore != 0 || operand != 0 || calib) return nullptr;
+        if (rescore != 0 || operand > 1 || calib) return nullptr;
+        if (operand == 1) return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 0, 1> : scan_batch_mfma<W, P, MODE, 2, 0, 1>;
         return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 0> : scan_batch_mfma<W, P, MODE, 2, 0>;
     }
 }

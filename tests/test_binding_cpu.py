@@ -525,6 +525,47 @@ def test_integer_filter_at_the_margin_never_drops_a_survivor(lib, exact_query):
         assert margin < 4.5                      # nothing but the arithmetic allowances (multiply-adds, XOR/popcount score)
 
 
+@pytest.mark.parametrize("dim,P,Pq,Q", [(64, 2, 3, 16), (128, 3, 4, 19), (64, 4, 3, 5), (128, 2, 1, 33), (64, 3, 3, 1)])
+def test_integer_operands_of_the_dyadic_modes_contract_to_the_exact_score(lib, dim, P, Pq, Q):
+    """Dyadic index: the integer contraction over ALL item planes, emulated from the operand bytes alone (one copy of
+    the query operand per item plane, every plane adding into one accumulator that starts at `start`), read as a
+    float and freed of 1.5 2^23, times unscale, IS the oracle's score with the weights 2^-i, 2^-j -- exactly; `mass`
+    is the most the last plane can add to an accumulator that holds the start value; every byte fits."""
+    rng = np.random.default_rng(10 * dim + 3 * P + Pq)
+    W = dim // 64
+    N = 40
+    qp = rng.integers(0, 2**64, size=(Q, Pq, W), dtype=np.uint64)
+    planes = rng.integers(0, 2**64, size=(P, N, W), dtype=np.uint64)
+    ops, unscale, start, mass = rbe.rbe_debug_batch_operands_i8_dyadic(qp, dim, P)
+    assert np.abs(ops.astype(np.int64)).max() <= 127
+    qs = np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32)
+    scales = np.tile(np.array([2.0 ** -j for j in range(P)], dtype=np.float32)[:, None], (1, N))
+    item_bits = ((planes[:, :, :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.int64).reshape(P, N, dim)
+    for q in range(Q):
+        want = oracle.scores(planes, scales, qp[q], qs)
+        views = [_i8_operand_view(ops[:, j], q, dim) for j in range(P)]
+        assert np.all(unscale[q] == np.float32(2.0 ** -(P + Pq + 4)))
+        sum_all = sum(int(v[0].sum()) for v in views)
+        assert float(start[q]) == K_ACC - 32 * sum_all
+        for z in range(N):
+            acc = int(np.float32(start[q]).view(np.int32))
+            for j in range(P):
+                T, stored, odd = views[j]
+                acc += int((stored * np.where(odd, -128, 64) * item_bits[j, z]).sum())
+            got = (float(np.array([acc], dtype=np.int32).view(np.float32)[0]) - K_ACC) * float(unscale[q])
+            assert got == float(want[z]), (q, z, got, float(want[z]))
+        # the last plane's copy: with the start value in place it adds 64 sum over its set bits, at most mass
+        T_last = views[P - 1][0]
+        assert float(mass[q]) == 32 * (int(np.abs(T_last).sum()) + int(T_last.sum()))
+        assert np.all(T_last % 2 == 0) and np.all(np.abs(T_last) < 2 ** (Pq + 1))
+
+
+def test_integer_operands_of_the_dyadic_modes_are_refused_when_they_do_not_fit(lib):
+    qp = np.zeros((3, 4, 1), dtype=np.uint64)
+    with pytest.raises(rbe.RbeError):
+        rbe.rbe_debug_batch_operands_i8_dyadic(qp, 64, 4)          # 2 * 15 * 8 = 240
+
+
 def test_lean_first_look_with_scale_copies_never_drops_a_survivor(lib):
     """The matrix-core scan's lean stream forms its first look with the one-byte copies h_j of the scales of planes
     0 .. P-2 and lowers the row's threshold by the most the copies can be off:

@@ -814,12 +814,14 @@ def test_matrix_core_batch_path_random_corpus_multi_level_and_dyadic():
 
 
 @pytest.mark.parametrize("d,P,Pq,Q,cosine", [(64, 2, 3, 16, False), (64, 4, 4, 37, True), (128, 3, 4, 24, False),
-                                             (128, 4, 2, 20, True), (128, 2, 2, 33, False)])
+                                             (128, 4, 2, 20, True), (128, 2, 2, 33, False), (64, 3, 3, 16, True),
+                                             (64, 4, 3, 9, False), (64, 2, 1, 7, True), (128, 4, 3, 40, False)])
 def test_matrix_core_batch_path_dyadic_is_bit_equal_to_popcount_path(d, P, Pq, Q, cosine):
     """Dyadic weights: every term of the contraction is a short dyadic fraction, so the matrix-core
-    path (one query half, plane weights folded into the query operand, one accumulator chain;
-    16 queries per launch at d=128 with 3 or 4 planes, else 32) must reproduce the integer
-    shift-add path bit for bit, ids included."""
+    path (plane weights folded into the query operand, one accumulator chain; 16 queries per launch
+    at d=128 with 3 or 4 planes, else 32) must reproduce the integer shift-add path bit for bit, ids
+    included -- with eight-bit integer operands (while 2 (2^Pq - 1) 2^(P-1) <= 127: every shape here
+    but 4 + 4 planes) and with one query half per component (path 3)."""
     rng = np.random.default_rng(1000 + d + P + Q)
     N, k = 70_003, 300
     planes = rng.integers(0, 2**64, size=(P, N, d // 64), dtype=np.uint64)
@@ -831,11 +833,45 @@ def test_matrix_core_batch_path_dyadic_is_bit_equal_to_popcount_path(d, P, Pq, Q
     ids_v, sc_v = rbe.rbe_search(ix, qp, None, k)
     np.testing.assert_array_equal(sc_m, sc_v)
     np.testing.assert_array_equal(ids_m, ids_v)
+    rbe.rbe_debug_set_batch_path(ix, 3)
+    ids_h, sc_h = rbe.rbe_search(ix, qp, None, k)
+    np.testing.assert_array_equal(sc_h, sc_v)
+    np.testing.assert_array_equal(ids_h, ids_v)
     oscales = dyadic_weights(P, N)
     if cosine:
         oscales = oracle.fold_cosine(planes, oscales)
     qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
     check_batch(planes, oscales, qp, qs, k, ids_m, sc_m)
+    rbe.rbe_free(ix)
+
+
+@pytest.mark.parametrize("d,P,Pq,cosine", [(64, 2, 3, True), (64, 3, 3, False), (128, 3, 2, True), (64, 4, 4, False)])
+def test_matrix_core_dyadic_on_a_clustered_corpus_with_tight_thresholds(d, P, Pq, cosine):
+    """Several levels on a clustered corpus, dyadic weights: the last levels start from tight thresholds, so the
+    first look (last plane left out) rules most blocks out and the second look scores the rest exactly.  Integer
+    operands, half operands and the shift-add scan give the same ids and scores."""
+    N, k, Q = 400_003, 50, 12
+    c = rbe_synth.centres_numpy(2048, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=500 + d + P)
+    planes, _ = oracle.encode(x, P)
+    qpl, _ = oracle.encode(rbe_synth.vectors_numpy(Q, c, 0.3, seed=501), Pq)
+    qp = np.ascontiguousarray(qpl.transpose(1, 0, 2))
+    oscales = dyadic_weights(P, N)
+    if cosine:
+        oscales = oracle.fold_cosine(planes, oscales)
+    ix = load_with_ratio(planes, None, 8, flags=rbe.RBE_DYADIC | (rbe.RBE_COSINE if cosine else 0))
+    res = {}
+    for path in (2, 3, 1):
+        rbe.rbe_debug_set_batch_path(ix, path)
+        res[path] = rbe.rbe_search(ix, qp, None, k)
+        st = rbe.rbe_get_search_stats(ix)
+        assert st["n_levels"] >= 3
+        assert (st["scan_kernel"][-1] == "scan_batch_mfma") == (path != 1)
+    for path in (3, 1):
+        np.testing.assert_array_equal(res[2][0], res[path][0])
+        np.testing.assert_array_equal(res[2][1], res[path][1])
+    qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
+    check_batch(planes, oscales, qp, qs, k, res[2][0], res[2][1])
     rbe.rbe_free(ix)
 
 
