@@ -1444,7 +1444,8 @@ static int launch_scan_round(const SearchCtx& c, const Round& r, bool dense, uin
         ba.row_amax = ix->d_row_amax; ba.row_asum = ix->d_row_amax ? ix->d_row_amax + (size_t)ix->layout.n_tiles * (kTileItems / kRow) : nullptr; ba.n_queries = c.Q;
         ba.out = out; ba.p_begin = r.begin; ba.p_end = r.end; ba.calib_repeat = c.calib_repeat;
         // (the lean stream prunes like the progressive scans, and goes by their switch)
-        ba.hints = (ix->progressive == 1 && can_prune(ix) && !dense) ? ix->d_hints : nullptr;
+        ba.lean = (ix->progressive == 1 && can_prune(ix) && !dense) ? 1u : 0u;
+        ba.hints = ba.lean ? ix->d_hints : nullptr;
         for (int j = 0; j < 3; ++j) ba.hint_base[j] = (uint8_t)ix->hint_base[j];
         ba.deep_units = ix->ws.status + 14;
         ba.rescore = batch_rescore(ix, c.float_batch); ba.operand = ix->batch_i8 ? 1u : 0u;

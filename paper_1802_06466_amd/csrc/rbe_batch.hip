@@ -129,7 +129,9 @@ __device__ __forceinline__ void load_raw(RawRow<W, P, S>& r, const char* __restr
 // some pair passes it then have their last plane and their fp32 scales read, all at once, and are looked at again
 // with every plane and the true scales -- the look a wave takes that has given the first look up.  What passes
 // that is scored exactly as before, so the results do not change.  A wave that looks again at more than half of
-// its blocks goes back to whole rows.
+// its blocks goes back to whole rows.  Dyadic modes: there are no scale arrays to copy (the stored inverse norm,
+// if any, stays in the stream); the stream leaves the last plane out -- 8W(P-1) [+ 4] instead of 8WP [+ 4] bytes
+// per item -- and the first look is the one these modes take anyway (the most the last plane could add in its place).
 template <int W, int P, int MODE, int NQT, int RS, int OP = 0, bool CALIB = false, bool LEAN = false>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu((NQT == 1 && W == 1 && P <= 3) ? 3 : 1)))
 void scan_batch_mfma(const BatchArgs a)
@@ -152,7 +154,7 @@ void scan_batch_mfma(const BatchArgs a)
     // last plane as well (dyadic modes: that is then the exact score) before anything is queued or scored exactly.
     // (With fp32 queries the saving did not pay for the extra table reads.)
     constexpr bool kCanSkip = (kBinary || kDy) && P >= 2;
-    static_assert(!LEAN || (kI8 && kBinary && P >= 2 && !CALIB), "the lean stream: integer operands, binary queries, two or more planes");
+    static_assert(!LEAN || (kI8 && (kBinary || kDy) && P >= 2 && !CALIB), "the lean stream: integer operands, binary queries, two or more planes");
     constexpr int PA = kDy ? P : 1;
     constexpr int PD_MAX = kDy ? 1 : P;
     constexpr int SEG = row_segments<W>();
@@ -285,7 +287,7 @@ void scan_batch_mfma(const BatchArgs a)
     uint32_t hw[NW] = {};
     uint32_t hint_lo[3] = {0u, 0u, 0u};
     float hint_floor = 0.0f;
-    if constexpr (LEAN) {
+    if constexpr (LEAN && !kDy) {
 #pragma unroll
         for (int j = 0; j < P - 1; ++j) {
             hint_lo[j] = (uint32_t)a.hint_base[j] << 5;
@@ -297,6 +299,10 @@ void scan_batch_mfma(const BatchArgs a)
     auto load_segment = [&](uint32_t tile_p, int sg, bool full) __attribute__((always_inline)) {
         if constexpr (LEAN) {
             if (!full) {
+                if constexpr (kDy) {
+                    load_raw<W, P, S, P - 1, S>(cur, a.tiles + (size_t)tile_p * tile_bytes, wave, sg, lane);
+                    return;
+                }
                 load_raw<W, P, S, P - 1, 0>(cur, a.tiles + (size_t)tile_p * tile_bytes, wave, sg, lane);
                 const uint32_t* src = a.hints + (((size_t)tile_p * kWavesPerBlock + wave) * 64 + lane) * NW;
                 if constexpr (NW == 1) {
@@ -332,7 +338,7 @@ void scan_batch_mfma(const BatchArgs a)
                     *reinterpret_cast<u32x4*>(dst) = cur.pl[j][s];
                 }
             }
-        if (lean_now) {
+        if (lean_now && !kDy) {
             // (the one-byte copies stand where the first look expects the scales)
 #pragma unroll
             for (int j = 0; j < P - 1; ++j)
@@ -579,15 +585,16 @@ void scan_batch_mfma(const BatchArgs a)
                 const uint32_t again_mask = blocks(std::true_type{}, std::integral_constant<int, 1>{}, 0u);
                 if (again_mask) {
                     second_looks += (uint32_t)__builtin_popcount(again_mask);
-                    lean_units += (uint32_t)__builtin_popcount(again_mask) * (32u * W + 16u * S);       // 8-byte units asked for beyond the stream
+                    lean_units += (uint32_t)__builtin_popcount(again_mask) * (32u * W + (kDy ? 0u : 16u * S));       // 8-byte units asked for beyond the stream
                     // the last plane and the fp32 scales of the blocks to look at again: every lane asks for what it
                     // would have staged of them, all loads in flight together, then they take their places in LDS
                     const char* tile = a.tiles + (size_t)p * tile_bytes;
                     const uint64_t* pj = reinterpret_cast<const uint64_t*>(tile + (P - 1) * geom.plane_bytes()) + (size_t)wave * kRow * W;
                     const float* sj0 = reinterpret_cast<const float*>(tile + geom.scales_offset()) + wave * kRow;
                     constexpr int SLOTS = 2 * W / SEG, PER = kItemsPerLane / SEG / SLOTS;     // item slots of a lane, items per slot
+                    constexpr int GS = kDy ? 0 : S;       // scale arrays to read (dyadic modes: the norm came with the stream)
                     u32x4 gpl[SLOTS];
-                    float gsc[S][SLOTS][PER];
+                    float gsc[GS > 0 ? GS : 1][SLOTS][PER];
                     bool mine[SLOTS];
 #pragma unroll
                     for (int sl = 0; sl < SLOTS; ++sl) {
@@ -595,14 +602,14 @@ void scan_batch_mfma(const BatchArgs a)
                         mine[sl] = ((again_mask >> (item0 >> 5)) & 1u) != 0u;
                         gpl[sl] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-                        for (int j = 0; j < S; ++j)
+                        for (int j = 0; j < GS; ++j)
 #pragma unroll
                             for (int e = 0; e < PER; ++e) gsc[j][sl][e] = 0.0f;
                         if (mine[sl]) {
                             const uint64_t* src = (W == 1) ? pj + sl * 128 + 2 * lane : pj + (size_t)((seg * (4 / SEG) + sl) * 64 + lane) * 2;
                             gpl[sl] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
 #pragma unroll
-                            for (int j = 0; j < S; ++j) {
+                            for (int j = 0; j < GS; ++j) {
                                 const float* sj = sj0 + j * kTileItems;
                                 if constexpr (W == 1) {
                                     const f32x2 v = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(sj + sl * 128 + 2 * lane));
@@ -619,7 +626,7 @@ void scan_batch_mfma(const BatchArgs a)
                             const int item0 = (W == 1) ? sl * 128 + 2 * lane : sl * 64 + lane;
                             *reinterpret_cast<u32x4*>(&s_pl[wave][P - 1][item0 * W]) = gpl[sl];
 #pragma unroll
-                            for (int j = 0; j < S; ++j)
+                            for (int j = 0; j < GS; ++j)
 #pragma unroll
                                 for (int e = 0; e < PER; ++e) s_sc[wave][j][item0 + e] = gsc[j][sl][e];
                         }
@@ -683,7 +690,11 @@ BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib,
         return nullptr;
     } else {
         if (rescore != 0 || operand > 1 || calib) return nullptr;
-        if (operand == 1) return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 0, 1> : scan_batch_mfma<W, P, MODE, 2, 0, 1>;
+        if (operand == 1) {
+            if constexpr (P >= 2)
+                if (lean && nqt == 1) return scan_batch_mfma<W, P, MODE, 1, 0, 1, false, true>;
+            return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 0, 1> : scan_batch_mfma<W, P, MODE, 2, 0, 1>;
+        }
         return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 0> : scan_batch_mfma<W, P, MODE, 2, 0>;
     }
 }
@@ -693,8 +704,8 @@ BatchFn batch_fn_m(int mode, uint32_t nqt, uint32_t rescore, uint32_t operand, b
 {
     switch (mode) {
         case kModeScaled: return batch_fn_q<W, P, kModeScaled>(nqt, rescore, operand, calib, lean);
-        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0, operand, calib, false);
-        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0, operand, calib, false);
+        case kModeDyadicNorm: return batch_fn_q<W, P, kModeDyadicNorm>(nqt, 0, operand, calib, lean);
+        case kModeDyadic: return batch_fn_q<W, P, kModeDyadic>(nqt, 0, operand, calib, lean);
         default: return nullptr;
     }
 }
@@ -706,7 +717,8 @@ hipError_t launch_scan_batch_w<RBE_W>(const KernelSel& k, const BatchArgs& a, ui
 {
     BatchFn fn = nullptr;
     // the lean stream: where the index holds one-byte copies of its scales (and so the rows' largest values too)
-    const bool lean = a.hints != nullptr && a.row_amax != nullptr && a.row_asum != nullptr && a.operand == 1 && a.rescore == 1 && a.calib_repeat == 0;
+    const bool lean = a.lean != 0 && a.operand == 1 && a.calib_repeat == 0 &&
+                      (k.mode == kModeScaled ? (a.hints != nullptr && a.row_amax != nullptr && a.row_asum != nullptr && a.rescore == 1) : a.rescore == 0);
     switch (k.P) {
         case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0, lean); break;
         case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0, lean); break;

@@ -621,6 +621,7 @@ struct BatchArgs {
     const uint32_t* hints;    // one-byte copies of the scale arrays 0 .. P-2 (see scale_hints), or null: integer operands
                               // and binary queries then take the lean stream (planes 0 .. P-2 and these copies)
     uint8_t hint_base[3];     // exponent base of each array's copies
+    uint32_t lean;            // nonzero: the lean stream where the launch allows it (a level with a threshold worth pruning by)
     uint32_t* deep_units;     // += bytes / 8 that the lean stream's second looks asked for (may be null)
     uint32_t* look_stats;     // [2] += waves that ran, waves that gave up leaving the last plane out (may be null)
     const uint64_t* tau;      // [Q] threshold keys

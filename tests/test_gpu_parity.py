@@ -872,6 +872,16 @@ def test_matrix_core_dyadic_on_a_clustered_corpus_with_tight_thresholds(d, P, Pq
         np.testing.assert_array_equal(res[2][1], res[path][1])
     qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
     check_batch(planes, oscales, qp, qs, k, res[2][0], res[2][1])
+    # integer operands take the lean stream (the last plane is read only for the blocks the first look cannot rule
+    # out); with the pruning switched down or off the same scan streams whole rows: same results
+    rbe.rbe_debug_set_batch_path(ix, 2)
+    fits = 2 * (2 ** Pq - 1) * 2 ** (P - 1) <= 127
+    for prog in (1, 2, 0):
+        rbe.rbe_debug_set_progressive(ix, prog)
+        got = rbe.rbe_search(ix, qp, None, k)
+        assert (rbe.rbe_get_search_stats(ix)["deep_units"] > 0) == (prog == 1 and fits)
+        np.testing.assert_array_equal(got[0], res[2][0])
+        np.testing.assert_array_equal(got[1], res[2][1])
     rbe.rbe_free(ix)
 
 
