@@ -153,8 +153,10 @@ void scan_batch_mfma(const BatchArgs a)
     // modes: a.q_mass), and only a block of items in which that leaves some pair above its threshold contracts the
     // last plane as well (dyadic modes: that is then the exact score) before anything is queued or scored exactly.
     // (With fp32 queries the saving did not pay for the extra table reads.)
-    constexpr bool kCanSkip = (kBinary || kDy) && P >= 2;
-    static_assert(!LEAN || (kI8 && (kBinary || kDy) && P >= 2 && !CALIB), "the lean stream: integer operands, binary queries, two or more planes");
+    // (fp32 queries on the lean stream: its second phase is the all-planes look they take anyway, so the saving comes
+    // without more survivors for the byte tables)
+    constexpr bool kCanSkip = (kBinary || kDy || LEAN) && P >= 2;
+    static_assert(!LEAN || (kI8 && P >= 2 && !CALIB), "the lean stream: integer operands, two or more planes");
     constexpr int PA = kDy ? P : 1;
     constexpr int PD_MAX = kDy ? 1 : P;
     constexpr int SEG = row_segments<W>();
@@ -673,6 +675,8 @@ BatchFn batch_fn_q(uint32_t nqt, uint32_t rescore, uint32_t operand, bool calib,
         if (operand == 1) {     // eight-bit integer operands
             if (rescore == 2) {
                 if (calib) return nullptr;
+                if constexpr (P >= 2)
+                    if (lean && nqt == 1) return scan_batch_mfma<W, P, MODE, 1, 2, 1, false, true>;
                 return nqt == 1 ? scan_batch_mfma<W, P, MODE, 1, 2, 1> : scan_batch_mfma<W, P, MODE, 2, 2, 1>;
             }
             if (rescore != 1) return nullptr;
@@ -718,7 +722,11 @@ hipError_t launch_scan_batch_w<RBE_W>(const KernelSel& k, const BatchArgs& a, ui
     BatchFn fn = nullptr;
     // the lean stream: where the index holds one-byte copies of its scales (and so the rows' largest values too)
     const bool lean = a.lean != 0 && a.operand == 1 && a.calib_repeat == 0 &&
-                      (k.mode == kModeScaled ? (a.hints != nullptr && a.row_amax != nullptr && a.row_asum != nullptr && a.rescore == 1) : a.rescore == 0);
+                      (k.mode == kModeScaled ? (a.hints != nullptr && a.row_amax != nullptr && a.row_asum != nullptr &&
+                                                // (fp32 queries: 1e9 items, whole rows / lean stream, 3 queries 7.7 / 6.9 ms, 8 queries
+                                                // 8.4 / 8.3, 16 queries 9.3 / 10.1: their second phase pays for the byte tables)
+                                                (a.rescore == 1 || (a.rescore == 2 && a.n_queries <= 8)))
+                                             : a.rescore == 0);
     switch (k.P) {
         case 1: fn = batch_fn_m<RBE_W, 1>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0, lean); break;
         case 2: fn = batch_fn_m<RBE_W, 2>(k.mode, n_query_tiles, a.rescore, a.operand, a.calib_repeat != 0, lean); break;

@@ -756,6 +756,38 @@ def test_matrix_core_scan_on_the_lean_stream(d, P, Pq, Q, k):
     rbe.rbe_free(ix)
 
 
+@pytest.mark.parametrize("d,P,Q", [(64, 3, 3), (64, 2, 8), (128, 4, 5), (64, 3, 12)])
+def test_matrix_core_scan_on_the_lean_stream_with_fp32_queries(d, P, Q):
+    """Up to eight fp32 queries per call take the lean stream too (the filter's second phase is the all-planes look
+    they take anyway; larger batches stream whole rows): same ids and hybrid scores as with whole rows streamed, as
+    the table scan's, and the oracle's."""
+    N, k = 400_003, 40
+    c = rbe_synth.centres_numpy(2048, d)
+    x = rbe_synth.vectors_numpy(N, c, 0.3, seed=620 + d + P)
+    q = rbe_synth.vectors_numpy(Q, c, 0.3, seed=621)
+    q[1] *= 1e-3
+    planes, scales = oracle.encode(x, P)
+    ix = load_with_ratio(planes, scales, 8)
+    rbe.rbe_debug_set_plan_split(ix, 1)
+    rbe.rbe_debug_set_batch_path(ix, 2)
+    res = {}
+    for prog in (1, 2, 0):
+        rbe.rbe_debug_set_progressive(ix, prog)
+        res[prog] = rbe.rbe_search_float(ix, q, k)
+        st = rbe.rbe_get_search_stats(ix)
+        assert st["scan_kernel"][-1] == "scan_batch_mfma"
+        assert (st["deep_units"] > 0) == (prog == 1 and Q <= 8), (prog, st["deep_units"])
+    rbe.rbe_debug_set_progressive(ix, 1)
+    rbe.rbe_debug_set_batch_path(ix, 1)
+    res["table"] = rbe.rbe_search_float(ix, q, k)
+    for key in (2, 0, "table"):
+        np.testing.assert_array_equal(res[1][0], res[key][0])
+        np.testing.assert_array_equal(res[1][1], res[key][1])
+    for i in range(Q):
+        check_topk_float(planes, scales, q[i], k, res[1][0][i], res[1][1][i])
+    rbe.rbe_free(ix)
+
+
 def test_matrix_core_scan_on_the_lean_stream_with_scales_outside_their_copies_range():
     """Scale arrays that span twelve binades (items below the smallest one-byte code of their array) and a corpus
     that cannot be pruned (random bits, scales that do not decay: waves go back to whole rows): ids and scores equal
