@@ -174,14 +174,16 @@ def timed_searches(rbe, torch, ix, qp, qs, Q, k, steps, warmup, mode=0, group_si
     per_step, scan_ms, select_ms, total_gpu, all_ids, deep_rows, deep_units, last_items, split_steps = [], [], [], [], [], [], [], [], 0
     stats = None
     fallbacks = 0
+    # (the interpreter's cyclic collector stays out of the timed steps: with torch imported a full collection takes
+    # about 40 ms, a dozen steps' worth, and comes about once in a thousand searches.  It is run before the warm-up
+    # steps, not between them and the timed ones: 40 ms of idling there and the first timed steps run at the
+    # clocks of an idle chip, 15 % slower for a batch)
+    gc.collect()
+    gc.disable()
     for s in range(warmup):
         sl = slice(s * Q, (s + 1) * Q)
         rbe.rbe_search(ix, qp[sl], qs[sl], k, mode, group_size_I)
     torch.cuda.synchronize()
-    # (the interpreter's cyclic collector stays out of the timed steps: with torch imported a full collection takes
-    # about 40 ms, a dozen steps' worth, and comes about once in a thousand searches)
-    gc.collect()
-    gc.disable()
     t_begin = time.perf_counter()
     for s in range(warmup, warmup + steps):
         sl = slice(s * Q, (s + 1) * Q)
