@@ -376,10 +376,15 @@ void scan_batch_mfma(const BatchArgs a)
         // alone, with the one-byte copies for scales; returns the set of blocks to look at again.  PHASE 2 (lean
         // stream, not SKIP): the blocks of `only`, with everything read for them by now; they were counted in phase 1.
         auto blocks = [&](auto skip_tag, auto phase_tag, uint32_t only) -> uint32_t {
-        constexpr bool SKIP = decltype(skip_tag)::value;
+        // skip_tag: planes the first look leaves out -- 0, 1 (the last), or 2 (general scales, four planes, whole rows
+        // streamed: the last plane by the row's largest last scale as before, the one before it by the item's own
+        // scale, a_{P-2} mass_q added per pair in place of its multiply-add)
+        constexpr int SKIPN = (int)decltype(skip_tag)::value;
+        constexpr bool SKIP = SKIPN != 0;
         constexpr int PHASE = decltype(phase_tag)::value;
-        static_assert(PHASE == 0 || (LEAN && SKIP == (PHASE == 1)), "phases of the lean stream");
-        constexpr int F = SKIP ? P - 1 : P;
+        static_assert(PHASE == 0 || (LEAN && SKIPN == (PHASE == 1 ? 1 : 0)), "phases of the lean stream");
+        static_assert(SKIPN <= 1 || (MODE == kModeScaled && P >= 4), "two planes are left out on general scales with four planes only");
+        constexpr int F = P - SKIPN;
         constexpr int PD = kDy ? 1 : F;
         static_assert(PD <= PD_MAX, "accumulators");
         uint32_t look_again = 0;
@@ -457,6 +462,12 @@ void scan_batch_mfma(const BatchArgs a)
                             v = adj;
 #pragma unroll
                             for (int j = 0; j < F; ++j) v = __fmaf_rn(aj[j], acc_value(D[j][qt], r), v);
+                            if constexpr (SKIPN == 2) {
+                                // (kept apart from what the second look continues: s holds the chain, the test adds the bound)
+                                s[u][qt][r] = v;
+                                any |= (__fmaf_rn(s_sc[wave][P - 2][item], qmass[qt][r], v) >= row_taus[qt][r]);
+                                continue;
+                            }
                         } else {
                             // (integer operands: the accumulator reads kAccBase too high; all terms are integers
                             // below 2^24 in magnitude, so the sum in brackets and the addition are exact)
@@ -475,18 +486,12 @@ void scan_batch_mfma(const BatchArgs a)
             }
             if (F < P && go) {
                 ++second_looks;
-                // second look, with the last plane contracted too
+                // second look, with the planes that the first look left out contracted too
                 bool any2 = false;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int item = 16 * (cb * U + u) + col;
-                    // general scales: the last plane alone; dyadic modes: every plane again (the exact score)
-                    acc_t DL[NQT];
-#pragma unroll
-                    for (int qt = 0; qt < NQT; ++qt) DL[qt] = acc_start(qt);
-#pragma unroll
-                    for (int j = kDy ? 0 : P - 1; j < P; ++j) {
-                        uint32_t part[KP];
+                    auto plane_words = [&](int j, uint32_t (&part)[KP]) {
                         if constexpr (W == 1) {
                             const uint64_t w = s_pl[wave][j][item];
                             part[0] = (uint32_t)w; part[1] = (uint32_t)(w >> 32);
@@ -494,25 +499,53 @@ void scan_batch_mfma(const BatchArgs a)
                             const u32x4 w = *reinterpret_cast<const u32x4*>(&s_pl[wave][j][item * 2]);
                             part[0] = w.x; part[1] = w.y; part[2] = w.z; part[3] = w.w;
                         }
-                        contract_plane(DL, part, kDy ? j : 0);
-                    }
+                    };
                     float a_item = 1.0f, adj2 = 0.0f;
                     if constexpr (MODE == kModeScaled) {
-                        a_item = s_sc[wave][P - 1][item];
-                        float asum = a_item;
+                        // general scales: the planes the first look left out, one after the other, each with the
+                        // item's own scale (integer operands: each accumulator's start constant leaves with it)
+#pragma unroll
+                        for (int j = F; j < P; ++j) {
+                            acc_t DL[NQT];
+#pragma unroll
+                            for (int qt = 0; qt < NQT; ++qt) DL[qt] = acc_start(qt);
+                            uint32_t part[KP];
+                            plane_words(j, part);
+                            contract_plane(DL, part, 0);
+                            const float a_j = s_sc[wave][j][item];
+#pragma unroll
+                            for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) {
+                                    const float sofar = kI8 ? __fmaf_rn(-kAccBase, a_j, s[u][qt][r]) : s[u][qt][r];
+                                    s[u][qt][r] = __fmaf_rn(a_j, acc_value(DL[qt], r), sofar);
+                                }
+                        }
+                        float asum = s_sc[wave][P - 1][item];
 #pragma unroll
                         for (int j = 0; j < P - 1; ++j) asum += s_sc[wave][j][item];
                         adj2 = a.margin * asum;          // the item's own filter slack
                     } else if constexpr (MODE == kModeDyadicNorm) {
                         a_item = s_sc[wave][0][item];
                     }
+                    // dyadic modes: every plane again (the exact score)
+                    acc_t DL[NQT];
+                    if constexpr (kDy) {
+#pragma unroll
+                        for (int qt = 0; qt < NQT; ++qt) DL[qt] = acc_start(qt);
+#pragma unroll
+                        for (int j = 0; j < P; ++j) {
+                            uint32_t part[KP];
+                            plane_words(j, part);
+                            contract_plane(DL, part, j);
+                        }
+                    }
 #pragma unroll
                     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            if (MODE == kModeScaled) {
-                                const float sofar = kI8 ? __fmaf_rn(-kAccBase, a_item, s[u][qt][r]) : s[u][qt][r];
-                                s[u][qt][r] = __fmaf_rn(a_item, acc_value(DL[qt], r), sofar) + adj2;
+                            if constexpr (MODE == kModeScaled) {
+                                s[u][qt][r] += adj2;
                             } else {
                                 const float dv = acc_value(DL[qt], r) - (kI8 ? kAccBase : 0.0f);      // (exact)
                                 s[u][qt][r] = MODE == kModeDyadicNorm ? a_item * dv : dv;
@@ -641,7 +674,8 @@ void scan_batch_mfma(const BatchArgs a)
                 blocks(std::false_type{}, phase0{}, 0u);
             }
         } else if constexpr (kCanSkip) {
-            if (skip_last) blocks(std::true_type{}, phase0{}, 0u);
+            constexpr int kLeaveOut = (MODE == kModeScaled && P >= 4) ? 2 : 1;       // planes the first look leaves out
+            if (skip_last) blocks(std::integral_constant<int, kLeaveOut>{}, phase0{}, 0u);
             else blocks(std::false_type{}, phase0{}, 0u);
             // a wave that takes the second look for more than half of its blocks (a loose threshold, or weights
             // that do not decay) contracts every plane in the first look from then on
