@@ -254,6 +254,17 @@ __device__ __forceinline__ uint32_t key_group(uint64_t key, uint32_t span)
     return (id / span) * 256u + (id & 255u);
 }
 
+// Slots of the table that a level with n candidates uses: the least power of two that is at least 2 n (and 1024),
+// never more than the table has.  The table is empty between levels, so any prefix of it serves; both kernels
+// derive the same number from the candidate count, and the second then has only that prefix to go through
+// (k = 4000, 8 queries: 2^21 slots per query, of which a level with 30 000 candidates needs 2^16).
+__device__ __forceinline__ uint32_t group_slots_in_use(uint32_t n, uint32_t slots)
+{
+    uint32_t e = 1024u;
+    while (e < slots && e < 2u * n) e <<= 1;
+    return e < slots ? e : slots;
+}
+
 __global__ __launch_bounds__(256) void group_best_build(const GroupBestArgs a)
 {
     const uint32_t q = blockIdx.y;
@@ -262,13 +273,14 @@ __global__ __launch_bounds__(256) void group_best_build(const GroupBestArgs a)
     if (blockIdx.x == 0 && threadIdx.x == 0 && appended > a.cap) atomicOr(a.status, kStatusOverflow);
     const uint64_t* keys = a.cand + (size_t)q * a.cap;
     unsigned long long* tbl = reinterpret_cast<unsigned long long*>(a.table + (size_t)q * a.slots * 2);
-    const uint32_t mask = a.slots - 1u;
+    const uint32_t in_use = group_slots_in_use(n, a.slots);
+    const uint32_t mask = in_use - 1u;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         const unsigned long long key = keys[i];
         const uint32_t g = key_group(key, a.group_span);
         uint32_t slot = (g * 2654435761u) >> 7 & mask;
-        // at most `slots` probes: the table has twice as many slots as there are candidates
-        for (uint32_t probe = 0; probe < a.slots; ++probe, slot = (slot + 1u) & mask) {
+        // at most `in_use` probes: the part in use has twice as many slots as there are candidates
+        for (uint32_t probe = 0; probe < in_use; ++probe, slot = (slot + 1u) & mask) {
             unsigned long long cur = *reinterpret_cast<volatile unsigned long long*>(&tbl[2 * (size_t)slot]);
             if (cur == 0ull) {
                 cur = atomicCAS(&tbl[2 * (size_t)slot], 0ull, key);
@@ -294,16 +306,18 @@ __global__ __launch_bounds__(256) void group_best_compact(const GroupBestArgs a)
     uint64_t* keys = a.cand + (size_t)q * a.cap;
     uint64_t* tbl = a.table + (size_t)q * a.slots * 2;
     uint32_t* aux = a.aux + q * 4;
+    const uint32_t appended = a.count[q * kCountStride];
+    const uint32_t in_use = group_slots_in_use(appended < a.cap ? appended : a.cap, a.slots);     // (as group_best_build)
     // one returning atomic per 2048 slots: with one per wave, the 8192 atomics on this one counter were the
     // kernel's whole run time
-    for (uint32_t base = blockIdx.x * (256u * kPer); base < a.slots; base += gridDim.x * (256u * kPer)) {
+    for (uint32_t base = blockIdx.x * (256u * kPer); base < in_use; base += gridDim.x * (256u * kPer)) {
         uint64_t k0[kPer], k1[kPer];
         uint32_t mine = 0;
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
             const uint32_t slot = base + (uint32_t)i * 256u + threadIdx.x;
             k0[i] = 0; k1[i] = 0;
-            if (slot < a.slots) {
+            if (slot < in_use) {
                 k0[i] = tbl[2 * (size_t)slot];
                 if (k0[i]) {
                     tbl[2 * (size_t)slot] = 0;
