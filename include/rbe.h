@@ -21,14 +21,15 @@
  * The popcounts are exact integers; the combination is evaluated in fp32 in
  * the order written (i inner, j outer), each inner sum starting from
  * dim * sum_i c_i and accumulating -2 c_i * popcount with fused multiply-adds.
- * With 5 or more queries per call (7 or more for RBE_DYADIC; exact mode, dim <= 128)
+ * With 5 or more queries per call (RBE_DYADIC: 4 or more, 6 or more with 4 query
+ * and 4 item planes; exact mode, dim <= 128)
  * the pairs are first filtered on the matrix cores: sum_j a_j[z] * (qhat . b_z^j),
  * qhat = sum_i c_i b_q^i reconstructed on the host in double and carried as eight-bit
  * integers times a power of two (half-precision numbers for indexes whose scales
  * exceed 2^80), with a slack that covers the rounding; what
  * can reach the threshold is then scored by the formula above, so the results do
- * not depend on the number of queries per call.  (RBE_DYADIC: the half-precision
- * form is exact and is the score.)  Such a call reads the corpus once per 32
+ * not depend on the number of queries per call.  (RBE_DYADIC: the integer form --
+ * half precision with 4 + 4 planes -- is exact and is the score.)  Such a call reads the corpus once per 32
  * queries (once per 16 for RBE_DYADIC with dim 128 and 3 or 4 planes).
  * With fewer queries per call (exact mode, 2 or more planes) the last pass
  * over the corpus reads an item's last plane only where an upper bound on its score -- the
@@ -285,7 +286,8 @@ int rbe_search_static(rbe_index *ix, const uint64_t *q_planes, const float *q_sc
  * For RBE_DYADIC indexes a_j = 2^-j (times the stored inverse norm with RBE_COSINE).
  * With 3 or more queries per call on an index with general scales (dim <= 128) the
  * pairs are first filtered on the matrix cores, exactly as rbe_search does with the
- * reconstructed binary queries (q itself, in half precision, is the left operand),
+ * reconstructed binary queries (q itself, rounded to eight-bit integers times a power
+ * of two, is the left operand),
  * what can reach the threshold is scored through the tables as above, so the results
  * do not depend on the number of queries per call, and the corpus is read once per
  * 32 queries; otherwise it is read once per query.
