@@ -1108,6 +1108,67 @@ def test_random_shapes_and_modes(seed):
     rbe.rbe_free(ix)
 
 
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_random_shapes_every_scan_gives_the_same_lists(seed):
+    """Seeded draw of shape, corpus kind (clustered; clustered with scales over twelve binades; random bits;
+    dyadic weights), batch size and sample ratio: the search under every combination of the switches -- last level
+    whole or in two parts, XOR/popcount or matrix cores (integer or half operands), pruning scans on, without scale
+    copies, without the first stage, off -- returns the same ids and scores bit for bit, which are the oracle's."""
+    rng = np.random.default_rng(7700 + seed)
+    d = int(rng.choice([64, 64, 128])); P = int(rng.choice([2, 3, 3, 4])); Pq = int(rng.integers(1, 5))
+    N = int(rng.integers(60_000, 300_000)); k = int(rng.choice([1, 10, 100, 300])); Q = int(rng.choice([1, 2, 3, 4, 5, 9, 16, 20, 33]))
+    ratio = int(rng.choice([4, 8, 16])); ncl = int(rng.choice([64, 1024])); sigma = float(rng.choice([0.05, 0.3, 1.0]))
+    kind = seed % 4
+    c = rbe_synth.centres_numpy(ncl, d)
+    if kind == 2:
+        planes, scales = random_corpus(rng, N, d, P); qp, qs = random_queries(rng, Q, d, Pq)
+    else:
+        planes, scales, qp, qs = clustered(N, d, P, ncl, sigma, Q, Pq, seed=7800 + seed)
+        if kind == 1:
+            f = rng.choice(np.array([2.0 ** -9, 2.0 ** -3, 1.0, 1.0], dtype=np.float32), size=N)
+            scales = (scales * f[None, :]).astype(np.float32)
+    flags = 0
+    if kind == 3:
+        flags = rbe.RBE_DYADIC | (rbe.RBE_COSINE if seed % 8 == 3 else 0)
+        scales = dyadic_weights(P, N)
+        if flags & rbe.RBE_COSINE:
+            scales = oracle.fold_cosine(planes, scales)
+        qs = np.tile(np.array([2.0 ** -i for i in range(Pq)], dtype=np.float32), (Q, 1))
+    print(f"d={d} P={P} Pq={Pq} N={N} k={k} Q={Q} ratio={ratio} clusters={ncl} sigma={sigma} kind={kind}", flush=True)
+    ix = load_with_ratio(planes, None if kind == 3 else scales, ratio, flags=flags)
+    ref = None
+    for split in (0, 1):
+        rbe.rbe_debug_set_plan_split(ix, split)
+        for path in (0, 1, 2, 3):
+            rbe.rbe_debug_set_batch_path(ix, path)
+            for prog in (1, 2, 3, 0):
+                rbe.rbe_debug_set_progressive(ix, prog)
+                got = rbe.rbe_search(ix, qp, None if kind == 3 else qs, k)
+                if ref is None:
+                    ref = got
+                else:
+                    np.testing.assert_array_equal(got[0], ref[0], err_msg=f"split {split} path {path} prog {prog}")
+                    np.testing.assert_array_equal(got[1], ref[1], err_msg=f"split {split} path {path} prog {prog}")
+    check_batch(planes, scales, qp, qs, k, ref[0], ref[1])
+    if kind != 3:
+        # fp32 queries: table scan and matrix cores, every pruning switch
+        x = rbe_synth.vectors_numpy(min(Q, 9), c, sigma, seed=7900 + seed)
+        fref = None
+        for path in (1, 2):
+            rbe.rbe_debug_set_batch_path(ix, path)
+            for prog in (1, 2, 3, 0):
+                rbe.rbe_debug_set_progressive(ix, prog)
+                got = rbe.rbe_search_float(ix, x, k)
+                if fref is None:
+                    fref = got
+                else:
+                    np.testing.assert_array_equal(got[0], fref[0], err_msg=f"float path {path} prog {prog}")
+                    np.testing.assert_array_equal(got[1], fref[1], err_msg=f"float path {path} prog {prog}")
+        for i in range(x.shape[0]):
+            check_topk_float(planes, scales, x[i], k, fref[0][i], fref[1][i])
+    rbe.rbe_free(ix)
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_cancelling_query_planes_in_a_batch(d):
     """Queries whose second plane is the complement of the first, with nearly equal coefficients: the
